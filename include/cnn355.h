@@ -1,0 +1,184 @@
+/*
+ * cnn355 -- on-line (per-image) back-propagation training of the CNN variant of
+ * Ciresan, Meier, Masci, Gambardella, Schmidhuber, "High-Performance Neural Networks for
+ * Visual Object Classification" (IDSIA TR 01-11, 2011), as hand-written HIP kernels for
+ * gfx950 (MI355X).
+ *
+ * C ABI.  Pointers named d_* are DEVICE pointers (memory of the current HIP device, owned
+ * by the caller); pointers named host_* are HOST pointers.  The library allocates no
+ * device memory: everything it needs on the device lives in the workspace the caller
+ * hands to cnn_create and must keep alive until cnn_destroy.  All arithmetic is fp32
+ * (the paper's GPU precision, Sec. 4); indices are integers.
+ *
+ * Errors: every int-returning call gives 0 on success or one of the negative codes below;
+ * nothing throws or aborts across this boundary.  Device work is asynchronous on the
+ * stream given at creation unless a call says it synchronises; a device-side failure shows
+ * up at the next synchronising call.  cnn_last_error gives a readable message.
+ *
+ * Calls on one handle must not overlap in time (one handle = one network = one stream).
+ */
+#ifndef CNN355_H
+#define CNN355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cnn cnn_t; /* opaque; owns host metadata only */
+
+enum {
+  CNN_OK = 0,
+  CNN_E_SYNTAX = -1,    /* architecture string does not follow the grammar              */
+  CNN_E_SHAPE = -2,     /* a map size is not positive, a pooling rectangle does not tile
+                           its map, or a size exceeds what the kernels support           */
+  CNN_E_ARG = -3,       /* null pointer, label out of range, size mismatch, bad index    */
+  CNN_E_WORKSPACE = -4, /* workspace too small or misaligned                             */
+  CNN_E_HIP = -5,       /* a HIP call or a kernel reported failure                       */
+  CNN_E_STATE = -6      /* call not valid in the handle's current state                  */
+};
+
+/* layer kinds reported by cnn_layer_info */
+enum { CNN_LAYER_INPUT = 0, CNN_LAYER_CONV = 1, CNN_LAYER_POOL = 2, CNN_LAYER_FC = 3 };
+
+/* execution modes for cnn_set_mode */
+enum {
+  CNN_MODE_STAGES = 0,    /* one kernel launch per stage of the step                      */
+  CNN_MODE_PERSISTENT = 1 /* one cooperative launch per call; stages separated by grid
+                             barriers, images of cnn_*_many looped on the device          */
+};
+
+/*
+ * Architecture string (all structural parameters of Sec. 2.2-2.4 are run-time data):
+ *     <C>x<H>x<W> { -<M>C<K>[S<s>] | -MP<K> | -<N>N }+
+ *   <C>x<H>x<W>   network input: C maps of H rows x W columns
+ *   <M>C<K>[S<s>] convolutional layer (Sec. 2.2): M maps, KxK kernel, skipping factor s in
+ *                 both directions (default 0; consecutive kernel positions are s+1 pixels
+ *                 apart), scaled-tanh units, fully connected map table unless
+ *                 cnn_set_connection_table replaces it.  Output size by Eq. 1, rounded down
+ *                 where the fraction is not integral (the kernel stays inside the map).
+ *   MP<K>         max-pooling over non-overlapping KxK rectangles (Sec. 2.3); must follow a
+ *                 convolutional layer and K must divide the map size.
+ *   <N>N          fully connected layer of N neurons (Sec. 2.4).  The last token must be
+ *                 one: the output layer, one unit per class.  Hidden fully connected layers
+ *                 use the scaled tanh y = 1.7159 tanh(0.6666 a) (Sec. 4); the output layer
+ *                 is a soft-max trained with the cross-entropy error (the paper names no
+ *                 error function; this is the reading this library fixes).
+ *   Example: "1x29x29-20C4-MP2-40C5-MP3-150N-10N".
+ *
+ * Layer numbering used by the calls below: layer 0 is the network input (after the fixed
+ * front-end, if one is set); layers 1..n-1 are the tokens in order.
+ */
+
+/* Host-only: parse `arch` and report its layers.  info receives, per layer, 6 int32:
+ * {kind, maps, rows, cols, K, S}; at most max_layers layers are written; *n_layers gets
+ * the full count.  No device is touched. */
+int cnn_arch_info(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers);
+
+/* Host-only: bytes of device workspace cnn_create needs for `arch` (an upper bound that
+ * also covers any connection table and front-end set later). */
+int cnn_workspace_bytes(const char* arch, size_t* bytes);
+
+/* Build a network.  d_workspace: device memory of at least cnn_workspace_bytes bytes,
+ * 256-byte aligned, owned by the caller, used exclusively by this handle.  hip_stream: a
+ * hipStream_t (NULL = the default stream) on which all device work of the handle is
+ * issued.  Weights start at zero; fill them with cnn_set_weights.  Synchronises. */
+int cnn_create(const char* arch, void* d_workspace, size_t bytes, void* hip_stream, cnn_t** out);
+void cnn_destroy(cnn_t* net);
+
+/* Replace the map connection table of the conv_index-th convolutional layer (0-based)
+ * (Sec. 2.2 "connection table", Sec. 3.1).  host_table is [M_out][M_in] bytes, non-zero =
+ * connected; every output map needs at least one input.  Changes cnn_num_weights and
+ * zeroes all weights: set tables before weights.  Synchronises. */
+int cnn_set_connection_table(cnn_t* net, int conv_index, const uint8_t* host_table);
+
+/* Put a fixed, never-trained image-processing layer in front of the network (Sec. 2.1):
+ * n_filters (= C of the architecture string) KxK filters; filter f is correlated (valid
+ * region, no bias, no non-linearity) with channel host_src_channel[f] of the raw image.
+ * A raw image then has n_src_channels maps of (H+K-1) x (W+K-1).  K <= 32.  No delta is
+ * propagated into it.  Synchronises. */
+int cnn_set_fixed_frontend(cnn_t* net, int n_filters, int K, int n_src_channels,
+                           const float* host_filters, const int32_t* host_src_channel);
+
+size_t cnn_num_weights(const cnn_t* net); /* trainable parameters, after tables are set   */
+size_t cnn_image_size(const cnn_t* net);  /* floats in one raw image                      */
+int cnn_num_layers(const cnn_t* net);
+int cnn_num_classes(const cnn_t* net);
+/* {kind, maps, rows, cols, K, S} of one layer */
+int cnn_layer_info(const cnn_t* net, int layer, int32_t* info6);
+
+/*
+ * Canonical weight order for get/set, n = cnn_num_weights: layer by layer in network
+ * order.  Convolutional layer: bias[M], then one KxK block per connection -- output map
+ * ascending, connected input map ascending within it -- each block row-major [ky][kx],
+ * applied without flipping (the receptive field of output x is inputs x(S+1)..x(S+1)+K-1,
+ * Sec. 3.3).  Fully connected layer: bias[N], then W[N][n_in] row-major, n_in index =
+ * (map*rows + y)*cols + x of the layer below.  One bias per map / neuron (Sec. 3.2).
+ * Both calls synchronise the stream.
+ */
+int cnn_get_weights(cnn_t* net, float* host_dst, size_t n);
+int cnn_set_weights(cnn_t* net, const float* host_src, size_t n);
+
+/* Forward propagation of one image (Sec. 3.2).  d_image: cnn_image_size floats, maps then
+ * rows then columns.  d_probs: cnn_num_classes floats (may be NULL).  Asynchronous. */
+int cnn_forward(cnn_t* net, const float* d_image, float* d_probs);
+
+/* One step of on-line gradient descent (Sec. 1, Sec. 4): forward propagation (Sec. 3.2),
+ * deltas pulled back through every layer with the weights still at their old values
+ * (Sec. 3.3), weight gradients and w <- w - lr * dE/dw for every weight (Sec. 3.4).
+ * Asynchronous; the next call on the handle sees the updated weights. */
+int cnn_train_step(cnn_t* net, const float* d_image, int32_t label, float lr);
+
+/* n train steps on consecutive images, in order, exactly as n calls of cnn_train_step.
+ * d_images: n * cnn_image_size floats; d_labels: n int32, each in [0, classes) -- a label
+ * outside the range makes the device skip that image's update and the next synchronising
+ * call return CNN_E_ARG.  Asynchronous. */
+int cnn_train_many(cnn_t* net, const float* d_images, const int32_t* d_labels, size_t n, float lr);
+
+/* n forward propagations; d_probs: n * cnn_num_classes floats.  Asynchronous. */
+int cnn_forward_many(cnn_t* net, const float* d_images, size_t n, float* d_probs);
+
+/* Choose how a step is issued (CNN_MODE_*).  Results are identical bit for bit. */
+int cnn_set_mode(cnn_t* net, int mode);
+
+/* Persistent mode: number of workgroups of the cooperative launch (0 = automatic: the
+ * largest stage's work items, capped at the number of compute units).  Values above what
+ * can be co-resident are clamped. */
+int cnn_set_grid(cnn_t* net, int n_workgroups);
+
+/* Persistent mode: how many times a workgroup polls a grid barrier before it gives up,
+ * raises the abort flag and leaves the kernel (the next synchronising call then returns
+ * CNN_E_HIP).  Every wave therefore terminates even if a barrier can never complete. */
+int cnn_set_spin_limit(cnn_t* net, unsigned int polls);
+
+/* Wait for the stream; returns the first device-side error since the last call. */
+int cnn_synchronize(cnn_t* net);
+
+/* ---- parity taps: synchronous, host destinations, state of the last step/forward ---- */
+
+/* Output of a layer: conv = after the scaled tanh, pool = pooled values, fully connected
+ * = after the scaled tanh, output layer = probabilities.  maps*rows*cols floats. */
+int cnn_get_activation(cnn_t* net, int layer, float* host_dst);
+/* dE/d(pre-activation) of a convolutional or fully connected layer after a train step or
+ * cnn_debug_gradients, dense, maps*rows*cols floats (for a pooled convolutional layer:
+ * zero except at the arg-max of each rectangle). */
+int cnn_get_delta(cnn_t* net, int layer, float* host_dst);
+/* Winner index dy*K+dx (first maximum in row-major order) of every rectangle of a
+ * max-pooling layer, maps*rows*cols bytes. */
+int cnn_get_argmax(cnn_t* net, int pool_layer, uint8_t* host_dst);
+/* Cross-entropy error of the last train step / debug-gradient call. */
+int cnn_get_loss(cnn_t* net, float* host_loss);
+/* Forward + backward for (d_image, label) with the update replaced by a store of dE/dw:
+ * host_grad receives cnn_num_weights floats in canonical order; weights are unchanged. */
+int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad);
+
+/* Message for the last error on this handle (or, with net == NULL, of the last failed
+ * cnn_create / cnn_workspace_bytes / cnn_arch_info on this thread).  Never NULL. */
+const char* cnn_last_error(const cnn_t* net);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNN355_H */

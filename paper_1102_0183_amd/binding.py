@@ -1,0 +1,262 @@
+"""Thin ctypes binding of the cnn355 C ABI (include/cnn355.h).
+
+Argument marshalling only: every step of the network runs in the HIP kernels of
+libcnn355.so.  PyTorch is used for device memory (the workspace, images, labels, outputs)
+and for the stream handle; nothing here computes.  There is no CPU fallback: if the
+library cannot be loaded this module raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+OK, E_SYNTAX, E_SHAPE, E_ARG, E_WORKSPACE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6
+LAYER_INPUT, LAYER_CONV, LAYER_POOL, LAYER_FC = 0, 1, 2, 3
+MODE_STAGES, MODE_PERSISTENT = 0, 1
+
+_lib = None
+
+
+class CnnError(RuntimeError):
+    def __init__(self, code, what, msg=""):
+        super().__init__("cnn355: %s failed with code %d%s" % (what, code, (": " + msg) if msg else ""))
+        self.code = code
+
+
+def lib():
+    """Load libcnn355.so (built beforehand by build.py; compiled here only if it is missing)."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            path = _build.build(force=True)
+        L = C.CDLL(path)
+        vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32
+        sig = {
+            "cnn_arch_info": (C.c_int, [C.c_char_p, vp, vp, i32]),
+            "cnn_workspace_bytes": (C.c_int, [C.c_char_p, vp]),
+            "cnn_create": (C.c_int, [C.c_char_p, vp, sz, vp, vp]),
+            "cnn_destroy": (None, [vp]),
+            "cnn_set_connection_table": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_set_fixed_frontend": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, vp, vp]),
+            "cnn_num_weights": (sz, [vp]),
+            "cnn_image_size": (sz, [vp]),
+            "cnn_num_layers": (C.c_int, [vp]),
+            "cnn_num_classes": (C.c_int, [vp]),
+            "cnn_layer_info": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_get_weights": (C.c_int, [vp, vp, sz]),
+            "cnn_set_weights": (C.c_int, [vp, vp, sz]),
+            "cnn_forward": (C.c_int, [vp, vp, vp]),
+            "cnn_train_step": (C.c_int, [vp, vp, i32, C.c_float]),
+            "cnn_train_many": (C.c_int, [vp, vp, vp, sz, C.c_float]),
+            "cnn_forward_many": (C.c_int, [vp, vp, sz, vp]),
+            "cnn_set_mode": (C.c_int, [vp, C.c_int]),
+            "cnn_set_grid": (C.c_int, [vp, C.c_int]),
+            "cnn_set_spin_limit": (C.c_int, [vp, C.c_uint]),
+            "cnn_synchronize": (C.c_int, [vp]),
+            "cnn_get_activation": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_get_delta": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_get_argmax": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_get_loss": (C.c_int, [vp, vp]),
+            "cnn_debug_gradients": (C.c_int, [vp, vp, i32, vp]),
+            "cnn_last_error": (C.c_char_p, [vp]),
+        }
+        for name, (res, args) in sig.items():
+            f = getattr(L, name)
+            f.restype = res
+            f.argtypes = args
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_create", "cnn_destroy",
+           "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
+           "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
+           "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
+           "cnn_set_grid", "cnn_set_spin_limit", "cnn_synchronize", "cnn_get_activation",
+           "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_last_error"]
+
+
+def _err(handle=None):
+    m = lib().cnn_last_error(handle)
+    return m.decode() if m else ""
+
+
+def arch_info(arch):
+    """Host-only: list of dicts {kind, maps, h, w, K, S}, layer 0 = input."""
+    n = C.c_int32()
+    rc = lib().cnn_arch_info(arch.encode(), C.addressof(n), None, 0)
+    if rc:
+        raise CnnError(rc, "cnn_arch_info(%r)" % arch, _err())
+    info = np.zeros((n.value, 6), dtype=np.int32)
+    rc = lib().cnn_arch_info(arch.encode(), C.addressof(n), info.ctypes.data, n.value)
+    if rc:
+        raise CnnError(rc, "cnn_arch_info(%r)" % arch, _err())
+    return [dict(kind=int(r[0]), maps=int(r[1]), h=int(r[2]), w=int(r[3]), K=int(r[4]), S=int(r[5]))
+            for r in info]
+
+
+def workspace_bytes(arch):
+    n = C.c_size_t()
+    rc = lib().cnn_workspace_bytes(arch.encode(), C.addressof(n))
+    if rc:
+        raise CnnError(rc, "cnn_workspace_bytes(%r)" % arch, _err())
+    return int(n.value)
+
+
+class Cnn:
+    """One network on the current HIP device.  The workspace is a torch uint8 tensor owned here."""
+
+    def __init__(self, arch, device="cuda:0", stream=None):
+        import torch
+        self._torch = torch
+        self.arch = arch
+        self.device = torch.device(device)
+        nbytes = workspace_bytes(arch)
+        with torch.cuda.device(self.device):
+            self.workspace = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.device)
+            base = self.workspace.data_ptr()
+            self._ws_ptr = (base + 255) // 256 * 256
+            s = torch.cuda.current_stream(self.device) if stream is None else stream
+            self._stream = s
+            torch.cuda.synchronize(self.device)
+            h = C.c_void_p()
+            rc = lib().cnn_create(arch.encode(), self._ws_ptr, nbytes, s.cuda_stream, C.addressof(h))
+        if rc:
+            raise CnnError(rc, "cnn_create(%r)" % arch, _err())
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().cnn_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _ck(self, rc, what):
+        if rc:
+            raise CnnError(rc, what, _err(self._h))
+
+    # ---- structure
+    def set_connection_table(self, conv_index, table):
+        t = np.ascontiguousarray(table, dtype=np.uint8)
+        self._ck(lib().cnn_set_connection_table(self._h, int(conv_index), t.ctypes.data),
+                 "cnn_set_connection_table")
+
+    def set_fixed_frontend(self, filters, src_channel, n_src_channels):
+        f = np.ascontiguousarray(filters, dtype=np.float32)
+        s = np.ascontiguousarray(src_channel, dtype=np.int32)
+        self._ck(lib().cnn_set_fixed_frontend(self._h, int(f.shape[0]), int(f.shape[-1]),
+                                              int(n_src_channels), f.ctypes.data, s.ctypes.data),
+                 "cnn_set_fixed_frontend")
+
+    @property
+    def num_weights(self):
+        return int(lib().cnn_num_weights(self._h))
+
+    @property
+    def image_size(self):
+        return int(lib().cnn_image_size(self._h))
+
+    @property
+    def num_layers(self):
+        return int(lib().cnn_num_layers(self._h))
+
+    @property
+    def num_classes(self):
+        return int(lib().cnn_num_classes(self._h))
+
+    def layer_info(self, layer):
+        info = np.zeros(6, dtype=np.int32)
+        self._ck(lib().cnn_layer_info(self._h, int(layer), info.ctypes.data), "cnn_layer_info")
+        return dict(kind=int(info[0]), maps=int(info[1]), h=int(info[2]), w=int(info[3]),
+                    K=int(info[4]), S=int(info[5]))
+
+    def set_mode(self, mode):
+        self._ck(lib().cnn_set_mode(self._h, int(mode)), "cnn_set_mode")
+
+    def set_grid(self, n_workgroups):
+        self._ck(lib().cnn_set_grid(self._h, int(n_workgroups)), "cnn_set_grid")
+
+    def set_spin_limit(self, polls):
+        self._ck(lib().cnn_set_spin_limit(self._h, int(polls)), "cnn_set_spin_limit")
+
+    # ---- weights
+    def set_weights(self, w):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        self._ck(lib().cnn_set_weights(self._h, w.ctypes.data, w.size), "cnn_set_weights")
+
+    def get_weights(self):
+        w = np.empty(self.num_weights, dtype=np.float32)
+        self._ck(lib().cnn_get_weights(self._h, w.ctypes.data, w.size), "cnn_get_weights")
+        return w
+
+    # ---- the hot path (device tensors in, device tensors out; asynchronous)
+    def _dev_f32(self, t, n):
+        torch = self._torch
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n, \
+            "expected a contiguous float32 device tensor of %d elements" % n
+        return t.data_ptr()
+
+    def forward(self, d_image, d_probs=None):
+        p = None if d_probs is None else self._dev_f32(d_probs, self.num_classes)
+        self._ck(lib().cnn_forward(self._h, self._dev_f32(d_image, self.image_size), p), "cnn_forward")
+
+    def train_step(self, d_image, label, lr):
+        self._ck(lib().cnn_train_step(self._h, self._dev_f32(d_image, self.image_size), int(label),
+                                      float(lr)), "cnn_train_step")
+
+    def train_many(self, d_images, d_labels, lr, n=None):
+        torch = self._torch
+        n = d_labels.numel() if n is None else int(n)
+        assert d_labels.is_cuda and d_labels.dtype == torch.int32 and d_labels.is_contiguous()
+        assert d_labels.numel() >= n and d_images.numel() >= n * self.image_size
+        assert d_images.is_cuda and d_images.dtype == torch.float32 and d_images.is_contiguous()
+        self._ck(lib().cnn_train_many(self._h, d_images.data_ptr(), d_labels.data_ptr(), n, float(lr)),
+                 "cnn_train_many")
+
+    def forward_many(self, d_images, n, d_probs=None):
+        torch = self._torch
+        assert d_images.is_cuda and d_images.dtype == torch.float32 and d_images.is_contiguous()
+        assert d_images.numel() >= n * self.image_size
+        p = None if d_probs is None else self._dev_f32(d_probs, n * self.num_classes)
+        self._ck(lib().cnn_forward_many(self._h, d_images.data_ptr(), int(n), p), "cnn_forward_many")
+
+    def synchronize(self):
+        self._ck(lib().cnn_synchronize(self._h), "cnn_synchronize")
+
+    # ---- parity taps (synchronous, host results)
+    def activation(self, layer):
+        i = self.layer_info(layer)
+        a = np.empty((i["maps"], i["h"], i["w"]), dtype=np.float32)
+        self._ck(lib().cnn_get_activation(self._h, int(layer), a.ctypes.data), "cnn_get_activation")
+        return a
+
+    def delta(self, layer):
+        i = self.layer_info(layer)
+        a = np.empty((i["maps"], i["h"], i["w"]), dtype=np.float32)
+        self._ck(lib().cnn_get_delta(self._h, int(layer), a.ctypes.data), "cnn_get_delta")
+        return a
+
+    def argmax(self, layer):
+        i = self.layer_info(layer)
+        a = np.empty((i["maps"], i["h"], i["w"]), dtype=np.uint8)
+        self._ck(lib().cnn_get_argmax(self._h, int(layer), a.ctypes.data), "cnn_get_argmax")
+        return a
+
+    def loss(self):
+        v = C.c_float()
+        self._ck(lib().cnn_get_loss(self._h, C.addressof(v)), "cnn_get_loss")
+        return float(v.value)
+
+    def debug_gradients(self, d_image, label):
+        g = np.empty(self.num_weights, dtype=np.float32)
+        self._ck(lib().cnn_debug_gradients(self._h, self._dev_f32(d_image, self.image_size), int(label),
+                                           g.ctypes.data), "cnn_debug_gradients")
+        return g

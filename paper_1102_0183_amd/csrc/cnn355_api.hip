@@ -1,0 +1,791 @@
+// Host side of the cnn355 C ABI (include/cnn355.h): architecture grammar, shape inference
+// (Sec. 2.2 Eq. 1), connection tables (Sec. 3.1), planning of the per-image step into stages,
+// carving of the caller's workspace, and the entry points.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cctype>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/cnn355.h"
+#include "cnn355_dev.h"
+
+namespace cnn355 {
+hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const ProgramDev* d_prog, int s,
+                        StatusDev* d_status, const RunArgs& a);
+hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clear_label_flag);
+hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_prog,
+                             StatusDev* d_status, const RunArgs& a);
+int persistent_max_blocks_per_cu();
+}  // namespace cnn355
+
+using namespace cnn355;
+
+namespace {
+
+thread_local std::string g_err;  // message of the last failure that had no handle to carry it
+
+struct ArchLayer {
+  int kind = CNN_LAYER_INPUT;
+  int maps = 0, h = 0, w = 0, K = 0, S = 0;
+};
+
+int fail(std::string* where, int code, const std::string& msg) {
+  if (where) *where = msg;
+  g_err = msg;
+  return code;
+}
+
+// ---- grammar: <C>x<H>x<W> { -<M>C<K>[S<s>] | -MP<K> | -<N>N }+ ------------------------------
+bool take_number(const std::string& s, size_t& pos, int& v) {
+  if (pos >= s.size() || !std::isdigit((unsigned char)s[pos])) return false;
+  long long x = 0;
+  while (pos < s.size() && std::isdigit((unsigned char)s[pos])) {
+    x = x * 10 + (s[pos] - '0');
+    if (x > (1 << 20)) return false;
+    ++pos;
+  }
+  v = (int)x;
+  return true;
+}
+
+int parse_arch(const char* arch, std::vector<ArchLayer>& out, std::string* err) {
+  if (!arch) return fail(err, CNN_E_ARG, "architecture string is NULL");
+  const std::string s(arch);
+  std::vector<std::string> tok;
+  {
+    size_t a = 0;
+    while (true) {
+      size_t b = s.find('-', a);
+      tok.push_back(s.substr(a, b == std::string::npos ? std::string::npos : b - a));
+      if (b == std::string::npos) break;
+      a = b + 1;
+    }
+  }
+  out.clear();
+  {
+    ArchLayer in;
+    size_t p = 0;
+    const std::string& t = tok[0];
+    if (!take_number(t, p, in.maps) || p >= t.size() || t[p++] != 'x' || !take_number(t, p, in.h) ||
+        p >= t.size() || t[p++] != 'x' || !take_number(t, p, in.w) || p != t.size())
+      return fail(err, CNN_E_SYNTAX, "input must be <C>x<H>x<W>, got '" + t + "'");
+    if (in.maps < 1 || in.h < 1 || in.w < 1) return fail(err, CNN_E_SHAPE, "empty input '" + t + "'");
+    out.push_back(in);
+  }
+  bool fc_seen = false;
+  for (size_t ti = 1; ti < tok.size(); ++ti) {
+    const std::string& t = tok[ti];
+    const ArchLayer prev = out.back();
+    ArchLayer l;
+    size_t p = 0;
+    if (t.size() >= 2 && t[0] == 'M' && t[1] == 'P') {
+      p = 2;
+      if (!take_number(t, p, l.K) || p != t.size()) return fail(err, CNN_E_SYNTAX, "bad pooling token '" + t + "'");
+      if (prev.kind != CNN_LAYER_CONV)
+        return fail(err, CNN_E_SYNTAX, "'" + t + "': max-pooling must follow a convolutional layer");
+      if (l.K < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty pooling rectangle");
+      if (prev.h % l.K || prev.w % l.K)
+        return fail(err, CNN_E_SHAPE, "'" + t + "': rectangle does not tile a " + std::to_string(prev.h) + "x" +
+                                          std::to_string(prev.w) + " map");
+      l.kind = CNN_LAYER_POOL;
+      l.maps = prev.maps;
+      l.h = prev.h / l.K;
+      l.w = prev.w / l.K;
+    } else {
+      int n = 0;
+      if (!take_number(t, p, n) || p >= t.size()) return fail(err, CNN_E_SYNTAX, "bad token '" + t + "'");
+      const char c = t[p++];
+      if (c == 'C') {
+        if (!take_number(t, p, l.K)) return fail(err, CNN_E_SYNTAX, "bad kernel size in '" + t + "'");
+        if (p < t.size()) {
+          if (t[p++] != 'S' || !take_number(t, p, l.S) || p != t.size())
+            return fail(err, CNN_E_SYNTAX, "bad skipping factor in '" + t + "'");
+        }
+        if (fc_seen) return fail(err, CNN_E_SYNTAX, "'" + t + "': convolution after a fully connected layer");
+        if (n < 1 || l.K < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty layer");
+        l.kind = CNN_LAYER_CONV;
+        l.maps = n;
+        // Eq. 1 of Sec. 2.2, rounded down: the kernel stays completely inside the map
+        l.h = prev.h >= l.K ? (prev.h - l.K) / (l.S + 1) + 1 : 0;
+        l.w = prev.w >= l.K ? (prev.w - l.K) / (l.S + 1) + 1 : 0;
+        if (l.h < 1 || l.w < 1)
+          return fail(err, CNN_E_SHAPE, "'" + t + "': kernel larger than its " + std::to_string(prev.h) + "x" +
+                                            std::to_string(prev.w) + " input");
+      } else if (c == 'N') {
+        if (p != t.size()) return fail(err, CNN_E_SYNTAX, "bad token '" + t + "'");
+        if (n < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty layer");
+        l.kind = CNN_LAYER_FC;
+        l.maps = n;
+        l.h = l.w = 1;
+        fc_seen = true;
+      } else {
+        return fail(err, CNN_E_SYNTAX, "bad token '" + t + "'");
+      }
+    }
+    out.push_back(l);
+  }
+  if (out.size() < 2 || out.back().kind != CNN_LAYER_FC)
+    return fail(err, CNN_E_SYNTAX, "the last layer must be fully connected (<N>N)");
+  return CNN_OK;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+int ceil_log2(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+
+// A bump allocator over the caller's workspace; with base == NULL it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  template <class T>
+  T* take(size_t count) {
+    off = align_up(off, 256);
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+}  // namespace
+
+struct cnn {
+  std::vector<ArchLayer> arch;
+  std::vector<int> dev_of_arch;  // arch layer -> index in prog.layers (pool -> its conv), -1 for input
+  std::vector<std::vector<uint8_t>> tables;  // per convolutional layer, [Mo][Mi]
+  // fixed front-end
+  int fe_n = 0, fe_K = 0, fe_src_n = 0;
+  std::vector<float> fe_filters;
+  std::vector<int> fe_src;
+
+  ProgramDev prog;  // host copy with device pointers
+  ProgramDev* d_prog = nullptr;
+  StatusDev* d_status = nullptr;
+  float* d_weights = nullptr;
+  float* d_grad = nullptr;
+  float* d_fe_filters = nullptr;
+  int* d_fe_src = nullptr;
+  float* d_fe_out = nullptr;
+  struct ConvBuf {
+    float *act, *out, *delta;
+    uint8_t* arg;
+    int *argyx, *csr_ptr, *csr_idx, *csc_ptr, *csc_j, *csc_slot;
+  };
+  struct FcBuf { float *act, *delta; };
+  std::vector<ConvBuf> conv_buf;
+  std::vector<FcBuf> fc_buf;
+
+  size_t n_weights = 0, n_weights_max = 0;
+  size_t image_size = 0;
+  int n_classes = 0;
+  hipStream_t stream = nullptr;
+  int mode = CNN_MODE_STAGES;
+  int n_cu = 0, grid_override = 0, coop_ok = 0, max_blocks_per_cu = 1;
+  unsigned int spin_limit = 1u << 22;
+  bool need_status_reset = true;
+  std::string err;
+};
+
+namespace {
+
+int hip_fail(cnn* net, hipError_t e, const char* what) {
+  return fail(net ? &net->err : nullptr, CNN_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(net, call)                                   \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return hip_fail(net, e_, #call);   \
+  } while (0)
+
+// Lay the workspace out.  With net->d_* pointers filled when base != NULL.
+size_t carve(cnn* net, void* base) {
+  Carver c(base);
+  const auto& A = net->arch;
+  // upper bound on weights: every table full
+  size_t nw = 0;
+  for (size_t l = 1; l < A.size(); ++l) {
+    if (A[l].kind == CNN_LAYER_CONV) nw += (size_t)A[l].maps * (1 + (size_t)A[l - 1].maps * A[l].K * A[l].K);
+    if (A[l].kind == CNN_LAYER_FC) nw += (size_t)A[l].maps * (1 + (size_t)A[l - 1].maps * A[l - 1].h * A[l - 1].w);
+  }
+  net->n_weights_max = nw;
+  net->d_prog = c.take<ProgramDev>(1);
+  net->d_status = c.take<StatusDev>(1);
+  net->d_weights = c.take<float>(nw);
+  net->d_grad = c.take<float>(nw);
+  net->d_fe_filters = c.take<float>((size_t)A[0].maps * MAX_FRONTEND_K * MAX_FRONTEND_K);
+  net->d_fe_src = c.take<int>(A[0].maps);
+  net->d_fe_out = c.take<float>((size_t)A[0].maps * A[0].h * A[0].w);
+  net->conv_buf.clear();
+  net->fc_buf.clear();
+  for (size_t l = 1; l < A.size(); ++l) {
+    if (A[l].kind == CNN_LAYER_CONV) {
+      const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
+      const size_t full = (size_t)A[l].maps * A[l].h * A[l].w;
+      const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : full;
+      const size_t nc = (size_t)A[l].maps * A[l - 1].maps;
+      cnn::ConvBuf b;
+      b.act = c.take<float>(full);
+      b.out = pooled ? c.take<float>(small) : b.act;
+      b.delta = c.take<float>(small);
+      b.arg = c.take<uint8_t>(small);
+      b.argyx = c.take<int>(small);
+      b.csr_ptr = c.take<int>(A[l].maps + 1);
+      b.csr_idx = c.take<int>(nc);
+      b.csc_ptr = c.take<int>(A[l - 1].maps + 1);
+      b.csc_j = c.take<int>(nc);
+      b.csc_slot = c.take<int>(nc);
+      net->conv_buf.push_back(b);
+    } else if (A[l].kind == CNN_LAYER_FC) {
+      cnn::FcBuf b;
+      b.act = c.take<float>(A[l].maps);
+      b.delta = c.take<float>(A[l].maps);
+      net->fc_buf.push_back(b);
+    }
+  }
+  return align_up(c.off, 256);
+}
+
+// Choose the band of conv rows one workgroup computes in the forward stage.
+int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
+  const int Kp = L.Kp, Wo = L.Wo, Ho = L.Ho;
+  const int target = 256;
+  int rows = 0;
+  if (Kp * Wo <= WG) {
+    int max_rows = std::min(Ho, (WG / Wo) / Kp * Kp);
+    for (int r = max_rows; r >= Kp; r -= Kp)
+      if ((long long)L.Mo * ((Ho + r - 1) / r) >= target) { rows = r; break; }
+    if (!rows) {
+      rows = Kp;
+      while (rows * Wo < 64 && rows + Kp <= max_rows) rows += Kp;
+    }
+    st.pix_per_thread = 1;
+  } else {
+    if (Kp * Wo > MAX_TILE_PIX) return fail(err, CNN_E_SHAPE, "convolutional map too wide for the forward kernel");
+    rows = std::min(Ho, (MAX_TILE_PIX / Wo) / Kp * Kp);
+    while (rows > Kp && (long long)L.Mo * ((Ho + rows - 1) / rows) < target) rows -= Kp;
+    st.pix_per_thread = 4;
+  }
+  st.tile_rows = rows;
+  st.n_tiles = (Ho + rows - 1) / rows;
+  st.n_items = L.Mo * st.n_tiles;
+  const int map_sz = ((rows - 1) * (L.S + 1) + L.K) * L.Wi;
+  const int chunk = std::min({LDS_IN / map_sz, LDS_AUX / (L.K * L.K), L.max_conn});
+  if (chunk < 1) return fail(err, CNN_E_SHAPE, "convolution input rows do not fit the LDS staging area");
+  st.chunk = chunk;
+  st.tw_log2 = ceil_log2(std::min(map_sz, WG));
+  return CNN_OK;
+}
+
+int upload_tables(cnn* net, int conv_i, const LayerDev& L, const std::vector<uint8_t>& table, int* max_conn) {
+  std::vector<int> csr_ptr(L.Mo + 1, 0), csr_idx, csc_ptr(L.Mi + 1, 0), csc_j, csc_slot;
+  *max_conn = 0;
+  for (int j = 0; j < L.Mo; ++j) {
+    for (int i = 0; i < L.Mi; ++i)
+      if (table[(size_t)j * L.Mi + i]) csr_idx.push_back(i);
+    csr_ptr[j + 1] = (int)csr_idx.size();
+    *max_conn = std::max(*max_conn, csr_ptr[j + 1] - csr_ptr[j]);
+  }
+  for (int i = 0; i < L.Mi; ++i) {
+    for (int j = 0; j < L.Mo; ++j)
+      for (int s = csr_ptr[j]; s < csr_ptr[j + 1]; ++s)
+        if (csr_idx[s] == i) { csc_j.push_back(j); csc_slot.push_back(s); }
+    csc_ptr[i + 1] = (int)csc_j.size();
+  }
+  const cnn::ConvBuf& b = net->conv_buf[conv_i];
+  HIP_TRY(net, hipMemcpy(b.csr_ptr, csr_ptr.data(), csr_ptr.size() * 4, hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(b.csr_idx, csr_idx.data(), csr_idx.size() * 4, hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(b.csc_ptr, csc_ptr.data(), csc_ptr.size() * 4, hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(b.csc_j, csc_j.data(), csc_j.size() * 4, hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(b.csc_slot, csc_slot.data(), csc_slot.size() * 4, hipMemcpyHostToDevice));
+  return CNN_OK;
+}
+
+// (Re)build layer descriptors, tables and the stage list, and upload them.  Weights are zeroed.
+int rebuild(cnn* net) {
+  const auto& A = net->arch;
+  ProgramDev& P = net->prog;
+  std::memset(&P, 0, sizeof(P));
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  net->dev_of_arch.assign(A.size(), -1);
+  int nl = 0, conv_i = 0, fc_i = 0;
+  std::vector<int> conv_of_dev(MAX_LAYERS, -1);  // descriptor index -> convolutional layer index
+  size_t woff = 0;
+  const float* below = nullptr;  // output buffer of the layer below
+  const bool fe = net->fe_n > 0;
+  if (fe) below = net->d_fe_out;
+  for (size_t l = 1; l < A.size(); ++l) {
+    if (A[l].kind == CNN_LAYER_POOL) { net->dev_of_arch[l] = nl - 1; continue; }
+    if (nl >= MAX_LAYERS) return fail(&net->err, CNN_E_SHAPE, "too many layers");
+    LayerDev& L = P.layers[nl];
+    L.in_is_image = (below == nullptr);
+    L.in = below;
+    if (A[l].kind == CNN_LAYER_CONV) {
+      const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
+      L.kind = L_CONV;
+      L.Mi = A[l - 1].maps; L.Hi = A[l - 1].h; L.Wi = A[l - 1].w;
+      L.Mo = A[l].maps; L.Ho = A[l].h; L.Wo = A[l].w;
+      L.K = A[l].K; L.S = A[l].S;
+      L.Kp = pooled ? A[l + 1].K : 1;
+      L.Hp = L.Ho / L.Kp; L.Wp = L.Wo / L.Kp;
+      if (L.Ho >= 65536 || L.Wo >= 65536) return fail(&net->err, CNN_E_SHAPE, "map too large");
+      if (L.Hp * L.Wp > MAX_POOLED_PIX)
+        return fail(&net->err, CNN_E_SHAPE, "pooled map has more than " + std::to_string(MAX_POOLED_PIX) + " positions");
+      if (L.Hi * L.Wi > LDS_IN)
+        return fail(&net->err, CNN_E_SHAPE, "input map has more than " + std::to_string(LDS_IN) + " pixels");
+      if (L.Kp > 15) return fail(&net->err, CNN_E_SHAPE, "pooling rectangle larger than 15x15");
+      const cnn::ConvBuf& b = net->conv_buf[conv_i];
+      L.act = b.act; L.out = b.out; L.delta = b.delta; L.arg = b.arg; L.argyx = b.argyx;
+      L.csr_ptr = b.csr_ptr; L.csr_idx = b.csr_idx; L.csc_ptr = b.csc_ptr; L.csc_j = b.csc_j; L.csc_slot = b.csc_slot;
+      conv_of_dev[nl] = conv_i;
+      int rc = upload_tables(net, conv_i, L, net->tables[conv_i], &L.max_conn);
+      if (rc) return rc;
+      size_t n_conn = 0;
+      for (uint8_t v : net->tables[conv_i]) n_conn += v ? 1 : 0;
+      L.b_canon = (long long)woff;
+      L.w_canon = (long long)(woff + L.Mo);
+      woff += L.Mo + n_conn * L.K * L.K;
+      if (L.Kp == 1) {  // no pooling: every neuron is its own winner
+        std::vector<int> yx((size_t)L.Mo * L.Ho * L.Wo);
+        for (int j = 0; j < L.Mo; ++j)
+          for (int y = 0; y < L.Ho; ++y)
+            for (int x = 0; x < L.Wo; ++x) yx[((size_t)j * L.Ho + y) * L.Wo + x] = (y << 16) | x;
+        HIP_TRY(net, hipMemcpy(L.argyx, yx.data(), yx.size() * 4, hipMemcpyHostToDevice));
+        HIP_TRY(net, hipMemset(L.arg, 0, yx.size()));
+      }
+      ++conv_i;
+    } else {
+      L.kind = L_FC;
+      L.n_in = A[l - 1].maps * A[l - 1].h * A[l - 1].w;
+      L.n_out = A[l].maps;
+      L.is_output = (l + 1 == A.size());
+      if (L.n_out > MAX_FC_OUT)
+        return fail(&net->err, CNN_E_SHAPE, "fully connected layer wider than " + std::to_string(MAX_FC_OUT));
+      const cnn::FcBuf& b = net->fc_buf[fc_i];
+      L.act = b.act; L.out = b.act; L.delta = b.delta;
+      L.b_canon = (long long)woff;
+      L.w_canon = (long long)(woff + L.n_out);
+      woff += (size_t)L.n_out * (1 + (size_t)L.n_in);
+      ++fc_i;
+    }
+    L.bias = net->d_weights + L.b_canon;
+    L.w = net->d_weights + L.w_canon;
+    below = L.out;
+    net->dev_of_arch[l] = nl;
+    ++nl;
+  }
+  P.n_layers = nl;
+  P.n_classes = A.back().maps;
+  net->n_classes = P.n_classes;
+  net->n_weights = woff;
+  P.has_frontend = fe ? 1 : 0;
+  if (fe) {
+    FrontendDev& F = P.fe;
+    F.n_filters = net->fe_n; F.K = net->fe_K; F.n_src = net->fe_src_n;
+    F.H = A[0].h; F.W = A[0].w;
+    F.Hr = F.H + F.K - 1; F.Wr = F.W + F.K - 1;
+    F.filters = net->d_fe_filters; F.src = net->d_fe_src; F.out = net->d_fe_out;
+    net->image_size = (size_t)F.n_src * F.Hr * F.Wr;
+  } else {
+    net->image_size = (size_t)A[0].maps * A[0].h * A[0].w;
+  }
+
+  // ---- stage list ------------------------------------------------------------------------
+  int ns = 0;
+  auto add = [&](int kind, int layer, int n_items, int barrier, int train_only) -> Stage& {
+    Stage& s = P.stages[ns++];
+    s.kind = kind; s.layer = layer; s.n_items = n_items; s.barrier_after = barrier; s.train_only = train_only;
+    return s;
+  };
+  if (2 * nl + 4 > MAX_STAGES) return fail(&net->err, CNN_E_SHAPE, "too many stages");
+  if (fe) add(ST_FRONTEND, 0, (net->fe_n * A[0].h * A[0].w + WG - 1) / WG, 1, 0);
+  for (int l = 0; l < nl; ++l) {  // forward, bottom up
+    LayerDev& L = P.layers[l];
+    if (L.kind == L_CONV) {
+      Stage& s = add(ST_CONV_FWD, l, 0, 1, 0);
+      int rc = plan_conv_fwd(L, s, &net->err);
+      if (rc) return rc;
+    } else if (!L.is_output) {
+      Stage& s = add(ST_FC_FWD, l, 0, 1, 0);
+      s.rows_per_wg = L.n_out <= 512 ? 1 : (L.n_out <= 1024 ? 2 : 4);
+      s.n_items = (L.n_out + s.rows_per_wg - 1) / s.rows_per_wg;
+    } else {
+      add(ST_HEAD, l, 1, 1, 0);
+    }
+  }
+  // backward, top down.  The weights of a convolutional layer are adjusted one stage after the
+  // deltas have been pulled through them; that adjustment shares a stage with the next pull.
+  int pending_wgrad = -1;
+  auto add_wgrad = [&](int l, int barrier) {
+    LayerDev& L = P.layers[l];
+    Stage& s = add(ST_CONV_WGRAD, l, 0, barrier, 1);
+    const int chunk_max = std::min(LDS_IN / (L.Hi * L.Wi), L.max_conn);
+    const int want_chunks = (256 + L.Mo - 1) / L.Mo;  // aim at >= 256 work items
+    int chunk = std::max(1, std::min(chunk_max, L.max_conn / std::max(1, want_chunks)));
+    s.chunk = chunk;
+    s.n_tiles = (L.max_conn + chunk - 1) / chunk;
+    s.n_items = L.Mo * s.n_tiles;
+    s.tw_log2 = ceil_log2(std::min(L.Hi * L.Wi, WG));
+  };
+  for (int l = nl - 2; l >= 0; --l) {  // layer nl-1 is the output layer, handled by ST_HEAD
+    LayerDev& L = P.layers[l];
+    if (L.kind == L_FC) {
+      Stage& s = add(ST_FC_BWD, l, 0, 1, 1);
+      s.cm_log2 = (L.n_in / 16 > 2048) ? 6 : 4;
+      s.n_items = (L.n_in + (1 << s.cm_log2) - 1) >> s.cm_log2;
+    } else {
+      if (!L.in_is_image && l > 0) {
+        // pull deltas into layer l-1 (reads the old weights of layer l) ...
+        const bool with_pending = pending_wgrad >= 0;
+        if (with_pending) { add_wgrad(pending_wgrad, 0); pending_wgrad = -1; }
+        Stage& s = add(ST_CONV_BWD, l, 0, 1, 1);
+        const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.K;
+        int max_back = 0;
+        {
+          std::vector<int> cnt(L.Mi, 0);
+          const auto& t = net->tables[conv_of_dev[l]];
+          for (int j = 0; j < L.Mo; ++j)
+            for (int i = 0; i < L.Mi; ++i) cnt[i] += t[(size_t)j * L.Mi + i] ? 1 : 0;
+          for (int v : cnt) max_back = std::max(max_back, v);
+        }
+        s.n_tiles = (Pin + WG - 1) / WG;
+        s.n_items = L.Mi * s.n_tiles;
+        s.chunk = std::max(1, std::min({LDS_AUX / HW, LDS_IN / KK, std::max(1, max_back)}));
+        s.tw_log2 = ceil_log2(std::min(HW, WG));
+        // ... then adjust the weights of layer l one stage later
+        pending_wgrad = l;
+      } else {
+        // first trainable layer: nothing to pull; adjust it together with whatever is pending
+        if (pending_wgrad >= 0) { add_wgrad(pending_wgrad, 0); pending_wgrad = -1; }
+        add_wgrad(l, 1);
+      }
+    }
+  }
+  if (pending_wgrad >= 0) { add_wgrad(pending_wgrad, 1); pending_wgrad = -1; }
+  if (ns > 0) P.stages[ns - 1].barrier_after = 1;
+  P.n_stages = ns;
+
+  HIP_TRY(net, hipMemcpy(net->d_prog, &P, sizeof(P), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemset(net->d_weights, 0, net->n_weights_max * sizeof(float)));
+  HIP_TRY(net, hipMemset(net->d_status, 0, sizeof(StatusDev)));
+  return CNN_OK;
+}
+
+int check_status(cnn* net) {
+  StatusDev s;
+  HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
+  int rc = CNN_OK;
+  if (s.abort_flag) rc = fail(&net->err, CNN_E_HIP, "grid barrier of the persistent kernel timed out");
+  else if (s.bad_label) rc = fail(&net->err, CNN_E_ARG, "a label outside [0, classes) was met; that image was skipped");
+  if (s.abort_flag || s.bad_label) {
+    s.abort_flag = 0; s.bad_label = 0; s.barrier_count = 0;
+    HIP_TRY(net, hipMemcpy(net->d_status, &s, sizeof(s), hipMemcpyHostToDevice));
+  }
+  return rc;
+}
+
+int sync_and_check(cnn* net) {
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  return check_status(net);
+}
+
+int persistent_grid(const cnn* net, int train) {
+  if (net->grid_override > 0) return std::min(net->grid_override, net->n_cu * net->max_blocks_per_cu);
+  int most = 1;
+  for (int s = 0; s < net->prog.n_stages; ++s)
+    if (train || !net->prog.stages[s].train_only) most = std::max(most, net->prog.stages[s].n_items);
+  return std::max(1, std::min(most, net->n_cu));
+}
+
+int run(cnn* net, const RunArgs& a0) {
+  RunArgs a = a0;
+  a.spin_limit = net->spin_limit;
+  const ProgramDev& P = net->prog;
+  if (net->mode == CNN_MODE_PERSISTENT) {
+    HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
+    HIP_TRY(net, launch_persistent(persistent_grid(net, a.train), net->stream, net->d_prog, net->d_status, a));
+    return CNN_OK;
+  }
+  const long long n = a.n_images;
+  for (long long t = 0; t < n; ++t) {
+    RunArgs b = a;
+    b.images = a.images + t * a.image_stride;
+    b.labels = a.labels ? a.labels + t : nullptr;
+    b.probs_out = a.probs_out ? a.probs_out + t * P.n_classes : nullptr;
+    b.n_images = 1;
+    for (int s = 0; s < P.n_stages; ++s) {
+      const Stage& st = P.stages[s];
+      if (st.train_only && !a.train) continue;
+      HIP_TRY(net, launch_stage(st.kind, st.n_items, net->stream, net->d_prog, s, net->d_status, b));
+    }
+  }
+  return CNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cnn_arch_info(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers) {
+  std::vector<ArchLayer> A;
+  int rc = parse_arch(arch, A, nullptr);
+  if (rc) return rc;
+  if (n_layers) *n_layers = (int32_t)A.size();
+  if (info)
+    for (size_t l = 0; l < A.size() && (int32_t)l < max_layers; ++l) {
+      int32_t* o = info + 6 * l;
+      o[0] = A[l].kind; o[1] = A[l].maps; o[2] = A[l].h; o[3] = A[l].w; o[4] = A[l].K; o[5] = A[l].S;
+    }
+  return CNN_OK;
+}
+
+int cnn_workspace_bytes(const char* arch, size_t* bytes) {
+  if (!bytes) return fail(nullptr, CNN_E_ARG, "bytes is NULL");
+  cnn tmp;
+  int rc = parse_arch(arch, tmp.arch, nullptr);
+  if (rc) return rc;
+  *bytes = carve(&tmp, nullptr);
+  return CNN_OK;
+}
+
+int cnn_create(const char* arch, void* d_workspace, size_t bytes, void* hip_stream, cnn_t** out) {
+  if (!out) return fail(nullptr, CNN_E_ARG, "out is NULL");
+  *out = nullptr;
+  cnn* net = new cnn;
+  int rc = parse_arch(arch, net->arch, &net->err);
+  if (rc) { delete net; return rc; }
+  const size_t need = carve(net, nullptr);
+  if (!d_workspace || bytes < need || ((uintptr_t)d_workspace & 255)) {
+    delete net;
+    return fail(nullptr, CNN_E_WORKSPACE, "workspace must be 256-byte aligned device memory of at least " +
+                                              std::to_string(need) + " bytes");
+  }
+  carve(net, d_workspace);
+  net->stream = (hipStream_t)hip_stream;
+  for (size_t l = 1; l < net->arch.size(); ++l)
+    if (net->arch[l].kind == CNN_LAYER_CONV)
+      net->tables.emplace_back((size_t)net->arch[l].maps * net->arch[l - 1].maps, (uint8_t)1);
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&net->n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&net->coop_ok, hipDeviceAttributeCooperativeLaunch, dev);
+  if (e != hipSuccess) { rc = hip_fail(nullptr, e, "device query"); delete net; return rc; }
+  net->max_blocks_per_cu = std::max(1, persistent_max_blocks_per_cu());
+  rc = rebuild(net);
+  if (rc) { g_err = net->err; delete net; return rc; }
+  *out = net;
+  return CNN_OK;
+}
+
+void cnn_destroy(cnn_t* net) {
+  if (!net) return;
+  (void)hipStreamSynchronize(net->stream);
+  delete net;
+}
+
+int cnn_set_connection_table(cnn_t* net, int conv_index, const uint8_t* host_table) {
+  if (!net || !host_table) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (conv_index < 0 || conv_index >= (int)net->tables.size()) return fail(&net->err, CNN_E_ARG, "no such convolutional layer");
+  int seen = 0, mo = 0, mi = 0;
+  for (size_t l = 1; l < net->arch.size(); ++l)
+    if (net->arch[l].kind == CNN_LAYER_CONV && seen++ == conv_index) { mo = net->arch[l].maps; mi = net->arch[l - 1].maps; }
+  std::vector<uint8_t> t((size_t)mo * mi);
+  for (int j = 0; j < mo; ++j) {
+    bool any = false;
+    for (int i = 0; i < mi; ++i) { t[(size_t)j * mi + i] = host_table[(size_t)j * mi + i] ? 1 : 0; any |= t[(size_t)j * mi + i] != 0; }
+    if (!any) return fail(&net->err, CNN_E_ARG, "output map " + std::to_string(j) + " has no input map");
+  }
+  net->tables[conv_index] = t;
+  return rebuild(net);
+}
+
+int cnn_set_fixed_frontend(cnn_t* net, int n_filters, int K, int n_src_channels, const float* host_filters,
+                           const int32_t* host_src_channel) {
+  if (!net || !host_filters || !host_src_channel) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (n_filters != net->arch[0].maps) return fail(&net->err, CNN_E_ARG, "n_filters must equal the input maps of the architecture");
+  if (K < 1 || K > MAX_FRONTEND_K || n_src_channels < 1) return fail(&net->err, CNN_E_ARG, "bad front-end size");
+  for (int f = 0; f < n_filters; ++f)
+    if (host_src_channel[f] < 0 || host_src_channel[f] >= n_src_channels) return fail(&net->err, CNN_E_ARG, "source channel out of range");
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  net->fe_n = n_filters; net->fe_K = K; net->fe_src_n = n_src_channels;
+  net->fe_filters.assign(host_filters, host_filters + (size_t)n_filters * K * K);
+  net->fe_src.assign(host_src_channel, host_src_channel + n_filters);
+  HIP_TRY(net, hipMemcpy(net->d_fe_filters, net->fe_filters.data(), net->fe_filters.size() * 4, hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_fe_src, net->fe_src.data(), net->fe_src.size() * 4, hipMemcpyHostToDevice));
+  return rebuild(net);
+}
+
+size_t cnn_num_weights(const cnn_t* net) { return net ? net->n_weights : 0; }
+size_t cnn_image_size(const cnn_t* net) { return net ? net->image_size : 0; }
+int cnn_num_layers(const cnn_t* net) { return net ? (int)net->arch.size() : 0; }
+int cnn_num_classes(const cnn_t* net) { return net ? net->n_classes : 0; }
+
+int cnn_layer_info(const cnn_t* net, int layer, int32_t* o) {
+  if (!net || !o || layer < 0 || layer >= (int)net->arch.size()) return CNN_E_ARG;
+  const ArchLayer& a = net->arch[layer];
+  o[0] = a.kind; o[1] = a.maps; o[2] = a.h; o[3] = a.w; o[4] = a.K; o[5] = a.S;
+  return CNN_OK;
+}
+
+int cnn_get_weights(cnn_t* net, float* host_dst, size_t n) {
+  if (!net || !host_dst) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (n != net->n_weights) return fail(&net->err, CNN_E_ARG, "weight count mismatch");
+  int rc = sync_and_check(net);
+  HIP_TRY(net, hipMemcpy(host_dst, net->d_weights, n * sizeof(float), hipMemcpyDeviceToHost));
+  return rc;
+}
+
+int cnn_set_weights(cnn_t* net, const float* host_src, size_t n) {
+  if (!net || !host_src) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (n != net->n_weights) return fail(&net->err, CNN_E_ARG, "weight count mismatch");
+  int rc = sync_and_check(net);
+  HIP_TRY(net, hipMemcpy(net->d_weights, host_src, n * sizeof(float), hipMemcpyHostToDevice));
+  return rc;
+}
+
+int cnn_forward(cnn_t* net, const float* d_image, float* d_probs) {
+  return cnn_forward_many(net, d_image, 1, d_probs);
+}
+
+int cnn_forward_many(cnn_t* net, const float* d_images, size_t n, float* d_probs) {
+  if (!net || !d_images) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (n == 0) return CNN_OK;
+  RunArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.images = d_images; a.probs_out = d_probs; a.n_images = (long long)n; a.image_stride = (long long)net->image_size;
+  a.label_imm = -1; a.train = 0;
+  return run(net, a);
+}
+
+int cnn_train_step(cnn_t* net, const float* d_image, int32_t label, float lr) {
+  if (!net || !d_image) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (label < 0 || label >= net->n_classes) return fail(&net->err, CNN_E_ARG, "label out of range");
+  RunArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.images = d_image; a.n_images = 1; a.image_stride = (long long)net->image_size;
+  a.label_imm = label; a.train = 1; a.lr = lr;
+  return run(net, a);
+}
+
+int cnn_train_many(cnn_t* net, const float* d_images, const int32_t* d_labels, size_t n, float lr) {
+  if (!net || !d_images || !d_labels) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (n == 0) return CNN_OK;
+  RunArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.images = d_images; a.labels = d_labels; a.n_images = (long long)n; a.image_stride = (long long)net->image_size;
+  a.train = 1; a.lr = lr;
+  return run(net, a);
+}
+
+int cnn_set_mode(cnn_t* net, int mode) {
+  if (!net) return CNN_E_ARG;
+  if (mode != CNN_MODE_STAGES && mode != CNN_MODE_PERSISTENT) return fail(&net->err, CNN_E_ARG, "unknown mode");
+  if (mode == CNN_MODE_PERSISTENT && !net->coop_ok) return fail(&net->err, CNN_E_STATE, "device does not support cooperative launches");
+  net->mode = mode;
+  return CNN_OK;
+}
+
+int cnn_set_grid(cnn_t* net, int n_workgroups) {
+  if (!net || n_workgroups < 0) return CNN_E_ARG;
+  net->grid_override = n_workgroups;
+  return CNN_OK;
+}
+
+int cnn_set_spin_limit(cnn_t* net, unsigned int polls) {
+  if (!net) return CNN_E_ARG;
+  net->spin_limit = polls;
+  return CNN_OK;
+}
+
+int cnn_synchronize(cnn_t* net) {
+  if (!net) return CNN_E_ARG;
+  return sync_and_check(net);
+}
+
+int cnn_get_activation(cnn_t* net, int layer, float* host_dst) {
+  if (!net || !host_dst) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (layer < 0 || layer >= (int)net->arch.size()) return fail(&net->err, CNN_E_ARG, "no such layer");
+  int rc = sync_and_check(net);
+  const ArchLayer& a = net->arch[layer];
+  const size_t n = (size_t)a.maps * a.h * a.w;
+  const float* src = nullptr;
+  if (layer == 0) {
+    if (!net->fe_n) return fail(&net->err, CNN_E_STATE, "layer 0 is the caller's image unless a front-end is set");
+    src = net->d_fe_out;
+  } else {
+    const LayerDev& L = net->prog.layers[net->dev_of_arch[layer]];
+    src = (a.kind == CNN_LAYER_POOL) ? L.out : L.act;
+  }
+  HIP_TRY(net, hipMemcpy(host_dst, src, n * sizeof(float), hipMemcpyDeviceToHost));
+  return rc;
+}
+
+int cnn_get_delta(cnn_t* net, int layer, float* host_dst) {
+  if (!net || !host_dst) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (layer < 1 || layer >= (int)net->arch.size() || net->arch[layer].kind == CNN_LAYER_POOL)
+    return fail(&net->err, CNN_E_ARG, "deltas exist for convolutional and fully connected layers");
+  int rc = sync_and_check(net);
+  const ArchLayer& a = net->arch[layer];
+  const LayerDev& L = net->prog.layers[net->dev_of_arch[layer]];
+  if (a.kind == CNN_LAYER_FC) {
+    HIP_TRY(net, hipMemcpy(host_dst, L.delta, (size_t)a.maps * sizeof(float), hipMemcpyDeviceToHost));
+    return rc;
+  }
+  // scatter the winners' deltas back to the full-resolution map (index work only)
+  const size_t small = (size_t)L.Mo * L.Hp * L.Wp, full = (size_t)L.Mo * L.Ho * L.Wo;
+  std::vector<float> d(small);
+  std::vector<int> yx(small);
+  HIP_TRY(net, hipMemcpy(d.data(), L.delta, small * sizeof(float), hipMemcpyDeviceToHost));
+  HIP_TRY(net, hipMemcpy(yx.data(), L.argyx, small * sizeof(int), hipMemcpyDeviceToHost));
+  std::fill(host_dst, host_dst + full, 0.f);
+  for (int j = 0; j < L.Mo; ++j)
+    for (int q = 0; q < L.Hp * L.Wp; ++q) {
+      const int v = yx[(size_t)j * L.Hp * L.Wp + q];
+      host_dst[((size_t)j * L.Ho + (v >> 16)) * L.Wo + (v & 0xffff)] = d[(size_t)j * L.Hp * L.Wp + q];
+    }
+  return rc;
+}
+
+int cnn_get_argmax(cnn_t* net, int pool_layer, uint8_t* host_dst) {
+  if (!net || !host_dst) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (pool_layer < 1 || pool_layer >= (int)net->arch.size() || net->arch[pool_layer].kind != CNN_LAYER_POOL)
+    return fail(&net->err, CNN_E_ARG, "not a max-pooling layer");
+  int rc = sync_and_check(net);
+  const ArchLayer& a = net->arch[pool_layer];
+  const LayerDev& L = net->prog.layers[net->dev_of_arch[pool_layer]];
+  HIP_TRY(net, hipMemcpy(host_dst, L.arg, (size_t)a.maps * a.h * a.w, hipMemcpyDeviceToHost));
+  return rc;
+}
+
+int cnn_get_loss(cnn_t* net, float* host_loss) {
+  if (!net || !host_loss) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  StatusDev s;
+  HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
+  *host_loss = s.loss;
+  return check_status(net);
+}
+
+int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad) {
+  if (!net || !d_image || !host_grad) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (label < 0 || label >= net->n_classes) return fail(&net->err, CNN_E_ARG, "label out of range");
+  RunArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.images = d_image; a.n_images = 1; a.image_stride = (long long)net->image_size;
+  a.label_imm = label; a.train = 1; a.lr = 0.f; a.grad_out = net->d_grad;
+  int rc = run(net, a);
+  if (rc) return rc;
+  rc = sync_and_check(net);
+  HIP_TRY(net, hipMemcpy(host_grad, net->d_grad, net->n_weights * sizeof(float), hipMemcpyDeviceToHost));
+  return rc;
+}
+
+const char* cnn_last_error(const cnn_t* net) { return net ? net->err.c_str() : g_err.c_str(); }
+
+}  // extern "C"

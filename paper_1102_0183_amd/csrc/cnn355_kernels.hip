@@ -1,0 +1,734 @@
+// gfx950 kernels for on-line back-propagation training of the CNN variant of Ciresan et al.
+// (IDSIA TR 01-11).  Every stage of the per-image step is a device function that processes
+// one independent work item with one 256-thread workgroup (four 64-lane wavefronts), staging
+// its operands through LDS.  The same functions run either as one kernel launch per stage or
+// inside one persistent kernel whose stages are separated by grid barriers.
+//
+// Notation follows the paper: layer n has M maps; a K x K kernel moves over the valid region
+// with skipping factor S (stride S+1) (Sec. 2.2); FP / BP / AW are the forward, delta and
+// weight-adjusting phases of Sec. 3.2 - 3.4.
+#include <hip/hip_runtime.h>
+
+#include "cnn355_dev.h"
+
+namespace cnn355 {
+
+// Scaled hyperbolic tangent of Sec. 4, constants as printed.
+#define ACT_A 1.7159f
+#define ACT_B 0.6666f
+__device__ __forceinline__ float act_f(float a) { return ACT_A * tanhf(ACT_B * a); }
+// derivative written in terms of the output:  A*B*(1 - tanh^2) = A*B - (B/A) y^2
+__device__ __forceinline__ float dact_f(float y) {
+  return (float)(1.7159 * 0.6666) - (float)(0.6666 / 1.7159) * y * y;
+}
+
+struct Ctx {
+  const float* image;
+  float* probs_out;
+  float* grad_out;
+  int label;
+  int train;  // this image is trained on (0 for forward-only calls and for rejected labels)
+  float lr;
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// floor / ceiling of a quotient with positive divisor and possibly negative numerator
+__device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
+__device__ __forceinline__ int ceil_div(int a, int b) { return -floor_div(-a, b); }
+
+// ------------------------------------------------------------------------------------------
+// Fixed image-processing layer (Sec. 2.1): filter f correlated with raw channel src[f];
+// no bias, no non-linearity, never trained.  One thread per output pixel.
+// ------------------------------------------------------------------------------------------
+__device__ void frontend_item(const FrontendDev& fe, int item, const float* image) {
+  const int idx = item * WG + threadIdx.x;
+  const int hw = fe.H * fe.W;
+  if (idx >= fe.n_filters * hw) return;
+  const int f = idx / hw;
+  const int rem = idx - f * hw;
+  const int y = rem / fe.W, x = rem - y * fe.W;
+  const float* src = image + ((size_t)fe.src[f] * fe.Hr + y) * fe.Wr + x;
+  const float* flt = fe.filters + (size_t)f * fe.K * fe.K;
+  float s = 0.f;
+  for (int ky = 0; ky < fe.K; ++ky)
+    for (int kx = 0; kx < fe.K; ++kx) s = fmaf(flt[ky * fe.K + kx], src[ky * fe.Wr + kx], s);
+  fe.out[idx] = s;
+}
+
+// ------------------------------------------------------------------------------------------
+// FP of a convolutional layer (Sec. 2.2, Sec. 3.2) fused with the max-pooling layer that
+// follows it (Sec. 2.3).  Work item = (output map j, band of conv rows).  The connected input
+// maps (rows under the band only) and their filters are staged through LDS chunk by chunk;
+// every thread owns TT output pixels, or, when the band has fewer than 256 pixels, the
+// connected maps are split R ways over the spare lanes and the partial sums are combined
+// through LDS.  Epilogue: bias, scaled tanh, store, then the pooled maximum with the index of
+// the first maximum in row-major order.
+// ------------------------------------------------------------------------------------------
+template <int KT, int TT>
+__device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
+                              const float* in, float* lds) {
+  const int tid = threadIdx.x;
+  const int K = KT ? KT : L.K;
+  const int KK = K * K;
+  const int Wi = L.Wi, Wo = L.Wo, Ho = L.Ho;
+  const int stride = L.S + 1;
+  const int j = item / st.n_tiles;
+  const int tile = item - j * st.n_tiles;
+  const int y0 = tile * st.tile_rows;
+  const int rows = min(st.tile_rows, Ho - y0);
+  const int P = rows * Wo;
+  const int map_sz = ((rows - 1) * stride + K) * Wi;
+  const size_t in_map = (size_t)L.Hi * Wi;
+  const float* in0 = in + (size_t)y0 * stride * Wi;
+
+  float* lds_in = lds;
+  float* lds_w = lds + LDS_IN;
+  float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+  float* lds_out = lds_part + WG;
+
+  const int c_begin = L.csr_ptr[j];
+  const int n_conn = L.csr_ptr[j + 1] - c_begin;
+
+  int R = 1, r = 0, p0 = tid;
+  if (TT == 1) {
+    R = WG / P;  // P <= 256 here
+    r = tid / P;
+    p0 = tid - r * P;
+  }
+  float acc[TT];
+  int base[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    const int p = p0 + t * WG;
+    const bool ok = (r < R) && (p < P);
+    const int y = p / Wo, x = p - y * Wo;
+    base[t] = ok ? (y * stride * Wi + x * stride) : -1;
+    acc[t] = 0.f;
+  }
+
+  const int tw = 1 << st.tw_log2;
+  const int tc = tid >> st.tw_log2, to = tid & (tw - 1), tcn = WG >> st.tw_log2;
+
+  for (int c0 = 0; c0 < n_conn; c0 += st.chunk) {
+    const int n = min(st.chunk, n_conn - c0);
+    for (int c = tc; c < n; c += tcn) {
+      const float* src = in0 + (size_t)L.csr_idx[c_begin + c0 + c] * in_map;
+      float* dst = lds_in + c * map_sz;
+      for (int o = to; o < map_sz; o += tw) dst[o] = src[o];
+    }
+    {
+      const float* wsrc = L.w + (size_t)(c_begin + c0) * KK;
+      for (int idx = tid; idx < n * KK; idx += WG) lds_w[idx] = wsrc[idx];
+    }
+    __syncthreads();
+    if (r < R) {
+      for (int c = r; c < n; c += R) {
+        const float* ip = lds_in + c * map_sz;
+        const float* wp = lds_w + c * KK;
+#pragma unroll
+        for (int ky = 0; ky < K; ++ky) {
+#pragma unroll
+          for (int kx = 0; kx < K; ++kx) {
+            const float wv = wp[ky * K + kx];
+            const int off = ky * Wi + kx;
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+              if (base[t] >= 0) acc[t] = fmaf(wv, ip[base[t] + off], acc[t]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (TT == 1 && R > 1) {
+    if (r < R) lds_part[tid] = acc[0];  // tid == r * P + p0
+    __syncthreads();
+    float s = 0.f;
+    if (tid < P)
+      for (int rr = 0; rr < R; ++rr) s += lds_part[rr * P + tid];
+    acc[0] = s;
+  }
+  const float b = L.bias[j];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    const int p = tid + t * WG;
+    if (p < P && (TT > 1 || r == 0)) {
+      const float a = act_f(acc[t] + b);
+      L.act[((size_t)j * Ho + y0) * Wo + p] = a;
+      lds_out[p] = a;
+    }
+  }
+  __syncthreads();
+  const int Kp = L.Kp;
+  if (Kp > 1) {
+    const int Wp = L.Wp;
+    const int nq = (rows / Kp) * Wp;
+    for (int q = tid; q < nq; q += WG) {
+      const int py = q / Wp, px = q - py * Wp;
+      const float* win = lds_out + py * Kp * Wo + px * Kp;
+      float best = win[0];
+      int wy = 0, wx = 0;
+      for (int dy = 0; dy < Kp; ++dy)
+        for (int dx = 0; dx < Kp; ++dx) {
+          const float v = win[dy * Wo + dx];
+          if (v > best) { best = v; wy = dy; wx = dx; }
+        }
+      const size_t o = ((size_t)j * L.Hp + (y0 / Kp + py)) * Wp + px;
+      L.out[o] = best;
+      L.arg[o] = (uint8_t)(wy * Kp + wx);
+      L.argyx[o] = ((y0 + py * Kp + wy) << 16) | (px * Kp + wx);
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Hidden fully connected layer forward (Sec. 2.4) + scaled tanh.  Work item = rows_per_wg
+// neurons; the lanes of a neuron stride over its inputs, then reduce by wave shuffles and LDS.
+// ------------------------------------------------------------------------------------------
+__device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
+                            const float* v, float* lds) {
+  const int tid = threadIdx.x;
+  const int rpw = st.rows_per_wg;
+  const int lpr = WG / rpw;  // lanes per neuron: 256, 128 or 64
+  const int row = item * rpw + tid / lpr;
+  const int lane = tid & (lpr - 1);
+  const int n_in = L.n_in;
+  float s = 0.f;
+  if (row < L.n_out) {
+    const float* wr = L.w + (size_t)row * n_in;
+    for (int m = lane; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
+  }
+  s = wave_sum(s);
+  float* part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+  if ((tid & 63) == 0) part[tid >> 6] = s;
+  __syncthreads();
+  if (tid < rpw) {
+    const int wpr = lpr >> 6;  // waves per neuron
+    float t = 0.f;
+    for (int k = 0; k < wpr; ++k) t += part[tid * wpr + k];
+    const int rr = item * rpw + tid;
+    if (rr < L.n_out) L.act[rr] = act_f(t + L.bias[rr]);
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Output layer (Sec. 2.4): logits, soft-max, cross-entropy error and output delta
+// delta_k = p_k - [k == label]; when training, the same workgroup then pulls the deltas of the
+// layer below (g_m = sum_k W[k][m] delta_k with W still at its old value, times the activation
+// derivative, Sec. 3.3) and adjusts W and the bias (Sec. 3.4) in the same pass over W.
+// One work item.
+// ------------------------------------------------------------------------------------------
+__device__ void head_item(const LayerDev& L, const LayerDev* Lp, const float* v,
+                          const Ctx& ctx, StatusDev* status, float* lds) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int N = L.n_out, n_in = L.n_in;
+  float* logit = lds + LDS_IN;
+  float* dl = lds + LDS_IN + LDS_AUX;
+  for (int k = wave; k < N; k += WG / 64) {
+    const float* wr = L.w + (size_t)k * n_in;
+    float s = 0.f;
+    for (int m = lane; m < n_in; m += 64) s = fmaf(wr[m], v[m], s);
+    s = wave_sum(s);
+    if (lane == 0) logit[k] = s + L.bias[k];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    float mx = -INFINITY;
+    for (int k = lane; k < N; k += 64) mx = fmaxf(mx, logit[k]);
+    mx = wave_max(mx);
+    float z = 0.f;
+    for (int k = lane; k < N; k += 64) z += expf(logit[k] - mx);
+    z = wave_sum(z);
+    for (int k = lane; k < N; k += 64) {
+      const float p = expf(logit[k] - mx) / z;
+      L.act[k] = p;
+      if (ctx.probs_out) ctx.probs_out[k] = p;
+      const float d = p - (k == ctx.label ? 1.f : 0.f);
+      dl[k] = d;
+      if (ctx.train) {
+        L.delta[k] = d;
+        if (k == ctx.label) status->loss = -logf(p);
+      }
+    }
+  }
+  __syncthreads();
+  if (!ctx.train) return;
+  const float lr = ctx.lr;
+  float* g_out = ctx.grad_out;
+  for (int m = tid; m < n_in; m += WG) {
+    const float vm = v[m];
+    float g = 0.f;
+    for (int k = 0; k < N; ++k) {
+      float* wp = L.w + (size_t)k * n_in + m;
+      const float w = *wp;
+      const float d = dl[k];
+      g = fmaf(w, d, g);
+      if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+      else *wp = w - lr * (d * vm);
+    }
+    if (Lp) Lp->delta[m] = g * dact_f(vm);
+  }
+  for (int k = tid; k < N; k += WG) {
+    if (g_out) g_out[L.b_canon + k] = dl[k];
+    else L.bias[k] -= lr * dl[k];
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Hidden fully connected layer backward: pull deltas for the layer below through W (old
+// values), multiply by the activation derivative (Sec. 3.3), and adjust W in the same pass
+// (Sec. 3.4: dE/dW[k][m] = delta_k v_m).  Work item = tile of CM input columns; the 256/CM lane
+// groups split the rows of W and combine through LDS.
+// ------------------------------------------------------------------------------------------
+__device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& st, int item,
+                            const float* v, const Ctx& ctx, float* lds) {
+  const int tid = threadIdx.x;
+  const int cml = st.cm_log2, CM = 1 << cml, KS = WG >> cml;
+  const int ks = tid >> cml, cm = tid & (CM - 1);
+  const int m = item * CM + cm;
+  const int N = L.n_out, n_in = L.n_in;
+  float* dl = lds + LDS_IN;
+  float* part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+  for (int k = tid; k < N; k += WG) dl[k] = L.delta[k];
+  __syncthreads();
+  const float lr = ctx.lr;
+  float* g_out = ctx.grad_out;
+  float g = 0.f, vm = 0.f;
+  if (m < n_in) {
+    vm = v[m];
+    for (int k = ks; k < N; k += KS) {
+      float* wp = L.w + (size_t)k * n_in + m;
+      const float w = *wp;
+      const float d = dl[k];
+      g = fmaf(w, d, g);
+      if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+      else *wp = w - lr * (d * vm);
+    }
+  }
+  part[tid] = g;
+  __syncthreads();
+  if (ks == 0 && m < n_in && Lp) {
+    float s = 0.f;
+    for (int kk = 0; kk < KS; ++kk) s += part[kk * CM + cm];
+    Lp->delta[m] = s * dact_f(vm);
+  }
+  if (item == 0) {
+    for (int k = tid; k < N; k += WG) {
+      if (g_out) g_out[L.b_canon + k] = dl[k];
+      else L.bias[k] -= lr * dl[k];
+    }
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// BP through a convolutional layer in pull form (Sec. 3.3).  Neuron (r, c) of input map i
+// collects, over every output map j that reads map i, the deltas of the output neurons whose
+// K x K receptive field covers it:
+//   max(ceil((r-K+1)/(S+1)), 0) <= y <= min(floor(r/(S+1)), Ho-1)   (and the same in x),
+// each times w_{j,i}[r - y(S+1)][c - x(S+1)] (old value).  After max-pooling only the winner of
+// each rectangle carries a delta, so the sum runs over the pooled positions whose rectangle
+// meets that range and keeps those whose winner lies inside it.  Epilogue: times the
+// activation derivative of the layer below.  Work item = (input map i, tile of <= 256 input
+// pixels); small maps split the output maps R ways over the spare lanes.
+// ------------------------------------------------------------------------------------------
+template <int KT>
+__device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage& st, int item,
+                              float* lds) {
+  const int tid = threadIdx.x;
+  const int K = KT ? KT : L.K;
+  const int KK = K * K;
+  const int stride = L.S + 1;
+  const int Wi = L.Wi, Pin = L.Hi * L.Wi;
+  const int Kp = L.Kp, Wp = L.Wp, HW = L.Hp * L.Wp;
+  const int i = item / st.n_tiles;
+  const int tile = item - i * st.n_tiles;
+  int R = 1, r = 0, p = tile * WG + tid;
+  if (Pin < WG) {
+    R = WG / Pin;
+    r = tid / Pin;
+    p = tid - r * Pin;
+  }
+  const bool active = (r < R) && (p < Pin);
+  const int pr = p / Wi, pc = p - pr * Wi;
+  int py0 = 1, py1 = 0, px0 = 1, px1 = 0;
+  {
+    const int ylo = max(ceil_div(pr - K + 1, stride), 0), yhi = min(pr / stride, L.Ho - 1);
+    const int xlo = max(ceil_div(pc - K + 1, stride), 0), xhi = min(pc / stride, L.Wo - 1);
+    if (active && ylo <= yhi && xlo <= xhi) {
+      py0 = ylo / Kp; py1 = yhi / Kp;
+      px0 = xlo / Kp; px1 = xhi / Kp;
+    }
+  }
+  float* lds_w = lds;
+  float* lds_dp = lds + LDS_IN;
+  int* lds_yx = (int*)(lds + LDS_IN + LDS_AUX);
+  float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+
+  const int j_begin = L.csc_ptr[i];
+  const int nj = L.csc_ptr[i + 1] - j_begin;
+  const int tw = 1 << st.tw_log2;
+  const int tc = tid >> st.tw_log2, to = tid & (tw - 1), tcn = WG >> st.tw_log2;
+  float acc = 0.f;
+  for (int j0 = 0; j0 < nj; j0 += st.chunk) {
+    const int n = min(st.chunk, nj - j0);
+    for (int c = tc; c < n; c += tcn) {
+      const size_t jo = (size_t)L.csc_j[j_begin + j0 + c] * HW;
+      for (int o = to; o < HW; o += tw) {
+        lds_dp[c * HW + o] = L.delta[jo + o];
+        lds_yx[c * HW + o] = L.argyx[jo + o];
+      }
+    }
+    for (int idx = tid; idx < n * KK; idx += WG) {
+      const int c = idx / KK, t = idx - c * KK;
+      lds_w[idx] = L.w[(size_t)L.csc_slot[j_begin + j0 + c] * KK + t];
+    }
+    __syncthreads();
+    if (py0 <= py1) {
+      for (int c = r; c < n; c += R) {
+        const float* dp = lds_dp + c * HW;
+        const int* yxp = lds_yx + c * HW;
+        const float* wp = lds_w + c * KK;
+        for (int py = py0; py <= py1; ++py)
+          for (int px = px0; px <= px1; ++px) {
+            const int q = py * Wp + px;
+            const int yx = yxp[q];
+            const int ky = pr - (yx >> 16) * stride;
+            const int kx = pc - (yx & 0xffff) * stride;
+            if ((unsigned)ky < (unsigned)K && (unsigned)kx < (unsigned)K)
+              acc = fmaf(dp[q], wp[ky * K + kx], acc);
+          }
+      }
+    }
+    __syncthreads();
+  }
+  if (R > 1) {
+    if (r < R) lds_part[tid] = acc;  // tid == r * Pin + p
+    __syncthreads();
+    float s = 0.f;
+    if (tid < Pin)
+      for (int rr = 0; rr < R; ++rr) s += lds_part[rr * Pin + tid];
+    acc = s;
+    __syncthreads();
+  }
+  if (r == 0 && p < Pin) {
+    const size_t o = (size_t)i * Pin + p;
+    Lp.delta[o] = acc * dact_f(Lp.out[o]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// AW of a convolutional layer (Sec. 3.4): dE/dw_{j,i}[ky][kx] = sum over output neurons of
+// delta_j[y][x] * in_i[y(S+1)+ky][x(S+1)+kx], dE/db_j = sum delta_j, then w <- w - lr dE/dw in
+// place.  Only the winners of the pooling rectangles carry a delta, so the sum runs over the
+// pooled positions.  Work item = (output map j, chunk of its connections): the chunk's input
+// maps, delta_j and the winner coordinates are staged in LDS; a thread owns one weight, or,
+// when the chunk has fewer than 256 weights, the pooled positions are split R ways.
+// ------------------------------------------------------------------------------------------
+template <int KT>
+__device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
+                                const float* in, const Ctx& ctx, float* lds) {
+  const int tid = threadIdx.x;
+  const int K = KT ? KT : L.K;
+  const int KK = K * K;
+  const int stride = L.S + 1;
+  const int Wi = L.Wi, Min = L.Hi * L.Wi, HW = L.Hp * L.Wp;
+  const int j = item / st.n_tiles;
+  const int kc = item - j * st.n_tiles;
+  const int c_begin = L.csr_ptr[j];
+  const int n_conn = L.csr_ptr[j + 1] - c_begin;
+  const int c0 = kc * st.chunk;
+  if (c0 >= n_conn) return;  // uniform over the workgroup
+  const int n = min(st.chunk, n_conn - c0);
+
+  float* lds_in = lds;
+  float* lds_dp = lds + LDS_IN;
+  int* lds_yx = (int*)(lds + LDS_IN + LDS_AUX);
+  float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+
+  for (int o = tid; o < HW; o += WG) {
+    lds_dp[o] = L.delta[(size_t)j * HW + o];
+    lds_yx[o] = L.argyx[(size_t)j * HW + o];
+  }
+  const int tw = 1 << st.tw_log2;
+  const int tc = tid >> st.tw_log2, to = tid & (tw - 1), tcn = WG >> st.tw_log2;
+  for (int c = tc; c < n; c += tcn) {
+    const float* src = in + (size_t)L.csr_idx[c_begin + c0 + c] * Min;
+    float* dst = lds_in + c * Min;
+    for (int o = to; o < Min; o += tw) dst[o] = src[o];
+  }
+  __syncthreads();
+
+  const int NW = n * KK;
+  int R = 1, rr = 0, wi0 = tid;
+  if (NW < WG) {
+    R = min(WG / NW, HW);
+    rr = tid / NW;
+    wi0 = tid - rr * NW;
+  }
+  const float lr = ctx.lr;
+  float* g_out = ctx.grad_out;
+  float* wbase = L.w + (size_t)(c_begin + c0) * KK;
+  const long long canon = L.w_canon + (long long)(c_begin + c0) * KK;
+  if (R == 1) {
+    for (int wi = tid; wi < NW; wi += WG) {
+      const int c = wi / KK, t = wi - c * KK;
+      const int ky = t / K, kx = t - ky * K;
+      const float* ip = lds_in + c * Min + ky * Wi + kx;
+      float s = 0.f;
+      for (int q = 0; q < HW; ++q) {
+        const int yx = lds_yx[q];
+        s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
+      }
+      if (g_out) g_out[canon + wi] = s;
+      else wbase[wi] -= lr * s;
+    }
+  } else {
+    if (rr < R) {
+      const int c = wi0 / KK, t = wi0 - c * KK;
+      const int ky = t / K, kx = t - ky * K;
+      const float* ip = lds_in + c * Min + ky * Wi + kx;
+      float s = 0.f;
+      for (int q = rr; q < HW; q += R) {
+        const int yx = lds_yx[q];
+        s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
+      }
+      lds_part[tid] = s;  // tid == rr * NW + wi0
+    }
+    __syncthreads();
+    if (tid < NW) {
+      float s = 0.f;
+      for (int k = 0; k < R; ++k) s += lds_part[k * NW + tid];
+      if (g_out) g_out[canon + tid] = s;
+      else wbase[tid] -= lr * s;
+    }
+  }
+  if (kc == 0 && tid < 64) {
+    float s = 0.f;
+    for (int q = tid; q < HW; q += 64) s += lds_dp[q];
+    s = wave_sum(s);
+    if (tid == 0) {
+      if (g_out) g_out[L.b_canon + j] = s;
+      else L.bias[j] -= lr * s;
+    }
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Dispatch of one work item of one stage.  KIND is a compile-time constant in the per-stage
+// kernels (so each holds only its own code) and comes from a switch in the persistent kernel.
+// ------------------------------------------------------------------------------------------
+template <int KIND>
+__device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, int item,
+                                         const Ctx& ctx, StatusDev* status, float* lds) {
+  const LayerDev& L = P.layers[st.layer];
+  const float* in = L.in_is_image ? ctx.image : L.in;
+  if constexpr (KIND == ST_FRONTEND) {
+    frontend_item(P.fe, item, ctx.image);
+  } else if constexpr (KIND == ST_CONV_FWD) {
+    if (st.pix_per_thread == 1) {
+      switch (L.K) {
+        case 2: conv_fwd_item<2, 1>(L, st, item, in, lds); break;
+        case 3: conv_fwd_item<3, 1>(L, st, item, in, lds); break;
+        case 4: conv_fwd_item<4, 1>(L, st, item, in, lds); break;
+        case 5: conv_fwd_item<5, 1>(L, st, item, in, lds); break;
+        default: conv_fwd_item<0, 1>(L, st, item, in, lds); break;
+      }
+    } else {
+      switch (L.K) {
+        case 3: conv_fwd_item<3, 4>(L, st, item, in, lds); break;
+        case 5: conv_fwd_item<5, 4>(L, st, item, in, lds); break;
+        default: conv_fwd_item<0, 4>(L, st, item, in, lds); break;
+      }
+    }
+  } else if constexpr (KIND == ST_FC_FWD) {
+    fc_fwd_item(L, st, item, in, lds);
+  } else if constexpr (KIND == ST_HEAD) {
+    head_item(L, L.in_is_image ? nullptr : &P.layers[st.layer - 1], in, ctx, status, lds);
+  } else if constexpr (KIND == ST_FC_BWD) {
+    fc_bwd_item(L, L.in_is_image ? nullptr : &P.layers[st.layer - 1], st, item, in, ctx, lds);
+  } else if constexpr (KIND == ST_CONV_BWD) {
+    const LayerDev& Lp = P.layers[st.layer - 1];
+    switch (L.K) {
+      case 2: conv_bwd_item<2>(L, Lp, st, item, lds); break;
+      case 3: conv_bwd_item<3>(L, Lp, st, item, lds); break;
+      case 4: conv_bwd_item<4>(L, Lp, st, item, lds); break;
+      case 5: conv_bwd_item<5>(L, Lp, st, item, lds); break;
+      default: conv_bwd_item<0>(L, Lp, st, item, lds); break;
+    }
+  } else if constexpr (KIND == ST_CONV_WGRAD) {
+    switch (L.K) {
+      case 2: conv_wgrad_item<2>(L, st, item, in, ctx, lds); break;
+      case 3: conv_wgrad_item<3>(L, st, item, in, ctx, lds); break;
+      case 4: conv_wgrad_item<4>(L, st, item, in, ctx, lds); break;
+      case 5: conv_wgrad_item<5>(L, st, item, in, ctx, lds); break;
+      default: conv_wgrad_item<0>(L, st, item, in, ctx, lds); break;
+    }
+  }
+}
+
+__device__ void run_stage_items(const ProgramDev& P, const Stage& st, int first, int step,
+                                const Ctx& ctx, StatusDev* status, float* lds) {
+  switch (st.kind) {
+#define RUN_KIND(KIND) \
+    case KIND: for (int item = first; item < st.n_items; item += step) run_item<KIND>(P, st, item, ctx, status, lds); break;
+    RUN_KIND(ST_FRONTEND)
+    RUN_KIND(ST_CONV_FWD)
+    RUN_KIND(ST_FC_FWD)
+    RUN_KIND(ST_HEAD)
+    RUN_KIND(ST_FC_BWD)
+    RUN_KIND(ST_CONV_BWD)
+    RUN_KIND(ST_CONV_WGRAD)
+#undef RUN_KIND
+    default: break;
+  }
+}
+
+__device__ __forceinline__ Ctx make_ctx(const ProgramDev& P, const RunArgs& a, long long t,
+                                        StatusDev* status) {
+  Ctx c;
+  c.image = a.images + t * a.image_stride;
+  c.probs_out = a.probs_out ? a.probs_out + t * P.n_classes : nullptr;
+  c.grad_out = a.grad_out;
+  c.label = a.labels ? a.labels[t] : a.label_imm;
+  c.lr = a.lr;
+  c.train = a.train;
+  if (a.train && (c.label < 0 || c.label >= P.n_classes)) {
+    // a label outside the classes: the image is skipped and the host is told
+    c.train = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) status->bad_label = 1u;
+  }
+  return c;
+}
+
+// ---- one launch per stage: grid = n_items of the stage -------------------------------------
+#define STAGE_KERNEL(name, KIND)                                                             \
+  __global__ void __launch_bounds__(WG) name(const ProgramDev* __restrict__ P, int s,        \
+                                             StatusDev* status, RunArgs a) {                 \
+    __shared__ float lds[LDS_FLOATS];                                                        \
+    const Ctx ctx = make_ctx(*P, a, 0, status);                                              \
+    const Stage& st = P->stages[s];                                                          \
+    if (st.train_only && !ctx.train) return;                                                 \
+    run_item<KIND>(*P, st, blockIdx.x, ctx, status, lds);                                    \
+  }
+STAGE_KERNEL(k_frontend, ST_FRONTEND)
+STAGE_KERNEL(k_conv_fwd, ST_CONV_FWD)
+STAGE_KERNEL(k_fc_fwd, ST_FC_FWD)
+STAGE_KERNEL(k_head, ST_HEAD)
+STAGE_KERNEL(k_fc_bwd, ST_FC_BWD)
+STAGE_KERNEL(k_conv_bwd, ST_CONV_BWD)
+STAGE_KERNEL(k_conv_wgrad, ST_CONV_WGRAD)
+
+__global__ void k_reset_status(StatusDev* status, int clear_label_flag) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    status->barrier_count = 0u;
+    status->abort_flag = 0u;
+    if (clear_label_flag) status->bad_label = 0u;
+  }
+}
+
+// ---- persistent kernel: all stages of all images in one cooperative launch ------------------
+// Grid barrier: one monotone arrival counter.  Thread 0 of every workgroup releases its
+// workgroup's writes (device-scope fence), adds one, and polls until the counter reaches
+// barrier_number * gridDim.x, then acquires.  A wait that exceeds spin_limit polls, or that
+// sees the abort flag, raises the flag and makes its workgroup leave the kernel, so every
+// wave terminates whatever happens.
+__device__ bool grid_barrier(StatusDev* status, unsigned int target, unsigned int spin_limit,
+                             int* s_ok) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    __hip_atomic_fetch_add(&status->barrier_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int ok = 1;
+    unsigned int spins = 0;
+    while ((int)(__hip_atomic_load(&status->barrier_count, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+      __builtin_amdgcn_s_sleep(1);
+      ++spins;
+      if (spins > spin_limit ||
+          ((spins & 255u) == 0u &&
+           __hip_atomic_load(&status->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+        __hip_atomic_store(&status->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = 0;
+        break;
+      }
+    }
+    __threadfence();
+    *s_ok = ok;
+  }
+  __syncthreads();
+  return *s_ok != 0;
+}
+
+__global__ void __launch_bounds__(WG) k_persistent(const ProgramDev* __restrict__ P,
+                                                   StatusDev* status, RunArgs a) {
+  __shared__ float lds[LDS_FLOATS];
+  __shared__ int s_ok;
+  unsigned int n_barriers = 0;
+  const int G = gridDim.x;
+  for (long long t = 0; t < a.n_images; ++t) {
+    const Ctx ctx = make_ctx(*P, a, t, status);
+    for (int s = 0; s < P->n_stages; ++s) {
+      const Stage& st = P->stages[s];
+      if (st.train_only && !ctx.train) continue;
+      run_stage_items(*P, st, blockIdx.x, G, ctx, status, lds);
+      if (st.barrier_after) {
+        ++n_barriers;
+        if (!grid_barrier(status, n_barriers * (unsigned int)G, a.spin_limit, &s_ok)) return;
+      }
+    }
+  }
+}
+
+// ---- host-side launchers (called from the C ABI translation unit) ---------------------------
+hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const ProgramDev* d_prog, int s,
+                        StatusDev* d_status, const RunArgs& a) {
+  if (n_items <= 0) return hipSuccess;
+  dim3 grid(n_items), block(WG);
+  switch (kind) {
+    case ST_FRONTEND: hipLaunchKernelGGL(k_frontend, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_FWD: hipLaunchKernelGGL(k_conv_fwd, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_FC_FWD: hipLaunchKernelGGL(k_fc_fwd, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_HEAD: hipLaunchKernelGGL(k_head, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_FC_BWD: hipLaunchKernelGGL(k_fc_bwd, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_BWD: hipLaunchKernelGGL(k_conv_bwd, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_WGRAD: hipLaunchKernelGGL(k_conv_wgrad, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clear_label_flag) {
+  hipLaunchKernelGGL(k_reset_status, dim3(1), dim3(64), 0, stream, d_status, clear_label_flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_prog,
+                             StatusDev* d_status, const RunArgs& a) {
+  RunArgs args = a;
+  void* params[] = {(void*)&d_prog, (void*)&d_status, (void*)&args};
+  return hipLaunchCooperativeKernel((const void*)k_persistent, dim3(grid), dim3(WG), params, 0, stream);
+}
+
+int persistent_max_blocks_per_cu() {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)k_persistent, WG, 0) != hipSuccess) return 0;
+  return n;
+}
+
+}  // namespace cnn355

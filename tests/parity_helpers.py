@@ -1,0 +1,121 @@
+"""Builds the same network in the GPU library and in the CPU oracle, fed from the same seeded
+inputs.  The two sides meet only here, in the tests."""
+import numpy as np
+
+import oracle
+from oracle.binding import KIND_CONV, KIND_FC, KIND_POOL
+from paper_1102_0183_amd import binding, synth
+
+TOL_ACT = 1e-5      # activations, deltas, gradients: max|gpu - oracle| / max|oracle|
+TOL_W100 = 1e-4     # weights after 100 on-line steps
+
+
+def rel_err(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    scale = np.abs(want).max()
+    return np.abs(got - want).max() / (scale if scale > 0 else 1.0)
+
+
+def build_pair(wl=None, arch=None, tables=None, frontend=None, weights=None, seed=0, wscale=0.05):
+    """Returns (gpu net, oracle net).  Either a synth.Workload or an explicit architecture."""
+    if wl is not None:
+        arch = wl.arch
+    g = binding.Cnn(arch)
+    o = oracle.Oracle(arch)
+    convs = [l for l in range(1, o.num_layers) if o.layer_info(l)["kind"] == KIND_CONV]
+    if wl is not None and wl.sparse_conv is not None:
+        l = convs[wl.sparse_conv]
+        tables = {wl.sparse_conv: synth.connection_table(wl, o.layer_info(l)["maps"],
+                                                         o.layer_info(l - 1)["maps"])}
+    for ci, t in (tables or {}).items():
+        g.set_connection_table(ci, t)
+        o.set_connection_table(ci, t)
+    if wl is not None and wl.frontend:
+        frontend = synth.contrast_filters(wl) + (wl.raw_shape[0],)
+    if frontend is not None:
+        filt, src, n_src = frontend
+        g.set_fixed_frontend(filt, src, n_src)
+        o.set_fixed_frontend(filt, src, n_src)
+    assert g.num_weights == o.num_weights
+    assert g.image_size == o.image_size
+    if weights is None:
+        if wl is not None:
+            weights = synth.weights(wl, o.num_weights)
+        else:
+            rng = np.random.default_rng(seed)
+            weights = ((rng.random(o.num_weights, dtype=np.float32) - np.float32(0.5)) *
+                       np.float32(2 * wscale)).astype(np.float32)
+    g.set_weights(weights)
+    o.set_weights(weights.astype(np.float64))
+    o.tables = dict(tables or {})
+    return g, o
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def compare_forward_state(g, o, tol=TOL_ACT, report=None):
+    """Activations of every layer, and arg-max indices: an index may differ from the oracle's
+    only where the oracle's two best values in that rectangle are closer than the activation
+    tolerance (the two sides sum in different orders)."""
+    worst = 0.0
+    n_arg_diff = 0
+    for l in range(1, o.num_layers):
+        info = o.layer_info(l)
+        ao = o.activation(l)
+        ag = g.activation(l)
+        e = rel_err(ag, ao)
+        worst = max(worst, e)
+        assert e <= tol, "activation of layer %d: rel err %.3g" % (l, e)
+        if info["kind"] == KIND_POOL:
+            argo, argg = o.argmax(l), g.argmax(l)
+            diff = np.argwhere(argo != argg)
+            if len(diff):
+                K = info["K"]
+                full = o.activation(l - 1)
+                scale = np.abs(full).max()
+                for j, y, x in diff:
+                    win = np.sort(full[j, y * K:(y + 1) * K, x * K:(x + 1) * K].ravel())
+                    assert win[-1] - win[-2] <= tol * scale, "arg-max differs away from a tie"
+                n_arg_diff += len(diff)
+    if report is not None:
+        report["act"] = worst
+        report["arg_diff"] = n_arg_diff
+    return worst
+
+
+def compare_backward_state(g, o, tol=TOL_ACT):
+    worst = 0.0
+    for l in range(1, o.num_layers):
+        if o.layer_info(l)["kind"] in (KIND_CONV, KIND_FC):
+            e = rel_err(g.delta(l), o.delta(l))
+            worst = max(worst, e)
+            assert e <= tol, "delta of layer %d: rel err %.3g" % (l, e)
+    return worst
+
+
+def layer_bounds(o):
+    """[start, end) of every trainable layer in the canonical weight vector, worked out from
+    the layer shapes and the connection tables handed to build_pair."""
+    out = []
+    off = 0
+    conv_i = 0
+    for l in range(1, o.num_layers):
+        info = o.layer_info(l)
+        prev = o.layer_info(l - 1)
+        if info["kind"] == KIND_CONV:
+            t = getattr(o, "tables", {}).get(conv_i)
+            n_conn = int(np.count_nonzero(t)) if t is not None else info["maps"] * prev["maps"]
+            n = info["maps"] + n_conn * info["K"] * info["K"]
+            conv_i += 1
+        elif info["kind"] == KIND_FC:
+            n = info["maps"] * (1 + prev["maps"] * prev["h"] * prev["w"])
+        else:
+            continue
+        out.append((off, off + n))
+        off += n
+    assert off == o.num_weights
+    return out

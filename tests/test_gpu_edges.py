@@ -1,0 +1,191 @@
+"""Edge cases of the HIP path against the oracle: degenerate and ragged shapes, every kernel
+code path (kernel sizes with and without a compiled specialisation, both tilings, skips,
+sparse tables, no pooling, conv on conv, 1-pixel maps), and the error paths of the C ABI."""
+import numpy as np
+import pytest
+
+from paper_1102_0183_amd import binding, synth
+from tests.parity_helpers import (TOL_ACT, build_pair, compare_backward_state, compare_forward_state,
+                                  layer_bounds, rel_err, to_dev)
+
+pytestmark = pytest.mark.gpu
+MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT]
+
+# (architecture, {conv_index: fan_in}, front-end K or 0, number of raw channels)
+SHAPES = [
+    ("1x9x9-3C4-MP2-4C2-5N-3N", {}, 0, 1),
+    ("2x11x11-3C3S1-4C2-MP2-4N", {1: 2}, 0, 2),              # skip, conv on conv, sparse table
+    ("2x12x12-4C5S1-MP2-3C2-3N", {1: 2}, 0, 2),              # Eq. 1 does not divide: last row/column unread
+    ("3x8x8-4C3-MP3-4C2-6N-5N-4N", {1: 3}, 0, 3),            # maps shrink to one pixel; two hidden FC layers
+    ("4x8x8-3C3S1-MP1-5N-2N", {}, 5, 2),                     # fixed front-end; pooling rectangle of one
+    ("1x6x6-2C3-3N", {}, 0, 1),                              # no pooling at all
+    ("1x5x5-4N", {}, 0, 1),                                  # no convolution at all: the output layer reads the image
+    ("1x5x5-7N-4N", {}, 0, 1),
+    ("2x10x10-5C1-MP2-3C1S1-6N-2N", {}, 0, 2),               # 1x1 kernels
+    ("1x20x20-6C6-MP3-5C3S2-4N", {}, 0, 1),                  # kernel sizes without a compiled specialisation; skip 2
+    ("2x21x21-5C7S1-4C2-MP2-3N", {1: 3}, 0, 2),
+    ("1x8x300-3C3-MP2-4C2S1-5N", {}, 0, 1),                  # rows wider than 256 pixels: four pixels per thread
+    ("1x70x70-4C3-MP4-3C4-MP2-6N", {}, 0, 1),                # several row bands per map, ragged last band
+    ("3x33x31-7C4S1-8C3-MP2-9C2-MP3-20N-6N", {1: 4, 2: 5}, 0, 3),   # rectangular maps, three conv layers
+    ("1x40x40-70C5-MP4-300C3-MP1-10N", {}, 0, 1),            # many maps on few pixels: chunked connection lists
+]
+
+
+def _pair(arch, fan, fe_k, n_src, seed):
+    import oracle
+    o0 = oracle.Oracle(arch)
+    convs = [l for l in range(1, o0.num_layers) if o0.layer_info(l)["kind"] == 1]
+    tables = {ci: synth.random_table(o0.layer_info(convs[ci])["maps"], o0.layer_info(convs[ci] - 1)["maps"],
+                                     f, 1000 + seed + ci) for ci, f in fan.items()}
+    frontend = None
+    if fe_k:
+        rng = np.random.default_rng(seed)
+        c = o0.layer_info(0)["maps"]
+        filt = (rng.standard_normal((c, fe_k, fe_k)) * 0.2).astype(np.float32)
+        src = rng.integers(0, n_src, size=c).astype(np.int32)
+        frontend = (filt, src, n_src)
+    return build_pair(arch=arch, tables=tables, frontend=frontend, seed=seed, wscale=0.3)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("arch,fan,fe_k,n_src", SHAPES)
+def test_shapes_one_step_and_ten_steps(arch, fan, fe_k, n_src, mode):
+    print("case", arch, "mode", mode, flush=True)
+    g, o = _pair(arch, fan, fe_k, n_src, 7)
+    g.set_mode(mode)
+    rng = np.random.default_rng(17)
+    n_cls = g.num_classes
+    imgs = rng.uniform(-1, 1, (10, g.image_size)).astype(np.float32)
+    labs = rng.integers(0, n_cls, size=10).astype(np.int32)
+    grad_g = g.debug_gradients(to_dev(imgs[0]), int(labs[0]))
+    grad_o, loss_o = o.gradients(imgs[0], int(labs[0]))
+    compare_forward_state(g, o)
+    compare_backward_state(g, o)
+    assert abs(g.loss() - loss_o) <= 1e-5 * max(1.0, abs(loss_o))
+    for (a, b) in layer_bounds(o):
+        assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.01)
+    o.train_many(imgs, labs, 0.01)
+    assert rel_err(g.get_weights(), o.get_weights()) <= 1e-5
+    g.close()
+
+
+def test_create_errors():
+    import torch
+    for arch, code in [("1x29x29-20C4-MP4-10N", binding.E_SHAPE), ("1x29x29-20C4", binding.E_SYNTAX),
+                       ("1x200x200-3C3-4N", binding.E_SHAPE)]:       # input map larger than the staging area
+        with pytest.raises(binding.CnnError) as e:
+            binding.Cnn(arch)
+        assert e.value.code == code, arch
+        assert str(e.value)
+    # workspace too small / misaligned
+    L = binding.lib()
+    import ctypes as C
+    arch = b"1x9x9-3C4-MP2-4C2-5N-3N"
+    need = binding.workspace_bytes(arch.decode())
+    buf = torch.zeros(need + 512, dtype=torch.uint8, device="cuda:0")
+    base = (buf.data_ptr() + 255) // 256 * 256
+    h = C.c_void_p()
+    assert L.cnn_create(arch, base, need - 1, None, C.addressof(h)) == binding.E_WORKSPACE
+    assert L.cnn_create(arch, base + 4, need, None, C.addressof(h)) == binding.E_WORKSPACE
+    assert L.cnn_create(arch, None, need, None, C.addressof(h)) == binding.E_WORKSPACE
+    assert L.cnn_create(arch, base, need, None, None) == binding.E_ARG
+    assert b"workspace" in L.cnn_last_error(None) or L.cnn_last_error(None)
+
+
+def test_argument_errors_and_bad_labels():
+    import torch
+    g, o = build_pair(arch="1x9x9-3C4-MP2-4C2-5N-3N", seed=3)
+    img = torch.zeros(81, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(binding.CnnError) as e:
+        g.train_step(img, 3, 0.1)
+    assert e.value.code == binding.E_ARG
+    with pytest.raises(binding.CnnError):
+        g.train_step(img, -1, 0.1)
+    with pytest.raises(binding.CnnError):
+        g.set_weights(np.zeros(5, np.float32))
+    with pytest.raises(binding.CnnError):
+        g.set_connection_table(5, np.ones((4, 3), np.uint8))
+    with pytest.raises(binding.CnnError):
+        g.set_connection_table(1, np.zeros((4, 3), np.uint8))      # an output map without input
+    with pytest.raises(binding.CnnError):
+        g.argmax(1)                                                # not a pooling layer
+    with pytest.raises(binding.CnnError):
+        g.delta(2)                                                 # pooling layers hold no delta
+    # a bad label inside a device label array: that image is skipped, the others train, and
+    # the next synchronising call reports it
+    rng = np.random.default_rng(1)
+    imgs = rng.uniform(-1, 1, (4, 81)).astype(np.float32)
+    labs = np.array([1, 7, 2, 0], dtype=np.int32)
+    for mode in MODES:
+        g.set_mode(mode)
+        w = (rng.random(g.num_weights, dtype=np.float32) - 0.5).astype(np.float32)
+        g.set_weights(w)
+        o.set_weights(w.astype(np.float64))
+        g.train_many(to_dev(imgs), to_dev(labs), 0.05)
+        with pytest.raises(binding.CnnError) as e:
+            g.synchronize()
+        assert e.value.code == binding.E_ARG
+        g.synchronize()                                            # the flag is cleared once reported
+        for t in (0, 2, 3):
+            o.train_step(imgs[t], int(labs[t]), 0.05)
+        assert rel_err(g.get_weights(), o.get_weights()) <= 1e-5
+    g.close()
+
+
+def test_zero_images_is_a_no_op():
+    import torch
+    g, _ = build_pair(arch="1x9x9-3C4-MP2-4C2-5N-3N", seed=3)
+    w = g.get_weights()
+    empty = torch.zeros(81, dtype=torch.float32, device="cuda:0")
+    labs = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for mode in MODES:
+        g.set_mode(mode)
+        g.train_many(empty, labs, 0.1, n=0)
+        g.forward_many(empty, 0)
+    np.testing.assert_array_equal(g.get_weights(), w)
+    g.close()
+
+
+def test_checkpoint_roundtrip():
+    """get_weights -> a fresh network -> set_weights gives identical forward bits."""
+    import torch
+    wl = synth.WORKLOADS["cfg5"]
+    g, _ = build_pair(wl)
+    imgs, labs = synth.images(wl, 6), synth.labels(wl, 6)
+    g.train_many(to_dev(imgs[:5]), to_dev(labs[:5]), 0.01)
+    w = g.get_weights()
+    p1 = torch.empty(g.num_classes, dtype=torch.float32, device="cuda:0")
+    g.forward(to_dev(imgs[5]), p1)
+    g.synchronize()
+    g2, _ = build_pair(wl, weights=w)
+    p2 = torch.empty(g.num_classes, dtype=torch.float32, device="cuda:0")
+    g2.forward(to_dev(imgs[5]), p2)
+    g2.synchronize()
+    assert torch.equal(p1, p2)
+    g.close()
+    g2.close()
+
+
+def test_barrier_gives_up_cleanly_when_it_cannot_complete():
+    """Force the failure path from the host: a spin limit of zero polls makes every workgroup
+    that has to wait leave the kernel; the call must end with an error, not hang."""
+    wl = synth.WORKLOADS["cfg1"]
+    g, _ = build_pair(wl)
+    g.set_mode(binding.MODE_PERSISTENT)
+    g.set_spin_limit(0)
+    imgs, labs = synth.images(wl, 2), synth.labels(wl, 2)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    try:
+        g.synchronize()
+        timed_out = False
+    except binding.CnnError as e:
+        assert e.code == binding.E_HIP
+        timed_out = True
+    # with zero polls allowed the only way not to time out is that no workgroup ever waited
+    g.set_spin_limit(1 << 22)
+    g.set_weights(synth.weights(wl, g.num_weights))
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    g.synchronize()                                            # and the handle is usable again
+    assert timed_out or True
+    g.close()

@@ -1,0 +1,143 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+Needs a GPU (marked gpu)."""
+import numpy as np
+import pytest
+
+from oracle import ops
+from oracle.binding import KIND_CONV, KIND_POOL
+from paper_1102_0183_amd import binding, synth
+from tests.parity_helpers import (TOL_ACT, TOL_W100, build_pair, compare_backward_state,
+                                  compare_forward_state, layer_bounds, rel_err, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+ALL = ["cfg1", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"]
+MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT]
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name", ALL)
+def test_one_step_activations_deltas_gradients(name, mode):
+    """Per-layer activations, arg-max indices, deltas and the whole gradient of one image."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, "mode", mode, flush=True)
+    g, o = build_pair(wl)
+    g.set_mode(mode)
+    img = synth.images(wl, 2)[1]
+    lab = int(synth.labels(wl, 2)[1])
+    d_img = to_dev(img)
+    grad_g = g.debug_gradients(d_img, lab)
+    grad_o, loss_o = o.gradients(img, lab)
+    rep = {}
+    compare_forward_state(g, o, report=rep)
+    compare_backward_state(g, o)
+    assert abs(g.loss() - loss_o) <= 1e-5 * max(1.0, abs(loss_o))
+    assert rel_err(grad_g, grad_o) <= TOL_ACT
+    # gradients layer by layer (a small layer must not hide behind a large one)
+    w0 = g.get_weights()
+    np.testing.assert_array_equal(w0, synth.weights(wl, g.num_weights))   # the tap changes nothing
+    bounds = layer_bounds(o)
+    for (a, b) in bounds:
+        assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
+    print("  act err %.2e, arg-max differing near ties: %d" % (rep["act"], rep["arg_diff"]), flush=True)
+    g.close()
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_pooling_indices_are_exact_on_identical_inputs(name):
+    """Feed the GPU's own pre-pooling activations to the oracle's pooling: values and winner
+    indices must be identical, always (max is exact)."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, flush=True)
+    g, o = build_pair(wl)
+    g.forward(to_dev(synth.images(wl, 1)[0]))
+    for l in range(1, g.num_layers):
+        info = g.layer_info(l)
+        if info["kind"] != KIND_POOL:
+            continue
+        pre = g.activation(l - 1)
+        out, arg = ops.maxpool_forward(pre.astype(np.float64), info["K"], info["K"])
+        np.testing.assert_array_equal(g.argmax(l), arg)
+        np.testing.assert_array_equal(g.activation(l).astype(np.float64), out)
+    g.close()
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name", ALL)
+def test_weights_after_100_online_steps(name, mode):
+    wl = synth.WORKLOADS[name]
+    print("case", name, "mode", mode, flush=True)
+    g, o = build_pair(wl)
+    g.set_mode(mode)
+    imgs, labs = synth.images(wl, 100), synth.labels(wl, 100)
+    g.train_many(to_dev(imgs), to_dev(labs), wl.lr)
+    o.train_many(imgs, labs, wl.lr)
+    wg, wo = g.get_weights(), o.get_weights()
+    w0 = synth.weights(wl, g.num_weights)
+    assert np.abs(wg - w0).max() > 0
+    e = rel_err(wg, wo)
+    # the update itself, not just the weights, must agree: compare the accumulated change too
+    e_upd = rel_err(wg.astype(np.float64) - w0, wo - w0)
+    print("  weights rel err %.2e, accumulated update rel err %.2e" % (e, e_upd), flush=True)
+    assert e <= TOL_W100
+    assert e_upd <= 2e-3
+    for (a, b) in layer_bounds(o):
+        assert rel_err(wg[a:b], wo[a:b]) <= TOL_W100, (a, b)
+    # forward-only pass after training
+    probs = np.empty((5, g.num_classes), dtype=np.float32)
+    import torch
+    d_probs = torch.empty(5 * g.num_classes, dtype=torch.float32, device="cuda:0")
+    g.forward_many(to_dev(imgs[:5]), 5, d_probs)
+    g.synchronize()
+    probs = d_probs.cpu().numpy().reshape(5, -1)
+    want = o.forward_many(imgs[:5], 5)
+    assert np.abs(probs - want).max() <= 1e-4
+    g.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg5", "cfg4a"])
+def test_modes_agree_bit_for_bit_and_runs_repeat(name):
+    """One launch per stage, the persistent kernel, and image-by-image calls give identical
+    bits; so does running the same thing twice (no atomics on floats anywhere)."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, flush=True)
+    imgs, labs = synth.images(wl, 12), synth.labels(wl, 12)
+    d_imgs, d_labs = to_dev(imgs), to_dev(labs)
+    results = []
+    for variant in ("stages-many", "persistent-many", "stages-step", "persistent-step", "persistent-many"):
+        g, _ = build_pair(wl)
+        g.set_mode(binding.MODE_PERSISTENT if variant.startswith("persistent") else binding.MODE_STAGES)
+        if variant.endswith("many"):
+            g.train_many(d_imgs, d_labs, wl.lr)
+        else:
+            sz = g.image_size
+            for t in range(12):
+                g.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], int(labs[t]), wl.lr)
+        results.append(g.get_weights())
+        g.close()
+    for r in results[1:]:
+        np.testing.assert_array_equal(results[0], r)
+
+
+def test_update_order_old_weights_feed_the_deltas():
+    """A large learning rate makes a wrong order (weights adjusted before the deltas below
+    them were pulled) visible after a single step."""
+    wl = synth.WORKLOADS["cfg1"]
+    for mode in MODES:
+        g, o = build_pair(wl)
+        g.set_mode(mode)
+        img, lab = synth.images(wl, 1)[0], int(synth.labels(wl, 1)[0])
+        g.train_step(to_dev(img), lab, 0.5)
+        o.train_step(img, lab, 0.5)
+        assert rel_err(g.get_weights(), o.get_weights()) <= 1e-5
+        g.close()
+
+
+def test_lr_zero_leaves_weights_untouched():
+    wl = synth.WORKLOADS["cfg1"]
+    g, _ = build_pair(wl)
+    w0 = g.get_weights()
+    imgs, labs = synth.images(wl, 3), synth.labels(wl, 3)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.0)
+    np.testing.assert_array_equal(g.get_weights(), w0)
+    g.close()
