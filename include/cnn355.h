@@ -78,8 +78,13 @@ enum {
 int cnn_arch_info(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers);
 
 /* Host-only: bytes of device workspace cnn_create needs for `arch` (an upper bound that
- * also covers any connection table and front-end set later). */
+ * also covers any connection table and front-end set later).  Fails with CNN_E_SHAPE when a
+ * layer is larger than the kernels support. */
 int cnn_workspace_bytes(const char* arch, size_t* bytes);
+
+/* Host-only: the stages one training step of `arch` is issued as (one text line per stage:
+ * kind, layer, work items, tiling), written NUL-terminated into buf (truncated to n). */
+int cnn_plan_text(const char* arch, char* buf, size_t n);
 
 /* Build a network.  d_workspace: device memory of at least cnn_workspace_bytes bytes,
  * 256-byte aligned, owned by the caller, used exclusively by this handle.  hip_stream: a

@@ -35,6 +35,9 @@ def lib():
         L.oracle_op_act_deriv_from_output.argtypes = [C.c_double]
         L.oracle_op_softmax_xent.restype = C.c_double
         L.oracle_train_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_void_p]
+        L.oracle_backward_update.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_void_p]
+        L.oracle_adopt_argmax_hint.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_double,
+                                               C.c_void_p, C.c_void_p]
         L.oracle_train_many.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_double]
         L.oracle_forward_many.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.oracle_set_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
@@ -140,6 +143,23 @@ class Oracle:
         loss = C.c_double()
         self._ck(lib().oracle_train_step(self._h, img.ctypes.data, int(label), float(lr),
                                          C.addressof(loss)), "train_step")
+        return loss.value
+
+    def adopt_argmax_hint(self, layer, hint, tol):
+        """After forward(): take another implementation's pooling winners where the choice is a
+        near-tie (gap <= tol * max|input|).  Returns (adopted, rejected)."""
+        hint = np.ascontiguousarray(hint, dtype=np.uint8)
+        assert hint.size == self.layer_size(layer)
+        a, r = C.c_int(), C.c_int()
+        self._ck(lib().oracle_adopt_argmax_hint(self._h, int(layer), hint.ctypes.data, float(tol),
+                                                C.addressof(a), C.addressof(r)), "adopt_argmax_hint")
+        return a.value, r.value
+
+    def backward_update(self, label, lr):
+        """After forward(): the backward pass and the SGD update of one on-line step."""
+        loss = C.c_double()
+        self._ck(lib().oracle_backward_update(self._h, int(label), float(lr), C.addressof(loss)),
+                 "backward_update")
         return loss.value
 
     def train_many(self, images, labels, lr):

@@ -478,7 +478,12 @@ struct Net {
     } else {
       for (size_t t = 0; t < act[0].size(); ++t) act[0][t] = (T)image[t];
     }
-    for (int l = 1; l < n_layers(); ++l) {
+    forward_from(1);
+  }
+
+  // Layers first .. top, the input of layer `first` being current.
+  void forward_from(int first) {
+    for (int l = first; l < n_layers(); ++l) {
       Layer& a = L()[l];
       const Layer& p = L()[l - 1];
       if (a.kind == K_CONV) {
@@ -559,6 +564,41 @@ struct Net {
     return loss;
   }
 };
+
+// Tie-break hints for a max-pooling layer (test support).  Two implementations that sum in
+// different orders can disagree on the winner of a rectangle only where its two best values are
+// nearly equal; there both choices are valid results.  A hinted winner is adopted where the
+// oracle's own maximum exceeds the hinted value by at most tol * max|input|, and refused
+// otherwise.  After an adoption the layers above are recomputed from the changed pooled values.
+template <class T>
+int adopt_argmax_hint(Net<T>& n, int layer, const uint8_t* hint, double tol, int* adopted, int* rejected) {
+  if (layer < 1 || layer >= n.n_layers() || n.L()[layer].kind != K_POOL) return E_ARG;
+  const Layer& a = n.L()[layer];
+  const Layer& p = n.L()[layer - 1];
+  double scale = 0;
+  for (const T& v : n.act[layer - 1]) scale = std::max(scale, (double)std::fabs(v));
+  int na = 0, nr = 0;
+  for (int j = 0; j < a.maps; ++j)
+    for (int y = 0; y < a.h; ++y)
+      for (int x = 0; x < a.w; ++x) {
+        const size_t o = ((size_t)j * a.h + y) * a.w + x;
+        const int h = hint[o];
+        if (h == n.arg[layer][o]) continue;
+        if (h >= a.ky * a.kx) { ++nr; continue; }
+        const T vh = n.act[layer - 1][((size_t)j * p.h + y * a.ky + h / a.kx) * p.w + x * a.kx + h % a.kx];
+        if ((double)(n.act[layer][o] - vh) <= tol * scale) {
+          n.arg[layer][o] = (uint8_t)h;
+          n.act[layer][o] = vh;
+          ++na;
+        } else {
+          ++nr;
+        }
+      }
+  if (na && layer + 1 < n.n_layers()) n.forward_from(layer + 1);
+  if (adopted) *adopted = na;
+  if (rejected) *rejected = nr;
+  return E_OK;
+}
 
 struct Handle {
   int precision;  // 32 or 64
@@ -726,6 +766,27 @@ int oracle_train_step(oracle_t* h, const float* image, int32_t label, double lr,
     if (loss) *loss = (double)e;
   });
   return E_OK;
+}
+
+// Forward state must be current (oracle_forward, possibly followed by oracle_adopt_argmax_hint):
+// backward pass, gradients and the SGD update of one on-line step.
+int oracle_backward_update(oracle_t* h, int32_t label, double lr, double* loss) {
+  if (!h) return E_ARG;
+  if (check_label(h, label)) return E_ARG;
+  WITH_NET(h, {
+    net.backward(label);
+    for (size_t t = 0; t < net.weights.size(); ++t) net.weights[t] -= (decltype(net.loss))lr * net.grad[t];
+    if (loss) *loss = (double)net.loss;
+  });
+  return E_OK;
+}
+
+int oracle_adopt_argmax_hint(oracle_t* h, int layer, const uint8_t* hint, double tol, int* adopted,
+                             int* rejected) {
+  if (!h || !hint) return E_ARG;
+  int rc;
+  WITH_NET(h, rc = adopt_argmax_hint(net, layer, hint, tol, adopted, rejected));
+  return rc;
 }
 
 int oracle_train_many(oracle_t* h, const float* images, const int32_t* labels, size_t n, double lr) {

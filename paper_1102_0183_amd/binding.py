@@ -37,6 +37,7 @@ def lib():
         sig = {
             "cnn_arch_info": (C.c_int, [C.c_char_p, vp, vp, i32]),
             "cnn_workspace_bytes": (C.c_int, [C.c_char_p, vp]),
+            "cnn_plan_text": (C.c_int, [C.c_char_p, vp, sz]),
             "cnn_create": (C.c_int, [C.c_char_p, vp, sz, vp, vp]),
             "cnn_destroy": (None, [vp]),
             "cnn_set_connection_table": (C.c_int, [vp, C.c_int, vp]),
@@ -71,7 +72,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_create", "cnn_destroy",
+EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_create", "cnn_destroy",
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
@@ -104,6 +105,15 @@ def workspace_bytes(arch):
     if rc:
         raise CnnError(rc, "cnn_workspace_bytes(%r)" % arch, _err())
     return int(n.value)
+
+
+def plan_text(arch):
+    """Host-only: the stage list of one training step, one line per stage."""
+    buf = C.create_string_buffer(1 << 14)
+    rc = lib().cnn_plan_text(arch.encode(), buf, len(buf))
+    if rc:
+        raise CnnError(rc, "cnn_plan_text(%r)" % arch, _err())
+    return buf.value.decode()
 
 
 class Cnn:

@@ -181,6 +181,8 @@ struct cnn {
   struct FcBuf { float *act, *delta; };
   std::vector<ConvBuf> conv_buf;
   std::vector<FcBuf> fc_buf;
+  struct HostTable { std::vector<int> csr_ptr, csr_idx, csc_ptr, csc_j, csc_slot; int max_conn = 0, max_back = 0; };
+  std::vector<HostTable> host_tables;  // per convolutional layer, rebuilt by plan()
 
   size_t n_weights = 0, n_weights_max = 0;
   size_t image_size = 0;
@@ -226,7 +228,8 @@ size_t carve(cnn* net, void* base) {
   net->fc_buf.clear();
   for (size_t l = 1; l < A.size(); ++l) {
     if (A[l].kind == CNN_LAYER_CONV) {
-      const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
+      // a pooling rectangle of one pixel is the identity: the pooled values are the activations
+      const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL && A[l + 1].K > 1;
       const size_t full = (size_t)A[l].maps * A[l].h * A[l].w;
       const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : full;
       const size_t nc = (size_t)A[l].maps * A[l - 1].maps;
@@ -283,48 +286,106 @@ int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
   return CNN_OK;
 }
 
-int upload_tables(cnn* net, int conv_i, const LayerDev& L, const std::vector<uint8_t>& table, int* max_conn) {
-  std::vector<int> csr_ptr(L.Mo + 1, 0), csr_idx, csc_ptr(L.Mi + 1, 0), csc_j, csc_slot;
-  *max_conn = 0;
-  for (int j = 0; j < L.Mo; ++j) {
-    for (int i = 0; i < L.Mi; ++i)
-      if (table[(size_t)j * L.Mi + i]) csr_idx.push_back(i);
-    csr_ptr[j + 1] = (int)csr_idx.size();
-    *max_conn = std::max(*max_conn, csr_ptr[j + 1] - csr_ptr[j]);
+// Forward (CSR), backward (CSC) and slot tables of one convolutional layer from its 0/1 table.
+void build_tables(int Mo, int Mi, const std::vector<uint8_t>& table, cnn::HostTable& T) {
+  T = cnn::HostTable();
+  T.csr_ptr.assign(Mo + 1, 0);
+  T.csc_ptr.assign(Mi + 1, 0);
+  for (int j = 0; j < Mo; ++j) {
+    for (int i = 0; i < Mi; ++i)
+      if (table[(size_t)j * Mi + i]) T.csr_idx.push_back(i);
+    T.csr_ptr[j + 1] = (int)T.csr_idx.size();
+    T.max_conn = std::max(T.max_conn, T.csr_ptr[j + 1] - T.csr_ptr[j]);
   }
-  for (int i = 0; i < L.Mi; ++i) {
-    for (int j = 0; j < L.Mo; ++j)
-      for (int s = csr_ptr[j]; s < csr_ptr[j + 1]; ++s)
-        if (csr_idx[s] == i) { csc_j.push_back(j); csc_slot.push_back(s); }
-    csc_ptr[i + 1] = (int)csc_j.size();
+  for (int i = 0; i < Mi; ++i) {
+    for (int j = 0; j < Mo; ++j)
+      for (int s = T.csr_ptr[j]; s < T.csr_ptr[j + 1]; ++s)
+        if (T.csr_idx[s] == i) { T.csc_j.push_back(j); T.csc_slot.push_back(s); }
+    T.csc_ptr[i + 1] = (int)T.csc_j.size();
+    T.max_back = std::max(T.max_back, T.csc_ptr[i + 1] - T.csc_ptr[i]);
   }
-  const cnn::ConvBuf& b = net->conv_buf[conv_i];
-  HIP_TRY(net, hipMemcpy(b.csr_ptr, csr_ptr.data(), csr_ptr.size() * 4, hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(b.csr_idx, csr_idx.data(), csr_idx.size() * 4, hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(b.csc_ptr, csc_ptr.data(), csc_ptr.size() * 4, hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(b.csc_j, csc_j.data(), csc_j.size() * 4, hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(b.csc_slot, csc_slot.data(), csc_slot.size() * 4, hipMemcpyHostToDevice));
+}
+
+// Every size a kernel relies on, re-derived from the finished plan: a stage whose operands do
+// not fit its LDS areas or its thread mapping is refused here, never launched.
+int check_plan(cnn* net) {
+  const ProgramDev& P = net->prog;
+  auto bad = [&](int s, const char* what) {
+    return fail(&net->err, CNN_E_SHAPE, "stage " + std::to_string(s) + ": " + what);
+  };
+  for (int s = 0; s < P.n_stages; ++s) {
+    const Stage& st = P.stages[s];
+    const LayerDev& L = P.layers[st.layer];
+    if (st.n_items < 1) return bad(s, "no work items");
+    switch (st.kind) {
+      case ST_CONV_FWD: {
+        const int P_max = st.tile_rows * L.Wo;
+        const int map_sz = ((st.tile_rows - 1) * (L.S + 1) + L.K) * L.Wi;
+        if (st.tile_rows < L.Kp || st.tile_rows % L.Kp) return bad(s, "row band not a multiple of the pooling size");
+        if (st.pix_per_thread == 1 ? P_max > WG : P_max > MAX_TILE_PIX) return bad(s, "row band too large");
+        if (st.pix_per_thread != 1 && st.pix_per_thread != 4) return bad(s, "bad pixels per thread");
+        if (st.chunk < 1 || (long long)st.chunk * map_sz > LDS_IN) return bad(s, "input chunk exceeds the LDS input area");
+        if (st.chunk * L.K * L.K > LDS_AUX) return bad(s, "filter chunk exceeds the LDS filter area");
+        if (st.n_tiles * st.tile_rows < L.Ho || st.n_items != L.Mo * st.n_tiles) return bad(s, "row bands do not cover the map");
+        if ((1 << st.tw_log2) > WG) return bad(s, "staging width");
+        break;
+      }
+      case ST_CONV_BWD: {
+        const int HW = L.Hp * L.Wp;
+        if (st.chunk < 1 || st.chunk * HW > LDS_AUX || st.chunk * HW > LDS_AUX2) return bad(s, "delta chunk exceeds its LDS area");
+        if (st.chunk * L.K * L.K > LDS_IN) return bad(s, "filter chunk exceeds its LDS area");
+        if (st.n_tiles * WG < L.Hi * L.Wi || st.n_items != L.Mi * st.n_tiles) return bad(s, "pixel tiles do not cover the map");
+        if ((1 << st.tw_log2) > WG || st.layer < 1) return bad(s, "staging width / layer");
+        break;
+      }
+      case ST_CONV_WGRAD: {
+        if (st.chunk < 1 || (long long)st.chunk * L.Hi * L.Wi > LDS_IN) return bad(s, "input maps exceed the LDS input area");
+        if (L.Hp * L.Wp > LDS_AUX || L.Hp * L.Wp > LDS_AUX2) return bad(s, "pooled map exceeds its LDS area");
+        if (st.n_tiles * st.chunk < L.max_conn || st.n_items != L.Mo * st.n_tiles) return bad(s, "chunks do not cover the connections");
+        if ((1 << st.tw_log2) > WG) return bad(s, "staging width");
+        break;
+      }
+      case ST_FC_FWD:
+        if (st.rows_per_wg != 1 && st.rows_per_wg != 2 && st.rows_per_wg != 4) return bad(s, "rows per workgroup");
+        if (st.n_items * st.rows_per_wg < L.n_out) return bad(s, "rows not covered");
+        break;
+      case ST_HEAD:
+        if (L.n_out > LDS_AUX || L.n_out > LDS_AUX2 || st.n_items != 1) return bad(s, "output layer too wide");
+        break;
+      case ST_FC_BWD:
+        if (L.n_out > LDS_AUX) return bad(s, "layer too wide");
+        if (st.cm_log2 < 0 || st.cm_log2 > 8 || (st.n_items << st.cm_log2) < L.n_in) return bad(s, "columns not covered");
+        break;
+      case ST_FRONTEND:
+        if (st.n_items * WG < P.fe.n_filters * P.fe.H * P.fe.W) return bad(s, "pixels not covered");
+        break;
+      default:
+        return bad(s, "unknown stage kind");
+    }
+  }
   return CNN_OK;
 }
 
-// (Re)build layer descriptors, tables and the stage list, and upload them.  Weights are zeroed.
-int rebuild(cnn* net) {
+// Build layer descriptors, tables and the stage list on the host (no device call).  Works on
+// a handle whose workspace pointers are NULL (measuring / checking only).
+int plan(cnn* net) {
   const auto& A = net->arch;
   ProgramDev& P = net->prog;
   std::memset(&P, 0, sizeof(P));
-  HIP_TRY(net, hipStreamSynchronize(net->stream));
   net->dev_of_arch.assign(A.size(), -1);
+  net->host_tables.assign(net->tables.size(), cnn::HostTable());
   int nl = 0, conv_i = 0, fc_i = 0;
   std::vector<int> conv_of_dev(MAX_LAYERS, -1);  // descriptor index -> convolutional layer index
   size_t woff = 0;
   const float* below = nullptr;  // output buffer of the layer below
   const bool fe = net->fe_n > 0;
+  bool has_below = fe;           // (pointers are all NULL when only measuring)
   if (fe) below = net->d_fe_out;
   for (size_t l = 1; l < A.size(); ++l) {
     if (A[l].kind == CNN_LAYER_POOL) { net->dev_of_arch[l] = nl - 1; continue; }
     if (nl >= MAX_LAYERS) return fail(&net->err, CNN_E_SHAPE, "too many layers");
     LayerDev& L = P.layers[nl];
-    L.in_is_image = (below == nullptr);
+    L.in_is_image = !has_below;
     L.in = below;
     if (A[l].kind == CNN_LAYER_CONV) {
       const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
@@ -344,21 +405,12 @@ int rebuild(cnn* net) {
       L.act = b.act; L.out = b.out; L.delta = b.delta; L.arg = b.arg; L.argyx = b.argyx;
       L.csr_ptr = b.csr_ptr; L.csr_idx = b.csr_idx; L.csc_ptr = b.csc_ptr; L.csc_j = b.csc_j; L.csc_slot = b.csc_slot;
       conv_of_dev[nl] = conv_i;
-      int rc = upload_tables(net, conv_i, L, net->tables[conv_i], &L.max_conn);
-      if (rc) return rc;
-      size_t n_conn = 0;
-      for (uint8_t v : net->tables[conv_i]) n_conn += v ? 1 : 0;
+      build_tables(L.Mo, L.Mi, net->tables[conv_i], net->host_tables[conv_i]);
+      L.max_conn = net->host_tables[conv_i].max_conn;
+      const size_t n_conn = net->host_tables[conv_i].csr_idx.size();
       L.b_canon = (long long)woff;
       L.w_canon = (long long)(woff + L.Mo);
       woff += L.Mo + n_conn * L.K * L.K;
-      if (L.Kp == 1) {  // no pooling: every neuron is its own winner
-        std::vector<int> yx((size_t)L.Mo * L.Ho * L.Wo);
-        for (int j = 0; j < L.Mo; ++j)
-          for (int y = 0; y < L.Ho; ++y)
-            for (int x = 0; x < L.Wo; ++x) yx[((size_t)j * L.Ho + y) * L.Wo + x] = (y << 16) | x;
-        HIP_TRY(net, hipMemcpy(L.argyx, yx.data(), yx.size() * 4, hipMemcpyHostToDevice));
-        HIP_TRY(net, hipMemset(L.arg, 0, yx.size()));
-      }
       ++conv_i;
     } else {
       L.kind = L_FC;
@@ -377,6 +429,7 @@ int rebuild(cnn* net) {
     L.bias = net->d_weights + L.b_canon;
     L.w = net->d_weights + L.w_canon;
     below = L.out;
+    has_below = true;
     net->dev_of_arch[l] = nl;
     ++nl;
   }
@@ -446,14 +499,7 @@ int rebuild(cnn* net) {
         if (with_pending) { add_wgrad(pending_wgrad, 0); pending_wgrad = -1; }
         Stage& s = add(ST_CONV_BWD, l, 0, 1, 1);
         const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.K;
-        int max_back = 0;
-        {
-          std::vector<int> cnt(L.Mi, 0);
-          const auto& t = net->tables[conv_of_dev[l]];
-          for (int j = 0; j < L.Mo; ++j)
-            for (int i = 0; i < L.Mi; ++i) cnt[i] += t[(size_t)j * L.Mi + i] ? 1 : 0;
-          for (int v : cnt) max_back = std::max(max_back, v);
-        }
+        const int max_back = net->host_tables[conv_of_dev[l]].max_back;
         s.n_tiles = (Pin + WG - 1) / WG;
         s.n_items = L.Mi * s.n_tiles;
         s.chunk = std::max(1, std::min({LDS_AUX / HW, LDS_IN / KK, std::max(1, max_back)}));
@@ -471,10 +517,44 @@ int rebuild(cnn* net) {
   if (ns > 0) P.stages[ns - 1].barrier_after = 1;
   P.n_stages = ns;
 
+  return check_plan(net);
+}
+
+// Upload what plan() built.  Weights are zeroed.
+int upload(cnn* net) {
+  const ProgramDev& P = net->prog;
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  int conv_i = 0;
+  for (int l = 0; l < P.n_layers; ++l) {
+    const LayerDev& L = P.layers[l];
+    if (L.kind != L_CONV) continue;
+    const cnn::HostTable& T = net->host_tables[conv_i];
+    const cnn::ConvBuf& b = net->conv_buf[conv_i];
+    HIP_TRY(net, hipMemcpy(b.csr_ptr, T.csr_ptr.data(), T.csr_ptr.size() * 4, hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(b.csr_idx, T.csr_idx.data(), T.csr_idx.size() * 4, hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(b.csc_ptr, T.csc_ptr.data(), T.csc_ptr.size() * 4, hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(b.csc_j, T.csc_j.data(), T.csc_j.size() * 4, hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(b.csc_slot, T.csc_slot.data(), T.csc_slot.size() * 4, hipMemcpyHostToDevice));
+    if (L.Kp == 1) {  // no pooling: every neuron is its own winner
+      std::vector<int> yx((size_t)L.Mo * L.Ho * L.Wo);
+      for (int j = 0; j < L.Mo; ++j)
+        for (int y = 0; y < L.Ho; ++y)
+          for (int x = 0; x < L.Wo; ++x) yx[((size_t)j * L.Ho + y) * L.Wo + x] = (y << 16) | x;
+      HIP_TRY(net, hipMemcpy(L.argyx, yx.data(), yx.size() * 4, hipMemcpyHostToDevice));
+      HIP_TRY(net, hipMemset(L.arg, 0, yx.size()));
+    }
+    ++conv_i;
+  }
   HIP_TRY(net, hipMemcpy(net->d_prog, &P, sizeof(P), hipMemcpyHostToDevice));
   HIP_TRY(net, hipMemset(net->d_weights, 0, net->n_weights_max * sizeof(float)));
   HIP_TRY(net, hipMemset(net->d_status, 0, sizeof(StatusDev)));
   return CNN_OK;
+}
+
+int rebuild(cnn* net) {
+  int rc = plan(net);
+  if (rc) return rc;
+  return upload(net);
 }
 
 int check_status(cnn* net) {
@@ -551,6 +631,36 @@ int cnn_workspace_bytes(const char* arch, size_t* bytes) {
   int rc = parse_arch(arch, tmp.arch, nullptr);
   if (rc) return rc;
   *bytes = carve(&tmp, nullptr);
+  for (size_t l = 1; l < tmp.arch.size(); ++l)
+    if (tmp.arch[l].kind == CNN_LAYER_CONV)
+      tmp.tables.emplace_back((size_t)tmp.arch[l].maps * tmp.arch[l - 1].maps, (uint8_t)1);
+  rc = plan(&tmp);  // shapes the kernels cannot take are refused here, without a device
+  if (rc) g_err = tmp.err;
+  return rc;
+}
+
+int cnn_plan_text(const char* arch, char* buf, size_t n) {
+  if (!buf || n == 0) return fail(nullptr, CNN_E_ARG, "buf is NULL");
+  cnn tmp;
+  int rc = parse_arch(arch, tmp.arch, nullptr);
+  if (rc) return rc;
+  carve(&tmp, nullptr);
+  for (size_t l = 1; l < tmp.arch.size(); ++l)
+    if (tmp.arch[l].kind == CNN_LAYER_CONV)
+      tmp.tables.emplace_back((size_t)tmp.arch[l].maps * tmp.arch[l - 1].maps, (uint8_t)1);
+  rc = plan(&tmp);
+  if (rc) { g_err = tmp.err; return rc; }
+  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad"};
+  std::string out;
+  char line[256];
+  for (int s = 0; s < tmp.prog.n_stages; ++s) {
+    const Stage& st = tmp.prog.stages[s];
+    std::snprintf(line, sizeof line, "%2d %-10s layer=%d items=%d barrier=%d train_only=%d rows=%d tiles=%d chunk=%d tw=%d ppt=%d rpw=%d cm=%d\n",
+                  s, names[st.kind], st.layer, st.n_items, st.barrier_after, st.train_only, st.tile_rows, st.n_tiles,
+                  st.chunk, 1 << st.tw_log2, st.pix_per_thread, st.rows_per_wg, 1 << st.cm_log2);
+    out += line;
+  }
+  std::snprintf(buf, n, "%s", out.c_str());
   return CNN_OK;
 }
 
@@ -747,7 +857,9 @@ int cnn_get_delta(cnn_t* net, int layer, float* host_dst) {
   for (int j = 0; j < L.Mo; ++j)
     for (int q = 0; q < L.Hp * L.Wp; ++q) {
       const int v = yx[(size_t)j * L.Hp * L.Wp + q];
-      host_dst[((size_t)j * L.Ho + (v >> 16)) * L.Wo + (v & 0xffff)] = d[(size_t)j * L.Hp * L.Wp + q];
+      const int y = v >> 16, x = v & 0xffff;
+      if (y < 0 || y >= L.Ho || x >= L.Wo) continue;  // no forward pass has filled the winners yet
+      host_dst[((size_t)j * L.Ho + y) * L.Wo + x] = d[(size_t)j * L.Hp * L.Wp + q];
     }
   return rc;
 }

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_1102_0183_amd import binding, synth
-from tests.parity_helpers import (TOL_ACT, build_pair, compare_backward_state, compare_forward_state,
+from tests.parity_helpers import (TOL_ACT, TOL_W100, build_pair, compare_backward_state, compare_forward_state,
                                   layer_bounds, rel_err, to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -23,10 +23,10 @@ SHAPES = [
     ("1x5x5-7N-4N", {}, 0, 1),
     ("2x10x10-5C1-MP2-3C1S1-6N-2N", {}, 0, 2),               # 1x1 kernels
     ("1x20x20-6C6-MP3-5C3S2-4N", {}, 0, 1),                  # kernel sizes without a compiled specialisation; skip 2
-    ("2x21x21-5C7S1-4C2-MP2-3N", {1: 3}, 0, 2),
+    ("2x23x23-5C7S1-4C2-MP2-3N", {1: 3}, 0, 2),
     ("1x8x300-3C3-MP2-4C2S1-5N", {}, 0, 1),                  # rows wider than 256 pixels: four pixels per thread
     ("1x70x70-4C3-MP4-3C4-MP2-6N", {}, 0, 1),                # several row bands per map, ragged last band
-    ("3x33x31-7C4S1-8C3-MP2-9C2-MP3-20N-6N", {1: 4, 2: 5}, 0, 3),   # rectangular maps, three conv layers
+    ("3x34x47-7C4S1-8C3-MP2-9C2-MP3-20N-6N", {1: 4, 2: 5}, 0, 3),   # rectangular maps, three conv layers
     ("1x40x40-70C5-MP4-300C3-MP1-10N", {}, 0, 1),            # many maps on few pixels: chunked connection lists
 ]
 
@@ -66,7 +66,8 @@ def test_shapes_one_step_and_ten_steps(arch, fan, fe_k, n_src, mode):
         assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
     g.train_many(to_dev(imgs), to_dev(labs), 0.01)
     o.train_many(imgs, labs, 0.01)
-    assert rel_err(g.get_weights(), o.get_weights()) <= 1e-5
+    # ten on-line steps with large weights and a large rate: the stated bound for trained weights
+    assert rel_err(g.get_weights(), o.get_weights()) <= TOL_W100
     g.close()
 
 

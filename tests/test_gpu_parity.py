@@ -65,34 +65,61 @@ def test_pooling_indices_are_exact_on_identical_inputs(name):
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name", ALL)
 def test_weights_after_100_online_steps(name, mode):
+    """100 on-line steps, GPU and oracle side by side from the same initial weights.
+
+    The two sides sum in different orders, so once in a few hundred thousand pooling
+    rectangles their winners differ at a near-tie; either winner is a valid result, but the
+    trajectories then part for good.  The GPU therefore steps image by image and the oracle is
+    told the GPU's winners: it adopts one only where its own two candidates are closer than the
+    activation tolerance and refuses it otherwise (a refusal fails the test).  The batched
+    entry point is then required to reproduce the stepwise GPU weights bit for bit."""
     wl = synth.WORKLOADS[name]
     print("case", name, "mode", mode, flush=True)
     g, o = build_pair(wl)
     g.set_mode(mode)
-    imgs, labs = synth.images(wl, 100), synth.labels(wl, 100)
-    g.train_many(to_dev(imgs), to_dev(labs), wl.lr)
-    o.train_many(imgs, labs, wl.lr)
+    n = 100
+    imgs, labs = synth.images(wl, n), synth.labels(wl, n)
+    d_imgs, d_labs = to_dev(imgs), to_dev(labs)
+    pools = [l for l in range(1, o.num_layers) if o.layer_info(l)["kind"] == KIND_POOL]
+    sz = g.image_size
+    adopted = 0
+    for t in range(n):
+        g.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], int(labs[t]), wl.lr)
+        o.forward(imgs[t])
+        for l in pools:
+            a, r = o.adopt_argmax_hint(l, g.argmax(l), TOL_ACT)
+            assert r == 0, "step %d layer %d: GPU winner is not a near-tie of the oracle's" % (t, l)
+            adopted += a
+        loss_o = o.backward_update(int(labs[t]), wl.lr)
+        if t % 25 == 0:
+            assert abs(g.loss() - loss_o) <= 1e-5 * max(1.0, abs(loss_o))
     wg, wo = g.get_weights(), o.get_weights()
     w0 = synth.weights(wl, g.num_weights)
     assert np.abs(wg - w0).max() > 0
     e = rel_err(wg, wo)
-    # the update itself, not just the weights, must agree: compare the accumulated change too
+    # the accumulated change, not just the weights, must agree
     e_upd = rel_err(wg.astype(np.float64) - w0, wo - w0)
-    print("  weights rel err %.2e, accumulated update rel err %.2e" % (e, e_upd), flush=True)
+    print("  weights rel err %.2e, accumulated update rel err %.2e, near-tie winners adopted: %d"
+          % (e, e_upd, adopted), flush=True)
     assert e <= TOL_W100
-    assert e_upd <= 2e-3
+    assert e_upd <= 1e-3
     for (a, b) in layer_bounds(o):
         assert rel_err(wg[a:b], wo[a:b]) <= TOL_W100, (a, b)
     # forward-only pass after training
-    probs = np.empty((5, g.num_classes), dtype=np.float32)
     import torch
     d_probs = torch.empty(5 * g.num_classes, dtype=torch.float32, device="cuda:0")
-    g.forward_many(to_dev(imgs[:5]), 5, d_probs)
+    g.forward_many(d_imgs, 5, d_probs)
     g.synchronize()
     probs = d_probs.cpu().numpy().reshape(5, -1)
     want = o.forward_many(imgs[:5], 5)
     assert np.abs(probs - want).max() <= 1e-4
+    # the batched call must land on the very same bits
+    g2, _ = build_pair(wl)
+    g2.set_mode(mode)
+    g2.train_many(d_imgs, d_labs, wl.lr)
+    np.testing.assert_array_equal(g2.get_weights(), wg)
     g.close()
+    g2.close()
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg5", "cfg4a"])

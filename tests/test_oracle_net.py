@@ -217,3 +217,56 @@ def test_float_instantiation_tracks_double():
     of.train_many(imgs, labs, 1e-3)
     d = np.abs(od.get_weights() - of.get_weights()).max()
     assert 0 < d < 1e-6
+
+
+def test_forward_then_backward_update_equals_train_step():
+    o, w, img, label, _, _ = _build("1x9x9-3C4-MP2-4C2-5N-3N", {}, False, 12)
+    o2, _, _, _, _, _ = _build("1x9x9-3C4-MP2-4C2-5N-3N", {}, False, 12)
+    e1 = o.train_step(img, label, 0.05)
+    o2.forward(img)
+    e2 = o2.backward_update(label, 0.05)
+    assert e1 == e2
+    np.testing.assert_array_equal(o.get_weights(), o2.get_weights())
+
+
+def test_argmax_hints_are_adopted_only_at_near_ties():
+    """Hints exist so that a second implementation's valid choice at a near-tie can be
+    followed; anything but a near-tie is refused and changes nothing."""
+    arch = "1x4x4-1C1-MP2-2N"
+    o = oracle.Oracle(arch)
+    # weights: conv bias 0, kernel 1 (identity up to the tanh); FC arbitrary
+    w = np.zeros(o.num_weights)
+    w[1] = 1.0
+    w[4:] = np.arange(o.num_weights - 4) * 0.1 - 0.3
+    o.set_weights(w)
+    img = np.array([[0.50, 0.50 - 1e-9, 0.1, 0.2],
+                    [0.10, 0.20, 0.9, 0.3],
+                    [0.30, 0.10, 0.4, 0.4],
+                    [0.20, 0.25, 0.1, 0.2]], dtype=np.float64).astype(np.float32)
+    # float32 rounding makes the first two equal or nearly so; window (1,1) holds an exact tie
+    o.forward(img)
+    own = o.argmax(2).copy()
+    assert own[0, 1, 1] == 0                       # exact tie -> first in row-major order
+    pooled = o.activation(2).copy()
+    # 1) hint equal to own choice: nothing happens
+    assert o.adopt_argmax_hint(2, own, 1e-6) == (0, 0)
+    # 2) hint picks the other member of the exact tie: adopted, pooled value unchanged
+    hint = own.copy()
+    hint[0, 1, 1] = 1
+    assert o.adopt_argmax_hint(2, hint, 1e-6) == (1, 0)
+    assert o.argmax(2)[0, 1, 1] == 1
+    np.testing.assert_allclose(o.activation(2), pooled, atol=1e-12)
+    # the delta now goes to the hinted position
+    o.backward_update(1, 0.0)
+    d = o.delta(1)[0]
+    assert d[2, 3] != 0 and d[2, 2] == 0
+    # 3) a hint that is not a near-tie is refused and leaves the state alone
+    o.forward(img)
+    hint = o.argmax(2).copy()
+    hint[0, 0, 1] = 0                              # value 0.1 against the maximum 0.9
+    assert o.adopt_argmax_hint(2, hint, 1e-6) == (0, 1)
+    np.testing.assert_array_equal(o.argmax(2), own)
+    # 4) an index outside the rectangle is refused
+    hint = own.copy()
+    hint[0, 0, 0] = 7
+    assert o.adopt_argmax_hint(2, hint, 1e-6) == (0, 1)
