@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the on-line training hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--mode persistent|stages]
+
+One "step" is one cnn_train_many call: B consecutive images of the 60,000-image synthetic
+29x29 stream (workload cfg2) trained on-line -- forward, delta pass, weight gradients and an
+SGD update after every image -- on the net 1x29x29-20C4-MP2-40C5-MP3-150N-10N.  The stream is
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+value        = images trained per second over the K timed steps (wall clock, synchronised).
+roofline     = the dominant kernel's algorithmic bytes per launch / its mean launch duration,
+               measured with HIP events on the launch stream, against the 8 TB/s HBM peak.
+cpu_baseline = the CPU oracle (float32 instantiation, OpenMP over output maps) timed on a
+               prefix of the same stream on this machine's host cores.
+extra        = the other measurements the workload names (larger net, forward-only passes).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_train_image(info, n_weights, image_floats):
+    """Compulsory traffic of one on-line step, fp32: every weight read by the forward pass, read
+    again by the delta pass (except the first layer, below which nothing is propagated), and read
+    and written by the update; the image read twice (forward, first layer's weight gradients);
+    every layer output written once and read once forward and once backward; one delta per
+    pooled position written and read; arg-max bytes written and read."""
+    first = info[1]
+    first_w = first["maps"] * (1 + info[0]["maps"] * first["K"] ** 2) if first["kind"] == 1 else \
+        first["maps"] * (1 + info[0]["maps"] * info[0]["h"] * info[0]["w"])
+    b = 4 * (4 * n_weights - first_w)
+    b += 4 * 2 * image_floats
+    for l in range(1, len(info)):
+        n = info[l]["maps"] * info[l]["h"] * info[l]["w"]
+        if info[l]["kind"] == 1:      # conv: full-resolution output written once
+            b += 4 * n
+            pooled = l + 1 < len(info) and info[l + 1]["kind"] == 2
+            if not pooled:
+                b += 4 * 2 * n + 4 * 2 * n      # read fwd + bwd, delta write + read
+        elif info[l]["kind"] == 2:    # pool: pooled values w + 2r, arg-max w + r, delta w + r
+            b += 4 * 3 * n + 2 * n + 4 * 2 * n
+        else:                         # fully connected: output w + 2r, delta w + r
+            b += 4 * 3 * n + 4 * 2 * n
+    return b
+
+
+def algorithmic_bytes_per_forward_image(info, n_weights, image_floats):
+    b = 4 * n_weights + 4 * image_floats
+    for l in range(1, len(info)):
+        n = info[l]["maps"] * info[l]["h"] * info[l]["w"]
+        b += 4 * n if info[l]["kind"] == 1 else 4 * 2 * n
+    return b
+
+
+def time_steps(torch, fn, steps, warmup):
+    """W untimed warm-up steps, then K steps: wall clock bracketed by synchronize on both sides,
+    and HIP events around every launch on the launch stream."""
+    stream = torch.cuda.current_stream()
+    for k in range(warmup):
+        fn(k)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+    t0 = time.perf_counter()
+    for k in range(steps):
+        ev[k][0].record(stream)
+        fn(warmup + k)
+        ev[k][1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [a.elapsed_time(b) for a, b in ev]
+    return wall, kernel_ms
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=1000, help="images per step (one cnn_train_many call)")
+    ap.add_argument("--mode", choices=["persistent", "stages"], default="persistent")
+    ap.add_argument("--grid", type=int, default=0, help="workgroups of the persistent kernel (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (on-line SGD is a strict chain over images); "
+                 "--gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    from paper_1102_0183_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = "cuda:0"
+    wl = synth.WORKLOADS["cfg2a"]
+    n_stream = wl.n_images
+    imgs = synth.images(wl)
+    labs = synth.labels(wl)
+    d_imgs = torch.from_numpy(imgs).to(dev)
+    d_labs = torch.from_numpy(labs).to(dev)
+    B = min(args.batch, n_stream)
+    per_epoch = n_stream // B
+
+    def make_net(workload, grid=0):
+        net = binding.Cnn(workload.arch)
+        net.set_mode(binding.MODE_PERSISTENT if args.mode == "persistent" else binding.MODE_STAGES)
+        if grid:
+            net.set_grid(grid)
+        net.set_weights(synth.weights(workload, net.num_weights))
+        return net
+
+    def train_fn(net):
+        sz = net.image_size
+
+        def fn(k):
+            o = (k % per_epoch) * B
+            net.train_many(d_imgs.view(-1)[o * sz:(o + B) * sz], d_labs[o:o + B], wl.lr, n=B)
+        return fn
+
+    def fwd_fn(net):
+        sz = net.image_size
+
+        def fn(k):
+            o = (k % per_epoch) * B
+            net.forward_many(d_imgs.view(-1)[o * sz:(o + B) * sz], B)
+        return fn
+
+    # ---- headline: on-line training, small cfg2 net
+    net = make_net(wl, args.grid)
+    info = binding.arch_info(wl.arch)
+    wall, kernel_ms = time_steps(torch, train_fn(net), args.steps, args.warmup)
+    net.synchronize()
+    w_end = net.get_weights()
+    assert np.isfinite(w_end).all(), "training diverged"
+    value = args.steps * B / wall
+    ms_per_step = 1e3 * wall / args.steps
+    kern_ms = float(np.mean(kernel_ms))
+    bytes_img = algorithmic_bytes_per_train_image(info, net.num_weights, net.image_size)
+    achieved = bytes_img * B / (kern_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "k_persistent" if args.mode == "persistent" else "per-stage kernels (sum)",
+        "achieved": round(achieved, 3), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 6), "traffic": None,
+        "algorithmic_bytes_per_image": bytes_img, "images_per_launch": B,
+        "launch_ms_mean": round(kern_ms, 4),
+        "flop_per_image": 10.9e6, "achieved_tflops": round(10.9e6 * B / (kern_ms * 1e-3) / 1e12, 4),
+        "us_per_image": round(1e3 * kern_ms / B, 3),
+    }
+    out = {
+        "metric": "online-training images/sec", "value": round(value, 1), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "cfg2 small net: %s, 60000 seeded 1x29x29 images U[-1,1], 10 uniform labels, "
+                               "on-line SGD lr=0.001, weights U[-0.05,0.05]" % wl.arch,
+                   "images_per_step": B, "mode": args.mode, "grid": args.grid},
+        "roofline": roofline,
+    }
+    net.close()
+
+    # ---- the other measurements the workload names
+    if not args.no_extra:
+        extra = {}
+        k_steps = max(3, min(args.steps, 20))
+        net = make_net(wl, args.grid)
+        wall, kms = time_steps(torch, fwd_fn(net), k_steps, 2)
+        net.synchronize()
+        fb = algorithmic_bytes_per_forward_image(info, net.num_weights, net.image_size)
+        extra["cfg2a_forward_only_images_per_s"] = round(k_steps * B / wall, 1)
+        extra["cfg2a_forward_only_hbm_frac"] = round(fb * B / (np.mean(kms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 6)
+        net.close()
+        wlb = synth.WORKLOADS["cfg2b"]
+        infob = binding.arch_info(wlb.arch)
+        net = make_net(wlb, args.grid)
+        wall, kms = time_steps(torch, train_fn(net), k_steps, 2)
+        net.synchronize()
+        tb = algorithmic_bytes_per_train_image(infob, net.num_weights, net.image_size)
+        extra["cfg2b_arch"] = wlb.arch
+        extra["cfg2b_train_images_per_s"] = round(k_steps * B / wall, 1)
+        extra["cfg2b_train_hbm_frac"] = round(tb * B / (np.mean(kms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 6)
+        wall, kms = time_steps(torch, fwd_fn(net), k_steps, 2)
+        net.synchronize()
+        extra["cfg2b_forward_only_images_per_s"] = round(k_steps * B / wall, 1)
+        net.close()
+        # launch cost: the same images through one cnn_train_step call each
+        net = make_net(wl, args.grid)
+        sz = net.image_size
+        lab_host = labs[:B].tolist()
+        nstep = min(B, 500)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(nstep):
+            net.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], lab_host[t], wl.lr)
+        torch.cuda.synchronize()
+        extra["cfg2a_train_step_calls_images_per_s"] = round(nstep / (time.perf_counter() - t0), 1)
+        net.close()
+        out["extra"] = extra
+
+    # ---- CPU baseline: the oracle as it stands, on this machine's host cores
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = oracle.set_threads(0)
+        ref = oracle.Oracle(wl.arch, 32)
+        ref.set_weights(synth.weights(wl, ref.num_weights))
+        probe = 200
+        t0 = time.perf_counter()
+        ref.train_many(imgs[:probe], labs[:probe], wl.lr)
+        rate = probe / (time.perf_counter() - t0)
+        n = int(max(probe, min(n_stream - probe, rate * args.cpu_seconds)))
+        t0 = time.perf_counter()
+        ref.train_many(imgs[probe:probe + n], labs[probe:probe + n], wl.lr)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(n / dt, 1), "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": "images %d..%d of the same stream, float32 instantiation of the oracle, "
+                      "OpenMP over output maps, %.1f s" % (probe, probe + n, dt)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

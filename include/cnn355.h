@@ -153,6 +153,12 @@ int cnn_set_mode(cnn_t* net, int mode);
  * can be co-resident are clamped. */
 int cnn_set_grid(cnn_t* net, int n_workgroups);
 
+/* Persistent mode: grid barrier between stages.  0 = one arrival counter with a device-scope
+ * release and acquire in every workgroup; 1 (default) = two levels, one arrival counter per
+ * XCD and one across XCDs, so that only one workgroup per XCD writes that XCD's L2 back.
+ * Results are identical. */
+int cnn_set_barrier(cnn_t* net, int kind);
+
 /* Persistent mode: how many times a workgroup polls a grid barrier before it gives up,
  * raises the abort flag and leaves the kernel (the next synchronising call then returns
  * CNN_E_HIP).  Every wave therefore terminates even if a barrier can never complete. */
@@ -175,6 +181,12 @@ int cnn_get_delta(cnn_t* net, int layer, float* host_dst);
 int cnn_get_argmax(cnn_t* net, int pool_layer, uint8_t* host_dst);
 /* Cross-entropy error of the last train step / debug-gradient call. */
 int cnn_get_loss(cnn_t* net, float* host_loss);
+/* Persistent mode only: device timestamps of the last image of the last call, as seen by
+ * workgroup 0.  host_us receives, per stage, 2 floats: microseconds spent on the stage's work
+ * items and microseconds spent in the grid barrier after it (0 for stages skipped by a
+ * forward-only call); *n_stages gets the stage count.  Synchronises. */
+int cnn_get_stage_times(cnn_t* net, float* host_us, int max_stages, int* n_stages);
+
 /* Forward + backward for (d_image, label) with the update replaced by a store of dE/dw:
  * host_grad receives cnn_num_weights floats in canonical order; weights are unchanged. */
 int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad);

@@ -56,12 +56,14 @@ def lib():
             "cnn_set_mode": (C.c_int, [vp, C.c_int]),
             "cnn_set_grid": (C.c_int, [vp, C.c_int]),
             "cnn_set_spin_limit": (C.c_int, [vp, C.c_uint]),
+            "cnn_set_barrier": (C.c_int, [vp, C.c_int]),
             "cnn_synchronize": (C.c_int, [vp]),
             "cnn_get_activation": (C.c_int, [vp, C.c_int, vp]),
             "cnn_get_delta": (C.c_int, [vp, C.c_int, vp]),
             "cnn_get_argmax": (C.c_int, [vp, C.c_int, vp]),
             "cnn_get_loss": (C.c_int, [vp, vp]),
             "cnn_debug_gradients": (C.c_int, [vp, vp, i32, vp]),
+            "cnn_get_stage_times": (C.c_int, [vp, vp, C.c_int, vp]),
             "cnn_last_error": (C.c_char_p, [vp]),
         }
         for name, (res, args) in sig.items():
@@ -76,8 +78,9 @@ EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_create"
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
-           "cnn_set_grid", "cnn_set_spin_limit", "cnn_synchronize", "cnn_get_activation",
-           "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_last_error"]
+           "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
+           "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
+           "cnn_last_error"]
 
 
 def _err(handle=None):
@@ -194,6 +197,9 @@ class Cnn:
     def set_grid(self, n_workgroups):
         self._ck(lib().cnn_set_grid(self._h, int(n_workgroups)), "cnn_set_grid")
 
+    def set_barrier(self, kind):
+        self._ck(lib().cnn_set_barrier(self._h, int(kind)), "cnn_set_barrier")
+
     def set_spin_limit(self, polls):
         self._ck(lib().cnn_set_spin_limit(self._h, int(polls)), "cnn_set_spin_limit")
 
@@ -264,6 +270,14 @@ class Cnn:
         v = C.c_float()
         self._ck(lib().cnn_get_loss(self._h, C.addressof(v)), "cnn_get_loss")
         return float(v.value)
+
+    def stage_times(self):
+        """Persistent mode: [(work_us, barrier_us)] per stage for the last image of the last call."""
+        buf = np.zeros(2 * 128, dtype=np.float32)
+        n = C.c_int()
+        self._ck(lib().cnn_get_stage_times(self._h, buf.ctypes.data, 128, C.addressof(n)),
+                 "cnn_get_stage_times")
+        return [(float(buf[2 * k]), float(buf[2 * k + 1])) for k in range(n.value)]
 
     def debug_gradients(self, d_image, label):
         g = np.empty(self.num_weights, dtype=np.float32)

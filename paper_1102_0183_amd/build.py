@@ -29,7 +29,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not stale():
         return LIB
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + ["-o", tmp] + sources()
+    extra = ["-DCNN355_STAMPS"] if os.environ.get("CNN355_STAMPS") else []
+    cmd = [HIPCC] + FLAGS + extra + ["-o", tmp] + sources()
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

@@ -20,6 +20,7 @@ hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clea
 hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_prog,
                              StatusDev* d_status, const RunArgs& a);
 int persistent_max_blocks_per_cu();
+void read_dbg(unsigned long long* out);
 }  // namespace cnn355
 
 using namespace cnn355;
@@ -191,6 +192,7 @@ struct cnn {
   int mode = CNN_MODE_STAGES;
   int n_cu = 0, grid_override = 0, coop_ok = 0, max_blocks_per_cu = 1;
   unsigned int spin_limit = 1u << 22;
+  int barrier_kind = 1;
   bool need_status_reset = true;
   std::string err;
 };
@@ -331,11 +333,11 @@ int check_plan(cnn* net) {
         break;
       }
       case ST_CONV_BWD: {
-        const int HW = L.Hp * L.Wp;
-        if (st.chunk < 1 || st.chunk * HW > LDS_AUX || st.chunk * HW > LDS_AUX2) return bad(s, "delta chunk exceeds its LDS area");
-        if (st.chunk * L.K * L.K > LDS_IN) return bad(s, "filter chunk exceeds its LDS area");
-        if (st.n_tiles * WG < L.Hi * L.Wi || st.n_items != L.Mi * st.n_tiles) return bad(s, "pixel tiles do not cover the map");
-        if ((1 << st.tw_log2) > WG || st.layer < 1) return bad(s, "staging width / layer");
+        const int pt = 1 << st.tw_log2;
+        if (st.chunk < 1 || (long long)st.chunk * (L.Ho + 1) * (L.Wo + 1) > LDS_IN) return bad(s, "delta chunk exceeds its LDS area");
+        if (st.chunk * L.K * L.K > LDS_AUX) return bad(s, "filter chunk exceeds its LDS area");
+        if (pt < 1 || pt > WG || st.n_tiles * pt < L.Hi * L.Wi || st.n_items != L.Mi * st.n_tiles) return bad(s, "pixel tiles do not cover the map");
+        if (st.layer < 1) return bad(s, "no layer below");
         break;
       }
       case ST_CONV_WGRAD: {
@@ -398,8 +400,8 @@ int plan(cnn* net) {
       if (L.Ho >= 65536 || L.Wo >= 65536) return fail(&net->err, CNN_E_SHAPE, "map too large");
       if (L.Hp * L.Wp > MAX_POOLED_PIX)
         return fail(&net->err, CNN_E_SHAPE, "pooled map has more than " + std::to_string(MAX_POOLED_PIX) + " positions");
-      if (L.Hi * L.Wi > LDS_IN)
-        return fail(&net->err, CNN_E_SHAPE, "input map has more than " + std::to_string(LDS_IN) + " pixels");
+      if (L.Hi * L.Wi > LDS_IN || (L.Ho + 1) * (L.Wo + 1) > LDS_IN)
+        return fail(&net->err, CNN_E_SHAPE, "a map has more than " + std::to_string(LDS_IN) + " pixels");
       if (L.Kp > 15) return fail(&net->err, CNN_E_SHAPE, "pooling rectangle larger than 15x15");
       const cnn::ConvBuf& b = net->conv_buf[conv_i];
       L.act = b.act; L.out = b.out; L.delta = b.delta; L.arg = b.arg; L.argyx = b.argyx;
@@ -407,6 +409,7 @@ int plan(cnn* net) {
       conv_of_dev[nl] = conv_i;
       build_tables(L.Mo, L.Mi, net->tables[conv_i], net->host_tables[conv_i]);
       L.max_conn = net->host_tables[conv_i].max_conn;
+      L.full_table = net->host_tables[conv_i].csr_idx.size() == (size_t)L.Mo * L.Mi;
       const size_t n_conn = net->host_tables[conv_i].csr_idx.size();
       L.b_canon = (long long)woff;
       L.w_canon = (long long)(woff + L.Mo);
@@ -500,10 +503,14 @@ int plan(cnn* net) {
         Stage& s = add(ST_CONV_BWD, l, 0, 1, 1);
         const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.K;
         const int max_back = net->host_tables[conv_of_dev[l]].max_back;
-        s.n_tiles = (Pin + WG - 1) / WG;
+        // pixel tile: a power of two between 16 and 256, small enough to give >= 256 work items
+        int pt = 256;
+        while (pt > 16 && (pt / 2 >= Pin || (long long)L.Mi * ((Pin + pt - 1) / pt) < 256)) pt /= 2;
+        s.tw_log2 = ceil_log2(pt);
+        s.n_tiles = (Pin + pt - 1) / pt;
         s.n_items = L.Mi * s.n_tiles;
-        s.chunk = std::max(1, std::min({LDS_AUX / HW, LDS_IN / KK, std::max(1, max_back)}));
-        s.tw_log2 = ceil_log2(std::min(HW, WG));
+        s.chunk = std::max(1, std::min({LDS_IN / ((L.Ho + 1) * (L.Wo + 1)), LDS_AUX / KK, std::max(1, max_back)}));
+        (void)HW;
         // ... then adjust the weights of layer l one stage later
         pending_wgrad = l;
       } else {
@@ -564,7 +571,9 @@ int check_status(cnn* net) {
   if (s.abort_flag) rc = fail(&net->err, CNN_E_HIP, "grid barrier of the persistent kernel timed out");
   else if (s.bad_label) rc = fail(&net->err, CNN_E_ARG, "a label outside [0, classes) was met; that image was skipped");
   if (s.abort_flag || s.bad_label) {
-    s.abort_flag = 0; s.bad_label = 0; s.barrier_count = 0;
+    const float loss = s.loss;
+    std::memset(&s, 0, sizeof(s));
+    s.loss = loss;
     HIP_TRY(net, hipMemcpy(net->d_status, &s, sizeof(s), hipMemcpyHostToDevice));
   }
   return rc;
@@ -586,6 +595,7 @@ int persistent_grid(const cnn* net, int train) {
 int run(cnn* net, const RunArgs& a0) {
   RunArgs a = a0;
   a.spin_limit = net->spin_limit;
+  a.barrier_kind = net->barrier_kind;
   const ProgramDev& P = net->prog;
   if (net->mode == CNN_MODE_PERSISTENT) {
     HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
@@ -807,6 +817,12 @@ int cnn_set_grid(cnn_t* net, int n_workgroups) {
   return CNN_OK;
 }
 
+int cnn_set_barrier(cnn_t* net, int kind) {
+  if (!net || (kind != 0 && kind != 1)) return CNN_E_ARG;
+  net->barrier_kind = kind;
+  return CNN_OK;
+}
+
 int cnn_set_spin_limit(cnn_t* net, unsigned int polls) {
   if (!net) return CNN_E_ARG;
   net->spin_limit = polls;
@@ -884,6 +900,23 @@ int cnn_get_loss(cnn_t* net, float* host_loss) {
   return check_status(net);
 }
 
+int cnn_get_stage_times(cnn_t* net, float* host_us, int max_stages, int* n_stages) {
+  if (!net || !host_us || !n_stages) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  StatusDev s;
+  HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
+  const int n = net->prog.n_stages;
+  *n_stages = n;
+  unsigned long long prev = s.stamps[0];
+  for (int k = 0; k < n && k < max_stages; ++k) {
+    const unsigned long long a = s.stamps[1 + 2 * k], b = s.stamps[2 + 2 * k];
+    host_us[2 * k] = (a >= prev) ? (float)(a - prev) * 0.01f : 0.f;
+    host_us[2 * k + 1] = (b >= a) ? (float)(b - a) * 0.01f : 0.f;
+    if (b >= prev) prev = b;
+  }
+  return CNN_OK;
+}
+
 int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad) {
   if (!net || !d_image || !host_grad) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
   if (label < 0 || label >= net->n_classes) return fail(&net->err, CNN_E_ARG, "label out of range");
@@ -897,6 +930,9 @@ int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* 
   HIP_TRY(net, hipMemcpy(host_grad, net->d_grad, net->n_weights * sizeof(float), hipMemcpyDeviceToHost));
   return rc;
 }
+
+// development aid, not part of the public header: in-item timestamps (zeros unless built with CNN355_STAMPS)
+void cnn355_read_stamps(unsigned long long* out64) { cnn355::read_dbg(out64); }
 
 const char* cnn_last_error(const cnn_t* net) { return net ? net->err.c_str() : g_err.c_str(); }
 

@@ -3,6 +3,13 @@
 #include <stddef.h>
 #include <stdint.h>
 
+// Pointers into device memory.  The kernel translation unit defines CNN_GLOBAL as the global
+// address space for its device pass, so that loads and stores through these fields compile to
+// global (not flat) memory instructions; everywhere else it is empty and the layout is the same.
+#ifndef CNN_GLOBAL
+#define CNN_GLOBAL
+#endif
+
 namespace cnn355 {
 
 constexpr int WG = 256;  // threads per workgroup: 4 wavefronts of 64
@@ -34,22 +41,22 @@ struct LayerDev {
   int is_output;       // soft-max output layer
   int in_is_image;     // input is the image handed to the call (no stored activation below)
   int max_conn;        // longest row of the connection table
-  int pad0;
-  const float* in;     // input activations (NULL when in_is_image)
-  float* act;          // conv: after tanh, full resolution; fc: after tanh / probabilities
-  float* out;          // what the layer above reads (conv: pooled values; fc: == act)
-  uint8_t* arg;        // conv: winner index dy*Kp+dx per pooled position
-  int* argyx;          // conv: (y << 16) | x of the winner in conv-output coordinates
-  float* delta;        // dE/d(pre-activation): conv at the winners [Mo][Hp][Wp]; fc [n_out]
-  float* bias;
-  float* w;            // conv: one K*K block per connection, CSR order; fc: [n_out][n_in]
+  int full_table;      // every output map reads every input map (slot of (j, i) is j * Mi + i)
+  const CNN_GLOBAL float* in;     // input activations (NULL when in_is_image)
+  CNN_GLOBAL float* act;          // conv: after tanh, full resolution; fc: after tanh / probabilities
+  CNN_GLOBAL float* out;          // what the layer above reads (conv: pooled values; fc: == act)
+  CNN_GLOBAL uint8_t* arg;        // conv: winner index dy*Kp+dx per pooled position
+  CNN_GLOBAL int* argyx;          // conv: (y << 16) | x of the winner in conv-output coordinates
+  CNN_GLOBAL float* delta;        // dE/d(pre-activation): conv at the winners [Mo][Hp][Wp]; fc [n_out]
+  CNN_GLOBAL float* bias;
+  CNN_GLOBAL float* w;            // conv: one K*K block per connection, CSR order; fc: [n_out][n_in]
   long long w_canon;   // offset of w in the canonical weight vector (for gradient taps)
   long long b_canon;
-  const int* csr_ptr;  // [Mo+1] forward table (C^n of Sec. 3.1): row j -> slots
-  const int* csr_idx;  // [n_conn] input map of every slot
-  const int* csc_ptr;  // [Mi+1] backward table (C_BP of Sec. 3.1): input map i -> entries
-  const int* csc_j;    // [n_conn] output map of every entry
-  const int* csc_slot; // [n_conn] weight slot of every entry (WIDX_BP of Sec. 3.1)
+  const CNN_GLOBAL int* csr_ptr;  // [Mo+1] forward table (C^n of Sec. 3.1): row j -> slots
+  const CNN_GLOBAL int* csr_idx;  // [n_conn] input map of every slot
+  const CNN_GLOBAL int* csc_ptr;  // [Mi+1] backward table (C_BP of Sec. 3.1): input map i -> entries
+  const CNN_GLOBAL int* csc_j;    // [n_conn] output map of every entry
+  const CNN_GLOBAL int* csc_slot; // [n_conn] weight slot of every entry (WIDX_BP of Sec. 3.1)
 };
 
 enum StageKind : int {
@@ -72,7 +79,7 @@ struct Stage {
   int tile_rows;      // CONV_FWD: conv rows per tile (multiple of Kp)
   int n_tiles;        // CONV_FWD / CONV_BWD: tiles per map; CONV_WGRAD: connection chunks per output map
   int chunk;          // maps staged per pass (CONV_FWD: input maps, CONV_BWD: output maps, CONV_WGRAD: input maps)
-  int tw_log2;        // log2 of the lane group width used when staging one map
+  int tw_log2;        // log2 of the lane group width used when staging one map; CONV_BWD: log2 of the pixel tile
   int pix_per_thread; // CONV_FWD: 1 or 4
   int rows_per_wg;    // FC_FWD: 1, 2 or 4
   int cm_log2;        // FC_BWD / HEAD: log2 of columns per tile
@@ -81,9 +88,9 @@ struct Stage {
 struct FrontendDev {
   int n_filters, K, n_src, Hr, Wr, H, W;  // raw image n_src x Hr x Wr -> n_filters x H x W
   int pad;
-  const float* filters;  // [n_filters][K][K]
-  const int* src;        // [n_filters]
-  float* out;            // [n_filters][H][W]
+  const CNN_GLOBAL float* filters;  // [n_filters][K][K]
+  const CNN_GLOBAL int* src;        // [n_filters]
+  CNN_GLOBAL float* out;            // [n_filters][H][W]
 };
 
 struct ProgramDev {
@@ -102,20 +109,30 @@ struct StatusDev {
   unsigned int abort_flag;     // set when a barrier wait gave up; every workgroup then leaves
   unsigned int bad_label;      // set when a label outside [0, classes) was met
   float loss;                  // cross-entropy error of the last trained image
+  // two-level barrier: one line per XCD (index x * 32), plus the cross-XCD counter
+  unsigned int top_count;
+  unsigned int pad_[27];
+  unsigned int xcd_members[16 * 32];  // workgroups of this launch that run on XCD x
+  unsigned int xcd_count[16 * 32];    // monotone arrivals on XCD x
+  unsigned int xcd_go[16 * 32];       // last barrier number released on XCD x
+  // persistent mode, last image of the last call, seen from workgroup 0 (100 MHz ticks):
+  // stamps[0] = image start; stamps[1 + 2 s] = stage s items done; stamps[2 + 2 s] = its barrier passed
+  unsigned long long stamps[2 * MAX_STAGES + 2];
 };
 
 // Per-call arguments.
 struct RunArgs {
-  const float* images;   // first image
-  const int* labels;     // device labels, or NULL to use label_imm
-  float* probs_out;      // optional [n_images][n_classes]
-  float* grad_out;       // when set: store dE/dw here (canonical order) instead of updating
+  const CNN_GLOBAL float* images;   // first image
+  const CNN_GLOBAL int* labels;     // device labels, or NULL to use label_imm
+  CNN_GLOBAL float* probs_out;      // optional [n_images][n_classes]
+  CNN_GLOBAL float* grad_out;       // when set: store dE/dw here (canonical order) instead of updating
   long long n_images;
   long long image_stride; // floats
   int label_imm;
   int train;             // 0: forward only
   float lr;
   unsigned int spin_limit; // grid-barrier polls before giving up
+  int barrier_kind;        // 0: one counter, full fences in every workgroup; 1: two-level (per XCD)
 };
 
 }  // namespace cnn355

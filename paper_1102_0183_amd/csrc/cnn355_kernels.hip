@@ -9,9 +9,14 @@
 // weight-adjusting phases of Sec. 3.2 - 3.4.
 #include <hip/hip_runtime.h>
 
+#if defined(__HIP_DEVICE_COMPILE__)
+#define CNN_GLOBAL __attribute__((address_space(1)))
+#endif
 #include "cnn355_dev.h"
 
 namespace cnn355 {
+
+typedef CNN_GLOBAL float gfloat;  // a float in device (global) memory
 
 // Scaled hyperbolic tangent of Sec. 4, constants as printed.
 #define ACT_A 1.7159f
@@ -22,10 +27,19 @@ __device__ __forceinline__ float dact_f(float y) {
   return (float)(1.7159 * 0.6666) - (float)(0.6666 / 1.7159) * y * y;
 }
 
+// Optional fine-grained timestamps inside work items (development aid; compiled out unless
+// CNN355_STAMPS is defined): workgroup 0 records 100 MHz ticks at numbered points.
+#ifdef CNN355_STAMPS
+__device__ unsigned long long g_dbg[64];
+#define DBG(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_dbg[i] = wall_clock64(); } while (0)
+#else
+#define DBG(i) do { } while (0)
+#endif
+
 struct Ctx {
-  const float* image;
-  float* probs_out;
-  float* grad_out;
+  const gfloat* image;
+  gfloat* probs_out;
+  gfloat* grad_out;
   int label;
   int train;  // this image is trained on (0 for forward-only calls and for rejected labels)
   float lr;
@@ -46,19 +60,50 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
 __device__ __forceinline__ int ceil_div(int a, int b) { return -floor_div(-a, b); }
 
+// Copy n maps of map_sz floats each into LDS (dst[c * map_sz + o] = src_of(c)[o]).  Lane groups
+// of 2^tw_log2 threads take one map each; every thread issues up to U independent,
+// unconditional global loads before it waits, so the copy costs a few memory latencies instead
+// of one per map (indices past the end are clamped to the last map and not stored).
+template <int U, class SrcOf>
+__device__ __forceinline__ void stage_maps_u(float* dst, int n, int map_sz, int tw_log2, SrcOf src_of) {
+  const int tid = threadIdx.x;
+  const int tw = 1 << tw_log2;
+  const int tc = tid >> tw_log2, to = tid & (tw - 1), tcn = WG >> tw_log2;
+  for (int c0 = tc; c0 < n; c0 += tcn * U) {
+    decltype(src_of(0)) src[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) src[u] = src_of(min(c0 + u * tcn, n - 1));
+    for (int o = to; o < map_sz; o += tw) {
+      float v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = src[u][o];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (c0 + u * tcn < n) dst[(c0 + u * tcn) * map_sz + o] = v[u];
+    }
+  }
+}
+template <class SrcOf>
+__device__ __forceinline__ void stage_maps(float* dst, int n, int map_sz, int tw_log2, SrcOf src_of) {
+  const int tcn = WG >> tw_log2;
+  if (n <= tcn) stage_maps_u<1>(dst, n, map_sz, tw_log2, src_of);
+  else if (n <= 4 * tcn) stage_maps_u<4>(dst, n, map_sz, tw_log2, src_of);
+  else stage_maps_u<8>(dst, n, map_sz, tw_log2, src_of);
+}
+
 // ------------------------------------------------------------------------------------------
 // Fixed image-processing layer (Sec. 2.1): filter f correlated with raw channel src[f];
 // no bias, no non-linearity, never trained.  One thread per output pixel.
 // ------------------------------------------------------------------------------------------
-__device__ void frontend_item(const FrontendDev& fe, int item, const float* image) {
+__device__ void frontend_item(const FrontendDev& fe, int item, const gfloat* image) {
   const int idx = item * WG + threadIdx.x;
   const int hw = fe.H * fe.W;
   if (idx >= fe.n_filters * hw) return;
   const int f = idx / hw;
   const int rem = idx - f * hw;
   const int y = rem / fe.W, x = rem - y * fe.W;
-  const float* src = image + ((size_t)fe.src[f] * fe.Hr + y) * fe.Wr + x;
-  const float* flt = fe.filters + (size_t)f * fe.K * fe.K;
+  const gfloat* src = image + ((size_t)fe.src[f] * fe.Hr + y) * fe.Wr + x;
+  const gfloat* flt = fe.filters + (size_t)f * fe.K * fe.K;
   float s = 0.f;
   for (int ky = 0; ky < fe.K; ++ky)
     for (int kx = 0; kx < fe.K; ++kx) s = fmaf(flt[ky * fe.K + kx], src[ky * fe.Wr + kx], s);
@@ -74,11 +119,35 @@ __device__ void frontend_item(const FrontendDev& fe, int item, const float* imag
 // through LDS.  Epilogue: bias, scaled tanh, store, then the pooled maximum with the index of
 // the first maximum in row-major order.
 // ------------------------------------------------------------------------------------------
+// multiply-accumulate over the maps c = c_first, c_first + R, ... of one staged chunk; the only
+// part of the forward stage that is compiled once per kernel size (KT = 0: any size)
 template <int KT, int TT>
+__device__ __forceinline__ void conv_fwd_mac(const float* lds_in, const float* lds_w, int c_first,
+                                             int n, int R, int map_sz, int Wi, int Krt,
+                                             const int (&base)[TT], float (&acc)[TT]) {
+  const int K = KT ? KT : Krt;
+  const int KK = K * K;
+  for (int c = c_first; c < n; c += R) {
+    const float* ip = lds_in + c * map_sz;
+    const float* wp = lds_w + c * KK;
+#pragma unroll
+    for (int ky = 0; ky < K; ++ky) {
+#pragma unroll
+      for (int kx = 0; kx < K; ++kx) {
+        const float wv = wp[ky * K + kx];
+        const int off = ky * Wi + kx;
+#pragma unroll
+        for (int t = 0; t < TT; ++t) acc[t] = fmaf(wv, ip[base[t] + off], acc[t]);
+      }
+    }
+  }
+}
+
+template <int TT>
 __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
-                              const float* in, float* lds) {
+                              const gfloat* in, float* lds) {
   const int tid = threadIdx.x;
-  const int K = KT ? KT : L.K;
+  const int K = L.K;
   const int KK = K * K;
   const int Wi = L.Wi, Wo = L.Wo, Ho = L.Ho;
   const int stride = L.S + 1;
@@ -89,15 +158,17 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   const int P = rows * Wo;
   const int map_sz = ((rows - 1) * stride + K) * Wi;
   const size_t in_map = (size_t)L.Hi * Wi;
-  const float* in0 = in + (size_t)y0 * stride * Wi;
+  const gfloat* in0 = in + (size_t)y0 * stride * Wi;
 
   float* lds_in = lds;
   float* lds_w = lds + LDS_IN;
   float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
   float* lds_out = lds_part + WG;
 
+  DBG(0);
   const int c_begin = L.csr_ptr[j];
   const int n_conn = L.csr_ptr[j + 1] - c_begin;
+  DBG(1);
 
   int R = 1, r = 0, p0 = tid;
   if (TT == 1) {
@@ -112,43 +183,36 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     const int p = p0 + t * WG;
     const bool ok = (r < R) && (p < P);
     const int y = p / Wo, x = p - y * Wo;
-    base[t] = ok ? (y * stride * Wi + x * stride) : -1;
+    base[t] = ok ? (y * stride * Wi + x * stride) : 0;  // idle lanes read a valid address, result unused
     acc[t] = 0.f;
   }
 
-  const int tw = 1 << st.tw_log2;
-  const int tc = tid >> st.tw_log2, to = tid & (tw - 1), tcn = WG >> st.tw_log2;
-
   for (int c0 = 0; c0 < n_conn; c0 += st.chunk) {
     const int n = min(st.chunk, n_conn - c0);
-    for (int c = tc; c < n; c += tcn) {
-      const float* src = in0 + (size_t)L.csr_idx[c_begin + c0 + c] * in_map;
-      float* dst = lds_in + c * map_sz;
-      for (int o = to; o < map_sz; o += tw) dst[o] = src[o];
-    }
+    if (L.full_table)  // uniform: input map of slot c is c itself
+      stage_maps(lds_in, n, map_sz, st.tw_log2, [&](int c) { return in0 + (size_t)(c0 + c) * in_map; });
+    else
+      stage_maps(lds_in, n, map_sz, st.tw_log2,
+                 [&](int c) { return in0 + (size_t)L.csr_idx[c_begin + c0 + c] * in_map; });
+    DBG(2);
     {
-      const float* wsrc = L.w + (size_t)(c_begin + c0) * KK;
+      const gfloat* wsrc = L.w + (size_t)(c_begin + c0) * KK;
       for (int idx = tid; idx < n * KK; idx += WG) lds_w[idx] = wsrc[idx];
     }
     __syncthreads();
-    if (r < R) {
-      for (int c = r; c < n; c += R) {
-        const float* ip = lds_in + c * map_sz;
-        const float* wp = lds_w + c * KK;
-#pragma unroll
-        for (int ky = 0; ky < K; ++ky) {
-#pragma unroll
-          for (int kx = 0; kx < K; ++kx) {
-            const float wv = wp[ky * K + kx];
-            const int off = ky * Wi + kx;
-#pragma unroll
-            for (int t = 0; t < TT; ++t)
-              if (base[t] >= 0) acc[t] = fmaf(wv, ip[base[t] + off], acc[t]);
-          }
-        }
+    DBG(3);
+    {
+      const int c_first = min(r, R - 1);  // lanes beyond the R splits repeat split R-1, unused
+      switch (K) {
+        case 2: conv_fwd_mac<2, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
+        case 3: conv_fwd_mac<3, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
+        case 4: conv_fwd_mac<4, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
+        case 5: conv_fwd_mac<5, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
+        default: conv_fwd_mac<0, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
       }
     }
     __syncthreads();
+    DBG(4);
   }
 
   if (TT == 1 && R > 1) {
@@ -159,6 +223,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
       for (int rr = 0; rr < R; ++rr) s += lds_part[rr * P + tid];
     acc[0] = s;
   }
+  DBG(5);
   const float b = L.bias[j];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
@@ -170,6 +235,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     }
   }
   __syncthreads();
+  DBG(6);
   const int Kp = L.Kp;
   if (Kp > 1) {
     const int Wp = L.Wp;
@@ -191,6 +257,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     }
     __syncthreads();
   }
+  DBG(7);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -198,7 +265,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
 // neurons; the lanes of a neuron stride over its inputs, then reduce by wave shuffles and LDS.
 // ------------------------------------------------------------------------------------------
 __device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
-                            const float* v, float* lds) {
+                            const gfloat* v, float* lds) {
   const int tid = threadIdx.x;
   const int rpw = st.rows_per_wg;
   const int lpr = WG / rpw;  // lanes per neuron: 256, 128 or 64
@@ -207,7 +274,8 @@ __device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
   const int n_in = L.n_in;
   float s = 0.f;
   if (row < L.n_out) {
-    const float* wr = L.w + (size_t)row * n_in;
+    const gfloat* wr = L.w + (size_t)row * n_in;
+#pragma unroll 4
     for (int m = lane; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
   }
   s = wave_sum(s);
@@ -231,20 +299,35 @@ __device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
 // derivative, Sec. 3.3) and adjusts W and the bias (Sec. 3.4) in the same pass over W.
 // One work item.
 // ------------------------------------------------------------------------------------------
-__device__ void head_item(const LayerDev& L, const LayerDev* Lp, const float* v,
+__device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v,
                           const Ctx& ctx, StatusDev* status, float* lds) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int N = L.n_out, n_in = L.n_in;
   float* logit = lds + LDS_IN;
   float* dl = lds + LDS_IN + LDS_AUX;
-  for (int k = wave; k < N; k += WG / 64) {
-    const float* wr = L.w + (size_t)k * n_in;
-    float s = 0.f;
-    for (int m = lane; m < n_in; m += 64) s = fmaf(wr[m], v[m], s);
-    s = wave_sum(s);
-    if (lane == 0) logit[k] = s + L.bias[k];
+  DBG(10);
+  {
+    // lane groups of 2^lpl lanes per output neuron, as many neurons side by side as fit
+    int lpl = 6;
+    while (lpl > 0 && (WG >> lpl) < N) --lpl;
+    const int lpr = 1 << lpl, rows_pp = WG >> lpl;
+    const int sub = tid & (lpr - 1);
+    for (int k0 = 0; k0 < N; k0 += rows_pp) {
+      const int k = k0 + (tid >> lpl);
+      float s = 0.f;
+      if (k < N) {
+        const gfloat* wr = L.w + (size_t)k * n_in;
+#pragma unroll 4
+        for (int m = sub; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1)
+        if (off < lpr) s += __shfl_xor(s, off, 64);
+      if (sub == 0 && k < N) logit[k] = s + L.bias[k];
+    }
   }
   __syncthreads();
+  DBG(11);
   if (wave == 0) {
     float mx = -INFINITY;
     for (int k = lane; k < N; k += 64) mx = fmaxf(mx, logit[k]);
@@ -265,14 +348,16 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const float* v,
     }
   }
   __syncthreads();
+  DBG(12);
   if (!ctx.train) return;
   const float lr = ctx.lr;
-  float* g_out = ctx.grad_out;
+  gfloat* g_out = ctx.grad_out;
   for (int m = tid; m < n_in; m += WG) {
     const float vm = v[m];
     float g = 0.f;
+#pragma unroll 4
     for (int k = 0; k < N; ++k) {
-      float* wp = L.w + (size_t)k * n_in + m;
+      gfloat* wp = L.w + (size_t)k * n_in + m;
       const float w = *wp;
       const float d = dl[k];
       g = fmaf(w, d, g);
@@ -281,11 +366,13 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const float* v,
     }
     if (Lp) Lp->delta[m] = g * dact_f(vm);
   }
+  DBG(13);
   for (int k = tid; k < N; k += WG) {
     if (g_out) g_out[L.b_canon + k] = dl[k];
     else L.bias[k] -= lr * dl[k];
   }
   __syncthreads();
+  DBG(14);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -295,7 +382,7 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const float* v,
 // groups split the rows of W and combine through LDS.
 // ------------------------------------------------------------------------------------------
 __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& st, int item,
-                            const float* v, const Ctx& ctx, float* lds) {
+                            const gfloat* v, const Ctx& ctx, float* lds) {
   const int tid = threadIdx.x;
   const int cml = st.cm_log2, CM = 1 << cml, KS = WG >> cml;
   const int ks = tid >> cml, cm = tid & (CM - 1);
@@ -306,12 +393,13 @@ __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& 
   for (int k = tid; k < N; k += WG) dl[k] = L.delta[k];
   __syncthreads();
   const float lr = ctx.lr;
-  float* g_out = ctx.grad_out;
+  gfloat* g_out = ctx.grad_out;
   float g = 0.f, vm = 0.f;
   if (m < n_in) {
     vm = v[m];
+#pragma unroll 4
     for (int k = ks; k < N; k += KS) {
-      float* wp = L.w + (size_t)k * n_in + m;
+      gfloat* wp = L.w + (size_t)k * n_in + m;
       const float w = *wp;
       const float d = dl[k];
       g = fmaf(w, d, g);
@@ -341,91 +429,117 @@ __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& 
 // K x K receptive field covers it:
 //   max(ceil((r-K+1)/(S+1)), 0) <= y <= min(floor(r/(S+1)), Ho-1)   (and the same in x),
 // each times w_{j,i}[r - y(S+1)][c - x(S+1)] (old value).  After max-pooling only the winner of
-// each rectangle carries a delta, so the sum runs over the pooled positions whose rectangle
-// meets that range and keeps those whose winner lies inside it.  Epilogue: times the
-// activation derivative of the layer below.  Work item = (input map i, tile of <= 256 input
-// pixels); small maps split the output maps R ways over the spare lanes.
+// each rectangle carries a delta: the staged chunk of delta maps is rebuilt at full resolution
+// in LDS (zero-fill, then scatter the winners), so the inner loop is the plain rectangle of the
+// paper with no data-dependent addressing.  Epilogue: times the activation derivative of the
+// layer below.  Work item = (input map i, tile of PT input pixels); the 256/PT lane groups
+// split the output maps and combine through LDS.
 // ------------------------------------------------------------------------------------------
 template <int KT>
+__device__ __forceinline__ float conv_bwd_mac(const float* lds_d, const float* lds_w, int c_first, int n,
+                                              int R, int HWd, const int (&yo)[5], const int (&xo)[5],
+                                              float acc) {
+  for (int c = c_first; c < n; c += R) {
+    const float* dp = lds_d + c * HWd;
+    const float* wp = lds_w + c * (KT * KT);
+#pragma unroll
+    for (int ky = 0; ky < KT; ++ky)
+#pragma unroll
+      for (int kx = 0; kx < KT; ++kx) acc = fmaf(dp[yo[ky] + xo[kx]], wp[ky * KT + kx], acc);
+  }
+  return acc;
+}
+
 __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage& st, int item,
                               float* lds) {
   const int tid = threadIdx.x;
-  const int K = KT ? KT : L.K;
+  const int K = L.K;
   const int KK = K * K;
   const int stride = L.S + 1;
   const int Wi = L.Wi, Pin = L.Hi * L.Wi;
-  const int Kp = L.Kp, Wp = L.Wp, HW = L.Hp * L.Wp;
+  const int Ho = L.Ho, Wo = L.Wo, HW = L.Hp * L.Wp;
+  // the staged delta maps carry one extra row and one extra column of zeros: a kernel tap that
+  // has no output neuron (border, or a skipped position) reads a zero instead of branching
+  const int Wd = Wo + 1, HWd = (Ho + 1) * Wd;
   const int i = item / st.n_tiles;
   const int tile = item - i * st.n_tiles;
-  int R = 1, r = 0, p = tile * WG + tid;
-  if (Pin < WG) {
-    R = WG / Pin;
-    r = tid / Pin;
-    p = tid - r * Pin;
-  }
-  const bool active = (r < R) && (p < Pin);
+  const int ptl = st.tw_log2;              // log2 of the pixel tile
+  const int PT = 1 << ptl, R = WG >> ptl;
+  const int r = tid >> ptl;
+  const int p = tile * PT + (tid & (PT - 1));
+  const bool active = p < Pin;
   const int pr = p / Wi, pc = p - pr * Wi;
-  int py0 = 1, py1 = 0, px0 = 1, px1 = 0;
-  {
-    const int ylo = max(ceil_div(pr - K + 1, stride), 0), yhi = min(pr / stride, L.Ho - 1);
-    const int xlo = max(ceil_div(pc - K + 1, stride), 0), xhi = min(pc / stride, L.Wo - 1);
-    if (active && ylo <= yhi && xlo <= xhi) {
-      py0 = ylo / Kp; py1 = yhi / Kp;
-      px0 = xlo / Kp; px1 = xhi / Kp;
-    }
-  }
-  float* lds_w = lds;
-  float* lds_dp = lds + LDS_IN;
-  int* lds_yx = (int*)(lds + LDS_IN + LDS_AUX);
+
+  float* lds_d = lds;                       // [chunk][(Ho+1)*(Wo+1)] deltas at full resolution
+  float* lds_w = lds + LDS_IN;              // [chunk][K*K]
   float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+
+  // tap ky of the kernel reaches output row (pr - ky) / (S+1) when that is a whole, existing
+  // row (the inequalities of Sec. 3.3 solved tap by tap); otherwise the zero row
+  auto row_off = [&](int ky) {
+    const int ry = pr - ky;
+    const int y = ry / stride;
+    const bool ok = active && ry >= 0 && ry - y * stride == 0 && y < Ho;
+    return (ok ? y : Ho) * Wd;
+  };
+  auto col_off = [&](int kx) {
+    const int rx = pc - kx;
+    const int x = rx / stride;
+    const bool ok = active && rx >= 0 && rx - x * stride == 0 && x < Wo;
+    return ok ? x : Wo;
+  };
+  int yo[5], xo[5];
+#pragma unroll
+  for (int k = 0; k < 5; ++k) { yo[k] = row_off(k); xo[k] = col_off(k); }
 
   const int j_begin = L.csc_ptr[i];
   const int nj = L.csc_ptr[i + 1] - j_begin;
-  const int tw = 1 << st.tw_log2;
-  const int tc = tid >> st.tw_log2, to = tid & (tw - 1), tcn = WG >> st.tw_log2;
   float acc = 0.f;
   for (int j0 = 0; j0 < nj; j0 += st.chunk) {
     const int n = min(st.chunk, nj - j0);
-    for (int c = tc; c < n; c += tcn) {
-      const size_t jo = (size_t)L.csc_j[j_begin + j0 + c] * HW;
-      for (int o = to; o < HW; o += tw) {
-        lds_dp[c * HW + o] = L.delta[jo + o];
-        lds_yx[c * HW + o] = L.argyx[jo + o];
-      }
-    }
+    for (int idx = tid; idx < n * HWd; idx += WG) lds_d[idx] = 0.f;
     for (int idx = tid; idx < n * KK; idx += WG) {
       const int c = idx / KK, t = idx - c * KK;
-      lds_w[idx] = L.w[(size_t)L.csc_slot[j_begin + j0 + c] * KK + t];
+      const int slot = L.full_table ? ((j0 + c) * L.Mi + i) : L.csc_slot[j_begin + j0 + c];
+      lds_w[idx] = L.w[(size_t)slot * KK + t];
     }
     __syncthreads();
-    if (py0 <= py1) {
-      for (int c = r; c < n; c += R) {
-        const float* dp = lds_dp + c * HW;
-        const int* yxp = lds_yx + c * HW;
-        const float* wp = lds_w + c * KK;
-        for (int py = py0; py <= py1; ++py)
-          for (int px = px0; px <= px1; ++px) {
-            const int q = py * Wp + px;
-            const int yx = yxp[q];
-            const int ky = pr - (yx >> 16) * stride;
-            const int kx = pc - (yx & 0xffff) * stride;
-            if ((unsigned)ky < (unsigned)K && (unsigned)kx < (unsigned)K)
-              acc = fmaf(dp[q], wp[ky * K + kx], acc);
+    for (int idx = tid; idx < n * HW; idx += WG) {
+      const int c = idx / HW, q = idx - c * HW;
+      const int j = L.full_table ? (j0 + c) : L.csc_j[j_begin + j0 + c];
+      const int yx = L.argyx[(size_t)j * HW + q];
+      lds_d[c * HWd + (yx >> 16) * Wd + (yx & 0xffff)] = L.delta[(size_t)j * HW + q];
+    }
+    __syncthreads();
+    switch (K) {
+      case 1: acc = conv_bwd_mac<1>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
+      case 2: acc = conv_bwd_mac<2>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
+      case 3: acc = conv_bwd_mac<3>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
+      case 4: acc = conv_bwd_mac<4>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
+      case 5: acc = conv_bwd_mac<5>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
+      default:
+        for (int c = r; c < n; c += R) {
+          const float* dp = lds_d + c * HWd;
+          const float* wp = lds_w + c * KK;
+          for (int ky = 0; ky < K; ++ky) {
+            const int ro = row_off(ky);
+            for (int kx = 0; kx < K; ++kx) acc = fmaf(dp[ro + col_off(kx)], wp[ky * K + kx], acc);
           }
-      }
+        }
+        break;
     }
     __syncthreads();
   }
   if (R > 1) {
-    if (r < R) lds_part[tid] = acc;  // tid == r * Pin + p
+    lds_part[tid] = acc;  // tid == r * PT + (p - tile * PT)
     __syncthreads();
     float s = 0.f;
-    if (tid < Pin)
-      for (int rr = 0; rr < R; ++rr) s += lds_part[rr * Pin + tid];
+    if (tid < PT)
+      for (int rr = 0; rr < R; ++rr) s += lds_part[rr * PT + tid];
     acc = s;
     __syncthreads();
   }
-  if (r == 0 && p < Pin) {
+  if (r == 0 && active) {
     const size_t o = (size_t)i * Pin + p;
     Lp.delta[o] = acc * dact_f(Lp.out[o]);
   }
@@ -439,11 +553,10 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
 // maps, delta_j and the winner coordinates are staged in LDS; a thread owns one weight, or,
 // when the chunk has fewer than 256 weights, the pooled positions are split R ways.
 // ------------------------------------------------------------------------------------------
-template <int KT>
 __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
-                                const float* in, const Ctx& ctx, float* lds) {
+                                const gfloat* in, const Ctx& ctx, float* lds) {
   const int tid = threadIdx.x;
-  const int K = KT ? KT : L.K;
+  const int K = L.K;
   const int KK = K * K;
   const int stride = L.S + 1;
   const int Wi = L.Wi, Min = L.Hi * L.Wi, HW = L.Hp * L.Wp;
@@ -464,13 +577,11 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
     lds_dp[o] = L.delta[(size_t)j * HW + o];
     lds_yx[o] = L.argyx[(size_t)j * HW + o];
   }
-  const int tw = 1 << st.tw_log2;
-  const int tc = tid >> st.tw_log2, to = tid & (tw - 1), tcn = WG >> st.tw_log2;
-  for (int c = tc; c < n; c += tcn) {
-    const float* src = in + (size_t)L.csr_idx[c_begin + c0 + c] * Min;
-    float* dst = lds_in + c * Min;
-    for (int o = to; o < Min; o += tw) dst[o] = src[o];
-  }
+  if (L.full_table)
+    stage_maps(lds_in, n, Min, st.tw_log2, [&](int c) { return in + (size_t)(c0 + c) * Min; });
+  else
+    stage_maps(lds_in, n, Min, st.tw_log2,
+               [&](int c) { return in + (size_t)L.csr_idx[c_begin + c0 + c] * Min; });
   __syncthreads();
 
   const int NW = n * KK;
@@ -481,8 +592,8 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
     wi0 = tid - rr * NW;
   }
   const float lr = ctx.lr;
-  float* g_out = ctx.grad_out;
-  float* wbase = L.w + (size_t)(c_begin + c0) * KK;
+  gfloat* g_out = ctx.grad_out;
+  gfloat* wbase = L.w + (size_t)(c_begin + c0) * KK;
   const long long canon = L.w_canon + (long long)(c_begin + c0) * KK;
   if (R == 1) {
     for (int wi = tid; wi < NW; wi += WG) {
@@ -490,6 +601,7 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
       const int ky = t / K, kx = t - ky * K;
       const float* ip = lds_in + c * Min + ky * Wi + kx;
       float s = 0.f;
+#pragma unroll 4
       for (int q = 0; q < HW; ++q) {
         const int yx = lds_yx[q];
         s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
@@ -503,6 +615,7 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
       const int ky = t / K, kx = t - ky * K;
       const float* ip = lds_in + c * Min + ky * Wi + kx;
       float s = 0.f;
+#pragma unroll 4
       for (int q = rr; q < HW; q += R) {
         const int yx = lds_yx[q];
         s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
@@ -537,25 +650,12 @@ template <int KIND>
 __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, int item,
                                          const Ctx& ctx, StatusDev* status, float* lds) {
   const LayerDev& L = P.layers[st.layer];
-  const float* in = L.in_is_image ? ctx.image : L.in;
+  const gfloat* in = L.in_is_image ? ctx.image : L.in;
   if constexpr (KIND == ST_FRONTEND) {
     frontend_item(P.fe, item, ctx.image);
   } else if constexpr (KIND == ST_CONV_FWD) {
-    if (st.pix_per_thread == 1) {
-      switch (L.K) {
-        case 2: conv_fwd_item<2, 1>(L, st, item, in, lds); break;
-        case 3: conv_fwd_item<3, 1>(L, st, item, in, lds); break;
-        case 4: conv_fwd_item<4, 1>(L, st, item, in, lds); break;
-        case 5: conv_fwd_item<5, 1>(L, st, item, in, lds); break;
-        default: conv_fwd_item<0, 1>(L, st, item, in, lds); break;
-      }
-    } else {
-      switch (L.K) {
-        case 3: conv_fwd_item<3, 4>(L, st, item, in, lds); break;
-        case 5: conv_fwd_item<5, 4>(L, st, item, in, lds); break;
-        default: conv_fwd_item<0, 4>(L, st, item, in, lds); break;
-      }
-    }
+    if (st.pix_per_thread == 1) conv_fwd_item<1>(L, st, item, in, lds);
+    else conv_fwd_item<4>(L, st, item, in, lds);
   } else if constexpr (KIND == ST_FC_FWD) {
     fc_fwd_item(L, st, item, in, lds);
   } else if constexpr (KIND == ST_HEAD) {
@@ -563,22 +663,9 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
   } else if constexpr (KIND == ST_FC_BWD) {
     fc_bwd_item(L, L.in_is_image ? nullptr : &P.layers[st.layer - 1], st, item, in, ctx, lds);
   } else if constexpr (KIND == ST_CONV_BWD) {
-    const LayerDev& Lp = P.layers[st.layer - 1];
-    switch (L.K) {
-      case 2: conv_bwd_item<2>(L, Lp, st, item, lds); break;
-      case 3: conv_bwd_item<3>(L, Lp, st, item, lds); break;
-      case 4: conv_bwd_item<4>(L, Lp, st, item, lds); break;
-      case 5: conv_bwd_item<5>(L, Lp, st, item, lds); break;
-      default: conv_bwd_item<0>(L, Lp, st, item, lds); break;
-    }
+    conv_bwd_item(L, P.layers[st.layer - 1], st, item, lds);
   } else if constexpr (KIND == ST_CONV_WGRAD) {
-    switch (L.K) {
-      case 2: conv_wgrad_item<2>(L, st, item, in, ctx, lds); break;
-      case 3: conv_wgrad_item<3>(L, st, item, in, ctx, lds); break;
-      case 4: conv_wgrad_item<4>(L, st, item, in, ctx, lds); break;
-      case 5: conv_wgrad_item<5>(L, st, item, in, ctx, lds); break;
-      default: conv_wgrad_item<0>(L, st, item, in, ctx, lds); break;
-    }
+    conv_wgrad_item(L, st, item, in, ctx, lds);
   }
 }
 
@@ -635,41 +722,96 @@ STAGE_KERNEL(k_conv_bwd, ST_CONV_BWD)
 STAGE_KERNEL(k_conv_wgrad, ST_CONV_WGRAD)
 
 __global__ void k_reset_status(StatusDev* status, int clear_label_flag) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
+  const int t = threadIdx.x;
+  if (blockIdx.x != 0) return;
+  if (t == 0) {
     status->barrier_count = 0u;
     status->abort_flag = 0u;
+    status->top_count = 0u;
     if (clear_label_flag) status->bad_label = 0u;
+  }
+  for (int i = t; i < 16 * 32; i += blockDim.x) {
+    status->xcd_members[i] = 0u;
+    status->xcd_count[i] = 0u;
+    status->xcd_go[i] = 0u;
   }
 }
 
 // ---- persistent kernel: all stages of all images in one cooperative launch ------------------
-// Grid barrier: one monotone arrival counter.  Thread 0 of every workgroup releases its
-// workgroup's writes (device-scope fence), adds one, and polls until the counter reaches
-// barrier_number * gridDim.x, then acquires.  A wait that exceeds spin_limit polls, or that
-// sees the abort flag, raises the flag and makes its workgroup leave the kernel, so every
-// wave terminates whatever happens.
+__device__ __forceinline__ unsigned int ld_agent(unsigned int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Bounded wait until *p has reached `target` (wrap-safe).  A wait that exceeds spin_limit polls,
+// or that sees the abort flag, raises the flag and fails, so that every wave terminates
+// whatever happens to the other workgroups.
+__device__ __forceinline__ bool wait_reached(StatusDev* status, unsigned int* p, unsigned int target,
+                                             unsigned int spin_limit) {
+  unsigned int spins = 0;
+  while ((int)(ld_agent(p) - target) < 0) {
+    __builtin_amdgcn_s_sleep(1);
+    ++spins;
+    if (spins > spin_limit || ((spins & 255u) == 0u && ld_agent(&status->abort_flag))) {
+      __hip_atomic_store(&status->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return false;
+    }
+  }
+  return true;
+}
+
+// Grid barrier, kind 0: one monotone arrival counter.  Thread 0 of every workgroup releases its
+// workgroup's writes (device-scope fence: L2 write-back), adds one, polls until the counter
+// reaches barrier_number * gridDim.x, then acquires (device-scope fence: L2 + L1 invalidate).
 __device__ bool grid_barrier(StatusDev* status, unsigned int target, unsigned int spin_limit,
                              int* s_ok) {
   __syncthreads();
   if (threadIdx.x == 0) {
     __threadfence();
     __hip_atomic_fetch_add(&status->barrier_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int ok = 1;
-    unsigned int spins = 0;
-    while ((int)(__hip_atomic_load(&status->barrier_count, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-      __builtin_amdgcn_s_sleep(1);
-      ++spins;
-      if (spins > spin_limit ||
-          ((spins & 255u) == 0u &&
-           __hip_atomic_load(&status->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-        __hip_atomic_store(&status->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ok = 0;
-        break;
-      }
-    }
+    const bool ok = wait_reached(status, &status->barrier_count, target, spin_limit);
     __threadfence();
-    *s_ok = ok;
+    *s_ok = ok ? 1 : 0;
+  }
+  __syncthreads();
+  return *s_ok != 0;
+}
+
+// Which XCD (accelerator die) this wave runs on: hardware register XCC_ID, bits 3:0.
+__device__ __forceinline__ unsigned int xcc_id() {
+  return __builtin_amdgcn_s_getreg(((4 - 1) << 11) | (0 << 6) | 20) & 0xfu;
+}
+
+struct BarCtx {
+  unsigned int xcd, n_local, n_xcd;
+};
+
+// Grid barrier, kind 1: two levels, built for a part whose eight XCDs each have a private L2.
+// A device-scope release writes back a whole L2; when every workgroup issues one they queue up
+// 32 deep per L2, which is where most of the time of kind 0 goes.  Here each workgroup first
+// makes sure its own stores have landed in its XCD's L2 (every wave waits for its outstanding
+// memory operations) and arrives on its XCD's counter.  The last arrival of an XCD alone
+// performs the device-scope release, arrives on the cross-XCD counter, waits for all XCDs and
+// releases its XCD.  Every workgroup still performs its own device-scope acquire afterwards
+// (measured: dropping only the CU's L1 lines in the followers leaves stale data behind).
+__device__ bool xcd_barrier(StatusDev* status, unsigned int epoch, const BarCtx& bc,
+                            unsigned int spin_limit, int* s_ok) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's stores are in L2
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    bool ok;
+    const unsigned int arrived = __hip_atomic_fetch_add(&status->xcd_count[bc.xcd * 32], 1u,
+                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (arrived + 1u == epoch * bc.n_local) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __hip_atomic_fetch_add(&status->top_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ok = wait_reached(status, &status->top_count, epoch * bc.n_xcd, spin_limit);
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      __hip_atomic_store(&status->xcd_go[bc.xcd * 32], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      ok = wait_reached(status, &status->xcd_go[bc.xcd * 32], epoch, spin_limit);
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    *s_ok = ok ? 1 : 0;
   }
   __syncthreads();
   return *s_ok != 0;
@@ -679,18 +821,49 @@ __global__ void __launch_bounds__(WG) k_persistent(const ProgramDev* __restrict_
                                                    StatusDev* status, RunArgs a) {
   __shared__ float lds[LDS_FLOATS];
   __shared__ int s_ok;
+  __shared__ BarCtx s_bc;
   unsigned int n_barriers = 0;
   const int G = gridDim.x;
+  const bool two_level = a.barrier_kind == 1;
+  if (two_level) {
+    // roll call: how many workgroups of this launch sit on each XCD
+    if (threadIdx.x == 0) {
+      s_bc.xcd = xcc_id();
+      __hip_atomic_fetch_add(&status->xcd_members[s_bc.xcd * 32], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    ++n_barriers;
+    if (!grid_barrier(status, n_barriers * (unsigned int)G, a.spin_limit, &s_ok)) return;
+    if (threadIdx.x == 0) {
+      s_bc.n_local = ld_agent(&status->xcd_members[s_bc.xcd * 32]);
+      unsigned int nx = 0;
+      for (int x = 0; x < 16; ++x) nx += ld_agent(&status->xcd_members[x * 32]) ? 1u : 0u;
+      s_bc.n_xcd = nx;
+    }
+    __syncthreads();
+  }
+  const BarCtx bc = s_bc;
+  unsigned int epoch = 0;
   for (long long t = 0; t < a.n_images; ++t) {
     const Ctx ctx = make_ctx(*P, a, t, status);
+    const bool stamp = (t == a.n_images - 1) && blockIdx.x == 0 && threadIdx.x == 0;
+    if (stamp) status->stamps[0] = wall_clock64();
     for (int s = 0; s < P->n_stages; ++s) {
       const Stage& st = P->stages[s];
       if (st.train_only && !ctx.train) continue;
       run_stage_items(*P, st, blockIdx.x, G, ctx, status, lds);
+      if (stamp) status->stamps[1 + 2 * s] = wall_clock64();
       if (st.barrier_after) {
-        ++n_barriers;
-        if (!grid_barrier(status, n_barriers * (unsigned int)G, a.spin_limit, &s_ok)) return;
+        bool ok;
+        if (two_level) {
+          ++epoch;
+          ok = xcd_barrier(status, epoch, bc, a.spin_limit, &s_ok);
+        } else {
+          ++n_barriers;
+          ok = grid_barrier(status, n_barriers * (unsigned int)G, a.spin_limit, &s_ok);
+        }
+        if (!ok) return;
       }
+      if (stamp) status->stamps[2 + 2 * s] = wall_clock64();
     }
   }
 }
@@ -714,7 +887,7 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
 }
 
 hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clear_label_flag) {
-  hipLaunchKernelGGL(k_reset_status, dim3(1), dim3(64), 0, stream, d_status, clear_label_flag);
+  hipLaunchKernelGGL(k_reset_status, dim3(1), dim3(256), 0, stream, d_status, clear_label_flag);
   return hipGetLastError();
 }
 
@@ -723,6 +896,14 @@ hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_p
   RunArgs args = a;
   void* params[] = {(void*)&d_prog, (void*)&d_status, (void*)&args};
   return hipLaunchCooperativeKernel((const void*)k_persistent, dim3(grid), dim3(WG), params, 0, stream);
+}
+
+void read_dbg(unsigned long long* out) {
+#ifdef CNN355_STAMPS
+  (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg), sizeof(g_dbg));
+#else
+  for (int i = 0; i < 64; ++i) out[i] = 0;
+#endif
 }
 
 int persistent_max_blocks_per_cu() {
