@@ -263,9 +263,12 @@ int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
   const int target = 256;
   int rows = 0;
   if (Kp * Wo <= WG) {
+    // the largest band of at most 256 pixels that still gives `want` work items; if no band does,
+    // the smallest band (most items) of at least one wavefront of pixels
+    const int want = 128;
     int max_rows = std::min(Ho, (WG / Wo) / Kp * Kp);
     for (int r = max_rows; r >= Kp; r -= Kp)
-      if ((long long)L.Mo * ((Ho + r - 1) / r) >= target) { rows = r; break; }
+      if ((long long)L.Mo * ((Ho + r - 1) / r) >= want) { rows = r; break; }
     if (!rows) {
       rows = Kp;
       while (rows * Wo < 64 && rows + Kp <= max_rows) rows += Kp;
@@ -275,7 +278,7 @@ int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
     if (Kp * Wo > MAX_TILE_PIX) return fail(err, CNN_E_SHAPE, "convolutional map too wide for the forward kernel");
     rows = std::min(Ho, (MAX_TILE_PIX / Wo) / Kp * Kp);
     while (rows > Kp && (long long)L.Mo * ((Ho + rows - 1) / rows) < target) rows -= Kp;
-    st.pix_per_thread = 4;
+    st.pix_per_thread = 2;
   }
   st.tile_rows = rows;
   st.n_tiles = (Ho + rows - 1) / rows;
@@ -325,7 +328,7 @@ int check_plan(cnn* net) {
         const int map_sz = ((st.tile_rows - 1) * (L.S + 1) + L.K) * L.Wi;
         if (st.tile_rows < L.Kp || st.tile_rows % L.Kp) return bad(s, "row band not a multiple of the pooling size");
         if (st.pix_per_thread == 1 ? P_max > WG : P_max > MAX_TILE_PIX) return bad(s, "row band too large");
-        if (st.pix_per_thread != 1 && st.pix_per_thread != 4) return bad(s, "bad pixels per thread");
+        if (st.pix_per_thread != 1 && st.pix_per_thread != 2) return bad(s, "bad pixels per thread");
         if (st.chunk < 1 || (long long)st.chunk * map_sz > LDS_IN) return bad(s, "input chunk exceeds the LDS input area");
         if (st.chunk * L.K * L.K > LDS_AUX) return bad(s, "filter chunk exceeds the LDS filter area");
         if (st.n_tiles * st.tile_rows < L.Ho || st.n_items != L.Mo * st.n_tiles) return bad(s, "row bands do not cover the map");
@@ -348,7 +351,7 @@ int check_plan(cnn* net) {
         break;
       }
       case ST_FC_FWD:
-        if (st.rows_per_wg != 1 && st.rows_per_wg != 2 && st.rows_per_wg != 4) return bad(s, "rows per workgroup");
+        if (st.rows_per_wg < 1 || st.rows_per_wg > WG / 64 || (st.rows_per_wg & (st.rows_per_wg - 1))) return bad(s, "rows per workgroup");
         if (st.n_items * st.rows_per_wg < L.n_out) return bad(s, "rows not covered");
         break;
       case ST_HEAD:
@@ -469,7 +472,10 @@ int plan(cnn* net) {
       if (rc) return rc;
     } else if (!L.is_output) {
       Stage& s = add(ST_FC_FWD, l, 0, 1, 0);
-      s.rows_per_wg = L.n_out <= 512 ? 1 : (L.n_out <= 1024 ? 2 : 4);
+      // lanes per neuron: about a quarter of its inputs (a few loads per lane), 64 .. 1024
+      int lanes = 64;
+      while (lanes < WG && lanes * 4 < L.n_in) lanes *= 2;
+      s.rows_per_wg = WG / lanes;
       s.n_items = (L.n_out + s.rows_per_wg - 1) / s.rows_per_wg;
     } else {
       add(ST_HEAD, l, 1, 1, 0);
@@ -482,7 +488,8 @@ int plan(cnn* net) {
     LayerDev& L = P.layers[l];
     Stage& s = add(ST_CONV_WGRAD, l, 0, barrier, 1);
     const int chunk_max = std::min(LDS_IN / (L.Hi * L.Wi), L.max_conn);
-    const int want_chunks = (256 + L.Mo - 1) / L.Mo;  // aim at >= 256 work items
+    const int want_chunks = std::max(1, 192 / L.Mo);  // aim at about 192 work items: one round on 256 CUs
+    // together with the small stage that shares the barrier interval
     int chunk = std::max(1, std::min(chunk_max, L.max_conn / std::max(1, want_chunks)));
     s.chunk = chunk;
     s.n_tiles = (L.max_conn + chunk - 1) / chunk;
@@ -503,8 +510,8 @@ int plan(cnn* net) {
         Stage& s = add(ST_CONV_BWD, l, 0, 1, 1);
         const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.K;
         const int max_back = net->host_tables[conv_of_dev[l]].max_back;
-        // pixel tile: a power of two between 16 and 256, small enough to give >= 256 work items
-        int pt = 256;
+        // pixel tile: a power of two between 16 and 1024, small enough to give about 256 work items
+        int pt = WG;
         while (pt > 16 && (pt / 2 >= Pin || (long long)L.Mi * ((Pin + pt - 1) / pt) < 256)) pt /= 2;
         s.tw_log2 = ceil_log2(pt);
         s.n_tiles = (Pin + pt - 1) / pt;

@@ -12,16 +12,17 @@
 
 namespace cnn355 {
 
-constexpr int WG = 256;  // threads per workgroup: 4 wavefronts of 64
+constexpr int WG = 1024;  // threads per workgroup: 16 wavefronts of 64, one workgroup per CU
 
-// LDS carve-up, in floats.  One static block per workgroup; every stage cuts it its own way.
-constexpr int LDS_IN = 8192;    // staged input maps (32 KB)
-constexpr int LDS_AUX = 3072;   // filters / deltas
-constexpr int LDS_AUX2 = 3072;  // arg-max coordinates
-constexpr int LDS_RED = 1280;   // cross-split partial sums (256) + one output tile (1024)
-constexpr int LDS_FLOATS = LDS_IN + LDS_AUX + LDS_AUX2 + LDS_RED;  // 15616 floats = 61 KB
+// LDS carve-up, in floats.  One static block per workgroup (gfx950 has 160 KB per CU); every
+// stage cuts it its own way.
+constexpr int LDS_IN = 20480;   // staged input maps / rebuilt delta maps (80 KB)
+constexpr int LDS_AUX = 6144;   // filters / deltas (24 KB)
+constexpr int LDS_AUX2 = 6144;  // winner coordinates (24 KB)
+constexpr int MAX_TILE_PIX = 2 * WG;     // conv outputs per workgroup tile (up to 2 per thread)
+constexpr int LDS_RED = WG + MAX_TILE_PIX;  // cross-split partial sums + one output tile (12 KB)
+constexpr int LDS_FLOATS = LDS_IN + LDS_AUX + LDS_AUX2 + LDS_RED;  // 35840 floats = 140 KB
 
-constexpr int MAX_TILE_PIX = 1024;   // conv outputs per workgroup tile (4 per thread)
 constexpr int MAX_POOLED_PIX = LDS_AUX; // pooled positions of one map that fit the staging area
 constexpr int MAX_FC_OUT = LDS_AUX;     // neurons of one fully connected layer (delta staged in LDS)
 constexpr int MAX_LAYERS = 32;
@@ -80,8 +81,8 @@ struct Stage {
   int n_tiles;        // CONV_FWD / CONV_BWD: tiles per map; CONV_WGRAD: connection chunks per output map
   int chunk;          // maps staged per pass (CONV_FWD: input maps, CONV_BWD: output maps, CONV_WGRAD: input maps)
   int tw_log2;        // log2 of the lane group width used when staging one map; CONV_BWD: log2 of the pixel tile
-  int pix_per_thread; // CONV_FWD: 1 or 4
-  int rows_per_wg;    // FC_FWD: 1, 2 or 4
+  int pix_per_thread; // CONV_FWD: 1 or 2
+  int rows_per_wg;    // FC_FWD: neurons per work item (power of two, 1..16)
   int cm_log2;        // FC_BWD / HEAD: log2 of columns per tile
 };
 

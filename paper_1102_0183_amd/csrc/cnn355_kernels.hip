@@ -60,35 +60,65 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
 __device__ __forceinline__ int ceil_div(int a, int b) { return -floor_div(-a, b); }
 
-// Copy n maps of map_sz floats each into LDS (dst[c * map_sz + o] = src_of(c)[o]).  Lane groups
+// Copy n maps of map_sz floats each into LDS (dst[c * map_sz + o] = base[off_of(c) + o]).  Lane groups
 // of 2^tw_log2 threads take one map each; every thread issues up to U independent,
 // unconditional global loads before it waits, so the copy costs a few memory latencies instead
 // of one per map (indices past the end are clamped to the last map and not stored).
-template <int U, class SrcOf>
-__device__ __forceinline__ void stage_maps_u(float* dst, int n, int map_sz, int tw_log2, SrcOf src_of) {
+template <int U, class OffOf>
+__device__ __forceinline__ void stage_maps_u(float* dst, const gfloat* base, int n, int map_sz,
+                                             int tw_log2, OffOf off_of) {
   const int tid = threadIdx.x;
   const int tw = 1 << tw_log2;
   const int tc = tid >> tw_log2, to = tid & (tw - 1), tcn = WG >> tw_log2;
   for (int c0 = tc; c0 < n; c0 += tcn * U) {
-    decltype(src_of(0)) src[U];
+    int off[U];  // element offset of each map from `base` (32 bits: keeps the register count low)
 #pragma unroll
-    for (int u = 0; u < U; ++u) src[u] = src_of(min(c0 + u * tcn, n - 1));
+    for (int u = 0; u < U; ++u) off[u] = off_of(min(c0 + u * tcn, n - 1));
     for (int o = to; o < map_sz; o += tw) {
       float v[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) v[u] = src[u][o];
+      for (int u = 0; u < U; ++u) v[u] = base[off[u] + o];
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (c0 + u * tcn < n) dst[(c0 + u * tcn) * map_sz + o] = v[u];
     }
   }
 }
-template <class SrcOf>
-__device__ __forceinline__ void stage_maps(float* dst, int n, int map_sz, int tw_log2, SrcOf src_of) {
+// off_of(c) = element offset of map c from `base`
+template <class OffOf>
+__device__ __forceinline__ void stage_maps(float* dst, const gfloat* base, int n, int map_sz,
+                                           int tw_log2, OffOf off_of) {
   const int tcn = WG >> tw_log2;
-  if (n <= tcn) stage_maps_u<1>(dst, n, map_sz, tw_log2, src_of);
-  else if (n <= 4 * tcn) stage_maps_u<4>(dst, n, map_sz, tw_log2, src_of);
-  else stage_maps_u<8>(dst, n, map_sz, tw_log2, src_of);
+  if (n <= tcn) stage_maps_u<1>(dst, base, n, map_sz, tw_log2, off_of);
+  else if (n <= 2 * tcn) stage_maps_u<2>(dst, base, n, map_sz, tw_log2, off_of);
+  else if (n <= 4 * tcn) stage_maps_u<4>(dst, base, n, map_sz, tw_log2, off_of);
+  else stage_maps_u<8>(dst, base, n, map_sz, tw_log2, off_of);
+}
+
+// First batch of a flat global -> LDS copy, split in two so that other loads can be issued
+// between the two halves: prefetch_flat puts up to U elements per thread in flight (indices past
+// the end are clamped), commit_flat stores them; copy_flat_rest handles what lies beyond U * WG.
+template <int U, class T, class P>
+__device__ __forceinline__ void prefetch_flat(T (&v)[U], P src, int n) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) v[u] = src[min((int)threadIdx.x + u * WG, n - 1)];
+}
+template <int U, class T, class D>
+__device__ __forceinline__ void commit_flat(const T (&v)[U], D* dst, int n) {
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if ((int)threadIdx.x + u * WG < n) dst[threadIdx.x + u * WG] = v[u];
+}
+template <int U, class D, class P>
+__device__ __forceinline__ void copy_flat_rest(D* dst, P src, int n) {
+  for (int base = U * WG; base < n; base += U * WG) {
+    D v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = src[min(base + (int)threadIdx.x + u * WG, n - 1)];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (base + (int)threadIdx.x + u * WG < n) dst[base + threadIdx.x + u * WG] = v[u];
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -157,7 +187,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   const int rows = min(st.tile_rows, Ho - y0);
   const int P = rows * Wo;
   const int map_sz = ((rows - 1) * stride + K) * Wi;
-  const size_t in_map = (size_t)L.Hi * Wi;
+  const int in_map = L.Hi * Wi;
   const gfloat* in0 = in + (size_t)y0 * stride * Wi;
 
   float* lds_in = lds;
@@ -166,13 +196,17 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   float* lds_out = lds_part + WG;
 
   DBG(0);
-  const int c_begin = L.csr_ptr[j];
-  const int n_conn = L.csr_ptr[j + 1] - c_begin;
+  const float b = L.bias[j];  // issued first, used last
+  int c_begin = j * L.Mi, n_conn = L.Mi;
+  if (!L.full_table) {
+    c_begin = L.csr_ptr[j];
+    n_conn = L.csr_ptr[j + 1] - c_begin;
+  }
   DBG(1);
 
   int R = 1, r = 0, p0 = tid;
   if (TT == 1) {
-    R = WG / P;  // P <= 256 here
+    R = WG / P;  // P <= WG here
     r = tid / P;
     p0 = tid - r * P;
   }
@@ -189,16 +223,17 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
 
   for (int c0 = 0; c0 < n_conn; c0 += st.chunk) {
     const int n = min(st.chunk, n_conn - c0);
+    const gfloat* wsrc = L.w + (size_t)(c_begin + c0) * KK;
+    float wv[4];
+    prefetch_flat(wv, wsrc, n * KK);  // filters in flight together with the input maps
     if (L.full_table)  // uniform: input map of slot c is c itself
-      stage_maps(lds_in, n, map_sz, st.tw_log2, [&](int c) { return in0 + (size_t)(c0 + c) * in_map; });
+      stage_maps(lds_in, in0, n, map_sz, st.tw_log2, [&](int c) { return (c0 + c) * in_map; });
     else
-      stage_maps(lds_in, n, map_sz, st.tw_log2,
-                 [&](int c) { return in0 + (size_t)L.csr_idx[c_begin + c0 + c] * in_map; });
+      stage_maps(lds_in, in0, n, map_sz, st.tw_log2,
+                 [&](int c) { return L.csr_idx[c_begin + c0 + c] * in_map; });
     DBG(2);
-    {
-      const gfloat* wsrc = L.w + (size_t)(c_begin + c0) * KK;
-      for (int idx = tid; idx < n * KK; idx += WG) lds_w[idx] = wsrc[idx];
-    }
+    commit_flat(wv, lds_w, n * KK);
+    copy_flat_rest<4>(lds_w, wsrc, n * KK);
     __syncthreads();
     DBG(3);
     {
@@ -224,7 +259,6 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     acc[0] = s;
   }
   DBG(5);
-  const float b = L.bias[j];
 #pragma unroll
   for (int t = 0; t < TT; ++t) {
     const int p = tid + t * WG;
@@ -268,14 +302,15 @@ __device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
                             const gfloat* v, float* lds) {
   const int tid = threadIdx.x;
   const int rpw = st.rows_per_wg;
-  const int lpr = WG / rpw;  // lanes per neuron: 256, 128 or 64
+  const int lpr = WG / rpw;  // lanes per neuron: 64 .. 1024
   const int row = item * rpw + tid / lpr;
   const int lane = tid & (lpr - 1);
   const int n_in = L.n_in;
+  const float bias = (tid < rpw && item * rpw + tid < L.n_out) ? L.bias[item * rpw + tid] : 0.f;
   float s = 0.f;
   if (row < L.n_out) {
     const gfloat* wr = L.w + (size_t)row * n_in;
-#pragma unroll 4
+#pragma unroll 8
     for (int m = lane; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
   }
   s = wave_sum(s);
@@ -287,7 +322,7 @@ __device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
     float t = 0.f;
     for (int k = 0; k < wpr; ++k) t += part[tid * wpr + k];
     const int rr = item * rpw + tid;
-    if (rr < L.n_out) L.act[rr] = act_f(t + L.bias[rr]);
+    if (rr < L.n_out) L.act[rr] = act_f(t + bias);
   }
   __syncthreads();
 }
@@ -303,9 +338,28 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
                           const Ctx& ctx, StatusDev* status, float* lds) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int N = L.n_out, n_in = L.n_in;
+  float* lds_W = lds;                 // copy of W when it fits (N * n_in <= LDS_IN)
   float* logit = lds + LDS_IN;
   float* dl = lds + LDS_IN + LDS_AUX;
+  const bool cached = N * n_in <= LDS_IN;
   DBG(10);
+#ifdef CNN355_STAMPS
+  {  // probe: one load of fresh data (written by the previous stage), one of old data, timed alone
+    float probe = v[tid % n_in];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    DBG(30);
+    float probe2 = L.w[tid];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    DBG(31);
+    float probe3 = v[(tid + 64) % n_in];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    DBG(32);
+    float probe4 = L.w[tid + 700];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    DBG(33);
+    if (probe + probe2 + probe3 + probe4 == 123.456f) lds[0] = probe;
+  }
+#endif
   {
     // lane groups of 2^lpl lanes per output neuron, as many neurons side by side as fit
     int lpl = 6;
@@ -314,16 +368,26 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
     const int sub = tid & (lpr - 1);
     for (int k0 = 0; k0 < N; k0 += rows_pp) {
       const int k = k0 + (tid >> lpl);
+      const float bk = (sub == 0 && k < N) ? L.bias[k] : 0.f;
       float s = 0.f;
       if (k < N) {
         const gfloat* wr = L.w + (size_t)k * n_in;
-#pragma unroll 4
-        for (int m = sub; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
+        if (cached) {
+#pragma unroll 8
+          for (int m = sub; m < n_in; m += lpr) {
+            const float w = wr[m];
+            lds_W[k * n_in + m] = w;
+            s = fmaf(w, v[m], s);
+          }
+        } else {
+#pragma unroll 8
+          for (int m = sub; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
+        }
       }
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1)
         if (off < lpr) s += __shfl_xor(s, off, 64);
-      if (sub == 0 && k < N) logit[k] = s + L.bias[k];
+      if (sub == 0 && k < N) logit[k] = s + bk;
     }
   }
   __syncthreads();
@@ -355,14 +419,25 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
   for (int m = tid; m < n_in; m += WG) {
     const float vm = v[m];
     float g = 0.f;
+    if (cached) {
 #pragma unroll 4
-    for (int k = 0; k < N; ++k) {
-      gfloat* wp = L.w + (size_t)k * n_in + m;
-      const float w = *wp;
-      const float d = dl[k];
-      g = fmaf(w, d, g);
-      if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
-      else *wp = w - lr * (d * vm);
+      for (int k = 0; k < N; ++k) {
+        const float w = lds_W[k * n_in + m];
+        const float d = dl[k];
+        g = fmaf(w, d, g);
+        if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+        else L.w[(size_t)k * n_in + m] = w - lr * (d * vm);
+      }
+    } else {
+#pragma unroll 8
+      for (int k = 0; k < N; ++k) {
+        gfloat* wp = L.w + (size_t)k * n_in + m;
+        const float w = *wp;
+        const float d = dl[k];
+        g = fmaf(w, d, g);
+        if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+        else *wp = w - lr * (d * vm);
+      }
     }
     if (Lp) Lp->delta[m] = g * dact_f(vm);
   }
@@ -390,15 +465,32 @@ __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& 
   const int N = L.n_out, n_in = L.n_in;
   float* dl = lds + LDS_IN;
   float* part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
+  // every global load this item needs is issued before the first wait: this column's first FB
+  // weights (rows ks, ks + KS, ...), its input, and the layer's deltas
+  constexpr int FB = 4;
+  const int mc = min(m, n_in - 1);
+  float wv[FB];
+#pragma unroll
+  for (int u = 0; u < FB; ++u) wv[u] = L.w[(size_t)min(ks + u * KS, N - 1) * n_in + mc];
+  const float vm = v[mc];
   for (int k = tid; k < N; k += WG) dl[k] = L.delta[k];
   __syncthreads();
   const float lr = ctx.lr;
   gfloat* g_out = ctx.grad_out;
-  float g = 0.f, vm = 0.f;
+  float g = 0.f;
   if (m < n_in) {
-    vm = v[m];
+#pragma unroll
+    for (int u = 0; u < FB; ++u) {
+      const int k = ks + u * KS;
+      if (k < N) {
+        const float d = dl[k];
+        g = fmaf(wv[u], d, g);
+        if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+        else L.w[(size_t)k * n_in + m] = wv[u] - lr * (d * vm);
+      }
+    }
 #pragma unroll 4
-    for (int k = ks; k < N; k += KS) {
+    for (int k = ks + FB * KS; k < N; k += KS) {
       gfloat* wp = L.w + (size_t)k * n_in + m;
       const float w = *wp;
       const float d = dl[k];
@@ -492,23 +584,49 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
 #pragma unroll
   for (int k = 0; k < 5; ++k) { yo[k] = row_off(k); xo[k] = col_off(k); }
 
-  const int j_begin = L.csc_ptr[i];
-  const int nj = L.csc_ptr[i + 1] - j_begin;
+  int j_begin = 0, nj = L.Mo;
+  if (!L.full_table) {
+    j_begin = L.csc_ptr[i];
+    nj = L.csc_ptr[i + 1] - j_begin;
+  }
   float acc = 0.f;
+  constexpr int BU = 4;  // loads in flight per thread and array
   for (int j0 = 0; j0 < nj; j0 += st.chunk) {
     const int n = min(st.chunk, nj - j0);
-    for (int idx = tid; idx < n * HWd; idx += WG) lds_d[idx] = 0.f;
-    for (int idx = tid; idx < n * KK; idx += WG) {
-      const int c = idx / KK, t = idx - c * KK;
-      const int slot = L.full_table ? ((j0 + c) * L.Mi + i) : L.csc_slot[j_begin + j0 + c];
-      lds_w[idx] = L.w[(size_t)slot * KK + t];
+    // filters of the chunk, gathered: entry c of the chunk uses weight slot (j, i)
+    for (int base = 0; base < n * KK; base += BU * WG) {
+      float wv[BU];
+#pragma unroll
+      for (int u = 0; u < BU; ++u) {
+        const int idx = min(base + tid + u * WG, n * KK - 1);
+        const int c = idx / KK, t = idx - c * KK;
+        const int slot = L.full_table ? ((j0 + c) * L.Mi + i) : L.csc_slot[j_begin + j0 + c];
+        wv[u] = L.w[(size_t)slot * KK + t];
+      }
+      if (base == 0)  // the zero fill overlaps the first batch of loads
+        for (int idx = tid; idx < n * HWd; idx += WG) lds_d[idx] = 0.f;
+#pragma unroll
+      for (int u = 0; u < BU; ++u)
+        if (base + tid + u * WG < n * KK) lds_w[base + tid + u * WG] = wv[u];
     }
     __syncthreads();
-    for (int idx = tid; idx < n * HW; idx += WG) {
-      const int c = idx / HW, q = idx - c * HW;
-      const int j = L.full_table ? (j0 + c) : L.csc_j[j_begin + j0 + c];
-      const int yx = L.argyx[(size_t)j * HW + q];
-      lds_d[c * HWd + (yx >> 16) * Wd + (yx & 0xffff)] = L.delta[(size_t)j * HW + q];
+    // winners' deltas scattered to their place in the zeroed full-resolution maps
+    for (int base = 0; base < n * HW; base += BU * WG) {
+      float dv[BU];
+      int yxv[BU], cv[BU];
+#pragma unroll
+      for (int u = 0; u < BU; ++u) {
+        const int idx = min(base + tid + u * WG, n * HW - 1);
+        const int c = idx / HW, q = idx - c * HW;
+        const int j = L.full_table ? (j0 + c) : L.csc_j[j_begin + j0 + c];
+        cv[u] = c;
+        yxv[u] = L.argyx[(size_t)j * HW + q];
+        dv[u] = L.delta[(size_t)j * HW + q];
+      }
+#pragma unroll
+      for (int u = 0; u < BU; ++u)
+        if (base + tid + u * WG < n * HW)
+          lds_d[cv[u] * HWd + (yxv[u] >> 16) * Wd + (yxv[u] & 0xffff)] = dv[u];
     }
     __syncthreads();
     switch (K) {
@@ -562,8 +680,11 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   const int Wi = L.Wi, Min = L.Hi * L.Wi, HW = L.Hp * L.Wp;
   const int j = item / st.n_tiles;
   const int kc = item - j * st.n_tiles;
-  const int c_begin = L.csr_ptr[j];
-  const int n_conn = L.csr_ptr[j + 1] - c_begin;
+  int c_begin = j * L.Mi, n_conn = L.Mi;
+  if (!L.full_table) {
+    c_begin = L.csr_ptr[j];
+    n_conn = L.csr_ptr[j + 1] - c_begin;
+  }
   const int c0 = kc * st.chunk;
   if (c0 >= n_conn) return;  // uniform over the workgroup
   const int n = min(st.chunk, n_conn - c0);
@@ -573,18 +694,28 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   int* lds_yx = (int*)(lds + LDS_IN + LDS_AUX);
   float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
 
-  for (int o = tid; o < HW; o += WG) {
-    lds_dp[o] = L.delta[(size_t)j * HW + o];
-    lds_yx[o] = L.argyx[(size_t)j * HW + o];
+  const int NW = n * KK;
+  gfloat* wbase = L.w + (size_t)(c_begin + c0) * KK;
+  constexpr int WU = 4;
+  float w_old[WU];  // the weights this thread will adjust: in flight from the start
+  prefetch_flat(w_old, wbase, NW);
+  const float b_old = L.bias[j];
+  {
+    float dv[2];
+    int yv[2];
+    prefetch_flat(dv, L.delta + (size_t)j * HW, HW);
+    prefetch_flat(yv, L.argyx + (size_t)j * HW, HW);
+    if (L.full_table)
+      stage_maps(lds_in, in, n, Min, st.tw_log2, [&](int c) { return (c0 + c) * Min; });
+    else
+      stage_maps(lds_in, in, n, Min, st.tw_log2, [&](int c) { return L.csr_idx[c_begin + c0 + c] * Min; });
+    commit_flat(dv, lds_dp, HW);
+    commit_flat(yv, lds_yx, HW);
+    copy_flat_rest<2>(lds_dp, L.delta + (size_t)j * HW, HW);
+    copy_flat_rest<2>(lds_yx, L.argyx + (size_t)j * HW, HW);
   }
-  if (L.full_table)
-    stage_maps(lds_in, n, Min, st.tw_log2, [&](int c) { return in + (size_t)(c0 + c) * Min; });
-  else
-    stage_maps(lds_in, n, Min, st.tw_log2,
-               [&](int c) { return in + (size_t)L.csr_idx[c_begin + c0 + c] * Min; });
   __syncthreads();
 
-  const int NW = n * KK;
   int R = 1, rr = 0, wi0 = tid;
   if (NW < WG) {
     R = min(WG / NW, HW);
@@ -593,41 +724,43 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   }
   const float lr = ctx.lr;
   gfloat* g_out = ctx.grad_out;
-  gfloat* wbase = L.w + (size_t)(c_begin + c0) * KK;
   const long long canon = L.w_canon + (long long)(c_begin + c0) * KK;
-  if (R == 1) {
-    for (int wi = tid; wi < NW; wi += WG) {
-      const int c = wi / KK, t = wi - c * KK;
-      const int ky = t / K, kx = t - ky * K;
-      const float* ip = lds_in + c * Min + ky * Wi + kx;
-      float s = 0.f;
+  // gradient of weight wi of the chunk, summed over the pooled positions q = q0, q0 + qs, ...
+  auto grad_of = [&](int wi, int q0, int qs) {
+    const int c = wi / KK, t = wi - c * KK;
+    const int ky = t / K, kx = t - ky * K;
+    const float* ip = lds_in + c * Min + ky * Wi + kx;
+    float s = 0.f;
 #pragma unroll 4
-      for (int q = 0; q < HW; ++q) {
-        const int yx = lds_yx[q];
-        s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
+    for (int q = q0; q < HW; q += qs) {
+      const int yx = lds_yx[q];
+      s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
+    }
+    return s;
+  };
+  if (R == 1) {
+#pragma unroll
+    for (int u = 0; u < WU; ++u) {
+      const int wi = tid + u * WG;
+      if (wi < NW) {
+        const float g = grad_of(wi, 0, 1);
+        if (g_out) g_out[canon + wi] = g;
+        else wbase[wi] = w_old[u] - lr * g;
       }
-      if (g_out) g_out[canon + wi] = s;
-      else wbase[wi] -= lr * s;
+    }
+    for (int wi = tid + WU * WG; wi < NW; wi += WG) {
+      const float g = grad_of(wi, 0, 1);
+      if (g_out) g_out[canon + wi] = g;
+      else wbase[wi] -= lr * g;
     }
   } else {
-    if (rr < R) {
-      const int c = wi0 / KK, t = wi0 - c * KK;
-      const int ky = t / K, kx = t - ky * K;
-      const float* ip = lds_in + c * Min + ky * Wi + kx;
-      float s = 0.f;
-#pragma unroll 4
-      for (int q = rr; q < HW; q += R) {
-        const int yx = lds_yx[q];
-        s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
-      }
-      lds_part[tid] = s;  // tid == rr * NW + wi0
-    }
+    if (rr < R) lds_part[tid] = grad_of(wi0, rr, R);  // tid == rr * NW + wi0
     __syncthreads();
     if (tid < NW) {
-      float s = 0.f;
-      for (int k = 0; k < R; ++k) s += lds_part[k * NW + tid];
-      if (g_out) g_out[canon + tid] = s;
-      else wbase[tid] -= lr * s;
+      float g = 0.f;
+      for (int k = 0; k < R; ++k) g += lds_part[k * NW + tid];
+      if (g_out) g_out[canon + tid] = g;
+      else wbase[tid] = w_old[0] - lr * g;
     }
   }
   if (kc == 0 && tid < 64) {
@@ -636,7 +769,7 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
     s = wave_sum(s);
     if (tid == 0) {
       if (g_out) g_out[L.b_canon + j] = s;
-      else L.bias[j] -= lr * s;
+      else L.bias[j] = b_old - lr * s;
     }
   }
   __syncthreads();
@@ -655,7 +788,7 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
     frontend_item(P.fe, item, ctx.image);
   } else if constexpr (KIND == ST_CONV_FWD) {
     if (st.pix_per_thread == 1) conv_fwd_item<1>(L, st, item, in, lds);
-    else conv_fwd_item<4>(L, st, item, in, lds);
+    else conv_fwd_item<2>(L, st, item, in, lds);
   } else if constexpr (KIND == ST_FC_FWD) {
     fc_fwd_item(L, st, item, in, lds);
   } else if constexpr (KIND == ST_HEAD) {

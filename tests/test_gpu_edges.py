@@ -24,7 +24,7 @@ SHAPES = [
     ("2x10x10-5C1-MP2-3C1S1-6N-2N", {}, 0, 2),               # 1x1 kernels
     ("1x20x20-6C6-MP3-5C3S2-4N", {}, 0, 1),                  # kernel sizes without a compiled specialisation; skip 2
     ("2x23x23-5C7S1-4C2-MP2-3N", {1: 3}, 0, 2),
-    ("1x8x300-3C3-MP2-4C2S1-5N", {}, 0, 1),                  # rows wider than 256 pixels: four pixels per thread
+    ("1x8x600-3C3-MP2-4C2S1-5N", {}, 0, 1),                  # rows wider than one workgroup: two pixels per thread
     ("1x70x70-4C3-MP4-3C4-MP2-6N", {}, 0, 1),                # several row bands per map, ragged last band
     ("3x34x47-7C4S1-8C3-MP2-9C2-MP3-20N-6N", {1: 4, 2: 5}, 0, 3),   # rectangular maps, three conv layers
     ("1x40x40-70C5-MP4-300C3-MP1-10N", {}, 0, 1),            # many maps on few pixels: chunked connection lists
