@@ -46,8 +46,15 @@ enum { CNN_LAYER_INPUT = 0, CNN_LAYER_CONV = 1, CNN_LAYER_POOL = 2, CNN_LAYER_FC
 /* execution modes for cnn_set_mode */
 enum {
   CNN_MODE_STAGES = 0,    /* one kernel launch per stage of the step                      */
-  CNN_MODE_PERSISTENT = 1 /* one cooperative launch per call; stages separated by grid
+  CNN_MODE_PERSISTENT = 1,/* one cooperative launch per call; stages separated by grid
                              barriers, images of cnn_*_many looped on the device          */
+  CNN_MODE_RESIDENT = 2   /* one cooperative launch per call; every workgroup owns whole
+                             maps and keeps their weights in LDS for the whole call; what
+                             workgroups exchange per image travels as tagged words, with no
+                             grid barrier.  Needs at least one convolutional layer, no fixed
+                             front-end, and a network whose per-workgroup share fits the LDS
+                             (cnn_mode_supported tells).  Weights in the workspace are read
+                             at the start of a call and written back at its end.            */
 };
 
 /*
@@ -145,8 +152,23 @@ int cnn_train_many(cnn_t* net, const float* d_images, const int32_t* d_labels, s
 /* n forward propagations; d_probs: n * cnn_num_classes floats.  Asynchronous. */
 int cnn_forward_many(cnn_t* net, const float* d_images, size_t n, float* d_probs);
 
-/* Choose how a step is issued (CNN_MODE_*).  Results are identical bit for bit. */
+/* Choose how a step is issued (CNN_MODE_*).  CNN_MODE_STAGES and CNN_MODE_PERSISTENT give
+ * identical bits; CNN_MODE_RESIDENT sums in another order and agrees with them to rounding.
+ * CNN_E_STATE when the mode cannot run this network (the mode is then unchanged).  Setting a
+ * connection table or a front-end re-plans the network: if resident mode can no longer run it
+ * the handle drops to CNN_MODE_PERSISTENT (cnn_get_mode tells). */
 int cnn_set_mode(cnn_t* net, int mode);
+int cnn_get_mode(const cnn_t* net);
+/* 1 when `mode` can run this network on this device, else 0 (cnn_last_error says why). */
+int cnn_mode_supported(cnn_t* net, int mode);
+
+/* Resident mode: size and placement of the team.  n_ranks workgroups share the maps (0 =
+ * automatic: one per map of the widest convolutional layer, at most one per compute unit);
+ * xcd_stride 8 launches 8 x n_ranks workgroups of which every eighth works, which puts the
+ * whole team on one XCD (at most 32 ranks); 1 spreads the team over all XCDs; 0 = automatic.
+ * Results do not depend on the placement, and for a given n_ranks they are reproducible bit
+ * for bit.  Synchronises. */
+int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride);
 
 /* Persistent mode: number of workgroups of the cooperative launch (0 = automatic: the
  * largest stage's work items, capped at the number of compute units).  Values above what

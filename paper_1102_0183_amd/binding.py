@@ -14,7 +14,7 @@ from . import build as _build
 
 OK, E_SYNTAX, E_SHAPE, E_ARG, E_WORKSPACE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6
 LAYER_INPUT, LAYER_CONV, LAYER_POOL, LAYER_FC = 0, 1, 2, 3
-MODE_STAGES, MODE_PERSISTENT = 0, 1
+MODE_STAGES, MODE_PERSISTENT, MODE_RESIDENT = 0, 1, 2
 
 _lib = None
 
@@ -54,6 +54,9 @@ def lib():
             "cnn_train_many": (C.c_int, [vp, vp, vp, sz, C.c_float]),
             "cnn_forward_many": (C.c_int, [vp, vp, sz, vp]),
             "cnn_set_mode": (C.c_int, [vp, C.c_int]),
+            "cnn_get_mode": (C.c_int, [vp]),
+            "cnn_mode_supported": (C.c_int, [vp, C.c_int]),
+            "cnn_set_team": (C.c_int, [vp, C.c_int, C.c_int]),
             "cnn_set_grid": (C.c_int, [vp, C.c_int]),
             "cnn_set_spin_limit": (C.c_int, [vp, C.c_uint]),
             "cnn_set_barrier": (C.c_int, [vp, C.c_int]),
@@ -78,7 +81,7 @@ EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_create"
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
-           "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
+           "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
            "cnn_last_error"]
 
@@ -194,6 +197,16 @@ class Cnn:
     def set_mode(self, mode):
         self._ck(lib().cnn_set_mode(self._h, int(mode)), "cnn_set_mode")
 
+    @property
+    def mode(self):
+        return int(lib().cnn_get_mode(self._h))
+
+    def mode_supported(self, mode):
+        return bool(lib().cnn_mode_supported(self._h, int(mode)))
+
+    def set_team(self, n_ranks=0, xcd_stride=0):
+        self._ck(lib().cnn_set_team(self._h, int(n_ranks), int(xcd_stride)), "cnn_set_team")
+
     def set_grid(self, n_workgroups):
         self._ck(lib().cnn_set_grid(self._h, int(n_workgroups)), "cnn_set_grid")
 
@@ -278,6 +291,15 @@ class Cnn:
         self._ck(lib().cnn_get_stage_times(self._h, buf.ctypes.data, 128, C.addressof(n)),
                  "cnn_get_stage_times")
         return [(float(buf[2 * k]), float(buf[2 * k + 1])) for k in range(n.value)]
+
+    def raw_stamps(self, n=128):
+        """Development aid: device timestamps (100 MHz ticks) left by the last call."""
+        buf = np.zeros(n, dtype=np.uint64)
+        f = lib().cnn355_read_status_stamps
+        f.restype = C.c_int
+        f.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
+        self._ck(f(self._h, buf.ctypes.data, n), "cnn355_read_status_stamps")
+        return buf
 
     def debug_gradients(self, d_image, label):
         g = np.empty(self.num_weights, dtype=np.float32)

@@ -21,6 +21,8 @@ hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_p
                              StatusDev* d_status, const RunArgs& a);
 int persistent_max_blocks_per_cu();
 void read_dbg(unsigned long long* out);
+hipError_t launch_resident(int grid, size_t lds_bytes, hipStream_t stream, const ProgramDev* d_prog,
+                           const FlowDev* d_flow, StatusDev* d_status, const RunArgs& a);
 }  // namespace cnn355
 
 using namespace cnn355;
@@ -185,6 +187,16 @@ struct cnn {
   struct HostTable { std::vector<int> csr_ptr, csr_idx, csc_ptr, csc_j, csc_slot; int max_conn = 0, max_back = 0; };
   std::vector<HostTable> host_tables;  // per convolutional layer, rebuilt by plan()
 
+  // resident mode
+  FlowDev flow;                 // host copy with device pointers
+  FlowDev* d_flow = nullptr;
+  tagged_t* d_xbuf = nullptr;   // every exchange buffer, one after the other
+  size_t xbuf_words = 0;
+  bool flow_ok = false;
+  std::string flow_why;         // why resident mode cannot run this network
+  int team_ranks = 0, team_stride = 0;  // 0 = automatic
+  unsigned long long epoch = 0; // images run in resident mode so far (their tags)
+
   size_t n_weights = 0, n_weights_max = 0;
   size_t image_size = 0;
   int n_classes = 0;
@@ -226,6 +238,23 @@ size_t carve(cnn* net, void* base) {
   net->d_fe_filters = c.take<float>((size_t)A[0].maps * MAX_FRONTEND_K * MAX_FRONTEND_K);
   net->d_fe_src = c.take<int>(A[0].maps);
   net->d_fe_out = c.take<float>((size_t)A[0].maps * A[0].h * A[0].w);
+  net->d_flow = c.take<FlowDev>(1);
+  {  // resident mode: tagged exchange buffers, sized for any team (see plan_flow for the split)
+    size_t words = 0, last_maps = 0, first_fc = 0;
+    for (size_t l = 1; l < A.size(); ++l) {
+      if (A[l].kind == CNN_LAYER_CONV) {
+        const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
+        const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : (size_t)A[l].maps * A[l].h * A[l].w;
+        words += 3 * 2 * small;  // pooled outputs, deltas, winner coordinates; two images in flight
+        last_maps = A[l].maps;
+      } else if (A[l].kind == CNN_LAYER_FC && !first_fc) {
+        first_fc = A[l].maps;
+      }
+    }
+    words += 2 * std::min<size_t>(last_maps, 256) * first_fc;
+    net->xbuf_words = words;
+    net->d_xbuf = c.take<tagged_t>(words);
+  }
   net->conv_buf.clear();
   net->fc_buf.clear();
   for (size_t l = 1; l < A.size(); ++l) {
@@ -370,6 +399,8 @@ int check_plan(cnn* net) {
   }
   return CNN_OK;
 }
+
+void plan_flow(cnn* net);
 
 // Build layer descriptors, tables and the stage list on the host (no device call).  Works on
 // a handle whose workspace pointers are NULL (measuring / checking only).
@@ -531,7 +562,114 @@ int plan(cnn* net) {
   if (ns > 0) P.stages[ns - 1].barrier_after = 1;
   P.n_stages = ns;
 
-  return check_plan(net);
+  int rc = check_plan(net);
+  if (rc) return rc;
+  plan_flow(net);
+  if (net->mode == CNN_MODE_RESIDENT && !net->flow_ok) net->mode = CNN_MODE_PERSISTENT;
+  return CNN_OK;
+}
+
+
+// Resident mode: choose the team, lay out every rank's LDS and the exchange buffers.  Sets
+// net->flow_ok; a network the mode cannot take keeps flow_ok = false with the reason in flow_why
+// (not an error: the other modes still run it).
+void plan_flow(cnn* net) {
+  const ProgramDev& P = net->prog;
+  FlowDev& F = net->flow;
+  std::memset(&F, 0, sizeof(F));
+  net->flow_ok = false;
+  auto no = [&](const std::string& why) { net->flow_why = why; };
+  int n_conv = 0;
+  while (n_conv < P.n_layers && P.layers[n_conv].kind == L_CONV) ++n_conv;
+  const int n_fc = P.n_layers - n_conv;
+  if (n_conv < 1) return no("resident mode needs at least one convolutional layer");
+  if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1) return no("too many layers for resident mode");
+  if (P.has_frontend) return no("resident mode does not run a fixed front-end");
+  int max_maps = 1;
+  for (int l = 0; l < n_conv; ++l) max_maps = std::max(max_maps, P.layers[l].Mo);
+  int stride = net->team_stride > 0 ? net->team_stride : 0;
+  int G = net->team_ranks > 0 ? net->team_ranks : max_maps;
+  const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
+  if (stride == 0) stride = (G <= n_cu / 8) ? 8 : 1;
+  if (stride != 1 && stride != 8) return no("team stride must be 1 or 8");
+  G = std::max(1, std::min({G, max_maps, n_cu / stride}));
+  F.G = G; F.stride = stride; F.n_conv = n_conv; F.n_fc = n_fc;
+
+  long long off = 0;
+  auto take = [&](long long n) { const long long o = off; off += (n + 3) / 4 * 4; return (int)std::min<long long>(o, 1 << 30); };
+  int max_act = 1, max_dall = 1, max_hwd = 1;
+  tagged_t* xb = net->d_xbuf;
+  size_t xoff = 0;
+  auto xtake = [&](size_t words) { tagged_t* p = xb ? xb + xoff : nullptr; xoff += words; return p; };
+  for (int l = 0; l < n_conv; ++l) {
+    const LayerDev& L = P.layers[l];
+    FlowConv& C = F.conv[l];
+    const cnn::HostTable& T = net->host_tables[l];
+    const int KK = L.K * L.K, HW = L.Hp * L.Wp;
+    C.n_own = (L.Mo + G - 1) / G;
+    C.n_own_below = l >= 1 ? (L.Mi + G - 1) / G : 0;
+    C.max_back = std::max(1, T.max_back);
+    C.o_in = take((long long)L.Mi * L.Hi * L.Wi);
+    C.o_wf = take((long long)C.n_own * L.max_conn * KK);
+    C.o_bf = take(C.n_own);
+    C.o_cidx = take((long long)C.n_own * L.max_conn);
+    C.o_ncf = take(C.n_own);
+    if (l >= 1) {
+      C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
+      C.o_bj = take((long long)C.n_own_below * C.max_back);
+      C.o_ncb = take(C.n_own_below);
+      max_dall = std::max(max_dall, L.Mo * HW);
+      max_hwd = std::max(max_hwd, (L.Ho + 1) * (L.Wo + 1));
+    }
+    C.o_pool = take((long long)C.n_own * HW);
+    C.o_yx = take((long long)C.n_own * HW);
+    C.o_delta = take((long long)C.n_own * HW);
+    max_act = std::max(max_act, L.Ho * L.Wo);
+    // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
+    long long n_w = (long long)C.n_own * L.max_conn * KK;
+    if (l >= 1) n_w = std::min(n_w, (long long)C.n_own_below * C.max_back * KK);
+    int rl2 = 0;
+    while (rl2 < 6 && (n_w << (rl2 + 1)) <= WG && (2 << rl2) <= HW) ++rl2;
+    C.wgrad_R_log2 = rl2;
+    const size_t small = (size_t)L.Mo * HW;
+    C.x_out = (l + 1 < n_conv) ? xtake(2 * small) : nullptr;
+    C.x_delta = (l >= 1) ? xtake(2 * small) : nullptr;
+    C.x_yx = (l >= 1) ? xtake(2 * small) : nullptr;
+    if (L.Ho >= 32768 || L.Wo >= 65536) return no("map too large");
+  }
+  const LayerDev& Lc = P.layers[n_conv - 1];
+  const LayerDev& L1 = P.layers[n_conv];
+  F.n_col_ranks = std::min(G, Lc.Mo);
+  for (int f = 0; f < n_fc; ++f) {
+    const LayerDev& L = P.layers[n_conv + f];
+    FlowFc& Q = F.fc[f];
+    Q.o_w = take(f == 0 ? (long long)F.conv[n_conv - 1].n_own * Lc.Hp * Lc.Wp * L.n_out : (long long)L.n_out * L.n_in);
+    Q.o_b = take(L.n_out);
+    Q.o_act = take(L.n_out);
+    Q.o_delta = take(L.n_out);
+  }
+  F.xp = xtake((size_t)2 * F.n_col_ranks * L1.n_out);
+  if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
+  F.o_act = take(max_act);
+  F.o_part = take(2 * WG);
+  F.o_dall = take(n_conv > 1 ? max_dall : 0);
+  F.o_yxall = take(n_conv > 1 ? max_dall : 0);
+  const long long need = std::max<long long>((long long)F.n_col_ranks * L1.n_out, n_conv > 1 ? max_hwd : 0);
+  if (off + need > FLOW_LDS_FLOATS_MAX)
+    return no("the weights and maps one workgroup would hold (" + std::to_string((off + need) * 4 / 1024) +
+              " KB) exceed its LDS");
+  // whatever is left serves as scratch: the more, the more delta maps one pass of the pull rebuilds
+  long long scratch = std::min<long long>(FLOW_LDS_FLOATS_MAX - off, 16384);
+  scratch = std::max(scratch, need);
+  F.o_scratch = take(scratch);
+  F.scratch_floats = (int)scratch;
+  F.lds_floats = (int)off;
+  for (int l = 1; l < n_conv; ++l) {
+    const LayerDev& L = P.layers[l];
+    F.conv[l].pull_chunk = std::max(1, std::min(F.conv[l].max_back, (int)(scratch / ((L.Ho + 1) * (L.Wo + 1)))));
+  }
+  net->flow_ok = true;
+  net->flow_why.clear();
 }
 
 // Upload what plan() built.  Weights are zeroed.
@@ -560,6 +698,9 @@ int upload(cnn* net) {
     ++conv_i;
   }
   HIP_TRY(net, hipMemcpy(net->d_prog, &P, sizeof(P), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowDev), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemset(net->d_xbuf, 0, net->xbuf_words * sizeof(tagged_t)));
+  net->epoch = 0;
   HIP_TRY(net, hipMemset(net->d_weights, 0, net->n_weights_max * sizeof(float)));
   HIP_TRY(net, hipMemset(net->d_status, 0, sizeof(StatusDev)));
   return CNN_OK;
@@ -575,7 +716,7 @@ int check_status(cnn* net) {
   StatusDev s;
   HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
   int rc = CNN_OK;
-  if (s.abort_flag) rc = fail(&net->err, CNN_E_HIP, "grid barrier of the persistent kernel timed out");
+  if (s.abort_flag) rc = fail(&net->err, CNN_E_HIP, "a wait inside the persistent or resident kernel timed out; the weights are undefined");
   else if (s.bad_label) rc = fail(&net->err, CNN_E_ARG, "a label outside [0, classes) was met; that image was skipped");
   if (s.abort_flag || s.bad_label) {
     const float loss = s.loss;
@@ -604,6 +745,22 @@ int run(cnn* net, const RunArgs& a0) {
   a.spin_limit = net->spin_limit;
   a.barrier_kind = net->barrier_kind;
   const ProgramDev& P = net->prog;
+  if (net->mode == CNN_MODE_RESIDENT) {
+    const unsigned long long n = (unsigned long long)a.n_images;
+    if (n >= (1ull << 31)) return fail(&net->err, CNN_E_ARG, "too many images in one call");
+    if (((net->epoch + n) >> 32) != (net->epoch >> 32)) {
+      // the 32-bit tags would wrap inside this call: start a fresh range on cleared buffers
+      net->epoch = ((net->epoch >> 32) + 1) << 32;
+      HIP_TRY(net, hipStreamSynchronize(net->stream));
+      HIP_TRY(net, hipMemset(net->d_xbuf, 0, net->xbuf_words * sizeof(tagged_t)));
+    }
+    a.epoch_base = (unsigned int)net->epoch;
+    net->epoch += n;
+    HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
+    HIP_TRY(net, launch_resident(net->flow.G * net->flow.stride, (size_t)net->flow.lds_floats * sizeof(float),
+                                 net->stream, net->d_prog, net->d_flow, net->d_status, a));
+    return CNN_OK;
+  }
   if (net->mode == CNN_MODE_PERSISTENT) {
     HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
     HIP_TRY(net, launch_persistent(persistent_grid(net, a.train), net->stream, net->d_prog, net->d_status, a));
@@ -812,9 +969,35 @@ int cnn_train_many(cnn_t* net, const float* d_images, const int32_t* d_labels, s
 
 int cnn_set_mode(cnn_t* net, int mode) {
   if (!net) return CNN_E_ARG;
-  if (mode != CNN_MODE_STAGES && mode != CNN_MODE_PERSISTENT) return fail(&net->err, CNN_E_ARG, "unknown mode");
-  if (mode == CNN_MODE_PERSISTENT && !net->coop_ok) return fail(&net->err, CNN_E_STATE, "device does not support cooperative launches");
+  if (mode != CNN_MODE_STAGES && mode != CNN_MODE_PERSISTENT && mode != CNN_MODE_RESIDENT)
+    return fail(&net->err, CNN_E_ARG, "unknown mode");
+  if (mode != CNN_MODE_STAGES && !net->coop_ok) return fail(&net->err, CNN_E_STATE, "device does not support cooperative launches");
+  if (mode == CNN_MODE_RESIDENT && !net->flow_ok) return fail(&net->err, CNN_E_STATE, net->flow_why);
   net->mode = mode;
+  return CNN_OK;
+}
+
+int cnn_mode_supported(cnn_t* net, int mode) {
+  if (!net) return 0;
+  if (mode == CNN_MODE_STAGES) return 1;
+  if (mode == CNN_MODE_PERSISTENT) return net->coop_ok ? 1 : 0;
+  if (mode == CNN_MODE_RESIDENT) return (net->coop_ok && net->flow_ok) ? 1 : 0;
+  return 0;
+}
+
+int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
+
+int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride) {
+  if (!net || n_ranks < 0 || (xcd_stride != 0 && xcd_stride != 1 && xcd_stride != 8)) return CNN_E_ARG;
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  net->team_ranks = n_ranks;
+  net->team_stride = xcd_stride;
+  plan_flow(net);
+  if (net->d_flow) HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowDev), hipMemcpyHostToDevice));
+  if (net->mode == CNN_MODE_RESIDENT && !net->flow_ok) {
+    net->mode = CNN_MODE_PERSISTENT;
+    return fail(&net->err, CNN_E_STATE, net->flow_why);
+  }
   return CNN_OK;
 }
 
@@ -936,6 +1119,16 @@ int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* 
   rc = sync_and_check(net);
   HIP_TRY(net, hipMemcpy(host_grad, net->d_grad, net->n_weights * sizeof(float), hipMemcpyDeviceToHost));
   return rc;
+}
+
+// development aid, not part of the public header: the raw device timestamps (100 MHz ticks) of the last call
+int cnn355_read_status_stamps(cnn_t* net, unsigned long long* out, int n) {
+  if (!net || !out) return CNN_E_ARG;
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  StatusDev s;
+  HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
+  for (int i = 0; i < n && i < 2 * MAX_STAGES + 2; ++i) out[i] = s.stamps[i];
+  return CNN_OK;
 }
 
 // development aid, not part of the public header: in-item timestamps (zeros unless built with CNN355_STAMPS)

@@ -134,6 +134,70 @@ struct RunArgs {
   float lr;
   unsigned int spin_limit; // grid-barrier polls before giving up
   int barrier_kind;        // 0: one counter, full fences in every workgroup; 1: two-level (per XCD)
+  unsigned int epoch_base; // resident mode: image t of this call carries tag epoch_base + t + 1
+};
+
+// ---- resident mode -----------------------------------------------------------------------
+// Every workgroup ("rank") of a team owns whole maps: output maps j = rank, rank + G, ... of every
+// convolutional layer.  For those it keeps in LDS, for the whole call, the filters it needs going
+// forward (row j of the connection table) and, for the maps it owns in the layer below, a second
+// copy of the filters that read them (column i), so that neither the forward pass nor the delta
+// pull nor the weight adjustment touches another rank's weights.  What ranks exchange per image
+// -- pooled outputs, partial sums of the first fully connected layer, deltas -- travels through
+// global memory as 64-bit words {value, tag}, written and polled with device-scope atomics; the
+// tag names the image, so a reader needs no barrier: it polls the word until the tag matches.
+typedef unsigned long long tagged_t;
+
+constexpr int FLOW_MAX_CONV = 12;
+constexpr int FLOW_MAX_FC = 12;
+constexpr int FLOW_LDS_FLOATS_MAX = 40704;  // 159 KB of the 160 KB of a gfx950 CU
+
+struct FlowConv {
+  int n_own;        // most output maps a rank owns: ceil(Mo / G)
+  int n_own_below;  // most input maps a rank owns (maps of the layer below): ceil(Mi / G); 0 for the first layer
+  int max_back;     // longest column of the connection table
+  int wgrad_R_log2; // pooled positions are split 2^this ways when summing a weight gradient
+  int pull_chunk;   // output maps rebuilt at full resolution per pass of the delta pull
+  // LDS offsets, in floats
+  int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
+  int o_wf;     // [n_own][max_conn][K*K] forward copy of the filters
+  int o_bf;     // [n_own] biases
+  int o_cidx;   // [n_own][max_conn] input map of every connection (int)
+  int o_wb;     // [n_own_below][max_back][K*K] pull copy of the filters (layers above the first)
+  int o_bj;     // [n_own_below][max_back] output map of every entry (int)
+  int o_pool;   // [n_own][Hp*Wp] pooled outputs of the own maps
+  int o_yx;     // [n_own][Hp*Wp] winner coordinates (y << 16 | x) (int)
+  int o_delta;  // [n_own][Hp*Wp] deltas at the winners
+  int o_ncf;    // [n_own] connections of every own map (int)
+  int o_ncb;    // [n_own_below] entries of every own input map (int)
+  CNN_GLOBAL tagged_t* x_out;    // [2][Mo*Hp*Wp] pooled outputs, when a convolutional layer follows
+  CNN_GLOBAL tagged_t* x_delta;  // [2][Mo*Hp*Wp] deltas at the winners (layers above the first)
+  CNN_GLOBAL tagged_t* x_yx;     // [2][Mo*Hp*Wp] their coordinates
+};
+
+struct FlowFc {
+  int o_w;      // first layer: [columns of the own maps][n_out]; others: [n_out][n_in], every rank
+  int o_b;      // [n_out]
+  int o_act;    // [n_out]
+  int o_delta;  // [n_out]
+};
+
+struct FlowDev {
+  int G;            // ranks
+  int stride;       // rank r is workgroup r * stride of the launch (8: all ranks on one XCD)
+  int n_conv, n_fc; // layers 0..n_conv-1 of the program are convolutional, the rest fully connected
+  int n_col_ranks;  // ranks that own maps of the last convolutional layer (and so columns of the first FC layer)
+  int lds_floats;
+  int o_act;        // [max Ho*Wo] full-resolution output of the map being computed
+  int o_part;       // [2 * WG] partial sums
+  int o_scratch;    // staged partial sums of the first FC layer / rebuilt delta maps
+  int scratch_floats;
+  int o_dall;       // [max Mo*Hp*Wp] deltas of every map of the layer being pulled through
+  int o_yxall;      // same, winner coordinates
+  int pad_;
+  FlowConv conv[FLOW_MAX_CONV];
+  FlowFc fc[FLOW_MAX_FC];
+  CNN_GLOBAL tagged_t* xp;  // [2][n_col_ranks][n_out of the first FC layer] partial sums
 };
 
 }  // namespace cnn355
