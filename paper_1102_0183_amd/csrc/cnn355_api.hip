@@ -21,6 +21,8 @@ hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_p
                              StatusDev* d_status, const RunArgs& a);
 int persistent_max_blocks_per_cu();
 void read_dbg(unsigned long long* out);
+hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, const float* d_images,
+                                 long long image_stride, int n_images, int items_per_image, float* d_out);
 hipError_t launch_resident(int grid, size_t lds_bytes, hipStream_t stream, const ProgramDev* d_prog,
                            const FlowDev* d_flow, StatusDev* d_status, const RunArgs& a);
 }  // namespace cnn355
@@ -28,6 +30,8 @@ hipError_t launch_resident(int grid, size_t lds_bytes, hipStream_t stream, const
 using namespace cnn355;
 
 namespace {
+
+constexpr int FE_BATCH = 256;  // images whose front-end outputs are computed ahead of the resident kernel
 
 thread_local std::string g_err;  // message of the last failure that had no handle to carry it
 
@@ -176,6 +180,7 @@ struct cnn {
   float* d_fe_filters = nullptr;
   int* d_fe_src = nullptr;
   float* d_fe_out = nullptr;
+  float* d_fe_batch = nullptr;  // resident mode: front-end outputs of FE_BATCH images at a time
   struct ConvBuf {
     float *act, *out, *delta;
     uint8_t* arg;
@@ -238,6 +243,7 @@ size_t carve(cnn* net, void* base) {
   net->d_fe_filters = c.take<float>((size_t)A[0].maps * MAX_FRONTEND_K * MAX_FRONTEND_K);
   net->d_fe_src = c.take<int>(A[0].maps);
   net->d_fe_out = c.take<float>((size_t)A[0].maps * A[0].h * A[0].w);
+  net->d_fe_batch = c.take<float>((size_t)FE_BATCH * A[0].maps * A[0].h * A[0].w);
   net->d_flow = c.take<FlowDev>(1);
   {  // resident mode: tagged exchange buffers, sized for any team (see plan_flow for the split)
     size_t words = 0, last_maps = 0, first_fc = 0;
@@ -584,7 +590,6 @@ void plan_flow(cnn* net) {
   const int n_fc = P.n_layers - n_conv;
   if (n_conv < 1) return no("resident mode needs at least one convolutional layer");
   if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1) return no("too many layers for resident mode");
-  if (P.has_frontend) return no("resident mode does not run a fixed front-end");
   int max_maps = 1;
   for (int l = 0; l < n_conv; ++l) max_maps = std::max(max_maps, P.layers[l].Mo);
   int stride = net->team_stride > 0 ? net->team_stride : 0;
@@ -597,7 +602,19 @@ void plan_flow(cnn* net) {
 
   long long off = 0;
   auto take = [&](long long n) { const long long o = off; off += (n + 3) / 4 * 4; return (int)std::min<long long>(o, 1 << 30); };
-  int max_act = 1, max_dall = 1, max_hwd = 1;
+  // strip width for a row of `width` output pixels: the one of {4, 5, 7} that wastes the fewest
+  // lanes on the ragged end of the row, the wider one on a tie; 0 = one pixel per lane
+  auto strip_for = [](int K, int stride, int width) {
+    if (stride != 1 || K < 2 || K > 5) return 0;
+    int best = 4;
+    double best_eff = 0;
+    for (int sw : {4, 5, 7}) {
+      const double eff = (double)width / (double)(((width + sw - 1) / sw) * sw);
+      if (eff >= best_eff) { best_eff = eff; best = sw; }
+    }
+    return best;
+  };
+  long long max_act = 1, max_part = (long long)FLOW_STRIP_MAX * WG, max_dall = 1, max_hwd = 0;
   tagged_t* xb = net->d_xbuf;
   size_t xoff = 0;
   auto xtake = [&](size_t words) { tagged_t* p = xb ? xb + xoff : nullptr; xoff += words; return p; };
@@ -614,17 +631,21 @@ void plan_flow(cnn* net) {
     C.o_bf = take(C.n_own);
     C.o_cidx = take((long long)C.n_own * L.max_conn);
     C.o_ncf = take(C.n_own);
+    C.fwd_strip = strip_for(L.K, L.S + 1, L.Wo);
     if (l >= 1) {
       C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
       C.o_bj = take((long long)C.n_own_below * C.max_back);
       C.o_ncb = take(C.n_own_below);
-      max_dall = std::max(max_dall, L.Mo * HW);
-      max_hwd = std::max(max_hwd, (L.Ho + 1) * (L.Wo + 1));
+      C.pull_strip = strip_for(L.K, 1, L.Wi);
+      max_dall = std::max<long long>(max_dall, (long long)L.Mo * HW);
+      max_hwd = std::max<long long>(max_hwd, (long long)(L.Hi + L.K - 1) * (L.Wi + L.K - 1));
+      max_part = std::max<long long>(max_part, (long long)C.n_own_below * L.Hi * L.Wi);
     }
     C.o_pool = take((long long)C.n_own * HW);
     C.o_yx = take((long long)C.n_own * HW);
     C.o_delta = take((long long)C.n_own * HW);
-    max_act = std::max(max_act, L.Ho * L.Wo);
+    max_act = std::max<long long>(max_act, (long long)C.n_own * L.Ho * L.Wo);
+    max_part = std::max<long long>(max_part, (long long)C.n_own * L.Ho * L.Wo);
     // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
     long long n_w = (long long)C.n_own * L.max_conn * KK;
     if (l >= 1) n_w = std::min(n_w, (long long)C.n_own_below * C.max_back * KK);
@@ -636,6 +657,7 @@ void plan_flow(cnn* net) {
     C.x_delta = (l >= 1) ? xtake(2 * small) : nullptr;
     C.x_yx = (l >= 1) ? xtake(2 * small) : nullptr;
     if (L.Ho >= 32768 || L.Wo >= 65536) return no("map too large");
+    if ((long long)L.Mi * L.Hi * L.Wi >= (1 << 20) || (long long)L.Mo * L.Ho * L.Wo >= (1 << 20)) return no("layer too large");
   }
   const LayerDev& Lc = P.layers[n_conv - 1];
   const LayerDev& L1 = P.layers[n_conv];
@@ -651,22 +673,28 @@ void plan_flow(cnn* net) {
   F.xp = xtake((size_t)2 * F.n_col_ranks * L1.n_out);
   if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
   F.o_act = take(max_act);
-  F.o_part = take(2 * WG);
+  F.o_part = take(max_part);
   F.o_dall = take(n_conv > 1 ? max_dall : 0);
   F.o_yxall = take(n_conv > 1 ? max_dall : 0);
-  const long long need = std::max<long long>((long long)F.n_col_ranks * L1.n_out, n_conv > 1 ? max_hwd : 0);
+  const long long pad = 16;  // strips read a few floats past the end of the last row of a map
+  const long long need = n_conv > 1 ? max_hwd + pad : pad;
   if (off + need > FLOW_LDS_FLOATS_MAX)
     return no("the weights and maps one workgroup would hold (" + std::to_string((off + need) * 4 / 1024) +
               " KB) exceed its LDS");
-  // whatever is left serves as scratch: the more, the more delta maps one pass of the pull rebuilds
-  long long scratch = std::min<long long>(FLOW_LDS_FLOATS_MAX - off, 16384);
-  scratch = std::max(scratch, need);
+  // the zero-bordered delta maps of the pull: the more fit, the fewer passes
+  long long scratch = need;
+  for (int l = 1; l < n_conv; ++l) {
+    const LayerDev& L = P.layers[l];
+    scratch = std::max(scratch, (long long)L.Mo * (L.Hi + L.K - 1) * (L.Wi + L.K - 1) + pad);
+  }
+  scratch = std::min(scratch, (long long)FLOW_LDS_FLOATS_MAX - off);
   F.o_scratch = take(scratch);
   F.scratch_floats = (int)scratch;
   F.lds_floats = (int)off;
   for (int l = 1; l < n_conv; ++l) {
     const LayerDev& L = P.layers[l];
-    F.conv[l].pull_chunk = std::max(1, std::min(F.conv[l].max_back, (int)(scratch / ((L.Ho + 1) * (L.Wo + 1)))));
+    const long long hwd = (long long)(L.Hi + L.K - 1) * (L.Wi + L.K - 1);
+    F.conv[l].pull_chunk = (int)std::max<long long>(1, std::min<long long>(L.Mo, (scratch - pad) / hwd));
   }
   net->flow_ok = true;
   net->flow_why.clear();
@@ -754,11 +782,36 @@ int run(cnn* net, const RunArgs& a0) {
       HIP_TRY(net, hipStreamSynchronize(net->stream));
       HIP_TRY(net, hipMemset(net->d_xbuf, 0, net->xbuf_words * sizeof(tagged_t)));
     }
-    a.epoch_base = (unsigned int)net->epoch;
-    net->epoch += n;
+    const int grid = net->flow.G * net->flow.stride;
+    const size_t lds_bytes = (size_t)net->flow.lds_floats * sizeof(float);
     HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
-    HIP_TRY(net, launch_resident(net->flow.G * net->flow.stride, (size_t)net->flow.lds_floats * sizeof(float),
-                                 net->stream, net->d_prog, net->d_flow, net->d_status, a));
+    if (!P.has_frontend) {
+      a.epoch_base = (unsigned int)net->epoch;
+      net->epoch += n;
+      HIP_TRY(net, launch_resident(grid, lds_bytes, net->stream, net->d_prog, net->d_flow, net->d_status, a));
+      return CNN_OK;
+    }
+    // fixed front-end: computed for FE_BATCH images at a time by all compute units, outside the
+    // on-line chain; the resident kernel then trains on its outputs
+    const size_t fe_sz = (size_t)P.fe.n_filters * P.fe.H * P.fe.W;
+    const int items = (int)((fe_sz + WG - 1) / WG);
+    for (unsigned long long t0 = 0; t0 < n; t0 += FE_BATCH) {
+      const int nb = (int)std::min<unsigned long long>(FE_BATCH, n - t0);
+      HIP_TRY(net, launch_frontend_batch(net->stream, net->d_prog, a0.images + t0 * a0.image_stride, a0.image_stride,
+                                         nb, items, net->d_fe_batch));
+      RunArgs b = a;
+      b.images = net->d_fe_batch;
+      b.image_stride = (long long)fe_sz;
+      b.labels = a.labels ? a.labels + t0 : nullptr;
+      b.probs_out = a.probs_out ? a.probs_out + t0 * P.n_classes : nullptr;
+      b.n_images = nb;
+      b.epoch_base = (unsigned int)net->epoch;
+      net->epoch += (unsigned long long)nb;
+      HIP_TRY(net, launch_resident(grid, lds_bytes, net->stream, net->d_prog, net->d_flow, net->d_status, b));
+      if (t0 + nb >= n)  // parity tap: layer 0 of the last image
+        HIP_TRY(net, hipMemcpyAsync(net->d_fe_out, net->d_fe_batch + (size_t)(nb - 1) * fe_sz, fe_sz * sizeof(float),
+                                    hipMemcpyDeviceToDevice, net->stream));
+    }
     return CNN_OK;
   }
   if (net->mode == CNN_MODE_PERSISTENT) {

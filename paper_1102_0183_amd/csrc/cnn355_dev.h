@@ -148,9 +148,12 @@ struct RunArgs {
 // tag names the image, so a reader needs no barrier: it polls the word until the tag matches.
 typedef unsigned long long tagged_t;
 
-constexpr int FLOW_MAX_CONV = 12;
-constexpr int FLOW_MAX_FC = 12;
-constexpr int FLOW_LDS_FLOATS_MAX = 40704;  // 159 KB of the 160 KB of a gfx950 CU
+constexpr int FLOW_MAX_CONV = 8;
+constexpr int FLOW_MAX_FC = 8;
+// the arena a rank carves up, in floats (154 KB of the 160 KB of a gfx950 CU; the rest holds a copy
+// of the descriptors)
+constexpr int FLOW_LDS_FLOATS_MAX = 39424;
+constexpr int FLOW_STRIP_MAX = 7;  // output pixels one lane accumulates in registers
 
 struct FlowConv {
   int n_own;        // most output maps a rank owns: ceil(Mo / G)
@@ -158,6 +161,8 @@ struct FlowConv {
   int max_back;     // longest column of the connection table
   int wgrad_R_log2; // pooled positions are split 2^this ways when summing a weight gradient
   int pull_chunk;   // output maps rebuilt at full resolution per pass of the delta pull
+  int fwd_strip;    // output pixels per lane in FP (0: one pixel per lane, any stride)
+  int pull_strip;   // same for the delta pull through this layer
   // LDS offsets, in floats
   int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
   int o_wf;     // [n_own][max_conn][K*K] forward copy of the filters
@@ -188,9 +193,9 @@ struct FlowDev {
   int n_conv, n_fc; // layers 0..n_conv-1 of the program are convolutional, the rest fully connected
   int n_col_ranks;  // ranks that own maps of the last convolutional layer (and so columns of the first FC layer)
   int lds_floats;
-  int o_act;        // [max Ho*Wo] full-resolution output of the map being computed
-  int o_part;       // [2 * WG] partial sums
-  int o_scratch;    // staged partial sums of the first FC layer / rebuilt delta maps
+  int o_act;        // [max n_own*Ho*Wo] full-resolution outputs of the own maps of the layer being computed
+  int o_part;       // partial sums
+  int o_scratch;    // delta maps of a chunk of output maps rebuilt at full resolution, zero border included
   int scratch_floats;
   int o_dall;       // [max Mo*Hp*Wp] deltas of every map of the layer being pulled through
   int o_yxall;      // same, winner coordinates

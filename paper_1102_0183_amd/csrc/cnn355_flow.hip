@@ -24,6 +24,11 @@
 //     two images ahead of another, so a buffer is never overwritten before it has been read.
 // Three such crossings per image for a network with two convolutional layers, against seven
 // grid-wide barriers in the stage-by-stage schedule.
+//
+// Inside a rank the two heavy loops (FP of a map, and the delta pull, which is FP's mirror image:
+// a correlation of the zero-padded delta maps with the filters rotated by 180 degrees) keep a strip
+// of output pixels in registers, so that one LDS read of an input or a weight feeds several
+// multiply-adds; with one pixel per lane the loop is bound by LDS bandwidth, not by the ALUs.
 #include <hip/hip_runtime.h>
 
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -42,18 +47,69 @@ __device__ __forceinline__ float f_act(float a) { return ACT_A * tanhf(ACT_B * a
 __device__ __forceinline__ float f_dact(float y) {
   return (float)(1.7159 * 0.6666) - (float)(0.6666 / 1.7159) * y * y;
 }
-__device__ __forceinline__ float f_wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+// Cross-lane moves inside a row of 16 lanes through the data-parallel primitives of the ALU (a few
+// cycles each), instead of the LDS crossbar a general shuffle goes through (an LDS latency each).
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+#define DPP_XOR1 0xB1         // quad_perm [1,0,3,2]
+#define DPP_XOR2 0x4E         // quad_perm [2,3,0,1]
+#define DPP_HALF_MIRROR 0x141 // lane i <-> 7 - i of every 8
+#define DPP_MIRROR 0x140      // lane i <-> 15 - i of every 16
+__device__ __forceinline__ float lane_f(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+// Sum over the aligned group of 2^gl2 lanes (gl2 <= 6) each lane belongs to; every lane of the group
+// gets the same bits (each step adds two values that are equal across the halves it joins).
+__device__ __forceinline__ float group_sum(float v, int gl2) {
+  if (gl2 >= 1) v += dpp_mov<DPP_XOR1>(v);
+  if (gl2 >= 2) v += dpp_mov<DPP_XOR2>(v);
+  if (gl2 >= 3) v += dpp_mov<DPP_HALF_MIRROR>(v);
+  if (gl2 >= 4) v += dpp_mov<DPP_MIRROR>(v);
+  if (gl2 >= 5) v += __shfl_xor(v, 16, 64);
+  if (gl2 >= 6) v += __shfl_xor(v, 32, 64);
   return v;
 }
+__device__ __forceinline__ float f_wave_sum(float v) {
+  v += dpp_mov<DPP_XOR1>(v);
+  v += dpp_mov<DPP_XOR2>(v);
+  v += dpp_mov<DPP_HALF_MIRROR>(v);
+  v += dpp_mov<DPP_MIRROR>(v);
+  return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
 __device__ __forceinline__ float f_wave_max(float v) {
+  v = fmaxf(v, dpp_mov<DPP_XOR1>(v));
+  v = fmaxf(v, dpp_mov<DPP_XOR2>(v));
+  v = fmaxf(v, dpp_mov<DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_mov<DPP_MIRROR>(v));
+  return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+}
+
+// sum of part[p], part[p + pitch], ... (n terms) in that order, the LDS reads issued eight at a time
+__device__ __forceinline__ float sum_strided(const float* part, int n, int pitch, int p) {
+  float s = 0.f;
+  for (int r0 = 0; r0 < n; r0 += 8) {
+    float v[8];
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
+    for (int u = 0; u < 8; ++u) v[u] = part[min(r0 + u, n - 1) * pitch + p];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (r0 + u < n) ? v[u] : 0.f;
+  }
+  return s;
 }
 
 __device__ __forceinline__ int n_mine(int M, int rank, int G) { return rank < M ? (M - rank + G - 1) / G : 0; }
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// x / d for 0 <= x < 2^20 and 1 <= d < 2^20 by a float multiplication with the hardware
+// reciprocal (1 ulp): (x + 0.5) / d lies at least 0.5 / d away from the next integer, the
+// product is off by less than x / d * 2^-21, which is smaller
+struct FDiv {
+  float inv;
+  __device__ __forceinline__ explicit FDiv(int d) : inv(__builtin_amdgcn_rcpf((float)d)) {}
+  __device__ __forceinline__ int div(int x) const { return (int)(((float)x + 0.5f) * inv); }
+};
 
 // ---- tagged words ---------------------------------------------------------------------------
 __device__ __forceinline__ void put_f(gtagged* p, float v, unsigned int tag) {
@@ -65,21 +121,49 @@ __device__ __forceinline__ void put_i(gtagged* p, int v, unsigned int tag) {
   __hip_atomic_store(p, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// A copy of the descriptors in LDS: reading them from global memory in every phase of every image
+// costs a memory round trip each time the scalar cache has dropped them.
+struct Shared {
+  FlowDev F;
+  LayerDev L[FLOW_MAX_CONV + FLOW_MAX_FC];
+  int fail;
+};
+
+static_assert(sizeof(Shared) + sizeof(float) * FLOW_LDS_FLOATS_MAX <= 160 * 1024, "LDS of one gfx950 compute unit");
+
+#ifdef CNN355_STAMPS
+#define DSTAMP(i) do { if (rt.dbg) rt.status->stamps[i] = wall_clock64(); } while (0)
+#else
+#define DSTAMP(i) do { } while (0)
+#endif
+
 struct Rt {  // what every phase needs
-  const ProgramDev* P;
-  const FlowDev* F;
+  bool dbg;
+  Shared* sh;
   StatusDev* status;
   float* lds;
-  int* s_fail;
   int rank;
   unsigned int spin_limit;
 };
 
+// Bounded polling: returns false when this lane has polled too often or another workgroup has
+// raised the abort flag; the flag is raised so that every workgroup leaves.
+__device__ __forceinline__ bool poll_again(const Rt& rt, unsigned int& spins) {
+  ++spins;
+  if (spins > rt.spin_limit ||
+      ((spins & 63u) == 0u && __hip_atomic_load(&rt.status->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+    __hip_atomic_store(&rt.status->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    rt.sh->fail = 1;
+    return false;
+  }
+  __builtin_amdgcn_s_sleep(1);
+  return true;
+}
+
 // Copy n tagged words into LDS (their 32-bit payloads), each lane polling its own words until
-// they carry `tag`.  Every wait is bounded: a lane that polls more than spin_limit times, or
-// that sees the abort flag, raises the flag; the caller then leaves the kernel.  Returns false
-// (to every thread of the workgroup) in that case.  Ends with a workgroup barrier.
-__device__ bool gather(const Rt& rt, unsigned int* dst, const gtagged* src, int n, unsigned int tag) {
+// they carry `tag`.  Ends with a workgroup barrier; returns false (to every thread of the
+// workgroup) when a wait gave up: the caller then leaves the kernel.
+__device__ __forceinline__ bool gather(const Rt& rt, unsigned int* dst, const gtagged* src, int n, unsigned int tag) {
   constexpr int U = 4;
   const int tid = threadIdx.x;
   for (int base = 0; base < n; base += U * WG) {
@@ -92,32 +176,56 @@ __device__ bool gather(const Rt& rt, unsigned int* dst, const gtagged* src, int 
       bool done = true;
 #pragma unroll
       for (int u = 0; u < U; ++u) done = done && ((unsigned int)(w[u] >> 32) == tag);
-      if (done) break;
-      ++spins;
-      if (spins > rt.spin_limit ||
-          ((spins & 63u) == 0u && __hip_atomic_load(&rt.status->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-        __hip_atomic_store(&rt.status->abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *rt.s_fail = 1;
-        break;
-      }
-      __builtin_amdgcn_s_sleep(1);
+      if (done || !poll_again(rt, spins)) break;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (base + tid + u * WG < n) dst[base + tid + u * WG] = (unsigned int)w[u];
   }
   __syncthreads();
-  return *rt.s_fail == 0;
+  return rt.sh->fail == 0;
+}
+
+// The same for two arrays of n words each, polled together (one round trip instead of two).
+__device__ __forceinline__ bool gather2(const Rt& rt, unsigned int* dst_a, const gtagged* src_a, unsigned int* dst_b,
+                                        const gtagged* src_b, int n, unsigned int tag) {
+  constexpr int U = 2;
+  const int tid = threadIdx.x;
+  for (int base = 0; base < n; base += U * WG) {
+    tagged_t wa[U], wb[U];
+    unsigned int spins = 0;
+    while (true) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = min(base + tid + u * WG, n - 1);
+        wa[u] = __hip_atomic_load(src_a + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        wb[u] = __hip_atomic_load(src_b + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      bool done = true;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        done = done && ((unsigned int)(wa[u] >> 32) == tag) && ((unsigned int)(wb[u] >> 32) == tag);
+      if (done || !poll_again(rt, spins)) break;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (base + tid + u * WG < n) {
+        dst_a[base + tid + u * WG] = (unsigned int)wa[u];
+        dst_b[base + tid + u * WG] = (unsigned int)wb[u];
+      }
+  }
+  __syncthreads();
+  return rt.sh->fail == 0;
 }
 
 // ---- weights: global (canonical order) <-> LDS -------------------------------------------------
-__device__ void flow_load(const Rt& rt) {
-  const ProgramDev& P = *rt.P;
-  const FlowDev& F = *rt.F;
+__device__ __forceinline__ void flow_load(const Rt& rt) {
+  const FlowDev& F = rt.sh->F;
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = F.G, rank = rt.rank;
+  for (int x = tid; x < F.scratch_floats; x += WG) lds[F.o_scratch + x] = 0.f;  // stays zero between uses
   for (int l = 0; l < F.n_conv; ++l) {
-    const LayerDev& L = P.layers[l];
+    const LayerDev& L = rt.sh->L[l];
     const FlowConv& C = F.conv[l];
     const int KK = L.K * L.K;
     const int nm = n_mine(L.Mo, rank, G);
@@ -136,6 +244,8 @@ __device__ void flow_load(const Rt& rt) {
       if (tid == 0) { bf[a] = L.bias[j]; ncf[a] = nc; }
     }
     if (l >= 1) {
+      // pull copy: the filters that read the own maps of the layer below, each rotated by 180
+      // degrees (tap t stored at K*K-1-t), entries in ascending order of the output map
       const int nb = n_mine(L.Mi, rank, G);
       float* wb = lds + C.o_wb;
       int* bj = (int*)(lds + C.o_bj);
@@ -149,7 +259,7 @@ __device__ void flow_load(const Rt& rt) {
           float v = 0.f;
           if (e < ne) {
             const int slot = L.full_table ? (e * L.Mi + i) : L.csc_slot[eb + e];
-            v = L.w[(size_t)slot * KK + t];
+            v = L.w[(size_t)slot * KK + (KK - 1 - t)];
           }
           wb[a * C.max_back * KK + x] = v;
         }
@@ -160,8 +270,8 @@ __device__ void flow_load(const Rt& rt) {
     }
   }
   {  // first fully connected layer: the columns fed by the own maps of the last convolutional layer
-    const LayerDev& Lc = P.layers[F.n_conv - 1];
-    const LayerDev& L = P.layers[F.n_conv];
+    const LayerDev& Lc = rt.sh->L[F.n_conv - 1];
+    const LayerDev& L = rt.sh->L[F.n_conv];
     const int HW = Lc.Hp * Lc.Wp, n1 = L.n_out;
     const int nm = n_mine(Lc.Mo, rank, G);
     float* wc = lds + F.fc[0].o_w;
@@ -173,21 +283,20 @@ __device__ void flow_load(const Rt& rt) {
     for (int k = tid; k < n1; k += WG) lds[F.fc[0].o_b + k] = L.bias[k];
   }
   for (int f = 1; f < F.n_fc; ++f) {
-    const LayerDev& L = P.layers[F.n_conv + f];
+    const LayerDev& L = rt.sh->L[F.n_conv + f];
     for (int x = tid; x < L.n_out * L.n_in; x += WG) lds[F.fc[f].o_w + x] = L.w[x];
     for (int k = tid; k < L.n_out; k += WG) lds[F.fc[f].o_b + k] = L.bias[k];
   }
   __syncthreads();
 }
 
-__device__ void flow_store(const Rt& rt) {
-  const ProgramDev& P = *rt.P;
-  const FlowDev& F = *rt.F;
+__device__ __forceinline__ void flow_store(const Rt& rt) {
+  const FlowDev& F = rt.sh->F;
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = F.G, rank = rt.rank;
   __syncthreads();
   for (int l = 0; l < F.n_conv; ++l) {
-    const LayerDev& L = P.layers[l];
+    const LayerDev& L = rt.sh->L[l];
     const FlowConv& C = F.conv[l];
     const int KK = L.K * L.K;
     const int nm = n_mine(L.Mo, rank, G);
@@ -201,8 +310,8 @@ __device__ void flow_store(const Rt& rt) {
     }
   }
   {
-    const LayerDev& Lc = P.layers[F.n_conv - 1];
-    const LayerDev& L = P.layers[F.n_conv];
+    const LayerDev& Lc = rt.sh->L[F.n_conv - 1];
+    const LayerDev& L = rt.sh->L[F.n_conv];
     const int HW = Lc.Hp * Lc.Wp, n1 = L.n_out;
     const int nm = n_mine(Lc.Mo, rank, G);
     for (int x = tid; x < nm * HW * n1; x += WG) {
@@ -215,22 +324,24 @@ __device__ void flow_store(const Rt& rt) {
   }
   if (rank == 0)
     for (int f = 1; f < F.n_fc; ++f) {
-      const LayerDev& L = P.layers[F.n_conv + f];
+      const LayerDev& L = rt.sh->L[F.n_conv + f];
       for (int x = tid; x < L.n_out * L.n_in; x += WG) L.w[x] = lds[F.fc[f].o_w + x];
       for (int k = tid; k < L.n_out; k += WG) L.bias[k] = lds[F.fc[f].o_b + k];
     }
 }
 
-// ---- FP of one own map (Sec. 2.2, Sec. 3.2): inputs, filters and index list all in LDS ------------
+// ---- the two multiply-accumulate loops -------------------------------------------------------------
+// One output pixel: sum over the connections c0, c0 + cstep, ... < nc and the K x K taps.  Map
+// of connection c is idx[c] - idx_off.  Any K (KT = 0: run-time size).
 template <int KT>
-__device__ __forceinline__ float conv_acc(const float* in, const float* wf, const int* cidx, int c0, int cstep,
-                                          int nc, int HiWi, int Wi, int Krt, int base) {
+__device__ __forceinline__ float pixel_mac(const float* in, const float* w, const int* idx, int idx_off, int c0,
+                                           int cstep, int nc, int map_sz, int Wi, int Krt, int base) {
   const int K = KT ? KT : Krt;
   const int KK = K * K;
   float acc = 0.f;
   for (int c = c0; c < nc; c += cstep) {
-    const float* ip = in + cidx[c] * HiWi + base;
-    const float* wp = wf + c * KK;
+    const float* ip = in + (idx[c] - idx_off) * map_sz + base;
+    const float* wp = w + c * KK;
 #pragma unroll
     for (int ky = 0; ky < K; ++ky)
 #pragma unroll
@@ -238,62 +349,204 @@ __device__ __forceinline__ float conv_acc(const float* in, const float* wf, cons
   }
   return acc;
 }
-__device__ __forceinline__ float conv_acc_k(int K, const float* in, const float* wf, const int* cidx, int c0,
-                                            int cstep, int nc, int HiWi, int Wi, int base) {
+__device__ __forceinline__ float pixel_mac_k(int K, const float* in, const float* w, const int* idx, int idx_off,
+                                             int c0, int cstep, int nc, int map_sz, int Wi, int base) {
   switch (K) {
-    case 2: return conv_acc<2>(in, wf, cidx, c0, cstep, nc, HiWi, Wi, K, base);
-    case 3: return conv_acc<3>(in, wf, cidx, c0, cstep, nc, HiWi, Wi, K, base);
-    case 4: return conv_acc<4>(in, wf, cidx, c0, cstep, nc, HiWi, Wi, K, base);
-    case 5: return conv_acc<5>(in, wf, cidx, c0, cstep, nc, HiWi, Wi, K, base);
-    default: return conv_acc<0>(in, wf, cidx, c0, cstep, nc, HiWi, Wi, K, base);
+    case 1: return pixel_mac<1>(in, w, idx, idx_off, c0, cstep, nc, map_sz, Wi, K, base);
+    case 2: return pixel_mac<2>(in, w, idx, idx_off, c0, cstep, nc, map_sz, Wi, K, base);
+    case 3: return pixel_mac<3>(in, w, idx, idx_off, c0, cstep, nc, map_sz, Wi, K, base);
+    case 4: return pixel_mac<4>(in, w, idx, idx_off, c0, cstep, nc, map_sz, Wi, K, base);
+    case 5: return pixel_mac<5>(in, w, idx, idx_off, c0, cstep, nc, map_sz, Wi, K, base);
+    default: return pixel_mac<0>(in, w, idx, idx_off, c0, cstep, nc, map_sz, Wi, K, base);
   }
 }
 
-// act[p] = A tanh(B (bias + sum over connections and taps)) for every pixel p of the map.  Maps
-// with at most WG/2 pixels split the connections over the spare lanes and add the partial sums
-// in a fixed order.
-__device__ void flow_conv_fwd_map(const LayerDev& L, const float* in, const float* wf, const int* cidx, int nc,
-                                  float bias, float* act, float* part) {
-  const int tid = threadIdx.x;
-  const int Wo = L.Wo, Wi = L.Wi, HiWi = L.Hi * L.Wi, stride = L.S + 1;
-  const int Pn = L.Ho * Wo;
-  if (2 * Pn <= WG) {
-    const int R = WG / Pn;
-    const int r = tid / Pn, p = tid - r * Pn;
-    float acc = 0.f;
-    if (r < R) {
-      const int y = p / Wo, x = p - y * Wo;
-      acc = conv_acc_k(L.K, in, wf, cidx, r, R, nc, HiWi, Wi, (y * Wi + x) * stride);
-    }
-    part[tid] = acc;
-    __syncthreads();
-    if (tid < Pn) {
-      float s = 0.f;
-      for (int rr = 0; rr < R; ++rr) s += part[rr * Pn + tid];
-      act[tid] = f_act(s + bias);
-    }
-  } else {
-    for (int p = tid; p < Pn; p += WG) {
-      const int y = p / Wo, x = p - y * Wo;
-      const float acc = conv_acc_k(L.K, in, wf, cidx, 0, 1, nc, HiWi, Wi, (y * Wi + x) * stride);
-      act[p] = f_act(acc + bias);
+// SW consecutive output pixels of one row (unit stride): per connection and kernel row, SW+K-1
+// inputs and K weights are read once and feed SW*K multiply-adds.
+template <int K, int SW>
+__device__ __forceinline__ void strip_mac(const float* in, const float* w, const int* idx, int idx_off, int c0,
+                                          int cstep, int nc, int map_sz, int Wi, int base, float (&acc)[SW]) {
+  for (int c = c0; c < nc; c += cstep) {
+    const float* ip = in + (idx[c] - idx_off) * map_sz + base;
+    const float* wp = w + c * (K * K);
+#pragma unroll
+    for (int ky = 0; ky < K; ++ky) {
+      float row[SW + K - 1];
+#pragma unroll
+      for (int i = 0; i < SW + K - 1; ++i) row[i] = ip[ky * Wi + i];
+      float wk[K];
+#pragma unroll
+      for (int kx = 0; kx < K; ++kx) wk[kx] = wp[ky * K + kx];
+#pragma unroll
+      for (int s = 0; s < SW; ++s)
+#pragma unroll
+        for (int kx = 0; kx < K; ++kx) acc[s] = fmaf(wk[kx], row[s + kx], acc[s]);
     }
   }
+}
+
+// A correlation job: n_maps output maps of Ho x Wo, each the sum over its connection list of
+// K x K correlations (unit stride for the strip form) of input maps of map_sz floats and row
+// pitch Wi.  Lanes take (map, row, strip of SW pixels) units, or (map, pixel) units when SW = 0,
+// and share the connections R ways when there are fewer units than lanes; partial sums go to
+// part[(r * n_maps + map) * Ho*Wo + pixel].  The chunk interface (first / last) lets the pull
+// accumulate over several passes with the inputs rebuilt in between.
+struct Corr {
+  const float* in;     // [..][map_sz]
+  const float* w;      // [n_maps][w_pitch][K*K]
+  const int* idx;      // [n_maps][w_pitch] input map of every connection
+  const int* cnt;      // [n_maps] connections of every map
+  int n_maps, w_pitch, Ho, Wo, K, stride, map_sz, Wi;
+  int max_cnt;
+};
+
+template <int K, int SW>
+struct StripJob {
+  const Corr J;
+  int NS, U, R, r, am, pix0, base, ncols;
+  bool on;
+  float acc[SW];
+  __device__ __forceinline__ StripJob(const Corr& j, int pass) : J(j) {
+    NS = (J.Wo + SW - 1) / SW;
+    U = J.n_maps * J.Ho * NS;
+    R = (U >= WG) ? 1 : max(1, min(WG / U, J.max_cnt));
+    const int u = pass * WG + (int)threadIdx.x;
+    on = u < U * R;
+    const FDiv dU(U), dNS(NS), dHo(J.Ho);
+    r = dU.div(u);
+    const int v = u - r * U;
+    const int row = dNS.div(v), s = v - row * NS;
+    am = dHo.div(row);
+    const int y = row - am * J.Ho, x0 = s * SW;
+    if (!on) { r = 0; am = 0; }
+    pix0 = y * J.Wo + x0;
+    ncols = min(SW, J.Wo - x0);
+    base = on ? y * J.Wi + x0 : 0;
+#pragma unroll
+    for (int i = 0; i < SW; ++i) acc[i] = 0.f;
+  }
+  __device__ __forceinline__ int passes() const { return (U * R + WG - 1) / WG; }
+  // connections [e_lo, e_hi) of the lane's map, maps numbered from idx_off
+  __device__ __forceinline__ void run(int e_lo, int e_hi, int idx_off) {
+    if (on)
+      strip_mac<K, SW>(J.in, J.w + (am * J.w_pitch) * (K * K), J.idx + am * J.w_pitch, idx_off, e_lo + r, R, e_hi,
+                       J.map_sz, J.Wi, base, acc);
+  }
+  __device__ __forceinline__ void store(float* part) const {
+    if (on) {
+      float* dst = part + (r * J.n_maps + am) * (J.Ho * J.Wo) + pix0;
+#pragma unroll
+      for (int i = 0; i < SW; ++i)
+        if (i < ncols) dst[i] = acc[i];
+    }
+  }
+};
+
+struct PixelJob {
+  const Corr J;
+  int U, R, r, am, p, base;
+  bool on;
+  float acc;
+  __device__ __forceinline__ PixelJob(const Corr& j, int pass) : J(j) {
+    const int Pn = J.Ho * J.Wo;
+    U = J.n_maps * Pn;
+    R = (U >= WG) ? 1 : max(1, min(WG / U, J.max_cnt));
+    const int u = pass * WG + (int)threadIdx.x;
+    on = u < U * R;
+    const FDiv dU(U), dP(Pn), dW(J.Wo);
+    r = dU.div(u);
+    const int v = u - r * U;
+    am = dP.div(v);
+    p = v - am * Pn;
+    const int y = dW.div(p), x = p - y * J.Wo;
+    if (!on) { r = 0; am = 0; p = 0; }
+    base = on ? (y * J.Wi + x) * J.stride : 0;
+    acc = 0.f;
+  }
+  __device__ __forceinline__ int passes() const { return (U * R + WG - 1) / WG; }
+  __device__ __forceinline__ void run(int e_lo, int e_hi, int idx_off) {
+    if (on)
+      acc += pixel_mac_k(J.K, J.in, J.w + (am * J.w_pitch) * (J.K * J.K), J.idx + am * J.w_pitch, idx_off, e_lo + r, R,
+                         e_hi, J.map_sz, J.Wi, base);
+  }
+  __device__ __forceinline__ void store(float* part) const {
+    if (on) part[(r * J.n_maps + am) * (J.Ho * J.Wo) + p] = acc;
+  }
+};
+
+// ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
+template <class Job>
+__device__ __forceinline__ int fwd_run(const Corr& J, float* part, const Rt& rt) {
+  int R = 1;
+  const int passes = Job(J, 0).passes();
+  for (int pass = 0; pass < passes; ++pass) {
+    Job job(J, pass);
+    R = job.R;
+    DSTAMP(114);
+    if (job.on) job.run(0, J.cnt[job.am], 0);
+    job.store(part);
+  }
+  return R;
+}
+
+__device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l, int nm) {
+  const FlowDev& F = rt.sh->F;
+  const LayerDev& L = rt.sh->L[l];
+  const FlowConv& C = F.conv[l];
+  float* lds = rt.lds;
+  const int tid = threadIdx.x;
+  Corr J;
+  J.in = lds + C.o_in;
+  J.w = lds + C.o_wf;
+  J.idx = (const int*)(lds + C.o_cidx);
+  J.cnt = (const int*)(lds + C.o_ncf);
+  J.n_maps = nm; J.w_pitch = uni(L.max_conn); J.Ho = uni(L.Ho); J.Wo = uni(L.Wo); J.K = uni(L.K);
+  J.stride = uni(L.S) + 1; J.map_sz = uni(L.Hi) * uni(L.Wi); J.Wi = uni(L.Wi); J.max_cnt = J.w_pitch;
+  float* part = lds + F.o_part;
+  int R = 1;
+  if (l == 1) DSTAMP(110);
+  switch (uni(C.fwd_strip) * 8 + J.K) {
+#define FWD_CASE(SW, KK_) case SW * 8 + KK_: R = fwd_run<StripJob<KK_, SW>>(J, part, rt); break;
+    FWD_CASE(4, 2) FWD_CASE(4, 3) FWD_CASE(4, 4) FWD_CASE(4, 5)
+    FWD_CASE(5, 2) FWD_CASE(5, 3) FWD_CASE(5, 4) FWD_CASE(5, 5)
+    FWD_CASE(7, 2) FWD_CASE(7, 3) FWD_CASE(7, 4) FWD_CASE(7, 5)
+#undef FWD_CASE
+    default: R = fwd_run<PixelJob>(J, part, rt); break;
+  }
+  DSTAMP(100 + 4 * l);
   __syncthreads();
+  DSTAMP(101 + 4 * l);
+  const int Pn = J.Ho * J.Wo, tot = nm * Pn;
+  const FDiv dP(Pn);
+  float* act = lds + F.o_act;
+  const float* bf = lds + C.o_bf;
+  for (int p = tid; p < tot; p += WG) {
+    const float s = sum_strided(part, R, tot, p);
+    act[p] = f_act(s + bf[dP.div(p)]);
+  }
+  DSTAMP(102 + 4 * l);
+  __syncthreads();
+  DSTAMP(103 + 4 * l);
 }
 
-// Max-pooling of one own map (Sec. 2.3): value and position of the first maximum in row-major
+// Max-pooling of the own maps (Sec. 2.3): value and position of the first maximum in row-major
 // order; the pooled value is what the next layer reads, so it is published at once.
-__device__ void flow_pool_map(const LayerDev& L, const FlowConv& C, float* lds, int a, int j, const float* act,
-                              unsigned int tag, bool taps) {
-  const int tid = threadIdx.x;
-  const int Kp = L.Kp, Wo = L.Wo, Wp = L.Wp, HW = L.Hp * L.Wp;
-  float* pool = lds + C.o_pool + a * HW;
-  int* yx = (int*)(lds + C.o_yx) + a * HW;
-  gtagged* xo = C.x_out ? C.x_out + (size_t)(tag & 1u) * L.Mo * HW + (size_t)j * HW : nullptr;
-  for (int q = tid; q < HW; q += WG) {
-    const int py = q / Wp, px = q - py * Wp;
-    const float* win = act + py * Kp * Wo + px * Kp;
+__device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned int tag, bool taps) {
+  const FlowDev& F = rt.sh->F;
+  const LayerDev& L = rt.sh->L[l];
+  const FlowConv& C = F.conv[l];
+  float* lds = rt.lds;
+  const int tid = threadIdx.x, G = F.G, rank = rt.rank;
+  const int Kp = L.Kp, Wo = L.Wo, Wp = L.Wp, HW = L.Hp * L.Wp, Pn = L.Ho * L.Wo;
+  const float* act = lds + F.o_act;
+  float* pool = lds + C.o_pool;
+  int* yx = (int*)(lds + C.o_yx);
+  gtagged* xo = C.x_out ? C.x_out + (size_t)(tag & 1u) * L.Mo * HW : nullptr;
+  const FDiv dHW(HW), dWp(Wp);
+  for (int x = tid; x < nm * HW; x += WG) {
+    const int am = dHW.div(x), q = x - am * HW;
+    const int py = dWp.div(q), px = q - py * Wp;
+    const float* win = act + am * Pn + py * Kp * Wo + px * Kp;
     float best = win[0];
     int wy = 0, wx = 0;
     for (int dy = 0; dy < Kp; ++dy)
@@ -302,18 +555,23 @@ __device__ void flow_pool_map(const LayerDev& L, const FlowConv& C, float* lds, 
         if (v > best) { best = v; wy = dy; wx = dx; }
       }
     const int code = ((py * Kp + wy) << 16) | (px * Kp + wx);
-    pool[q] = best;
-    yx[q] = code;
-    if (xo) put_f(xo + q, best, tag);
+    pool[x] = best;
+    yx[x] = code;
+    const size_t o = (size_t)(rank + am * G) * HW + q;
+    if (xo) put_f(xo + o, best, tag);
     if (taps) {
-      const size_t o = (size_t)j * HW + q;
       if (Kp > 1) L.out[o] = best;
       L.arg[o] = (uint8_t)(wy * Kp + wx);
       L.argyx[o] = code;
     }
   }
-  if (taps)
-    for (int p = tid; p < L.Ho * Wo; p += WG) L.act[(size_t)j * L.Ho * Wo + p] = act[p];
+  if (taps) {
+    const FDiv dP(Pn);
+    for (int x = tid; x < nm * Pn; x += WG) {
+      const int am = dP.div(x), p = x - am * Pn;
+      L.act[(size_t)(rank + am * G) * Pn + p] = act[x];
+    }
+  }
   __syncthreads();
 }
 
@@ -345,12 +603,23 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
     if (wi < n_w) {
       I = info(wi);
       if (I.ok)
-        for (int q = rr; q < HW; q += R) {
-          const int yx = I.yx[q];
-          s = fmaf(I.d[q], I.in[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
+        for (int q0 = rr; q0 < HW; q0 += 4 * R) {
+          int yx[4];
+          float dv[4], iv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int q = min(q0 + u * R, HW - 1);
+            yx[u] = I.yx[q];
+            dv[u] = I.d[q];
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) iv[u] = I.in[((yx[u] >> 16) * Wi + (yx[u] & 0xffff)) * stride];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (q0 + u * R < HW) s = fmaf(dv[u], iv[u], s);
         }
     }
-    for (int off = R >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    s = group_sum(s, Rl2);
     if (I.ok && rr == 0) {
       if (g_out) g_out[I.canon] = s;
       else w[wi] = fmaf(-lr, s, w[wi]);
@@ -358,114 +627,102 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
   }
 }
 
-// ---- BP through a convolutional layer, pull form (Sec. 3.3), for one own input map -------------------
-template <int KT>
-__device__ __forceinline__ float pull_acc(const float* dd, const float* wb, int c0, int cstep, int n, int HWd,
-                                          const int (&yo)[5], const int (&xo)[5], float acc) {
-  for (int c = c0; c < n; c += cstep) {
-    const float* dp = dd + c * HWd;
-    const float* wp = wb + c * (KT * KT);
-#pragma unroll
-    for (int ky = 0; ky < KT; ++ky)
-#pragma unroll
-      for (int kx = 0; kx < KT; ++kx) acc = fmaf(dp[yo[ky] + xo[kx]], wp[ky * KT + kx], acc);
-  }
-  return acc;
-}
-
+// ---- BP through a convolutional layer, pull form (Sec. 3.3), for the own input maps ------------------
 // Neuron (r, c) of input map i collects, over every output map j that reads map i, the deltas of
 // the output neurons whose receptive field covers it (the four inequalities of Sec. 3.3), each
-// times its weight (old value).  The deltas of a chunk of output maps are rebuilt at full
-// resolution in LDS with one extra row and column of zeros (only pooling winners are non-zero),
-// so a tap that has no output neuron reads a zero and the inner loop has no branches.
-// out[p] = pulled sum * f'(y[p]).
-__device__ void flow_pull_map(const Rt& rt, const LayerDev& L, const FlowConv& C, int a, int ne, const float* dall,
-                              const int* yxall, const float* ybelow, float* out) {
-  const FlowDev& F = *rt.F;
+// times its weight (old value).  Written as FP's mirror image: the deltas of a chunk of output
+// maps are put at their places (y (S+1) + K-1, x (S+1) + K-1) in maps of (Hi+K-1) x (Wi+K-1) zeros
+// -- only pooling winners are non-zero -- and correlated with the filters rotated by 180 degrees;
+// a tap that has no output neuron then meets a zero and the loop has no branches.  The zero maps
+// are kept zero between uses: after a chunk the winners' places are cleared again.
+// delta_below[p] = pulled sum * f'(y_below[p]).
+template <class Job>
+__device__ __forceinline__ void pull_run(const Rt& rt, const LayerDev& L, const FlowConv& C, const Corr& J,
+                                         const float* dall, const int* yxall, int nb, float* part, int& R_out) {
+  const FlowDev& F = rt.sh->F;
+  float* dd = rt.lds + F.o_scratch;
+  const int tid = threadIdx.x;
+  const int Mo = uni(L.Mo), HW = uni(L.Hp) * uni(L.Wp), stride = uni(L.S) + 1, Km1 = uni(L.K) - 1;
+  const int Wd = J.Wi, HWd = J.map_sz;
+  const int chunk = uni(C.pull_chunk);
+  const bool full = uni(L.full_table) != 0;
+  const FDiv dHW(HW);
+  const int passes = Job(J, 0).passes();
+  for (int pass = 0; pass < passes; ++pass) {
+    Job job(J, pass);
+    R_out = job.R;
+    for (int j0 = 0; j0 < Mo; j0 += chunk) {
+      const int n = min(chunk, Mo - j0);
+      for (int x = tid; x < n * HW; x += WG) {
+        const int c = dHW.div(x), q = x - c * HW;
+        const int yx = yxall[(j0 + c) * HW + q];
+        dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
+      }
+      __syncthreads();
+      if (job.on) {
+        // entries of the lane's input map whose output map lies in [j0, j0 + n)
+        int e_lo = j0, e_hi = j0 + n;
+        if (!full) {
+          const int* bj = J.idx + job.am * J.w_pitch;
+          const int ne = J.cnt[job.am];
+          e_lo = 0;
+          while (e_lo < ne && bj[e_lo] < j0) ++e_lo;
+          e_hi = e_lo;
+          while (e_hi < ne && bj[e_hi] < j0 + n) ++e_hi;
+        }
+        job.run(e_lo, e_hi, j0);
+      }
+      __syncthreads();
+      for (int x = tid; x < n * HW; x += WG) {
+        const int c = dHW.div(x), q = x - c * HW;
+        const int yx = yxall[(j0 + c) * HW + q];
+        dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = 0.f;
+      }
+      __syncthreads();
+    }
+    job.store(part);
+  }
+  (void)nb;
+}
+
+__device__ __forceinline__ void flow_pull(const Rt& rt, int l, int nb, const float* dall, const int* yxall) {
+  const FlowDev& F = rt.sh->F;
+  const LayerDev& L = rt.sh->L[l];
+  const FlowConv& C = F.conv[l];
+  const FlowConv& Cb = F.conv[l - 1];
   float* lds = rt.lds;
   const int tid = threadIdx.x;
-  const int K = L.K, KK = K * K, stride = L.S + 1;
-  const int Wi = L.Wi, Pin = L.Hi * L.Wi;
-  const int Ho = L.Ho, Wo = L.Wo, HW = L.Hp * L.Wp;
-  const int Wd = Wo + 1, HWd = (Ho + 1) * Wd;
-  float* dd = lds + F.o_scratch;
+  const int K = uni(L.K), Hi = uni(L.Hi), Wi = uni(L.Wi);
+  Corr J;
+  J.in = lds + F.o_scratch;
+  J.w = lds + C.o_wb;
+  J.idx = (const int*)(lds + C.o_bj);
+  J.cnt = (const int*)(lds + C.o_ncb);
+  J.n_maps = nb; J.w_pitch = uni(C.max_back); J.Ho = Hi; J.Wo = Wi; J.K = K; J.stride = 1;
+  J.Wi = Wi + K - 1; J.map_sz = (Hi + K - 1) * (Wi + K - 1); J.max_cnt = min(J.w_pitch, uni(C.pull_chunk));
   float* part = lds + F.o_part;
-  const float* wb = lds + C.o_wb + a * C.max_back * KK;
-  const int* bj = (const int*)(lds + C.o_bj) + a * C.max_back;
-  const bool split = 2 * Pin <= WG;
-  const int R = split ? WG / Pin : 1;
-  const int PB = split ? Pin : WG;
-  for (int p0 = 0; p0 < Pin; p0 += PB) {
-    const int r = split ? tid / Pin : 0;
-    const int p = split ? tid - r * Pin : p0 + tid;
-    const bool on = r < R && p < Pin;
-    const int pr = p / Wi, pc = p - pr * Wi;
-    auto row_off = [&](int ky) {
-      const int ry = pr - ky;
-      const int y = ry / stride;
-      const bool ok = on && ry >= 0 && ry - y * stride == 0 && y < Ho;
-      return (ok ? y : Ho) * Wd;
-    };
-    auto col_off = [&](int kx) {
-      const int rx = pc - kx;
-      const int x = rx / stride;
-      const bool ok = on && rx >= 0 && rx - x * stride == 0 && x < Wo;
-      return ok ? x : Wo;
-    };
-    int yo[5], xo[5];
-#pragma unroll
-    for (int k = 0; k < 5; ++k) { yo[k] = row_off(k); xo[k] = col_off(k); }
-    float acc = 0.f;
-    for (int e0 = 0; e0 < ne; e0 += C.pull_chunk) {
-      const int n = min(C.pull_chunk, ne - e0);
-      for (int idx = tid; idx < n * HWd; idx += WG) dd[idx] = 0.f;
-      __syncthreads();
-      for (int idx = tid; idx < n * HW; idx += WG) {
-        const int c = idx / HW, q = idx - c * HW;
-        const int j = bj[e0 + c];
-        const int yx = yxall[j * HW + q];
-        dd[c * HWd + (yx >> 16) * Wd + (yx & 0xffff)] = dall[j * HW + q];
-      }
-      __syncthreads();
-      const float* wbc = wb + e0 * KK;
-      const int c0 = min(r, R - 1);
-      switch (K) {
-        case 1: acc = pull_acc<1>(dd, wbc, c0, R, n, HWd, yo, xo, acc); break;
-        case 2: acc = pull_acc<2>(dd, wbc, c0, R, n, HWd, yo, xo, acc); break;
-        case 3: acc = pull_acc<3>(dd, wbc, c0, R, n, HWd, yo, xo, acc); break;
-        case 4: acc = pull_acc<4>(dd, wbc, c0, R, n, HWd, yo, xo, acc); break;
-        case 5: acc = pull_acc<5>(dd, wbc, c0, R, n, HWd, yo, xo, acc); break;
-        default:
-          for (int c = c0; c < n; c += R) {
-            const float* dp = dd + c * HWd;
-            const float* wp = wbc + c * KK;
-            for (int ky = 0; ky < K; ++ky) {
-              const int ro = row_off(ky);
-              for (int kx = 0; kx < K; ++kx) acc = fmaf(dp[ro + col_off(kx)], wp[ky * K + kx], acc);
-            }
-          }
-          break;
-      }
-      __syncthreads();
-    }
-    if (split) {
-      part[tid] = (r < R) ? acc : 0.f;
-      __syncthreads();
-      if (tid < Pin) {
-        float s = 0.f;
-        for (int rr = 0; rr < R; ++rr) s += part[rr * Pin + tid];
-        out[tid] = s * f_dact(ybelow[tid]);
-      }
-      __syncthreads();
-    } else if (on) {
-      out[p] = acc * f_dact(ybelow[p]);
-    }
+  int R = 1;
+  switch (uni(C.pull_strip) * 8 + K) {
+#define PULL_CASE(SW, KK_) case SW * 8 + KK_: pull_run<StripJob<KK_, SW>>(rt, L, C, J, dall, yxall, nb, part, R); break;
+    PULL_CASE(4, 2) PULL_CASE(4, 3) PULL_CASE(4, 4) PULL_CASE(4, 5)
+    PULL_CASE(5, 2) PULL_CASE(5, 3) PULL_CASE(5, 4) PULL_CASE(5, 5)
+    PULL_CASE(7, 2) PULL_CASE(7, 3) PULL_CASE(7, 4) PULL_CASE(7, 5)
+#undef PULL_CASE
+    default: pull_run<PixelJob>(rt, L, C, J, dall, yxall, nb, part, R); break;
+  }
+  __syncthreads();
+  const int tot = nb * Hi * Wi;
+  const float* ybelow = lds + Cb.o_pool;
+  float* dbelow = lds + Cb.o_delta;
+  for (int p = tid; p < tot; p += WG) {
+    const float s = sum_strided(part, R, tot, p);
+    dbelow[p] = s * f_dact(ybelow[p]);
   }
   __syncthreads();
 }
 
 // y[k] = b[k] + sum_m W[k][m] v[m], all in LDS; lane groups of a power of two per row.
-__device__ void flow_matvec(const float* W, const float* b, const float* v, float* y, int n_out, int n_in) {
+__device__ __forceinline__ void flow_matvec(const float* W, const float* b, const float* v, float* y, int n_out, int n_in) {
   const int tid = threadIdx.x;
   int lpl = 6;
   while (lpl > 0 && (WG >> lpl) < n_out) --lpl;
@@ -478,43 +735,95 @@ __device__ void flow_matvec(const float* W, const float* b, const float* v, floa
       const float* wr = W + k * n_in;
       for (int m = sub; m < n_in; m += lpr) s = fmaf(wr[m], v[m], s);
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
-      if (off < lpr) s += __shfl_xor(s, off, 64);
+    s = group_sum(s, lpl);
     if (sub == 0 && k < n_out) y[k] = s + b[k];
   }
   __syncthreads();
 }
 
+// Sum over the ranks of the partial sums of the first fully connected layer, every rank in the
+// same order: lane (k, part) adds the ranks of its part one after the other as their words
+// arrive, the parts are then added in order.  y[k] = b[k] + sum.
+__device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged* xp, int NR, int n1, const float* b, float* y,
+                                     float* part, unsigned int tag) {
+  const int tid = threadIdx.x;
+  const int parts = max(1, min(WG / max(n1, 1), NR));
+  const int per = (NR + parts - 1) / parts;
+  constexpr int U = 8;
+  const FDiv dN(n1);
+  for (int k0 = 0; k0 < n1; k0 += WG) {
+    const int pi = dN.div(tid), k = k0 + tid - pi * n1;
+    const bool on = pi < parts && k < n1;
+    if (on) {
+      const int r_lo = pi * per, r_hi = min(NR, r_lo + per);
+      float s = 0.f;
+      for (int r0 = r_lo; r0 < r_hi; r0 += U) {
+        tagged_t w[U];
+        unsigned int spins = 0;
+        while (true) {
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            w[u] = __hip_atomic_load(xp + (size_t)min(r0 + u, r_hi - 1) * n1 + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          bool done = true;
+#pragma unroll
+          for (int u = 0; u < U; ++u) done = done && ((unsigned int)(w[u] >> 32) == tag);
+          if (done || !poll_again(rt, spins)) break;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (r0 + u < r_hi) s += __uint_as_float((unsigned int)w[u]);
+      }
+      part[pi * n1 + (k - k0)] = s;
+    }
+    __syncthreads();
+    if (tid < n1 - k0 && tid < WG) {
+      y[k0 + tid] = b[k0 + tid] + sum_strided(part, parts, n1, tid);
+    }
+    __syncthreads();
+    if (n1 <= WG) break;
+  }
+  return rt.sh->fail == 0;
+}
+
 #define STAMP(i)                                                                              \
   do {                                                                                        \
-    if (stamp) rt.status->stamps[i] = wall_clock64();                                         \
+    if (stamp) status->stamps[i] = wall_clock64();                                            \
   } while (0)
 
 __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ Pp, const FlowDev* __restrict__ Fp,
                                                  StatusDev* status, RunArgs a) {
   extern __shared__ float lds[];
-  __shared__ int s_fail;
-  const FlowDev& F = *Fp;
-  const ProgramDev& P = *Pp;
-  if (blockIdx.x % F.stride != 0) return;
-  const int rank = blockIdx.x / F.stride;
-  if (rank >= F.G) return;
-  const int tid = threadIdx.x, G = F.G;
-  if (tid == 0) s_fail = 0;
+  __shared__ Shared sh;
+  const int tid = threadIdx.x;
+  {
+    const int stride = Fp->stride, G0 = Fp->G;
+    if (blockIdx.x % stride != 0 || (int)(blockIdx.x / stride) >= G0) return;
+    const int n_layers = Fp->n_conv + Fp->n_fc;
+    const unsigned int* src = (const unsigned int*)Fp;
+    unsigned int* dst = (unsigned int*)&sh.F;
+    for (int i = tid; i < (int)(sizeof(FlowDev) / 4); i += WG) dst[i] = src[i];
+    src = (const unsigned int*)&Pp->layers[0];
+    dst = (unsigned int*)&sh.L[0];
+    for (int i = tid; i < n_layers * (int)(sizeof(LayerDev) / 4); i += WG) dst[i] = src[i];
+    if (tid == 0) sh.fail = 0;
+    __syncthreads();
+  }
+  const FlowDev& F = sh.F;
+  const int G = uni(F.G);
+  const int rank = blockIdx.x / uni(F.stride);
   Rt rt;
-  rt.P = Pp; rt.F = Fp; rt.status = status; rt.lds = lds; rt.s_fail = &s_fail; rt.rank = rank;
-  rt.spin_limit = a.spin_limit;
+  rt.sh = &sh; rt.status = status; rt.lds = lds; rt.rank = rank; rt.spin_limit = a.spin_limit;
+  rt.dbg = false;
   flow_load(rt);
 
-  const int n_conv = F.n_conv, n_fc = F.n_fc;
-  const LayerDev& Lc = P.layers[n_conv - 1];       // last convolutional layer
-  const LayerDev& L1 = P.layers[n_conv];           // first fully connected layer
-  const int HWc = Lc.Hp * Lc.Wp;
-  const int ncols = n_mine(Lc.Mo, rank, G) * HWc;  // own columns of the first fully connected layer
-  const int n1 = L1.n_out;
+  const int n_conv = uni(F.n_conv), n_fc = uni(F.n_fc), n_classes = Pp->n_classes;
+  const LayerDev& Lc = sh.L[n_conv - 1];           // last convolutional layer
+  const LayerDev& L1 = sh.L[n_conv];               // first fully connected layer
+  const int HWc = uni(Lc.Hp) * uni(Lc.Wp);
+  const int ncols = n_mine(uni(Lc.Mo), rank, G) * HWc;  // own columns of the first fully connected layer
+  const int n1 = uni(L1.n_out);
+  const int NR = uni(F.n_col_ranks);
   float* part = lds + F.o_part;
-  float* act = lds + F.o_act;
   gfloat* g_out = a.grad_out;
   const float lr = a.lr;
 
@@ -523,16 +832,17 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     const unsigned int par = tag & 1u;
     const bool taps = (t == a.n_images - 1);
     const bool stamp = taps && rank == 0 && tid == 0;
-    int label = a.labels ? a.labels[t] : a.label_imm;
+    rt.dbg = stamp;
+    const int label = a.labels ? a.labels[t] : a.label_imm;
     bool train = a.train != 0;
-    if (train && (label < 0 || label >= P.n_classes)) {
+    if (train && (label < 0 || label >= n_classes)) {
       train = false;
       if (rank == 0 && tid == 0) status->bad_label = 1u;
     }
     STAMP(0);
     {  // the image
       const gfloat* img = a.images + t * a.image_stride;
-      const LayerDev& L = P.layers[0];
+      const LayerDev& L = sh.L[0];
       const int n = L.Mi * L.Hi * L.Wi;
       float* in = lds + F.conv[0].o_in;
       for (int x = tid; x < n; x += WG) in[x] = img[x];
@@ -541,20 +851,17 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     STAMP(1);
     // ---- FP, convolutional layers ----
     for (int l = 0; l < n_conv; ++l) {
-      const LayerDev& L = P.layers[l];
+      const LayerDev& L = sh.L[l];
       const FlowConv& C = F.conv[l];
-      const int KK = L.K * L.K;
       if (l >= 1) {
         const int nw = L.Mi * L.Hi * L.Wi;
         if (!gather(rt, (unsigned int*)(lds + C.o_in), F.conv[l - 1].x_out + (size_t)par * nw, nw, tag)) return;
       }
       STAMP(2 + 2 * l);
-      const int nm = n_mine(L.Mo, rank, G);
-      for (int am = 0; am < nm; ++am) {
-        flow_conv_fwd_map(L, lds + C.o_in, lds + C.o_wf + am * L.max_conn * KK,
-                          (const int*)(lds + C.o_cidx) + am * L.max_conn, ((const int*)(lds + C.o_ncf))[am],
-                          lds[C.o_bf + am], act, part);
-        flow_pool_map(L, C, lds, am, rank + am * G, act, tag, taps);
+      const int nm = n_mine(uni(L.Mo), rank, G);
+      if (nm > 0) {
+        flow_conv_fwd(rt, l, nm);
+        flow_pool(rt, l, nm, tag, taps);
       }
       STAMP(3 + 2 * l);
     }
@@ -562,30 +869,37 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     {
       const float* wc = lds + F.fc[0].o_w;
       const float* vcol = lds + F.conv[n_conv - 1].o_pool;
-      if (rank < F.n_col_ranks) {
-        gtagged* xp = F.xp + ((size_t)par * F.n_col_ranks + rank) * n1;
+      if (rank < NR) {
+        gtagged* xp = F.xp + ((size_t)par * NR + rank) * n1;
         for (int k = tid; k < n1; k += WG) {
           float s = 0.f;
-          for (int c = 0; c < ncols; ++c) s = fmaf(wc[c * n1 + k], vcol[c], s);
+          for (int c0 = 0; c0 < ncols; c0 += 8) {
+            float wv[8], vv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              const int c = min(c0 + u, ncols - 1);
+              wv[u] = wc[c * n1 + k];
+              vv[u] = vcol[c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              if (c0 + u < ncols) s = fmaf(wv[u], vv[u], s);
+          }
           put_f(xp + k, s, tag);
         }
       }
       STAMP(30);
-      float* stage = lds + F.o_scratch;
-      if (!gather(rt, (unsigned int*)stage, F.xp + (size_t)par * F.n_col_ranks * n1, F.n_col_ranks * n1, tag)) return;
-      STAMP(31);
       float* y = lds + F.fc[0].o_act;
-      const float* b = lds + F.fc[0].o_b;
-      for (int k = tid; k < n1; k += WG) {
-        float s = b[k];
-        for (int r = 0; r < F.n_col_ranks; ++r) s += stage[r * n1 + k];
-        y[k] = L1.is_output ? s : f_act(s);
+      if (!flow_reduce_partials(rt, F.xp + (size_t)par * NR * n1, NR, n1, lds + F.fc[0].o_b, y, part, tag)) return;
+      STAMP(31);
+      if (!L1.is_output) {
+        for (int k = tid; k < n1; k += WG) y[k] = f_act(y[k]);
+        __syncthreads();
       }
-      __syncthreads();
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----
     for (int f = 1; f < n_fc; ++f) {
-      const LayerDev& L = P.layers[n_conv + f];
+      const LayerDev& L = sh.L[n_conv + f];
       float* y = lds + F.fc[f].o_act;
       flow_matvec(lds + F.fc[f].o_w, lds + F.fc[f].o_b, lds + F.fc[f - 1].o_act, y, L.n_out, L.n_in);
       if (!L.is_output) {
@@ -595,7 +909,8 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     }
     STAMP(32);
     {  // soft-max, cross-entropy error, output delta  delta_k = p_k - [k == label]
-      const LayerDev& L = P.layers[n_conv + n_fc - 1];
+      DSTAMP(111);
+      const LayerDev& L = sh.L[n_conv + n_fc - 1];
       float* y = lds + F.fc[n_fc - 1].o_act;
       float* d = lds + F.fc[n_fc - 1].o_delta;
       const int N = L.n_out;
@@ -611,16 +926,18 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
           y[k] = p;
           d[k] = p - (k == label ? 1.f : 0.f);
           if (rank == 0) {
-            if (a.probs_out) a.probs_out[t * P.n_classes + k] = p;
+            if (a.probs_out) a.probs_out[t * n_classes + k] = p;
             if (train && k == label) status->loss = -logf(p);
           }
         }
       }
+      DSTAMP(112);
       __syncthreads();
+      DSTAMP(113);
     }
     if (taps && rank == 0)
       for (int f = 0; f < n_fc; ++f) {
-        const LayerDev& L = P.layers[n_conv + f];
+        const LayerDev& L = sh.L[n_conv + f];
         for (int k = tid; k < L.n_out; k += WG) L.act[k] = lds[F.fc[f].o_act + k];
       }
     STAMP(33);
@@ -628,7 +945,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
 
     // ---- BP + AW, fully connected layers behind the first (every rank, same arithmetic) ----
     for (int f = n_fc - 1; f >= 1; --f) {
-      const LayerDev& L = P.layers[n_conv + f];
+      const LayerDev& L = sh.L[n_conv + f];
       float* W = lds + F.fc[f].o_w;
       float* b = lds + F.fc[f].o_b;
       const float* d = lds + F.fc[f].o_delta;
@@ -638,12 +955,23 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       for (int m = tid; m < n_in; m += WG) {
         const float vm = v[m];
         float g = 0.f;
-        for (int k = 0; k < n_out; ++k) {
-          const float w = W[k * n_in + m];
-          const float dk = d[k];
-          g = fmaf(w, dk, g);
-          if (g_out) { if (rank == 0) g_out[L.w_canon + (long long)k * n_in + m] = dk * vm; }
-          else W[k * n_in + m] = fmaf(-lr, dk * vm, w);
+        for (int k0 = 0; k0 < n_out; k0 += 4) {
+          float wv[4], dv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int k = min(k0 + u, n_out - 1);
+            wv[u] = W[k * n_in + m];
+            dv[u] = d[k];
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int k = k0 + u;
+            if (k < n_out) {
+              g = fmaf(wv[u], dv[u], g);
+              if (g_out) { if (rank == 0) g_out[L.w_canon + (long long)k * n_in + m] = dv[u] * vm; }
+              else W[k * n_in + m] = fmaf(-lr, dv[u] * vm, wv[u]);
+            }
+          }
         }
         dprev[m] = g * f_dact(vm);
       }
@@ -669,11 +997,12 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
         if (lane == 0) dconv[c] = s * f_dact(vcol[c]);
       }
       __syncthreads();
+      const FDiv dN(n1), dHW(HWc);
       for (int x = tid; x < ncols * n1; x += WG) {
-        const int c = x / n1, k = x - c * n1;
+        const int c = dN.div(x), k = x - c * n1;
         const float g = d[k] * vcol[c];
         if (g_out) {
-          const int am = c / HWc, q = c - am * HWc;
+          const int am = dHW.div(c), q = c - am * HWc;
           g_out[L1.w_canon + (long long)k * L1.n_in + (long long)(rank + am * G) * HWc + q] = g;
         } else {
           wc[x] = fmaf(-lr, g, wc[x]);
@@ -689,40 +1018,49 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     STAMP(35);
     // ---- BP + AW, convolutional layers, top down ----
     for (int l = n_conv - 1; l >= 0; --l) {
-      const LayerDev& L = P.layers[l];
+      const LayerDev& L = sh.L[l];
       const FlowConv& C = F.conv[l];
-      const int K = L.K, KK = K * K, HW = L.Hp * L.Wp, stride = L.S + 1, Wi = L.Wi, HiWi = L.Hi * L.Wi;
-      const int nm = n_mine(L.Mo, rank, G);
+      const int K = uni(L.K), KK = K * K, HW = uni(L.Hp) * uni(L.Wp), stride = uni(L.S) + 1, Wi = uni(L.Wi),
+                HiWi = uni(L.Hi) * Wi, Mo = uni(L.Mo);
+      const int nm = n_mine(Mo, rank, G);
       const float* dl = lds + C.o_delta;
       const int* yx = (const int*)(lds + C.o_yx);
       if (l >= 1 || taps) {
+        const FDiv dHW(HW);
         for (int x = tid; x < nm * HW; x += WG) {
-          const int am = x / HW, q = x - am * HW;
+          const int am = dHW.div(x), q = x - am * HW;
           const size_t o = (size_t)(rank + am * G) * HW + q;
           if (l >= 1) {
-            put_f(C.x_delta + (size_t)par * L.Mo * HW + o, dl[x], tag);
-            put_i(C.x_yx + (size_t)par * L.Mo * HW + o, yx[x], tag);
+            put_f(C.x_delta + (size_t)par * Mo * HW + o, dl[x], tag);
+            put_i(C.x_yx + (size_t)par * Mo * HW + o, yx[x], tag);
           }
           if (taps) L.delta[o] = dl[x];
         }
       }
       STAMP(40 + 4 * l);
-      {  // forward copy of the own maps' filters, and their biases
+      if (nm > 0) {  // forward copy of the own maps' filters, and their biases
         const int* cidx = (const int*)(lds + C.o_cidx);
         const int* ncf = (const int*)(lds + C.o_ncf);
         const float* in = lds + C.o_in;
-        const int per_map = L.max_conn * KK;
-        flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, C.wgrad_R_log2, lr, g_out, [&](int wi) {
-          const int am = wi / per_map, rem = wi - am * per_map;
-          const int c = rem / KK, tt = rem - c * KK;
-          const int ky = tt / K, kx = tt - ky * K;
+        const int pitch = uni(L.max_conn);
+        const int per_map = pitch * KK;
+        const FDiv dPM(per_map), dKK(KK), dK(K);
+        const bool full = uni(L.full_table) != 0;
+        const int Mi = uni(L.Mi);
+        flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, uni(C.wgrad_R_log2), lr, g_out, [&](int wi) {
+          const int am = dPM.div(wi), rem = wi - am * per_map;
+          const int c = dKK.div(rem), tt = rem - c * KK;
+          const int ky = dK.div(tt), kx = tt - ky * K;
           WgradInfo I;
           I.ok = c < ncf[am];
           I.d = dl + am * HW;
           I.yx = yx + am * HW;
-          I.in = in + cidx[am * L.max_conn + c] * HiWi + ky * Wi + kx;
-          const int j = rank + am * G;
-          I.canon = L.w_canon + (long long)((L.full_table ? j * L.Mi : L.csr_ptr[j]) + c) * KK + tt;
+          I.in = in + cidx[am * pitch + c] * HiWi + ky * Wi + kx;
+          I.canon = 0;
+          if (g_out) {
+            const int j = rank + am * G;
+            I.canon = L.w_canon + (long long)((full ? j * Mi : L.csr_ptr[j]) + c) * KK + tt;
+          }
           return I;
         });
         const int wave = tid >> 6, lane = tid & 63;
@@ -739,39 +1077,40 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       }
       STAMP(41 + 4 * l);
       if (l >= 1) {
-        const LayerDev& Lb = P.layers[l - 1];
-        const FlowConv& Cb = F.conv[l - 1];
-        const int nb = n_mine(L.Mi, rank, G);
+        const int nb = n_mine(uni(L.Mi), rank, G);
         if (nb > 0) {
           float* dall = lds + F.o_dall;
           int* yxall = (int*)(lds + F.o_yxall);
-          if (!gather(rt, (unsigned int*)dall, C.x_delta + (size_t)par * L.Mo * HW, L.Mo * HW, tag)) return;
-          if (!gather(rt, (unsigned int*)yxall, C.x_yx + (size_t)par * L.Mo * HW, L.Mo * HW, tag)) return;
+          if (!gather2(rt, (unsigned int*)dall, C.x_delta + (size_t)par * Mo * HW, (unsigned int*)yxall,
+                       C.x_yx + (size_t)par * Mo * HW, Mo * HW, tag))
+            return;
           STAMP(42 + 4 * l);
-          const int* ncb = (const int*)(lds + C.o_ncb);
-          for (int ab = 0; ab < nb; ++ab)
-            flow_pull_map(rt, L, C, ab, ncb[ab], dall, yxall, lds + Cb.o_pool + ab * HiWi, lds + Cb.o_delta + ab * HiWi);
+          flow_pull(rt, l, nb, dall, yxall);
           STAMP(43 + 4 * l);
-          // pull copy of the filters that read the own maps of the layer below
-          const int* bj = (const int*)(lds + C.o_bj);
-          const float* in = lds + C.o_in;
-          const int per_map = C.max_back * KK;
-          flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, C.wgrad_R_log2, lr, (gfloat*)nullptr, [&](int wi) {
-            const int ab = wi / per_map, rem = wi - ab * per_map;
-            const int e = rem / KK, tt = rem - e * KK;
-            const int ky = tt / K, kx = tt - ky * K;
-            const int j = bj[ab * C.max_back + e];
-            WgradInfo I;
-            I.ok = e < ncb[ab] && !g_out;
-            I.d = dall + j * HW;
-            I.yx = yxall + j * HW;
-            I.in = in + (rank + ab * G) * HiWi + ky * Wi + kx;
-            I.canon = 0;
-            return I;
-          });
-          __syncthreads();
+          if (!g_out) {
+            // pull copy of the filters that read the own maps of the layer below (stored rotated)
+            const int* bj = (const int*)(lds + C.o_bj);
+            const int* ncb = (const int*)(lds + C.o_ncb);
+            const float* in = lds + C.o_in;
+            const int pitch = uni(C.max_back);
+            const int per_map = pitch * KK;
+            const FDiv dPM(per_map), dKK(KK), dK(K);
+            flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, uni(C.wgrad_R_log2), lr, (gfloat*)nullptr, [&](int wi) {
+              const int ab = dPM.div(wi), rem = wi - ab * per_map;
+              const int e = dKK.div(rem), tt = KK - 1 - (rem - e * KK);
+              const int ky = dK.div(tt), kx = tt - ky * K;
+              const int j = bj[ab * pitch + e];
+              WgradInfo I;
+              I.ok = e < ncb[ab];
+              I.d = dall + j * HW;
+              I.yx = yxall + j * HW;
+              I.in = in + (rank + ab * G) * HiWi + ky * Wi + kx;
+              I.canon = 0;
+              return I;
+            });
+            __syncthreads();
+          }
         }
-        (void)Lb;
       }
     }
     STAMP(60);
@@ -787,5 +1126,7 @@ hipError_t launch_resident(int grid, size_t lds_bytes, hipStream_t stream, const
   void* params[] = {(void*)&d_prog, (void*)&d_flow, (void*)&d_status, (void*)&args};
   return hipLaunchCooperativeKernel((const void*)k_resident, dim3(grid), dim3(WG), params, (unsigned int)lds_bytes, stream);
 }
+
+size_t resident_static_lds_bytes() { return sizeof(Shared); }
 
 }  // namespace cnn355

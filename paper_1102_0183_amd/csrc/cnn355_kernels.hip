@@ -854,6 +854,18 @@ STAGE_KERNEL(k_fc_bwd, ST_FC_BWD)
 STAGE_KERNEL(k_conv_bwd, ST_CONV_BWD)
 STAGE_KERNEL(k_conv_wgrad, ST_CONV_WGRAD)
 
+// Fixed image-processing layer for a whole batch at once (it depends on no weight, so it need not
+// sit inside the on-line chain): image t of `images` -> out[t], one workgroup per WG output pixels.
+// (plain pointer types in the signature: the host and the device pass must agree on its mangled name)
+__global__ void __launch_bounds__(WG) k_frontend_batch(const ProgramDev* __restrict__ P, const float* images,
+                                                       long long image_stride, int items_per_image, float* out) {
+  const int t = blockIdx.x / items_per_image;
+  const int item = blockIdx.x - t * items_per_image;
+  FrontendDev fe = P->fe;
+  fe.out = (gfloat*)out + (size_t)t * fe.n_filters * fe.H * fe.W;
+  frontend_item(fe, item, (const gfloat*)images + (size_t)t * image_stride);
+}
+
 __global__ void k_reset_status(StatusDev* status, int clear_label_flag) {
   const int t = threadIdx.x;
   if (blockIdx.x != 0) return;
@@ -1016,6 +1028,14 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
     case ST_CONV_WGRAD: hipLaunchKernelGGL(k_conv_wgrad, grid, block, 0, stream, d_prog, s, d_status, a); break;
     default: return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, const float* d_images,
+                                 long long image_stride, int n_images, int items_per_image, float* d_out) {
+  if (n_images <= 0 || items_per_image <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_frontend_batch, dim3((unsigned)n_images * items_per_image), dim3(WG), 0, stream, d_prog,
+                     d_images, image_stride, items_per_image, d_out);
   return hipGetLastError();
 }
 

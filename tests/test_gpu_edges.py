@@ -9,7 +9,7 @@ from tests.parity_helpers import (TOL_ACT, TOL_W100, build_pair, compare_backwar
                                   layer_bounds, rel_err, to_dev)
 
 pytestmark = pytest.mark.gpu
-MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT]
+MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT, binding.MODE_RESIDENT]
 
 # (architecture, {conv_index: fan_in}, front-end K or 0, number of raw channels)
 SHAPES = [
@@ -52,6 +52,9 @@ def _pair(arch, fan, fe_k, n_src, seed):
 def test_shapes_one_step_and_ten_steps(arch, fan, fe_k, n_src, mode):
     print("case", arch, "mode", mode, flush=True)
     g, o = _pair(arch, fan, fe_k, n_src, 7)
+    if not g.mode_supported(mode):
+        g.close()
+        pytest.skip("mode %d cannot run this network" % mode)
     g.set_mode(mode)
     rng = np.random.default_rng(17)
     n_cls = g.num_classes
@@ -168,12 +171,14 @@ def test_checkpoint_roundtrip():
     g2.close()
 
 
-def test_barrier_gives_up_cleanly_when_it_cannot_complete():
+@pytest.mark.parametrize("mode", [binding.MODE_PERSISTENT, binding.MODE_RESIDENT])
+def test_barrier_gives_up_cleanly_when_it_cannot_complete(mode):
     """Force the failure path from the host: a spin limit of zero polls makes every workgroup
-    that has to wait leave the kernel; the call must end with an error, not hang."""
+    that has to wait (at a grid barrier, or for a tagged word) leave the kernel; the call must
+    end with an error, not hang."""
     wl = synth.WORKLOADS["cfg1"]
     g, _ = build_pair(wl)
-    g.set_mode(binding.MODE_PERSISTENT)
+    g.set_mode(mode)
     g.set_spin_limit(0)
     imgs, labs = synth.images(wl, 2), synth.labels(wl, 2)
     g.train_many(to_dev(imgs), to_dev(labs), 0.001)

@@ -12,7 +12,15 @@ from tests.parity_helpers import (TOL_ACT, TOL_W100, build_pair, compare_backwar
 pytestmark = pytest.mark.gpu
 
 ALL = ["cfg1", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"]
-MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT]
+MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT, binding.MODE_RESIDENT]
+
+
+def use_mode(g, mode):
+    """Switch the network to `mode`, or skip the test when the mode cannot run this network."""
+    if not g.mode_supported(mode):
+        g.close()
+        pytest.skip("mode %d cannot run this network" % mode)
+    g.set_mode(mode)
 
 
 @pytest.mark.parametrize("mode", MODES)
@@ -22,7 +30,7 @@ def test_one_step_activations_deltas_gradients(name, mode):
     wl = synth.WORKLOADS[name]
     print("case", name, "mode", mode, flush=True)
     g, o = build_pair(wl)
-    g.set_mode(mode)
+    use_mode(g, mode)
     img = synth.images(wl, 2)[1]
     lab = int(synth.labels(wl, 2)[1])
     d_img = to_dev(img)
@@ -76,7 +84,7 @@ def test_weights_after_100_online_steps(name, mode):
     wl = synth.WORKLOADS[name]
     print("case", name, "mode", mode, flush=True)
     g, o = build_pair(wl)
-    g.set_mode(mode)
+    use_mode(g, mode)
     n = 100
     imgs, labs = synth.images(wl, n), synth.labels(wl, n)
     d_imgs, d_labs = to_dev(imgs), to_dev(labs)
@@ -144,6 +152,46 @@ def test_modes_agree_bit_for_bit_and_runs_repeat(name):
         g.close()
     for r in results[1:]:
         np.testing.assert_array_equal(results[0], r)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2b", "cfg5"])
+def test_resident_mode_repeats_and_agrees_with_stages(name):
+    """Resident mode sums in another order than the stage kernels, so it agrees with them to
+    rounding, not bit for bit; but it must repeat itself bit for bit, give the same bits whether
+    the images come in one call or one by one, and not depend on where the team is placed."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, flush=True)
+    n = 12
+    imgs, labs = synth.images(wl, n), synth.labels(wl, n)
+    d_imgs, d_labs = to_dev(imgs), to_dev(labs)
+    ref, _ = build_pair(wl)
+    ref.set_mode(binding.MODE_STAGES)
+    ref.train_many(d_imgs, d_labs, wl.lr)
+    w_ref = ref.get_weights()
+    ref.close()
+    results = {}
+    for variant in ("many", "many-again", "step", "one-xcd", "spread"):
+        g, _ = build_pair(wl)
+        use_mode(g, binding.MODE_RESIDENT)
+        if variant == "one-xcd":
+            g.set_team(32, 8)
+        elif variant == "spread":
+            g.set_team(32, 1)
+        if variant == "step":
+            sz = g.image_size
+            for t in range(n):
+                g.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], int(labs[t]), wl.lr)
+        else:
+            g.train_many(d_imgs, d_labs, wl.lr)
+        results[variant] = g.get_weights()
+        g.close()
+    np.testing.assert_array_equal(results["many"], results["many-again"])
+    np.testing.assert_array_equal(results["many"], results["step"])
+    np.testing.assert_array_equal(results["one-xcd"], results["spread"])
+    w0 = synth.weights(wl, len(w_ref))
+    for variant, w in results.items():
+        assert rel_err(w.astype(np.float64) - w0, w_ref.astype(np.float64) - w0) <= 1e-3, variant
+        assert rel_err(w, w_ref) <= 1e-5, variant
 
 
 def test_update_order_old_weights_feed_the_deltas():
