@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the on-line training hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--mode persistent|stages]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--mode resident|persistent|stages]
 
 One "step" is one cnn_train_many call: B consecutive images of the 60,000-image synthetic
 29x29 stream (workload cfg2) trained on-line -- forward, delta pass, weight gradients and an
@@ -10,7 +10,9 @@ resident in HBM before the timed region starts.  Prints ONE JSON line.
 
 value        = images trained per second over the K timed steps (wall clock, synchronised).
 roofline     = the dominant kernel's algorithmic bytes per launch / its mean launch duration,
-               measured with HIP events on the launch stream, against the 8 TB/s HBM peak.
+               measured with HIP events on the launch stream, against the 8 TB/s HBM peak;
+               traffic = HBM bytes per launch from the rocprofv3 counter summary under profiles/
+               (FETCH_SIZE + WRITE_SIZE, calibrated on a copy of known size), when one is there.
 cpu_baseline = the CPU oracle (float32 instantiation, OpenMP over output maps) timed on a
                prefix of the same stream on this machine's host cores.
 extra        = the other measurements the workload names (larger net, forward-only passes).
@@ -26,6 +28,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+KERNEL_OF_MODE = {"resident": "k_resident", "persistent": "k_persistent", "stages": "per-stage kernels (sum)"}
+
+
+def measured_traffic(mode, batch):
+    """HBM bytes per launch of the mode's kernel on the benchmark workload, from the committed
+    rocprofv3 --pmc summary (a text file with a line 'traffic_bytes_per_launch: N batch: B')."""
+    path = os.path.join(ROOT, "profiles", "%s_cfg2a_train_traffic.txt" % KERNEL_OF_MODE[mode].split()[0])
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                f = line.split()
+                if int(f[3]) == batch:
+                    return int(f[1])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
 
 
 def algorithmic_bytes_per_train_image(info, n_weights, image_floats):
@@ -87,8 +105,10 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=1000, help="images per step (one cnn_train_many call)")
-    ap.add_argument("--mode", choices=["persistent", "stages"], default="persistent")
+    ap.add_argument("--mode", choices=["resident", "persistent", "stages"], default="resident")
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the persistent kernel (0 = automatic)")
+    ap.add_argument("--ranks", type=int, default=0, help="resident mode: workgroups in the team (0 = automatic)")
+    ap.add_argument("--xcd-stride", type=int, default=0, help="resident mode: 8 = team on one XCD, 1 = spread, 0 = automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -116,9 +136,12 @@ def main():
 
     def make_net(workload, grid=0):
         net = binding.Cnn(workload.arch)
-        net.set_mode(binding.MODE_PERSISTENT if args.mode == "persistent" else binding.MODE_STAGES)
+        net.set_mode({"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
+                      "stages": binding.MODE_STAGES}[args.mode])
         if grid:
             net.set_grid(grid)
+        if args.mode == "resident" and (args.ranks or args.xcd_stride):
+            net.set_team(args.ranks, args.xcd_stride)
         net.set_weights(synth.weights(workload, net.num_weights))
         return net
 
@@ -151,9 +174,9 @@ def main():
     bytes_img = algorithmic_bytes_per_train_image(info, net.num_weights, net.image_size)
     achieved = bytes_img * B / (kern_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "k_persistent" if args.mode == "persistent" else "per-stage kernels (sum)",
+        "bound": "hbm", "kernel": KERNEL_OF_MODE[args.mode],
         "achieved": round(achieved, 3), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 6), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 6), "traffic": measured_traffic(args.mode, B),
         "algorithmic_bytes_per_image": bytes_img, "images_per_launch": B,
         "launch_ms_mean": round(kern_ms, 4),
         "flop_per_image": 10.9e6, "achieved_tflops": round(10.9e6 * B / (kern_ms * 1e-3) / 1e12, 4),
@@ -166,7 +189,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "cfg2 small net: %s, 60000 seeded 1x29x29 images U[-1,1], 10 uniform labels, "
                                "on-line SGD lr=0.001, weights U[-0.05,0.05]" % wl.arch,
-                   "images_per_step": B, "mode": args.mode, "grid": args.grid},
+                   "images_per_step": B, "mode": args.mode, "grid": args.grid, "ranks": args.ranks,
+                   "xcd_stride": args.xcd_stride},
         "roofline": roofline,
     }
     net.close()

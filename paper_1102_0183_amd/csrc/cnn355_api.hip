@@ -602,15 +602,24 @@ void plan_flow(cnn* net) {
 
   long long off = 0;
   auto take = [&](long long n) { const long long o = off; off += (n + 3) / 4 * 4; return (int)std::min<long long>(o, 1 << 30); };
-  // strip width for a row of `width` output pixels: the one of {4, 5, 7} that wastes the fewest
-  // lanes on the ragged end of the row, the wider one on a tie; 0 = one pixel per lane
-  auto strip_for = [](int K, int stride, int width) {
+  // Strip width for a correlation job of n_maps maps of rows x width pixels with up to max_cnt
+  // connections each: the one of {4, 5, 7} that leaves the least multiply-accumulate work per
+  // lane once the connections are shared over the spare lanes (the rule the kernel applies), the
+  // wider one on a tie; 0 = one pixel per lane (any stride, any kernel size).
+  auto strip_for = [](int K, int stride, int n_maps, int rows, int width, int max_cnt) {
     if (stride != 1 || K < 2 || K > 5) return 0;
     int best = 4;
-    double best_eff = 0;
+    long long best_cost = -1;
     for (int sw : {4, 5, 7}) {
-      const double eff = (double)width / (double)(((width + sw - 1) / sw) * sw);
-      if (eff >= best_eff) { best_eff = eff; best = sw; }
+      const long long U = (long long)n_maps * rows * ((width + sw - 1) / sw);
+      long long iters = max_cnt;
+      if (U < WG) {
+        const long long r_max = std::max<long long>(1, std::min<long long>(WG / U, max_cnt));
+        iters = (max_cnt + r_max - 1) / r_max;
+      }
+      const long long passes = (U + WG - 1) / WG;
+      const long long cost = passes * iters * (sw * K * K + (sw + 2 * K - 1) * K / 2);
+      if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best = sw; }
     }
     return best;
   };
@@ -631,12 +640,12 @@ void plan_flow(cnn* net) {
     C.o_bf = take(C.n_own);
     C.o_cidx = take((long long)C.n_own * L.max_conn);
     C.o_ncf = take(C.n_own);
-    C.fwd_strip = strip_for(L.K, L.S + 1, L.Wo);
+    C.fwd_strip = strip_for(L.K, L.S + 1, C.n_own, L.Ho, L.Wo, L.max_conn);
     if (l >= 1) {
       C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
       C.o_bj = take((long long)C.n_own_below * C.max_back);
       C.o_ncb = take(C.n_own_below);
-      C.pull_strip = strip_for(L.K, 1, L.Wi);
+      C.pull_strip = strip_for(L.K, 1, C.n_own_below, L.Hi, L.Wi, C.max_back);
       max_dall = std::max<long long>(max_dall, (long long)L.Mo * HW);
       max_hwd = std::max<long long>(max_hwd, (long long)(L.Hi + L.K - 1) * (L.Wi + L.K - 1));
       max_part = std::max<long long>(max_part, (long long)C.n_own_below * L.Hi * L.Wi);
@@ -681,6 +690,14 @@ void plan_flow(cnn* net) {
   if (off + need > FLOW_LDS_FLOATS_MAX)
     return no("the weights and maps one workgroup would hold (" + std::to_string((off + need) * 4 / 1024) +
               " KB) exceed its LDS");
+  // lane tables of the correlation jobs, while there is room (a rank decodes its share of a job
+  // once instead of once per image); the first layers' jobs first
+  for (int l = 0; l < n_conv; ++l) { F.conv[l].o_tab_fwd = -1; F.conv[l].o_tab_pull = -1; }
+  for (int l = 0; l < n_conv; ++l) {
+    if (F.conv[l].n_own < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX) F.conv[l].o_tab_fwd = take(3 * WG);
+    if (l >= 1 && F.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX)
+      F.conv[l].o_tab_pull = take(3 * WG);
+  }
   // the zero-bordered delta maps of the pull: the more fit, the fewer passes
   long long scratch = need;
   for (int l = 1; l < n_conv; ++l) {

@@ -152,7 +152,7 @@ constexpr int FLOW_MAX_CONV = 8;
 constexpr int FLOW_MAX_FC = 8;
 // the arena a rank carves up, in floats (154 KB of the 160 KB of a gfx950 CU; the rest holds a copy
 // of the descriptors)
-constexpr int FLOW_LDS_FLOATS_MAX = 39424;
+constexpr int FLOW_LDS_FLOATS_MAX = 39168;
 constexpr int FLOW_STRIP_MAX = 7;  // output pixels one lane accumulates in registers
 
 struct FlowConv {
@@ -175,6 +175,8 @@ struct FlowConv {
   int o_delta;  // [n_own][Hp*Wp] deltas at the winners
   int o_ncf;    // [n_own] connections of every own map (int)
   int o_ncb;    // [n_own_below] entries of every own input map (int)
+  int o_tab_fwd;   // [3][WG] every lane's share of the FP job (int), or -1
+  int o_tab_pull;  // [3][WG] every lane's share of the pull job (int), or -1
   CNN_GLOBAL tagged_t* x_out;    // [2][Mo*Hp*Wp] pooled outputs, when a convolutional layer follows
   CNN_GLOBAL tagged_t* x_delta;  // [2][Mo*Hp*Wp] deltas at the winners (layers above the first)
   CNN_GLOBAL tagged_t* x_yx;     // [2][Mo*Hp*Wp] their coordinates

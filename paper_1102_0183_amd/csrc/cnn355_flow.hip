@@ -43,7 +43,13 @@ typedef CNN_GLOBAL tagged_t gtagged;
 
 #define ACT_A 1.7159f
 #define ACT_B 0.6666f
-__device__ __forceinline__ float f_act(float a) { return ACT_A * tanhf(ACT_B * a); }
+// Scaled hyperbolic tangent of Sec. 4, constants as printed, as 1 - 2 / (e^{2Ba} + 1) on the hardware
+// exponential and reciprocal: absolute error about 1e-7 (the library tanhf costs thirty times as
+// many cycles on the critical path of every layer); saturates correctly at both ends.
+__device__ __forceinline__ float f_act(float a) {
+  const float z = __builtin_amdgcn_exp2f((2.0f * ACT_B * 1.44269504088896340736f) * a);
+  return fmaf(-2.0f * ACT_A, __builtin_amdgcn_rcpf(z + 1.0f), ACT_A);
+}
 __device__ __forceinline__ float f_dact(float y) {
   return (float)(1.7159 * 0.6666) - (float)(0.6666 / 1.7159) * y * y;
 }
@@ -123,9 +129,20 @@ __device__ __forceinline__ void put_i(gtagged* p, int v, unsigned int tag) {
 
 // A copy of the descriptors in LDS: reading them from global memory in every phase of every image
 // costs a memory round trip each time the scalar cache has dropped them.
+struct JobDesc {
+  int in, w, idx, cnt;  // LDS offsets (floats): inputs [..][map_sz], weights [n_maps][w_pitch][K*K],
+                        // input map of every connection [n_maps][w_pitch], connections per map [n_maps]
+  int n_maps, w_pitch, Ho, Wo, K, stride, map_sz, Wi, max_cnt;
+  int variant;          // SW * 8 + K for a strip job, 0: one pixel per lane (any K, any stride)
+  int U, R, passes;     // units, ways the connections are shared, passes over the lanes
+  int table;            // LDS offset of the lane table [3][WG] (int), or -1
+};
+
 struct Shared {
   FlowDev F;
   LayerDev L[FLOW_MAX_CONV + FLOW_MAX_FC];
+  JobDesc fwd[FLOW_MAX_CONV];   // FP of the own maps of every convolutional layer
+  JobDesc pull[FLOW_MAX_CONV];  // delta pull through layer l into the own maps of layer l-1 (l >= 1)
   int fail;
 };
 
@@ -387,145 +404,166 @@ __device__ __forceinline__ void strip_mac(const float* in, const float* w, const
 
 // A correlation job: n_maps output maps of Ho x Wo, each the sum over its connection list of
 // K x K correlations (unit stride for the strip form) of input maps of map_sz floats and row
-// pitch Wi.  Lanes take (map, row, strip of SW pixels) units, or (map, pixel) units when SW = 0,
+// pitch Wi.  Lanes take (map, row, strip of SW pixels) units, or (map, pixel) units when SW = 1,
 // and share the connections R ways when there are fewer units than lanes; partial sums go to
-// part[(r * n_maps + map) * Ho*Wo + pixel].  The chunk interface (first / last) lets the pull
-// accumulate over several passes with the inputs rebuilt in between.
-struct Corr {
-  const float* in;     // [..][map_sz]
-  const float* w;      // [n_maps][w_pitch][K*K]
-  const int* idx;      // [n_maps][w_pitch] input map of every connection
-  const int* cnt;      // [n_maps] connections of every map
-  int n_maps, w_pitch, Ho, Wo, K, stride, map_sz, Wi;
-  int max_cnt;
-};
-
-template <int K, int SW>
-struct StripJob {
-  const Corr J;
-  int NS, U, R, r, am, pix0, base, ncols;
+// part[(r * n_maps + map) * Ho*Wo + pixel].  A job is the same for every image of a call: it is
+// described once, and (LDS permitting) every lane's share of it is decoded once and kept in a
+// table, because working it out again per image -- integer divisions, a dozen descriptor
+// reads -- costs more than the multiply-accumulates of a small layer.
+struct Lane {
+  int r, am, pix, base, ncols;
   bool on;
-  float acc[SW];
-  __device__ __forceinline__ StripJob(const Corr& j, int pass) : J(j) {
-    NS = (J.Wo + SW - 1) / SW;
-    U = J.n_maps * J.Ho * NS;
-    R = (U >= WG) ? 1 : max(1, min(WG / U, J.max_cnt));
-    const int u = pass * WG + (int)threadIdx.x;
-    on = u < U * R;
-    const FDiv dU(U), dNS(NS), dHo(J.Ho);
-    r = dU.div(u);
-    const int v = u - r * U;
-    const int row = dNS.div(v), s = v - row * NS;
-    am = dHo.div(row);
-    const int y = row - am * J.Ho, x0 = s * SW;
-    if (!on) { r = 0; am = 0; }
-    pix0 = y * J.Wo + x0;
-    ncols = min(SW, J.Wo - x0);
-    base = on ? y * J.Wi + x0 : 0;
-#pragma unroll
-    for (int i = 0; i < SW; ++i) acc[i] = 0.f;
-  }
-  __device__ __forceinline__ int passes() const { return (U * R + WG - 1) / WG; }
-  // connections [e_lo, e_hi) of the lane's map, maps numbered from idx_off
-  __device__ __forceinline__ void run(int e_lo, int e_hi, int idx_off) {
-    if (on)
-      strip_mac<K, SW>(J.in, J.w + (am * J.w_pitch) * (K * K), J.idx + am * J.w_pitch, idx_off, e_lo + r, R, e_hi,
-                       J.map_sz, J.Wi, base, acc);
-  }
-  __device__ __forceinline__ void store(float* part) const {
-    if (on) {
-      float* dst = part + (r * J.n_maps + am) * (J.Ho * J.Wo) + pix0;
-#pragma unroll
-      for (int i = 0; i < SW; ++i)
-        if (i < ncols) dst[i] = acc[i];
-    }
-  }
 };
 
-struct PixelJob {
-  const Corr J;
-  int U, R, r, am, p, base;
-  bool on;
-  float acc;
-  __device__ __forceinline__ PixelJob(const Corr& j, int pass) : J(j) {
-    const int Pn = J.Ho * J.Wo;
-    U = J.n_maps * Pn;
-    R = (U >= WG) ? 1 : max(1, min(WG / U, J.max_cnt));
-    const int u = pass * WG + (int)threadIdx.x;
-    on = u < U * R;
-    const FDiv dU(U), dP(Pn), dW(J.Wo);
-    r = dU.div(u);
-    const int v = u - r * U;
-    am = dP.div(v);
-    p = v - am * Pn;
-    const int y = dW.div(p), x = p - y * J.Wo;
-    if (!on) { r = 0; am = 0; p = 0; }
-    base = on ? (y * J.Wi + x) * J.stride : 0;
-    acc = 0.f;
-  }
-  __device__ __forceinline__ int passes() const { return (U * R + WG - 1) / WG; }
-  __device__ __forceinline__ void run(int e_lo, int e_hi, int idx_off) {
-    if (on)
-      acc += pixel_mac_k(J.K, J.in, J.w + (am * J.w_pitch) * (J.K * J.K), J.idx + am * J.w_pitch, idx_off, e_lo + r, R,
-                         e_hi, J.map_sz, J.Wi, base);
-  }
-  __device__ __forceinline__ void store(float* part) const {
-    if (on) part[(r * J.n_maps + am) * (J.Ho * J.Wo) + p] = acc;
-  }
-};
-
-// ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
-template <class Job>
-__device__ __forceinline__ int fwd_run(const Corr& J, float* part, const Rt& rt) {
-  int R = 1;
-  const int passes = Job(J, 0).passes();
-  for (int pass = 0; pass < passes; ++pass) {
-    Job job(J, pass);
-    R = job.R;
-    DSTAMP(114);
-    if (job.on) job.run(0, J.cnt[job.am], 0);
-    job.store(part);
-  }
-  return R;
+// How many ways U units share their (at most max_cnt) connections over the WG lanes: as many as fit,
+// then the fewest ways that still need no more passes over the connections per lane.
+__device__ __forceinline__ int split_ways(int U, int max_cnt) {
+  if (U >= WG) return 1;
+  const int r_max = max(1, min(WG / U, max_cnt));
+  const int iters = (max_cnt + r_max - 1) / r_max;
+  return (max_cnt + iters - 1) / iters;
 }
 
+__device__ __forceinline__ void job_finish(JobDesc& D) {
+  const int SW = D.variant >> 3;
+  D.U = SW ? D.n_maps * D.Ho * ((D.Wo + SW - 1) / SW) : D.n_maps * D.Ho * D.Wo;
+  D.R = D.U > 0 ? split_ways(D.U, D.max_cnt) : 1;
+  D.passes = (D.U * D.R + WG - 1) / WG;
+}
+
+// the share of lane `tid` in pass `pass`
+__device__ __forceinline__ Lane lane_decode(const JobDesc& D, int pass) {
+  const int SW = D.variant >> 3;
+  Lane ln;
+  const int u = pass * WG + (int)threadIdx.x;
+  ln.on = u < D.U * D.R;
+  const FDiv dU(D.U);
+  ln.r = dU.div(u);
+  const int v = u - ln.r * D.U;
+  if (SW) {
+    const int NS = (D.Wo + SW - 1) / SW;
+    const FDiv dNS(NS), dHo(D.Ho);
+    const int row = dNS.div(v), s = v - row * NS;
+    ln.am = dHo.div(row);
+    const int y = row - ln.am * D.Ho, x0 = s * SW;
+    ln.pix = y * D.Wo + x0;
+    ln.ncols = min(SW, D.Wo - x0);
+    ln.base = y * D.Wi + x0;
+  } else {
+    const int Pn = D.Ho * D.Wo;
+    const FDiv dP(Pn), dW(D.Wo);
+    ln.am = dP.div(v);
+    ln.pix = v - ln.am * Pn;
+    const int y = dW.div(ln.pix), x = ln.pix - y * D.Wo;
+    ln.ncols = 1;
+    ln.base = (y * D.Wi + x) * D.stride;
+  }
+  if (!ln.on) { ln.r = 0; ln.am = 0; ln.pix = 0; ln.base = 0; ln.ncols = 0; }
+  return ln;
+}
+__device__ __forceinline__ void lane_save(const Lane& ln, int* tab) {
+  const int tid = threadIdx.x;
+  tab[tid] = ln.base;
+  tab[WG + tid] = ln.pix;
+  tab[2 * WG + tid] = ln.r | (ln.am << 10) | (ln.ncols << 20) | ((ln.on ? 1 : 0) << 24);
+}
+__device__ __forceinline__ Lane lane_load(const int* tab) {
+  const int tid = threadIdx.x;
+  Lane ln;
+  ln.base = tab[tid];
+  ln.pix = tab[WG + tid];
+  const int m = tab[2 * WG + tid];
+  ln.r = m & 1023;
+  ln.am = (m >> 10) & 1023;
+  ln.ncols = (m >> 20) & 15;
+  ln.on = (m >> 24) != 0;
+  return ln;
+}
+__device__ __forceinline__ Lane lane_get(const JobDesc& D, const float* lds, int pass) {
+  if (D.table >= 0 && D.passes == 1) return lane_load((const int*)(lds + D.table));
+  return lane_decode(D, pass);
+}
+
+template <int V>
+struct IC { static constexpr int value = V; };
+
+// call f(K, SW) with the job's compile-time kernel size and strip width (K = 0: any size, one pixel)
+template <class Fn>
+__device__ __forceinline__ void job_dispatch(int variant, Fn f) {
+  switch (variant) {
+#define JOB_CASE(SW, K) case SW * 8 + K: f(IC<K>{}, IC<SW>{}); break;
+    JOB_CASE(4, 2) JOB_CASE(4, 3) JOB_CASE(4, 4) JOB_CASE(4, 5)
+    JOB_CASE(5, 2) JOB_CASE(5, 3) JOB_CASE(5, 4) JOB_CASE(5, 5)
+    JOB_CASE(7, 2) JOB_CASE(7, 3) JOB_CASE(7, 4) JOB_CASE(7, 5)
+#undef JOB_CASE
+    default: f(IC<0>{}, IC<1>{}); break;
+  }
+}
+
+// acc[] += the lane's share of connections [e_lo, e_hi) of its map (maps numbered from idx_off)
+template <int K, int SW>
+__device__ __forceinline__ void job_mac(const JobDesc& D, const float* lds, const Lane& ln, int e_lo, int e_hi,
+                                        int idx_off, float (&acc)[SW]) {
+  const float* w = lds + D.w + (ln.am * D.w_pitch) * (D.K * D.K);
+  const int* idx = (const int*)(lds + D.idx) + ln.am * D.w_pitch;
+  if constexpr (K == 0)
+    acc[0] += pixel_mac_k(D.K, lds + D.in, w, idx, idx_off, e_lo + ln.r, D.R, e_hi, D.map_sz, D.Wi, ln.base);
+  else
+    strip_mac<K, SW>(lds + D.in, w, idx, idx_off, e_lo + ln.r, D.R, e_hi, D.map_sz, D.Wi, ln.base, acc);
+}
+
+// ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
 __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l, int nm) {
   const FlowDev& F = rt.sh->F;
-  const LayerDev& L = rt.sh->L[l];
   const FlowConv& C = F.conv[l];
   float* lds = rt.lds;
   const int tid = threadIdx.x;
-  Corr J;
-  J.in = lds + C.o_in;
-  J.w = lds + C.o_wf;
-  J.idx = (const int*)(lds + C.o_cidx);
-  J.cnt = (const int*)(lds + C.o_ncf);
-  J.n_maps = nm; J.w_pitch = uni(L.max_conn); J.Ho = uni(L.Ho); J.Wo = uni(L.Wo); J.K = uni(L.K);
-  J.stride = uni(L.S) + 1; J.map_sz = uni(L.Hi) * uni(L.Wi); J.Wi = uni(L.Wi); J.max_cnt = J.w_pitch;
+  const JobDesc D = rt.sh->fwd[l];
   float* part = lds + F.o_part;
-  int R = 1;
-  if (l == 1) DSTAMP(110);
-  switch (uni(C.fwd_strip) * 8 + J.K) {
-#define FWD_CASE(SW, KK_) case SW * 8 + KK_: R = fwd_run<StripJob<KK_, SW>>(J, part, rt); break;
-    FWD_CASE(4, 2) FWD_CASE(4, 3) FWD_CASE(4, 4) FWD_CASE(4, 5)
-    FWD_CASE(5, 2) FWD_CASE(5, 3) FWD_CASE(5, 4) FWD_CASE(5, 5)
-    FWD_CASE(7, 2) FWD_CASE(7, 3) FWD_CASE(7, 4) FWD_CASE(7, 5)
-#undef FWD_CASE
-    default: R = fwd_run<PixelJob>(J, part, rt); break;
-  }
+  float* act = lds + F.o_act;
+  const float* bf = lds + C.o_bf;
+  const int* cnt = (const int*)(lds + D.cnt);
+  const int Pn = D.Ho * D.Wo, tot = nm * Pn;
+  if (l == 1) DSTAMP(110); else DSTAMP(118);
+  job_dispatch(D.variant, [&](auto k_, auto sw_) {
+    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value;
+    for (int pass = 0; pass < D.passes; ++pass) {
+      if (l == 0) DSTAMP(115);
+      const Lane ln = lane_get(D, lds, pass);
+      if (l == 0) DSTAMP(116); else DSTAMP(114);
+      float acc[SW];
+#pragma unroll
+      for (int i = 0; i < SW; ++i) acc[i] = 0.f;
+      if (ln.on) {
+        job_mac<K, SW>(D, lds, ln, 0, cnt[ln.am], 0, acc);
+        if (l == 0) DSTAMP(117);
+        if (D.R == 1) {  // unsplit: the finished sums go straight through the activation function
+          const float b = bf[ln.am];
+          float* dst = act + ln.am * Pn + ln.pix;
+#pragma unroll
+          for (int i = 0; i < SW; ++i)
+            if (i < ln.ncols) dst[i] = f_act(acc[i] + b);
+        } else {
+          float* dst = part + (ln.r * nm + ln.am) * Pn + ln.pix;
+#pragma unroll
+          for (int i = 0; i < SW; ++i)
+            if (i < ln.ncols) dst[i] = acc[i];
+        }
+      }
+    }
+  });
   DSTAMP(100 + 4 * l);
   __syncthreads();
   DSTAMP(101 + 4 * l);
-  const int Pn = J.Ho * J.Wo, tot = nm * Pn;
-  const FDiv dP(Pn);
-  float* act = lds + F.o_act;
-  const float* bf = lds + C.o_bf;
-  for (int p = tid; p < tot; p += WG) {
-    const float s = sum_strided(part, R, tot, p);
-    act[p] = f_act(s + bf[dP.div(p)]);
+  if (D.R > 1) {
+    const FDiv dP(Pn);
+    for (int p = tid; p < tot; p += WG) {
+      const float s = sum_strided(part, D.R, tot, p);
+      act[p] = f_act(s + bf[dP.div(p)]);
+    }
+    DSTAMP(102 + 4 * l);
+    __syncthreads();
   }
-  DSTAMP(102 + 4 * l);
-  __syncthreads();
   DSTAMP(103 + 4 * l);
 }
 
@@ -636,55 +674,6 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
 // a tap that has no output neuron then meets a zero and the loop has no branches.  The zero maps
 // are kept zero between uses: after a chunk the winners' places are cleared again.
 // delta_below[p] = pulled sum * f'(y_below[p]).
-template <class Job>
-__device__ __forceinline__ void pull_run(const Rt& rt, const LayerDev& L, const FlowConv& C, const Corr& J,
-                                         const float* dall, const int* yxall, int nb, float* part, int& R_out) {
-  const FlowDev& F = rt.sh->F;
-  float* dd = rt.lds + F.o_scratch;
-  const int tid = threadIdx.x;
-  const int Mo = uni(L.Mo), HW = uni(L.Hp) * uni(L.Wp), stride = uni(L.S) + 1, Km1 = uni(L.K) - 1;
-  const int Wd = J.Wi, HWd = J.map_sz;
-  const int chunk = uni(C.pull_chunk);
-  const bool full = uni(L.full_table) != 0;
-  const FDiv dHW(HW);
-  const int passes = Job(J, 0).passes();
-  for (int pass = 0; pass < passes; ++pass) {
-    Job job(J, pass);
-    R_out = job.R;
-    for (int j0 = 0; j0 < Mo; j0 += chunk) {
-      const int n = min(chunk, Mo - j0);
-      for (int x = tid; x < n * HW; x += WG) {
-        const int c = dHW.div(x), q = x - c * HW;
-        const int yx = yxall[(j0 + c) * HW + q];
-        dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
-      }
-      __syncthreads();
-      if (job.on) {
-        // entries of the lane's input map whose output map lies in [j0, j0 + n)
-        int e_lo = j0, e_hi = j0 + n;
-        if (!full) {
-          const int* bj = J.idx + job.am * J.w_pitch;
-          const int ne = J.cnt[job.am];
-          e_lo = 0;
-          while (e_lo < ne && bj[e_lo] < j0) ++e_lo;
-          e_hi = e_lo;
-          while (e_hi < ne && bj[e_hi] < j0 + n) ++e_hi;
-        }
-        job.run(e_lo, e_hi, j0);
-      }
-      __syncthreads();
-      for (int x = tid; x < n * HW; x += WG) {
-        const int c = dHW.div(x), q = x - c * HW;
-        const int yx = yxall[(j0 + c) * HW + q];
-        dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = 0.f;
-      }
-      __syncthreads();
-    }
-    job.store(part);
-  }
-  (void)nb;
-}
-
 __device__ __forceinline__ void flow_pull(const Rt& rt, int l, int nb, const float* dall, const int* yxall) {
   const FlowDev& F = rt.sh->F;
   const LayerDev& L = rt.sh->L[l];
@@ -692,30 +681,65 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, int nb, const flo
   const FlowConv& Cb = F.conv[l - 1];
   float* lds = rt.lds;
   const int tid = threadIdx.x;
-  const int K = uni(L.K), Hi = uni(L.Hi), Wi = uni(L.Wi);
-  Corr J;
-  J.in = lds + F.o_scratch;
-  J.w = lds + C.o_wb;
-  J.idx = (const int*)(lds + C.o_bj);
-  J.cnt = (const int*)(lds + C.o_ncb);
-  J.n_maps = nb; J.w_pitch = uni(C.max_back); J.Ho = Hi; J.Wo = Wi; J.K = K; J.stride = 1;
-  J.Wi = Wi + K - 1; J.map_sz = (Hi + K - 1) * (Wi + K - 1); J.max_cnt = min(J.w_pitch, uni(C.pull_chunk));
+  const JobDesc D = rt.sh->pull[l];
+  float* dd = lds + F.o_scratch;
   float* part = lds + F.o_part;
-  int R = 1;
-  switch (uni(C.pull_strip) * 8 + K) {
-#define PULL_CASE(SW, KK_) case SW * 8 + KK_: pull_run<StripJob<KK_, SW>>(rt, L, C, J, dall, yxall, nb, part, R); break;
-    PULL_CASE(4, 2) PULL_CASE(4, 3) PULL_CASE(4, 4) PULL_CASE(4, 5)
-    PULL_CASE(5, 2) PULL_CASE(5, 3) PULL_CASE(5, 4) PULL_CASE(5, 5)
-    PULL_CASE(7, 2) PULL_CASE(7, 3) PULL_CASE(7, 4) PULL_CASE(7, 5)
-#undef PULL_CASE
-    default: pull_run<PixelJob>(rt, L, C, J, dall, yxall, nb, part, R); break;
-  }
+  const int Mo = uni(L.Mo), HW = uni(L.Hp) * uni(L.Wp), stride = uni(L.S) + 1, Km1 = D.K - 1;
+  const int Wd = D.Wi, HWd = D.map_sz;
+  const int chunk = uni(C.pull_chunk);
+  const bool full = uni(L.full_table) != 0;
+  const int* cnt = (const int*)(lds + D.cnt);
+  const int tot = nb * D.Ho * D.Wo;
+  const FDiv dHW(HW);
+  job_dispatch(D.variant, [&](auto k_, auto sw_) {
+    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value;
+    for (int pass = 0; pass < D.passes; ++pass) {
+      const Lane ln = lane_get(D, lds, pass);
+      float acc[SW];
+#pragma unroll
+      for (int i = 0; i < SW; ++i) acc[i] = 0.f;
+      for (int j0 = 0; j0 < Mo; j0 += chunk) {
+        const int n = min(chunk, Mo - j0);
+        for (int x = tid; x < n * HW; x += WG) {
+          const int c = dHW.div(x), q = x - c * HW;
+          const int yx = yxall[(j0 + c) * HW + q];
+          dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
+        }
+        __syncthreads();
+        if (ln.on) {
+          // entries of the lane's input map whose output map lies in [j0, j0 + n)
+          int e_lo = j0, e_hi = j0 + n;
+          if (!full) {
+            const int* bj = (const int*)(lds + D.idx) + ln.am * D.w_pitch;
+            const int ne = cnt[ln.am];
+            e_lo = 0;
+            while (e_lo < ne && bj[e_lo] < j0) ++e_lo;
+            e_hi = e_lo;
+            while (e_hi < ne && bj[e_hi] < j0 + n) ++e_hi;
+          }
+          job_mac<K, SW>(D, lds, ln, e_lo, e_hi, j0, acc);
+        }
+        __syncthreads();
+        for (int x = tid; x < n * HW; x += WG) {
+          const int c = dHW.div(x), q = x - c * HW;
+          const int yx = yxall[(j0 + c) * HW + q];
+          dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = 0.f;
+        }
+        if (j0 + chunk < Mo) __syncthreads();
+      }
+      if (ln.on) {
+        float* dst = part + (ln.r * nb + ln.am) * (D.Ho * D.Wo) + ln.pix;
+#pragma unroll
+        for (int i = 0; i < SW; ++i)
+          if (i < ln.ncols) dst[i] = acc[i];
+      }
+    }
+  });
   __syncthreads();
-  const int tot = nb * Hi * Wi;
   const float* ybelow = lds + Cb.o_pool;
   float* dbelow = lds + Cb.o_delta;
   for (int p = tid; p < tot; p += WG) {
-    const float s = sum_strided(part, R, tot, p);
+    const float s = sum_strided(part, D.R, tot, p);
     dbelow[p] = s * f_dact(ybelow[p]);
   }
   __syncthreads();
@@ -785,6 +809,46 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
   return rt.sh->fail == 0;
 }
 
+// Describe the correlation jobs of this rank and fill their lane tables (once per call).
+__device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
+  Shared& sh = *rt.sh;
+  const FlowDev& F = sh.F;
+  const int G = F.G, rank = rt.rank;
+  if (threadIdx.x == 0) {
+    for (int l = 0; l < F.n_conv; ++l) {
+      const LayerDev& L = sh.L[l];
+      const FlowConv& C = F.conv[l];
+      JobDesc& D = sh.fwd[l];
+      D.in = C.o_in; D.w = C.o_wf; D.idx = C.o_cidx; D.cnt = C.o_ncf;
+      D.n_maps = n_mine(L.Mo, rank, G); D.w_pitch = L.max_conn; D.Ho = L.Ho; D.Wo = L.Wo; D.K = L.K;
+      D.stride = L.S + 1; D.map_sz = L.Hi * L.Wi; D.Wi = L.Wi; D.max_cnt = L.max_conn;
+      D.variant = C.fwd_strip ? C.fwd_strip * 8 + L.K : 0;
+      D.table = C.o_tab_fwd;
+      job_finish(D);
+      if (l >= 1) {
+        JobDesc& B = sh.pull[l];
+        B.in = F.o_scratch; B.w = C.o_wb; B.idx = C.o_bj; B.cnt = C.o_ncb;
+        B.n_maps = n_mine(L.Mi, rank, G); B.w_pitch = C.max_back; B.Ho = L.Hi; B.Wo = L.Wi; B.K = L.K;
+        B.stride = 1; B.Wi = L.Wi + L.K - 1; B.map_sz = (L.Hi + L.K - 1) * (L.Wi + L.K - 1);
+        B.max_cnt = min(C.max_back, C.pull_chunk);
+        B.variant = C.pull_strip ? C.pull_strip * 8 + L.K : 0;
+        B.table = C.o_tab_pull;
+        job_finish(B);
+      }
+    }
+  }
+  __syncthreads();
+  for (int l = 0; l < F.n_conv; ++l) {
+    const JobDesc& D = sh.fwd[l];
+    if (D.n_maps > 0 && D.table >= 0 && D.passes == 1) lane_save(lane_decode(D, 0), (int*)(rt.lds + D.table));
+    if (l >= 1) {
+      const JobDesc& B = sh.pull[l];
+      if (B.n_maps > 0 && B.table >= 0 && B.passes == 1) lane_save(lane_decode(B, 0), (int*)(rt.lds + B.table));
+    }
+  }
+  __syncthreads();
+}
+
 #define STAMP(i)                                                                              \
   do {                                                                                        \
     if (stamp) status->stamps[i] = wall_clock64();                                            \
@@ -815,6 +879,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
   rt.sh = &sh; rt.status = status; rt.lds = lds; rt.rank = rank; rt.spin_limit = a.spin_limit;
   rt.dbg = false;
   flow_load(rt);
+  flow_prepare_jobs(rt);
 
   const int n_conv = uni(F.n_conv), n_fc = uni(F.n_fc), n_classes = Pp->n_classes;
   const LayerDev& Lc = sh.L[n_conv - 1];           // last convolutional layer
