@@ -170,6 +170,12 @@ int cnn_mode_supported(cnn_t* net, int mode);
  * for bit.  Synchronises. */
 int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride);
 
+/* Stage and persistent modes: whether wide convolutional layers (full table, at least 64 output
+ * maps and 256 inputs x taps per output) run their forward pass as an implicit GEMM on the matrix
+ * cores (fp32 MFMA) -- on by default -- or through the vector kernel like every other layer.
+ * Results agree to rounding.  Weights and tables are kept.  Synchronises. */
+int cnn_set_matrix_cores(cnn_t* net, int on);
+
 /* Persistent mode: number of workgroups of the cooperative launch (0 = automatic: the
  * largest stage's work items, capped at the number of compute units).  Values above what
  * can be co-resident are clamped. */

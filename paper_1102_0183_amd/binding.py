@@ -57,6 +57,7 @@ def lib():
             "cnn_get_mode": (C.c_int, [vp]),
             "cnn_mode_supported": (C.c_int, [vp, C.c_int]),
             "cnn_set_team": (C.c_int, [vp, C.c_int, C.c_int]),
+            "cnn_set_matrix_cores": (C.c_int, [vp, C.c_int]),
             "cnn_set_grid": (C.c_int, [vp, C.c_int]),
             "cnn_set_spin_limit": (C.c_int, [vp, C.c_uint]),
             "cnn_set_barrier": (C.c_int, [vp, C.c_int]),
@@ -81,7 +82,7 @@ EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_create"
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
-           "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
+           "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
            "cnn_last_error"]
 
@@ -206,6 +207,9 @@ class Cnn:
 
     def set_team(self, n_ranks=0, xcd_stride=0):
         self._ck(lib().cnn_set_team(self._h, int(n_ranks), int(xcd_stride)), "cnn_set_team")
+
+    def set_matrix_cores(self, on):
+        self._ck(lib().cnn_set_matrix_cores(self._h, 1 if on else 0), "cnn_set_matrix_cores")
 
     def set_grid(self, n_workgroups):
         self._ck(lib().cnn_set_grid(self._h, int(n_workgroups)), "cnn_set_grid")

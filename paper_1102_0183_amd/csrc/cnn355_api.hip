@@ -141,6 +141,14 @@ int parse_arch(const char* arch, std::vector<ArchLayer>& out, std::string* err) 
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Does a convolutional layer go to the matrix cores?  Only where the contraction is really dense:
+// at least 64 output maps, at least 256 terms per output (input maps x kernel taps), and a map that
+// one wavefront set can tile (32-pixel tiles, at most 4 per wavefront).  The table must be full.
+bool mfma_shape_ok(int Mi, int K, int Mo, int Ho, int Wo) {
+  const long long Kd = (long long)Mi * K * K, P = (long long)Ho * Wo;
+  return Mo >= 64 && Kd >= 256 && P >= 16 && P <= MAX_TILE_PIX && (P + 31) / 32 <= (WG / 64) * 4;
+}
 int ceil_log2(int v) {
   int l = 0;
   while ((1 << l) < v) ++l;
@@ -181,6 +189,8 @@ struct cnn {
   int* d_fe_src = nullptr;
   float* d_fe_out = nullptr;
   float* d_fe_batch = nullptr;  // resident mode: front-end outputs of FE_BATCH images at a time
+  float* d_mm_part = nullptr;   // partial sums of the matrix-core forward pass (one layer at a time)
+  int use_mfma = 1;
   struct ConvBuf {
     float *act, *out, *delta;
     uint8_t* arg;
@@ -244,6 +254,13 @@ size_t carve(cnn* net, void* base) {
   net->d_fe_src = c.take<int>(A[0].maps);
   net->d_fe_out = c.take<float>((size_t)A[0].maps * A[0].h * A[0].w);
   net->d_fe_batch = c.take<float>((size_t)FE_BATCH * A[0].maps * A[0].h * A[0].w);
+  {
+    size_t mm = 0;
+    for (size_t l = 1; l < A.size(); ++l)
+      if (A[l].kind == CNN_LAYER_CONV && mfma_shape_ok(A[l - 1].maps, A[l].K, A[l].maps, A[l].h, A[l].w))
+        mm = std::max(mm, (size_t)MFMA_MAX_SLICES * A[l].maps * A[l].h * A[l].w);
+    net->d_mm_part = c.take<float>(mm);
+  }
   net->d_flow = c.take<FlowDev>(1);
   {  // resident mode: tagged exchange buffers, sized for any team (see plan_flow for the split)
     size_t words = 0, last_maps = 0, first_fc = 0;
@@ -399,6 +416,22 @@ int check_plan(cnn* net) {
       case ST_FRONTEND:
         if (st.n_items * WG < P.fe.n_filters * P.fe.H * P.fe.W) return bad(s, "pixels not covered");
         break;
+      case ST_CONV_FWD_MFMA: {
+        const int KK = L.K * L.K, HiWi = L.Hi * L.Wi, Pn = L.Ho * L.Wo;
+        const int NT = (Pn + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
+        const int WP = st.chunk * KK + 1 + ((st.chunk * KK) & 1);
+        if (!L.full_table || !mfma_shape_ok(L.Mi, L.K, L.Mo, L.Ho, L.Wo)) return bad(s, "layer not fit for the matrix-core kernel");
+        if (st.chunk < 1 || (long long)st.chunk * HiWi + 32LL * WP + (long long)st.chunk * KK > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
+        if (st.n_tiles < 1 || st.n_tiles > L.Mi || st.n_items != ((L.Mo + 31) / 32) * st.n_tiles) return bad(s, "slices do not cover the input maps");
+        if (st.rows_per_wg != st.n_tiles || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "too many partial-sum planes");
+        if (KW > 1 && (long long)KW * NT * 1024 > LDS_FLOATS) return bad(s, "k splits do not fit LDS");
+        if (((L.Mi + st.n_tiles - 1) / st.n_tiles) * (st.n_tiles - 1) >= L.Mi) return bad(s, "an empty slice");
+        break;
+      }
+      case ST_CONV_EPI:
+        if (st.n_items != L.Mo || st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
+        if (L.Ho * L.Wo > MAX_TILE_PIX) return bad(s, "map too large");
+        break;
       default:
         return bad(s, "unknown stage kind");
     }
@@ -446,6 +479,7 @@ int plan(cnn* net) {
       const cnn::ConvBuf& b = net->conv_buf[conv_i];
       L.act = b.act; L.out = b.out; L.delta = b.delta; L.arg = b.arg; L.argyx = b.argyx;
       L.csr_ptr = b.csr_ptr; L.csr_idx = b.csr_idx; L.csc_ptr = b.csc_ptr; L.csc_j = b.csc_j; L.csc_slot = b.csc_slot;
+      L.mm_part = net->d_mm_part;
       conv_of_dev[nl] = conv_i;
       build_tables(L.Mo, L.Mi, net->tables[conv_i], net->host_tables[conv_i]);
       L.max_conn = net->host_tables[conv_i].max_conn;
@@ -499,11 +533,29 @@ int plan(cnn* net) {
     s.kind = kind; s.layer = layer; s.n_items = n_items; s.barrier_after = barrier; s.train_only = train_only;
     return s;
   };
-  if (2 * nl + 4 > MAX_STAGES) return fail(&net->err, CNN_E_SHAPE, "too many stages");
+  if (3 * nl + 4 > MAX_STAGES) return fail(&net->err, CNN_E_SHAPE, "too many stages");
   if (fe) add(ST_FRONTEND, 0, (net->fe_n * A[0].h * A[0].w + WG - 1) / WG, 1, 0);
   for (int l = 0; l < nl; ++l) {  // forward, bottom up
     LayerDev& L = P.layers[l];
-    if (L.kind == L_CONV) {
+    if (L.kind == L_CONV && net->use_mfma && L.full_table && mfma_shape_ok(L.Mi, L.K, L.Mo, L.Ho, L.Wo)) {
+      // wide layer: implicit GEMM on the matrix cores, the contraction split over workgroups, then
+      // a second stage that adds the partial sums and does what follows the sum
+      const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
+      const int KK = L.K * L.K, HiWi = L.Hi * L.Wi, P = L.Ho * L.Wo;
+      const int NT = (P + 31) / 32, waves = WG / 64;
+      const int KW = NT >= waves ? 1 : waves / NT;
+      const int RT = (L.Mo + 31) / 32;
+      (void)KW;  // the k splits inside a workgroup are added there: one plane of partial sums per work item
+      int KS = std::max(1, std::min({n_cu / RT, L.Mi, MFMA_MAX_SLICES}));
+      const int per = (L.Mi + KS - 1) / KS;
+      KS = (L.Mi + per - 1) / per;
+      const int IC = std::min(per, (LDS_FLOATS - 64) / (HiWi + 33 * KK + 2));
+      if (IC < 1) return fail(&net->err, CNN_E_SHAPE, "an input map does not fit the LDS staging area of the matrix-core kernel");
+      Stage& s = add(ST_CONV_FWD_MFMA, l, RT * KS, 1, 0);
+      s.n_tiles = KS; s.chunk = IC; s.rows_per_wg = KS;
+      Stage& e = add(ST_CONV_EPI, l, L.Mo, 1, 0);
+      e.rows_per_wg = KS;
+    } else if (L.kind == L_CONV) {
       Stage& s = add(ST_CONV_FWD, l, 0, 1, 0);
       int rc = plan_conv_fwd(L, s, &net->err);
       if (rc) return rc;
@@ -894,7 +946,7 @@ int cnn_plan_text(const char* arch, char* buf, size_t n) {
       tmp.tables.emplace_back((size_t)tmp.arch[l].maps * tmp.arch[l - 1].maps, (uint8_t)1);
   rc = plan(&tmp);
   if (rc) { g_err = tmp.err; return rc; }
-  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad"};
+  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad", "conv_mfma", "conv_epi"};
   std::string out;
   char line[256];
   for (int s = 0; s < tmp.prog.n_stages; ++s) {
@@ -1068,6 +1120,19 @@ int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride) {
     net->mode = CNN_MODE_PERSISTENT;
     return fail(&net->err, CNN_E_STATE, net->flow_why);
   }
+  return CNN_OK;
+}
+
+int cnn_set_matrix_cores(cnn_t* net, int on) {
+  if (!net) return CNN_E_ARG;
+  if ((on != 0) == (net->use_mfma != 0)) return CNN_OK;
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  net->use_mfma = on ? 1 : 0;
+  // re-plan the stages only: tables, weights and everything else on the device stay as they are
+  int rc = plan(net);
+  if (rc) return rc;
+  HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowDev), hipMemcpyHostToDevice));
   return CNN_OK;
 }
 

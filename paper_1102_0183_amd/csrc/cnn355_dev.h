@@ -58,6 +58,7 @@ struct LayerDev {
   const CNN_GLOBAL int* csc_ptr;  // [Mi+1] backward table (C_BP of Sec. 3.1): input map i -> entries
   const CNN_GLOBAL int* csc_j;    // [n_conn] output map of every entry
   const CNN_GLOBAL int* csc_slot; // [n_conn] weight slot of every entry (WIDX_BP of Sec. 3.1)
+  CNN_GLOBAL float* mm_part;      // [slices][Mo][Ho*Wo] partial sums of the matrix-core forward pass (shared scratch)
 };
 
 enum StageKind : int {
@@ -68,7 +69,10 @@ enum StageKind : int {
   ST_FC_BWD = 5,     // hidden fully connected layer: pull deltas + update its weights
   ST_CONV_BWD = 6,   // pull deltas through a convolutional layer
   ST_CONV_WGRAD = 7, // convolutional weight gradients + update
+  ST_CONV_FWD_MFMA = 8, // wide convolutional layer as an implicit GEMM on the matrix cores: partial sums
+  ST_CONV_EPI = 9,      // ... then: sum of the partial sums + bias + tanh + max-pool + arg-max
 };
+constexpr int MFMA_MAX_SLICES = 64;  // partial-sum slices (splits of the contraction) per layer
 
 struct Stage {
   int kind;
@@ -82,7 +86,7 @@ struct Stage {
   int chunk;          // maps staged per pass (CONV_FWD: input maps, CONV_BWD: output maps, CONV_WGRAD: input maps)
   int tw_log2;        // log2 of the lane group width used when staging one map; CONV_BWD: log2 of the pixel tile
   int pix_per_thread; // CONV_FWD: 1 or 2
-  int rows_per_wg;    // FC_FWD: neurons per work item (power of two, 1..16)
+  int rows_per_wg;    // FC_FWD: neurons per work item (power of two, 1..16); CONV_FWD_MFMA / CONV_EPI: partial-sum slices
   int cm_log2;        // FC_BWD / HEAD: log2 of columns per tile
 };
 

@@ -295,6 +295,219 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
 }
 
 // ------------------------------------------------------------------------------------------
+// FP of a wide, fully connected-table convolutional layer as an implicit GEMM on the matrix
+// cores (fp32 MFMA).  C[j][p] = sum_k W[j][k] X[k][p] with k = (input map i, tap ky, kx) and
+// p = output pixel: W is the layer's filter block as it lies in memory (row j holds Mi*K*K
+// contiguous floats), X is never formed: X[k][p] = in_i[(y(S+1)+ky) Wi + x(S+1)+kx] is the
+// sum of an offset that depends on k only and one that depends on p only.
+// Work item = (tile of 32 output maps, slice of the input maps).  The slice's input maps and
+// the 32 x (maps*K*K) block of filters are staged through LDS chunk by chunk; each wavefront
+// owns one (or several) tiles of 32 pixels, and when there are fewer pixel tiles than
+// wavefronts the spare ones split the chunk's k range.  v_mfma_f32_32x32x2_f32: lane l feeds
+// A[l%32][l/32] and B[l/32][l%32], two k per instruction, 16 accumulators per lane.
+// The partial sums of every (slice, k split) go to their own plane of mm_part; ST_CONV_EPI
+// adds the planes in a fixed order (no atomics: results do not depend on timing).
+// ------------------------------------------------------------------------------------------
+typedef float v16f __attribute__((ext_vector_type(16)));
+constexpr int MM_TPW = 4;  // pixel tiles one wavefront can carry (64 accumulators)
+
+__device__ void conv_fwd_mfma_item(const LayerDev& L, const Stage& st, int item, const gfloat* in, float* lds) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int lrow = lane & 31, lk = lane >> 5;
+  const int KS = st.n_tiles;
+  const int jt = item / KS, ks = item - jt * KS;
+  const int j0 = jt * 32;
+  const int Mi = L.Mi, Mo = L.Mo, K = L.K, KK = K * K, HiWi = L.Hi * L.Wi, Wi = L.Wi, Wo = L.Wo;
+  const int P = L.Ho * L.Wo, stride = L.S + 1;
+  const int per = (Mi + KS - 1) / KS;
+  const int i_lo = ks * per, i_hi = min(Mi, i_lo + per);
+  const int IC = st.chunk;
+  const int WP = IC * KK + 1 + ((IC * KK) & 1);   // odd row pitch: the 32 rows of a column lie in 32 banks
+  const int NT = (P + 31) >> 5;
+  constexpr int WAVES = WG / 64;
+  const int NTw = min(NT, WAVES);
+  const int KW = (NT >= WAVES) ? 1 : WAVES / NT;
+  const int kw = (NT >= WAVES) ? 0 : wave / NT;
+  const int tw = (NT >= WAVES) ? wave : wave - kw * NT;
+  const bool wave_on = kw < KW;
+
+  float* lds_in = lds;                         // [IC][Hi*Wi]
+  float* lds_w = lds + IC * HiWi;              // [32][WP]
+  int* koff = (int*)(lds_w + 32 * WP);         // [IC*KK] offset of k inside the staged maps
+
+  for (int x = tid; x < IC * KK; x += WG) {
+    const int c = x / KK, t = x - c * KK;
+    const int ky = t / K, kx = t - ky * K;
+    koff[x] = c * HiWi + ky * Wi + kx;
+  }
+  int pbase[MM_TPW];
+#pragma unroll
+  for (int t = 0; t < MM_TPW; ++t) {
+    const int p = (tw + t * NTw) * 32 + lrow;
+    const int y = p / Wo, x = p - y * Wo;
+    pbase[t] = (p < P) ? (y * Wi + x) * stride : 0;
+  }
+  v16f acc[MM_TPW];
+#pragma unroll
+  for (int t = 0; t < MM_TPW; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  const int n_my_tiles = wave_on ? ((NT - tw + NTw - 1) / NTw) : 0;   // 1 unless there are more than 16 pixel tiles
+
+  for (int ic0 = i_lo; ic0 < i_hi; ic0 += IC) {
+    const int n_ic = min(IC, i_hi - ic0);
+    const int kc = n_ic * KK;
+    {  // stage the chunk, eight loads in flight per lane: the inputs (one contiguous block) ...
+      const gfloat* src = in + (size_t)ic0 * HiWi;
+      const int n_in = n_ic * HiWi;
+      for (int x0 = 0; x0 < n_in; x0 += 8 * WG) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[min(x0 + u * WG + tid, n_in - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (x0 + u * WG + tid < n_in) lds_in[x0 + u * WG + tid] = v[u];
+      }
+      // ... and the 32 filter rows (one contiguous run of kc floats each; 32 lanes per row)
+      const int r = tid >> 5, xl = tid & 31;
+      const bool row_ok = j0 + r < Mo;
+      const gfloat* wr = L.w + ((size_t)min(j0 + r, Mo - 1) * Mi + ic0) * KK;
+      for (int x0 = 0; x0 < kc; x0 += 8 * 32) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = wr[min(x0 + u * 32 + xl, kc - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (x0 + u * 32 + xl < kc) lds_w[r * WP + x0 + u * 32 + xl] = row_ok ? v[u] : 0.f;
+      }
+    }
+    __syncthreads();
+    if (wave_on) {
+      // this wavefront's share of the chunk's k range (even bounds: two k per instruction);
+      // four instructions' operands are fetched from LDS together
+      const int kper = (((kc + KW - 1) / KW) + 1) & ~1;
+      const int k_lo = kw * kper, k_hi = min(kc, k_lo + kper);
+      for (int kk = k_lo; kk < k_hi; kk += 8) {
+        float a[4];
+        int ko[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int k = kk + 2 * u + lk;
+          a[u] = (k < k_hi) ? lds_w[lrow * WP + min(k, kc - 1)] : 0.f;
+          ko[u] = koff[min(k, kc - 1)];
+        }
+#pragma unroll
+        for (int t = 0; t < MM_TPW; ++t)
+          if (t < n_my_tiles) {
+            float b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) b[u] = lds_in[ko[u] + pbase[t]];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc[t], 0, 0, 0);
+          }
+      }
+    }
+    __syncthreads();
+  }
+  // the k splits inside the workgroup are added here (through LDS, in a fixed order), so that one
+  // work item leaves one plane of partial sums
+  gfloat* plane = L.mm_part + (size_t)ks * Mo * P;
+  if (KW > 1) {
+    float* red = lds;  // [KW][NT][32 rows][32 pixels]
+    if (wave_on) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        red[((kw * NT + tw) * 32 + (v >> 2) * 8 + lk * 4 + (v & 3)) * 32 + lrow] = acc[0][v];
+    }
+    __syncthreads();
+    for (int x = tid; x < NT * 1024; x += WG) {
+      const int t = x >> 10, row = (x >> 5) & 31, col = x & 31;
+      float sum = 0.f;
+      for (int q = 0; q < KW; ++q) sum += red[((q * NT + t) * 32 + row) * 32 + col];
+      const int p = t * 32 + col, j = j0 + row;
+      if (p < P && j < Mo) plane[(size_t)j * P + p] = sum;
+    }
+    __syncthreads();
+  } else if (wave_on) {
+#pragma unroll
+    for (int t = 0; t < MM_TPW; ++t)
+      if (t < n_my_tiles) {
+        const int p = (tw + t * NTw) * 32 + lrow;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int j = j0 + (v >> 2) * 8 + lk * 4 + (v & 3);
+          if (p < P && j < Mo) plane[(size_t)j * P + p] = acc[t][v];
+        }
+      }
+  }
+}
+
+// Second half of the matrix-core forward pass.  Work item = output map j: add the planes of
+// partial sums (lane groups share the planes, eight loads in flight per lane, fixed order), bias,
+// scaled tanh, store; then the pooled maximum with the index of the first maximum in row-major
+// order, exactly as the one-stage forward kernel does.
+__device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* lds) {
+  const int tid = threadIdx.x;
+  const int Wo = L.Wo, Ho = L.Ho, P = Ho * Wo, Mo = L.Mo;
+  const int n_planes = st.rows_per_wg;
+  float* lds_out = lds;                 // [P]
+  float* lds_part = lds + MAX_TILE_PIX; // [G][P] partial sums of the plane groups
+  const float b = L.bias[j];
+  // G lane groups of P lanes each take every G-th block of 8 planes
+  const int G = (P >= WG) ? 1 : min(WG / P, (n_planes + 7) / 8);
+  const int grp = (P >= WG) ? 0 : tid / P;
+  for (int p0 = 0; p0 < P; p0 += WG) {
+    const int p = (P >= WG) ? p0 + tid : tid - grp * P;
+    const bool on = grp < G && p < P;
+    float s = 0.f;
+    if (on)
+      for (int s0 = grp * 8; s0 < n_planes; s0 += G * 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = L.mm_part[((size_t)min(s0 + u, n_planes - 1) * Mo + j) * P + p];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (s0 + u < n_planes) ? v[u] : 0.f;
+      }
+    if (G > 1) {
+      if (on) lds_part[grp * P + p] = s;
+      __syncthreads();
+      if (tid < P) {
+        s = 0.f;
+        for (int q = 0; q < G; ++q) s += lds_part[q * P + tid];
+      }
+    }
+    if ((G > 1) ? (tid < P) : on) {
+      const int pp = (G > 1) ? tid : p;
+      const float a = act_f(s + b);
+      L.act[(size_t)j * P + pp] = a;
+      lds_out[pp] = a;
+    }
+  }
+  __syncthreads();
+  const int Kp = L.Kp;
+  if (Kp > 1) {
+    const int Wp = L.Wp;
+    const int nq = L.Hp * Wp;
+    for (int q = tid; q < nq; q += WG) {
+      const int py = q / Wp, px = q - py * Wp;
+      const float* win = lds_out + py * Kp * Wo + px * Kp;
+      float best = win[0];
+      int wy = 0, wx = 0;
+      for (int dy = 0; dy < Kp; ++dy)
+        for (int dx = 0; dx < Kp; ++dx) {
+          const float v = win[dy * Wo + dx];
+          if (v > best) { best = v; wy = dy; wx = dx; }
+        }
+      const size_t o = (size_t)j * nq + q;
+      L.out[o] = best;
+      L.arg[o] = (uint8_t)(wy * Kp + wx);
+      L.argyx[o] = ((py * Kp + wy) << 16) | (px * Kp + wx);
+    }
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
 // Hidden fully connected layer forward (Sec. 2.4) + scaled tanh.  Work item = rows_per_wg
 // neurons; the lanes of a neuron stride over its inputs, then reduce by wave shuffles and LDS.
 // ------------------------------------------------------------------------------------------
@@ -799,6 +1012,10 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
     conv_bwd_item(L, P.layers[st.layer - 1], st, item, lds);
   } else if constexpr (KIND == ST_CONV_WGRAD) {
     conv_wgrad_item(L, st, item, in, ctx, lds);
+  } else if constexpr (KIND == ST_CONV_FWD_MFMA) {
+    conv_fwd_mfma_item(L, st, item, in, lds);
+  } else if constexpr (KIND == ST_CONV_EPI) {
+    conv_epi_item(L, st, item, lds);
   }
 }
 
@@ -814,6 +1031,8 @@ __device__ void run_stage_items(const ProgramDev& P, const Stage& st, int first,
     RUN_KIND(ST_FC_BWD)
     RUN_KIND(ST_CONV_BWD)
     RUN_KIND(ST_CONV_WGRAD)
+    RUN_KIND(ST_CONV_FWD_MFMA)
+    RUN_KIND(ST_CONV_EPI)
 #undef RUN_KIND
     default: break;
   }
@@ -853,6 +1072,8 @@ STAGE_KERNEL(k_head, ST_HEAD)
 STAGE_KERNEL(k_fc_bwd, ST_FC_BWD)
 STAGE_KERNEL(k_conv_bwd, ST_CONV_BWD)
 STAGE_KERNEL(k_conv_wgrad, ST_CONV_WGRAD)
+STAGE_KERNEL(k_conv_fwd_mfma, ST_CONV_FWD_MFMA)
+STAGE_KERNEL(k_conv_epi, ST_CONV_EPI)
 
 // Fixed image-processing layer for a whole batch at once (it depends on no weight, so it need not
 // sit inside the on-line chain): image t of `images` -> out[t], one workgroup per WG output pixels.
@@ -1026,6 +1247,8 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
     case ST_FC_BWD: hipLaunchKernelGGL(k_fc_bwd, grid, block, 0, stream, d_prog, s, d_status, a); break;
     case ST_CONV_BWD: hipLaunchKernelGGL(k_conv_bwd, grid, block, 0, stream, d_prog, s, d_status, a); break;
     case ST_CONV_WGRAD: hipLaunchKernelGGL(k_conv_wgrad, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_FWD_MFMA: hipLaunchKernelGGL(k_conv_fwd_mfma, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_EPI: hipLaunchKernelGGL(k_conv_epi, grid, block, 0, stream, d_prog, s, d_status, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

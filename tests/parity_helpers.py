@@ -119,3 +119,24 @@ def layer_bounds(o):
         off += n
     assert off == o.num_weights
     return out
+
+
+def lockstep_train(g, o, imgs, labs, lr):
+    """Train GPU and oracle side by side, image by image.  The two sides sum in different orders,
+    so once in many thousand pooling rectangles their winners differ at a near-tie and the
+    trajectories would part for good; the oracle is therefore told the GPU's winners and adopts
+    one only where its own two best candidates are closer than the activation tolerance -- it
+    refuses otherwise, which fails the test.  Returns the number of winners adopted."""
+    pools = [l for l in range(1, o.num_layers) if o.layer_info(l)["kind"] == KIND_POOL]
+    d_imgs = to_dev(imgs)
+    sz = g.image_size
+    adopted = 0
+    for t in range(len(labs)):
+        g.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], int(labs[t]), lr)
+        o.forward(imgs[t])
+        for l in pools:
+            a, r = o.adopt_argmax_hint(l, g.argmax(l), TOL_ACT)
+            assert r == 0, "step %d layer %d: GPU winner is not a near-tie of the oracle's" % (t, l)
+            adopted += a
+        o.backward_update(int(labs[t]), lr)
+    return adopted

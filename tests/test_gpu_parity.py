@@ -194,6 +194,30 @@ def test_resident_mode_repeats_and_agrees_with_stages(name):
         assert rel_err(w, w_ref) <= 1e-5, variant
 
 
+@pytest.mark.parametrize("name", ["cfg2b", "cfg3", "cfg4a", "cfg4b"])
+def test_matrix_core_forward_matches_the_vector_kernel(name):
+    """Wide layers run their forward pass as an implicit GEMM on the matrix cores; switching that
+    off sends them through the vector kernel.  Both must meet the oracle's activations, and each
+    other to rounding; the plan must really contain a matrix-core stage for these networks."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, flush=True)
+    assert "conv_mfma" in binding.plan_text(wl.arch)
+    g, o = build_pair(wl)
+    img = synth.images(wl, 1)[0]
+    d_img = to_dev(img)
+    o.forward(img)
+    acts = {}
+    for on in (True, False):
+        g.set_matrix_cores(on)
+        g.forward(d_img)
+        g.synchronize()
+        compare_forward_state(g, o)
+        acts[on] = [g.activation(l) for l in range(1, g.num_layers)]
+    for a, b in zip(acts[True], acts[False]):
+        assert rel_err(a, b) <= TOL_ACT
+    g.close()
+
+
 def test_update_order_old_weights_feed_the_deltas():
     """A large learning rate makes a wrong order (weights adjusted before the deltas below
     them were pulled) visible after a single step."""
