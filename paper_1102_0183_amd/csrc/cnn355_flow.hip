@@ -896,7 +896,8 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     const unsigned int tag = a.epoch_base + (unsigned int)t + 1u;
     const unsigned int par = tag & 1u;
     const bool taps = (t == a.n_images - 1);
-    const bool stamp = taps && rank == 0 && tid == 0;
+    // timestamps: the last image but one (the last also stores the parity taps)
+    const bool stamp = (a.n_images > 1 ? t == a.n_images - 2 : taps) && rank == 0 && tid == 0;
     rt.dbg = stamp;
     const int label = a.labels ? a.labels[t] : a.label_imm;
     bool train = a.train != 0;
@@ -966,42 +967,64 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     for (int f = 1; f < n_fc; ++f) {
       const LayerDev& L = sh.L[n_conv + f];
       float* y = lds + F.fc[f].o_act;
-      flow_matvec(lds + F.fc[f].o_w, lds + F.fc[f].o_b, lds + F.fc[f - 1].o_act, y, L.n_out, L.n_in);
+      flow_matvec(lds + F.fc[f].o_w, lds + F.fc[f].o_b, lds + F.fc[f - 1].o_act, y, uni(L.n_out), uni(L.n_in));
       if (!L.is_output) {
         for (int k = tid; k < L.n_out; k += WG) y[k] = f_act(y[k]);
         __syncthreads();
       }
     }
     STAMP(32);
-    {  // soft-max, cross-entropy error, output delta  delta_k = p_k - [k == label]
-      DSTAMP(111);
-      const LayerDev& L = sh.L[n_conv + n_fc - 1];
+    // soft-max, cross-entropy error, output delta  delta_k = p_k - [k == label].  With at most 64
+    // classes every wavefront works them out for itself (lane k holds class k), so nobody waits
+    // for a broadcast: the output layer's BP below reads delta_k straight from its own wave.
+    float dreg = 0.f;
+    const LayerDev& Lo = sh.L[n_conv + n_fc - 1];
+    const int N = uni(Lo.n_out);
+    const bool wave_softmax = N <= 64;
+    {
       float* y = lds + F.fc[n_fc - 1].o_act;
       float* d = lds + F.fc[n_fc - 1].o_delta;
-      const int N = L.n_out;
-      if (tid < 64) {
-        float mx = -INFINITY;
-        for (int k = tid; k < N; k += 64) mx = fmaxf(mx, y[k]);
-        mx = f_wave_max(mx);
-        float z = 0.f;
-        for (int k = tid; k < N; k += 64) z += expf(y[k] - mx);
-        z = f_wave_sum(z);
-        for (int k = tid; k < N; k += 64) {
-          const float p = expf(y[k] - mx) / z;
-          y[k] = p;
-          d[k] = p - (k == label ? 1.f : 0.f);
+      if (wave_softmax) {
+        const int k = tid & 63;
+        const float yk = (k < N) ? y[k] : -INFINITY;
+        const float mx = f_wave_max(yk);
+        const float e = (k < N) ? expf(yk - mx) : 0.f;
+        const float z = f_wave_sum(e);
+        const float p = e / z;
+        dreg = p - (k == label ? 1.f : 0.f);
+        if (tid < N) {
           if (rank == 0) {
             if (a.probs_out) a.probs_out[t * n_classes + k] = p;
             if (train && k == label) status->loss = -logf(p);
           }
+          if (taps || n_fc == 1) d[k] = dreg;
+          if (taps && rank == 0) Lo.act[k] = p;
         }
+        if (n_fc == 1) __syncthreads();  // the first FC layer's BP reads the deltas from LDS
+      } else {
+        if (tid < 64) {
+          float mx = -INFINITY;
+          for (int k = tid; k < N; k += 64) mx = fmaxf(mx, y[k]);
+          mx = f_wave_max(mx);
+          float z = 0.f;
+          for (int k = tid; k < N; k += 64) z += expf(y[k] - mx);
+          z = f_wave_sum(z);
+          for (int k = tid; k < N; k += 64) {
+            const float p = expf(y[k] - mx) / z;
+            y[k] = p;
+            d[k] = p - (k == label ? 1.f : 0.f);
+            if (rank == 0) {
+              if (a.probs_out) a.probs_out[t * n_classes + k] = p;
+              if (train && k == label) status->loss = -logf(p);
+              if (taps) Lo.act[k] = p;
+            }
+          }
+        }
+        __syncthreads();
       }
-      DSTAMP(112);
-      __syncthreads();
-      DSTAMP(113);
     }
     if (taps && rank == 0)
-      for (int f = 0; f < n_fc; ++f) {
+      for (int f = 0; f + 1 < n_fc; ++f) {
         const LayerDev& L = sh.L[n_conv + f];
         for (int k = tid; k < L.n_out; k += WG) L.act[k] = lds[F.fc[f].o_act + k];
       }
@@ -1016,7 +1039,8 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       const float* d = lds + F.fc[f].o_delta;
       const float* v = lds + F.fc[f - 1].o_act;
       float* dprev = lds + F.fc[f - 1].o_delta;
-      const int n_in = L.n_in, n_out = L.n_out;
+      const int n_in = uni(L.n_in), n_out = uni(L.n_out);
+      const bool from_reg = wave_softmax && f == n_fc - 1;
       for (int m = tid; m < n_in; m += WG) {
         const float vm = v[m];
         float g = 0.f;
@@ -1026,7 +1050,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
           for (int u = 0; u < 4; ++u) {
             const int k = min(k0 + u, n_out - 1);
             wv[u] = W[k * n_in + m];
-            dv[u] = d[k];
+            dv[u] = from_reg ? lane_f(dreg, k) : d[k];
           }
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
@@ -1041,9 +1065,10 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
         dprev[m] = g * f_dact(vm);
       }
       for (int k = tid; k < n_out; k += WG) {
-        if (g_out) { if (rank == 0) g_out[L.b_canon + k] = d[k]; }
-        else b[k] = fmaf(-lr, d[k], b[k]);
-        if (taps && rank == 0) L.delta[k] = d[k];
+        const float dk = from_reg ? dreg : d[k];   // tid < 64 here: lane k of wave 0
+        if (g_out) { if (rank == 0) g_out[L.b_canon + k] = dk; }
+        else b[k] = fmaf(-lr, dk, b[k]);
+        if (taps && rank == 0) L.delta[k] = dk;
       }
       __syncthreads();
     }
@@ -1054,15 +1079,28 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       const float* d = lds + F.fc[0].o_delta;
       const float* vcol = lds + F.conv[n_conv - 1].o_pool;
       float* dconv = lds + F.conv[n_conv - 1].o_delta;
+      const int* yxc = (const int*)(lds + F.conv[n_conv - 1].o_yx);
+      const FlowConv& Cc = F.conv[n_conv - 1];
+      const int Moc = uni(Lc.Mo);
       const int wave = tid >> 6, lane = tid & 63;
+      const FDiv dN(n1), dHW(HWc);
       for (int c = wave; c < ncols; c += WG / 64) {
         float s = 0.f;
         for (int k = lane; k < n1; k += 64) s = fmaf(wc[c * n1 + k], d[k], s);
         s = f_wave_sum(s);
-        if (lane == 0) dconv[c] = s * f_dact(vcol[c]);
+        if (lane == 0) {
+          const float dc = s * f_dact(vcol[c]);
+          dconv[c] = dc;
+          const int am = dHW.div(c), q = c - am * HWc;
+          const size_t o = (size_t)(rank + am * G) * HWc + q;
+          if (n_conv >= 2) {  // the layer below pulls through these: on their way at once
+            put_f(Cc.x_delta + (size_t)par * Moc * HWc + o, dc, tag);
+            put_i(Cc.x_yx + (size_t)par * Moc * HWc + o, yxc[c], tag);
+          }
+          if (taps) Lc.delta[o] = dc;
+        }
       }
       __syncthreads();
-      const FDiv dN(n1), dHW(HWc);
       for (int x = tid; x < ncols * n1; x += WG) {
         const int c = dN.div(x), k = x - c * n1;
         const float g = d[k] * vcol[c];
@@ -1078,7 +1116,6 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
         else b[k] = fmaf(-lr, d[k], b[k]);
         if (taps && rank == 0) L1.delta[k] = d[k];
       }
-      __syncthreads();
     }
     STAMP(35);
     // ---- BP + AW, convolutional layers, top down ----
@@ -1090,7 +1127,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       const int nm = n_mine(Mo, rank, G);
       const float* dl = lds + C.o_delta;
       const int* yx = (const int*)(lds + C.o_yx);
-      if (l >= 1 || taps) {
+      if (l < n_conv - 1 && (l >= 1 || taps)) {  // (the last layer's went out with the first FC layer's BP)
         const FDiv dHW(HW);
         for (int x = tid; x < nm * HW; x += WG) {
           const int am = dHW.div(x), q = x - am * HW;
