@@ -296,6 +296,13 @@ class Cnn:
                  "cnn_get_stage_times")
         return [(float(buf[2 * k]), float(buf[2 * k + 1])) for k in range(n.value)]
 
+    def resident_static_id(self):
+        """Development aid: which compiled-in network the resident plan equals (0: none)."""
+        f = lib().cnn355_resident_static_id
+        f.restype = C.c_int
+        f.argtypes = [C.c_void_p]
+        return int(f(self._h))
+
     def raw_stamps(self, n=128):
         """Development aid: device timestamps (100 MHz ticks) left by the last call."""
         buf = np.zeros(n, dtype=np.uint64)

@@ -12,6 +12,7 @@
 
 #include "../../include/cnn355.h"
 #include "cnn355_dev.h"
+#include "cnn355_flowspec.h"
 
 namespace cnn355 {
 hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const ProgramDev* d_prog, int s,
@@ -23,8 +24,9 @@ int persistent_max_blocks_per_cu();
 void read_dbg(unsigned long long* out);
 hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, const float* d_images,
                                  long long image_stride, int n_images, int items_per_image, float* d_out);
-hipError_t launch_resident(int grid, size_t lds_bytes, hipStream_t stream, const ProgramDev* d_prog,
-                           const FlowDev* d_flow, StatusDev* d_status, const RunArgs& a);
+hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
+                           const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a);
+int resident_static_id(const FlowSpec& z);
 }  // namespace cnn355
 
 using namespace cnn355;
@@ -203,8 +205,11 @@ struct cnn {
   std::vector<HostTable> host_tables;  // per convolutional layer, rebuilt by plan()
 
   // resident mode
-  FlowDev flow;                 // host copy with device pointers
-  FlowDev* d_flow = nullptr;
+  FlowSpec flow;                // the plan (plain integers)
+  FlowPtrs flow_ptrs;           // where the layers and the exchange buffers lie on the device
+  FlowSpec* d_flow = nullptr;
+  FlowPtrs* d_flow_ptrs = nullptr;
+  int flow_static_id = 0;       // > 0: the plan equals that of a kernel compiled for a fixed network
   tagged_t* d_xbuf = nullptr;   // every exchange buffer, one after the other
   size_t xbuf_words = 0;
   bool flow_ok = false;
@@ -261,7 +266,8 @@ size_t carve(cnn* net, void* base) {
         mm = std::max(mm, (size_t)MFMA_MAX_SLICES * A[l].maps * A[l].h * A[l].w);
     net->d_mm_part = c.take<float>(mm);
   }
-  net->d_flow = c.take<FlowDev>(1);
+  net->d_flow = c.take<FlowSpec>(1);
+  net->d_flow_ptrs = c.take<FlowPtrs>(1);
   {  // resident mode: tagged exchange buffers, sized for any team (see plan_flow for the split)
     size_t words = 0, last_maps = 0, first_fc = 0;
     for (size_t l = 1; l < A.size(); ++l) {
@@ -628,143 +634,68 @@ int plan(cnn* net) {
 }
 
 
-// Resident mode: choose the team, lay out every rank's LDS and the exchange buffers.  Sets
-// net->flow_ok; a network the mode cannot take keeps flow_ok = false with the reason in flow_why
-// (not an error: the other modes still run it).
+// Resident mode: choose the team, lay out every rank's LDS (flow_plan, shared with the kernels that
+// are compiled for fixed networks) and the exchange buffers.  Sets net->flow_ok; a network the mode
+// cannot take keeps flow_ok = false with the reason in flow_why (not an error: the other modes
+// still run it).
 void plan_flow(cnn* net) {
   const ProgramDev& P = net->prog;
-  FlowDev& F = net->flow;
-  std::memset(&F, 0, sizeof(F));
+  FlowSpec& Z = net->flow;
+  FlowPtrs& Q = net->flow_ptrs;
+  std::memset(&Z, 0, sizeof(Z));
+  std::memset(&Q, 0, sizeof(Q));
   net->flow_ok = false;
+  net->flow_static_id = 0;
   auto no = [&](const std::string& why) { net->flow_why = why; };
   int n_conv = 0;
   while (n_conv < P.n_layers && P.layers[n_conv].kind == L_CONV) ++n_conv;
   const int n_fc = P.n_layers - n_conv;
   if (n_conv < 1) return no("resident mode needs at least one convolutional layer");
-  if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1) return no("too many layers for resident mode");
-  int max_maps = 1;
-  for (int l = 0; l < n_conv; ++l) max_maps = std::max(max_maps, P.layers[l].Mo);
-  int stride = net->team_stride > 0 ? net->team_stride : 0;
-  int G = net->team_ranks > 0 ? net->team_ranks : max_maps;
-  const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
-  if (stride == 0) stride = (G <= n_cu / 8) ? 8 : 1;
-  if (stride != 1 && stride != 8) return no("team stride must be 1 or 8");
-  G = std::max(1, std::min({G, max_maps, n_cu / stride}));
-  F.G = G; F.stride = stride; F.n_conv = n_conv; F.n_fc = n_fc;
-
-  long long off = 0;
-  auto take = [&](long long n) { const long long o = off; off += (n + 3) / 4 * 4; return (int)std::min<long long>(o, 1 << 30); };
-  // Strip width for a correlation job of n_maps maps of rows x width pixels with up to max_cnt
-  // connections each: the one of {4, 5, 7} that leaves the least multiply-accumulate work per
-  // lane once the connections are shared over the spare lanes (the rule the kernel applies), the
-  // wider one on a tie; 0 = one pixel per lane (any stride, any kernel size).
-  auto strip_for = [](int K, int stride, int n_maps, int rows, int width, int max_cnt) {
-    if (stride != 1 || K < 2 || K > 5) return 0;
-    int best = 4;
-    long long best_cost = -1;
-    for (int sw : {4, 5, 7}) {
-      const long long U = (long long)n_maps * rows * ((width + sw - 1) / sw);
-      long long iters = max_cnt;
-      if (U < WG) {
-        const long long r_max = std::max<long long>(1, std::min<long long>(WG / U, max_cnt));
-        iters = (max_cnt + r_max - 1) / r_max;
-      }
-      const long long passes = (U + WG - 1) / WG;
-      const long long cost = passes * iters * (sw * K * K + (sw + 2 * K - 1) * K / 2);
-      if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best = sw; }
-    }
-    return best;
-  };
-  long long max_act = 1, max_part = (long long)FLOW_STRIP_MAX * WG, max_dall = 1, max_hwd = 0;
+  if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1)
+    return no("resident mode takes at most " + std::to_string(FLOW_MAX_CONV) + " convolutional and " +
+              std::to_string(FLOW_MAX_FC) + " fully connected layers");
+  Z.n_conv = n_conv; Z.n_fc = n_fc; Z.n_classes = P.n_classes;
+  for (int l = 0; l < n_conv; ++l) {
+    const LayerDev& L = P.layers[l];
+    ConvSpec& C = Z.conv[l];
+    C.Mi = L.Mi; C.Hi = L.Hi; C.Wi = L.Wi; C.Mo = L.Mo; C.Ho = L.Ho; C.Wo = L.Wo;
+    C.K = L.K; C.S = L.S; C.Kp = L.Kp; C.Hp = L.Hp; C.Wp = L.Wp;
+    C.max_conn = L.max_conn; C.max_back = net->host_tables[l].max_back; C.full_table = L.full_table;
+  }
+  for (int f = 0; f < n_fc; ++f) {
+    const LayerDev& L = P.layers[n_conv + f];
+    Z.fc[f].n_in = L.n_in; Z.fc[f].n_out = L.n_out; Z.fc[f].is_output = L.is_output;
+  }
+  switch (flow_plan(Z, net->team_ranks, net->team_stride, net->n_cu)) {
+    case FLOW_OK: break;
+    case FLOW_BAD_STRIDE: return no("team stride must be 1 or 8");
+    case FLOW_TOO_LARGE: return no("a layer is too large for resident mode");
+    case FLOW_NO_LDS: return no("the weights and maps one workgroup would hold exceed its LDS");
+    default: return no("resident mode cannot run this network");
+  }
+  // pointers: layers, tables, exchange buffers
   tagged_t* xb = net->d_xbuf;
   size_t xoff = 0;
   auto xtake = [&](size_t words) { tagged_t* p = xb ? xb + xoff : nullptr; xoff += words; return p; };
   for (int l = 0; l < n_conv; ++l) {
     const LayerDev& L = P.layers[l];
-    FlowConv& C = F.conv[l];
-    const cnn::HostTable& T = net->host_tables[l];
-    const int KK = L.K * L.K, HW = L.Hp * L.Wp;
-    C.n_own = (L.Mo + G - 1) / G;
-    C.n_own_below = l >= 1 ? (L.Mi + G - 1) / G : 0;
-    C.max_back = std::max(1, T.max_back);
-    C.o_in = take((long long)L.Mi * L.Hi * L.Wi);
-    C.o_wf = take((long long)C.n_own * L.max_conn * KK);
-    C.o_bf = take(C.n_own);
-    C.o_cidx = take((long long)C.n_own * L.max_conn);
-    C.o_ncf = take(C.n_own);
-    C.fwd_strip = strip_for(L.K, L.S + 1, C.n_own, L.Ho, L.Wo, L.max_conn);
-    if (l >= 1) {
-      C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
-      C.o_bj = take((long long)C.n_own_below * C.max_back);
-      C.o_ncb = take(C.n_own_below);
-      C.pull_strip = strip_for(L.K, 1, C.n_own_below, L.Hi, L.Wi, C.max_back);
-      max_dall = std::max<long long>(max_dall, (long long)L.Mo * HW);
-      max_hwd = std::max<long long>(max_hwd, (long long)(L.Hi + L.K - 1) * (L.Wi + L.K - 1));
-      max_part = std::max<long long>(max_part, (long long)C.n_own_below * L.Hi * L.Wi);
-    }
-    C.o_pool = take((long long)C.n_own * HW);
-    C.o_yx = take((long long)C.n_own * HW);
-    C.o_delta = take((long long)C.n_own * HW);
-    max_act = std::max<long long>(max_act, (long long)C.n_own * L.Ho * L.Wo);
-    max_part = std::max<long long>(max_part, (long long)C.n_own * L.Ho * L.Wo);
-    // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
-    long long n_w = (long long)C.n_own * L.max_conn * KK;
-    if (l >= 1) n_w = std::min(n_w, (long long)C.n_own_below * C.max_back * KK);
-    int rl2 = 0;
-    while (rl2 < 6 && (n_w << (rl2 + 1)) <= WG && (2 << rl2) <= HW) ++rl2;
-    C.wgrad_R_log2 = rl2;
-    const size_t small = (size_t)L.Mo * HW;
+    FlowConvPtrs& C = Q.conv[l];
+    C.w = L.w; C.bias = L.bias; C.act = L.act; C.out = L.out; C.arg = L.arg; C.argyx = L.argyx; C.delta = L.delta;
+    C.csr_ptr = L.csr_ptr; C.csr_idx = L.csr_idx; C.csc_ptr = L.csc_ptr; C.csc_j = L.csc_j; C.csc_slot = L.csc_slot;
+    C.w_canon = L.w_canon; C.b_canon = L.b_canon;
+    const size_t small = (size_t)L.Mo * L.Hp * L.Wp;
     C.x_out = (l + 1 < n_conv) ? xtake(2 * small) : nullptr;
     C.x_delta = (l >= 1) ? xtake(2 * small) : nullptr;
     C.x_yx = (l >= 1) ? xtake(2 * small) : nullptr;
-    if (L.Ho >= 32768 || L.Wo >= 65536) return no("map too large");
-    if ((long long)L.Mi * L.Hi * L.Wi >= (1 << 20) || (long long)L.Mo * L.Ho * L.Wo >= (1 << 20)) return no("layer too large");
   }
-  const LayerDev& Lc = P.layers[n_conv - 1];
-  const LayerDev& L1 = P.layers[n_conv];
-  F.n_col_ranks = std::min(G, Lc.Mo);
   for (int f = 0; f < n_fc; ++f) {
     const LayerDev& L = P.layers[n_conv + f];
-    FlowFc& Q = F.fc[f];
-    Q.o_w = take(f == 0 ? (long long)F.conv[n_conv - 1].n_own * Lc.Hp * Lc.Wp * L.n_out : (long long)L.n_out * L.n_in);
-    Q.o_b = take(L.n_out);
-    Q.o_act = take(L.n_out);
-    Q.o_delta = take(L.n_out);
+    FlowFcPtrs& C = Q.fc[f];
+    C.w = L.w; C.bias = L.bias; C.act = L.act; C.delta = L.delta; C.w_canon = L.w_canon; C.b_canon = L.b_canon;
   }
-  F.xp = xtake((size_t)2 * F.n_col_ranks * L1.n_out);
+  Q.xp = xtake((size_t)2 * Z.n_col_ranks * Z.fc[0].n_out);
   if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
-  F.o_act = take(max_act);
-  F.o_part = take(max_part);
-  F.o_dall = take(n_conv > 1 ? max_dall : 0);
-  F.o_yxall = take(n_conv > 1 ? max_dall : 0);
-  const long long pad = 16;  // strips read a few floats past the end of the last row of a map
-  const long long need = n_conv > 1 ? max_hwd + pad : pad;
-  if (off + need > FLOW_LDS_FLOATS_MAX)
-    return no("the weights and maps one workgroup would hold (" + std::to_string((off + need) * 4 / 1024) +
-              " KB) exceed its LDS");
-  // lane tables of the correlation jobs, while there is room (a rank decodes its share of a job
-  // once instead of once per image); the first layers' jobs first
-  for (int l = 0; l < n_conv; ++l) { F.conv[l].o_tab_fwd = -1; F.conv[l].o_tab_pull = -1; }
-  for (int l = 0; l < n_conv; ++l) {
-    if (F.conv[l].n_own < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX) F.conv[l].o_tab_fwd = take(3 * WG);
-    if (l >= 1 && F.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX)
-      F.conv[l].o_tab_pull = take(3 * WG);
-  }
-  // the zero-bordered delta maps of the pull: the more fit, the fewer passes
-  long long scratch = need;
-  for (int l = 1; l < n_conv; ++l) {
-    const LayerDev& L = P.layers[l];
-    scratch = std::max(scratch, (long long)L.Mo * (L.Hi + L.K - 1) * (L.Wi + L.K - 1) + pad);
-  }
-  scratch = std::min(scratch, (long long)FLOW_LDS_FLOATS_MAX - off);
-  F.o_scratch = take(scratch);
-  F.scratch_floats = (int)scratch;
-  F.lds_floats = (int)off;
-  for (int l = 1; l < n_conv; ++l) {
-    const LayerDev& L = P.layers[l];
-    const long long hwd = (long long)(L.Hi + L.K - 1) * (L.Wi + L.K - 1);
-    F.conv[l].pull_chunk = (int)std::max<long long>(1, std::min<long long>(L.Mo, (scratch - pad) / hwd));
-  }
+  net->flow_static_id = resident_static_id(Z);
   net->flow_ok = true;
   net->flow_why.clear();
 }
@@ -795,7 +726,8 @@ int upload(cnn* net) {
     ++conv_i;
   }
   HIP_TRY(net, hipMemcpy(net->d_prog, &P, sizeof(P), hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowDev), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   HIP_TRY(net, hipMemset(net->d_xbuf, 0, net->xbuf_words * sizeof(tagged_t)));
   net->epoch = 0;
   HIP_TRY(net, hipMemset(net->d_weights, 0, net->n_weights_max * sizeof(float)));
@@ -857,7 +789,8 @@ int run(cnn* net, const RunArgs& a0) {
     if (!P.has_frontend) {
       a.epoch_base = (unsigned int)net->epoch;
       net->epoch += n;
-      HIP_TRY(net, launch_resident(grid, lds_bytes, net->stream, net->d_prog, net->d_flow, net->d_status, a));
+      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->d_flow, net->d_flow_ptrs,
+                                   net->d_status, a));
       return CNN_OK;
     }
     // fixed front-end: computed for FE_BATCH images at a time by all compute units, outside the
@@ -876,7 +809,8 @@ int run(cnn* net, const RunArgs& a0) {
       b.n_images = nb;
       b.epoch_base = (unsigned int)net->epoch;
       net->epoch += (unsigned long long)nb;
-      HIP_TRY(net, launch_resident(grid, lds_bytes, net->stream, net->d_prog, net->d_flow, net->d_status, b));
+      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->d_flow, net->d_flow_ptrs,
+                                   net->d_status, b));
       if (t0 + nb >= n)  // parity tap: layer 0 of the last image
         HIP_TRY(net, hipMemcpyAsync(net->d_fe_out, net->d_fe_batch + (size_t)(nb - 1) * fe_sz, fe_sz * sizeof(float),
                                     hipMemcpyDeviceToDevice, net->stream));
@@ -1109,13 +1043,19 @@ int cnn_mode_supported(cnn_t* net, int mode) {
 
 int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
 
+// development aid, not part of the public header: which compiled-in network the resident plan equals (0: none)
+int cnn355_resident_static_id(const cnn_t* net) { return net ? net->flow_static_id : -1; }
+
 int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride) {
   if (!net || n_ranks < 0 || (xcd_stride != 0 && xcd_stride != 1 && xcd_stride != 8)) return CNN_E_ARG;
   HIP_TRY(net, hipStreamSynchronize(net->stream));
   net->team_ranks = n_ranks;
   net->team_stride = xcd_stride;
   plan_flow(net);
-  if (net->d_flow) HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowDev), hipMemcpyHostToDevice));
+  if (net->d_flow) {
+    HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
+  }
   if (net->mode == CNN_MODE_RESIDENT && !net->flow_ok) {
     net->mode = CNN_MODE_PERSISTENT;
     return fail(&net->err, CNN_E_STATE, net->flow_why);
@@ -1132,7 +1072,8 @@ int cnn_set_matrix_cores(cnn_t* net, int on) {
   int rc = plan(net);
   if (rc) return rc;
   HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowDev), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   return CNN_OK;
 }
 

@@ -152,62 +152,42 @@ struct RunArgs {
 // tag names the image, so a reader needs no barrier: it polls the word until the tag matches.
 typedef unsigned long long tagged_t;
 
-constexpr int FLOW_MAX_CONV = 8;
-constexpr int FLOW_MAX_FC = 8;
+constexpr int FLOW_MAX_CONV = 4;
+constexpr int FLOW_MAX_FC = 4;
 // the arena a rank carves up, in floats (154 KB of the 160 KB of a gfx950 CU; the rest holds a copy
 // of the descriptors)
-constexpr int FLOW_LDS_FLOATS_MAX = 39168;
+constexpr int FLOW_LDS_FLOATS_MAX = 39424;
 constexpr int FLOW_STRIP_MAX = 7;  // output pixels one lane accumulates in registers
 
-struct FlowConv {
-  int n_own;        // most output maps a rank owns: ceil(Mo / G)
-  int n_own_below;  // most input maps a rank owns (maps of the layer below): ceil(Mi / G); 0 for the first layer
-  int max_back;     // longest column of the connection table
-  int wgrad_R_log2; // pooled positions are split 2^this ways when summing a weight gradient
-  int pull_chunk;   // output maps rebuilt at full resolution per pass of the delta pull
-  int fwd_strip;    // output pixels per lane in FP (0: one pixel per lane, any stride)
-  int pull_strip;   // same for the delta pull through this layer
-  // LDS offsets, in floats
-  int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
-  int o_wf;     // [n_own][max_conn][K*K] forward copy of the filters
-  int o_bf;     // [n_own] biases
-  int o_cidx;   // [n_own][max_conn] input map of every connection (int)
-  int o_wb;     // [n_own_below][max_back][K*K] pull copy of the filters (layers above the first)
-  int o_bj;     // [n_own_below][max_back] output map of every entry (int)
-  int o_pool;   // [n_own][Hp*Wp] pooled outputs of the own maps
-  int o_yx;     // [n_own][Hp*Wp] winner coordinates (y << 16 | x) (int)
-  int o_delta;  // [n_own][Hp*Wp] deltas at the winners
-  int o_ncf;    // [n_own] connections of every own map (int)
-  int o_ncb;    // [n_own_below] entries of every own input map (int)
-  int o_tab_fwd;   // [3][WG] every lane's share of the FP job (int), or -1
-  int o_tab_pull;  // [3][WG] every lane's share of the pull job (int), or -1
+// What the resident kernel needs besides the plan (cnn355_flowspec.h): where things lie in global memory.
+struct FlowConvPtrs {
+  CNN_GLOBAL float* w;            // one K*K block per connection, CSR order (canonical)
+  CNN_GLOBAL float* bias;
+  CNN_GLOBAL float* act;          // parity taps: full-resolution outputs,
+  CNN_GLOBAL float* out;          //   pooled values,
+  CNN_GLOBAL uint8_t* arg;        //   winner index dy*Kp+dx,
+  CNN_GLOBAL int* argyx;          //   winner coordinates,
+  CNN_GLOBAL float* delta;        //   deltas at the winners
+  const CNN_GLOBAL int* csr_ptr;
+  const CNN_GLOBAL int* csr_idx;
+  const CNN_GLOBAL int* csc_ptr;
+  const CNN_GLOBAL int* csc_j;
+  const CNN_GLOBAL int* csc_slot;
   CNN_GLOBAL tagged_t* x_out;    // [2][Mo*Hp*Wp] pooled outputs, when a convolutional layer follows
   CNN_GLOBAL tagged_t* x_delta;  // [2][Mo*Hp*Wp] deltas at the winners (layers above the first)
   CNN_GLOBAL tagged_t* x_yx;     // [2][Mo*Hp*Wp] their coordinates
+  long long w_canon, b_canon;    // offsets in the canonical weight vector (gradient tap)
 };
-
-struct FlowFc {
-  int o_w;      // first layer: [columns of the own maps][n_out]; others: [n_out][n_in], every rank
-  int o_b;      // [n_out]
-  int o_act;    // [n_out]
-  int o_delta;  // [n_out]
+struct FlowFcPtrs {
+  CNN_GLOBAL float* w;
+  CNN_GLOBAL float* bias;
+  CNN_GLOBAL float* act;
+  CNN_GLOBAL float* delta;
+  long long w_canon, b_canon;
 };
-
-struct FlowDev {
-  int G;            // ranks
-  int stride;       // rank r is workgroup r * stride of the launch (8: all ranks on one XCD)
-  int n_conv, n_fc; // layers 0..n_conv-1 of the program are convolutional, the rest fully connected
-  int n_col_ranks;  // ranks that own maps of the last convolutional layer (and so columns of the first FC layer)
-  int lds_floats;
-  int o_act;        // [max n_own*Ho*Wo] full-resolution outputs of the own maps of the layer being computed
-  int o_part;       // partial sums
-  int o_scratch;    // delta maps of a chunk of output maps rebuilt at full resolution, zero border included
-  int scratch_floats;
-  int o_dall;       // [max Mo*Hp*Wp] deltas of every map of the layer being pulled through
-  int o_yxall;      // same, winner coordinates
-  int pad_;
-  FlowConv conv[FLOW_MAX_CONV];
-  FlowFc fc[FLOW_MAX_FC];
+struct FlowPtrs {
+  FlowConvPtrs conv[FLOW_MAX_CONV];
+  FlowFcPtrs fc[FLOW_MAX_FC];
   CNN_GLOBAL tagged_t* xp;  // [2][n_col_ranks][n_out of the first FC layer] partial sums
 };
 

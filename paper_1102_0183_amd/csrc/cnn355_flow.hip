@@ -35,6 +35,7 @@
 #define CNN_GLOBAL __attribute__((address_space(1)))
 #endif
 #include "cnn355_dev.h"
+#include "cnn355_flowspec.h"
 
 namespace cnn355 {
 
@@ -111,10 +112,14 @@ __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlan
 // x / d for 0 <= x < 2^20 and 1 <= d < 2^20 by a float multiplication with the hardware
 // reciprocal (1 ulp): (x + 0.5) / d lies at least 0.5 / d away from the next integer, the
 // product is off by less than x / d * 2^-21, which is smaller
+// (a divisor the compiler knows -- the kernels instantiated for a fixed network -- is divided by directly)
 struct FDiv {
+  int d;
   float inv;
-  __device__ __forceinline__ explicit FDiv(int d) : inv(__builtin_amdgcn_rcpf((float)d)) {}
-  __device__ __forceinline__ int div(int x) const { return (int)(((float)x + 0.5f) * inv); }
+  __device__ __forceinline__ explicit FDiv(int d_) : d(d_), inv(__builtin_amdgcn_rcpf((float)d_)) {}
+  __device__ __forceinline__ int div(int x) const {
+    return __builtin_constant_p(d) ? x / d : (int)(((float)x + 0.5f) * inv);
+  }
 };
 
 // ---- tagged words ---------------------------------------------------------------------------
@@ -127,22 +132,17 @@ __device__ __forceinline__ void put_i(gtagged* p, int v, unsigned int tag) {
   __hip_atomic_store(p, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// A copy of the descriptors in LDS: reading them from global memory in every phase of every image
-// costs a memory round trip each time the scalar cache has dropped them.
-struct JobDesc {
-  int in, w, idx, cnt;  // LDS offsets (floats): inputs [..][map_sz], weights [n_maps][w_pitch][K*K],
-                        // input map of every connection [n_maps][w_pitch], connections per map [n_maps]
-  int n_maps, w_pitch, Ho, Wo, K, stride, map_sz, Wi, max_cnt;
-  int variant;          // SW * 8 + K for a strip job, 0: one pixel per lane (any K, any stride)
-  int U, R, passes;     // units, ways the connections are shared, passes over the lanes
-  int table;            // LDS offset of the lane table [3][WG] (int), or -1
+// A copy of the plan and of the pointers in LDS: reading them from global memory in every phase of
+// every image costs a memory round trip each time the scalar cache has dropped them.  A kernel
+// instantiated for a fixed network (ID > 0) takes the plan from StaticSpec<ID> instead, as literals.
+struct JobDyn {  // the part of a correlation job that depends on the rank
+  int n_maps, U, R, passes;
 };
-
 struct Shared {
-  FlowDev F;
-  LayerDev L[FLOW_MAX_CONV + FLOW_MAX_FC];
-  JobDesc fwd[FLOW_MAX_CONV];   // FP of the own maps of every convolutional layer
-  JobDesc pull[FLOW_MAX_CONV];  // delta pull through layer l into the own maps of layer l-1 (l >= 1)
+  FlowSpec spec;
+  FlowPtrs ptrs;
+  JobDyn fwd[FLOW_MAX_CONV];   // FP of the own maps of every convolutional layer
+  JobDyn pull[FLOW_MAX_CONV];  // delta pull through layer l into the own maps of layer l-1 (l >= 1)
   int fail;
 };
 
@@ -162,6 +162,19 @@ struct Rt {  // what every phase needs
   int rank;
   unsigned int spin_limit;
 };
+
+// The plan: literals in a kernel instantiated for a fixed network, the copy in LDS otherwise.  (A
+// function-local constexpr copy, not a reference to the class-scope constant: a device-side
+// global may be initialised from outside the module, so the compiler would not fold its contents.)
+#define DECL_SPEC(Z, shared)                                                 \
+  constexpr FlowSpec Z##_lit = StaticSpec<(ID ? ID : 1)>::value;             \
+  const FlowSpec& Z = ID ? Z##_lit : (shared).spec
+// a value every lane holds alike, made known to the compiler as such (nothing to do for a literal)
+template <int ID>
+__device__ __forceinline__ int uni_of(int v) {
+  if constexpr (ID == 0) return __builtin_amdgcn_readfirstlane(v);
+  else return v;
+}
 
 // Bounded polling: returns false when this lane has polled too often or another workgroup has
 // raised the abort flag; the flag is raised so that every workgroup leaves.
@@ -236,115 +249,124 @@ __device__ __forceinline__ bool gather2(const Rt& rt, unsigned int* dst_a, const
 }
 
 // ---- weights: global (canonical order) <-> LDS -------------------------------------------------
+template <int ID>
 __device__ __forceinline__ void flow_load(const Rt& rt) {
-  const FlowDev& F = rt.sh->F;
+  DECL_SPEC(Z, *rt.sh);
+  const FlowPtrs& Q = rt.sh->ptrs;
   float* lds = rt.lds;
-  const int tid = threadIdx.x, G = F.G, rank = rt.rank;
-  for (int x = tid; x < F.scratch_floats; x += WG) lds[F.o_scratch + x] = 0.f;  // stays zero between uses
-  for (int l = 0; l < F.n_conv; ++l) {
-    const LayerDev& L = rt.sh->L[l];
-    const FlowConv& C = F.conv[l];
-    const int KK = L.K * L.K;
-    const int nm = n_mine(L.Mo, rank, G);
+  const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
+  for (int x = tid; x < Z.scratch_floats; x += WG) lds[Z.o_scratch + x] = 0.f;  // stays zero between uses
+#pragma unroll
+  for (int l = 0; l < Z.n_conv; ++l) {
+    const ConvSpec& C = Z.conv[l];
+    const FlowConvPtrs& P = Q.conv[l];
+    const int KK = C.K * C.K;
+    const int nm = n_mine(C.Mo, rank, G);
     float* wf = lds + C.o_wf;
     float* bf = lds + C.o_bf;
     int* cidx = (int*)(lds + C.o_cidx);
     int* ncf = (int*)(lds + C.o_ncf);
     for (int a = 0; a < nm; ++a) {
       const int j = rank + a * G;
-      int cb = j * L.Mi, nc = L.Mi;
-      if (!L.full_table) { cb = L.csr_ptr[j]; nc = L.csr_ptr[j + 1] - cb; }
-      for (int x = tid; x < L.max_conn * KK; x += WG)
-        wf[a * L.max_conn * KK + x] = (x < nc * KK) ? L.w[(size_t)cb * KK + x] : 0.f;
-      for (int c = tid; c < L.max_conn; c += WG)
-        cidx[a * L.max_conn + c] = (c < nc) ? (L.full_table ? c : L.csr_idx[cb + c]) : 0;
-      if (tid == 0) { bf[a] = L.bias[j]; ncf[a] = nc; }
+      int cb = j * C.Mi, nc = C.Mi;
+      if (!C.full_table) { cb = P.csr_ptr[j]; nc = P.csr_ptr[j + 1] - cb; }
+      for (int x = tid; x < C.max_conn * KK; x += WG)
+        wf[a * C.max_conn * KK + x] = (x < nc * KK) ? P.w[(size_t)cb * KK + x] : 0.f;
+      for (int c = tid; c < C.max_conn; c += WG)
+        cidx[a * C.max_conn + c] = (c < nc) ? (C.full_table ? c : P.csr_idx[cb + c]) : 0;
+      if (tid == 0) { bf[a] = P.bias[j]; ncf[a] = nc; }
     }
     if (l >= 1) {
       // pull copy: the filters that read the own maps of the layer below, each rotated by 180
       // degrees (tap t stored at K*K-1-t), entries in ascending order of the output map
-      const int nb = n_mine(L.Mi, rank, G);
+      const int nb = n_mine(C.Mi, rank, G);
       float* wb = lds + C.o_wb;
       int* bj = (int*)(lds + C.o_bj);
       int* ncb = (int*)(lds + C.o_ncb);
       for (int a = 0; a < nb; ++a) {
         const int i = rank + a * G;
-        int eb = 0, ne = L.Mo;
-        if (!L.full_table) { eb = L.csc_ptr[i]; ne = L.csc_ptr[i + 1] - eb; }
+        int eb = 0, ne = C.Mo;
+        if (!C.full_table) { eb = P.csc_ptr[i]; ne = P.csc_ptr[i + 1] - eb; }
         for (int x = tid; x < C.max_back * KK; x += WG) {
           const int e = x / KK, t = x - e * KK;
           float v = 0.f;
           if (e < ne) {
-            const int slot = L.full_table ? (e * L.Mi + i) : L.csc_slot[eb + e];
-            v = L.w[(size_t)slot * KK + (KK - 1 - t)];
+            const int slot = C.full_table ? (e * C.Mi + i) : P.csc_slot[eb + e];
+            v = P.w[(size_t)slot * KK + (KK - 1 - t)];
           }
           wb[a * C.max_back * KK + x] = v;
         }
         for (int e = tid; e < C.max_back; e += WG)
-          bj[a * C.max_back + e] = (e < ne) ? (L.full_table ? e : L.csc_j[eb + e]) : 0;
+          bj[a * C.max_back + e] = (e < ne) ? (C.full_table ? e : P.csc_j[eb + e]) : 0;
         if (tid == 0) ncb[a] = ne;
       }
     }
   }
   {  // first fully connected layer: the columns fed by the own maps of the last convolutional layer
-    const LayerDev& Lc = rt.sh->L[F.n_conv - 1];
-    const LayerDev& L = rt.sh->L[F.n_conv];
-    const int HW = Lc.Hp * Lc.Wp, n1 = L.n_out;
-    const int nm = n_mine(Lc.Mo, rank, G);
-    float* wc = lds + F.fc[0].o_w;
+    const ConvSpec& Cc = Z.conv[Z.n_conv - 1];
+    const FcSpec& L = Z.fc[0];
+    const int HW = Cc.Hp * Cc.Wp, n1 = L.n_out;
+    const int nm = n_mine(Cc.Mo, rank, G);
+    float* wc = lds + L.o_w;
     for (int x = tid; x < nm * HW * n1; x += WG) {
       const int c = x / n1, k = x - c * n1;
       const int a = c / HW, q = c - a * HW;
-      wc[x] = L.w[(size_t)k * L.n_in + (size_t)(rank + a * G) * HW + q];
+      wc[x] = Q.fc[0].w[(size_t)k * L.n_in + (size_t)(rank + a * G) * HW + q];
     }
-    for (int k = tid; k < n1; k += WG) lds[F.fc[0].o_b + k] = L.bias[k];
+    for (int k = tid; k < n1; k += WG) lds[L.o_b + k] = Q.fc[0].bias[k];
   }
-  for (int f = 1; f < F.n_fc; ++f) {
-    const LayerDev& L = rt.sh->L[F.n_conv + f];
-    for (int x = tid; x < L.n_out * L.n_in; x += WG) lds[F.fc[f].o_w + x] = L.w[x];
-    for (int k = tid; k < L.n_out; k += WG) lds[F.fc[f].o_b + k] = L.bias[k];
+#pragma unroll
+  for (int f = 1; f < Z.n_fc; ++f) {
+    const FcSpec& L = Z.fc[f];
+    for (int x = tid; x < L.n_out * L.n_in; x += WG) lds[L.o_w + x] = Q.fc[f].w[x];
+    for (int k = tid; k < L.n_out; k += WG) lds[L.o_b + k] = Q.fc[f].bias[k];
   }
   __syncthreads();
 }
 
+template <int ID>
 __device__ __forceinline__ void flow_store(const Rt& rt) {
-  const FlowDev& F = rt.sh->F;
+  DECL_SPEC(Z, *rt.sh);
+  const FlowPtrs& Q = rt.sh->ptrs;
   float* lds = rt.lds;
-  const int tid = threadIdx.x, G = F.G, rank = rt.rank;
+  const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
   __syncthreads();
-  for (int l = 0; l < F.n_conv; ++l) {
-    const LayerDev& L = rt.sh->L[l];
-    const FlowConv& C = F.conv[l];
-    const int KK = L.K * L.K;
-    const int nm = n_mine(L.Mo, rank, G);
+#pragma unroll
+  for (int l = 0; l < Z.n_conv; ++l) {
+    const ConvSpec& C = Z.conv[l];
+    const FlowConvPtrs& P = Q.conv[l];
+    const int KK = C.K * C.K;
+    const int nm = n_mine(C.Mo, rank, G);
     const int* ncf = (const int*)(lds + C.o_ncf);
     for (int a = 0; a < nm; ++a) {
       const int j = rank + a * G;
       const int nc = ncf[a];
-      const int cb = L.full_table ? j * L.Mi : L.csr_ptr[j];
-      for (int x = tid; x < nc * KK; x += WG) L.w[(size_t)cb * KK + x] = lds[C.o_wf + a * L.max_conn * KK + x];
-      if (tid == 0) L.bias[j] = lds[C.o_bf + a];
+      const int cb = C.full_table ? j * C.Mi : P.csr_ptr[j];
+      for (int x = tid; x < nc * KK; x += WG) P.w[(size_t)cb * KK + x] = lds[C.o_wf + a * C.max_conn * KK + x];
+      if (tid == 0) P.bias[j] = lds[C.o_bf + a];
     }
   }
   {
-    const LayerDev& Lc = rt.sh->L[F.n_conv - 1];
-    const LayerDev& L = rt.sh->L[F.n_conv];
-    const int HW = Lc.Hp * Lc.Wp, n1 = L.n_out;
-    const int nm = n_mine(Lc.Mo, rank, G);
+    const ConvSpec& Cc = Z.conv[Z.n_conv - 1];
+    const FcSpec& L = Z.fc[0];
+    const int HW = Cc.Hp * Cc.Wp, n1 = L.n_out;
+    const int nm = n_mine(Cc.Mo, rank, G);
     for (int x = tid; x < nm * HW * n1; x += WG) {
       const int c = x / n1, k = x - c * n1;
       const int a = c / HW, q = c - a * HW;
-      L.w[(size_t)k * L.n_in + (size_t)(rank + a * G) * HW + q] = lds[F.fc[0].o_w + x];
+      Q.fc[0].w[(size_t)k * L.n_in + (size_t)(rank + a * G) * HW + q] = lds[L.o_w + x];
     }
     if (rank == 0)
-      for (int k = tid; k < n1; k += WG) L.bias[k] = lds[F.fc[0].o_b + k];
+      for (int k = tid; k < n1; k += WG) Q.fc[0].bias[k] = lds[L.o_b + k];
   }
-  if (rank == 0)
-    for (int f = 1; f < F.n_fc; ++f) {
-      const LayerDev& L = rt.sh->L[F.n_conv + f];
-      for (int x = tid; x < L.n_out * L.n_in; x += WG) L.w[x] = lds[F.fc[f].o_w + x];
-      for (int k = tid; k < L.n_out; k += WG) L.bias[k] = lds[F.fc[f].o_b + k];
+  if (rank == 0) {
+#pragma unroll
+    for (int f = 1; f < Z.n_fc; ++f) {
+      const FcSpec& L = Z.fc[f];
+      for (int x = tid; x < L.n_out * L.n_in; x += WG) Q.fc[f].w[x] = lds[L.o_w + x];
+      for (int k = tid; k < L.n_out; k += WG) Q.fc[f].bias[k] = lds[L.o_b + k];
     }
+  }
 }
 
 // ---- the two multiply-accumulate loops -------------------------------------------------------------
@@ -406,10 +428,40 @@ __device__ __forceinline__ void strip_mac(const float* in, const float* w, const
 // K x K correlations (unit stride for the strip form) of input maps of map_sz floats and row
 // pitch Wi.  Lanes take (map, row, strip of SW pixels) units, or (map, pixel) units when SW = 1,
 // and share the connections R ways when there are fewer units than lanes; partial sums go to
-// part[(r * n_maps + map) * Ho*Wo + pixel].  A job is the same for every image of a call: it is
-// described once, and (LDS permitting) every lane's share of it is decoded once and kept in a
-// table, because working it out again per image -- integer divisions, a dozen descriptor
-// reads -- costs more than the multiply-accumulates of a small layer.
+// part[(r * n_maps + map) * Ho*Wo + pixel].  A job is the same for every image of a call: the
+// part of it that depends on the rank (how many maps, hence units and ways) is worked out once,
+// and (LDS permitting) every lane's share of it is decoded once and kept in a table, because
+// working it out again per image -- integer divisions, a dozen descriptor reads -- costs more
+// than the multiply-accumulates of a small layer.
+struct JobStat {  // the part of a job the plan fixes
+  int in, w, idx, cnt;  // LDS offsets (floats): inputs [..][map_sz], weights [n_maps][w_pitch][K*K],
+                        // input map of every connection [n_maps][w_pitch], connections per map [n_maps]
+  int w_pitch, Ho, Wo, K, stride, map_sz, Wi, max_cnt;
+  int variant;          // SW * 8 + K for a strip job, 0: one pixel per lane (any K, any stride)
+  int table;            // LDS offset of the lane table [3][WG] (int), or -1
+};
+__device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
+  const ConvSpec& C = Z.conv[l];
+  JobStat S;
+  S.in = C.o_in; S.w = C.o_wf; S.idx = C.o_cidx; S.cnt = C.o_ncf;
+  S.w_pitch = C.max_conn; S.Ho = C.Ho; S.Wo = C.Wo; S.K = C.K; S.stride = C.S + 1;
+  S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn;
+  S.variant = C.fwd_strip ? C.fwd_strip * 8 + C.K : 0;
+  S.table = C.o_tab_fwd;
+  return S;
+}
+__device__ __forceinline__ JobStat pull_job(const FlowSpec& Z, int l) {
+  const ConvSpec& C = Z.conv[l];
+  JobStat S;
+  S.in = Z.o_scratch; S.w = C.o_wb; S.idx = C.o_bj; S.cnt = C.o_ncb;
+  S.w_pitch = C.max_back; S.Ho = C.Hi; S.Wo = C.Wi; S.K = C.K; S.stride = 1;
+  S.Wi = C.Wi + C.K - 1; S.map_sz = (C.Hi + C.K - 1) * (C.Wi + C.K - 1);
+  S.max_cnt = min(C.max_back, C.pull_chunk);
+  S.variant = C.pull_strip ? C.pull_strip * 8 + C.K : 0;
+  S.table = C.o_tab_pull;
+  return S;
+}
+
 struct Lane {
   int r, am, pix, base, ncols;
   bool on;
@@ -423,17 +475,19 @@ __device__ __forceinline__ int split_ways(int U, int max_cnt) {
   const int iters = (max_cnt + r_max - 1) / r_max;
   return (max_cnt + iters - 1) / iters;
 }
-
-__device__ __forceinline__ void job_finish(JobDesc& D) {
-  const int SW = D.variant >> 3;
-  D.U = SW ? D.n_maps * D.Ho * ((D.Wo + SW - 1) / SW) : D.n_maps * D.Ho * D.Wo;
-  D.R = D.U > 0 ? split_ways(D.U, D.max_cnt) : 1;
+__device__ __forceinline__ JobDyn job_dyn(const JobStat& S, int n_maps) {
+  const int SW = S.variant >> 3;
+  JobDyn D;
+  D.n_maps = n_maps;
+  D.U = SW ? n_maps * S.Ho * ((S.Wo + SW - 1) / SW) : n_maps * S.Ho * S.Wo;
+  D.R = D.U > 0 ? split_ways(D.U, S.max_cnt) : 1;
   D.passes = (D.U * D.R + WG - 1) / WG;
+  return D;
 }
 
 // the share of lane `tid` in pass `pass`
-__device__ __forceinline__ Lane lane_decode(const JobDesc& D, int pass) {
-  const int SW = D.variant >> 3;
+__device__ __forceinline__ Lane lane_decode(const JobStat& S, const JobDyn& D, int pass) {
+  const int SW = S.variant >> 3;
   Lane ln;
   const int u = pass * WG + (int)threadIdx.x;
   ln.on = u < D.U * D.R;
@@ -441,22 +495,22 @@ __device__ __forceinline__ Lane lane_decode(const JobDesc& D, int pass) {
   ln.r = dU.div(u);
   const int v = u - ln.r * D.U;
   if (SW) {
-    const int NS = (D.Wo + SW - 1) / SW;
-    const FDiv dNS(NS), dHo(D.Ho);
+    const int NS = (S.Wo + SW - 1) / SW;
+    const FDiv dNS(NS), dHo(S.Ho);
     const int row = dNS.div(v), s = v - row * NS;
     ln.am = dHo.div(row);
-    const int y = row - ln.am * D.Ho, x0 = s * SW;
-    ln.pix = y * D.Wo + x0;
-    ln.ncols = min(SW, D.Wo - x0);
-    ln.base = y * D.Wi + x0;
+    const int y = row - ln.am * S.Ho, x0 = s * SW;
+    ln.pix = y * S.Wo + x0;
+    ln.ncols = min(SW, S.Wo - x0);
+    ln.base = y * S.Wi + x0;
   } else {
-    const int Pn = D.Ho * D.Wo;
-    const FDiv dP(Pn), dW(D.Wo);
+    const int Pn = S.Ho * S.Wo;
+    const FDiv dP(Pn), dW(S.Wo);
     ln.am = dP.div(v);
     ln.pix = v - ln.am * Pn;
-    const int y = dW.div(ln.pix), x = ln.pix - y * D.Wo;
+    const int y = dW.div(ln.pix), x = ln.pix - y * S.Wo;
     ln.ncols = 1;
-    ln.base = (y * D.Wi + x) * D.stride;
+    ln.base = (y * S.Wi + x) * S.stride;
   }
   if (!ln.on) { ln.r = 0; ln.am = 0; ln.pix = 0; ln.base = 0; ln.ncols = 0; }
   return ln;
@@ -479,9 +533,9 @@ __device__ __forceinline__ Lane lane_load(const int* tab) {
   ln.on = (m >> 24) != 0;
   return ln;
 }
-__device__ __forceinline__ Lane lane_get(const JobDesc& D, const float* lds, int pass) {
-  if (D.table >= 0 && D.passes == 1) return lane_load((const int*)(lds + D.table));
-  return lane_decode(D, pass);
+__device__ __forceinline__ Lane lane_get(const JobStat& S, const JobDyn& D, const float* lds, int pass) {
+  if (S.table >= 0 && D.passes == 1) return lane_load((const int*)(lds + S.table));
+  return lane_decode(S, D, pass);
 }
 
 template <int V>
@@ -502,41 +556,40 @@ __device__ __forceinline__ void job_dispatch(int variant, Fn f) {
 
 // acc[] += the lane's share of connections [e_lo, e_hi) of its map (maps numbered from idx_off)
 template <int K, int SW>
-__device__ __forceinline__ void job_mac(const JobDesc& D, const float* lds, const Lane& ln, int e_lo, int e_hi,
+__device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* lds, const Lane& ln, int e_lo, int e_hi,
                                         int idx_off, float (&acc)[SW]) {
-  const float* w = lds + D.w + (ln.am * D.w_pitch) * (D.K * D.K);
-  const int* idx = (const int*)(lds + D.idx) + ln.am * D.w_pitch;
+  const float* w = lds + S.w + (ln.am * S.w_pitch) * (S.K * S.K);
+  const int* idx = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
   if constexpr (K == 0)
-    acc[0] += pixel_mac_k(D.K, lds + D.in, w, idx, idx_off, e_lo + ln.r, D.R, e_hi, D.map_sz, D.Wi, ln.base);
+    acc[0] += pixel_mac_k(S.K, lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base);
   else
-    strip_mac<K, SW>(lds + D.in, w, idx, idx_off, e_lo + ln.r, D.R, e_hi, D.map_sz, D.Wi, ln.base, acc);
+    strip_mac<K, SW>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, acc);
 }
 
 // ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
-__device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l, int nm) {
-  const FlowDev& F = rt.sh->F;
-  const FlowConv& C = F.conv[l];
+template <int ID>
+__device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
+  DECL_SPEC(Z, *rt.sh);
+  const ConvSpec& C = Z.conv[l];
   float* lds = rt.lds;
   const int tid = threadIdx.x;
-  const JobDesc D = rt.sh->fwd[l];
-  float* part = lds + F.o_part;
-  float* act = lds + F.o_act;
+  const JobStat S = fwd_job(Z, l);
+  const JobDyn D = rt.sh->fwd[l];
+  const int nm = D.n_maps;
+  float* part = lds + Z.o_part;
+  float* act = lds + Z.o_act;
   const float* bf = lds + C.o_bf;
-  const int* cnt = (const int*)(lds + D.cnt);
-  const int Pn = D.Ho * D.Wo, tot = nm * Pn;
-  if (l == 1) DSTAMP(110); else DSTAMP(118);
-  job_dispatch(D.variant, [&](auto k_, auto sw_) {
+  const int* cnt = (const int*)(lds + S.cnt);
+  const int Pn = S.Ho * S.Wo, tot = nm * Pn;
+  job_dispatch(S.variant, [&](auto k_, auto sw_) {
     constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
-      if (l == 0) DSTAMP(115);
-      const Lane ln = lane_get(D, lds, pass);
-      if (l == 0) DSTAMP(116); else DSTAMP(114);
+      const Lane ln = lane_get(S, D, lds, pass);
       float acc[SW];
 #pragma unroll
       for (int i = 0; i < SW; ++i) acc[i] = 0.f;
       if (ln.on) {
-        job_mac<K, SW>(D, lds, ln, 0, cnt[ln.am], 0, acc);
-        if (l == 0) DSTAMP(117);
+        job_mac<K, SW>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
         if (D.R == 1) {  // unsplit: the finished sums go straight through the activation function
           const float b = bf[ln.am];
           float* dst = act + ln.am * Pn + ln.pix;
@@ -552,34 +605,31 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l, int nm) {
       }
     }
   });
-  DSTAMP(100 + 4 * l);
   __syncthreads();
-  DSTAMP(101 + 4 * l);
   if (D.R > 1) {
     const FDiv dP(Pn);
     for (int p = tid; p < tot; p += WG) {
       const float s = sum_strided(part, D.R, tot, p);
       act[p] = f_act(s + bf[dP.div(p)]);
     }
-    DSTAMP(102 + 4 * l);
     __syncthreads();
   }
-  DSTAMP(103 + 4 * l);
 }
 
 // Max-pooling of the own maps (Sec. 2.3): value and position of the first maximum in row-major
 // order; the pooled value is what the next layer reads, so it is published at once.
+template <int ID>
 __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned int tag, bool taps) {
-  const FlowDev& F = rt.sh->F;
-  const LayerDev& L = rt.sh->L[l];
-  const FlowConv& C = F.conv[l];
+  DECL_SPEC(Z, *rt.sh);
+  const ConvSpec& C = Z.conv[l];
+  const FlowConvPtrs& P = rt.sh->ptrs.conv[l];
   float* lds = rt.lds;
-  const int tid = threadIdx.x, G = F.G, rank = rt.rank;
-  const int Kp = L.Kp, Wo = L.Wo, Wp = L.Wp, HW = L.Hp * L.Wp, Pn = L.Ho * L.Wo;
-  const float* act = lds + F.o_act;
+  const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
+  const int Kp = C.Kp, Wo = C.Wo, Wp = C.Wp, HW = C.Hp * C.Wp, Pn = C.Ho * C.Wo;
+  const float* act = lds + Z.o_act;
   float* pool = lds + C.o_pool;
   int* yx = (int*)(lds + C.o_yx);
-  gtagged* xo = C.x_out ? C.x_out + (size_t)(tag & 1u) * L.Mo * HW : nullptr;
+  gtagged* xo = C.has_x_out ? P.x_out + (size_t)(tag & 1u) * C.Mo * HW : nullptr;
   const FDiv dHW(HW), dWp(Wp);
   for (int x = tid; x < nm * HW; x += WG) {
     const int am = dHW.div(x), q = x - am * HW;
@@ -587,7 +637,9 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
     const float* win = act + am * Pn + py * Kp * Wo + px * Kp;
     float best = win[0];
     int wy = 0, wx = 0;
+#pragma unroll 4
     for (int dy = 0; dy < Kp; ++dy)
+#pragma unroll 4
       for (int dx = 0; dx < Kp; ++dx) {
         const float v = win[dy * Wo + dx];
         if (v > best) { best = v; wy = dy; wx = dx; }
@@ -598,16 +650,16 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
     const size_t o = (size_t)(rank + am * G) * HW + q;
     if (xo) put_f(xo + o, best, tag);
     if (taps) {
-      if (Kp > 1) L.out[o] = best;
-      L.arg[o] = (uint8_t)(wy * Kp + wx);
-      L.argyx[o] = code;
+      if (Kp > 1) P.out[o] = best;
+      P.arg[o] = (uint8_t)(wy * Kp + wx);
+      P.argyx[o] = code;
     }
   }
   if (taps) {
     const FDiv dP(Pn);
     for (int x = tid; x < nm * Pn; x += WG) {
       const int am = dP.div(x), p = x - am * Pn;
-      L.act[(size_t)(rank + am * G) * Pn + p] = act[x];
+      P.act[(size_t)(rank + am * G) * Pn + p] = act[x];
     }
   }
   __syncthreads();
@@ -674,27 +726,29 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
 // a tap that has no output neuron then meets a zero and the loop has no branches.  The zero maps
 // are kept zero between uses: after a chunk the winners' places are cleared again.
 // delta_below[p] = pulled sum * f'(y_below[p]).
-__device__ __forceinline__ void flow_pull(const Rt& rt, int l, int nb, const float* dall, const int* yxall) {
-  const FlowDev& F = rt.sh->F;
-  const LayerDev& L = rt.sh->L[l];
-  const FlowConv& C = F.conv[l];
-  const FlowConv& Cb = F.conv[l - 1];
+template <int ID>
+__device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall, const int* yxall) {
+  DECL_SPEC(Z, *rt.sh);
+  const ConvSpec& C = Z.conv[l];
+  const ConvSpec& Cb = Z.conv[l - 1];
   float* lds = rt.lds;
   const int tid = threadIdx.x;
-  const JobDesc D = rt.sh->pull[l];
-  float* dd = lds + F.o_scratch;
-  float* part = lds + F.o_part;
-  const int Mo = uni(L.Mo), HW = uni(L.Hp) * uni(L.Wp), stride = uni(L.S) + 1, Km1 = D.K - 1;
-  const int Wd = D.Wi, HWd = D.map_sz;
-  const int chunk = uni(C.pull_chunk);
-  const bool full = uni(L.full_table) != 0;
-  const int* cnt = (const int*)(lds + D.cnt);
-  const int tot = nb * D.Ho * D.Wo;
+  const JobStat S = pull_job(Z, l);
+  const JobDyn D = rt.sh->pull[l];
+  const int nb = D.n_maps;
+  float* dd = lds + Z.o_scratch;
+  float* part = lds + Z.o_part;
+  const int Mo = C.Mo, HW = C.Hp * C.Wp, stride = C.S + 1, Km1 = C.K - 1;
+  const int Wd = S.Wi, HWd = S.map_sz;
+  const int chunk = C.pull_chunk;
+  const bool full = C.full_table != 0;
+  const int* cnt = (const int*)(lds + S.cnt);
+  const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
-  job_dispatch(D.variant, [&](auto k_, auto sw_) {
+  job_dispatch(S.variant, [&](auto k_, auto sw_) {
     constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
-      const Lane ln = lane_get(D, lds, pass);
+      const Lane ln = lane_get(S, D, lds, pass);
       float acc[SW];
 #pragma unroll
       for (int i = 0; i < SW; ++i) acc[i] = 0.f;
@@ -710,14 +764,14 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, int nb, const flo
           // entries of the lane's input map whose output map lies in [j0, j0 + n)
           int e_lo = j0, e_hi = j0 + n;
           if (!full) {
-            const int* bj = (const int*)(lds + D.idx) + ln.am * D.w_pitch;
+            const int* bj = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
             const int ne = cnt[ln.am];
             e_lo = 0;
             while (e_lo < ne && bj[e_lo] < j0) ++e_lo;
             e_hi = e_lo;
             while (e_hi < ne && bj[e_hi] < j0 + n) ++e_hi;
           }
-          job_mac<K, SW>(D, lds, ln, e_lo, e_hi, j0, acc);
+          job_mac<K, SW>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
         __syncthreads();
         for (int x = tid; x < n * HW; x += WG) {
@@ -728,7 +782,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, int nb, const flo
         if (j0 + chunk < Mo) __syncthreads();
       }
       if (ln.on) {
-        float* dst = part + (ln.r * nb + ln.am) * (D.Ho * D.Wo) + ln.pix;
+        float* dst = part + (ln.r * nb + ln.am) * (S.Ho * S.Wo) + ln.pix;
 #pragma unroll
         for (int i = 0; i < SW; ++i)
           if (i < ln.ncols) dst[i] = acc[i];
@@ -768,8 +822,8 @@ __device__ __forceinline__ void flow_matvec(const float* W, const float* b, cons
 // Sum over the ranks of the partial sums of the first fully connected layer, every rank in the
 // same order: lane (k, part) adds the ranks of its part one after the other as their words
 // arrive, the parts are then added in order.  y[k] = b[k] + sum.
-__device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged* xp, int NR, int n1, const float* b, float* y,
-                                     float* part, unsigned int tag) {
+__device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged* xp, int NR, int n1, const float* b,
+                                                     float* y, float* part, unsigned int tag) {
   const int tid = threadIdx.x;
   const int parts = max(1, min(WG / max(n1, 1), NR));
   const int per = (NR + parts - 1) / parts;
@@ -800,50 +854,36 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
       part[pi * n1 + (k - k0)] = s;
     }
     __syncthreads();
-    if (tid < n1 - k0 && tid < WG) {
-      y[k0 + tid] = b[k0 + tid] + sum_strided(part, parts, n1, tid);
-    }
+    if (tid < n1 - k0 && tid < WG) y[k0 + tid] = b[k0 + tid] + sum_strided(part, parts, n1, tid);
     __syncthreads();
     if (n1 <= WG) break;
   }
   return rt.sh->fail == 0;
 }
 
-// Describe the correlation jobs of this rank and fill their lane tables (once per call).
+// Work out the rank's share of the correlation jobs and fill their lane tables (once per call).
+template <int ID>
 __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
   Shared& sh = *rt.sh;
-  const FlowDev& F = sh.F;
-  const int G = F.G, rank = rt.rank;
+  DECL_SPEC(Z, sh);
+  const int G = Z.G, rank = rt.rank;
   if (threadIdx.x == 0) {
-    for (int l = 0; l < F.n_conv; ++l) {
-      const LayerDev& L = sh.L[l];
-      const FlowConv& C = F.conv[l];
-      JobDesc& D = sh.fwd[l];
-      D.in = C.o_in; D.w = C.o_wf; D.idx = C.o_cidx; D.cnt = C.o_ncf;
-      D.n_maps = n_mine(L.Mo, rank, G); D.w_pitch = L.max_conn; D.Ho = L.Ho; D.Wo = L.Wo; D.K = L.K;
-      D.stride = L.S + 1; D.map_sz = L.Hi * L.Wi; D.Wi = L.Wi; D.max_cnt = L.max_conn;
-      D.variant = C.fwd_strip ? C.fwd_strip * 8 + L.K : 0;
-      D.table = C.o_tab_fwd;
-      job_finish(D);
-      if (l >= 1) {
-        JobDesc& B = sh.pull[l];
-        B.in = F.o_scratch; B.w = C.o_wb; B.idx = C.o_bj; B.cnt = C.o_ncb;
-        B.n_maps = n_mine(L.Mi, rank, G); B.w_pitch = C.max_back; B.Ho = L.Hi; B.Wo = L.Wi; B.K = L.K;
-        B.stride = 1; B.Wi = L.Wi + L.K - 1; B.map_sz = (L.Hi + L.K - 1) * (L.Wi + L.K - 1);
-        B.max_cnt = min(C.max_back, C.pull_chunk);
-        B.variant = C.pull_strip ? C.pull_strip * 8 + L.K : 0;
-        B.table = C.o_tab_pull;
-        job_finish(B);
-      }
+#pragma unroll
+    for (int l = 0; l < Z.n_conv; ++l) {
+      sh.fwd[l] = job_dyn(fwd_job(Z, l), n_mine(Z.conv[l].Mo, rank, G));
+      if (l >= 1) sh.pull[l] = job_dyn(pull_job(Z, l), n_mine(Z.conv[l].Mi, rank, G));
     }
   }
   __syncthreads();
-  for (int l = 0; l < F.n_conv; ++l) {
-    const JobDesc& D = sh.fwd[l];
-    if (D.n_maps > 0 && D.table >= 0 && D.passes == 1) lane_save(lane_decode(D, 0), (int*)(rt.lds + D.table));
+#pragma unroll
+  for (int l = 0; l < Z.n_conv; ++l) {
+    const JobStat S = fwd_job(Z, l);
+    const JobDyn D = sh.fwd[l];
+    if (D.n_maps > 0 && S.table >= 0 && D.passes == 1) lane_save(lane_decode(S, D, 0), (int*)(rt.lds + S.table));
     if (l >= 1) {
-      const JobDesc& B = sh.pull[l];
-      if (B.n_maps > 0 && B.table >= 0 && B.passes == 1) lane_save(lane_decode(B, 0), (int*)(rt.lds + B.table));
+      const JobStat B = pull_job(Z, l);
+      const JobDyn E = sh.pull[l];
+      if (E.n_maps > 0 && B.table >= 0 && E.passes == 1) lane_save(lane_decode(B, E, 0), (int*)(rt.lds + B.table));
     }
   }
   __syncthreads();
@@ -854,41 +894,48 @@ __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
     if (stamp) status->stamps[i] = wall_clock64();                                            \
   } while (0)
 
-__global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ Pp, const FlowDev* __restrict__ Fp,
+// ID = 0: any network, the plan read from *gspec.  ID > 0: the network of StaticSpec<ID>; the host
+// launches it only when the plan it made at run time equals that one word for word.
+template <int ID>
+__global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gspec, const FlowPtrs* __restrict__ gptrs,
                                                  StatusDev* status, RunArgs a) {
   extern __shared__ float lds[];
   __shared__ Shared sh;
   const int tid = threadIdx.x;
   {
-    const int stride = Fp->stride, G0 = Fp->G;
+    const int stride = ID ? StaticSpec<(ID ? ID : 1)>::value.stride : gspec->stride;
+    const int G0 = ID ? StaticSpec<(ID ? ID : 1)>::value.G : gspec->G;
     if (blockIdx.x % stride != 0 || (int)(blockIdx.x / stride) >= G0) return;
-    const int n_layers = Fp->n_conv + Fp->n_fc;
-    const unsigned int* src = (const unsigned int*)Fp;
-    unsigned int* dst = (unsigned int*)&sh.F;
-    for (int i = tid; i < (int)(sizeof(FlowDev) / 4); i += WG) dst[i] = src[i];
-    src = (const unsigned int*)&Pp->layers[0];
-    dst = (unsigned int*)&sh.L[0];
-    for (int i = tid; i < n_layers * (int)(sizeof(LayerDev) / 4); i += WG) dst[i] = src[i];
+    if (ID == 0) {
+      const unsigned int* src = (const unsigned int*)gspec;
+      unsigned int* dst = (unsigned int*)&sh.spec;
+      for (int i = tid; i < (int)(sizeof(FlowSpec) / 4); i += WG) dst[i] = src[i];
+    }
+    const unsigned int* src = (const unsigned int*)gptrs;
+    unsigned int* dst = (unsigned int*)&sh.ptrs;
+    for (int i = tid; i < (int)(sizeof(FlowPtrs) / 4); i += WG) dst[i] = src[i];
     if (tid == 0) sh.fail = 0;
     __syncthreads();
   }
-  const FlowDev& F = sh.F;
-  const int G = uni(F.G);
-  const int rank = blockIdx.x / uni(F.stride);
+  DECL_SPEC(Z, sh);
+  const FlowPtrs& Q = sh.ptrs;
+  const int G = uni_of<ID>(Z.G);
+  const int rank = blockIdx.x / uni_of<ID>(Z.stride);
   Rt rt;
   rt.sh = &sh; rt.status = status; rt.lds = lds; rt.rank = rank; rt.spin_limit = a.spin_limit;
   rt.dbg = false;
-  flow_load(rt);
-  flow_prepare_jobs(rt);
+  flow_load<ID>(rt);
+  flow_prepare_jobs<ID>(rt);
 
-  const int n_conv = uni(F.n_conv), n_fc = uni(F.n_fc), n_classes = Pp->n_classes;
-  const LayerDev& Lc = sh.L[n_conv - 1];           // last convolutional layer
-  const LayerDev& L1 = sh.L[n_conv];               // first fully connected layer
-  const int HWc = uni(Lc.Hp) * uni(Lc.Wp);
-  const int ncols = n_mine(uni(Lc.Mo), rank, G) * HWc;  // own columns of the first fully connected layer
-  const int n1 = uni(L1.n_out);
-  const int NR = uni(F.n_col_ranks);
-  float* part = lds + F.o_part;
+  const int n_conv = uni_of<ID>(Z.n_conv), n_fc = uni_of<ID>(Z.n_fc), n_classes = uni_of<ID>(Z.n_classes);
+  const ConvSpec& Cc = Z.conv[n_conv - 1];      // last convolutional layer
+  const FlowConvPtrs& Pc = Q.conv[n_conv - 1];
+  const FcSpec& L1 = Z.fc[0];                   // first fully connected layer
+  const int HWc = uni_of<ID>(Cc.Hp) * uni_of<ID>(Cc.Wp);
+  const int ncols = n_mine(uni_of<ID>(Cc.Mo), rank, G) * HWc;  // own columns of the first fully connected layer
+  const int n1 = uni_of<ID>(L1.n_out);
+  const int NR = uni_of<ID>(Z.n_col_ranks);
+  float* part = lds + Z.o_part;
   gfloat* g_out = a.grad_out;
   const float lr = a.lr;
 
@@ -908,35 +955,35 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     STAMP(0);
     {  // the image
       const gfloat* img = a.images + t * a.image_stride;
-      const LayerDev& L = sh.L[0];
-      const int n = L.Mi * L.Hi * L.Wi;
-      float* in = lds + F.conv[0].o_in;
+      const ConvSpec& C = Z.conv[0];
+      const int n = C.Mi * C.Hi * C.Wi;
+      float* in = lds + C.o_in;
       for (int x = tid; x < n; x += WG) in[x] = img[x];
       __syncthreads();
     }
     STAMP(1);
     // ---- FP, convolutional layers ----
+#pragma unroll
     for (int l = 0; l < n_conv; ++l) {
-      const LayerDev& L = sh.L[l];
-      const FlowConv& C = F.conv[l];
+      const ConvSpec& C = Z.conv[l];
       if (l >= 1) {
-        const int nw = L.Mi * L.Hi * L.Wi;
-        if (!gather(rt, (unsigned int*)(lds + C.o_in), F.conv[l - 1].x_out + (size_t)par * nw, nw, tag)) return;
+        const int nw = C.Mi * C.Hi * C.Wi;
+        if (!gather(rt, (unsigned int*)(lds + C.o_in), Q.conv[l - 1].x_out + (size_t)par * nw, nw, tag)) return;
       }
       STAMP(2 + 2 * l);
-      const int nm = n_mine(uni(L.Mo), rank, G);
+      const int nm = sh.fwd[l].n_maps;
       if (nm > 0) {
-        flow_conv_fwd(rt, l, nm);
-        flow_pool(rt, l, nm, tag, taps);
+        flow_conv_fwd<ID>(rt, l);
+        flow_pool<ID>(rt, l, nm, tag, taps);
       }
       STAMP(3 + 2 * l);
     }
     // ---- FP, first fully connected layer: partial sums over the own columns, exchanged ----
     {
-      const float* wc = lds + F.fc[0].o_w;
-      const float* vcol = lds + F.conv[n_conv - 1].o_pool;
+      const float* wc = lds + L1.o_w;
+      const float* vcol = lds + Cc.o_pool;
       if (rank < NR) {
-        gtagged* xp = F.xp + ((size_t)par * NR + rank) * n1;
+        gtagged* xp = Q.xp + ((size_t)par * NR + rank) * n1;
         for (int k = tid; k < n1; k += WG) {
           float s = 0.f;
           for (int c0 = 0; c0 < ncols; c0 += 8) {
@@ -955,8 +1002,8 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
         }
       }
       STAMP(30);
-      float* y = lds + F.fc[0].o_act;
-      if (!flow_reduce_partials(rt, F.xp + (size_t)par * NR * n1, NR, n1, lds + F.fc[0].o_b, y, part, tag)) return;
+      float* y = lds + L1.o_act;
+      if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, part, tag)) return;
       STAMP(31);
       if (!L1.is_output) {
         for (int k = tid; k < n1; k += WG) y[k] = f_act(y[k]);
@@ -964,10 +1011,11 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       }
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----
+#pragma unroll
     for (int f = 1; f < n_fc; ++f) {
-      const LayerDev& L = sh.L[n_conv + f];
-      float* y = lds + F.fc[f].o_act;
-      flow_matvec(lds + F.fc[f].o_w, lds + F.fc[f].o_b, lds + F.fc[f - 1].o_act, y, uni(L.n_out), uni(L.n_in));
+      const FcSpec& L = Z.fc[f];
+      float* y = lds + L.o_act;
+      flow_matvec(lds + L.o_w, lds + L.o_b, lds + Z.fc[f - 1].o_act, y, uni_of<ID>(L.n_out), uni_of<ID>(L.n_in));
       if (!L.is_output) {
         for (int k = tid; k < L.n_out; k += WG) y[k] = f_act(y[k]);
         __syncthreads();
@@ -978,12 +1026,13 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     // classes every wavefront works them out for itself (lane k holds class k), so nobody waits
     // for a broadcast: the output layer's BP below reads delta_k straight from its own wave.
     float dreg = 0.f;
-    const LayerDev& Lo = sh.L[n_conv + n_fc - 1];
-    const int N = uni(Lo.n_out);
+    const FcSpec& Lo = Z.fc[n_fc - 1];
+    const FlowFcPtrs& Po = Q.fc[n_fc - 1];
+    const int N = n_classes;
     const bool wave_softmax = N <= 64;
     {
-      float* y = lds + F.fc[n_fc - 1].o_act;
-      float* d = lds + F.fc[n_fc - 1].o_delta;
+      float* y = lds + Lo.o_act;
+      float* d = lds + Lo.o_delta;
       if (wave_softmax) {
         const int k = tid & 63;
         const float yk = (k < N) ? y[k] : -INFINITY;
@@ -998,7 +1047,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
             if (train && k == label) status->loss = -logf(p);
           }
           if (taps || n_fc == 1) d[k] = dreg;
-          if (taps && rank == 0) Lo.act[k] = p;
+          if (taps && rank == 0) Po.act[k] = p;
         }
         if (n_fc == 1) __syncthreads();  // the first FC layer's BP reads the deltas from LDS
       } else {
@@ -1016,30 +1065,32 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
             if (rank == 0) {
               if (a.probs_out) a.probs_out[t * n_classes + k] = p;
               if (train && k == label) status->loss = -logf(p);
-              if (taps) Lo.act[k] = p;
+              if (taps) Po.act[k] = p;
             }
           }
         }
         __syncthreads();
       }
     }
-    if (taps && rank == 0)
-      for (int f = 0; f + 1 < n_fc; ++f) {
-        const LayerDev& L = sh.L[n_conv + f];
-        for (int k = tid; k < L.n_out; k += WG) L.act[k] = lds[F.fc[f].o_act + k];
-      }
+    if (taps && rank == 0) {
+#pragma unroll
+      for (int f = 0; f + 1 < n_fc; ++f)
+        for (int k = tid; k < Z.fc[f].n_out; k += WG) Q.fc[f].act[k] = lds[Z.fc[f].o_act + k];
+    }
     STAMP(33);
     if (!train) continue;
 
     // ---- BP + AW, fully connected layers behind the first (every rank, same arithmetic) ----
+#pragma unroll
     for (int f = n_fc - 1; f >= 1; --f) {
-      const LayerDev& L = sh.L[n_conv + f];
-      float* W = lds + F.fc[f].o_w;
-      float* b = lds + F.fc[f].o_b;
-      const float* d = lds + F.fc[f].o_delta;
-      const float* v = lds + F.fc[f - 1].o_act;
-      float* dprev = lds + F.fc[f - 1].o_delta;
-      const int n_in = uni(L.n_in), n_out = uni(L.n_out);
+      const FcSpec& L = Z.fc[f];
+      const FlowFcPtrs& PL = Q.fc[f];
+      float* W = lds + L.o_w;
+      float* b = lds + L.o_b;
+      const float* d = lds + L.o_delta;
+      const float* v = lds + Z.fc[f - 1].o_act;
+      float* dprev = lds + Z.fc[f - 1].o_delta;
+      const int n_in = uni_of<ID>(L.n_in), n_out = uni_of<ID>(L.n_out);
       const bool from_reg = wave_softmax && f == n_fc - 1;
       for (int m = tid; m < n_in; m += WG) {
         const float vm = v[m];
@@ -1057,7 +1108,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
             const int k = k0 + u;
             if (k < n_out) {
               g = fmaf(wv[u], dv[u], g);
-              if (g_out) { if (rank == 0) g_out[L.w_canon + (long long)k * n_in + m] = dv[u] * vm; }
+              if (g_out) { if (rank == 0) g_out[PL.w_canon + (long long)k * n_in + m] = dv[u] * vm; }
               else W[k * n_in + m] = fmaf(-lr, dv[u] * vm, wv[u]);
             }
           }
@@ -1066,22 +1117,22 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       }
       for (int k = tid; k < n_out; k += WG) {
         const float dk = from_reg ? dreg : d[k];   // tid < 64 here: lane k of wave 0
-        if (g_out) { if (rank == 0) g_out[L.b_canon + k] = dk; }
+        if (g_out) { if (rank == 0) g_out[PL.b_canon + k] = dk; }
         else b[k] = fmaf(-lr, dk, b[k]);
-        if (taps && rank == 0) L.delta[k] = dk;
+        if (taps && rank == 0) PL.delta[k] = dk;
       }
       __syncthreads();
     }
     STAMP(34);
     {  // ---- BP + AW, first fully connected layer: own columns ----
-      float* wc = lds + F.fc[0].o_w;
-      float* b = lds + F.fc[0].o_b;
-      const float* d = lds + F.fc[0].o_delta;
-      const float* vcol = lds + F.conv[n_conv - 1].o_pool;
-      float* dconv = lds + F.conv[n_conv - 1].o_delta;
-      const int* yxc = (const int*)(lds + F.conv[n_conv - 1].o_yx);
-      const FlowConv& Cc = F.conv[n_conv - 1];
-      const int Moc = uni(Lc.Mo);
+      const FlowFcPtrs& P1 = Q.fc[0];
+      float* wc = lds + L1.o_w;
+      float* b = lds + L1.o_b;
+      const float* d = lds + L1.o_delta;
+      const float* vcol = lds + Cc.o_pool;
+      float* dconv = lds + Cc.o_delta;
+      const int* yxc = (const int*)(lds + Cc.o_yx);
+      const int Moc = uni_of<ID>(Cc.Mo);
       const int wave = tid >> 6, lane = tid & 63;
       const FDiv dN(n1), dHW(HWc);
       for (int c = wave; c < ncols; c += WG / 64) {
@@ -1094,10 +1145,10 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
           const int am = dHW.div(c), q = c - am * HWc;
           const size_t o = (size_t)(rank + am * G) * HWc + q;
           if (n_conv >= 2) {  // the layer below pulls through these: on their way at once
-            put_f(Cc.x_delta + (size_t)par * Moc * HWc + o, dc, tag);
-            put_i(Cc.x_yx + (size_t)par * Moc * HWc + o, yxc[c], tag);
+            put_f(Pc.x_delta + (size_t)par * Moc * HWc + o, dc, tag);
+            put_i(Pc.x_yx + (size_t)par * Moc * HWc + o, yxc[c], tag);
           }
-          if (taps) Lc.delta[o] = dc;
+          if (taps) Pc.delta[o] = dc;
         }
       }
       __syncthreads();
@@ -1106,25 +1157,26 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
         const float g = d[k] * vcol[c];
         if (g_out) {
           const int am = dHW.div(c), q = c - am * HWc;
-          g_out[L1.w_canon + (long long)k * L1.n_in + (long long)(rank + am * G) * HWc + q] = g;
+          g_out[P1.w_canon + (long long)k * L1.n_in + (long long)(rank + am * G) * HWc + q] = g;
         } else {
           wc[x] = fmaf(-lr, g, wc[x]);
         }
       }
       for (int k = tid; k < n1; k += WG) {
-        if (g_out) { if (rank == 0) g_out[L1.b_canon + k] = d[k]; }
+        if (g_out) { if (rank == 0) g_out[P1.b_canon + k] = d[k]; }
         else b[k] = fmaf(-lr, d[k], b[k]);
-        if (taps && rank == 0) L1.delta[k] = d[k];
+        if (taps && rank == 0) P1.delta[k] = d[k];
       }
     }
     STAMP(35);
     // ---- BP + AW, convolutional layers, top down ----
+#pragma unroll
     for (int l = n_conv - 1; l >= 0; --l) {
-      const LayerDev& L = sh.L[l];
-      const FlowConv& C = F.conv[l];
-      const int K = uni(L.K), KK = K * K, HW = uni(L.Hp) * uni(L.Wp), stride = uni(L.S) + 1, Wi = uni(L.Wi),
-                HiWi = uni(L.Hi) * Wi, Mo = uni(L.Mo);
-      const int nm = n_mine(Mo, rank, G);
+      const ConvSpec& C = Z.conv[l];
+      const FlowConvPtrs& P = Q.conv[l];
+      const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1,
+                Wi = uni_of<ID>(C.Wi), HiWi = uni_of<ID>(C.Hi) * Wi, Mo = uni_of<ID>(C.Mo);
+      const int nm = sh.fwd[l].n_maps;
       const float* dl = lds + C.o_delta;
       const int* yx = (const int*)(lds + C.o_yx);
       if (l < n_conv - 1 && (l >= 1 || taps)) {  // (the last layer's went out with the first FC layer's BP)
@@ -1133,10 +1185,10 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
           const int am = dHW.div(x), q = x - am * HW;
           const size_t o = (size_t)(rank + am * G) * HW + q;
           if (l >= 1) {
-            put_f(C.x_delta + (size_t)par * Mo * HW + o, dl[x], tag);
-            put_i(C.x_yx + (size_t)par * Mo * HW + o, yx[x], tag);
+            put_f(P.x_delta + (size_t)par * Mo * HW + o, dl[x], tag);
+            put_i(P.x_yx + (size_t)par * Mo * HW + o, yx[x], tag);
           }
-          if (taps) L.delta[o] = dl[x];
+          if (taps) P.delta[o] = dl[x];
         }
       }
       STAMP(40 + 4 * l);
@@ -1144,12 +1196,12 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
         const int* cidx = (const int*)(lds + C.o_cidx);
         const int* ncf = (const int*)(lds + C.o_ncf);
         const float* in = lds + C.o_in;
-        const int pitch = uni(L.max_conn);
+        const int pitch = uni_of<ID>(C.max_conn);
         const int per_map = pitch * KK;
         const FDiv dPM(per_map), dKK(KK), dK(K);
-        const bool full = uni(L.full_table) != 0;
-        const int Mi = uni(L.Mi);
-        flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, uni(C.wgrad_R_log2), lr, g_out, [&](int wi) {
+        const bool full = C.full_table != 0;
+        const int Mi = uni_of<ID>(C.Mi);
+        flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, g_out, [&](int wi) {
           const int am = dPM.div(wi), rem = wi - am * per_map;
           const int c = dKK.div(rem), tt = rem - c * KK;
           const int ky = dK.div(tt), kx = tt - ky * K;
@@ -1161,7 +1213,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
           I.canon = 0;
           if (g_out) {
             const int j = rank + am * G;
-            I.canon = L.w_canon + (long long)((full ? j * Mi : L.csr_ptr[j]) + c) * KK + tt;
+            I.canon = P.w_canon + (long long)((full ? j * Mi : P.csr_ptr[j]) + c) * KK + tt;
           }
           return I;
         });
@@ -1171,7 +1223,7 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
           for (int q = lane; q < HW; q += 64) s += dl[am * HW + q];
           s = f_wave_sum(s);
           if (lane == 0) {
-            if (g_out) g_out[L.b_canon + rank + am * G] = s;
+            if (g_out) g_out[P.b_canon + rank + am * G] = s;
             else lds[C.o_bf + am] = fmaf(-lr, s, lds[C.o_bf + am]);
           }
         }
@@ -1179,37 +1231,38 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
       }
       STAMP(41 + 4 * l);
       if (l >= 1) {
-        const int nb = n_mine(uni(L.Mi), rank, G);
+        const int nb = sh.pull[l].n_maps;
         if (nb > 0) {
-          float* dall = lds + F.o_dall;
-          int* yxall = (int*)(lds + F.o_yxall);
-          if (!gather2(rt, (unsigned int*)dall, C.x_delta + (size_t)par * Mo * HW, (unsigned int*)yxall,
-                       C.x_yx + (size_t)par * Mo * HW, Mo * HW, tag))
+          float* dall = lds + Z.o_dall;
+          int* yxall = (int*)(lds + Z.o_yxall);
+          if (!gather2(rt, (unsigned int*)dall, P.x_delta + (size_t)par * Mo * HW, (unsigned int*)yxall,
+                       P.x_yx + (size_t)par * Mo * HW, Mo * HW, tag))
             return;
           STAMP(42 + 4 * l);
-          flow_pull(rt, l, nb, dall, yxall);
+          flow_pull<ID>(rt, l, dall, yxall);
           STAMP(43 + 4 * l);
           if (!g_out) {
             // pull copy of the filters that read the own maps of the layer below (stored rotated)
             const int* bj = (const int*)(lds + C.o_bj);
             const int* ncb = (const int*)(lds + C.o_ncb);
             const float* in = lds + C.o_in;
-            const int pitch = uni(C.max_back);
+            const int pitch = uni_of<ID>(C.max_back);
             const int per_map = pitch * KK;
             const FDiv dPM(per_map), dKK(KK), dK(K);
-            flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, uni(C.wgrad_R_log2), lr, (gfloat*)nullptr, [&](int wi) {
-              const int ab = dPM.div(wi), rem = wi - ab * per_map;
-              const int e = dKK.div(rem), tt = KK - 1 - (rem - e * KK);
-              const int ky = dK.div(tt), kx = tt - ky * K;
-              const int j = bj[ab * pitch + e];
-              WgradInfo I;
-              I.ok = e < ncb[ab];
-              I.d = dall + j * HW;
-              I.yx = yxall + j * HW;
-              I.in = in + (rank + ab * G) * HiWi + ky * Wi + kx;
-              I.canon = 0;
-              return I;
-            });
+            flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, (gfloat*)nullptr,
+                       [&](int wi) {
+                         const int ab = dPM.div(wi), rem = wi - ab * per_map;
+                         const int e = dKK.div(rem), tt = KK - 1 - (rem - e * KK);
+                         const int ky = dK.div(tt), kx = tt - ky * K;
+                         const int j = bj[ab * pitch + e];
+                         WgradInfo I;
+                         I.ok = e < ncb[ab];
+                         I.d = dall + j * HW;
+                         I.yx = yxall + j * HW;
+                         I.in = in + (rank + ab * G) * HiWi + ky * Wi + kx;
+                         I.canon = 0;
+                         return I;
+                       });
             __syncthreads();
           }
         }
@@ -1217,18 +1270,35 @@ __global__ void __launch_bounds__(WG) k_resident(const ProgramDev* __restrict__ 
     }
     STAMP(60);
   }
-  if (!g_out && a.train) flow_store(rt);
+  if (!g_out && a.train) flow_store<ID>(rt);
 }
 
-hipError_t launch_resident(int grid, size_t lds_bytes, hipStream_t stream, const ProgramDev* d_prog,
-                           const FlowDev* d_flow, StatusDev* d_status, const RunArgs& a) {
-  hipError_t e = hipFuncSetAttribute((const void*)k_resident, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+template <int ID>
+static hipError_t launch_resident_id(int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
+                                     const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a) {
+  hipError_t e = hipFuncSetAttribute((const void*)k_resident<ID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   RunArgs args = a;
-  void* params[] = {(void*)&d_prog, (void*)&d_flow, (void*)&d_status, (void*)&args};
-  return hipLaunchCooperativeKernel((const void*)k_resident, dim3(grid), dim3(WG), params, (unsigned int)lds_bytes, stream);
+  void* params[] = {(void*)&d_spec, (void*)&d_ptrs, (void*)&d_status, (void*)&args};
+  return hipLaunchCooperativeKernel((const void*)k_resident<ID>, dim3(grid), dim3(WG), params, (unsigned int)lds_bytes, stream);
 }
 
-size_t resident_static_lds_bytes() { return sizeof(Shared); }
+// static_id: 0 = the kernel for any network; k > 0 = the one compiled for StaticSpec<k> (the caller
+// has checked that the plan in *d_spec equals it)
+hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
+                           const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a) {
+  switch (static_id) {
+    case 1: return launch_resident_id<1>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
+    case 2: return launch_resident_id<2>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
+    default: return launch_resident_id<0>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
+  }
+}
+
+// which compiled-in network, if any, has exactly this plan
+int resident_static_id(const FlowSpec& z) {
+  if (__builtin_memcmp(&z, &StaticSpec<1>::value, sizeof(FlowSpec)) == 0) return 1;
+  if (__builtin_memcmp(&z, &StaticSpec<2>::value, sizeof(FlowSpec)) == 0) return 2;
+  return 0;
+}
 
 }  // namespace cnn355

@@ -1,0 +1,253 @@
+// Resident mode: the shape of a network and the plan of a team, as plain integers, and the planner
+// that derives the plan.  Everything here is constexpr, so that the same planner serves the host
+// at run time (any network) and the compiler (kernels instantiated for a fixed list of networks,
+// in which every size, offset and trip count is then a literal).
+#pragma once
+#include "cnn355_dev.h"
+
+namespace cnn355 {
+
+// One convolutional layer (with the max-pooling layer folded into it) and its share of a rank's LDS.
+struct ConvSpec {
+  int Mi, Hi, Wi, Mo, Ho, Wo, K, S, Kp, Hp, Wp;
+  int max_conn;     // longest row of the connection table
+  int max_back;     // longest column
+  int full_table;
+  int n_own;        // most output maps a rank owns: ceil(Mo / G)
+  int n_own_below;  // most input maps a rank owns (maps of the layer below): ceil(Mi / G); 0 for the first layer
+  int wgrad_R_log2; // pooled positions are split 2^this ways when summing a weight gradient
+  int pull_chunk;   // output maps rebuilt at full resolution per pass of the delta pull
+  int fwd_strip;    // output pixels per lane in FP (0: one pixel per lane, any stride)
+  int pull_strip;   // same for the delta pull through this layer
+  int has_x_out;    // the pooled outputs are exchanged (a convolutional layer follows)
+  // LDS offsets, in floats
+  int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
+  int o_wf;     // [n_own][max_conn][K*K] forward copy of the filters
+  int o_bf;     // [n_own] biases
+  int o_cidx;   // [n_own][max_conn] input map of every connection (int)
+  int o_ncf;    // [n_own] connections of every own map (int)
+  int o_wb;     // [n_own_below][max_back][K*K] pull copy of the filters, rotated (layers above the first)
+  int o_bj;     // [n_own_below][max_back] output map of every entry (int)
+  int o_ncb;    // [n_own_below] entries of every own input map (int)
+  int o_pool;   // [n_own][Hp*Wp] pooled outputs of the own maps
+  int o_yx;     // [n_own][Hp*Wp] winner coordinates (y << 16 | x) (int)
+  int o_delta;  // [n_own][Hp*Wp] deltas at the winners
+  int o_tab_fwd;   // [3][WG] every lane's share of the FP job (int), or -1
+  int o_tab_pull;  // [3][WG] every lane's share of the pull job (int), or -1
+};
+
+struct FcSpec {
+  int n_in, n_out, is_output;
+  int o_w;      // first layer: [columns of the own maps][n_out]; others: [n_out][n_in], every rank
+  int o_b;      // [n_out]
+  int o_act;    // [n_out]
+  int o_delta;  // [n_out]
+};
+
+struct FlowSpec {
+  int G;            // ranks
+  int stride;       // rank r is workgroup r * stride of the launch (8: all ranks on one XCD)
+  int n_conv, n_fc;
+  int n_col_ranks;  // ranks that own maps of the last convolutional layer (and so columns of the first FC layer)
+  int n_classes;
+  int lds_floats;
+  int o_act;        // [max n_own*Ho*Wo] full-resolution outputs of the own maps of the layer being computed
+  int o_part;       // partial sums
+  int o_scratch;    // delta maps of a chunk of output maps rebuilt at full resolution, zero border included
+  int scratch_floats;
+  int o_dall;       // [max Mo*Hp*Wp] deltas of every map of the layer being pulled through
+  int o_yxall;      // same, winner coordinates
+  ConvSpec conv[FLOW_MAX_CONV];
+  FcSpec fc[FLOW_MAX_FC];
+};
+
+// reasons a network cannot run in resident mode
+enum FlowWhy : int {
+  FLOW_OK = 0, FLOW_NO_CONV, FLOW_TOO_MANY_LAYERS, FLOW_BAD_STRIDE, FLOW_TOO_LARGE, FLOW_NO_LDS
+};
+
+constexpr int flow_min(int a, int b) { return a < b ? a : b; }
+constexpr int flow_max(int a, int b) { return a > b ? a : b; }
+constexpr long long flow_minl(long long a, long long b) { return a < b ? a : b; }
+constexpr long long flow_maxl(long long a, long long b) { return a > b ? a : b; }
+
+// Strip width for a correlation job of n_maps maps of rows x width pixels with up to max_cnt
+// connections each: the one of {4, 5, 7} that leaves the least multiply-accumulate work per lane
+// once the connections are shared over the spare lanes (the rule the kernel applies), the wider
+// one on a tie; 0 = one pixel per lane (any stride, any kernel size).
+constexpr int flow_strip_for(int K, int stride, int n_maps, int rows, int width, int max_cnt) {
+  if (stride != 1 || K < 2 || K > 5) return 0;
+  int best = 4;
+  long long best_cost = -1;
+  const int widths[3] = {4, 5, 7};
+  for (int wi = 0; wi < 3; ++wi) {
+    const int sw = widths[wi];
+    const long long U = (long long)n_maps * rows * ((width + sw - 1) / sw);
+    long long iters = max_cnt;
+    if (U < WG) {
+      const long long r_max = flow_maxl(1, flow_minl(WG / U, max_cnt));
+      iters = (max_cnt + r_max - 1) / r_max;
+    }
+    const long long passes = (U + WG - 1) / WG;
+    const long long cost = passes * iters * (sw * K * K + (sw + 2 * K - 1) * K / 2);
+    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best = sw; }
+  }
+  return best;
+}
+
+// Choose the team and lay out every rank's LDS.  On entry Z holds the shape (n_conv, n_fc,
+// n_classes, and per layer Mi..Wp, max_conn, max_back, full_table / n_in, n_out, is_output); on
+// success the rest of Z is filled in.  team_ranks / team_stride: 0 = automatic.
+constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) {
+  const int n_conv = Z.n_conv, n_fc = Z.n_fc;
+  if (n_conv < 1) return FLOW_NO_CONV;
+  if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1) return FLOW_TOO_MANY_LAYERS;
+  int max_maps = 1;
+  for (int l = 0; l < n_conv; ++l) max_maps = flow_max(max_maps, Z.conv[l].Mo);
+  int stride = team_stride > 0 ? team_stride : 0;
+  int G = team_ranks > 0 ? team_ranks : max_maps;
+  if (n_cu <= 0) n_cu = 256;
+  if (stride == 0) stride = (G <= n_cu / 8) ? 8 : 1;
+  if (stride != 1 && stride != 8) return FLOW_BAD_STRIDE;
+  G = flow_max(1, flow_min(flow_min(G, max_maps), n_cu / stride));
+  Z.G = G;
+  Z.stride = stride;
+
+  long long off = 0;
+  auto take = [&off](long long n) {
+    const long long o = off;
+    off += (n + 3) / 4 * 4;
+    return (int)flow_minl(o, 1 << 30);
+  };
+  long long max_act = 1, max_part = (long long)FLOW_STRIP_MAX * WG, max_dall = 1, max_hwd = 0;
+  for (int l = 0; l < n_conv; ++l) {
+    ConvSpec& C = Z.conv[l];
+    const int KK = C.K * C.K, HW = C.Hp * C.Wp;
+    if (C.Ho >= 32768 || C.Wo >= 65536) return FLOW_TOO_LARGE;
+    if ((long long)C.Mi * C.Hi * C.Wi >= (1 << 20) || (long long)C.Mo * C.Ho * C.Wo >= (1 << 20)) return FLOW_TOO_LARGE;
+    C.n_own = (C.Mo + G - 1) / G;
+    C.n_own_below = l >= 1 ? (C.Mi + G - 1) / G : 0;
+    C.max_back = flow_max(1, C.max_back);
+    C.has_x_out = (l + 1 < n_conv) ? 1 : 0;
+    C.o_in = take((long long)C.Mi * C.Hi * C.Wi);
+    C.o_wf = take((long long)C.n_own * C.max_conn * KK);
+    C.o_bf = take(C.n_own);
+    C.o_cidx = take((long long)C.n_own * C.max_conn);
+    C.o_ncf = take(C.n_own);
+    C.fwd_strip = flow_strip_for(C.K, C.S + 1, C.n_own, C.Ho, C.Wo, C.max_conn);
+    C.o_wb = 0; C.o_bj = 0; C.o_ncb = 0; C.pull_strip = 0; C.pull_chunk = 1;
+    if (l >= 1) {
+      C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
+      C.o_bj = take((long long)C.n_own_below * C.max_back);
+      C.o_ncb = take(C.n_own_below);
+      C.pull_strip = flow_strip_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.max_back);
+      max_dall = flow_maxl(max_dall, (long long)C.Mo * HW);
+      max_hwd = flow_maxl(max_hwd, (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1));
+      max_part = flow_maxl(max_part, (long long)C.n_own_below * C.Hi * C.Wi);
+    }
+    C.o_pool = take((long long)C.n_own * HW);
+    C.o_yx = take((long long)C.n_own * HW);
+    C.o_delta = take((long long)C.n_own * HW);
+    max_act = flow_maxl(max_act, (long long)C.n_own * C.Ho * C.Wo);
+    max_part = flow_maxl(max_part, (long long)C.n_own * C.Ho * C.Wo);
+    // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
+    long long n_w = (long long)C.n_own * C.max_conn * KK;
+    if (l >= 1) n_w = flow_minl(n_w, (long long)C.n_own_below * C.max_back * KK);
+    int rl2 = 0;
+    while (rl2 < 6 && (n_w << (rl2 + 1)) <= WG && (2 << rl2) <= HW) ++rl2;
+    C.wgrad_R_log2 = rl2;
+    C.o_tab_fwd = -1;
+    C.o_tab_pull = -1;
+  }
+  const ConvSpec& Cl = Z.conv[n_conv - 1];
+  Z.n_col_ranks = flow_min(G, Cl.Mo);
+  for (int f = 0; f < n_fc; ++f) {
+    FcSpec& Q = Z.fc[f];
+    Q.o_w = take(f == 0 ? (long long)Cl.n_own * Cl.Hp * Cl.Wp * Q.n_out : (long long)Q.n_out * Q.n_in);
+    Q.o_b = take(Q.n_out);
+    Q.o_act = take(Q.n_out);
+    Q.o_delta = take(Q.n_out);
+  }
+  Z.o_act = take(max_act);
+  Z.o_part = take(max_part);
+  Z.o_dall = take(n_conv > 1 ? max_dall : 0);
+  Z.o_yxall = take(n_conv > 1 ? max_dall : 0);
+  const long long pad = 16;  // strips read a few floats past the end of the last row of a map
+  const long long need = n_conv > 1 ? max_hwd + pad : pad;
+  if (off + need > FLOW_LDS_FLOATS_MAX) return FLOW_NO_LDS;
+  // lane tables of the correlation jobs, while there is room (a rank decodes its share of a job
+  // once instead of once per image); the first layers' jobs first
+  for (int l = 0; l < n_conv; ++l) {
+    if (Z.conv[l].n_own < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX) Z.conv[l].o_tab_fwd = take(3 * WG);
+    if (l >= 1 && Z.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX)
+      Z.conv[l].o_tab_pull = take(3 * WG);
+  }
+  // the zero-bordered delta maps of the pull: the more fit, the fewer passes
+  long long scratch = need;
+  for (int l = 1; l < n_conv; ++l) {
+    const ConvSpec& C = Z.conv[l];
+    scratch = flow_maxl(scratch, (long long)C.Mo * (C.Hi + C.K - 1) * (C.Wi + C.K - 1) + pad);
+  }
+  scratch = flow_minl(scratch, (long long)FLOW_LDS_FLOATS_MAX - off);
+  Z.o_scratch = take(scratch);
+  Z.scratch_floats = (int)scratch;
+  Z.lds_floats = (int)off;
+  for (int l = 1; l < n_conv; ++l) {
+    ConvSpec& C = Z.conv[l];
+    const long long hwd = (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1);
+    C.pull_chunk = (int)flow_maxl(1, flow_minl(C.Mo, (scratch - pad) / hwd));
+  }
+  return FLOW_OK;
+}
+
+// ---- networks the resident kernel is also compiled for, every size a literal --------------------
+// A network of convolutional layers with full connection tables, each followed by max-pooling of
+// Kp (1 = none), then fully connected layers; Eq. 1 of Sec. 2.2 gives the map sizes.
+struct StaticConv { int maps, K, S, Kp; };
+constexpr FlowSpec flow_static_spec(int C0, int H0, int W0, int n_conv, const StaticConv* conv, int n_fc, const int* fc,
+                                    int team_ranks, int team_stride) {
+  FlowSpec Z{};
+  Z.n_conv = n_conv;
+  Z.n_fc = n_fc;
+  int m = C0, h = H0, w = W0;
+  for (int l = 0; l < n_conv; ++l) {
+    ConvSpec& C = Z.conv[l];
+    C.Mi = m; C.Hi = h; C.Wi = w;
+    C.Mo = conv[l].maps; C.K = conv[l].K; C.S = conv[l].S; C.Kp = conv[l].Kp;
+    C.Ho = (h - C.K) / (C.S + 1) + 1;
+    C.Wo = (w - C.K) / (C.S + 1) + 1;
+    C.Hp = C.Ho / C.Kp; C.Wp = C.Wo / C.Kp;
+    C.max_conn = m; C.max_back = C.Mo; C.full_table = 1;
+    m = C.Mo; h = C.Hp; w = C.Wp;
+  }
+  int n_in = m * h * w;
+  for (int f = 0; f < n_fc; ++f) {
+    Z.fc[f].n_in = n_in;
+    Z.fc[f].n_out = fc[f];
+    Z.fc[f].is_output = (f + 1 == n_fc) ? 1 : 0;
+    n_in = fc[f];
+  }
+  Z.n_classes = n_in;
+  flow_plan(Z, team_ranks, team_stride, 256);
+  return Z;
+}
+
+// 1: 1x29x29-20C4-MP2-40C5-MP3-150N-10N (the benchmark network), automatic team
+// 2: 1x29x29-40C4-MP2-80C5-MP3-300N-10N, automatic team
+constexpr int FLOW_N_STATIC = 2;
+template <int ID>
+struct StaticSpec;
+template <>
+struct StaticSpec<1> {
+  static constexpr StaticConv conv[2] = {{20, 4, 0, 2}, {40, 5, 0, 3}};
+  static constexpr int fc[2] = {150, 10};
+  static constexpr FlowSpec value = flow_static_spec(1, 29, 29, 2, conv, 2, fc, 0, 0);
+};
+template <>
+struct StaticSpec<2> {
+  static constexpr StaticConv conv[2] = {{40, 4, 0, 2}, {80, 5, 0, 3}};
+  static constexpr int fc[2] = {300, 10};
+  static constexpr FlowSpec value = flow_static_spec(1, 29, 29, 2, conv, 2, fc, 0, 0);
+};
+
+}  // namespace cnn355
