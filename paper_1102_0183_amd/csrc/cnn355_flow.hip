@@ -176,6 +176,57 @@ __device__ __forceinline__ int uni_of(int v) {
   else return v;
 }
 
+// Loops over layers.  In a kernel instantiated for a fixed network they are unrolled by the
+// compiler front end itself (the layer index is a template constant in every copy), so that
+// every size and offset taken from the plan folds; otherwise they are ordinary loops.  The body
+// returns false to stop (a wait gave up).
+template <int V>
+struct IC { static constexpr int value = V; };
+__device__ __forceinline__ constexpr int lv(int x) { return x; }
+template <int V>
+__device__ __forceinline__ constexpr int lv(IC<V>) { return V; }
+
+template <int I, int MAXN, class F>
+__device__ __forceinline__ bool for_up_static(int n, F& f) {
+  if constexpr (I < MAXN) {
+    if (I < n && !f(IC<I>{})) return false;
+    return for_up_static<I + 1, MAXN>(n, f);
+  } else {
+    return true;
+  }
+}
+template <int I, int LO, class F>
+__device__ __forceinline__ bool for_down_static(int n, F& f) {
+  if constexpr (I >= LO) {
+    if (I < n && !f(IC<I>{})) return false;
+    return for_down_static<I - 1, LO>(n, f);
+  } else {
+    return true;
+  }
+}
+// l = LO .. n-1
+template <int ID, int LO, int MAXN, class F>
+__device__ __forceinline__ bool for_up(int n, F f) {
+  if constexpr (ID == 0) {
+    for (int l = LO; l < n; ++l)
+      if (!f(l)) return false;
+    return true;
+  } else {
+    return for_up_static<LO, MAXN>(n, f);
+  }
+}
+// l = n-1 .. LO
+template <int ID, int LO, int MAXN, class F>
+__device__ __forceinline__ bool for_down(int n, F f) {
+  if constexpr (ID == 0) {
+    for (int l = n - 1; l >= LO; --l)
+      if (!f(l)) return false;
+    return true;
+  } else {
+    return for_down_static<MAXN - 1, LO>(n, f);
+  }
+}
+
 // Bounded polling: returns false when this lane has polled too often or another workgroup has
 // raised the abort flag; the flag is raised so that every workgroup leaves.
 __device__ __forceinline__ bool poll_again(const Rt& rt, unsigned int& spins) {
@@ -256,8 +307,8 @@ __device__ __forceinline__ void flow_load(const Rt& rt) {
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
   for (int x = tid; x < Z.scratch_floats; x += WG) lds[Z.o_scratch + x] = 0.f;  // stays zero between uses
-#pragma unroll
-  for (int l = 0; l < Z.n_conv; ++l) {
+  for_up<ID, 0, FLOW_MAX_CONV>(Z.n_conv, [&](auto lc) {
+    const int l = lv(lc);
     const ConvSpec& C = Z.conv[l];
     const FlowConvPtrs& P = Q.conv[l];
     const int KK = C.K * C.K;
@@ -301,7 +352,8 @@ __device__ __forceinline__ void flow_load(const Rt& rt) {
         if (tid == 0) ncb[a] = ne;
       }
     }
-  }
+    return true;
+  });
   {  // first fully connected layer: the columns fed by the own maps of the last convolutional layer
     const ConvSpec& Cc = Z.conv[Z.n_conv - 1];
     const FcSpec& L = Z.fc[0];
@@ -315,12 +367,13 @@ __device__ __forceinline__ void flow_load(const Rt& rt) {
     }
     for (int k = tid; k < n1; k += WG) lds[L.o_b + k] = Q.fc[0].bias[k];
   }
-#pragma unroll
-  for (int f = 1; f < Z.n_fc; ++f) {
+  for_up<ID, 1, FLOW_MAX_FC>(Z.n_fc, [&](auto fc_) {
+    const int f = lv(fc_);
     const FcSpec& L = Z.fc[f];
     for (int x = tid; x < L.n_out * L.n_in; x += WG) lds[L.o_w + x] = Q.fc[f].w[x];
     for (int k = tid; k < L.n_out; k += WG) lds[L.o_b + k] = Q.fc[f].bias[k];
-  }
+    return true;
+  });
   __syncthreads();
 }
 
@@ -331,8 +384,8 @@ __device__ __forceinline__ void flow_store(const Rt& rt) {
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
   __syncthreads();
-#pragma unroll
-  for (int l = 0; l < Z.n_conv; ++l) {
+  for_up<ID, 0, FLOW_MAX_CONV>(Z.n_conv, [&](auto lc) {
+    const int l = lv(lc);
     const ConvSpec& C = Z.conv[l];
     const FlowConvPtrs& P = Q.conv[l];
     const int KK = C.K * C.K;
@@ -345,7 +398,8 @@ __device__ __forceinline__ void flow_store(const Rt& rt) {
       for (int x = tid; x < nc * KK; x += WG) P.w[(size_t)cb * KK + x] = lds[C.o_wf + a * C.max_conn * KK + x];
       if (tid == 0) P.bias[j] = lds[C.o_bf + a];
     }
-  }
+    return true;
+  });
   {
     const ConvSpec& Cc = Z.conv[Z.n_conv - 1];
     const FcSpec& L = Z.fc[0];
@@ -359,14 +413,14 @@ __device__ __forceinline__ void flow_store(const Rt& rt) {
     if (rank == 0)
       for (int k = tid; k < n1; k += WG) Q.fc[0].bias[k] = lds[L.o_b + k];
   }
-  if (rank == 0) {
-#pragma unroll
-    for (int f = 1; f < Z.n_fc; ++f) {
+  if (rank == 0)
+    for_up<ID, 1, FLOW_MAX_FC>(Z.n_fc, [&](auto fc_) {
+      const int f = lv(fc_);
       const FcSpec& L = Z.fc[f];
       for (int x = tid; x < L.n_out * L.n_in; x += WG) Q.fc[f].w[x] = lds[L.o_w + x];
       for (int k = tid; k < L.n_out; k += WG) Q.fc[f].bias[k] = lds[L.o_b + k];
-    }
-  }
+      return true;
+    });
 }
 
 // ---- the two multiply-accumulate loops -------------------------------------------------------------
@@ -400,26 +454,33 @@ __device__ __forceinline__ float pixel_mac_k(int K, const float* in, const float
   }
 }
 
-// SW consecutive output pixels of one row (unit stride): per connection and kernel row, SW+K-1
-// inputs and K weights are read once and feed SW*K multiply-adds.
-template <int K, int SW>
+// A tile of TH rows x SW consecutive output pixels (unit stride).  Per connection the K*K weights
+// are read once; every input row of SW+K-1 floats is read once and feeds the (up to K) kernel rows
+// and (up to TH) output rows it meets: (TH+K-1)(SW+K-1) + K*K LDS reads for TH*SW*K*K multiply-adds.
+template <int K, int SW, int TH>
 __device__ __forceinline__ void strip_mac(const float* in, const float* w, const int* idx, int idx_off, int c0,
-                                          int cstep, int nc, int map_sz, int Wi, int base, float (&acc)[SW]) {
+                                          int cstep, int nc, int map_sz, int Wi, int base, float (&acc)[TH * SW]) {
   for (int c = c0; c < nc; c += cstep) {
     const float* ip = in + (idx[c] - idx_off) * map_sz + base;
     const float* wp = w + c * (K * K);
+    float wk[K * K];
 #pragma unroll
-    for (int ky = 0; ky < K; ++ky) {
+    for (int t = 0; t < K * K; ++t) wk[t] = wp[t];
+#pragma unroll
+    for (int iy = 0; iy < TH + K - 1; ++iy) {
       float row[SW + K - 1];
 #pragma unroll
-      for (int i = 0; i < SW + K - 1; ++i) row[i] = ip[ky * Wi + i];
-      float wk[K];
+      for (int i = 0; i < SW + K - 1; ++i) row[i] = ip[iy * Wi + i];
 #pragma unroll
-      for (int kx = 0; kx < K; ++kx) wk[kx] = wp[ky * K + kx];
+      for (int ty = 0; ty < TH; ++ty) {
+        const int ky = iy - ty;
+        if (ky >= 0 && ky < K) {
 #pragma unroll
-      for (int s = 0; s < SW; ++s)
+          for (int s = 0; s < SW; ++s)
 #pragma unroll
-        for (int kx = 0; kx < K; ++kx) acc[s] = fmaf(wk[kx], row[s + kx], acc[s]);
+            for (int kx = 0; kx < K; ++kx) acc[ty * SW + s] = fmaf(wk[ky * K + kx], row[s + kx], acc[ty * SW + s]);
+        }
+      }
     }
   }
 }
@@ -437,7 +498,8 @@ struct JobStat {  // the part of a job the plan fixes
   int in, w, idx, cnt;  // LDS offsets (floats): inputs [..][map_sz], weights [n_maps][w_pitch][K*K],
                         // input map of every connection [n_maps][w_pitch], connections per map [n_maps]
   int w_pitch, Ho, Wo, K, stride, map_sz, Wi, max_cnt;
-  int variant;          // SW * 8 + K for a strip job, 0: one pixel per lane (any K, any stride)
+  int variant;          // (TH - 1) * 64 + SW * 8 + K for a job in tiles of TH rows x SW pixels, 0: one pixel per
+                        // lane (any K, any stride)
   int table;            // LDS offset of the lane table [3][WG] (int), or -1
 };
 __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
@@ -446,7 +508,7 @@ __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
   S.in = C.o_in; S.w = C.o_wf; S.idx = C.o_cidx; S.cnt = C.o_ncf;
   S.w_pitch = C.max_conn; S.Ho = C.Ho; S.Wo = C.Wo; S.K = C.K; S.stride = C.S + 1;
   S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn;
-  S.variant = C.fwd_strip ? C.fwd_strip * 8 + C.K : 0;
+  S.variant = C.fwd_strip ? (C.fwd_rows - 1) * 64 + C.fwd_strip * 8 + C.K : 0;
   S.table = C.o_tab_fwd;
   return S;
 }
@@ -457,51 +519,45 @@ __device__ __forceinline__ JobStat pull_job(const FlowSpec& Z, int l) {
   S.w_pitch = C.max_back; S.Ho = C.Hi; S.Wo = C.Wi; S.K = C.K; S.stride = 1;
   S.Wi = C.Wi + C.K - 1; S.map_sz = (C.Hi + C.K - 1) * (C.Wi + C.K - 1);
   S.max_cnt = min(C.max_back, C.pull_chunk);
-  S.variant = C.pull_strip ? C.pull_strip * 8 + C.K : 0;
+  S.variant = C.pull_strip ? (C.pull_rows - 1) * 64 + C.pull_strip * 8 + C.K : 0;
   S.table = C.o_tab_pull;
   return S;
 }
 
 struct Lane {
-  int r, am, pix, base, ncols;
+  int r, am, pix, base, ncols, nrows;
   bool on;
 };
 
-// How many ways U units share their (at most max_cnt) connections over the WG lanes: as many as fit,
-// then the fewest ways that still need no more passes over the connections per lane.
-__device__ __forceinline__ int split_ways(int U, int max_cnt) {
-  if (U >= WG) return 1;
-  const int r_max = max(1, min(WG / U, max_cnt));
-  const int iters = (max_cnt + r_max - 1) / r_max;
-  return (max_cnt + iters - 1) / iters;
-}
 __device__ __forceinline__ JobDyn job_dyn(const JobStat& S, int n_maps) {
-  const int SW = S.variant >> 3;
+  const int SW = (S.variant >> 3) & 7, TH = (S.variant >> 6) + 1;
   JobDyn D;
   D.n_maps = n_maps;
-  D.U = SW ? n_maps * S.Ho * ((S.Wo + SW - 1) / SW) : n_maps * S.Ho * S.Wo;
-  D.R = D.U > 0 ? split_ways(D.U, S.max_cnt) : 1;
+  D.U = SW ? n_maps * ((S.Ho + TH - 1) / TH) * ((S.Wo + SW - 1) / SW) : n_maps * S.Ho * S.Wo;
+  D.R = flow_split_ways(D.U, S.max_cnt);
   D.passes = (D.U * D.R + WG - 1) / WG;
   return D;
 }
 
 // the share of lane `tid` in pass `pass`
 __device__ __forceinline__ Lane lane_decode(const JobStat& S, const JobDyn& D, int pass) {
-  const int SW = S.variant >> 3;
+  const int SW = (S.variant >> 3) & 7, TH = (S.variant >> 6) + 1;
   Lane ln;
   const int u = pass * WG + (int)threadIdx.x;
   ln.on = u < D.U * D.R;
   const FDiv dU(D.U);
   ln.r = dU.div(u);
   const int v = u - ln.r * D.U;
+  ln.nrows = 1;
   if (SW) {
-    const int NS = (S.Wo + SW - 1) / SW;
-    const FDiv dNS(NS), dHo(S.Ho);
+    const int NS = (S.Wo + SW - 1) / SW, NG = (S.Ho + TH - 1) / TH;
+    const FDiv dNS(NS), dNG(NG);
     const int row = dNS.div(v), s = v - row * NS;
-    ln.am = dHo.div(row);
-    const int y = row - ln.am * S.Ho, x0 = s * SW;
+    ln.am = dNG.div(row);
+    const int y = (row - ln.am * NG) * TH, x0 = s * SW;
     ln.pix = y * S.Wo + x0;
     ln.ncols = min(SW, S.Wo - x0);
+    ln.nrows = min(TH, S.Ho - y);
     ln.base = y * S.Wi + x0;
   } else {
     const int Pn = S.Ho * S.Wo;
@@ -512,14 +568,14 @@ __device__ __forceinline__ Lane lane_decode(const JobStat& S, const JobDyn& D, i
     ln.ncols = 1;
     ln.base = (y * S.Wi + x) * S.stride;
   }
-  if (!ln.on) { ln.r = 0; ln.am = 0; ln.pix = 0; ln.base = 0; ln.ncols = 0; }
+  if (!ln.on) { ln.r = 0; ln.am = 0; ln.pix = 0; ln.base = 0; ln.ncols = 0; ln.nrows = 0; }
   return ln;
 }
 __device__ __forceinline__ void lane_save(const Lane& ln, int* tab) {
   const int tid = threadIdx.x;
   tab[tid] = ln.base;
   tab[WG + tid] = ln.pix;
-  tab[2 * WG + tid] = ln.r | (ln.am << 10) | (ln.ncols << 20) | ((ln.on ? 1 : 0) << 24);
+  tab[2 * WG + tid] = ln.r | (ln.am << 10) | (ln.ncols << 20) | (ln.nrows << 24) | ((ln.on ? 1 : 0) << 28);
 }
 __device__ __forceinline__ Lane lane_load(const int* tab) {
   const int tid = threadIdx.x;
@@ -530,7 +586,8 @@ __device__ __forceinline__ Lane lane_load(const int* tab) {
   ln.r = m & 1023;
   ln.am = (m >> 10) & 1023;
   ln.ncols = (m >> 20) & 15;
-  ln.on = (m >> 24) != 0;
+  ln.nrows = (m >> 24) & 15;
+  ln.on = (m >> 28) != 0;
   return ln;
 }
 __device__ __forceinline__ Lane lane_get(const JobStat& S, const JobDyn& D, const float* lds, int pass) {
@@ -538,32 +595,31 @@ __device__ __forceinline__ Lane lane_get(const JobStat& S, const JobDyn& D, cons
   return lane_decode(S, D, pass);
 }
 
-template <int V>
-struct IC { static constexpr int value = V; };
-
-// call f(K, SW) with the job's compile-time kernel size and strip width (K = 0: any size, one pixel)
+// call f(K, SW, TH) with the job's compile-time kernel size and tile (K = 0: any size, one pixel)
 template <class Fn>
 __device__ __forceinline__ void job_dispatch(int variant, Fn f) {
   switch (variant) {
-#define JOB_CASE(SW, K) case SW * 8 + K: f(IC<K>{}, IC<SW>{}); break;
+#define JOB_CASE(SW, K)                                         \
+  case SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<1>{}); break;        \
+  case 64 + SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<2>{}); break;
     JOB_CASE(4, 2) JOB_CASE(4, 3) JOB_CASE(4, 4) JOB_CASE(4, 5)
     JOB_CASE(5, 2) JOB_CASE(5, 3) JOB_CASE(5, 4) JOB_CASE(5, 5)
     JOB_CASE(7, 2) JOB_CASE(7, 3) JOB_CASE(7, 4) JOB_CASE(7, 5)
 #undef JOB_CASE
-    default: f(IC<0>{}, IC<1>{}); break;
+    default: f(IC<0>{}, IC<1>{}, IC<1>{}); break;
   }
 }
 
 // acc[] += the lane's share of connections [e_lo, e_hi) of its map (maps numbered from idx_off)
-template <int K, int SW>
+template <int K, int SW, int TH>
 __device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* lds, const Lane& ln, int e_lo, int e_hi,
-                                        int idx_off, float (&acc)[SW]) {
+                                        int idx_off, float (&acc)[TH * SW]) {
   const float* w = lds + S.w + (ln.am * S.w_pitch) * (S.K * S.K);
   const int* idx = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
   if constexpr (K == 0)
     acc[0] += pixel_mac_k(S.K, lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base);
   else
-    strip_mac<K, SW>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, acc);
+    strip_mac<K, SW, TH>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, acc);
 }
 
 // ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
@@ -581,26 +637,30 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
   const float* bf = lds + C.o_bf;
   const int* cnt = (const int*)(lds + S.cnt);
   const int Pn = S.Ho * S.Wo, tot = nm * Pn;
-  job_dispatch(S.variant, [&](auto k_, auto sw_) {
-    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value;
+  job_dispatch(S.variant, [&](auto k_, auto sw_, auto th_) {
+    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
       const Lane ln = lane_get(S, D, lds, pass);
-      float acc[SW];
+      float acc[TH * SW];
 #pragma unroll
-      for (int i = 0; i < SW; ++i) acc[i] = 0.f;
+      for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
       if (ln.on) {
-        job_mac<K, SW>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
+        job_mac<K, SW, TH>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
         if (D.R == 1) {  // unsplit: the finished sums go straight through the activation function
           const float b = bf[ln.am];
           float* dst = act + ln.am * Pn + ln.pix;
 #pragma unroll
-          for (int i = 0; i < SW; ++i)
-            if (i < ln.ncols) dst[i] = f_act(acc[i] + b);
+          for (int ty = 0; ty < TH; ++ty)
+#pragma unroll
+            for (int i = 0; i < SW; ++i)
+              if (ty < ln.nrows && i < ln.ncols) dst[ty * S.Wo + i] = f_act(acc[ty * SW + i] + b);
         } else {
           float* dst = part + (ln.r * nm + ln.am) * Pn + ln.pix;
 #pragma unroll
-          for (int i = 0; i < SW; ++i)
-            if (i < ln.ncols) dst[i] = acc[i];
+          for (int ty = 0; ty < TH; ++ty)
+#pragma unroll
+            for (int i = 0; i < SW; ++i)
+              if (ty < ln.nrows && i < ln.ncols) dst[ty * S.Wo + i] = acc[ty * SW + i];
         }
       }
     }
@@ -745,13 +805,13 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
   const int* cnt = (const int*)(lds + S.cnt);
   const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
-  job_dispatch(S.variant, [&](auto k_, auto sw_) {
-    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value;
+  job_dispatch(S.variant, [&](auto k_, auto sw_, auto th_) {
+    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
       const Lane ln = lane_get(S, D, lds, pass);
-      float acc[SW];
+      float acc[TH * SW];
 #pragma unroll
-      for (int i = 0; i < SW; ++i) acc[i] = 0.f;
+      for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
       for (int j0 = 0; j0 < Mo; j0 += chunk) {
         const int n = min(chunk, Mo - j0);
         for (int x = tid; x < n * HW; x += WG) {
@@ -759,7 +819,9 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
           const int yx = yxall[(j0 + c) * HW + q];
           dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
         }
+        DSTAMP(120);
         __syncthreads();
+        DSTAMP(121);
         if (ln.on) {
           // entries of the lane's input map whose output map lies in [j0, j0 + n)
           int e_lo = j0, e_hi = j0 + n;
@@ -771,9 +833,11 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
             e_hi = e_lo;
             while (e_hi < ne && bj[e_hi] < j0 + n) ++e_hi;
           }
-          job_mac<K, SW>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
+          job_mac<K, SW, TH>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
+        DSTAMP(122);
         __syncthreads();
+        DSTAMP(123);
         for (int x = tid; x < n * HW; x += WG) {
           const int c = dHW.div(x), q = x - c * HW;
           const int yx = yxall[(j0 + c) * HW + q];
@@ -784,19 +848,25 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
       if (ln.on) {
         float* dst = part + (ln.r * nb + ln.am) * (S.Ho * S.Wo) + ln.pix;
 #pragma unroll
-        for (int i = 0; i < SW; ++i)
-          if (i < ln.ncols) dst[i] = acc[i];
+        for (int ty = 0; ty < TH; ++ty)
+#pragma unroll
+          for (int i = 0; i < SW; ++i)
+            if (ty < ln.nrows && i < ln.ncols) dst[ty * S.Wo + i] = acc[ty * SW + i];
       }
     }
   });
+  DSTAMP(124);
   __syncthreads();
+  DSTAMP(125);
   const float* ybelow = lds + Cb.o_pool;
   float* dbelow = lds + Cb.o_delta;
   for (int p = tid; p < tot; p += WG) {
     const float s = sum_strided(part, D.R, tot, p);
     dbelow[p] = s * f_dact(ybelow[p]);
   }
+  DSTAMP(126);
   __syncthreads();
+  DSTAMP(127);
 }
 
 // y[k] = b[k] + sum_m W[k][m] v[m], all in LDS; lane groups of a power of two per row.
@@ -867,16 +937,16 @@ __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
   Shared& sh = *rt.sh;
   DECL_SPEC(Z, sh);
   const int G = Z.G, rank = rt.rank;
-  if (threadIdx.x == 0) {
-#pragma unroll
-    for (int l = 0; l < Z.n_conv; ++l) {
+  if (threadIdx.x == 0)
+    for_up<ID, 0, FLOW_MAX_CONV>(Z.n_conv, [&](auto lc) {
+      const int l = lv(lc);
       sh.fwd[l] = job_dyn(fwd_job(Z, l), n_mine(Z.conv[l].Mo, rank, G));
       if (l >= 1) sh.pull[l] = job_dyn(pull_job(Z, l), n_mine(Z.conv[l].Mi, rank, G));
-    }
-  }
+      return true;
+    });
   __syncthreads();
-#pragma unroll
-  for (int l = 0; l < Z.n_conv; ++l) {
+  for_up<ID, 0, FLOW_MAX_CONV>(Z.n_conv, [&](auto lc) {
+    const int l = lv(lc);
     const JobStat S = fwd_job(Z, l);
     const JobDyn D = sh.fwd[l];
     if (D.n_maps > 0 && S.table >= 0 && D.passes == 1) lane_save(lane_decode(S, D, 0), (int*)(rt.lds + S.table));
@@ -885,7 +955,8 @@ __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
       const JobDyn E = sh.pull[l];
       if (E.n_maps > 0 && B.table >= 0 && E.passes == 1) lane_save(lane_decode(B, E, 0), (int*)(rt.lds + B.table));
     }
-  }
+    return true;
+  });
   __syncthreads();
 }
 
@@ -963,21 +1034,24 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
     }
     STAMP(1);
     // ---- FP, convolutional layers ----
-#pragma unroll
-    for (int l = 0; l < n_conv; ++l) {
-      const ConvSpec& C = Z.conv[l];
-      if (l >= 1) {
-        const int nw = C.Mi * C.Hi * C.Wi;
-        if (!gather(rt, (unsigned int*)(lds + C.o_in), Q.conv[l - 1].x_out + (size_t)par * nw, nw, tag)) return;
-      }
-      STAMP(2 + 2 * l);
-      const int nm = sh.fwd[l].n_maps;
-      if (nm > 0) {
-        flow_conv_fwd<ID>(rt, l);
-        flow_pool<ID>(rt, l, nm, tag, taps);
-      }
-      STAMP(3 + 2 * l);
-    }
+    if (!for_up<ID, 0, FLOW_MAX_CONV>(n_conv, [&](auto lc) {
+          const int l = lv(lc);
+          const ConvSpec& C = Z.conv[l];
+          if (l >= 1) {
+            const int nw = C.Mi * C.Hi * C.Wi;
+            if (!gather(rt, (unsigned int*)(lds + C.o_in), Q.conv[l >= 1 ? l - 1 : 0].x_out + (size_t)par * nw, nw, tag))
+              return false;
+          }
+          STAMP(2 + 2 * l);
+          const int nm = sh.fwd[l].n_maps;
+          if (nm > 0) {
+            flow_conv_fwd<ID>(rt, l);
+            flow_pool<ID>(rt, l, nm, tag, taps);
+          }
+          STAMP(3 + 2 * l);
+          return true;
+        }))
+      return;
     // ---- FP, first fully connected layer: partial sums over the own columns, exchanged ----
     {
       const float* wc = lds + L1.o_w;
@@ -1011,16 +1085,17 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
       }
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----
-#pragma unroll
-    for (int f = 1; f < n_fc; ++f) {
+    for_up<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
+      const int f = lv(fc_);
       const FcSpec& L = Z.fc[f];
       float* y = lds + L.o_act;
-      flow_matvec(lds + L.o_w, lds + L.o_b, lds + Z.fc[f - 1].o_act, y, uni_of<ID>(L.n_out), uni_of<ID>(L.n_in));
+      flow_matvec(lds + L.o_w, lds + L.o_b, lds + Z.fc[f >= 1 ? f - 1 : 0].o_act, y, uni_of<ID>(L.n_out), uni_of<ID>(L.n_in));
       if (!L.is_output) {
         for (int k = tid; k < L.n_out; k += WG) y[k] = f_act(y[k]);
         __syncthreads();
       }
-    }
+      return true;
+    });
     STAMP(32);
     // soft-max, cross-entropy error, output delta  delta_k = p_k - [k == label].  With at most 64
     // classes every wavefront works them out for itself (lane k holds class k), so nobody waits
@@ -1072,24 +1147,25 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         __syncthreads();
       }
     }
-    if (taps && rank == 0) {
-#pragma unroll
-      for (int f = 0; f + 1 < n_fc; ++f)
+    if (taps && rank == 0)
+      for_up<ID, 0, FLOW_MAX_FC>(n_fc - 1, [&](auto fc_) {
+        const int f = lv(fc_);
         for (int k = tid; k < Z.fc[f].n_out; k += WG) Q.fc[f].act[k] = lds[Z.fc[f].o_act + k];
-    }
+        return true;
+      });
     STAMP(33);
     if (!train) continue;
 
     // ---- BP + AW, fully connected layers behind the first (every rank, same arithmetic) ----
-#pragma unroll
-    for (int f = n_fc - 1; f >= 1; --f) {
+    for_down<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
+      const int f = lv(fc_);
       const FcSpec& L = Z.fc[f];
       const FlowFcPtrs& PL = Q.fc[f];
       float* W = lds + L.o_w;
       float* b = lds + L.o_b;
       const float* d = lds + L.o_delta;
-      const float* v = lds + Z.fc[f - 1].o_act;
-      float* dprev = lds + Z.fc[f - 1].o_delta;
+      const float* v = lds + Z.fc[f >= 1 ? f - 1 : 0].o_act;
+      float* dprev = lds + Z.fc[f >= 1 ? f - 1 : 0].o_delta;
       const int n_in = uni_of<ID>(L.n_in), n_out = uni_of<ID>(L.n_out);
       const bool from_reg = wave_softmax && f == n_fc - 1;
       for (int m = tid; m < n_in; m += WG) {
@@ -1122,7 +1198,8 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         if (taps && rank == 0) PL.delta[k] = dk;
       }
       __syncthreads();
-    }
+      return true;
+    });
     STAMP(34);
     {  // ---- BP + AW, first fully connected layer: own columns ----
       const FlowFcPtrs& P1 = Q.fc[0];
@@ -1170,8 +1247,8 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
     }
     STAMP(35);
     // ---- BP + AW, convolutional layers, top down ----
-#pragma unroll
-    for (int l = n_conv - 1; l >= 0; --l) {
+    if (!for_down<ID, 0, FLOW_MAX_CONV>(n_conv, [&](auto lc) {
+      const int l = lv(lc);
       const ConvSpec& C = Z.conv[l];
       const FlowConvPtrs& P = Q.conv[l];
       const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1,
@@ -1237,7 +1314,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
           int* yxall = (int*)(lds + Z.o_yxall);
           if (!gather2(rt, (unsigned int*)dall, P.x_delta + (size_t)par * Mo * HW, (unsigned int*)yxall,
                        P.x_yx + (size_t)par * Mo * HW, Mo * HW, tag))
-            return;
+            return false;
           STAMP(42 + 4 * l);
           flow_pull<ID>(rt, l, dall, yxall);
           STAMP(43 + 4 * l);
@@ -1267,7 +1344,9 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
           }
         }
       }
-    }
+      return true;
+    }))
+      return;
     STAMP(60);
   }
   if (!g_out && a.train) flow_store<ID>(rt);

@@ -17,8 +17,10 @@ struct ConvSpec {
   int n_own_below;  // most input maps a rank owns (maps of the layer below): ceil(Mi / G); 0 for the first layer
   int wgrad_R_log2; // pooled positions are split 2^this ways when summing a weight gradient
   int pull_chunk;   // output maps rebuilt at full resolution per pass of the delta pull
-  int fwd_strip;    // output pixels per lane in FP (0: one pixel per lane, any stride)
+  int fwd_strip;    // FP: a lane computes a tile of fwd_rows x fwd_strip output pixels (strip 0: one pixel per
+  int fwd_rows;     //   lane, any stride)
   int pull_strip;   // same for the delta pull through this layer
+  int pull_rows;
   int has_x_out;    // the pooled outputs are exchanged (a convolutional layer follows)
   // LDS offsets, in floats
   int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
@@ -71,27 +73,57 @@ constexpr int flow_max(int a, int b) { return a > b ? a : b; }
 constexpr long long flow_minl(long long a, long long b) { return a < b ? a : b; }
 constexpr long long flow_maxl(long long a, long long b) { return a > b ? a : b; }
 
-// Strip width for a correlation job of n_maps maps of rows x width pixels with up to max_cnt
-// connections each: the one of {4, 5, 7} that leaves the least multiply-accumulate work per lane
-// once the connections are shared over the spare lanes (the rule the kernel applies), the wider
-// one on a tie; 0 = one pixel per lane (any stride, any kernel size).
-constexpr int flow_strip_for(int K, int stride, int n_maps, int rows, int width, int max_cnt) {
+// How many ways U units share their (at most max_cnt) connections over the WG lanes: as many as fit,
+// then the fewest ways that still need no more passes over the connections per lane.
+constexpr int flow_split_ways(int U, int max_cnt) {
+  if (U >= WG || U < 1) return 1;
+  const int r_max = flow_max(1, flow_min(WG / U, max_cnt));
+  const int iters = (max_cnt + r_max - 1) / r_max;
+  return (max_cnt + iters - 1) / iters;
+}
+// floats of partial sums a job of n_maps (or one map fewer: ranks differ by one) maps needs
+constexpr long long flow_part_need(int strip, int th, int n_maps, int rows, int width, int max_cnt) {
+  long long need = 0;
+  for (int nm = flow_max(1, n_maps - 1); nm <= n_maps; ++nm) {
+    const int U = strip ? nm * ((rows + th - 1) / th) * ((width + strip - 1) / strip) : nm * rows * width;
+    need = flow_maxl(need, (long long)flow_split_ways(U, max_cnt) * nm * rows * width);
+  }
+  return need;
+}
+
+// Tile for a correlation job of n_maps maps of rows x width pixels with up to max_cnt connections
+// each: rows (1 or 2) x strip (4, 5 or 7 pixels) per lane, the combination with the shortest
+// estimated time once the connections are shared over the spare lanes (the rule the kernel
+// applies).  Two things bound that time: the multiply-adds of one lane (a wavefront issues one
+// vector instruction per about 5 cycles, however many wavefronts share its SIMD), and the LDS
+// reads of all wavefronts together (128 bytes per cycle and compute unit: 2 cycles per wavefront
+// read, taken as 3 with bank conflicts).  0 = one pixel per lane (any stride, any kernel size).
+// Returns strip + 16 * rows.
+constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, int max_cnt) {
   if (stride != 1 || K < 2 || K > 5) return 0;
-  int best = 4;
+  int best = 4 + 16;
   long long best_cost = -1;
   const int widths[3] = {4, 5, 7};
-  for (int wi = 0; wi < 3; ++wi) {
-    const int sw = widths[wi];
-    const long long U = (long long)n_maps * rows * ((width + sw - 1) / sw);
-    long long iters = max_cnt;
-    if (U < WG) {
-      const long long r_max = flow_maxl(1, flow_minl(WG / U, max_cnt));
-      iters = (max_cnt + r_max - 1) / r_max;
+  for (int th = 1; th <= 2; ++th)
+    for (int wi = 0; wi < 3; ++wi) {
+      const int sw = widths[wi];
+      const long long U = (long long)n_maps * ((rows + th - 1) / th) * ((width + sw - 1) / sw);
+      long long iters = max_cnt;
+      if (U < WG) {
+        const long long r_max = flow_maxl(1, flow_minl(WG / U, max_cnt));
+        iters = (max_cnt + r_max - 1) / r_max;
+      }
+      const long long passes = (U + WG - 1) / WG;
+      const long long macs = (long long)th * sw * K * K;
+      const long long reads = (long long)(th + K - 1) * (sw + K - 1) + K * K;
+      const long long ways = (max_cnt + iters - 1) / iters;
+      const long long waves = (flow_minl(U * ways, WG) + 63) / 64;
+      const long long valu = iters * macs * 5, lds = waves * iters * reads * 3;
+      long long cost = passes * ((valu > lds ? valu : lds) + 200);
+      // partial sums beyond 32 KB crowd out the weights and maps a rank must hold: last resort only
+      if (flow_part_need(sw, th, n_maps, rows, width, max_cnt) > 8 * WG) cost += 1000000;
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sw + 16 * th; }
     }
-    const long long passes = (U + WG - 1) / WG;
-    const long long cost = passes * iters * (sw * K * K + (sw + 2 * K - 1) * K / 2);
-    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best = sw; }
-  }
   return best;
 }
 
@@ -119,7 +151,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     off += (n + 3) / 4 * 4;
     return (int)flow_minl(o, 1 << 30);
   };
-  long long max_act = 1, max_part = (long long)FLOW_STRIP_MAX * WG, max_dall = 1, max_hwd = 0;
+  long long max_act = 1, max_part = WG, max_dall = 1, max_hwd = 0;
   for (int l = 0; l < n_conv; ++l) {
     ConvSpec& C = Z.conv[l];
     const int KK = C.K * C.K, HW = C.Hp * C.Wp;
@@ -134,22 +166,29 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     C.o_bf = take(C.n_own);
     C.o_cidx = take((long long)C.n_own * C.max_conn);
     C.o_ncf = take(C.n_own);
-    C.fwd_strip = flow_strip_for(C.K, C.S + 1, C.n_own, C.Ho, C.Wo, C.max_conn);
-    C.o_wb = 0; C.o_bj = 0; C.o_ncb = 0; C.pull_strip = 0; C.pull_chunk = 1;
+    {
+      const int tile = flow_tile_for(C.K, C.S + 1, C.n_own, C.Ho, C.Wo, C.max_conn);
+      C.fwd_strip = tile & 15; C.fwd_rows = tile ? tile >> 4 : 1;
+    }
+    C.o_wb = 0; C.o_bj = 0; C.o_ncb = 0; C.pull_strip = 0; C.pull_rows = 1; C.pull_chunk = 1;
     if (l >= 1) {
       C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
       C.o_bj = take((long long)C.n_own_below * C.max_back);
       C.o_ncb = take(C.n_own_below);
-      C.pull_strip = flow_strip_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.max_back);
+      {
+        const int tile = flow_tile_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.max_back);
+        C.pull_strip = tile & 15; C.pull_rows = tile ? tile >> 4 : 1;
+      }
       max_dall = flow_maxl(max_dall, (long long)C.Mo * HW);
       max_hwd = flow_maxl(max_hwd, (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1));
-      max_part = flow_maxl(max_part, (long long)C.n_own_below * C.Hi * C.Wi);
+      max_part = flow_maxl(max_part, flow_part_need(C.pull_strip, C.pull_rows, C.n_own_below, C.Hi, C.Wi,
+                                                    flow_min(C.max_back, C.Mo)));
     }
     C.o_pool = take((long long)C.n_own * HW);
     C.o_yx = take((long long)C.n_own * HW);
     C.o_delta = take((long long)C.n_own * HW);
     max_act = flow_maxl(max_act, (long long)C.n_own * C.Ho * C.Wo);
-    max_part = flow_maxl(max_part, (long long)C.n_own * C.Ho * C.Wo);
+    max_part = flow_maxl(max_part, flow_part_need(C.fwd_strip, C.fwd_rows, C.n_own, C.Ho, C.Wo, C.max_conn));
     // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
     long long n_w = (long long)C.n_own * C.max_conn * KK;
     if (l >= 1) n_w = flow_minl(n_w, (long long)C.n_own_below * C.max_back * KK);
@@ -172,7 +211,9 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
   Z.o_part = take(max_part);
   Z.o_dall = take(n_conv > 1 ? max_dall : 0);
   Z.o_yxall = take(n_conv > 1 ? max_dall : 0);
-  const long long pad = 16;  // strips read a few floats past the end of the last row of a map
+  // tiles read a few floats past the end of the last row of a map, and a row past its last row
+  long long pad = 16;
+  for (int l = 1; l < n_conv; ++l) pad = flow_maxl(pad, 16 + Z.conv[l].Wi + Z.conv[l].K);
   const long long need = n_conv > 1 ? max_hwd + pad : pad;
   if (off + need > FLOW_LDS_FLOATS_MAX) return FLOW_NO_LDS;
   // lane tables of the correlation jobs, while there is room (a rank decodes its share of a job
