@@ -93,6 +93,9 @@ int cnn_workspace_bytes(const char* arch, size_t* bytes);
  * kind, layer, work items, tiling), written NUL-terminated into buf (truncated to n). */
 int cnn_plan_text(const char* arch, char* buf, size_t n);
 
+/* The same for an existing network, with its connection tables and front-end as they are now. */
+int cnn_get_plan_text(const cnn_t* net, char* buf, size_t n);
+
 /* Build a network.  d_workspace: device memory of at least cnn_workspace_bytes bytes,
  * 256-byte aligned, owned by the caller, used exclusively by this handle.  hip_stream: a
  * hipStream_t (NULL = the default stream) on which all device work of the handle is

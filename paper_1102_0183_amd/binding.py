@@ -38,6 +38,7 @@ def lib():
             "cnn_arch_info": (C.c_int, [C.c_char_p, vp, vp, i32]),
             "cnn_workspace_bytes": (C.c_int, [C.c_char_p, vp]),
             "cnn_plan_text": (C.c_int, [C.c_char_p, vp, sz]),
+            "cnn_get_plan_text": (C.c_int, [vp, vp, sz]),
             "cnn_create": (C.c_int, [C.c_char_p, vp, sz, vp, vp]),
             "cnn_destroy": (None, [vp]),
             "cnn_set_connection_table": (C.c_int, [vp, C.c_int, vp]),
@@ -78,7 +79,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_create", "cnn_destroy",
+EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_get_plan_text", "cnn_create", "cnn_destroy",
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
@@ -197,6 +198,12 @@ class Cnn:
 
     def set_mode(self, mode):
         self._ck(lib().cnn_set_mode(self._h, int(mode)), "cnn_set_mode")
+
+    def plan_text(self):
+        """The stage list of one training step of this network as it is now, one line per stage."""
+        buf = C.create_string_buffer(1 << 14)
+        self._ck(lib().cnn_get_plan_text(self._h, buf, len(buf)), "cnn_get_plan_text")
+        return buf.value.decode()
 
     @property
     def mode(self):

@@ -869,6 +869,21 @@ int cnn_workspace_bytes(const char* arch, size_t* bytes) {
   return rc;
 }
 
+static int plan_to_text(const ProgramDev& P, char* buf, size_t n) {
+  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad", "conv_mfma", "conv_epi"};
+  std::string out;
+  char line[256];
+  for (int s = 0; s < P.n_stages; ++s) {
+    const Stage& st = P.stages[s];
+    std::snprintf(line, sizeof line, "%2d %-10s layer=%d items=%d barrier=%d train_only=%d rows=%d tiles=%d chunk=%d tw=%d ppt=%d rpw=%d cm=%d\n",
+                  s, names[st.kind], st.layer, st.n_items, st.barrier_after, st.train_only, st.tile_rows, st.n_tiles,
+                  st.chunk, 1 << st.tw_log2, st.pix_per_thread, st.rows_per_wg, 1 << st.cm_log2);
+    out += line;
+  }
+  std::snprintf(buf, n, "%s", out.c_str());
+  return CNN_OK;
+}
+
 int cnn_plan_text(const char* arch, char* buf, size_t n) {
   if (!buf || n == 0) return fail(nullptr, CNN_E_ARG, "buf is NULL");
   cnn tmp;
@@ -880,18 +895,12 @@ int cnn_plan_text(const char* arch, char* buf, size_t n) {
       tmp.tables.emplace_back((size_t)tmp.arch[l].maps * tmp.arch[l - 1].maps, (uint8_t)1);
   rc = plan(&tmp);
   if (rc) { g_err = tmp.err; return rc; }
-  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad", "conv_mfma", "conv_epi"};
-  std::string out;
-  char line[256];
-  for (int s = 0; s < tmp.prog.n_stages; ++s) {
-    const Stage& st = tmp.prog.stages[s];
-    std::snprintf(line, sizeof line, "%2d %-10s layer=%d items=%d barrier=%d train_only=%d rows=%d tiles=%d chunk=%d tw=%d ppt=%d rpw=%d cm=%d\n",
-                  s, names[st.kind], st.layer, st.n_items, st.barrier_after, st.train_only, st.tile_rows, st.n_tiles,
-                  st.chunk, 1 << st.tw_log2, st.pix_per_thread, st.rows_per_wg, 1 << st.cm_log2);
-    out += line;
-  }
-  std::snprintf(buf, n, "%s", out.c_str());
-  return CNN_OK;
+  return plan_to_text(tmp.prog, buf, n);
+}
+
+int cnn_get_plan_text(const cnn_t* net, char* buf, size_t n) {
+  if (!net || !buf || n == 0) return CNN_E_ARG;
+  return plan_to_text(net->prog, buf, n);
 }
 
 int cnn_create(const char* arch, void* d_workspace, size_t bytes, void* hip_stream, cnn_t** out) {

@@ -1,0 +1,61 @@
+#!/usr/bin/env python3
+"""Small driver to put under rocprofv3: trains a few on-line calls of one synthetic workload.
+
+    python3 paper_1102_0183_amd/probe.py --workload cfg4b --mode stages --images 200 --calls 1
+    python3 paper_1102_0183_amd/probe.py --workload cfg2a --mode resident --images 1000 --calls 3 --copy-calibration
+
+--copy-calibration first runs a 256 MiB device-to-device copy three times, so that a counter
+collected in the same run (FETCH_SIZE, WRITE_SIZE) can be scaled by what it reads for a
+transfer of known size.  Everything the network computes runs in libcnn355.so.
+"""
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="cfg2a")
+    ap.add_argument("--mode", choices=["resident", "persistent", "stages"], default="resident")
+    ap.add_argument("--images", type=int, default=1000, help="images per cnn_train_many call")
+    ap.add_argument("--calls", type=int, default=3)
+    ap.add_argument("--forward", action="store_true", help="forward-only calls instead of training")
+    ap.add_argument("--copy-calibration", action="store_true")
+    args = ap.parse_args()
+
+    import torch
+
+    from paper_1102_0183_amd import binding, synth
+
+    if args.copy_calibration:
+        x = torch.empty(64 << 20, dtype=torch.float32, device="cuda:0").normal_()   # 256 MiB
+        y = torch.empty_like(x)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+    wl = synth.WORKLOADS[args.workload]
+    n = args.images
+    imgs, labs = synth.images(wl, n * args.calls), synth.labels(wl, n * args.calls)
+    d_imgs = torch.from_numpy(imgs).to("cuda:0")
+    d_labs = torch.from_numpy(labs).to("cuda:0")
+    net = synth.build_network(binding.Cnn(wl.arch), wl)
+    net.set_mode({"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
+                  "stages": binding.MODE_STAGES}[args.mode])
+    sz = net.image_size
+    for r in range(args.calls):
+        im = d_imgs.view(-1)[r * n * sz:(r + 1) * n * sz]
+        if args.forward:
+            net.forward_many(im, n)
+        else:
+            net.train_many(im, d_labs[r * n:(r + 1) * n], wl.lr, n=n)
+    net.synchronize()
+    print("probe done: %s, %s mode, %d calls of %d images" % (args.workload, args.mode, args.calls, n), flush=True)
+
+
+if __name__ == "__main__":
+    main()

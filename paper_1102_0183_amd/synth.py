@@ -132,3 +132,18 @@ def contrast_filters(wl: Workload, k: int = 5):
         g /= np.abs(g).sum()
         filt[f] = g if f % 2 == 0 else -g
     return filt.astype(np.float32), np.array([0, 0, 1, 1], dtype=np.int32)
+
+
+def build_network(net, wl: Workload):
+    """Give a freshly created network (the GPU library's or the oracle's: same method names) the
+    workload's connection table, fixed front-end and seeded weights.  Returns the network."""
+    if wl.sparse_conv is not None:
+        convs = [l for l in range(1, net.num_layers) if net.layer_info(l)["kind"] == 1]
+        l = convs[wl.sparse_conv]
+        net.set_connection_table(wl.sparse_conv, connection_table(wl, net.layer_info(l)["maps"],
+                                                                  net.layer_info(l - 1)["maps"]))
+    if wl.frontend:
+        filt, src = contrast_filters(wl)
+        net.set_fixed_frontend(filt, src, wl.raw_shape[0])
+    net.set_weights(weights(wl, net.num_weights))
+    return net
