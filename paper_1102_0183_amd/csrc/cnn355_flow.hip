@@ -241,24 +241,31 @@ __device__ __forceinline__ bool poll_again(const Rt& rt, unsigned int& spins) {
   return true;
 }
 
-// Copy n tagged words into LDS (their 32-bit payloads), each lane polling its own words until
-// they carry `tag`.  Ends with a workgroup barrier; returns false (to every thread of the
-// workgroup) when a wait gave up: the caller then leaves the kernel.
+// Fetch U tagged words (addr(u) gives their places) until every one carries `tag`: all are loaded
+// together, again and again.  False: gave up.
+template <int U, class Addr>
+__device__ __forceinline__ bool fetch_tagged(const Rt& rt, tagged_t (&w)[U], unsigned int tag, Addr addr) {
+  unsigned int spins = 0;
+  while (true) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) w[u] = __hip_atomic_load(addr(u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool done = true;
+#pragma unroll
+    for (int u = 0; u < U; ++u) done = done && ((unsigned int)(w[u] >> 32) == tag);
+    if (done) return true;
+    if (!poll_again(rt, spins)) return false;
+  }
+}
+
+// Copy n tagged words into LDS (their 32-bit payloads), each lane waiting for its own words to
+// carry `tag`.  Ends with a workgroup barrier; returns false (to every thread of the workgroup)
+// when a wait gave up: the caller then leaves the kernel.
 __device__ __forceinline__ bool gather(const Rt& rt, unsigned int* dst, const gtagged* src, int n, unsigned int tag) {
   constexpr int U = 4;
   const int tid = threadIdx.x;
   for (int base = 0; base < n; base += U * WG) {
     tagged_t w[U];
-    unsigned int spins = 0;
-    while (true) {
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        w[u] = __hip_atomic_load(src + min(base + tid + u * WG, n - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      bool done = true;
-#pragma unroll
-      for (int u = 0; u < U; ++u) done = done && ((unsigned int)(w[u] >> 32) == tag);
-      if (done || !poll_again(rt, spins)) break;
-    }
+    if (!fetch_tagged<U>(rt, w, tag, [&](int u) { return src + min(base + tid + u * WG, n - 1); })) break;
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (base + tid + u * WG < n) dst[base + tid + u * WG] = (unsigned int)w[u];
@@ -267,32 +274,22 @@ __device__ __forceinline__ bool gather(const Rt& rt, unsigned int* dst, const gt
   return rt.sh->fail == 0;
 }
 
-// The same for two arrays of n words each, polled together (one round trip instead of two).
+// The same for two arrays of n words each, fetched together (one round trip instead of two).
 __device__ __forceinline__ bool gather2(const Rt& rt, unsigned int* dst_a, const gtagged* src_a, unsigned int* dst_b,
                                         const gtagged* src_b, int n, unsigned int tag) {
   constexpr int U = 2;
   const int tid = threadIdx.x;
   for (int base = 0; base < n; base += U * WG) {
-    tagged_t wa[U], wb[U];
-    unsigned int spins = 0;
-    while (true) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i = min(base + tid + u * WG, n - 1);
-        wa[u] = __hip_atomic_load(src_a + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        wb[u] = __hip_atomic_load(src_b + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      bool done = true;
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        done = done && ((unsigned int)(wa[u] >> 32) == tag) && ((unsigned int)(wb[u] >> 32) == tag);
-      if (done || !poll_again(rt, spins)) break;
-    }
+    tagged_t w[2 * U];
+    if (!fetch_tagged<2 * U>(rt, w, tag, [&](int u) {
+          return ((u & 1) ? src_b : src_a) + min(base + tid + (u >> 1) * WG, n - 1);
+        }))
+      break;
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (base + tid + u * WG < n) {
-        dst_a[base + tid + u * WG] = (unsigned int)wa[u];
-        dst_b[base + tid + u * WG] = (unsigned int)wb[u];
+        dst_a[base + tid + u * WG] = (unsigned int)w[2 * u];
+        dst_b[base + tid + u * WG] = (unsigned int)w[2 * u + 1];
       }
   }
   __syncthreads();
@@ -819,9 +816,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
           const int yx = yxall[(j0 + c) * HW + q];
           dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
         }
-        DSTAMP(120);
         __syncthreads();
-        DSTAMP(121);
         if (ln.on) {
           // entries of the lane's input map whose output map lies in [j0, j0 + n)
           int e_lo = j0, e_hi = j0 + n;
@@ -835,9 +830,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
           }
           job_mac<K, SW, TH>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
-        DSTAMP(122);
         __syncthreads();
-        DSTAMP(123);
         for (int x = tid; x < n * HW; x += WG) {
           const int c = dHW.div(x), q = x - c * HW;
           const int yx = yxall[(j0 + c) * HW + q];
@@ -855,18 +848,14 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
       }
     }
   });
-  DSTAMP(124);
   __syncthreads();
-  DSTAMP(125);
   const float* ybelow = lds + Cb.o_pool;
   float* dbelow = lds + Cb.o_delta;
   for (int p = tid; p < tot; p += WG) {
     const float s = sum_strided(part, D.R, tot, p);
     dbelow[p] = s * f_dact(ybelow[p]);
   }
-  DSTAMP(126);
   __syncthreads();
-  DSTAMP(127);
 }
 
 // y[k] = b[k] + sum_m W[k][m] v[m], all in LDS; lane groups of a power of two per row.
@@ -907,16 +896,7 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
       float s = 0.f;
       for (int r0 = r_lo; r0 < r_hi; r0 += U) {
         tagged_t w[U];
-        unsigned int spins = 0;
-        while (true) {
-#pragma unroll
-          for (int u = 0; u < U; ++u)
-            w[u] = __hip_atomic_load(xp + (size_t)min(r0 + u, r_hi - 1) * n1 + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          bool done = true;
-#pragma unroll
-          for (int u = 0; u < U; ++u) done = done && ((unsigned int)(w[u] >> 32) == tag);
-          if (done || !poll_again(rt, spins)) break;
-        }
+        if (!fetch_tagged<U>(rt, w, tag, [&](int u) { return xp + (size_t)min(r0 + u, r_hi - 1) * n1 + k; })) break;
 #pragma unroll
         for (int u = 0; u < U; ++u)
           if (r0 + u < r_hi) s += __uint_as_float((unsigned int)w[u]);
@@ -1010,6 +990,16 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
   gfloat* g_out = a.grad_out;
   const float lr = a.lr;
 
+  bool pend = false;  // the previous image left adjustments to do
+  constexpr int IMG_U = 4;
+  const int img_n = uni_of<ID>(Z.conv[0].Mi) * uni_of<ID>(Z.conv[0].Hi) * uni_of<ID>(Z.conv[0].Wi);
+  const bool img_ahead = img_n <= IMG_U * WG;
+  float img_reg[IMG_U] = {0.f, 0.f, 0.f, 0.f};
+  if (img_ahead && a.n_images > 0) {
+#pragma unroll
+    for (int u = 0; u < IMG_U; ++u)
+      if (tid + u * WG < img_n) img_reg[u] = a.images[tid + u * WG];
+  }
   for (long long t = 0; t < a.n_images; ++t) {
     const unsigned int tag = a.epoch_base + (unsigned int)t + 1u;
     const unsigned int par = tag & 1u;
@@ -1023,14 +1013,133 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
       train = false;
       if (rank == 0 && tid == 0) status->bad_label = 1u;
     }
-    STAMP(0);
-    {  // the image
-      const gfloat* img = a.images + t * a.image_stride;
-      const ConvSpec& C = Z.conv[0];
-      const int n = C.Mi * C.Hi * C.Wi;
-      float* in = lds + C.o_in;
-      for (int x = tid; x < n; x += WG) in[x] = img[x];
+
+    // ---- AW pieces that may run either in place or during the next image's waits ----
+    // first fully connected layer: own columns, and the (replicated) biases
+    auto fc1_update = [&]() {
+      const FlowFcPtrs& P1 = Q.fc[0];
+      float* wc = lds + L1.o_w;
+      float* b = lds + L1.o_b;
+      const float* d = lds + L1.o_delta;
+      const float* vcol = lds + Cc.o_pool;
+      const FDiv dN(n1), dHW(HWc);
+      for (int x = tid; x < ncols * n1; x += WG) {
+        const int c = dN.div(x), k = x - c * n1;
+        const float g = d[k] * vcol[c];
+        if (g_out) {
+          const int am = dHW.div(c), q = c - am * HWc;
+          g_out[P1.w_canon + (long long)k * L1.n_in + (long long)(rank + am * G) * HWc + q] = g;
+        } else {
+          wc[x] = fmaf(-lr, g, wc[x]);
+        }
+      }
+      for (int k = tid; k < n1; k += WG) {
+        if (g_out) { if (rank == 0) g_out[P1.b_canon + k] = d[k]; }
+        else b[k] = fmaf(-lr, d[k], b[k]);
+        if (taps && rank == 0) P1.delta[k] = d[k];  // (the last image is never put off)
+      }
+    };
+    // forward copy of the own maps' filters of conv layer l, and their biases
+    auto wgrad_fwd = [&](auto lc) {
+      const int l = lv(lc);
+      const ConvSpec& C = Z.conv[l];
+      const FlowConvPtrs& P = Q.conv[l];
+      const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1,
+                Wi = uni_of<ID>(C.Wi), HiWi = uni_of<ID>(C.Hi) * Wi;
+      const int nm = sh.fwd[l].n_maps;
+      if (nm <= 0) return;
+      const float* dl = lds + C.o_delta;
+      const int* yx = (const int*)(lds + C.o_yx);
+      const int* cidx = (const int*)(lds + C.o_cidx);
+      const int* ncf = (const int*)(lds + C.o_ncf);
+      const float* in = lds + C.o_in;
+      const int pitch = uni_of<ID>(C.max_conn);
+      const int per_map = pitch * KK;
+      const FDiv dPM(per_map), dKK(KK), dK(K);
+      const bool full = C.full_table != 0;
+      const int Mi = uni_of<ID>(C.Mi);
+      flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, g_out, [&](int wi) {
+        const int am = dPM.div(wi), rem = wi - am * per_map;
+        const int c = dKK.div(rem), tt = rem - c * KK;
+        const int ky = dK.div(tt), kx = tt - ky * K;
+        WgradInfo I;
+        I.ok = c < ncf[am];
+        I.d = dl + am * HW;
+        I.yx = yx + am * HW;
+        I.in = in + cidx[am * pitch + c] * HiWi + ky * Wi + kx;
+        I.canon = 0;
+        if (g_out) {
+          const int j = rank + am * G;
+          I.canon = P.w_canon + (long long)((full ? j * Mi : P.csr_ptr[j]) + c) * KK + tt;
+        }
+        return I;
+      });
+      const int wave = tid >> 6, lane = tid & 63;
+      for (int am = wave; am < nm; am += WG / 64) {
+        float s = 0.f;
+        for (int q = lane; q < HW; q += 64) s += dl[am * HW + q];
+        s = f_wave_sum(s);
+        if (lane == 0) {
+          if (g_out) g_out[P.b_canon + rank + am * G] = s;
+          else lds[C.o_bf + am] = fmaf(-lr, s, lds[C.o_bf + am]);
+        }
+      }
       __syncthreads();
+    };
+    // pull copy of the filters of conv layer l that read the own maps of the layer below (stored
+    // rotated); own_in = those maps' pooled outputs, [n_own_below][Hi*Wi]
+    auto wgrad_pull = [&](auto lc, const float* own_in) {
+      const int l = lv(lc);
+      const ConvSpec& C = Z.conv[l];
+      const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1,
+                Wi = uni_of<ID>(C.Wi), HiWi = uni_of<ID>(C.Hi) * Wi;
+      const int nb = sh.pull[l].n_maps;
+      if (nb <= 0) return;
+      const float* dall = lds + Z.o_dall;
+      const int* yxall = (const int*)(lds + Z.o_yxall);
+      const int* bj = (const int*)(lds + C.o_bj);
+      const int* ncb = (const int*)(lds + C.o_ncb);
+      const int pitch = uni_of<ID>(C.max_back);
+      const int per_map = pitch * KK;
+      const FDiv dPM(per_map), dKK(KK), dK(K);
+      flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, (gfloat*)nullptr,
+                 [&](int wi) {
+                   const int ab = dPM.div(wi), rem = wi - ab * per_map;
+                   const int e = dKK.div(rem), tt = KK - 1 - (rem - e * KK);
+                   const int ky = dK.div(tt), kx = tt - ky * K;
+                   const int j = bj[ab * pitch + e];
+                   WgradInfo I;
+                   I.ok = e < ncb[ab];
+                   I.d = dall + j * HW;
+                   I.yx = yxall + j * HW;
+                   I.in = own_in + ab * HiWi + ky * Wi + kx;
+                   I.canon = 0;
+                   return I;
+                 });
+      __syncthreads();
+    };
+    // Put off what no other rank and no later step of this image waits for: the adjustments of the
+    // conv layers' forward copies (above the first layer) and of the first FC layer run while the
+    // next image's inputs of that layer are on their way, the pull copy of the second conv layer
+    // while the first FC layer's partial sums are.  Same arithmetic on the same values, only later.
+    const bool defer = Z.defer != 0 && !taps && !g_out && train;
+    STAMP(0);
+    {  // the image: a small one was fetched into registers while the previous image was being worked on
+      const gfloat* img = a.images + t * a.image_stride;
+      float* in = lds + Z.conv[0].o_in;
+      if (img_ahead) {
+#pragma unroll
+        for (int u = 0; u < IMG_U; ++u)
+          if (tid + u * WG < img_n) in[tid + u * WG] = img_reg[u];
+      } else {
+        for (int x = tid; x < img_n; x += WG) in[x] = img[x];
+      }
+      __syncthreads();
+      if (img_ahead && t + 1 < a.n_images) {
+#pragma unroll
+        for (int u = 0; u < IMG_U; ++u)
+          if (tid + u * WG < img_n) img_reg[u] = img[a.image_stride + tid + u * WG];
+      }
     }
     STAMP(1);
     // ---- FP, convolutional layers ----
@@ -1038,6 +1147,10 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
           const int l = lv(lc);
           const ConvSpec& C = Z.conv[l];
           if (l >= 1) {
+            if (pend) {
+              if (l == n_conv - 1) fc1_update();
+              wgrad_fwd(lc);
+            }
             const int nw = C.Mi * C.Hi * C.Wi;
             if (!gather(rt, (unsigned int*)(lds + C.o_in), Q.conv[l >= 1 ? l - 1 : 0].x_out + (size_t)par * nw, nw, tag))
               return false;
@@ -1076,6 +1189,10 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         }
       }
       STAMP(30);
+      if (pend) {
+        wgrad_pull(IC<1>{}, lds + Z.o_prev);
+        pend = false;
+      }
       float* y = lds + L1.o_act;
       if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, part, tag)) return;
       STAMP(31);
@@ -1202,16 +1319,14 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
     });
     STAMP(34);
     {  // ---- BP + AW, first fully connected layer: own columns ----
-      const FlowFcPtrs& P1 = Q.fc[0];
-      float* wc = lds + L1.o_w;
-      float* b = lds + L1.o_b;
+      const float* wc = lds + L1.o_w;
       const float* d = lds + L1.o_delta;
       const float* vcol = lds + Cc.o_pool;
       float* dconv = lds + Cc.o_delta;
       const int* yxc = (const int*)(lds + Cc.o_yx);
       const int Moc = uni_of<ID>(Cc.Mo);
       const int wave = tid >> 6, lane = tid & 63;
-      const FDiv dN(n1), dHW(HWc);
+      const FDiv dHW(HWc);
       for (int c = wave; c < ncols; c += WG / 64) {
         float s = 0.f;
         for (int k = lane; k < n1; k += 64) s = fmaf(wc[c * n1 + k], d[k], s);
@@ -1229,21 +1344,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         }
       }
       __syncthreads();
-      for (int x = tid; x < ncols * n1; x += WG) {
-        const int c = dN.div(x), k = x - c * n1;
-        const float g = d[k] * vcol[c];
-        if (g_out) {
-          const int am = dHW.div(c), q = c - am * HWc;
-          g_out[P1.w_canon + (long long)k * L1.n_in + (long long)(rank + am * G) * HWc + q] = g;
-        } else {
-          wc[x] = fmaf(-lr, g, wc[x]);
-        }
-      }
-      for (int k = tid; k < n1; k += WG) {
-        if (g_out) { if (rank == 0) g_out[P1.b_canon + k] = d[k]; }
-        else b[k] = fmaf(-lr, d[k], b[k]);
-        if (taps && rank == 0) P1.delta[k] = d[k];
-      }
+      if (!defer) fc1_update();
     }
     STAMP(35);
     // ---- BP + AW, convolutional layers, top down ----
@@ -1251,8 +1352,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
       const int l = lv(lc);
       const ConvSpec& C = Z.conv[l];
       const FlowConvPtrs& P = Q.conv[l];
-      const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1,
-                Wi = uni_of<ID>(C.Wi), HiWi = uni_of<ID>(C.Hi) * Wi, Mo = uni_of<ID>(C.Mo);
+      const int HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), HiWi = uni_of<ID>(C.Hi) * uni_of<ID>(C.Wi), Mo = uni_of<ID>(C.Mo);
       const int nm = sh.fwd[l].n_maps;
       const float* dl = lds + C.o_delta;
       const int* yx = (const int*)(lds + C.o_yx);
@@ -1269,43 +1369,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         }
       }
       STAMP(40 + 4 * l);
-      if (nm > 0) {  // forward copy of the own maps' filters, and their biases
-        const int* cidx = (const int*)(lds + C.o_cidx);
-        const int* ncf = (const int*)(lds + C.o_ncf);
-        const float* in = lds + C.o_in;
-        const int pitch = uni_of<ID>(C.max_conn);
-        const int per_map = pitch * KK;
-        const FDiv dPM(per_map), dKK(KK), dK(K);
-        const bool full = C.full_table != 0;
-        const int Mi = uni_of<ID>(C.Mi);
-        flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, g_out, [&](int wi) {
-          const int am = dPM.div(wi), rem = wi - am * per_map;
-          const int c = dKK.div(rem), tt = rem - c * KK;
-          const int ky = dK.div(tt), kx = tt - ky * K;
-          WgradInfo I;
-          I.ok = c < ncf[am];
-          I.d = dl + am * HW;
-          I.yx = yx + am * HW;
-          I.in = in + cidx[am * pitch + c] * HiWi + ky * Wi + kx;
-          I.canon = 0;
-          if (g_out) {
-            const int j = rank + am * G;
-            I.canon = P.w_canon + (long long)((full ? j * Mi : P.csr_ptr[j]) + c) * KK + tt;
-          }
-          return I;
-        });
-        const int wave = tid >> 6, lane = tid & 63;
-        for (int am = wave; am < nm; am += WG / 64) {
-          float s = 0.f;
-          for (int q = lane; q < HW; q += 64) s += dl[am * HW + q];
-          s = f_wave_sum(s);
-          if (lane == 0) {
-            if (g_out) g_out[P.b_canon + rank + am * G] = s;
-            else lds[C.o_bf + am] = fmaf(-lr, s, lds[C.o_bf + am]);
-          }
-        }
-        __syncthreads();
-      }
+      if (!(defer && l >= 1)) wgrad_fwd(lc);
       STAMP(41 + 4 * l);
       if (l >= 1) {
         const int nb = sh.pull[l].n_maps;
@@ -1318,29 +1382,14 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
           STAMP(42 + 4 * l);
           flow_pull<ID>(rt, l, dall, yxall);
           STAMP(43 + 4 * l);
-          if (!g_out) {
-            // pull copy of the filters that read the own maps of the layer below (stored rotated)
-            const int* bj = (const int*)(lds + C.o_bj);
-            const int* ncb = (const int*)(lds + C.o_ncb);
-            const float* in = lds + C.o_in;
-            const int pitch = uni_of<ID>(C.max_back);
-            const int per_map = pitch * KK;
-            const FDiv dPM(per_map), dKK(KK), dK(K);
-            flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, (gfloat*)nullptr,
-                       [&](int wi) {
-                         const int ab = dPM.div(wi), rem = wi - ab * per_map;
-                         const int e = dKK.div(rem), tt = KK - 1 - (rem - e * KK);
-                         const int ky = dK.div(tt), kx = tt - ky * K;
-                         const int j = bj[ab * pitch + e];
-                         WgradInfo I;
-                         I.ok = e < ncb[ab];
-                         I.d = dall + j * HW;
-                         I.yx = yxall + j * HW;
-                         I.in = in + (rank + ab * G) * HiWi + ky * Wi + kx;
-                         I.canon = 0;
-                         return I;
-                       });
-            __syncthreads();
+          if (defer && l == 1) {
+            // the pull copy is adjusted during the next image's wait; the next FP overwrites the
+            // own pooled maps it needs, so they are set aside
+            const float* own = lds + Z.conv[0].o_pool;
+            float* prev = lds + Z.o_prev;
+            for (int x = tid; x < nb * HiWi; x += WG) prev[x] = own[x];
+          } else if (!g_out) {
+            wgrad_pull(lc, lds + Z.conv[l >= 1 ? l - 1 : 0].o_pool);
           }
         }
       }
@@ -1348,6 +1397,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
     }))
       return;
     STAMP(60);
+    pend = defer;
   }
   if (!g_out && a.train) flow_store<ID>(rt);
 }

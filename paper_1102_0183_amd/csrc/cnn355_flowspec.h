@@ -59,6 +59,8 @@ struct FlowSpec {
   int scratch_floats;
   int o_dall;       // [max Mo*Hp*Wp] deltas of every map of the layer being pulled through
   int o_yxall;      // same, winner coordinates
+  int defer;        // 1: weight adjustments nobody is waiting for are put off into the next image's waits
+  int o_prev;       // [conv[1].n_own_below * Hi * Wi] the own pooled maps of the first layer, previous image
   ConvSpec conv[FLOW_MAX_CONV];
   FcSpec fc[FLOW_MAX_FC];
 };
@@ -211,11 +213,20 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
   Z.o_part = take(max_part);
   Z.o_dall = take(n_conv > 1 ? max_dall : 0);
   Z.o_yxall = take(n_conv > 1 ? max_dall : 0);
+  Z.defer = 0;
+  Z.o_prev = 0;
   // tiles read a few floats past the end of the last row of a map, and a row past its last row
   long long pad = 16;
   for (int l = 1; l < n_conv; ++l) pad = flow_maxl(pad, 16 + Z.conv[l].Wi + Z.conv[l].K);
   const long long need = n_conv > 1 ? max_hwd + pad : pad;
   if (off + need > FLOW_LDS_FLOATS_MAX) return FLOW_NO_LDS;
+  if (n_conv > 1) {
+    const long long prev = (long long)Z.conv[1].n_own_below * Z.conv[1].Hi * Z.conv[1].Wi;
+    if (off + prev + need <= FLOW_LDS_FLOATS_MAX) {
+      Z.o_prev = take(prev);
+      Z.defer = 1;
+    }
+  }
   // lane tables of the correlation jobs, while there is room (a rank decodes its share of a job
   // once instead of once per image); the first layers' jobs first
   for (int l = 0; l < n_conv; ++l) {
