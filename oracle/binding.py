@@ -34,6 +34,8 @@ def lib():
         L.oracle_op_act_deriv_from_output.restype = C.c_double
         L.oracle_op_act_deriv_from_output.argtypes = [C.c_double]
         L.oracle_op_softmax_xent.restype = C.c_double
+        L.oracle_op_tanh_sqerr.restype = C.c_double
+        L.oracle_set_output_units.argtypes = [C.c_void_p, C.c_int]
         L.oracle_train_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_void_p]
         L.oracle_backward_update.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_void_p]
         L.oracle_adopt_argmax_hint.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_double,
@@ -91,6 +93,10 @@ class Oracle:
         t = np.ascontiguousarray(table, dtype=np.uint8)
         self._ck(lib().oracle_set_connection_table(self._h, int(conv_index), _p(t, C.c_uint8)),
                  "set_connection_table")
+
+    def set_output_units(self, kind):
+        """0: soft-max + cross-entropy (default); 1: scaled tanh + squared error, targets +-1."""
+        self._ck(lib().oracle_set_output_units(self._h, int(kind)), "set_output_units")
 
     def set_fixed_frontend(self, filters, src_channel, n_src_channels):
         f = _f32(filters)
@@ -313,5 +319,14 @@ class _Ops:
                                          _p(d, C.c_double))
         return e, p, d
 
+    def tanh_sqerr(self, a, label):
+        a = _f64(a)
+        y = np.empty_like(a)
+        d = np.empty_like(a)
+        e = lib().oracle_op_tanh_sqerr(_p(a, C.c_double), a.size, int(label), _p(y, C.c_double),
+                                       _p(d, C.c_double))
+        return e, y, d
+
 
 ops = _Ops()
+OUT_SOFTMAX_XENT, OUT_TANH_SQERR = 0, 1

@@ -62,8 +62,9 @@ template <class T> inline T act_deriv_from_output(T y) {
 // Output map size of a convolutional layer, Sec. 2.2 Eq. (1):
 //   M^n = (M^{n-1} - K^n) / (S^n + 1) + 1.
 // The paper writes a plain fraction; where it is not integral we take the
-// floor, which is what "the kernel has to be completely inside the image"
-// (Sec. 2.2) gives.  Returns <= 0 when the kernel does not fit.
+// floor, which follows from Sec. 2.2's rule that a kernel position counts only
+// when the whole kernel lies inside the input map.  Returns <= 0 when the
+// kernel does not fit.
 int conv_out_size(int m_prev, int k, int s) {
   if (m_prev < k) return 0;
   return (m_prev - k) / (s + 1) + 1;
@@ -298,6 +299,25 @@ T softmax_xent(const T* a, int n, int label, T* p, T* delta) {
   return (label >= 0 && label < n) ? -std::log(p[label]) : T(0);
 }
 
+// The output variant that follows Sec. 4 to the letter: the output neurons use the same scaled
+// hyperbolic tangent as every other neuron.  The paper names no error function and no target
+// coding; this variant takes the sum of squared errors against targets +1 for the image's class
+// and -1 for the others (the two values the activation maps +-1 onto):
+//   y_k = A tanh(B a_k),  E = 1/2 sum_k (y_k - t_k)^2,  dE/da_k = (y_k - t_k) f'(y_k).
+template <class T>
+T tanh_sqerr(const T* a, int n, int label, T* y, T* delta) {
+  T e = T(0);
+  for (int k = 0; k < n; ++k) {
+    y[k] = scaled_tanh(a[k]);
+    const T t = (k == label) ? T(1) : T(-1);
+    e += (y[k] - t) * (y[k] - t);
+    if (delta) delta[k] = (y[k] - t) * act_deriv_from_output(y[k]);
+  }
+  return (label >= 0 && label < n) ? e / T(2) : T(0);
+}
+
+enum OutputUnits { OUT_SOFTMAX_XENT = 0, OUT_TANH_SQERR = 1 };
+
 // ---------------------------------------------------------------------------
 // The network
 // ---------------------------------------------------------------------------
@@ -413,6 +433,7 @@ struct Net {
   std::vector<std::vector<uint8_t>> arg;
   std::vector<T> grad;                 // canonical layout
   T loss = T(0);
+  int out_units = OUT_SOFTMAX_XENT;    // what the last layer computes and which error it is trained on
 
   std::vector<Layer>& L() { return arch.layers; }
   int n_layers() const { return (int)arch.layers.size(); }
@@ -497,6 +518,8 @@ struct Net {
                       act[l].data());
         if (l + 1 < n_layers()) {
           for (auto& v : act[l]) v = scaled_tanh(v);  // hidden units: scaled tanh (Sec. 4)
+        } else if (out_units == OUT_TANH_SQERR) {
+          for (auto& v : act[l]) v = scaled_tanh(v);
         } else {
           std::vector<T> logits(act[l]);
           softmax_xent<T>(logits.data(), a.maps, -1, act[l].data(), nullptr);
@@ -505,18 +528,34 @@ struct Net {
     }
   }
 
+  // E of the last forward pass for `label`; when d is given, also dE/d(pre-activation) of the
+  // output neurons.  Soft-max: act[top] holds the probabilities, delta_k = p_k - [k == label].
+  // Scaled tanh: act[top] holds the outputs, delta_k = (y_k - t_k) f'(y_k), t = +-1.
+  T error_and_output_delta(int label, T* d) {
+    const int top = n_layers() - 1;
+    const int n = L()[top].maps;
+    const std::vector<T>& y = act[top];
+    if (out_units == OUT_TANH_SQERR) {
+      T e = T(0);
+      for (int k = 0; k < n; ++k) {
+        const T t = (k == label) ? T(1) : T(-1);
+        e += (y[k] - t) * (y[k] - t);
+        if (d) d[k] = (y[k] - t) * act_deriv_from_output(y[k]);
+      }
+      return e / T(2);
+    }
+    if (d)
+      for (int k = 0; k < n; ++k) d[k] = y[k] - (k == label ? T(1) : T(0));
+    return -std::log(y[label]);
+  }
+
   // Backward pass and gradients with every weight still at its pre-update
   // value (Sec. 3.3 for the deltas, Sec. 3.4 for the weight gradients).
   // Requires forward() on the same image.  Nothing is propagated into the
   // network input: there is nothing to adjust below it.
   void backward(int label) {
     const int top = n_layers() - 1;
-    {
-      // act[top] holds the probabilities; delta_k = p_k - [k == label]
-      Layer& a = L()[top];
-      for (int k = 0; k < a.maps; ++k) delta[top][k] = act[top][k] - (k == label ? T(1) : T(0));
-      loss = -std::log(act[top][label]);
-    }
+    loss = error_and_output_delta(label, delta[top].data());
     for (int l = top; l >= 1; --l) {
       Layer& a = L()[l];
       const Layer& p = L()[l - 1];
@@ -541,8 +580,7 @@ struct Net {
         maxpool_backward<T>(gout[l].data(), arg[l].data(), p.maps, p.h, p.w, a.ky, a.kx,
                             gout[l - 1].data());
       } else {  // K_CONV
-        // "each thread multiplies the result by the derivative of the
-        // activation function" (Sec. 3.3)
+        // the summed error is multiplied by the activation function's derivative (Sec. 3.3)
         for (size_t t = 0; t < delta[l].size(); ++t)
           delta[l][t] = gout[l][t] * act_deriv_from_output(act[l][t]);
         conv_weight_grad<T>(delta[l].data(), a.h, a.w, act[l - 1].data(), p.h, p.w, a.conn, a.ky,
@@ -691,6 +729,14 @@ int oracle_set_fixed_frontend(oracle_t* h, int n_filters, int k, int n_src_chann
   return rc;
 }
 
+// 0: soft-max outputs trained on the cross-entropy error (default); 1: scaled-tanh outputs trained
+// on the squared error against +-1 targets.
+int oracle_set_output_units(oracle_t* h, int kind) {
+  if (!h || (kind != OUT_SOFTMAX_XENT && kind != OUT_TANH_SQERR)) return E_ARG;
+  WITH_NET(h, net.out_units = kind);
+  return E_OK;
+}
+
 size_t oracle_num_weights(oracle_t* h) {
   size_t n;
   WITH_NET(h, n = net.weights.size());
@@ -827,7 +873,7 @@ int oracle_loss(oracle_t* h, const float* image, int32_t label, double* loss) {
   if (check_label(h, label)) return E_ARG;
   WITH_NET(h, {
     net.forward(image);
-    *loss = -(double)std::log(net.act.back()[label]);
+    *loss = (double)net.error_and_output_delta(label, nullptr);
   });
   return E_OK;
 }
@@ -929,6 +975,10 @@ double oracle_op_act_deriv_from_output(double y) { return act_deriv_from_output<
 
 double oracle_op_softmax_xent(const double* a, int n, int label, double* p, double* delta) {
   return softmax_xent<double>(a, n, label, p, delta);
+}
+
+double oracle_op_tanh_sqerr(const double* a, int n, int label, double* y, double* delta) {
+  return tanh_sqerr<double>(a, n, label, y, delta);
 }
 
 int oracle_set_threads(int n) {

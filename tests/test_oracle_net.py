@@ -17,9 +17,10 @@ TINY = [
 ]
 
 
-def _build(arch, fan, frontend, seed):
+def _build(arch, fan, frontend, seed, out_units=0):
     rng = np.random.default_rng(seed)
     o = oracle.Oracle(arch)
+    o.set_output_units(out_units)
     tables = {}
     convs = [l for l in range(1, o.num_layers) if o.layer_info(l)["kind"] == oracle.binding.KIND_CONV]
     for ci, f in fan.items():
@@ -48,11 +49,13 @@ def _raw_shape(o, frontend):
     return (i["maps"], i["h"], i["w"])
 
 
+@pytest.mark.parametrize("out_units", [0, 1])
 @pytest.mark.parametrize("arch,fan,frontend", TINY)
-def test_gradient_vs_central_finite_differences(arch, fan, frontend):
+def test_gradient_vs_central_finite_differences(arch, fan, frontend, out_units):
     """The paper's own check of its CPU version (Sec. 4): analytic gradient against finite
-    differences of E, here in double with a relative step."""
-    o, w, img, label, _, _ = _build(arch, fan, frontend, 1234)
+    differences of E, here in double with a relative step; for soft-max + cross-entropy
+    outputs and for scaled-tanh + squared-error outputs."""
+    o, w, img, label, _, _ = _build(arch, fan, frontend, 1234, out_units)
     g, e = o.gradients(img, label)
     assert e == pytest.approx(o.loss(img, label), rel=1e-14)
     rng = np.random.default_rng(5)
@@ -72,12 +75,14 @@ def test_gradient_vs_central_finite_differences(arch, fan, frontend):
     assert worst <= 2e-8 * max(1.0, np.abs(g).max()), worst
 
 
+@pytest.mark.parametrize("out_units", [0, 1])
 @pytest.mark.parametrize("arch,fan,frontend", TINY)
-def test_whole_network_vs_autograd_library(arch, fan, frontend):
-    o, w, img, label, tables, fe = _build(arch, fan, frontend, 4321)
+def test_whole_network_vs_autograd_library(arch, fan, frontend, out_units):
+    o, w, img, label, tables, fe = _build(arch, fan, frontend, 4321, out_units)
     g, e = o.gradients(img, label)
     p = o.forward(img)
-    e2, g2, p2 = loss_and_grads(arch, w, img.reshape(_raw_shape(o, frontend)), label, tables, fe)
+    e2, g2, p2 = loss_and_grads(arch, w, img.reshape(_raw_shape(o, frontend)), label, tables, fe,
+                                tanh_outputs=bool(out_units))
     assert e == pytest.approx(e2, rel=1e-12)
     np.testing.assert_allclose(p, p2, rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(g, g2, rtol=1e-10, atol=1e-12)
@@ -270,3 +275,29 @@ def test_argmax_hints_are_adopted_only_at_near_ties():
     hint = own.copy()
     hint[0, 0, 0] = 7
     assert o.adopt_argmax_hint(2, hint, 1e-6) == (0, 1)
+
+
+def test_tanh_outputs_train_toward_their_targets():
+    """Scaled-tanh output units with the squared error: presenting one image again and again
+    with a small rate drives E down and every output toward its +-1 target; the soft-max
+    default is untouched by the option being set and reset."""
+    arch = "1x9x9-3C4-MP2-4C2-5N-3N"
+    o, w, img, label, _, _ = _build(arch, {}, False, 77)
+    p_softmax = o.forward(img)
+    o.set_output_units(1)
+    y0 = o.forward(img)
+    assert np.all(np.abs(y0) < 1.7159) and abs(y0.sum() - 1.0) > 1e-3   # outputs, not probabilities
+    e_first = o.loss(img, label)
+    last = e_first
+    for _ in range(60):
+        e = o.train_step(img, label, 0.02)
+        assert e <= last + 1e-12
+        last = e
+    y = o.forward(img)
+    t = -np.ones(3)
+    t[label] = 1.0
+    assert last < 0.2 * e_first
+    assert np.abs(y - t).max() < np.abs(y0 - t).max()
+    o.set_output_units(0)
+    o.set_weights(w)
+    np.testing.assert_array_equal(o.forward(img), p_softmax)

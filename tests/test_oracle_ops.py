@@ -275,3 +275,47 @@ def test_softmax_xent_invariants():
     # huge logits do not overflow
     e, p, _ = ops.softmax_xent(np.array([1000.0, 0.0]), 0)
     assert np.isfinite(e) and p[0] == pytest.approx(1.0)
+
+
+# ------------------------------------------------------------------ scaled-tanh outputs / squared error
+
+def test_tanh_sqerr_closed_forms_and_derivative():
+    """The output variant with the paper's activation on the output neurons (Sec. 4) and the
+    squared error against +-1 targets: values that follow from the definition alone."""
+    A, B = 1.7159, 0.6666
+    # zero pre-activations: y = 0, E = n/2, delta_k = -t_k * f'(0) = -t_k A B
+    e, y, d = ops.tanh_sqerr(np.zeros(5), 3)
+    assert e == pytest.approx(2.5, rel=1e-15)
+    np.testing.assert_array_equal(y, np.zeros(5))
+    want = np.full(5, A * B)
+    want[3] = -A * B
+    np.testing.assert_allclose(d, want, rtol=1e-14)
+    # pre-activations that put every output on its target: E = 0, delta = 0
+    a_one = np.arctanh(1.0 / A) / B
+    a = np.full(4, -a_one)
+    a[1] = a_one
+    e, y, d = ops.tanh_sqerr(a, 1)
+    assert e == pytest.approx(0.0, abs=1e-28)
+    np.testing.assert_allclose(d, 0.0, atol=1e-14)
+    # saturated and wrong: y -> -A on the class unit, error (A + 1)^2 / 2 from it alone, tiny delta
+    e, y, d = ops.tanh_sqerr(np.array([-40.0, -a_one]), 0)
+    assert e == pytest.approx((A + 1.0) ** 2 / 2, rel=1e-12)
+    assert abs(d[0]) < 1e-12
+    # general case: definition retyped with the library tanh, derivative by central differences
+    rng = np.random.default_rng(33)
+    for n in (2, 5, 10):
+        a = rng.standard_normal(n) * 1.5
+        lab = int(rng.integers(n))
+        e, y, d = ops.tanh_sqerr(a, lab)
+        t = -np.ones(n)
+        t[lab] = 1.0
+        yy = A * torch.tanh(B * torch.from_numpy(a)).numpy()
+        np.testing.assert_allclose(y, yy, rtol=1e-14)
+        assert e == pytest.approx(0.5 * np.sum((yy - t) ** 2), rel=1e-13)
+        for k in range(n):
+            h = 1e-6
+            ap, am = a.copy(), a.copy()
+            ap[k] += h
+            am[k] -= h
+            fd = (ops.tanh_sqerr(ap, lab)[0] - ops.tanh_sqerr(am, lab)[0]) / (2 * h)
+            assert d[k] == pytest.approx(fd, abs=1e-8)

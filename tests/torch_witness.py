@@ -27,9 +27,11 @@ def parse(arch):
     return (c, h, w), layers
 
 
-def loss_and_grads(arch, weights, image, label, tables=None, frontend=None):
+def loss_and_grads(arch, weights, image, label, tables=None, frontend=None, tanh_outputs=False):
     """Returns (loss, grad in the canonical flat layout, probs).  tables: {conv_index: [mo, mi]}.
-    frontend: (filters [n, k, k], src_channel [n]) applied to the raw image first (linear)."""
+    frontend: (filters [n, k, k], src_channel [n]) applied to the raw image first (linear).
+    tanh_outputs: scaled-tanh output units and half the squared error against +-1 targets
+    (the outputs are then returned in place of the probabilities)."""
     tables = tables or {}
     (c, h, w), layers = parse(arch)
     wt = torch.tensor(np.asarray(weights, dtype=np.float64), requires_grad=True)
@@ -79,6 +81,13 @@ def loss_and_grads(arch, weights, image, label, tables=None, frontend=None):
             if li + 1 < len(layers):
                 x = A * torch.tanh(B * x)
     assert off == wt.numel()
+    if tanh_outputs:
+        y = A * torch.tanh(B * x[0])
+        target = -torch.ones_like(y)
+        target[int(label)] = 1.0
+        loss = 0.5 * torch.sum((y - target) ** 2)
+        loss.backward()
+        return loss.item(), wt.grad.numpy().copy(), y.detach().numpy()
     logp = torch.log_softmax(x[0], 0)
     loss = -logp[int(label)]
     loss.backward()
