@@ -51,10 +51,21 @@ enum {
   CNN_MODE_RESIDENT = 2   /* one cooperative launch per call; every workgroup owns whole
                              maps and keeps their weights in LDS for the whole call; what
                              workgroups exchange per image travels as tagged words, with no
-                             grid barrier.  Needs at least one convolutional layer, no fixed
-                             front-end, and a network whose per-workgroup share fits the LDS
-                             (cnn_mode_supported tells).  Weights in the workspace are read
-                             at the start of a call and written back at its end.            */
+                             grid barrier.  Needs one to four convolutional and one to four
+                             fully connected layers and a network whose per-workgroup share
+                             fits the LDS (cnn_mode_supported tells).  Weights in the
+                             workspace are read at the start of a call and written back at
+                             its end.                                                       */
+};
+
+/* output units for cnn_set_output_units */
+enum {
+  CNN_OUTPUT_SOFTMAX_XENT = 0, /* soft-max outputs, cross-entropy error E = -log p[label];
+                                  delta_k = p_k - [k == label] (default)                    */
+  CNN_OUTPUT_TANH_SQERR = 1    /* the scaled hyperbolic tangent of Sec. 4 on the output
+                                  neurons too, E = 1/2 sum_k (y_k - t_k)^2 with targets
+                                  t = +1 for the image's class and -1 otherwise;
+                                  delta_k = (y_k - t_k) f'(y_k)                             */
 };
 
 /*
@@ -172,6 +183,14 @@ int cnn_mode_supported(cnn_t* net, int mode);
  * Results do not depend on the placement, and for a given n_ranks they are reproducible bit
  * for bit.  Synchronises. */
 int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride);
+
+/* What the last layer computes and which error the net is trained on (Sec. 4 gives every neuron
+ * the scaled hyperbolic tangent and names no error function: both readings are offered).  With
+ * CNN_OUTPUT_TANH_SQERR the d_probs arguments receive the outputs y_k instead of probabilities
+ * and cnn_get_loss the squared error.  Every mode honours it; weights, tables and the weight
+ * count are unchanged.  kind outside the enum: CNN_E_ARG.  Synchronises. */
+int cnn_set_output_units(cnn_t* net, int kind);
+int cnn_get_output_units(const cnn_t* net);
 
 /* Stage and persistent modes: whether wide convolutional layers (full table, at least 64 output
  * maps and 256 inputs x taps per output) run their forward pass as an implicit GEMM on the matrix

@@ -15,6 +15,7 @@ from . import build as _build
 OK, E_SYNTAX, E_SHAPE, E_ARG, E_WORKSPACE, E_HIP, E_STATE = 0, -1, -2, -3, -4, -5, -6
 LAYER_INPUT, LAYER_CONV, LAYER_POOL, LAYER_FC = 0, 1, 2, 3
 MODE_STAGES, MODE_PERSISTENT, MODE_RESIDENT = 0, 1, 2
+OUTPUT_SOFTMAX_XENT, OUTPUT_TANH_SQERR = 0, 1
 
 _lib = None
 
@@ -58,6 +59,8 @@ def lib():
             "cnn_get_mode": (C.c_int, [vp]),
             "cnn_mode_supported": (C.c_int, [vp, C.c_int]),
             "cnn_set_team": (C.c_int, [vp, C.c_int, C.c_int]),
+            "cnn_set_output_units": (C.c_int, [vp, C.c_int]),
+            "cnn_get_output_units": (C.c_int, [vp]),
             "cnn_set_matrix_cores": (C.c_int, [vp, C.c_int]),
             "cnn_set_grid": (C.c_int, [vp, C.c_int]),
             "cnn_set_spin_limit": (C.c_int, [vp, C.c_uint]),
@@ -83,7 +86,8 @@ EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_get_pla
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many", "cnn_set_mode",
-           "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
+           "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
+           "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
            "cnn_last_error"]
 
@@ -214,6 +218,14 @@ class Cnn:
 
     def set_team(self, n_ranks=0, xcd_stride=0):
         self._ck(lib().cnn_set_team(self._h, int(n_ranks), int(xcd_stride)), "cnn_set_team")
+
+    def set_output_units(self, kind):
+        """OUTPUT_SOFTMAX_XENT (default) or OUTPUT_TANH_SQERR."""
+        self._ck(lib().cnn_set_output_units(self._h, int(kind)), "cnn_set_output_units")
+
+    @property
+    def output_units(self):
+        return lib().cnn_get_output_units(self._h)
 
     def set_matrix_cores(self, on):
         self._ck(lib().cnn_set_matrix_cores(self._h, 1 if on else 0), "cnn_set_matrix_cores")

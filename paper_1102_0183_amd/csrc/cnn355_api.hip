@@ -193,6 +193,7 @@ struct cnn {
   float* d_fe_batch = nullptr;  // resident mode: front-end outputs of FE_BATCH images at a time
   float* d_mm_part = nullptr;   // partial sums of the matrix-core forward pass (one layer at a time)
   int use_mfma = 1;
+  int out_units = CNN_OUTPUT_SOFTMAX_XENT;
   struct ConvBuf {
     float *act, *out, *delta;
     uint8_t* arg;
@@ -500,6 +501,7 @@ int plan(cnn* net) {
       L.n_in = A[l - 1].maps * A[l - 1].h * A[l - 1].w;
       L.n_out = A[l].maps;
       L.is_output = (l + 1 == A.size());
+      L.out_units = L.is_output ? net->out_units : 0;
       if (L.n_out > MAX_FC_OUT)
         return fail(&net->err, CNN_E_SHAPE, "fully connected layer wider than " + std::to_string(MAX_FC_OUT));
       const cnn::FcBuf& b = net->fc_buf[fc_i];
@@ -654,7 +656,7 @@ void plan_flow(cnn* net) {
   if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1)
     return no("resident mode takes at most " + std::to_string(FLOW_MAX_CONV) + " convolutional and " +
               std::to_string(FLOW_MAX_FC) + " fully connected layers");
-  Z.n_conv = n_conv; Z.n_fc = n_fc; Z.n_classes = P.n_classes;
+  Z.n_conv = n_conv; Z.n_fc = n_fc; Z.n_classes = P.n_classes; Z.out_units = net->out_units;
   for (int l = 0; l < n_conv; ++l) {
     const LayerDev& L = P.layers[l];
     ConvSpec& C = Z.conv[l];
@@ -1085,6 +1087,22 @@ int cnn_set_matrix_cores(cnn_t* net, int on) {
   HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   return CNN_OK;
 }
+
+int cnn_set_output_units(cnn_t* net, int kind) {
+  if (!net || (kind != CNN_OUTPUT_SOFTMAX_XENT && kind != CNN_OUTPUT_TANH_SQERR)) return CNN_E_ARG;
+  if (kind == net->out_units) return CNN_OK;
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  net->out_units = kind;
+  // re-plan: the descriptors carry the kind; weights, tables and buffers stay as they are
+  int rc = plan(net);
+  if (rc) return rc;
+  HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
+  HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
+  return CNN_OK;
+}
+
+int cnn_get_output_units(const cnn_t* net) { return net ? net->out_units : CNN_E_ARG; }
 
 int cnn_set_grid(cnn_t* net, int n_workgroups) {
   if (!net || n_workgroups < 0) return CNN_E_ARG;

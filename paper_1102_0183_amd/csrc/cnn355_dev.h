@@ -39,7 +39,8 @@ struct LayerDev {
   // skipping factor S (stride S+1), pooled by Kp to Hp x Wp
   int Mi, Hi, Wi, Mo, Ho, Wo, K, S, Kp, Hp, Wp;
   int n_in, n_out;     // fully connected: W is [n_out][n_in]
-  int is_output;       // soft-max output layer
+  int is_output;       // output layer
+  int out_units;       // output layer: 0 soft-max + cross-entropy, 1 scaled tanh + squared error (targets +-1)
   int in_is_image;     // input is the image handed to the call (no stored activation below)
   int max_conn;        // longest row of the connection table
   int full_table;      // every output map reads every input map (slot of (j, i) is j * Mi + i)

@@ -1222,6 +1222,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
     const FlowFcPtrs& Po = Q.fc[n_fc - 1];
     const int N = n_classes;
     const bool wave_softmax = N <= 64;
+    const bool tanh_out = uni_of<ID>(Z.out_units) == 1;
     {
       float* y = lds + Lo.o_act;
       float* d = lds + Lo.o_delta;
@@ -1231,19 +1232,42 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         const float mx = f_wave_max(yk);
         const float e = (k < N) ? expf(yk - mx) : 0.f;
         const float z = f_wave_sum(e);
-        const float p = e / z;
+        float p = e / z;
         dreg = p - (k == label ? 1.f : 0.f);
+        float err = 0.f;
+        if (tanh_out) {  // scaled-tanh outputs, squared error against targets +1 / -1
+          p = (k < N) ? f_act(yk) : 0.f;
+          const float dev = (k < N) ? p - (k == label ? 1.f : -1.f) : 0.f;
+          dreg = dev * f_dact(p);
+          err = 0.5f * f_wave_sum(dev * dev);
+        }
         if (tid < N) {
           if (rank == 0) {
             if (a.probs_out) a.probs_out[t * n_classes + k] = p;
-            if (train && k == label) status->loss = -logf(p);
+            if (train && tanh_out && k == 0) status->loss = err;
+            if (train && !tanh_out && k == label) status->loss = -logf(p);
           }
           if (taps || n_fc == 1) d[k] = dreg;
           if (taps && rank == 0) Po.act[k] = p;
         }
         if (n_fc == 1) __syncthreads();  // the first FC layer's BP reads the deltas from LDS
       } else {
-        if (tid < 64) {
+        if (tid < 64 && tanh_out) {
+          float err = 0.f;
+          for (int k = tid; k < N; k += 64) {
+            const float p = f_act(y[k]);
+            const float dev = p - (k == label ? 1.f : -1.f);
+            y[k] = p;
+            d[k] = dev * f_dact(p);
+            err = fmaf(dev, dev, err);
+            if (rank == 0) {
+              if (a.probs_out) a.probs_out[t * n_classes + k] = p;
+              if (taps) Po.act[k] = p;
+            }
+          }
+          err = f_wave_sum(err);
+          if (rank == 0 && train && tid == 0) status->loss = 0.5f * err;
+        } else if (tid < 64) {
           float mx = -INFINITY;
           for (int k = tid; k < N; k += 64) mx = fmaxf(mx, y[k]);
           mx = f_wave_max(mx);

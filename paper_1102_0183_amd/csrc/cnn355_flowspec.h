@@ -59,6 +59,7 @@ struct FlowSpec {
   int scratch_floats;
   int o_dall;       // [max Mo*Hp*Wp] deltas of every map of the layer being pulled through
   int o_yxall;      // same, winner coordinates
+  int out_units;    // 0 soft-max + cross-entropy, 1 scaled tanh + squared error
   int defer;        // 1: weight adjustments nobody is waiting for are put off into the next image's waits
   int o_prev;       // [conv[1].n_own_below * Hi * Wi] the own pooled maps of the first layer, previous image
   ConvSpec conv[FLOW_MAX_CONV];
@@ -130,7 +131,7 @@ constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, 
 }
 
 // Choose the team and lay out every rank's LDS.  On entry Z holds the shape (n_conv, n_fc,
-// n_classes, and per layer Mi..Wp, max_conn, max_back, full_table / n_in, n_out, is_output); on
+// n_classes, out_units, and per layer Mi..Wp, max_conn, max_back, full_table / n_in, n_out, is_output); on
 // success the rest of Z is filled in.  team_ranks / team_stride: 0 = automatic.
 constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) {
   const int n_conv = Z.n_conv, n_fc = Z.n_fc;

@@ -605,7 +605,22 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
   }
   __syncthreads();
   DBG(11);
-  if (wave == 0) {
+  if (wave == 0 && L.out_units == 1) {
+    // scaled-tanh output neurons (Sec. 4), squared error against targets +1 (the image's class) / -1
+    float e = 0.f;
+    for (int k = lane; k < N; k += 64) {
+      const float y = act_f(logit[k]);
+      const float t = (k == ctx.label) ? 1.f : -1.f;
+      L.act[k] = y;
+      if (ctx.probs_out) ctx.probs_out[k] = y;
+      const float d = (y - t) * dact_f(y);
+      dl[k] = d;
+      e = fmaf(y - t, y - t, e);
+      if (ctx.train) L.delta[k] = d;
+    }
+    e = wave_sum(e);
+    if (ctx.train && lane == 0) status->loss = 0.5f * e;
+  } else if (wave == 0) {
     float mx = -INFINITY;
     for (int k = lane; k < N; k += 64) mx = fmaxf(mx, logit[k]);
     mx = wave_max(mx);

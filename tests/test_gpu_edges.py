@@ -123,6 +123,9 @@ def test_argument_errors_and_bad_labels():
         g.argmax(1)                                                # not a pooling layer
     with pytest.raises(binding.CnnError):
         g.delta(2)                                                 # pooling layers hold no delta
+    with pytest.raises(binding.CnnError) as e:
+        g.set_output_units(7)                                      # neither of the two kinds
+    assert e.value.code == binding.E_ARG and g.output_units == binding.OUTPUT_SOFTMAX_XENT
     # a bad label inside a device label array: that image is skipped, the others train, and
     # the next synchronising call reports it
     rng = np.random.default_rng(1)

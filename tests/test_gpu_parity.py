@@ -243,3 +243,61 @@ def test_lr_zero_leaves_weights_untouched():
     g.train_many(to_dev(imgs), to_dev(labs), 0.0)
     np.testing.assert_array_equal(g.get_weights(), w0)
     g.close()
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name", ["cfg1", "cfg5", "cfg4a"])
+def test_tanh_output_units_one_step_and_100_steps(name, mode):
+    """The output variant with scaled-tanh output neurons trained on the squared error against
+    +-1 targets: outputs, error, deltas and gradients of one image, then 100 on-line steps in
+    lock-step with the oracle, the batched call reproducing the steps bit for bit, and the
+    forward-only call returning the outputs."""
+    from tests.parity_helpers import lockstep_train
+    import torch
+    wl = synth.WORKLOADS[name]
+    print("case", name, "mode", mode, flush=True)
+    g, o = build_pair(wl)
+    use_mode(g, mode)
+    g.set_output_units(binding.OUTPUT_TANH_SQERR)
+    assert g.output_units == binding.OUTPUT_TANH_SQERR
+    o.set_output_units(1)
+    img = synth.images(wl, 2)[1]
+    lab = int(synth.labels(wl, 2)[1])
+    grad_g = g.debug_gradients(to_dev(img), lab)
+    grad_o, loss_o = o.gradients(img, lab)
+    compare_forward_state(g, o)
+    compare_backward_state(g, o)
+    assert abs(g.loss() - loss_o) <= 1e-5 * max(1.0, abs(loss_o))
+    for (a, b) in layer_bounds(o):
+        assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
+    n = 100
+    imgs, labs = synth.images(wl, n), synth.labels(wl, n)
+    adopted = lockstep_train(g, o, imgs, labs, wl.lr)
+    wg, wo = g.get_weights(), o.get_weights()
+    w0 = synth.weights(wl, g.num_weights)
+    e, e_upd = rel_err(wg, wo), rel_err(wg.astype(np.float64) - w0, wo - w0)
+    print("  weights rel err %.2e, accumulated update rel err %.2e, near-tie winners adopted: %d"
+          % (e, e_upd, adopted), flush=True)
+    assert e <= TOL_W100 and e_upd <= 1e-3
+    d_imgs, d_labs = to_dev(imgs), to_dev(labs)
+    d_out = torch.empty(5 * g.num_classes, dtype=torch.float32, device="cuda:0")
+    g.forward_many(d_imgs, 5, d_out)
+    g.synchronize()
+    want = o.forward_many(imgs[:5], 5)
+    assert np.abs(d_out.cpu().numpy().reshape(5, -1) - want).max() <= 1e-4
+    assert np.abs(want.sum(axis=1) - 1.0).max() > 1e-3      # outputs, not probabilities
+    g2, _ = build_pair(wl)
+    g2.set_mode(mode)
+    g2.set_output_units(binding.OUTPUT_TANH_SQERR)
+    g2.train_many(d_imgs, d_labs, wl.lr)
+    np.testing.assert_array_equal(g2.get_weights(), wg)
+    # back to the default: the soft-max path is untouched
+    g2.set_output_units(binding.OUTPUT_SOFTMAX_XENT)
+    g2.set_weights(w0)
+    o.set_output_units(0)
+    o.set_weights(w0.astype(np.float64))
+    g2.forward(to_dev(img))
+    o.forward(img)
+    compare_forward_state(g2, o)
+    g.close()
+    g2.close()
