@@ -147,6 +147,24 @@ int cnn_layer_info(const cnn_t* net, int layer, int32_t* info6);
 int cnn_get_weights(cnn_t* net, float* host_dst, size_t n);
 int cnn_set_weights(cnn_t* net, const float* host_src, size_t n);
 
+/* Forward propagation of many images at once (Sec. 3.2; validation and test passes change no
+ * weight, Sec. 4, so their images are independent).  Every layer becomes one matrix product over
+ * the whole batch on the matrix cores, fp32 in and out; results agree with cnn_forward_many to
+ * rounding (other summation order), whatever the mode of the handle.
+ *   cnn_forward_batch_scratch_bytes: device memory the call needs for `batch` images in flight
+ *     (re-packed weights, the layer outputs of one batch); the caller allocates it.
+ *   cnn_forward_batch: d_images [n][cnn_image_size], d_probs [n][cnn_num_classes] (probabilities, or
+ *     the outputs with CNN_OUTPUT_TANH_SQERR), both device memory; d_scratch: device memory,
+ *     256-byte aligned, at least scratch_bytes, owned by the caller, free for other use once the
+ *     stream has passed the call.  The n images are run `batch` at a time.  The weights are read as
+ *     they stand when the call reaches them on the stream.  Asynchronous.
+ * Errors: CNN_E_ARG (NULL, batch 0, misaligned scratch), CNN_E_WORKSPACE (scratch too small),
+ * CNN_E_SHAPE (a single input map of some layer, times the images one workgroup touches, exceeds
+ * the LDS budget of 64 KB), CNN_E_HIP. */
+int cnn_forward_batch_scratch_bytes(cnn_t* net, size_t batch, size_t* bytes);
+int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
+                      size_t scratch_bytes, size_t batch);
+
 /* Forward propagation of one image (Sec. 3.2).  d_image: cnn_image_size floats, maps then
  * rows then columns.  d_probs: cnn_num_classes floats (may be NULL).  Asynchronous. */
 int cnn_forward(cnn_t* net, const float* d_image, float* d_probs);

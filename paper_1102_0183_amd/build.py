@@ -5,9 +5,10 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcnn355.so")
-SOURCES = ["cnn355_kernels.hip", "cnn355_flow.hip", "cnn355_api.hip"]
+SOURCES = ["cnn355_kernels.hip", "cnn355_flow.hip", "cnn355_batch.hip", "cnn355_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed-FP32 instructions are switched off on purpose ("compiler flags")
+# packed-FP32 instructions are switched off on purpose: some of their forms have given wrong
+# results on this hardware, without any error
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-pass-failed"]
 

@@ -27,6 +27,12 @@ hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, c
 hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
                            const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a);
 int resident_static_id(const FlowSpec& z);
+size_t batch_gemm_lds_bytes(const BatchGemm& g);
+hipError_t launch_batch_gemm(hipStream_t stream, const BatchGemm& g);
+hipError_t launch_batch_pool(hipStream_t stream, const BatchPool& q);
+hipError_t launch_batch_outputs(hipStream_t stream, const float* logits, float* probs, long long n_images,
+                                int n_classes, int out_units);
+hipError_t launch_batch_pack(hipStream_t stream, const BatchPack& q, long long wt_floats);
 }  // namespace cnn355
 
 using namespace cnn355;
@@ -842,6 +848,115 @@ int run(cnn* net, const RunArgs& a0) {
 
 }  // namespace
 
+// ---- batched forward pass ------------------------------------------------------------------
+namespace {
+
+struct BatchStep {
+  BatchGemm g;
+  BatchPool pool;     // used when g.fuse == 0
+  BatchPack pack;
+  size_t wt_off = 0;  // floats from the start of the scratch
+  size_t wt_floats = 0;
+  size_t out_per_image = 0;
+};
+struct BatchPlan {
+  std::vector<BatchStep> steps;
+  size_t wt_total = 0, sums_per_image = 0, act_per_image = 0, fe_per_image = 0;
+  size_t floats(size_t batch) const {
+    return wt_total + batch * (sums_per_image + 2 * act_per_image + fe_per_image) + 4 * 64;
+  }
+};
+
+size_t up64(size_t x) { return (x + 63) / 64 * 64; }
+
+// Shape of every layer's matrix product, tile choice and LDS budget.  Returns 0 or an error code.
+int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
+  const ProgramDev& P = net->prog;
+  constexpr size_t LDS_FLOATS = 16384;  // 64 KB per workgroup: two workgroups per compute unit
+  B = BatchPlan();
+  for (int l = 0; l < P.n_layers; ++l) {
+    const LayerDev& L = P.layers[l];
+    BatchStep st;
+    BatchGemm& g = st.g;
+    std::memset(&g, 0, sizeof(g));
+    int Kp = 1, Ho = 1, Hp = 1, Wp = 1;
+    if (L.kind == L_CONV) {
+      g.Mi = L.Mi; g.Hi = L.Hi; g.Wi = L.Wi; g.K = L.K; g.stride = L.S + 1; g.Mo = L.Mo; g.Wo = L.Wo;
+      g.P = L.Ho * L.Wo; Ho = L.Ho; Kp = L.Kp; Hp = L.Hp; Wp = L.Wp;
+    } else {  // a fully connected layer: n_in maps of one pixel, K = 1
+      g.Mi = L.n_in; g.Hi = 1; g.Wi = 1; g.K = 1; g.stride = 1; g.Mo = L.n_out; g.Wo = 1; g.P = 1;
+    }
+    // map tiles per workgroup: the choice that pads the fewest maps, the larger on a tie
+    int best_pad = 0;
+    for (int mt : {4, 2, 1}) {
+      const int pad = (g.Mo + 32 * mt - 1) / (32 * mt) * (32 * mt);
+      if (!best_pad || pad < best_pad) { best_pad = pad; g.MT = mt; }
+    }
+    g.MoPad = best_pad;
+    g.n_img_max = (int)std::min<size_t>(std::max<size_t>(batch, 1), (size_t)((128 - 1 + g.P - 1) / g.P + 1));
+    const int KK = g.K * g.K, HiWi = g.Hi * g.Wi;
+    // input maps per chunk: as many as the LDS budget takes; when that leaves several chunks,
+    // prefer a chunk that also fits the prefetch registers (16 + 48 floats per thread), unless
+    // such a chunk would be too short to hide anything behind.  One-pixel maps (fully connected
+    // layers) take a power of two, so that staging finds image and offset by shifting.
+    int ic = 0, ic_pre = 0;
+    for (int c = 1; c <= g.Mi; ++c) {
+      const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * 32;
+      if (in_f + w_f + (size_t)c * KK > LDS_FLOATS) break;
+      if (HiWi == 1 && c < g.Mi && (c & (c - 1)) != 0) continue;
+      ic = c;
+      if (in_f <= 16 * 256 && w_f <= 48 * 256) ic_pre = c;
+    }
+    if (ic == 0)
+      return fail(&net->err, CNN_E_SHAPE, "batched forward pass: one input map of a layer (times the images a "
+                                          "workgroup touches) exceeds the LDS budget");
+    g.prefetch = 0;
+    if (ic < g.Mi && ic_pre * KK >= 96) { ic = ic_pre; g.prefetch = 1; }
+    g.IC = ic;
+    // few columns and a long k range (fully connected layers, deep layers on small maps): the k
+    // range is cut into slices, one workgroup each, until some 512 workgroups are in flight
+    const int n_chunks = (g.Mi + ic - 1) / ic;
+    const size_t wgs = ((batch * g.P + 127) / 128) * (size_t)(g.MoPad / (32 * g.MT));
+    int ks = 1;
+    if (wgs < 512 && n_chunks > 1) ks = (int)std::min<size_t>((size_t)n_chunks, (512 + wgs - 1) / wgs);
+    g.chunks_per_slice = (n_chunks + ks - 1) / ks;
+    g.KS = (n_chunks + g.chunks_per_slice - 1) / g.chunks_per_slice;
+    g.slice_stride = (long long)(batch * g.Mo * g.P);
+    g.fuse = (Kp > 1 || g.KS > 1) ? 0 : (L.is_output ? 2 : 1);
+    g.bias = L.bias;
+    g.in_stride = (long long)g.Mi * HiWi;
+    g.out_stride = (long long)g.Mo * g.P;
+    st.wt_floats = up64((size_t)g.Mi * KK * g.MoPad);
+    st.wt_off = B.wt_total;
+    B.wt_total += st.wt_floats;
+    BatchPack& k = st.pack;
+    std::memset(&k, 0, sizeof(k));
+    k.w = L.w; k.csr_ptr = L.csr_ptr; k.csr_idx = L.csr_idx;
+    k.is_fc = L.kind != L_CONV; k.full_table = L.full_table; k.Mi = g.Mi; k.Mo = g.Mo; k.K = g.K; k.n_in = L.n_in;
+    k.MoPad = g.MoPad;
+    if (L.kind == L_CONV) {
+      int ci = 0;
+      for (int q = 0; q < l; ++q) ci += P.layers[q].kind == L_CONV;
+      k.total = (long long)net->host_tables[ci].csr_idx.size() * KK;
+    } else {
+      k.total = (long long)L.n_in * L.n_out;
+    }
+    BatchPool& q = st.pool;
+    std::memset(&q, 0, sizeof(q));
+    q.bias = L.bias; q.Mo = g.Mo; q.Ho = Ho; q.Wo = g.Wo; q.Kp = Kp; q.Hp = Hp; q.Wp = Wp;
+    q.n_slices = g.KS; q.slice_stride = g.slice_stride; q.act = L.is_output ? 0 : 1;
+    st.out_per_image = (Kp > 1) ? (size_t)g.Mo * Hp * Wp : (size_t)g.Mo * g.P;
+    if (g.fuse == 0) B.sums_per_image = std::max(B.sums_per_image, up64((size_t)g.KS * g.Mo * g.P));
+    B.act_per_image = std::max(B.act_per_image, up64(st.out_per_image));
+    B.steps.push_back(st);
+  }
+  if (P.has_frontend) B.fe_per_image = up64((size_t)P.fe.n_filters * P.fe.H * P.fe.W);
+  return CNN_OK;
+}
+
+}  // namespace
+
+
 extern "C" {
 
 int cnn_arch_info(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers) {
@@ -1238,5 +1353,70 @@ int cnn355_read_status_stamps(cnn_t* net, unsigned long long* out, int n) {
 void cnn355_read_stamps(unsigned long long* out64) { cnn355::read_dbg(out64); }
 
 const char* cnn_last_error(const cnn_t* net) { return net ? net->err.c_str() : g_err.c_str(); }
+
+int cnn_forward_batch_scratch_bytes(cnn_t* net, size_t batch, size_t* bytes) {
+  if (!net || !bytes || batch == 0) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument or batch of 0");
+  BatchPlan B;
+  int rc = batch_plan(net, batch, B);
+  if (rc) return rc;
+  *bytes = B.floats(batch) * sizeof(float);
+  return CNN_OK;
+}
+
+int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
+                      size_t scratch_bytes, size_t batch) {
+  if (!net) return fail(nullptr, CNN_E_ARG, "NULL handle");
+  if (n == 0) return CNN_OK;
+  if (!d_images || !d_probs || !d_scratch || batch == 0) return fail(&net->err, CNN_E_ARG, "NULL argument or batch of 0");
+  if (((uintptr_t)d_scratch & 255u) != 0) return fail(&net->err, CNN_E_ARG, "scratch must be 256-byte aligned");
+  BatchPlan B;
+  int rc = batch_plan(net, batch, B);
+  if (rc) return rc;
+  if (scratch_bytes < B.floats(batch) * sizeof(float))
+    return fail(&net->err, CNN_E_WORKSPACE, "scratch smaller than cnn_forward_batch_scratch_bytes says");
+  const ProgramDev& P = net->prog;
+  float* base = (float*)d_scratch;
+  float* d_sums = base + B.wt_total;
+  float* d_act[2] = {d_sums + batch * B.sums_per_image, d_sums + batch * (B.sums_per_image + B.act_per_image)};
+  float* d_fe = d_act[1] + batch * B.act_per_image;
+  // the weights as the products read them: one [k][map] matrix per layer, from their present values
+  for (BatchStep& st : B.steps) {
+    st.pack.wt = base + st.wt_off;
+    HIP_TRY(net, launch_batch_pack(net->stream, st.pack, (long long)st.wt_floats));
+  }
+  const size_t fe_sz = P.has_frontend ? (size_t)P.fe.n_filters * P.fe.H * P.fe.W : 0;
+  for (size_t t0 = 0; t0 < n; t0 += batch) {
+    const size_t nb = std::min(batch, n - t0);
+    const float* in = d_images + t0 * net->image_size;
+    long long in_stride = (long long)net->image_size;
+    if (P.has_frontend) {
+      HIP_TRY(net, launch_frontend_batch(net->stream, net->d_prog, in, in_stride, (int)nb, (int)((fe_sz + WG - 1) / WG), d_fe));
+      in = d_fe;
+      in_stride = (long long)fe_sz;
+    }
+    int cur = 0;
+    for (size_t s = 0; s < B.steps.size(); ++s) {
+      BatchStep& st = B.steps[s];
+      BatchGemm g = st.g;
+      g.in = in; g.in_stride = in_stride; g.wt = base + st.wt_off; g.N = (long long)nb * g.P;
+      float* out = d_act[cur];
+      if (g.fuse == 0) {
+        g.out = d_sums;
+        HIP_TRY(net, launch_batch_gemm(net->stream, g));
+        BatchPool q = st.pool;
+        q.sums = d_sums; q.out = out; q.total = (long long)nb * q.Mo * q.Hp * q.Wp;
+        HIP_TRY(net, launch_batch_pool(net->stream, q));
+      } else {
+        g.out = out;
+        HIP_TRY(net, launch_batch_gemm(net->stream, g));
+      }
+      in = out;
+      in_stride = (long long)st.out_per_image;
+      cur ^= 1;
+    }
+    HIP_TRY(net, launch_batch_outputs(net->stream, in, d_probs + t0 * P.n_classes, (long long)nb, P.n_classes, net->out_units));
+  }
+  return CNN_OK;
+}
 
 }  // extern "C"

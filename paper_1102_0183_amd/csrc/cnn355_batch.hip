@@ -1,0 +1,335 @@
+// Batched forward propagation (Sec. 3.2 for many images at once): validation and test passes
+// change no weight (Sec. 4), so their images are independent and every layer becomes one dense
+// matrix product over the whole batch,
+//     sums[j][n] = sum_k  Wt[k][j] * X[k][n],     n = (image b, output pixel p),  k = (input map i, ky, kx),
+// which is what the matrix cores are for.  X is never formed: its element is
+// in[b][i][(y (S+1) + ky)][(x (S+1) + kx)], read from the images staged in LDS at offset
+// koff(k) + pbase(n).  A fully connected layer is the same product with 1 x 1 maps and K = 1.
+// fp32 operands and fp32 accumulation (v_mfma_f32_32x32x2_f32): the results stay within the
+// tolerance of the one-image path.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#define CNN_GLOBAL __attribute__((address_space(1)))
+#include "cnn355_dev.h"
+
+namespace cnn355 {
+
+typedef const CNN_GLOBAL float* cgf;
+typedef CNN_GLOBAL float* gf;
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int BT = 256;        // threads of a GEMM workgroup: four wavefronts, 32 columns each
+constexpr int BCOLS = 128;     // columns (image, pixel) of a workgroup
+
+__device__ __forceinline__ float b_act(float a) { return 1.7159f * tanhf(0.6666f * a); }
+
+constexpr int PRE_IN = 16;     // floats per thread a prefetched chunk may hold: staged images ...
+constexpr int PRE_W = 48;      // ... and rows of Wt
+
+// Workgroup (x, y): columns [128 x, 128 x + 128) and map tiles [MT y, MT y + MT) of 32 maps each.
+// Every wavefront owns 32 columns and all MT map tiles, so one operand fetched from the staged
+// images feeds MT matrix instructions.  The k range is walked in chunks of IC input maps: the
+// chunk's maps of every image the columns touch, and the chunk's rows of Wt, are staged in LDS.
+// With g.prefetch the next chunk is fetched into registers while the matrix cores work on the
+// present one (global latency hidden behind arithmetic); the host sets it only when a chunk
+// fits the register budget (PRE_IN, PRE_W floats per thread).
+template <int MT>
+__global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
+  extern __shared__ float lds[];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int lrow = lane & 31, lk = lane >> 5;
+  const int HiWi = g.Hi * g.Wi, KK = g.K * g.K;
+  const int slot_sz = g.IC * HiWi;
+  const int KC = g.IC * KK;                        // k per full chunk
+  constexpr int WROW = MT * 32;
+  float* lds_in = lds;                              // [n_img_max][IC][Hi*Wi]
+  float* lds_w = lds + g.n_img_max * slot_sz;       // [KC + 1][MT * 32]; the row behind the last is zero
+  int* koff = (int*)(lds_w + (KC + 1) * WROW);      // [KC]
+
+  const long long n0 = (long long)blockIdx.x * BCOLS;
+  const int mt0 = blockIdx.y * MT;
+  const long long b_lo = n0 / g.P;
+  const long long n_last = min(n0 + BCOLS, g.N) - 1;
+  const int n_img = (int)(n_last / g.P - b_lo) + 1;
+
+  for (int x = tid; x < KC; x += BT) {
+    const int c = x / KK, t = x - c * KK;
+    const int ky = t / g.K, kx = t - ky * g.K;
+    koff[x] = c * HiWi + ky * g.Wi + kx;
+  }
+  const long long n = n0 + wave * 32 + lrow;
+  const bool col_ok = n < g.N;
+  long long b = 0;
+  int p = 0, pbase = 0;
+  if (col_ok) {
+    b = n / g.P;
+    p = (int)(n - b * g.P);
+    const int y = p / g.Wo, x = p - y * g.Wo;
+    pbase = (int)(b - b_lo) * slot_sz + (y * g.Wi + x) * g.stride;
+  }
+  v16f acc[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
+
+  // Element e of a chunk's staged images is float x of image slot s, e = s * cnt + x, where
+  // cnt = n_ic * Hi * Wi is the run of contiguous floats the chunk takes from one image; a thread
+  // walks e = tid, tid + BT, ... and keeps (s, x) by carrying instead of dividing.  Element e of
+  // the chunk's weights is Wt[ic0 * KK + e / WROW][mt0 * 32 + e % WROW], WROW a power of two.
+  struct Walk {
+    int s, x, cnt, sh;   // sh >= 0: cnt == 1 << sh
+    __device__ __forceinline__ Walk(int tid, int cnt_) : cnt(cnt_) {
+      sh = (cnt_ & (cnt_ - 1)) == 0 ? __ffs(cnt_) - 1 : -1;
+      s = sh >= 0 ? tid >> sh : tid / cnt_;
+      x = tid - s * cnt_;
+    }
+    __device__ __forceinline__ void step() {
+      x += BT;
+      if (sh >= 0) { s += x >> sh; x &= cnt - 1; }
+      else while (x >= cnt) { x -= cnt; ++s; }
+    }
+  };
+  auto in_ptr = [&](int ic0, const Walk& w, bool ok) -> cgf {
+    return g.in + (b_lo + (ok ? w.s : 0)) * g.in_stride + (long long)ic0 * HiWi + (ok ? w.x : 0);
+  };
+  auto w_val = [&](int ic0, int kc, int e) -> float {
+    const int kr = e / WROW, c = e - kr * WROW;
+    return (kr < kc) ? g.wt[((long long)ic0 * KK + kr) * g.MoPad + mt0 * 32 + c] : 0.f;
+  };
+  // straight to LDS, eight loads in flight per thread (first chunk, and every chunk without prefetch)
+  auto stage_now = [&](int ic0) {
+    const int n_ic = min(g.IC, g.Mi - ic0);
+    const int cnt = n_ic * HiWi, tot = n_img * cnt;
+    Walk w(tid, cnt);
+    for (int e0 = 0; e0 < tot; e0 += 8 * BT) {
+      float v[8];
+      int d[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool ok = e0 + u * BT + tid < tot;
+        v[u] = *in_ptr(ic0, w, ok);
+        d[u] = ok ? w.s * slot_sz + w.x : -1;
+        w.step();
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (d[u] >= 0) lds_in[d[u]] = v[u];
+    }
+    const int kc = n_ic * KK, wtot = (kc + 1) * WROW;
+    for (int e0 = 0; e0 < wtot; e0 += 8 * BT) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = w_val(ic0, kc, min(e0 + u * BT + tid, wtot - 1));
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (e0 + u * BT + tid < wtot) lds_w[e0 + u * BT + tid] = v[u];
+    }
+  };
+  float ri[PRE_IN], rw[PRE_W];
+  auto fetch = [&](int ic0) {
+    const int n_ic = min(g.IC, g.Mi - ic0);
+    const int cnt = n_ic * HiWi, tot = n_img * cnt;
+    Walk w(tid, cnt);
+#pragma unroll
+    for (int u = 0; u < PRE_IN; ++u) {
+      ri[u] = *in_ptr(ic0, w, u * BT + tid < tot);
+      w.step();
+    }
+    const int kc = n_ic * KK, wtot = (kc + 1) * WROW;
+#pragma unroll
+    for (int u = 0; u < PRE_W; ++u) rw[u] = (u * BT < wtot) ? w_val(ic0, kc, min(u * BT + tid, wtot - 1)) : 0.f;
+  };
+  auto put = [&](int ic0) {
+    const int n_ic = min(g.IC, g.Mi - ic0);
+    const int cnt = n_ic * HiWi, tot = n_img * cnt;
+    Walk w(tid, cnt);
+#pragma unroll
+    for (int u = 0; u < PRE_IN; ++u) {
+      if (u * BT + tid < tot) lds_in[w.s * slot_sz + w.x] = ri[u];
+      w.step();
+    }
+    const int wtot = (n_ic * KK + 1) * WROW;
+#pragma unroll
+    for (int u = 0; u < PRE_W; ++u)
+      if (u * BT + tid < wtot) lds_w[u * BT + tid] = rw[u];
+  };
+
+  // slice blockIdx.z of the k range: chunks [z * cps, (z + 1) * cps)
+  const int ic_first = blockIdx.z * g.chunks_per_slice * g.IC;
+  const int ic_end = min(g.Mi, ic_first + g.chunks_per_slice * g.IC);
+  for (int ic0 = ic_first; ic0 < ic_end; ic0 += g.IC) {
+    const int n_ic = min(g.IC, g.Mi - ic0);
+    const int kc = n_ic * KK;
+    if (ic0 == ic_first || !g.prefetch) stage_now(ic0);
+    else put(ic0);
+    __syncthreads();
+    if (g.prefetch && ic0 + g.IC < ic_end) fetch(ic0 + g.IC);
+    // two k per instruction (lanes 0..31 the even one, lanes 32..63 the odd one); the operands
+    // of four instructions per map tile are fetched together
+    for (int kk = 0; kk < kc; kk += 8) {
+      float a[4][MT], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int k = kk + 2 * u + lk;
+        const int kr = min(k, kc);               // row kc is the zero row
+        const int ko = koff[min(k, kc - 1)];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) a[u][m] = lds_w[kr * WROW + m * 32 + lrow];
+        bv[u] = lds_in[ko + pbase];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  if (!col_ok) return;
+  // element v of a lane: row (v / 4) * 8 + (lane / 32) * 4 + v % 4 of the tile, column lane % 32
+  gf dst = g.out + (long long)blockIdx.z * g.slice_stride + b * g.out_stride + p;
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int j = (mt0 + m) * 32 + (v >> 2) * 8 + lk * 4 + (v & 3);
+      if (j < g.Mo) {
+        float s = acc[m][v];
+        if (g.fuse) s += g.bias[j];
+        if (g.fuse == 1) s = b_act(s);
+        dst[(long long)j * g.P] = s;
+      }
+    }
+}
+
+// bias + scaled tanh + max-pooling (Sec. 2.2, 2.3) of the raw sums of a whole batch; the sums may
+// come as several planes (slices of the k range), added here in a fixed order.  The activation
+// function is increasing, so the maximum is taken first: one tanh per window.  act 0: none (the
+// output layer's sums go on to the output units).
+__global__ void __launch_bounds__(256) k_batch_pool(BatchPool q) {
+  const long long x = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (x >= q.total) return;
+  const int HpWp = q.Hp * q.Wp;
+  const long long bj = x / HpWp;
+  const int w = (int)(x - bj * HpWp);
+  const int j = (int)(bj % q.Mo);
+  const int py = w / q.Wp, px = w - py * q.Wp;
+  cgf src = q.sums + bj * ((long long)q.Ho * q.Wo) + (py * q.Kp) * q.Wo + px * q.Kp;
+  float best = -INFINITY;
+  for (int dy = 0; dy < q.Kp; ++dy)
+    for (int dx = 0; dx < q.Kp; ++dx) {
+      float v = 0.f;
+      for (int sl = 0; sl < q.n_slices; ++sl) v += src[(long long)sl * q.slice_stride + dy * q.Wo + dx];
+      best = fmaxf(best, v);
+    }
+  best += q.bias[j];
+  q.out[x] = q.act ? b_act(best) : best;
+}
+
+// Output units of a whole batch: soft-max of the output layer's sums (bias included), or the
+// scaled tanh for the variant with tanh output neurons.  One thread per image.
+__global__ void __launch_bounds__(256) k_batch_outputs(cgf logits, gf probs, long long n_images, int n_classes,
+                                                       int out_units) {
+  const long long b = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (b >= n_images) return;
+  cgf a = logits + b * n_classes;
+  gf o = probs + b * n_classes;
+  if (out_units == 1) {
+    for (int k = 0; k < n_classes; ++k) o[k] = b_act(a[k]);
+    return;
+  }
+  float mx = a[0];
+  for (int k = 1; k < n_classes; ++k) mx = fmaxf(mx, a[k]);
+  float z = 0.f;
+  for (int k = 0; k < n_classes; ++k) z += expf(a[k] - mx);
+  for (int k = 0; k < n_classes; ++k) o[k] = expf(a[k] - mx) / z;
+}
+
+// Wt[k][j] of one layer from the canonical weights: k = (input map, ky, kx), j = output map;
+// absent connections and the padding maps stay zero (the buffer is cleared first).
+__global__ void __launch_bounds__(256) k_batch_pack(BatchPack q) {
+  const long long x = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (x >= q.total) return;
+  if (q.is_fc) {  // W[n_out][n_in]
+    const int j = (int)(x / q.n_in), m = (int)(x - (long long)j * q.n_in);
+    q.wt[(long long)m * q.MoPad + j] = q.w[x];
+    return;
+  }
+  const int KK = q.K * q.K;
+  const long long slot = x / KK;
+  const int t = (int)(x - slot * KK);
+  int j, i;
+  if (q.full_table) {
+    j = (int)(slot / q.Mi);
+    i = (int)(slot - (long long)j * q.Mi);
+  } else {
+    // row j with csr_ptr[j] <= slot < csr_ptr[j + 1]
+    int lo = 0, hi = q.Mo;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (q.csr_ptr[mid] <= slot) lo = mid; else hi = mid;
+    }
+    j = lo;
+    i = q.csr_idx[slot];
+  }
+  q.wt[((long long)i * KK + t) * q.MoPad + j] = q.w[x];
+}
+
+__global__ void __launch_bounds__(256) k_batch_zero(gf p, long long n) {
+  const long long x = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (x < n) p[x] = 0.f;
+}
+
+template <int MT>
+hipError_t launch_gemm_mt(hipStream_t stream, const BatchGemm& g, size_t lds_bytes) {
+  hipError_t e = hipFuncSetAttribute((const void*)k_batch_gemm<MT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (e != hipSuccess) return e;
+  const unsigned gx = (unsigned)((g.N + BCOLS - 1) / BCOLS);
+  const unsigned gy = (unsigned)((g.MoPad / 32 + MT - 1) / MT);
+  hipLaunchKernelGGL(k_batch_gemm<MT>, dim3(gx, gy, (unsigned)g.KS), dim3(BT), lds_bytes, stream, g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t batch_gemm_lds_bytes(const BatchGemm& g) {
+  const int KC = g.IC * g.K * g.K;
+  return ((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + (size_t)(KC + 1) * g.MT * 32 + KC) * sizeof(float);
+}
+
+hipError_t launch_batch_gemm(hipStream_t stream, const BatchGemm& g) {
+  if (g.N <= 0) return hipSuccess;
+  const size_t lds_bytes = batch_gemm_lds_bytes(g);
+  switch (g.MT) {
+    case 1: return launch_gemm_mt<1>(stream, g, lds_bytes);
+    case 2: return launch_gemm_mt<2>(stream, g, lds_bytes);
+    case 4: return launch_gemm_mt<4>(stream, g, lds_bytes);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_batch_pool(hipStream_t stream, const BatchPool& q) {
+  if (q.total <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_batch_pool, dim3((unsigned)((q.total + 255) / 256)), dim3(256), 0, stream, q);
+  return hipGetLastError();
+}
+
+hipError_t launch_batch_outputs(hipStream_t stream, const float* logits, float* probs, long long n_images,
+                                int n_classes, int out_units) {
+  if (n_images <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_batch_outputs, dim3((unsigned)((n_images + 255) / 256)), dim3(256), 0, stream, (cgf)logits,
+                     (gf)probs, n_images, n_classes, out_units);
+  return hipGetLastError();
+}
+
+hipError_t launch_batch_pack(hipStream_t stream, const BatchPack& q, long long wt_floats) {
+  hipLaunchKernelGGL(k_batch_zero, dim3((unsigned)((wt_floats + 255) / 256)), dim3(256), 0, stream, q.wt, wt_floats);
+  hipLaunchKernelGGL(k_batch_pack, dim3((unsigned)((q.total + 255) / 256)), dim3(256), 0, stream, q);
+  return hipGetLastError();
+}
+
+}  // namespace cnn355

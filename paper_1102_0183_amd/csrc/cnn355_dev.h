@@ -192,4 +192,40 @@ struct FlowPtrs {
   CNN_GLOBAL tagged_t* xp;  // [2][n_col_ranks][n_out of the first FC layer] partial sums
 };
 
+// ---- batched forward pass ----------------------------------------------------------------
+// One layer over a whole batch as a matrix product on the matrix cores (cnn355_batch.hip).
+struct BatchGemm {
+  const CNN_GLOBAL float* in;    // [batch] images of [Mi][Hi][Wi], in_stride floats apart
+  const CNN_GLOBAL float* wt;    // [Mi*K*K][MoPad]: k = (input map, ky, kx) by output map, zero where unconnected
+  const CNN_GLOBAL float* bias;  // [Mo]
+  CNN_GLOBAL float* out;         // [batch][Mo][P], out_stride floats per image
+  long long in_stride, out_stride;
+  long long N;                   // columns: batch * P
+  int Mi, Hi, Wi, K, stride, Mo, MoPad, Wo, P;
+  int IC;                        // input maps staged per chunk
+  int n_img_max;                 // images the 128 columns of a workgroup can touch
+  int MT;                        // map tiles (of 32) per workgroup: 1, 2 or 4
+  int KS, chunks_per_slice;      // the k range is cut into KS slices of so many chunks, one per blockIdx.z,
+  long long slice_stride;        //   each writing its own plane of `out`, slice_stride floats apart
+  int prefetch;                  // the next chunk is fetched into registers during the arithmetic
+  int fuse;                      // 0: raw sums (pooling follows); 1: bias + scaled tanh; 2: bias only (output layer)
+};
+struct BatchPool {
+  const CNN_GLOBAL float* sums;  // [batch][Mo][Ho][Wo] raw sums
+  const CNN_GLOBAL float* bias;
+  CNN_GLOBAL float* out;         // [batch][Mo][Hp][Wp]
+  long long total;               // batch * Mo * Hp * Wp
+  long long slice_stride;        // floats between the planes of partial sums
+  int Mo, Ho, Wo, Kp, Hp, Wp, n_slices;
+  int act;                       // 1: scaled tanh, 0: none
+};
+struct BatchPack {
+  const CNN_GLOBAL float* w;     // conv: [n_conn][K*K] in table order; fc: [n_out][n_in]
+  CNN_GLOBAL float* wt;          // [Kdim][MoPad]
+  const CNN_GLOBAL int* csr_ptr;
+  const CNN_GLOBAL int* csr_idx;
+  long long total;               // weights of the layer (biases apart)
+  int is_fc, full_table, Mi, Mo, K, n_in, MoPad;
+};
+
 }  // namespace cnn355

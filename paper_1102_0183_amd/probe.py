@@ -3,6 +3,7 @@
 
     python3 paper_1102_0183_amd/probe.py --workload cfg4b --mode stages --images 200 --calls 1
     python3 paper_1102_0183_amd/probe.py --workload cfg2a --mode resident --images 1000 --calls 3 --copy-calibration
+    python3 paper_1102_0183_amd/probe.py --workload cfg2a --forward --batch 4096 --images 16384 --calls 3
 
 --copy-calibration first runs a 256 MiB device-to-device copy three times, so that a counter
 collected in the same run (FETCH_SIZE, WRITE_SIZE) can be scaled by what it reads for a
@@ -24,6 +25,8 @@ def main():
     ap.add_argument("--images", type=int, default=1000, help="images per cnn_train_many call")
     ap.add_argument("--calls", type=int, default=3)
     ap.add_argument("--forward", action="store_true", help="forward-only calls instead of training")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="with --forward: cnn_forward_batch with this many images in flight")
     ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
 
@@ -47,9 +50,14 @@ def main():
     net.set_mode({"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
                   "stages": binding.MODE_STAGES}[args.mode])
     sz = net.image_size
+    if args.batch:
+        scratch = torch.empty(net.forward_batch_scratch_bytes(args.batch), dtype=torch.uint8, device="cuda:0")
+        d_probs = torch.empty(n * net.num_classes, dtype=torch.float32, device="cuda:0")
     for r in range(args.calls):
         im = d_imgs.view(-1)[r * n * sz:(r + 1) * n * sz]
-        if args.forward:
+        if args.forward and args.batch:
+            net.forward_batch(im, n, d_probs, scratch, args.batch)
+        elif args.forward:
             net.forward_many(im, n)
         else:
             net.train_many(im, d_labs[r * n:(r + 1) * n], wl.lr, n=n)

@@ -1,0 +1,97 @@
+"""Batched forward pass (every layer one matrix product over the batch, on the matrix cores)
+against the CPU oracle, through the C ABI.  Needs a GPU (marked gpu)."""
+import numpy as np
+import pytest
+
+from paper_1102_0183_amd import binding, synth
+from tests.parity_helpers import build_pair, to_dev
+
+pytestmark = pytest.mark.gpu
+
+# (workload, images, batch, images the oracle checks)
+CASES = [
+    ("cfg1", 300, 128, 300),      # three chunks, the last one ragged; columns straddle images
+    ("cfg1", 5, 64, 5),           # fewer images than one workgroup's columns
+    ("cfg2b", 200, 200, 60),
+    ("cfg3", 70, 32, 12),
+    ("cfg4a", 70, 64, 12),
+    ("cfg4b", 40, 16, 3),
+    ("cfg5", 150, 100, 40),       # fixed front-end, skipping factor, sparse table
+]
+
+
+def _scratch(g, batch):
+    import torch
+    return torch.empty(g.forward_batch_scratch_bytes(batch), dtype=torch.uint8, device="cuda:0")
+
+
+@pytest.mark.parametrize("name,n,batch,n_check", CASES)
+def test_batched_forward_matches_the_oracle(name, n, batch, n_check):
+    import torch
+    wl = synth.WORKLOADS[name]
+    print("case", name, "images", n, "batch", batch, flush=True)
+    g, o = build_pair(wl)
+    imgs = synth.images(wl, n)
+    d_imgs = to_dev(imgs)
+    d_probs = torch.full((n * g.num_classes,), -1.0, dtype=torch.float32, device="cuda:0")
+    g.forward_batch(d_imgs, n, d_probs, _scratch(g, batch), batch)
+    g.synchronize()
+    got = d_probs.cpu().numpy().reshape(n, -1)
+    assert np.all(got >= 0) and np.abs(got.sum(axis=1) - 1.0).max() <= 1e-5
+    # the oracle on a sample spread over the chunks (first, last, around the chunk borders)
+    idx = sorted(set(np.linspace(0, n - 1, n_check).astype(int).tolist() +
+                     [i for i in (batch - 1, batch, n - 1) if 0 <= i < n]))
+    want = np.stack([o.forward(imgs[i]) for i in idx])
+    e = np.abs(got[idx] - want).max() / np.abs(want).max()
+    print("  probabilities, %d images checked by the oracle: rel err %.2e" % (len(idx), e), flush=True)
+    assert e <= 1e-5
+    # and every image against the one-image path of the same library
+    d_seq = torch.empty_like(d_probs)
+    g.forward_many(d_imgs, n, d_seq)
+    g.synchronize()
+    seq = d_seq.cpu().numpy().reshape(n, -1)
+    assert np.abs(got - seq).max() <= 1e-5
+    g.close()
+
+
+def test_batched_forward_sees_trained_weights_and_the_tanh_outputs():
+    """The call reads the weights as they stand: after training in resident mode (weights live in
+    LDS during a call and are written back at its end) it must see the trained values; with
+    scaled-tanh output units it returns the outputs."""
+    import torch
+    wl = synth.WORKLOADS["cfg1"]
+    g, o = build_pair(wl)
+    g.set_mode(binding.MODE_RESIDENT)
+    g.set_output_units(binding.OUTPUT_TANH_SQERR)
+    o.set_output_units(1)
+    n = 40
+    imgs, labs = synth.images(wl, n), synth.labels(wl, n)
+    d_imgs, d_labs = to_dev(imgs), to_dev(labs)
+    g.train_many(d_imgs, d_labs, wl.lr)
+    d_out = torch.empty(n * g.num_classes, dtype=torch.float32, device="cuda:0")
+    g.forward_batch(d_imgs, n, d_out, _scratch(g, 16), 16)
+    g.synchronize()
+    o.set_weights(g.get_weights().astype(np.float64))
+    want = o.forward_many(imgs, n)
+    got = d_out.cpu().numpy().reshape(n, -1)
+    assert np.abs(got - want).max() / np.abs(want).max() <= 1e-5
+    assert np.abs(want.sum(axis=1) - 1.0).max() > 1e-3
+    g.close()
+
+
+def test_batched_forward_argument_errors():
+    import torch
+    wl = synth.WORKLOADS["cfg1"]
+    g, _ = build_pair(wl)
+    d_imgs = to_dev(synth.images(wl, 4))
+    d_probs = torch.empty(4 * g.num_classes, dtype=torch.float32, device="cuda:0")
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(binding.CnnError) as e:
+        g.forward_batch(d_imgs, 4, d_probs, small, 4)
+    assert e.value.code == binding.E_WORKSPACE
+    with pytest.raises(binding.CnnError) as e:
+        g.forward_batch(d_imgs, 4, d_probs, _scratch(g, 4), 0)
+    assert e.value.code == binding.E_ARG
+    g.forward_batch(d_imgs, 0, d_probs[:0], _scratch(g, 4), 4)  # no images: nothing to do
+    g.synchronize()
+    g.close()
