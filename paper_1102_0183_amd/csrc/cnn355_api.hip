@@ -893,20 +893,32 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
       if (!best_pad || pad < best_pad) { best_pad = pad; g.MT = mt; }
     }
     g.MoPad = best_pad;
-    g.n_img_max = (int)std::min<size_t>(std::max<size_t>(batch, 1), (size_t)((128 - 1 + g.P - 1) / g.P + 1));
     const int KK = g.K * g.K, HiWi = g.Hi * g.Wi;
     // input maps per chunk: as many as the LDS budget takes; when that leaves several chunks,
     // prefer a chunk that also fits the prefetch registers (16 + 48 floats per thread), unless
     // such a chunk would be too short to hide anything behind.  One-pixel maps (fully connected
     // layers) take a power of two, so that staging finds image and offset by shifting.
     int ic = 0, ic_pre = 0;
-    for (int c = 1; c <= g.Mi; ++c) {
-      const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * 32;
-      if (in_f + w_f + (size_t)c * KK > LDS_FLOATS) break;
-      if (HiWi == 1 && c < g.Mi && (c & (c - 1)) != 0) continue;
-      ic = c;
-      if (in_f <= 16 * 256 && w_f <= 48 * 256) ic_pre = c;
+    auto fit = [&](int cols_per_image) {
+      g.n_img_max = (int)std::min<size_t>(std::max<size_t>(batch, 1), (size_t)((128 - 1 + cols_per_image - 1) / cols_per_image + 1));
+      ic = 0; ic_pre = 0;
+      for (int c = 1; c <= g.Mi; ++c) {
+        const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * 32;
+        if (in_f + 3 + w_f + (size_t)c * KK > LDS_FLOATS) break;
+        if (HiWi == 1 && c < g.Mi && (c & (c - 1)) != 0) continue;
+        ic = c;
+        if (in_f <= 16 * 256 && w_f <= 48 * 256) ic_pre = c;
+      }
+    };
+    // Pooling inside the product: when the whole k range is one chunk, a column is a pooled pixel
+    // and the wavefront walks the Kp x Kp members of its window one after the other, keeping the
+    // running maximum in registers; the full-resolution sums then never reach memory.
+    g.Kp = 1;
+    if (Kp > 1) {
+      fit(Hp * Wp);
+      if (ic == g.Mi) { g.Kp = Kp; g.P = Hp * Wp; g.Wo = Wp; }
     }
+    if (g.Kp == 1) fit(g.P);
     if (ic == 0)
       return fail(&net->err, CNN_E_SHAPE, "batched forward pass: one input map of a layer (times the images a "
                                           "workgroup touches) exceeds the LDS budget");
@@ -922,7 +934,7 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     g.chunks_per_slice = (n_chunks + ks - 1) / ks;
     g.KS = (n_chunks + g.chunks_per_slice - 1) / g.chunks_per_slice;
     g.slice_stride = (long long)(batch * g.Mo * g.P);
-    g.fuse = (Kp > 1 || g.KS > 1) ? 0 : (L.is_output ? 2 : 1);
+    g.fuse = ((Kp > 1 && g.Kp == 1) || g.KS > 1) ? 0 : (L.is_output ? 2 : 1);
     g.bias = L.bias;
     g.in_stride = (long long)g.Mi * HiWi;
     g.out_stride = (long long)g.Mo * g.P;
@@ -943,10 +955,11 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     }
     BatchPool& q = st.pool;
     std::memset(&q, 0, sizeof(q));
-    q.bias = L.bias; q.Mo = g.Mo; q.Ho = Ho; q.Wo = g.Wo; q.Kp = Kp; q.Hp = Hp; q.Wp = Wp;
+    q.bias = L.bias; q.Mo = g.Mo; q.Ho = Ho; q.Wo = (L.kind == L_CONV) ? L.Wo : 1; q.Kp = Kp; q.Hp = Hp; q.Wp = Wp;
     q.n_slices = g.KS; q.slice_stride = g.slice_stride; q.act = L.is_output ? 0 : 1;
     st.out_per_image = (Kp > 1) ? (size_t)g.Mo * Hp * Wp : (size_t)g.Mo * g.P;
     if (g.fuse == 0) B.sums_per_image = std::max(B.sums_per_image, up64((size_t)g.KS * g.Mo * g.P));
+    // (g.P is Ho * Wo whenever fuse == 0 with pooling: pooling inside the product always has fuse != 0)
     B.act_per_image = std::max(B.act_per_image, up64(st.out_per_image));
     B.steps.push_back(st);
   }
@@ -1372,6 +1385,9 @@ int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_prob
   BatchPlan B;
   int rc = batch_plan(net, batch, B);
   if (rc) return rc;
+  for (const BatchStep& st : B.steps)
+    if ((unsigned long long)batch * (unsigned long long)st.g.P >= (1ull << 31) - 256)
+      return fail(&net->err, CNN_E_ARG, "batch too large: batch x output pixels of a layer must stay below 2^31");
   if (scratch_bytes < B.floats(batch) * sizeof(float))
     return fail(&net->err, CNN_E_WORKSPACE, "scratch smaller than cnn_forward_batch_scratch_bytes says");
   const ProgramDev& P = net->prog;

@@ -19,13 +19,19 @@ namespace cnn355 {
 typedef const CNN_GLOBAL float* cgf;
 typedef CNN_GLOBAL float* gf;
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 namespace {
 
 constexpr int BT = 256;        // threads of a GEMM workgroup: four wavefronts, 32 columns each
 constexpr int BCOLS = 128;     // columns (image, pixel) of a workgroup
 
-__device__ __forceinline__ float b_act(float a) { return 1.7159f * tanhf(0.6666f * a); }
+// scaled tanh 1.7159 tanh(0.6666 a) (Sec. 4) as A (1 - 2 / (e^{2 B a} + 1)) on the hardware
+// exponential and reciprocal: absolute error about 1e-7
+__device__ __forceinline__ float b_act(float a) {
+  const float z = __builtin_amdgcn_exp2f((2.0f * 0.6666f * 1.44269504088896340736f) * a);
+  return 1.7159f - (2.0f * 1.7159f) * __builtin_amdgcn_rcpf(z + 1.0f);
+}
 
 constexpr int PRE_IN = 16;     // floats per thread a prefetched chunk may hold: staged images ...
 constexpr int PRE_W = 48;      // ... and rows of Wt
@@ -47,35 +53,36 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   const int KC = g.IC * KK;                        // k per full chunk
   constexpr int WROW = MT * 32;
   float* lds_in = lds;                              // [n_img_max][IC][Hi*Wi]
-  float* lds_w = lds + g.n_img_max * slot_sz;       // [KC + 1][MT * 32]; the row behind the last is zero
+  float* lds_w = lds + ((g.n_img_max * slot_sz + 3) & ~3);  // [KC + 1][MT * 32]; the row behind the last is zero
   int* koff = (int*)(lds_w + (KC + 1) * WROW);      // [KC]
 
-  const long long n0 = (long long)blockIdx.x * BCOLS;
+  // (columns are counted in 32 bits: the host keeps batch * P below 2^31)
+  const int N = (int)g.N;
+  const int n0 = blockIdx.x * BCOLS;
   const int mt0 = blockIdx.y * MT;
-  const long long b_lo = n0 / g.P;
-  const long long n_last = min(n0 + BCOLS, g.N) - 1;
-  const int n_img = (int)(n_last / g.P - b_lo) + 1;
+  const int b_lo = n0 / g.P;
+  const int n_last = min(n0 + BCOLS, N) - 1;
+  const int n_img = n_last / g.P - b_lo + 1;
 
   for (int x = tid; x < KC; x += BT) {
     const int c = x / KK, t = x - c * KK;
     const int ky = t / g.K, kx = t - ky * g.K;
     koff[x] = c * HiWi + ky * g.Wi + kx;
   }
-  const long long n = n0 + wave * 32 + lrow;
-  const bool col_ok = n < g.N;
-  long long b = 0;
-  int p = 0, pbase = 0;
+  const int n = n0 + wave * 32 + lrow;
+  const bool col_ok = n < N;
+  int b = 0, p = 0, pbase = 0;
   if (col_ok) {
     b = n / g.P;
-    p = (int)(n - b * g.P);
+    p = n - b * g.P;
     const int y = p / g.Wo, x = p - y * g.Wo;
-    pbase = (int)(b - b_lo) * slot_sz + (y * g.Wi + x) * g.stride;
+    pbase = (b - b_lo) * slot_sz + (y * g.Wi + x) * (g.Kp * g.stride);
   }
-  v16f acc[MT];
+  v16f acc[MT], best[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
+    for (int v = 0; v < 16; ++v) { acc[m][v] = 0.f; best[m][v] = -INFINITY; }
 
   // Element e of a chunk's staged images is float x of image slot s, e = s * cnt + x, where
   // cnt = n_ic * Hi * Wi is the run of contiguous floats the chunk takes from one image; a thread
@@ -95,11 +102,13 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     }
   };
   auto in_ptr = [&](int ic0, const Walk& w, bool ok) -> cgf {
-    return g.in + (b_lo + (ok ? w.s : 0)) * g.in_stride + (long long)ic0 * HiWi + (ok ? w.x : 0);
+    return g.in + (long long)(b_lo + (ok ? w.s : 0)) * g.in_stride + (long long)ic0 * HiWi + (ok ? w.x : 0);
   };
-  auto w_val = [&](int ic0, int kc, int e) -> float {
-    const int kr = e / WROW, c = e - kr * WROW;
-    return (kr < kc) ? g.wt[((long long)ic0 * KK + kr) * g.MoPad + mt0 * 32 + c] : 0.f;
+  // four weights at a time: rows of Wt and of the staged copy start on 128-byte boundaries
+  auto w_val = [&](int ic0, int kc, int e4) -> v4f {
+    const int kr = e4 / (WROW / 4), c = (e4 - kr * (WROW / 4)) * 4;
+    if (kr >= kc) return v4f{0.f, 0.f, 0.f, 0.f};
+    return *(const CNN_GLOBAL v4f*)(g.wt + ((long long)ic0 * KK + kr) * g.MoPad + mt0 * 32 + c);
   };
   // straight to LDS, eight loads in flight per thread (first chunk, and every chunk without prefetch)
   auto stage_now = [&](int ic0) {
@@ -120,17 +129,18 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
       for (int u = 0; u < 8; ++u)
         if (d[u] >= 0) lds_in[d[u]] = v[u];
     }
-    const int kc = n_ic * KK, wtot = (kc + 1) * WROW;
-    for (int e0 = 0; e0 < wtot; e0 += 8 * BT) {
-      float v[8];
+    const int kc = n_ic * KK, wtot = (kc + 1) * (WROW / 4);
+    for (int e0 = 0; e0 < wtot; e0 += 4 * BT) {
+      v4f v[4];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = w_val(ic0, kc, min(e0 + u * BT + tid, wtot - 1));
+      for (int u = 0; u < 4; ++u) v[u] = w_val(ic0, kc, min(e0 + u * BT + tid, wtot - 1));
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (e0 + u * BT + tid < wtot) lds_w[e0 + u * BT + tid] = v[u];
+      for (int u = 0; u < 4; ++u)
+        if (e0 + u * BT + tid < wtot) ((v4f*)lds_w)[e0 + u * BT + tid] = v[u];
     }
   };
-  float ri[PRE_IN], rw[PRE_W];
+  float ri[PRE_IN];
+  v4f rw[PRE_W / 4];
   auto fetch = [&](int ic0) {
     const int n_ic = min(g.IC, g.Mi - ic0);
     const int cnt = n_ic * HiWi, tot = n_img * cnt;
@@ -140,9 +150,10 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
       ri[u] = *in_ptr(ic0, w, u * BT + tid < tot);
       w.step();
     }
-    const int kc = n_ic * KK, wtot = (kc + 1) * WROW;
+    const int kc = n_ic * KK, wtot = (kc + 1) * (WROW / 4);
 #pragma unroll
-    for (int u = 0; u < PRE_W; ++u) rw[u] = (u * BT < wtot) ? w_val(ic0, kc, min(u * BT + tid, wtot - 1)) : 0.f;
+    for (int u = 0; u < PRE_W / 4; ++u)
+      rw[u] = (u * BT < wtot) ? w_val(ic0, kc, min(u * BT + tid, wtot - 1)) : v4f{0.f, 0.f, 0.f, 0.f};
   };
   auto put = [&](int ic0) {
     const int n_ic = min(g.IC, g.Mi - ic0);
@@ -153,10 +164,10 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
       if (u * BT + tid < tot) lds_in[w.s * slot_sz + w.x] = ri[u];
       w.step();
     }
-    const int wtot = (n_ic * KK + 1) * WROW;
+    const int wtot = (n_ic * KK + 1) * (WROW / 4);
 #pragma unroll
-    for (int u = 0; u < PRE_W; ++u)
-      if (u * BT + tid < wtot) lds_w[u * BT + tid] = rw[u];
+    for (int u = 0; u < PRE_W / 4; ++u)
+      if (u * BT + tid < wtot) ((v4f*)lds_w)[u * BT + tid] = rw[u];
   };
 
   // slice blockIdx.z of the k range: chunks [z * cps, (z + 1) * cps)
@@ -169,36 +180,52 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     else put(ic0);
     __syncthreads();
     if (g.prefetch && ic0 + g.IC < ic_end) fetch(ic0 + g.IC);
-    // two k per instruction (lanes 0..31 the even one, lanes 32..63 the odd one); the operands
-    // of four instructions per map tile are fetched together
-    for (int kk = 0; kk < kc; kk += 8) {
-      float a[4][MT], bv[4];
+    // Members of the pooling window, one after the other (one member, the pixel itself, without
+    // pooling; with it the host has made the k range a single chunk, so a member's sums are
+    // complete when its loop ends).
+    for (int d = 0; d < g.Kp * g.Kp; ++d) {
+      const int dy = d / g.Kp, dx = d - dy * g.Kp;
+      const int pb = pbase + (dy * g.Wi + dx) * g.stride;
+      // two k per instruction (lanes 0..31 the even one, lanes 32..63 the odd one); the operands
+      // of four instructions per map tile are fetched together
+      for (int kk = 0; kk < kc; kk += 8) {
+        float a[4][MT], bv[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int k = kk + 2 * u + lk;
-        const int kr = min(k, kc);               // row kc is the zero row
-        const int ko = koff[min(k, kc - 1)];
+        for (int u = 0; u < 4; ++u) {
+          const int k = kk + 2 * u + lk;
+          const int kr = min(k, kc);               // row kc is the zero row
+          const int ko = koff[min(k, kc - 1)];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) a[u][m] = lds_w[kr * WROW + m * 32 + lrow];
-        bv[u] = lds_in[ko + pbase];
+          for (int m = 0; m < MT; ++m) a[u][m] = lds_w[kr * WROW + m * 32 + lrow];
+          bv[u] = lds_in[ko + pb];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
       }
+      if (g.Kp > 1) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+        for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
+          for (int v = 0; v < 16; ++v) {
+            best[m][v] = fmaxf(best[m][v], acc[m][v]);
+            acc[m][v] = 0.f;
+          }
+      }
     }
     __syncthreads();
   }
   if (!col_ok) return;
   // element v of a lane: row (v / 4) * 8 + (lane / 32) * 4 + v % 4 of the tile, column lane % 32
-  gf dst = g.out + (long long)blockIdx.z * g.slice_stride + b * g.out_stride + p;
+  gf dst = g.out + (long long)blockIdx.z * g.slice_stride + (long long)b * g.out_stride + p;
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int j = (mt0 + m) * 32 + (v >> 2) * 8 + lk * 4 + (v & 3);
       if (j < g.Mo) {
-        float s = acc[m][v];
+        float s = (g.Kp > 1) ? best[m][v] : acc[m][v];
         if (g.fuse) s += g.bias[j];
         if (g.fuse == 1) s = b_act(s);
         dst[(long long)j * g.P] = s;
@@ -298,7 +325,7 @@ hipError_t launch_gemm_mt(hipStream_t stream, const BatchGemm& g, size_t lds_byt
 
 size_t batch_gemm_lds_bytes(const BatchGemm& g) {
   const int KC = g.IC * g.K * g.K;
-  return ((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + (size_t)(KC + 1) * g.MT * 32 + KC) * sizeof(float);
+  return ((((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + 3) & ~(size_t)3) + (size_t)(KC + 1) * g.MT * 32 + KC) * sizeof(float);
 }
 
 hipError_t launch_batch_gemm(hipStream_t stream, const BatchGemm& g) {

@@ -198,10 +198,11 @@ struct BatchGemm {
   const CNN_GLOBAL float* in;    // [batch] images of [Mi][Hi][Wi], in_stride floats apart
   const CNN_GLOBAL float* wt;    // [Mi*K*K][MoPad]: k = (input map, ky, kx) by output map, zero where unconnected
   const CNN_GLOBAL float* bias;  // [Mo]
-  CNN_GLOBAL float* out;         // [batch][Mo][P], out_stride floats per image
+  CNN_GLOBAL float* out;         // [batch][Mo][P], out_stride floats per image (P: see below)
   long long in_stride, out_stride;
   long long N;                   // columns: batch * P
-  int Mi, Hi, Wi, K, stride, Mo, MoPad, Wo, P;
+  int Mi, Hi, Wi, K, stride, Mo, MoPad, Wo, P;  // Wo, P: width and size of the column grid of one image
+  int Kp;                        // > 1: a column is a pooled pixel, its Kp x Kp window is maximised inside the product
   int IC;                        // input maps staged per chunk
   int n_img_max;                 // images the 128 columns of a workgroup can touch
   int MT;                        // map tiles (of 32) per workgroup: 1, 2 or 4
