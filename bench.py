@@ -27,6 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
 KERNEL_OF_MODE = {"resident": "k_resident", "persistent": "k_persistent", "stages": "per-stage kernels (sum)"}
 
@@ -44,6 +45,18 @@ def measured_traffic(mode, batch):
     except (OSError, ValueError, IndexError):
         pass
     return None
+
+
+def forward_flops_per_image(info):
+    """2 x multiply-accumulates of one forward pass, full connection tables (Sec. 2.2, 2.4)."""
+    f = 0
+    for l in range(1, len(info)):
+        a, p = info[l], info[l - 1]
+        if a["kind"] == 1:
+            f += 2 * a["maps"] * a["h"] * a["w"] * p["maps"] * a["K"] ** 2
+        elif a["kind"] == 3:
+            f += 2 * a["maps"] * p["maps"] * p["h"] * p["w"]
+    return f
 
 
 def algorithmic_bytes_per_train_image(info, n_weights, image_floats):
@@ -219,6 +232,31 @@ def main():
         net.synchronize()
         extra["cfg2b_forward_only_images_per_s"] = round(k_steps * B / wall, 1)
         net.close()
+        # validation / test passes: the whole stream through the batched forward pass (every layer one
+        # matrix product over 4096 images on the matrix cores); timed with events around each call
+        for key, w_, inf in (("cfg2a", wl, info), ("cfg2b", wlb, infob)):
+            net = make_net(w_, args.grid)
+            fbatch = 4096
+            scratch = torch.empty(net.forward_batch_scratch_bytes(fbatch), dtype=torch.uint8, device="cuda:0")
+            d_probs = torch.empty(n_stream * net.num_classes, dtype=torch.float32, device="cuda:0")
+            net.forward_batch(d_imgs, n_stream, d_probs, scratch, fbatch)
+            net.synchronize()
+            best = None
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                net.forward_batch(d_imgs, n_stream, d_probs, scratch, fbatch)
+                e1.record()
+                e1.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None else min(best, ms)
+            assert torch.isfinite(d_probs).all()
+            tf = forward_flops_per_image(inf) * n_stream / (best * 1e-3) / 1e12
+            extra[key + "_forward_batch_images_per_s"] = round(n_stream / (best * 1e-3), 1)
+            extra[key + "_forward_batch_tflops"] = round(tf, 2)
+            extra[key + "_forward_batch_fp32_mfma_frac"] = round(tf / FP32_MFMA_PEAK_TFLOPS, 4)
+            del scratch, d_probs
+            net.close()
         # launch cost: the same images through one cnn_train_step call each
         net = make_net(wl, args.grid)
         sz = net.image_size

@@ -872,7 +872,7 @@ size_t up64(size_t x) { return (x + 63) / 64 * 64; }
 // Shape of every layer's matrix product, tile choice and LDS budget.  Returns 0 or an error code.
 int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
   const ProgramDev& P = net->prog;
-  constexpr size_t LDS_FLOATS = 16384;  // 64 KB per workgroup: two workgroups per compute unit
+  constexpr size_t LDS_FLOATS = 20000;  // 78 KB per workgroup: two workgroups per compute unit
   B = BatchPlan();
   for (int l = 0; l < P.n_layers; ++l) {
     const LayerDev& L = P.layers[l];
@@ -904,7 +904,7 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
       ic = 0; ic_pre = 0;
       for (int c = 1; c <= g.Mi; ++c) {
         const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * 32;
-        if (in_f + 3 + w_f + (size_t)c * KK > LDS_FLOATS) break;
+        if (in_f + 3 + w_f + (size_t)c * KK + 9 > LDS_FLOATS) break;
         if (HiWi == 1 && c < g.Mi && (c & (c - 1)) != 0) continue;
         ic = c;
         if (in_f <= 16 * 256 && w_f <= 48 * 256) ic_pre = c;
@@ -1385,9 +1385,15 @@ int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_prob
   BatchPlan B;
   int rc = batch_plan(net, batch, B);
   if (rc) return rc;
-  for (const BatchStep& st : B.steps)
-    if ((unsigned long long)batch * (unsigned long long)st.g.P >= (1ull << 31) - 256)
-      return fail(&net->err, CNN_E_ARG, "batch too large: batch x output pixels of a layer must stay below 2^31");
+  for (const BatchStep& st : B.steps) {
+    const unsigned long long lim = (1ull << 31) - 256;
+    const unsigned long long b = batch;
+    if (b * (unsigned long long)st.g.P >= lim || b * (unsigned long long)st.g.out_stride >= lim ||
+        b * (unsigned long long)st.g.in_stride >= lim || (unsigned long long)st.wt_floats >= lim)
+      return fail(&net->err, CNN_E_ARG, "batch too large: the layer inputs and outputs of one batch must stay below 2^31 floats each");
+  }
+  if (net->prog.has_frontend && (unsigned long long)batch * net->image_size >= (1ull << 31) - 256)
+    return fail(&net->err, CNN_E_ARG, "batch too large: the images of one batch must stay below 2^31 floats");
   if (scratch_bytes < B.floats(batch) * sizeof(float))
     return fail(&net->err, CNN_E_WORKSPACE, "scratch smaller than cnn_forward_batch_scratch_bytes says");
   const ProgramDev& P = net->prog;

@@ -54,7 +54,10 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   constexpr int WROW = MT * 32;
   float* lds_in = lds;                              // [n_img_max][IC][Hi*Wi]
   float* lds_w = lds + ((g.n_img_max * slot_sz + 3) & ~3);  // [KC + 1][MT * 32]; the row behind the last is zero
-  int* koff = (int*)(lds_w + (KC + 1) * WROW);      // [KC]
+  // byte offset of k inside a staged image, even k and odd k apart so that a lane (which takes the
+  // k of its own parity) finds the four it needs next to each other: [2][KH], KH a multiple of 4
+  const int KH = (((KC + 1) >> 1) + 3) & ~3;
+  int* koff = (int*)(lds_w + (KC + 1) * WROW);
 
   // (columns are counted in 32 bits: the host keeps batch * P below 2^31)
   const int N = (int)g.N;
@@ -64,10 +67,12 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   const int n_last = min(n0 + BCOLS, N) - 1;
   const int n_img = n_last / g.P - b_lo + 1;
 
-  for (int x = tid; x < KC; x += BT) {
-    const int c = x / KK, t = x - c * KK;
+  for (int x = tid; x < 2 * KH; x += BT) {
+    const int par = x >= KH, h = x - par * KH;
+    const int k = min(2 * h + par, KC - 1);
+    const int c = k / KK, t = k - c * KK;
     const int ky = t / g.K, kx = t - ky * g.K;
-    koff[x] = c * HiWi + ky * g.Wi + kx;
+    koff[x] = (c * HiWi + ky * g.Wi + kx) * 4;
   }
   const int n = n0 + wave * 32 + lrow;
   const bool col_ok = n < N;
@@ -101,14 +106,18 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
       else while (x >= cnt) { x -= cnt; ++s; }
     }
   };
+  // addresses as a uniform base plus a 32-bit offset per lane (the host keeps every array the
+  // kernel indexes this way below 2^31 floats)
+  const cgf in0 = g.in + (long long)b_lo * g.in_stride;
+  const unsigned in_stride32 = (unsigned)g.in_stride;
   auto in_ptr = [&](int ic0, const Walk& w, bool ok) -> cgf {
-    return g.in + (long long)(b_lo + (ok ? w.s : 0)) * g.in_stride + (long long)ic0 * HiWi + (ok ? w.x : 0);
+    return in0 + ic0 * HiWi + (ok ? (unsigned)w.s * in_stride32 + (unsigned)w.x : 0u);
   };
   // four weights at a time: rows of Wt and of the staged copy start on 128-byte boundaries
   auto w_val = [&](int ic0, int kc, int e4) -> v4f {
     const int kr = e4 / (WROW / 4), c = (e4 - kr * (WROW / 4)) * 4;
     if (kr >= kc) return v4f{0.f, 0.f, 0.f, 0.f};
-    return *(const CNN_GLOBAL v4f*)(g.wt + ((long long)ic0 * KK + kr) * g.MoPad + mt0 * 32 + c);
+    return *(const CNN_GLOBAL v4f*)(g.wt + ((long long)ic0 * KK * g.MoPad + mt0 * 32) + (unsigned)(kr * g.MoPad + c));
   };
   // straight to LDS, eight loads in flight per thread (first chunk, and every chunk without prefetch)
   auto stage_now = [&](int ic0) {
@@ -187,17 +196,37 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
       const int dy = d / g.Kp, dx = d - dy * g.Kp;
       const int pb = pbase + (dy * g.Wi + dx) * g.stride;
       // two k per instruction (lanes 0..31 the even one, lanes 32..63 the odd one); the operands
-      // of four instructions per map tile are fetched together
-      for (int kk = 0; kk < kc; kk += 8) {
+      // of four instructions per map tile are fetched together.  Whole groups of eight k first,
+      // without any clamping; then the tail, where k beyond the chunk meets the zero row of Wt.
+      const char* in_b = (const char*)lds_in + pb * 4;
+      const int kc8 = kc & ~7;
+      for (int kk = 0; kk < kc8; kk += 8) {
+        const int4 ko = *(const int4*)(koff + lk * KH + (kk >> 1));
+        const float* wr = lds_w + (kk + lk) * WROW + lrow;
+        float a[4][MT], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int m = 0; m < MT; ++m) a[u][m] = wr[2 * u * WROW + m * 32];
+        bv[0] = *(const float*)(in_b + ko.x);
+        bv[1] = *(const float*)(in_b + ko.y);
+        bv[2] = *(const float*)(in_b + ko.z);
+        bv[3] = *(const float*)(in_b + ko.w);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
+      }
+      if (kc8 < kc) {
         float a[4][MT], bv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int k = kk + 2 * u + lk;
+          const int k = kc8 + 2 * u + lk;
           const int kr = min(k, kc);               // row kc is the zero row
-          const int ko = koff[min(k, kc - 1)];
+          const int ko = koff[lk * KH + min(k >> 1, KH - 1)];
 #pragma unroll
           for (int m = 0; m < MT; ++m) a[u][m] = lds_w[kr * WROW + m * 32 + lrow];
-          bv[u] = lds_in[ko + pb];
+          bv[u] = *(const float*)(in_b + ko);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -218,7 +247,8 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   }
   if (!col_ok) return;
   // element v of a lane: row (v / 4) * 8 + (lane / 32) * 4 + v % 4 of the tile, column lane % 32
-  gf dst = g.out + (long long)blockIdx.z * g.slice_stride + (long long)b * g.out_stride + p;
+  gf dst = g.out + (long long)blockIdx.z * g.slice_stride;
+  const unsigned o0 = (unsigned)b * (unsigned)g.out_stride + (unsigned)p;
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -228,7 +258,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
         float s = (g.Kp > 1) ? best[m][v] : acc[m][v];
         if (g.fuse) s += g.bias[j];
         if (g.fuse == 1) s = b_act(s);
-        dst[(long long)j * g.P] = s;
+        dst[o0 + (unsigned)j * (unsigned)g.P] = s;
       }
     }
 }
@@ -325,7 +355,8 @@ hipError_t launch_gemm_mt(hipStream_t stream, const BatchGemm& g, size_t lds_byt
 
 size_t batch_gemm_lds_bytes(const BatchGemm& g) {
   const int KC = g.IC * g.K * g.K;
-  return ((((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + 3) & ~(size_t)3) + (size_t)(KC + 1) * g.MT * 32 + KC) * sizeof(float);
+  const size_t KH = ((((size_t)KC + 1) >> 1) + 3) & ~(size_t)3;
+  return ((((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + 3) & ~(size_t)3) + (size_t)(KC + 1) * g.MT * 32 + 2 * KH) * sizeof(float);
 }
 
 hipError_t launch_batch_gemm(hipStream_t stream, const BatchGemm& g) {
