@@ -160,7 +160,7 @@ int cnn_set_weights(cnn_t* net, const float* host_src, size_t n);
  *     they stand when the call reaches them on the stream.  Asynchronous.
  * Errors: CNN_E_ARG (NULL, batch 0, misaligned scratch), CNN_E_WORKSPACE (scratch too small),
  * CNN_E_SHAPE (a single input map of some layer, times the images one workgroup touches, exceeds
- * the LDS budget of 64 KB), CNN_E_HIP. */
+ * 148 KB of LDS: maps beyond about 135 x 135), CNN_E_HIP. */
 int cnn_forward_batch_scratch_bytes(cnn_t* net, size_t batch, size_t* bytes);
 int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
                       size_t scratch_bytes, size_t batch);

@@ -872,7 +872,8 @@ size_t up64(size_t x) { return (x + 63) / 64 * 64; }
 // Shape of every layer's matrix product, tile choice and LDS budget.  Returns 0 or an error code.
 int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
   const ProgramDev& P = net->prog;
-  constexpr size_t LDS_FLOATS = 20000;  // 78 KB per workgroup: two workgroups per compute unit
+  constexpr size_t LDS_FLOATS = 20000;      // 78 KB per workgroup: two workgroups per compute unit
+  constexpr size_t LDS_FLOATS_BIG = 38000;  // large input maps: one workgroup per compute unit
   B = BatchPlan();
   for (int l = 0; l < P.n_layers; ++l) {
     const LayerDev& L = P.layers[l];
@@ -899,12 +900,12 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     // such a chunk would be too short to hide anything behind.  One-pixel maps (fully connected
     // layers) take a power of two, so that staging finds image and offset by shifting.
     int ic = 0, ic_pre = 0;
-    auto fit = [&](int cols_per_image) {
+    auto fit = [&](int cols_per_image, size_t budget) {
       g.n_img_max = (int)std::min<size_t>(std::max<size_t>(batch, 1), (size_t)((128 - 1 + cols_per_image - 1) / cols_per_image + 1));
       ic = 0; ic_pre = 0;
       for (int c = 1; c <= g.Mi; ++c) {
         const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * 32;
-        if (in_f + 3 + w_f + (size_t)c * KK + 9 > LDS_FLOATS) break;
+        if (in_f + 3 + w_f + (size_t)c * KK + 9 > budget) break;
         if (HiWi == 1 && c < g.Mi && (c & (c - 1)) != 0) continue;
         ic = c;
         if (in_f <= 16 * 256 && w_f <= 48 * 256) ic_pre = c;
@@ -915,10 +916,13 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     // running maximum in registers; the full-resolution sums then never reach memory.
     g.Kp = 1;
     if (Kp > 1) {
-      fit(Hp * Wp);
+      fit(Hp * Wp, LDS_FLOATS);
       if (ic == g.Mi) { g.Kp = Kp; g.P = Hp * Wp; g.Wo = Wp; }
     }
-    if (g.Kp == 1) fit(g.P);
+    if (g.Kp == 1) {
+      fit(g.P, LDS_FLOATS);
+      if (ic == 0) fit(g.P, LDS_FLOATS_BIG);
+    }
     if (ic == 0)
       return fail(&net->err, CNN_E_SHAPE, "batched forward pass: one input map of a layer (times the images a "
                                           "workgroup touches) exceeds the LDS budget");
