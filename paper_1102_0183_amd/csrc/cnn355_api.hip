@@ -157,6 +157,12 @@ bool mfma_shape_ok(int Mi, int K, int Mo, int Ho, int Wo) {
   const long long Kd = (long long)Mi * K * K, P = (long long)Ho * Wo;
   return Mo >= 64 && Kd >= 256 && P >= 16 && P <= MAX_TILE_PIX && (P + 31) / 32 <= (WG / 64) * 4;
 }
+// The same for the delta pull through such a layer, which is FP's mirror image when the skipping
+// factor is 0: rows = input maps, contraction over (output map, tap), columns = input pixels.
+bool mfma_bwd_shape_ok(int Mi, int K, int S, int Mo, int Hi, int Wi) {
+  const long long Kd = (long long)Mo * K * K, P = (long long)Hi * Wi;
+  return S == 0 && Mi >= 32 && Kd >= 256 && P >= 16 && P <= MAX_TILE_PIX && (P + 31) / 32 <= (WG / 64) * 4;
+}
 int ceil_log2(int v) {
   int l = 0;
   while ((1 << l) < v) ++l;
@@ -269,8 +275,12 @@ size_t carve(cnn* net, void* base) {
   {
     size_t mm = 0;
     for (size_t l = 1; l < A.size(); ++l)
-      if (A[l].kind == CNN_LAYER_CONV && mfma_shape_ok(A[l - 1].maps, A[l].K, A[l].maps, A[l].h, A[l].w))
-        mm = std::max(mm, (size_t)MFMA_MAX_SLICES * A[l].maps * A[l].h * A[l].w);
+      if (A[l].kind == CNN_LAYER_CONV) {
+        if (mfma_shape_ok(A[l - 1].maps, A[l].K, A[l].maps, A[l].h, A[l].w))
+          mm = std::max(mm, (size_t)MFMA_MAX_SLICES * A[l].maps * A[l].h * A[l].w);
+        if (l >= 2 && mfma_bwd_shape_ok(A[l - 1].maps, A[l].K, A[l].S, A[l].maps, A[l - 1].h, A[l - 1].w))
+          mm = std::max(mm, (size_t)MFMA_MAX_SLICES * A[l - 1].maps * A[l - 1].h * A[l - 1].w);
+      }
     net->d_mm_part = c.take<float>(mm);
   }
   net->d_flow = c.take<FlowSpec>(1);
@@ -441,6 +451,23 @@ int check_plan(cnn* net) {
         if (((L.Mi + st.n_tiles - 1) / st.n_tiles) * (st.n_tiles - 1) >= L.Mi) return bad(s, "an empty slice");
         break;
       }
+      case ST_CONV_BWD_MFMA: {
+        const int KK = L.K * L.K, HWd = (L.Hi + L.K - 1) * (L.Wi + L.K - 1), Pn = L.Hi * L.Wi;
+        const int NT = (Pn + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
+        const int WP = st.chunk * KK + 1 + ((st.chunk * KK) & 1);
+        if (!L.full_table || !mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) return bad(s, "layer not fit for the matrix-core pull");
+        if (st.chunk < 1 || (long long)st.chunk * HWd + 32LL * WP + (long long)st.chunk * KK > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
+        if (st.n_tiles < 1 || st.n_tiles > L.Mo || st.n_items != ((L.Mi + 31) / 32) * st.n_tiles) return bad(s, "slices do not cover the output maps");
+        if (st.rows_per_wg != st.n_tiles || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "too many partial-sum planes");
+        if (KW > 1 && (long long)KW * NT * 1024 > LDS_FLOATS) return bad(s, "k splits do not fit LDS");
+        if (((L.Mo + st.n_tiles - 1) / st.n_tiles) * (st.n_tiles - 1) >= L.Mo) return bad(s, "an empty slice");
+        if (st.layer < 1 || P.layers[st.layer - 1].kind != L_CONV) return bad(s, "no convolutional layer below");
+        break;
+      }
+      case ST_CONV_BWD_EPI:
+        if (st.n_items != L.Mi || st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
+        if (st.layer < 1) return bad(s, "no layer below");
+        break;
       case ST_CONV_EPI:
         if (st.n_items != L.Mo || st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
         if (L.Ho * L.Wo > MAX_TILE_PIX) return bad(s, "map too large");
@@ -547,7 +574,7 @@ int plan(cnn* net) {
     s.kind = kind; s.layer = layer; s.n_items = n_items; s.barrier_after = barrier; s.train_only = train_only;
     return s;
   };
-  if (3 * nl + 4 > MAX_STAGES) return fail(&net->err, CNN_E_SHAPE, "too many stages");
+  if (4 * nl + 4 > MAX_STAGES) return fail(&net->err, CNN_E_SHAPE, "too many stages");
   if (fe) add(ST_FRONTEND, 0, (net->fe_n * A[0].h * A[0].w + WG - 1) / WG, 1, 0);
   for (int l = 0; l < nl; ++l) {  // forward, bottom up
     LayerDev& L = P.layers[l];
@@ -610,6 +637,26 @@ int plan(cnn* net) {
         // pull deltas into layer l-1 (reads the old weights of layer l) ...
         const bool with_pending = pending_wgrad >= 0;
         if (with_pending) { add_wgrad(pending_wgrad, 0); pending_wgrad = -1; }
+        if (net->use_mfma && L.full_table && mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) {
+          // wide layer: the pull as FP's mirror image on the matrix cores, the contraction over the
+          // output maps split over workgroups; the second stage adds the partial sums -- the
+          // adjustment of this layer's weights, which the first stage has read, shares its interval
+          const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
+          const int KK = L.K * L.K, HWd = (L.Hi + L.K - 1) * (L.Wi + L.K - 1);
+          const int RT = (L.Mi + 31) / 32;
+          int KS = std::max(1, std::min({n_cu / RT, L.Mo, MFMA_MAX_SLICES}));
+          const int per = (L.Mo + KS - 1) / KS;
+          KS = (L.Mo + per - 1) / per;
+          const int IC = std::min(per, (LDS_FLOATS - 64) / (HWd + 33 * KK + 2));
+          if (IC >= 1) {
+            Stage& s = add(ST_CONV_BWD_MFMA, l, RT * KS, 1, 1);
+            s.n_tiles = KS; s.chunk = IC; s.rows_per_wg = KS;
+            add_wgrad(l, 0);
+            Stage& e = add(ST_CONV_BWD_EPI, l, L.Mi, 1, 1);
+            e.rows_per_wg = KS;
+            continue;
+          }
+        }
         Stage& s = add(ST_CONV_BWD, l, 0, 1, 1);
         const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.K;
         const int max_back = net->host_tables[conv_of_dev[l]].max_back;
@@ -1004,7 +1051,8 @@ int cnn_workspace_bytes(const char* arch, size_t* bytes) {
 }
 
 static int plan_to_text(const ProgramDev& P, char* buf, size_t n) {
-  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad", "conv_mfma", "conv_epi"};
+  static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad", "conv_mfma", "conv_epi",
+                                "conv_bwd_mfma", "conv_bwd_epi"};
   std::string out;
   char line[256];
   for (int s = 0; s < P.n_stages; ++s) {

@@ -311,14 +311,25 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
 typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int MM_TPW = 4;  // pixel tiles one wavefront can carry (64 accumulators)
 
-__device__ void conv_fwd_mfma_item(const LayerDev& L, const Stage& st, int item, const gfloat* in, float* lds) {
+// BWD = false: FP, rows = output maps, contraction over (input map, tap), staged maps = the
+// layer's inputs.  BWD = true: the delta pull of Sec. 3.3 as FP's mirror image (skipping factor 0
+// only): rows = input maps i, contraction over (output map j, tap), staged maps = the deltas of
+// the output maps put at their winners' places inside (Hi+K-1) x (Wi+K-1) zeros, so that
+//   g_i[r][c] = sum_j sum_{ky,kx} D_j[r + K-1-ky][c + K-1-kx] w_{j,i}[ky][kx]
+// has the same operand pattern in[koff(k) + pbase(p)] as FP; the weights are used as they lie
+// (the tap order is turned round in koff instead).  One plane of partial sums per work item.
+template <bool BWD>
+__device__ void conv_mfma_item(const LayerDev& L, const Stage& st, int item, const gfloat* in, float* lds) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int lrow = lane & 31, lk = lane >> 5;
   const int KS = st.n_tiles;
   const int jt = item / KS, ks = item - jt * KS;
   const int j0 = jt * 32;
-  const int Mi = L.Mi, Mo = L.Mo, K = L.K, KK = K * K, HiWi = L.Hi * L.Wi, Wi = L.Wi, Wo = L.Wo;
-  const int P = L.Ho * L.Wo, stride = L.S + 1;
+  const int K = L.K, KK = K * K;
+  // rows of the product, maps contracted over, size and row pitch of a staged map, output pixels
+  const int Mo = BWD ? L.Mi : L.Mo, Mi = BWD ? L.Mo : L.Mi;
+  const int Wi = BWD ? L.Wi + K - 1 : L.Wi, HiWi = BWD ? (L.Hi + K - 1) * (L.Wi + K - 1) : L.Hi * L.Wi;
+  const int Wo = BWD ? L.Wi : L.Wo, P = BWD ? L.Hi * L.Wi : L.Ho * L.Wo, stride = BWD ? 1 : L.S + 1;
   const int per = (Mi + KS - 1) / KS;
   const int i_lo = ks * per, i_hi = min(Mi, i_lo + per);
   const int IC = st.chunk;
@@ -338,7 +349,7 @@ __device__ void conv_fwd_mfma_item(const LayerDev& L, const Stage& st, int item,
   for (int x = tid; x < IC * KK; x += WG) {
     const int c = x / KK, t = x - c * KK;
     const int ky = t / K, kx = t - ky * K;
-    koff[x] = c * HiWi + ky * Wi + kx;
+    koff[x] = BWD ? c * HiWi + (K - 1 - ky) * Wi + (K - 1 - kx) : c * HiWi + ky * Wi + kx;
   }
   int pbase[MM_TPW];
 #pragma unroll
@@ -357,7 +368,7 @@ __device__ void conv_fwd_mfma_item(const LayerDev& L, const Stage& st, int item,
   for (int ic0 = i_lo; ic0 < i_hi; ic0 += IC) {
     const int n_ic = min(IC, i_hi - ic0);
     const int kc = n_ic * KK;
-    {  // stage the chunk, eight loads in flight per lane: the inputs (one contiguous block) ...
+    if constexpr (!BWD) {  // stage the chunk, eight loads in flight per lane: the inputs (one contiguous block) ...
       const gfloat* src = in + (size_t)ic0 * HiWi;
       const int n_in = n_ic * HiWi;
       for (int x0 = 0; x0 < n_in; x0 += 8 * WG) {
@@ -379,6 +390,50 @@ __device__ void conv_fwd_mfma_item(const LayerDev& L, const Stage& st, int item,
 #pragma unroll
         for (int u = 0; u < 8; ++u)
           if (x0 + u * 32 + xl < kc) lds_w[r * WP + x0 + u * 32 + xl] = row_ok ? v[u] : 0.f;
+      }
+    } else {
+      // the filters w_{j,i} of the chunk's output maps j and the 32 input maps i of this tile: for
+      // one j they are 32 * KK consecutive floats (i runs fastest after the tap)
+      const int n_rows = min(32, Mo - j0);
+      const int run = n_rows * KK, tot = n_ic * run;
+      for (int x0 = 0; x0 < tot; x0 += 8 * WG) {
+        float v[8];
+        int d[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int x = min(x0 + u * WG + tid, tot - 1);
+          const int jj = x / run, rem = x - jj * run;
+          const int r = rem / KK, t = rem - r * KK;
+          v[u] = L.w[((size_t)(ic0 + jj) * Mo + j0) * KK + rem];
+          d[u] = r * WP + jj * KK + t;
+        }
+        if (x0 == 0) {  // the zero fill overlaps the first batch of loads
+          for (int x = tid; x < n_ic * HiWi; x += WG) lds_in[x] = 0.f;
+          if (n_rows < 32)
+            for (int x = tid; x < (32 - n_rows) * WP; x += WG) lds_w[n_rows * WP + x] = 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (x0 + u * WG + tid < tot) lds_w[d[u]] = v[u];
+      }
+      __syncthreads();
+      // the chunk's deltas, each to its winner's place inside the zeros
+      const int HW = L.Hp * L.Wp, ntot = n_ic * HW;
+      for (int x0 = 0; x0 < ntot; x0 += 4 * WG) {
+        float dv[4];
+        int yx[4], cc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int x = min(x0 + u * WG + tid, ntot - 1);
+          cc[u] = x / HW;
+          const size_t o = (size_t)(ic0 + cc[u]) * HW + (x - cc[u] * HW);
+          yx[u] = L.argyx[o];
+          dv[u] = L.delta[o];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (x0 + u * WG + tid < ntot)
+            lds_in[cc[u] * HiWi + ((yx[u] >> 16) + K - 1) * Wi + (yx[u] & 0xffff) + K - 1] = dv[u];
       }
     }
     __syncthreads();
@@ -1003,6 +1058,27 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   __syncthreads();
 }
 
+// Second half of the matrix-core delta pull: the planes of partial sums of input map i added in a
+// fixed order, times the derivative of the activation function at the output of the layer below
+// (Sec. 3.3): delta of that layer at its pooled positions.  One work item per input map.
+__device__ void conv_bwd_epi_item(const LayerDev& L, const LayerDev& Lp, const Stage& st, int i) {
+  const int tid = threadIdx.x;
+  const int P = L.Hi * L.Wi, Mi = L.Mi;
+  const int n_planes = st.rows_per_wg;
+  for (int p = tid; p < P; p += WG) {
+    float s = 0.f;
+    for (int s0 = 0; s0 < n_planes; s0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = L.mm_part[((size_t)min(s0 + u, n_planes - 1) * Mi + i) * P + p];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += (s0 + u < n_planes) ? v[u] : 0.f;
+    }
+    const size_t o = (size_t)i * P + p;
+    Lp.delta[o] = s * dact_f(Lp.out[o]);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Dispatch of one work item of one stage.  KIND is a compile-time constant in the per-stage
 // kernels (so each holds only its own code) and comes from a switch in the persistent kernel.
@@ -1028,9 +1104,13 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
   } else if constexpr (KIND == ST_CONV_WGRAD) {
     conv_wgrad_item(L, st, item, in, ctx, lds);
   } else if constexpr (KIND == ST_CONV_FWD_MFMA) {
-    conv_fwd_mfma_item(L, st, item, in, lds);
+    conv_mfma_item<false>(L, st, item, in, lds);
   } else if constexpr (KIND == ST_CONV_EPI) {
     conv_epi_item(L, st, item, lds);
+  } else if constexpr (KIND == ST_CONV_BWD_MFMA) {
+    conv_mfma_item<true>(L, st, item, in, lds);
+  } else if constexpr (KIND == ST_CONV_BWD_EPI) {
+    conv_bwd_epi_item(L, P.layers[st.layer - 1], st, item);
   }
 }
 
@@ -1048,6 +1128,8 @@ __device__ void run_stage_items(const ProgramDev& P, const Stage& st, int first,
     RUN_KIND(ST_CONV_WGRAD)
     RUN_KIND(ST_CONV_FWD_MFMA)
     RUN_KIND(ST_CONV_EPI)
+    RUN_KIND(ST_CONV_BWD_MFMA)
+    RUN_KIND(ST_CONV_BWD_EPI)
 #undef RUN_KIND
     default: break;
   }
@@ -1089,6 +1171,8 @@ STAGE_KERNEL(k_conv_bwd, ST_CONV_BWD)
 STAGE_KERNEL(k_conv_wgrad, ST_CONV_WGRAD)
 STAGE_KERNEL(k_conv_fwd_mfma, ST_CONV_FWD_MFMA)
 STAGE_KERNEL(k_conv_epi, ST_CONV_EPI)
+STAGE_KERNEL(k_conv_bwd_mfma, ST_CONV_BWD_MFMA)
+STAGE_KERNEL(k_conv_bwd_epi, ST_CONV_BWD_EPI)
 
 // Fixed image-processing layer for a whole batch at once (it depends on no weight, so it need not
 // sit inside the on-line chain): image t of `images` -> out[t], one workgroup per WG output pixels.
@@ -1264,6 +1348,8 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
     case ST_CONV_WGRAD: hipLaunchKernelGGL(k_conv_wgrad, grid, block, 0, stream, d_prog, s, d_status, a); break;
     case ST_CONV_FWD_MFMA: hipLaunchKernelGGL(k_conv_fwd_mfma, grid, block, 0, stream, d_prog, s, d_status, a); break;
     case ST_CONV_EPI: hipLaunchKernelGGL(k_conv_epi, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_BWD_MFMA: hipLaunchKernelGGL(k_conv_bwd_mfma, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_BWD_EPI: hipLaunchKernelGGL(k_conv_bwd_epi, grid, block, 0, stream, d_prog, s, d_status, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

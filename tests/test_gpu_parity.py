@@ -199,25 +199,42 @@ def test_resident_mode_repeats_bit_for_bit_wherever_the_team_sits(name):
 
 @pytest.mark.parametrize("name", ["cfg2b", "cfg3", "cfg4a", "cfg4b"])
 def test_matrix_core_forward_matches_the_vector_kernel(name):
-    """Wide layers run their forward pass as an implicit GEMM on the matrix cores; switching that
-    off sends them through the vector kernel.  Both must meet the oracle's activations, and each
-    other to rounding; the plan must really contain a matrix-core stage for these networks."""
+    """Wide layers run their forward pass, and the delta pull through them, as implicit GEMMs on
+    the matrix cores; switching that off sends them through the vector kernels.  Both must meet
+    the oracle's activations, deltas and gradients, and each other to rounding; the plan must
+    really contain the matrix-core stages for these networks.  With a large learning rate the
+    pull must still have read the weights before they were adjusted."""
     wl = synth.WORKLOADS[name]
     print("case", name, flush=True)
-    assert "conv_mfma" in binding.plan_text(wl.arch)
+    plan = binding.plan_text(wl.arch)
+    assert "conv_mfma" in plan and "conv_bwd_mfma" in plan
     g, o = build_pair(wl)
     img = synth.images(wl, 1)[0]
+    lab = int(synth.labels(wl, 1)[0])
     d_img = to_dev(img)
-    o.forward(img)
-    acts = {}
+    grad_o, _ = o.gradients(img, lab)
+    acts, grads = {}, {}
     for on in (True, False):
         g.set_matrix_cores(on)
-        g.forward(d_img)
-        g.synchronize()
+        assert ("conv_bwd_mfma" in g.plan_text()) == on
+        grads[on] = g.debug_gradients(d_img, lab)
         compare_forward_state(g, o)
+        compare_backward_state(g, o)
+        for (a, b) in layer_bounds(o):
+            assert rel_err(grads[on][a:b], grad_o[a:b]) <= TOL_ACT, (on, a, b)
         acts[on] = [g.activation(l) for l in range(1, g.num_layers)]
     for a, b in zip(acts[True], acts[False]):
         assert rel_err(a, b) <= TOL_ACT
+    assert rel_err(grads[True], grads[False]) <= TOL_ACT
+    # one step with a rate that changes the weights a lot: deltas must come from the old weights
+    w0 = g.get_weights()
+    for on in (True, False):
+        g.set_matrix_cores(on)
+        g.set_weights(w0)
+        o.set_weights(w0.astype(np.float64))
+        g.train_step(d_img, lab, 0.3)
+        o.train_step(img, lab, 0.3)
+        assert rel_err(g.get_weights(), o.get_weights()) <= TOL_ACT, on
     g.close()
 
 
