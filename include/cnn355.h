@@ -185,7 +185,10 @@ int cnn_train_many(cnn_t* net, const float* d_images, const int32_t* d_labels, s
 int cnn_forward_many(cnn_t* net, const float* d_images, size_t n, float* d_probs);
 
 /* Choose how a step is issued (CNN_MODE_*).  CNN_MODE_STAGES and CNN_MODE_PERSISTENT give
- * identical bits; CNN_MODE_RESIDENT sums in another order and agrees with them to rounding.
+ * identical bits, except for networks with wide layers while the matrix cores are on
+ * (cnn_set_matrix_cores): there only CNN_MODE_STAGES pulls the deltas on the matrix cores, and
+ * the two agree to rounding.  CNN_MODE_RESIDENT sums in another order and agrees with them to
+ * rounding.  Switching to or from CNN_MODE_STAGES re-plans the stage list (synchronises).
  * CNN_E_STATE when the mode cannot run this network (the mode is then unchanged).  Setting a
  * connection table or a front-end re-plans the network: if resident mode can no longer run it
  * the handle drops to CNN_MODE_PERSISTENT (cnn_get_mode tells). */
@@ -211,8 +214,9 @@ int cnn_set_output_units(cnn_t* net, int kind);
 int cnn_get_output_units(const cnn_t* net);
 
 /* Stage and persistent modes: whether wide convolutional layers (full table, at least 64 output
- * maps and 256 inputs x taps per output) run their forward pass as an implicit GEMM on the matrix
- * cores (fp32 MFMA) -- on by default -- or through the vector kernel like every other layer.
+ * maps and 256 inputs x taps per output) run their forward pass -- and, in the stage mode, the
+ * delta pull through them (at least 32 input maps, skipping factor 0) -- as implicit GEMMs on the
+ * matrix cores (fp32 MFMA) -- on by default -- or through the vector kernels like every other layer.
  * Results agree to rounding.  Weights and tables are kept.  Synchronises. */
 int cnn_set_matrix_cores(cnn_t* net, int on);
 

@@ -18,7 +18,7 @@ namespace cnn355 {
 hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const ProgramDev* d_prog, int s,
                         StatusDev* d_status, const RunArgs& a);
 hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clear_label_flag);
-hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_prog,
+hipError_t launch_persistent(int grid, bool with_matrix_stages, hipStream_t stream, const ProgramDev* d_prog,
                              StatusDev* d_status, const RunArgs& a);
 int persistent_max_blocks_per_cu();
 void read_dbg(unsigned long long* out);
@@ -455,6 +455,7 @@ int check_plan(cnn* net) {
         const int KK = L.K * L.K, HWd = (L.Hi + L.K - 1) * (L.Wi + L.K - 1), Pn = L.Hi * L.Wi;
         const int NT = (Pn + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
         const int WP = st.chunk * KK + 1 + ((st.chunk * KK) & 1);
+        if (net->mode != CNN_MODE_STAGES) return bad(s, "the matrix-core pull is planned for the stage-launch mode only");
         if (!L.full_table || !mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) return bad(s, "layer not fit for the matrix-core pull");
         if (st.chunk < 1 || (long long)st.chunk * HWd + 32LL * WP + (long long)st.chunk * KK > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
         if (st.n_tiles < 1 || st.n_tiles > L.Mo || st.n_items != ((L.Mi + 31) / 32) * st.n_tiles) return bad(s, "slices do not cover the output maps");
@@ -637,8 +638,10 @@ int plan(cnn* net) {
         // pull deltas into layer l-1 (reads the old weights of layer l) ...
         const bool with_pending = pending_wgrad >= 0;
         if (with_pending) { add_wgrad(pending_wgrad, 0); pending_wgrad = -1; }
-        if (net->use_mfma && L.full_table && mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) {
-          // wide layer: the pull as FP's mirror image on the matrix cores, the contraction over the
+        if (net->use_mfma && net->mode == CNN_MODE_STAGES && L.full_table &&
+            mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) {
+          // wide layer, one launch per stage (the persistent kernel does not hold this stage kind:
+          // its registers would slow every other stage): the pull as FP's mirror image on the matrix cores, the contraction over the
           // output maps split over workgroups; the second stage adds the partial sums -- the
           // adjustment of this layer's weights, which the first stage has read, shares its interval
           const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
@@ -874,7 +877,9 @@ int run(cnn* net, const RunArgs& a0) {
   }
   if (net->mode == CNN_MODE_PERSISTENT) {
     HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
-    HIP_TRY(net, launch_persistent(persistent_grid(net, a.train), net->stream, net->d_prog, net->d_status, a));
+    bool mm = false;
+    for (int s = 0; s < P.n_stages; ++s) mm = mm || P.stages[s].kind >= ST_CONV_FWD_MFMA;
+    HIP_TRY(net, launch_persistent(persistent_grid(net, a.train), mm, net->stream, net->d_prog, net->d_status, a));
     return CNN_OK;
   }
   const long long n = a.n_images;
@@ -1220,7 +1225,20 @@ int cnn_set_mode(cnn_t* net, int mode) {
     return fail(&net->err, CNN_E_ARG, "unknown mode");
   if (mode != CNN_MODE_STAGES && !net->coop_ok) return fail(&net->err, CNN_E_STATE, "device does not support cooperative launches");
   if (mode == CNN_MODE_RESIDENT && !net->flow_ok) return fail(&net->err, CNN_E_STATE, net->flow_why);
+  const bool replan = (mode == CNN_MODE_STAGES) != (net->mode == CNN_MODE_STAGES);
+  if (replan) HIP_TRY(net, hipStreamSynchronize(net->stream));
+  const int old_mode = net->mode;
   net->mode = mode;
+  if (replan) {
+    // the stage-launch mode pulls the deltas of wide layers on the matrix cores, the other modes do
+    // not: the stage list differs; weights, tables and everything else on the device stay
+    int rc = plan(net);
+    if (rc) { net->mode = old_mode; return rc; }
+    net->mode = mode;
+    HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
+    HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
+  }
   return CNN_OK;
 }
 

@@ -1114,8 +1114,24 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
   }
 }
 
+// MM: the forward matrix-core stage kinds are compiled in (64 accumulators per lane push other
+// stages' registers out to scratch memory, so plans without such stages get a kernel without
+// them).  The matrix-core pull is not compiled into the persistent kernel at all: with it the
+// register allocation of every stage suffers (measured: all stages 1.5 x slower); the host plans
+// it for the stage-launch mode only.
+template <bool MM>
 __device__ void run_stage_items(const ProgramDev& P, const Stage& st, int first, int step,
                                 const Ctx& ctx, StatusDev* status, float* lds) {
+  if constexpr (MM) {
+    switch (st.kind) {
+#define RUN_KIND(KIND) \
+      case KIND: for (int item = first; item < st.n_items; item += step) run_item<KIND>(P, st, item, ctx, status, lds); return;
+      RUN_KIND(ST_CONV_FWD_MFMA)
+      RUN_KIND(ST_CONV_EPI)
+#undef RUN_KIND
+      default: break;
+    }
+  }
   switch (st.kind) {
 #define RUN_KIND(KIND) \
     case KIND: for (int item = first; item < st.n_items; item += step) run_item<KIND>(P, st, item, ctx, status, lds); break;
@@ -1126,10 +1142,6 @@ __device__ void run_stage_items(const ProgramDev& P, const Stage& st, int first,
     RUN_KIND(ST_FC_BWD)
     RUN_KIND(ST_CONV_BWD)
     RUN_KIND(ST_CONV_WGRAD)
-    RUN_KIND(ST_CONV_FWD_MFMA)
-    RUN_KIND(ST_CONV_EPI)
-    RUN_KIND(ST_CONV_BWD_MFMA)
-    RUN_KIND(ST_CONV_BWD_EPI)
 #undef RUN_KIND
     default: break;
   }
@@ -1282,6 +1294,7 @@ __device__ bool xcd_barrier(StatusDev* status, unsigned int epoch, const BarCtx&
   return *s_ok != 0;
 }
 
+template <bool MM>
 __global__ void __launch_bounds__(WG) k_persistent(const ProgramDev* __restrict__ P,
                                                    StatusDev* status, RunArgs a) {
   __shared__ float lds[LDS_FLOATS];
@@ -1315,7 +1328,7 @@ __global__ void __launch_bounds__(WG) k_persistent(const ProgramDev* __restrict_
     for (int s = 0; s < P->n_stages; ++s) {
       const Stage& st = P->stages[s];
       if (st.train_only && !ctx.train) continue;
-      run_stage_items(*P, st, blockIdx.x, G, ctx, status, lds);
+      run_stage_items<MM>(*P, st, blockIdx.x, G, ctx, status, lds);
       if (stamp) status->stamps[1 + 2 * s] = wall_clock64();
       if (st.barrier_after) {
         bool ok;
@@ -1368,11 +1381,13 @@ hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clea
   return hipGetLastError();
 }
 
-hipError_t launch_persistent(int grid, hipStream_t stream, const ProgramDev* d_prog,
+// with_matrix_stages: the plan holds forward matrix-core stages (the kernel without them is leaner)
+hipError_t launch_persistent(int grid, bool with_matrix_stages, hipStream_t stream, const ProgramDev* d_prog,
                              StatusDev* d_status, const RunArgs& a) {
   RunArgs args = a;
   void* params[] = {(void*)&d_prog, (void*)&d_status, (void*)&args};
-  return hipLaunchCooperativeKernel((const void*)k_persistent, dim3(grid), dim3(WG), params, 0, stream);
+  const void* k = with_matrix_stages ? (const void*)k_persistent<true> : (const void*)k_persistent<false>;
+  return hipLaunchCooperativeKernel(k, dim3(grid), dim3(WG), params, 0, stream);
 }
 
 void read_dbg(unsigned long long* out) {
@@ -1385,8 +1400,10 @@ void read_dbg(unsigned long long* out) {
 
 int persistent_max_blocks_per_cu() {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)k_persistent, WG, 0) != hipSuccess) return 0;
-  return n;
+  int m = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)k_persistent<true>, WG, 0) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&m, (const void*)k_persistent<false>, WG, 0) != hipSuccess) return 0;
+  return n < m ? n : m;
 }
 
 }  // namespace cnn355

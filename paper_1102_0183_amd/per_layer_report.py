@@ -87,7 +87,9 @@ for name in ("cfg1", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"):
                     fl = 2 * d["nconn"] * KK * P; by = 4 * nin + w_b + 4 * d["maps"] * (P + 2 * HW)
                 elif kind == "conv_epi":
                     fl = d["maps"] * P * 10; by = 4 * d["maps"] * (P + 2 * HW)   # plane sums are the kernel's own traffic, not algorithmic
-                elif kind == "conv_bwd":
+                elif kind == "conv_bwd_epi":
+                    fl = nin * 4; by = 4 * nin * 2      # plane sums are the kernel's own traffic, not algorithmic
+                elif kind in ("conv_bwd", "conv_bwd_mfma"):
                     fl = 2 * d["nconn"] * KK * P; by = 4 * d["maps"] * HW * 2 + w_b + 4 * nin * 2    # dense count (the kernel multiplies the whole rectangle)
                 elif kind == "conv_wgrad":
                     fl = 2 * d["nconn"] * KK * HW; by = 4 * nin + 4 * d["maps"] * HW * 2 + 2 * w_b  # sparse count: winners only
