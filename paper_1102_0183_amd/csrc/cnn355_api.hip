@@ -163,6 +163,14 @@ bool mfma_bwd_shape_ok(int Mi, int K, int S, int Mo, int Hi, int Wi) {
   const long long Kd = (long long)Mo * K * K, P = (long long)Hi * Wi;
   return S == 0 && Mi >= 32 && Kd >= 256 && P >= 16 && P <= MAX_TILE_PIX && (P + 31) / 32 <= (WG / 64) * 4;
 }
+// Weight gradients of such a layer as a matrix product over the output pixels: rows = output maps,
+// columns = (input map, tap); the deltas of 32 maps over the whole output map must fit in LDS next
+// to at least one input map.
+bool mfma_wgrad_shape_ok(int Mi, int K, int Mo, int Hi, int Wi, int Ho, int Wo) {
+  const long long cols = (long long)Mi * K * K, P = (long long)Ho * Wo;
+  // (measured: below some 300 000 weights the vector kernel, which visits the winners only, is as fast)
+  return Mo >= 64 && cols >= 256 && Mo * cols >= 300000 && P >= 4 && 32 * (P + 2) + P + (long long)Hi * Wi + 64 <= LDS_FLOATS;
+}
 int ceil_log2(int v) {
   int l = 0;
   while ((1 << l) < v) ++l;
@@ -465,6 +473,17 @@ int check_plan(cnn* net) {
         if (st.layer < 1 || P.layers[st.layer - 1].kind != L_CONV) return bad(s, "no convolutional layer below");
         break;
       }
+      case ST_CONV_WGRAD_MFMA: {
+        const int KK = L.K * L.K, Pn = L.Ho * L.Wo, WP = Pn + 1 + (Pn & 1);
+        const int NT = (std::min(st.chunk, L.Mi) * KK + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
+        if (net->mode != CNN_MODE_STAGES) return bad(s, "the matrix-core gradient is planned for the stage-launch mode only");
+        if (!L.full_table || !mfma_wgrad_shape_ok(L.Mi, L.K, L.Mo, L.Hi, L.Wi, L.Ho, L.Wo)) return bad(s, "layer not fit for the matrix-core gradient");
+        if (st.chunk < 1 || (long long)st.chunk * L.Hi * L.Wi + 32LL * WP + Pn > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
+        if (NT > 4 * waves) return bad(s, "too many column tiles");
+        if (KW * NT * 1024 > LDS_FLOATS) return bad(s, "k splits do not fit LDS");
+        if (st.n_tiles * st.chunk < L.Mi || (st.n_tiles - 1) * st.chunk >= L.Mi || st.n_items != ((L.Mo + 31) / 32) * st.n_tiles) return bad(s, "chunks do not cover the input maps");
+        break;
+      }
       case ST_CONV_BWD_EPI:
         if (st.n_items != L.Mi || st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
         if (st.layer < 1) return bad(s, "no layer below");
@@ -617,6 +636,28 @@ int plan(cnn* net) {
   int pending_wgrad = -1;
   auto add_wgrad = [&](int l, int barrier) {
     LayerDev& L = P.layers[l];
+    if (net->use_mfma && net->mode == CNN_MODE_STAGES && L.full_table &&
+        mfma_wgrad_shape_ok(L.Mi, L.K, L.Mo, L.Hi, L.Wi, L.Ho, L.Wo)) {
+      // wide layer, one launch per stage: the gradients as a matrix product over the output pixels.
+      // Input maps per work item: about one work item per compute unit, whole column tiles of 32
+      // where the kernel size allows, at most 64 column tiles, and what LDS holds.
+      const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
+      const int KK = L.K * L.K, HiWi = L.Hi * L.Wi, Pn = L.Ho * L.Wo;
+      const int RT = (L.Mo + 31) / 32;
+      const int WP = Pn + 1 + (Pn & 1);
+      const int ic_lds = (LDS_FLOATS - 64 - 32 * WP - Pn) / HiWi;
+      int unit = 1;
+      while ((unit * KK) % 32 != 0 && unit < 8) unit *= 2;   // a few maps that fill whole column tiles, if there are such
+      if ((unit * KK) % 32 != 0) unit = 1;
+      int ic = (L.Mi + std::max(1, n_cu / RT) - 1) / std::max(1, n_cu / RT);
+      ic = (ic + unit - 1) / unit * unit;
+      ic = std::max(1, std::min({ic, ic_lds, 64 * 32 / KK, L.Mi}));
+      Stage& s = add(ST_CONV_WGRAD_MFMA, l, 0, barrier, 1);
+      s.chunk = ic;
+      s.n_tiles = (L.Mi + ic - 1) / ic;
+      s.n_items = RT * s.n_tiles;
+      return;
+    }
     Stage& s = add(ST_CONV_WGRAD, l, 0, barrier, 1);
     const int chunk_max = std::min(LDS_IN / (L.Hi * L.Wi), L.max_conn);
     const int want_chunks = std::max(1, 192 / L.Mo);  // aim at about 192 work items: one round on 256 CUs
@@ -1057,7 +1098,7 @@ int cnn_workspace_bytes(const char* arch, size_t* bytes) {
 
 static int plan_to_text(const ProgramDev& P, char* buf, size_t n) {
   static const char* names[] = {"?", "frontend", "conv_fwd", "fc_fwd", "head", "fc_bwd", "conv_bwd", "conv_wgrad", "conv_mfma", "conv_epi",
-                                "conv_bwd_mfma", "conv_bwd_epi"};
+                                "conv_bwd_mfma", "conv_bwd_epi", "conv_wgrad_mfma"};
   std::string out;
   char line[256];
   for (int s = 0; s < P.n_stages; ++s) {

@@ -74,6 +74,7 @@ enum StageKind : int {
   ST_CONV_EPI = 9,      // ... then: sum of the partial sums + bias + tanh + max-pool + arg-max
   ST_CONV_BWD_MFMA = 10, // delta pull through a wide layer as FP's mirror image on the matrix cores: partial sums
   ST_CONV_BWD_EPI = 11,  // ... then: sum of the partial sums, times the activation derivative of the layer below
+  ST_CONV_WGRAD_MFMA = 12, // weight gradients of a wide layer as a matrix product over the output pixels, and the adjustment
 };
 constexpr int MFMA_MAX_SLICES = 64;  // partial-sum slices (splits of the contraction) per layer
 

@@ -1058,6 +1058,166 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   __syncthreads();
 }
 
+// Weight gradients of a wide layer with a full table on the matrix cores (Sec. 3.4), and the
+// adjustment that follows them.  With the deltas written out over the whole output map (zero
+// except at the pooling winners) the sum over output neurons is a plain matrix product,
+//   dE/dw_{j,i}[ky][kx] = sum_p delta_j[p] * in_i[pos(p) + (ky, kx)],
+// rows = output maps j, columns = (input map i, tap), contraction over the output pixels p --
+// the forward product with pixels and taps in each other's place, so the operand pattern
+// in[koff(p) + cbase(column)] is the same.  It multiplies Kp^2 times more zeros than the vector
+// kernel skips, which the matrix cores do faster than that kernel follows each map's winners.
+// Work item = (tile of 32 output maps, chunk of IC input maps): it holds the whole contraction,
+// so every weight is read and written by exactly one work item.  Bias: the items of chunk 0.
+__device__ void conv_wgrad_mfma_item(const LayerDev& L, const Stage& st, int item, const gfloat* in,
+                                     const Ctx& ctx, float* lds) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int lrow = lane & 31, lk = lane >> 5;
+  const int NC = st.n_tiles;                 // chunks of input maps
+  const int jt = item / NC, ks = item - jt * NC;
+  const int j0 = jt * 32;
+  const int K = L.K, KK = K * K, Mi = L.Mi, Mo = L.Mo, Wi = L.Wi, HiWi = L.Hi * L.Wi;
+  const int Wo = L.Wo, P = L.Ho * L.Wo, HW = L.Hp * L.Wp, stride = L.S + 1;
+  const int IC = st.chunk;
+  const int ic0 = ks * IC, n_ic = min(IC, Mi - ic0);
+  const int ncol = n_ic * KK;                // columns of this item
+  const int WP = P + 1 + (P & 1);            // odd row pitch of the delta rows
+  const int NT = (ncol + 31) >> 5;           // column tiles
+  constexpr int WAVES = WG / 64;
+  const int NTw = min(NT, WAVES);
+  const int KW = (NT >= WAVES) ? 1 : WAVES / NT;
+  const int kw = (NT >= WAVES) ? 0 : wave / NT;
+  const int tw = (NT >= WAVES) ? wave : wave - kw * NT;
+  const bool wave_on = kw < KW;
+
+  float* lds_in = lds;                        // [IC][Hi*Wi]
+  float* lds_d = lds + IC * HiWi;             // [32][WP] deltas over the whole output map
+  int* koff = (int*)(lds_d + 32 * WP);        // [P] place of output pixel p's field in an input map
+
+  for (int x = tid; x < P; x += WG) {
+    const int y = x / Wo, xx = x - y * Wo;
+    koff[x] = (y * Wi + xx) * stride;
+  }
+  for (int x = tid; x < 32 * WP; x += WG) lds_d[x] = 0.f;
+  {  // the chunk's input maps: one contiguous block
+    const gfloat* src = in + (size_t)ic0 * HiWi;
+    const int n_in = n_ic * HiWi;
+    for (int x0 = 0; x0 < n_in; x0 += 8 * WG) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = src[min(x0 + u * WG + tid, n_in - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (x0 + u * WG + tid < n_in) lds_in[x0 + u * WG + tid] = v[u];
+    }
+  }
+  __syncthreads();
+  {  // the tile's deltas, each to its winner's place
+    const int n_rows = min(32, Mo - j0), ntot = n_rows * HW;
+    for (int x0 = 0; x0 < ntot; x0 += 4 * WG) {
+      float dv[4];
+      int yx[4], rr[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int x = min(x0 + u * WG + tid, ntot - 1);
+        rr[u] = x / HW;
+        const size_t o = (size_t)(j0 + rr[u]) * HW + (x - rr[u] * HW);
+        yx[u] = L.argyx[o];
+        dv[u] = L.delta[o];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (x0 + u * WG + tid < ntot) lds_d[rr[u] * WP + (yx[u] >> 16) * Wo + (yx[u] & 0xffff)] = dv[u];
+    }
+  }
+  int cbase[MM_TPW];
+#pragma unroll
+  for (int t = 0; t < MM_TPW; ++t) {
+    const int n = (tw + t * NTw) * 32 + lrow;
+    const int c = n / KK, tt = n - c * KK;
+    const int ky = tt / K, kx = tt - ky * K;
+    cbase[t] = (n < ncol) ? c * HiWi + ky * Wi + kx : 0;
+  }
+  v16f acc[MM_TPW];
+#pragma unroll
+  for (int t = 0; t < MM_TPW; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  const int n_my_tiles = wave_on ? ((NT - tw + NTw - 1) / NTw) : 0;
+  __syncthreads();
+  if (wave_on) {
+    const int kper = (((P + KW - 1) / KW) + 1) & ~1;
+    const int k_lo = kw * kper, k_hi = min(P, k_lo + kper);
+    for (int kk = k_lo; kk < k_hi; kk += 8) {
+      float a[4];
+      int ko[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int k = kk + 2 * u + lk;
+        a[u] = (k < k_hi) ? lds_d[lrow * WP + min(k, P - 1)] : 0.f;
+        ko[u] = koff[min(k, P - 1)];
+      }
+#pragma unroll
+      for (int t = 0; t < MM_TPW; ++t)
+        if (t < n_my_tiles) {
+          float b[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) b[u] = lds_in[ko[u] + cbase[t]];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc[t], 0, 0, 0);
+        }
+    }
+  }
+  // bias gradients of the tile (the work items of chunk 0): sum of a delta row
+  const float lr = ctx.lr;
+  gfloat* g_out = ctx.grad_out;
+  if (ks == 0) {
+    for (int r = wave; r < 32; r += WAVES) {
+      float sb = 0.f;
+      for (int q = lane; q < P; q += 64) sb += lds_d[r * WP + q];
+      sb = wave_sum(sb);
+      if (lane == 0 && j0 + r < Mo) {
+        if (g_out) g_out[L.b_canon + j0 + r] = sb;
+        else L.bias[j0 + r] -= lr * sb;
+      }
+    }
+  }
+  __syncthreads();
+  // weight (j, ic0 * KK + n) of the full table lies at ((j * Mi + ic0) * KK + n)
+  auto apply = [&](int j, int n, float g) {
+    const size_t o = ((size_t)j * Mi + ic0) * KK + n;
+    if (g_out) g_out[L.w_canon + o] = g;
+    else L.w[o] -= lr * g;
+  };
+  if (KW > 1) {
+    float* red = lds;  // [KW][NT][32 rows][32 columns]; the staged maps are no longer needed
+    if (wave_on) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        red[((kw * NT + tw) * 32 + (v >> 2) * 8 + lk * 4 + (v & 3)) * 32 + lrow] = acc[0][v];
+    }
+    __syncthreads();
+    for (int x = tid; x < NT * 1024; x += WG) {
+      const int t = x >> 10, row = (x >> 5) & 31, col = x & 31;
+      float sum = 0.f;
+      for (int q = 0; q < KW; ++q) sum += red[((q * NT + t) * 32 + row) * 32 + col];
+      const int n = t * 32 + col, j = j0 + row;
+      if (n < ncol && j < Mo) apply(j, n, sum);
+    }
+    __syncthreads();
+  } else if (wave_on) {
+#pragma unroll
+    for (int t = 0; t < MM_TPW; ++t)
+      if (t < n_my_tiles) {
+        const int n = (tw + t * NTw) * 32 + lrow;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int j = j0 + (v >> 2) * 8 + lk * 4 + (v & 3);
+          if (n < ncol && j < Mo) apply(j, n, acc[t][v]);
+        }
+      }
+  }
+}
+
 // Second half of the matrix-core delta pull: the planes of partial sums of input map i added in a
 // fixed order, times the derivative of the activation function at the output of the layer below
 // (Sec. 3.3): delta of that layer at its pooled positions.  One work item per input map.
@@ -1111,6 +1271,8 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
     conv_mfma_item<true>(L, st, item, in, lds);
   } else if constexpr (KIND == ST_CONV_BWD_EPI) {
     conv_bwd_epi_item(L, P.layers[st.layer - 1], st, item);
+  } else if constexpr (KIND == ST_CONV_WGRAD_MFMA) {
+    conv_wgrad_mfma_item(L, st, item, in, ctx, lds);
   }
 }
 
@@ -1185,6 +1347,7 @@ STAGE_KERNEL(k_conv_fwd_mfma, ST_CONV_FWD_MFMA)
 STAGE_KERNEL(k_conv_epi, ST_CONV_EPI)
 STAGE_KERNEL(k_conv_bwd_mfma, ST_CONV_BWD_MFMA)
 STAGE_KERNEL(k_conv_bwd_epi, ST_CONV_BWD_EPI)
+STAGE_KERNEL(k_conv_wgrad_mfma, ST_CONV_WGRAD_MFMA)
 
 // Fixed image-processing layer for a whole batch at once (it depends on no weight, so it need not
 // sit inside the on-line chain): image t of `images` -> out[t], one workgroup per WG output pixels.
@@ -1363,6 +1526,7 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
     case ST_CONV_EPI: hipLaunchKernelGGL(k_conv_epi, grid, block, 0, stream, d_prog, s, d_status, a); break;
     case ST_CONV_BWD_MFMA: hipLaunchKernelGGL(k_conv_bwd_mfma, grid, block, 0, stream, d_prog, s, d_status, a); break;
     case ST_CONV_BWD_EPI: hipLaunchKernelGGL(k_conv_bwd_epi, grid, block, 0, stream, d_prog, s, d_status, a); break;
+    case ST_CONV_WGRAD_MFMA: hipLaunchKernelGGL(k_conv_wgrad_mfma, grid, block, 0, stream, d_prog, s, d_status, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -211,6 +211,7 @@ def test_matrix_core_forward_matches_the_vector_kernel(name):
     print("case", name, flush=True)
     plan = binding.plan_text(wl.arch)
     assert "conv_mfma" in plan and "conv_bwd_mfma" in plan
+    assert ("conv_wgrad_mfma" in plan) == (name == "cfg4b")
     g, o = build_pair(wl)
     img = synth.images(wl, 1)[0]
     lab = int(synth.labels(wl, 1)[0])
