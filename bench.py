@@ -257,6 +257,26 @@ def main():
             extra[key + "_forward_batch_fp32_mfma_frac"] = round(tf / FP32_MFMA_PEAK_TFLOPS, 4)
             del scratch, d_probs
             net.close()
+        # the other benchmark networks, each in the mode that runs it fastest: on-line training of 400 seeded
+        # images (one launch per stage: wide layers on the matrix cores; cfg5 fits the resident kernel)
+        for key, mode_o in (("cfg3", binding.MODE_STAGES), ("cfg4a", binding.MODE_STAGES),
+                            ("cfg4b", binding.MODE_STAGES), ("cfg5", binding.MODE_RESIDENT)):
+            wo = synth.WORKLOADS[key]
+            n_o = 400
+            io, lo = synth.images(wo, n_o), synth.labels(wo, n_o)
+            d_io, d_lo = torch.from_numpy(io).to(dev), torch.from_numpy(lo).to(dev)
+            net = synth.build_network(binding.Cnn(wo.arch), wo)
+            net.set_mode(mode_o)
+            net.train_many(d_io, d_lo, wo.lr, n=50)
+            net.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            net.train_many(d_io, d_lo, wo.lr)
+            e1.record()
+            e1.synchronize()
+            extra[key + "_train_images_per_s"] = round(n_o / (e0.elapsed_time(e1) * 1e-3), 1)
+            net.close()
+            del d_io, d_lo
         # launch cost: the same images through one cnn_train_step call each
         net = make_net(wl, args.grid)
         sz = net.image_size
