@@ -82,8 +82,9 @@ enum {
  *   <N>N          fully connected layer of N neurons (Sec. 2.4).  The last token must be
  *                 one: the output layer, one unit per class.  Hidden fully connected layers
  *                 use the scaled tanh y = 1.7159 tanh(0.6666 a) (Sec. 4); the output layer
- *                 is a soft-max trained with the cross-entropy error (the paper names no
- *                 error function; this is the reading this library fixes).
+ *                 is a soft-max trained with the cross-entropy error by default (the paper
+ *                 names no error function); cnn_set_output_units switches to scaled-tanh
+ *                 output neurons trained on the squared error.
  *   Example: "1x29x29-20C4-MP2-40C5-MP3-150N-10N".
  *
  * Layer numbering used by the calls below: layer 0 is the network input (after the fixed
