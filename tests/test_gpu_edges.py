@@ -18,6 +18,8 @@ SHAPES = [
     ("2x12x12-4C5S1-MP2-3C2-3N", {1: 2}, 0, 2),              # Eq. 1 does not divide: last row/column unread
     ("3x8x8-4C3-MP3-4C2-6N-5N-4N", {1: 3}, 0, 3),            # maps shrink to one pixel; two hidden FC layers
     ("4x8x8-3C3S1-MP1-5N-2N", {}, 5, 2),                     # fixed front-end; pooling rectangle of one
+    ("4x12x12-3C3-MP2-5N-2N", {}, 21, 2),                    # 21 x 21 fixed filters (Sec. 4.2) on a 2x32x32 raw image
+    ("3x10x10-4C3-MP2-3N", {}, 13, 3),                       # 13 x 13 fixed filters (Sec. 4.3), one per colour channel
     ("1x6x6-2C3-3N", {}, 0, 1),                              # no pooling at all
     ("1x5x5-4N", {}, 0, 1),                                  # no convolution at all: the output layer reads the image
     ("1x5x5-7N-4N", {}, 0, 1),
