@@ -106,6 +106,35 @@ __device__ __forceinline__ float sum_strided(const float* part, int n, int pitch
   return s;
 }
 
+// The same sums for tot outputs p, fn(p, sum) called once per output.  With many terms and few
+// outputs eight lanes share an output -- lane g adds the terms g, g + 8, ... in that order, the
+// eight are then added across the lanes in a fixed pattern -- instead of one lane walking a long
+// chain of dependent LDS reads.
+template <class Fn>
+__device__ __forceinline__ void reduce_partials(const float* part, int n, int tot, Fn fn) {
+  const int tid = threadIdx.x;
+  int gl2 = 0;                                  // log2 of the lanes that share an output: up to 8
+  if (n >= 16)
+    while (gl2 < 3 && (tot << (gl2 + 1)) <= WG) ++gl2;
+  if (gl2 > 0) {
+    const int G = 1 << gl2;
+    const int p = tid >> gl2, g = tid & (G - 1);
+    float s = 0.f;
+    if (p < tot)
+      for (int r0 = g; r0 < n; r0 += 4 * G) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = part[min(r0 + u * G, n - 1) * tot + p];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += (r0 + u * G < n) ? v[u] : 0.f;
+      }
+    s = group_sum(s, gl2);
+    if (p < tot && g == 0) fn(p, s);
+  } else {
+    for (int p = tid; p < tot; p += WG) fn(p, sum_strided(part, n, tot, p));
+  }
+}
+
 __device__ __forceinline__ int n_mine(int M, int rank, int G) { return rank < M ? (M - rank + G - 1) / G : 0; }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -665,10 +694,7 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
   __syncthreads();
   if (D.R > 1) {
     const FDiv dP(Pn);
-    for (int p = tid; p < tot; p += WG) {
-      const float s = sum_strided(part, D.R, tot, p);
-      act[p] = f_act(s + bf[dP.div(p)]);
-    }
+    reduce_partials(part, D.R, tot, [&](int p, float s) { act[p] = f_act(s + bf[dP.div(p)]); });
     __syncthreads();
   }
 }
@@ -802,6 +828,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
   const int* cnt = (const int*)(lds + S.cnt);
   const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
+  DSTAMP(120);
   job_dispatch(S.variant, [&](auto k_, auto sw_, auto th_) {
     constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
@@ -809,6 +836,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
       float acc[TH * SW];
 #pragma unroll
       for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
+      int e_next = 0;
       for (int j0 = 0; j0 < Mo; j0 += chunk) {
         const int n = min(chunk, Mo - j0);
         for (int x = tid; x < n * HW; x += WG) {
@@ -817,20 +845,27 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
           dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
         }
         __syncthreads();
+        if (j0 == 0) DSTAMP(121);
         if (ln.on) {
-          // entries of the lane's input map whose output map lies in [j0, j0 + n)
+          // entries of the lane's input map whose output map lies in [j0, j0 + n): the list is
+          // sorted, this chunk's start is the last chunk's end, its end is found by bisection
           int e_lo = j0, e_hi = j0 + n;
           if (!full) {
             const int* bj = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
-            const int ne = cnt[ln.am];
-            e_lo = 0;
-            while (e_lo < ne && bj[e_lo] < j0) ++e_lo;
-            e_hi = e_lo;
-            while (e_hi < ne && bj[e_hi] < j0 + n) ++e_hi;
+            e_lo = e_next;
+            int lo = e_lo, hi = cnt[ln.am];
+            while (lo < hi) {
+              const int mid = (lo + hi) >> 1;
+              if (bj[mid] < j0 + n) lo = mid + 1; else hi = mid;
+            }
+            e_hi = lo;
+            e_next = e_hi;
           }
+          if (j0 == 0) DSTAMP(122);
           job_mac<K, SW, TH>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
         __syncthreads();
+        if (j0 == 0) DSTAMP(123);
         for (int x = tid; x < n * HW; x += WG) {
           const int c = dHW.div(x), q = x - c * HW;
           const int yx = yxall[(j0 + c) * HW + q];
@@ -849,12 +884,10 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
     }
   });
   __syncthreads();
+  DSTAMP(124);
   const float* ybelow = lds + Cb.o_pool;
   float* dbelow = lds + Cb.o_delta;
-  for (int p = tid; p < tot; p += WG) {
-    const float s = sum_strided(part, D.R, tot, p);
-    dbelow[p] = s * f_dact(ybelow[p]);
-  }
+  reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s * f_dact(ybelow[p]); });
   __syncthreads();
 }
 
