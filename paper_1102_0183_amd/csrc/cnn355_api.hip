@@ -794,6 +794,7 @@ void plan_flow(cnn* net) {
   }
   Q.xp = xtake((size_t)2 * Z.n_col_ranks * Z.fc[0].n_out);
   if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
+  if (xb && !Q.xp) return no("internal: an exchange buffer was not laid out");
   net->flow_static_id = resident_static_id(Z);
   net->flow_ok = true;
   net->flow_why.clear();

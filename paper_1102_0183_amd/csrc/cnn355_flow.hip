@@ -524,6 +524,7 @@ struct JobStat {  // the part of a job the plan fixes
   int in, w, idx, cnt;  // LDS offsets (floats): inputs [..][map_sz], weights [n_maps][w_pitch][K*K],
                         // input map of every connection [n_maps][w_pitch], connections per map [n_maps]
   int w_pitch, Ho, Wo, K, stride, map_sz, Wi, max_cnt;
+  int plan_cnt;         // the connection count the planner sized the partial sums for (>= max_cnt)
   int variant;          // (TH - 1) * 64 + SW * 8 + K for a job in tiles of TH rows x SW pixels, 0: one pixel per
                         // lane (any K, any stride)
   int table;            // LDS offset of the lane table [3][WG] (int), or -1
@@ -533,7 +534,7 @@ __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
   JobStat S;
   S.in = C.o_in; S.w = C.o_wf; S.idx = C.o_cidx; S.cnt = C.o_ncf;
   S.w_pitch = C.max_conn; S.Ho = C.Ho; S.Wo = C.Wo; S.K = C.K; S.stride = C.S + 1;
-  S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn;
+  S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn; S.plan_cnt = C.max_conn;
   S.variant = C.fwd_strip ? (C.fwd_rows - 1) * 64 + C.fwd_strip * 8 + C.K : 0;
   S.table = C.o_tab_fwd;
   return S;
@@ -545,6 +546,7 @@ __device__ __forceinline__ JobStat pull_job(const FlowSpec& Z, int l) {
   S.w_pitch = C.max_back; S.Ho = C.Hi; S.Wo = C.Wi; S.K = C.K; S.stride = 1;
   S.Wi = C.Wi + C.K - 1; S.map_sz = (C.Hi + C.K - 1) * (C.Wi + C.K - 1);
   S.max_cnt = min(C.max_back, C.pull_chunk);
+  S.plan_cnt = min(C.max_back, C.Mo);
   S.variant = C.pull_strip ? (C.pull_rows - 1) * 64 + C.pull_strip * 8 + C.K : 0;
   S.table = C.o_tab_pull;
   return S;
@@ -560,7 +562,9 @@ __device__ __forceinline__ JobDyn job_dyn(const JobStat& S, int n_maps) {
   JobDyn D;
   D.n_maps = n_maps;
   D.U = SW ? n_maps * ((S.Ho + TH - 1) / TH) * ((S.Wo + SW - 1) / SW) : n_maps * S.Ho * S.Wo;
-  D.R = flow_split_ways(D.U, S.max_cnt);
+  // the ways one chunk of connections can be shared, but never more than the planner laid out
+  // partial sums for (it counted the whole list; a shorter chunk can divide into more ways)
+  D.R = min(flow_split_ways(D.U, S.max_cnt), flow_split_ways(D.U, S.plan_cnt));
   D.passes = (D.U * D.R + WG - 1) / WG;
   return D;
 }

@@ -228,11 +228,28 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
       Z.defer = 1;
     }
   }
-  // lane tables of the correlation jobs, while there is room (a rank decodes its share of a job
-  // once instead of once per image); the first layers' jobs first
+  // Lane tables of the correlation jobs (a rank decodes its share of a job once instead of once per
+  // image), the first layers' jobs first -- but only where a table does not cost the pull a pass:
+  // the zero-bordered delta maps below get what is left, and every pass over a chunk of them costs
+  // more than decoding a job again.
+  auto pull_passes = [&](long long floats) {
+    long long worst = 1;
+    for (int l = 1; l < n_conv; ++l) {
+      const ConvSpec& C = Z.conv[l];
+      const long long hwd = (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1);
+      const long long chunk = flow_maxl(1, flow_minl(C.Mo, (floats - pad) / hwd));
+      worst = flow_maxl(worst, (C.Mo + chunk - 1) / chunk);
+    }
+    return worst;
+  };
   for (int l = 0; l < n_conv; ++l) {
-    if (Z.conv[l].n_own < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX) Z.conv[l].o_tab_fwd = take(3 * WG);
-    if (l >= 1 && Z.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX)
+    const long long free_now = (long long)FLOW_LDS_FLOATS_MAX - off;
+    if (Z.conv[l].n_own < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX &&
+        pull_passes(free_now - 3 * WG) == pull_passes(free_now))
+      Z.conv[l].o_tab_fwd = take(3 * WG);
+    const long long free_then = (long long)FLOW_LDS_FLOATS_MAX - off;
+    if (l >= 1 && Z.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX &&
+        pull_passes(free_then - 3 * WG) == pull_passes(free_then))
       Z.conv[l].o_tab_pull = take(3 * WG);
   }
   // the zero-bordered delta maps of the pull: the more fit, the fewer passes
