@@ -264,8 +264,47 @@ int cnn_get_stage_times(cnn_t* net, float* host_us, int max_stages, int* n_stage
  * host_grad receives cnn_num_weights floats in canonical order; weights are unchanged. */
 int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad);
 
+/* ---- on-line deformation of training images --------------------------------------------------
+ * Sec. 4.1: every presentation of a training image is deformed anew by a combination of affine maps
+ * (translation, rotation, scaling, horizontal shearing) and an elastic deformation (Simard et al. 2003);
+ * Sec. 4.2 and 4.3: random translations of at most 5 % of the image side.  The paper gives no formulas;
+ * what this call computes, with every range a parameter:
+ *   presentation t = first_index + k of the stream (output image k; all C maps share one deformation)
+ *   draws: mix64(key + G (j + 1)), key = mix64(seed + G (t + 1)), mix64 = SplitMix64's output function,
+ *          G = 0x9E3779B97F4A7C15; a 32-bit half b of a draw gives sym(b) = 2 (b >> 8) / 2^24 - 1
+ *   draw 0: tx = sym(hi) max_translation W, ty = sym(lo) max_translation H          (pixels)
+ *   draw 1: theta = sym(hi) max_rotation (degrees), shear = sym(lo) max_shear
+ *   draw 2: sx = 1 + sym(hi) max_scaling, sy = 1 + sym(lo) max_scaling
+ *   draw 3 + y W + x: the two random fields rx[y][x] = sym(hi), ry[y][x] = sym(lo)
+ *   Dx = alpha (g (x) g) * rx, Dy likewise: g[i] = exp(-i^2 / (2 sigma^2)), |i| <= ceil(3 sigma), normalised to
+ *          sum 1; the fields are zero outside the image; sigma == 0 or alpha == 0: no elastic part
+ *   A = Rot(theta) [[1, shear], [0, 1]] diag(sx, sy) about the centre ((W-1)/2, (H-1)/2)
+ *   output pixel (y, x) is the source map sampled at (cx + A (x - cx, y - cy) + (tx, ty) + (Dx, Dy)[y][x]) by
+ *   bilinear interpolation; a neighbour outside the map counts as `fill`.
+ * The result depends on (seed, t) only, not on how presentations are grouped into calls.
+ *
+ * d_src: device, n_src images [C][H][W] (fp32, contiguous); d_dst: device, n images, must not overlap d_src.
+ * d_src_index (device, n int32, or NULL): source image of every output; NULL means output k is image k
+ * (then n <= n_src); an entry outside [0, n_src) gives an image of `fill`.  d_displacement (device,
+ * [n][2][H][W], or NULL): receives, per output pixel, its source position minus its own (x, then y).
+ * hip_stream: a hipStream_t (NULL: the default stream).  Asynchronous; nothing is allocated; the caller owns
+ * every buffer.  Limits: H W <= 9216, C <= 1024, sigma <= 16, max_scaling < 1, ranges >= 0 and finite.
+ * Errors: CNN_E_ARG, CNN_E_SHAPE, CNN_E_HIP; the message is cnn_last_error(NULL)'s. */
+typedef struct cnn_deform_params {
+  float max_translation; /* fraction of the image side                                   */
+  float max_rotation;    /* degrees                                                      */
+  float max_scaling;     /* fraction: factors in [1 - m, 1 + m), x and y independently   */
+  float max_shear;       /* horizontal shear coefficient: x += shear * y                 */
+  float sigma;           /* std of the smoothing Gaussian, pixels                        */
+  float alpha;           /* amplitude of the elastic part, pixels                        */
+  float fill;            /* value outside the source image                               */
+} cnn_deform_params;
+int cnn_deform_images(void* hip_stream, const float* d_src, size_t n_src, float* d_dst, size_t n, int C, int H, int W,
+                      const cnn_deform_params* p, uint64_t seed, uint64_t first_index,
+                      const int32_t* d_src_index, float* d_displacement);
+
 /* Message for the last error on this handle (or, with net == NULL, of the last failed
- * cnn_create / cnn_workspace_bytes / cnn_arch_info on this thread).  Never NULL. */
+ * cnn_create / cnn_workspace_bytes / cnn_arch_info / cnn_deform_images on this thread).  Never NULL. */
 const char* cnn_last_error(const cnn_t* net);
 
 #ifdef __cplusplus

@@ -42,6 +42,7 @@ def lib():
             "cnn_get_plan_text": (C.c_int, [vp, vp, sz]),
             "cnn_create": (C.c_int, [C.c_char_p, vp, sz, vp, vp]),
             "cnn_destroy": (None, [vp]),
+            "cnn_deform_images": (C.c_int, [vp, vp, sz, vp, sz, C.c_int, C.c_int, C.c_int, vp, C.c_uint64, C.c_uint64, vp, vp]),
             "cnn_set_connection_table": (C.c_int, [vp, C.c_int, vp]),
             "cnn_set_fixed_frontend": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, vp, vp]),
             "cnn_num_weights": (sz, [vp]),
@@ -92,12 +93,42 @@ EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_get_pla
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
            "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
-           "cnn_last_error"]
+           "cnn_deform_images", "cnn_last_error"]
 
 
 def _err(handle=None):
     m = lib().cnn_last_error(handle)
     return m.decode() if m else ""
+
+
+class DeformParams(C.Structure):
+    """cnn_deform_params of the header, field for field."""
+    _fields_ = [("max_translation", C.c_float), ("max_rotation", C.c_float), ("max_scaling", C.c_float),
+                ("max_shear", C.c_float), ("sigma", C.c_float), ("alpha", C.c_float), ("fill", C.c_float)]
+
+
+def deform_images(d_src, d_dst, n, params, seed, first_index, d_src_index=None, d_displacement=None, stream=None):
+    """cnn_deform_images: d_src [n_src][C][H][W] and d_dst [>= n][C][H][W] float32 device tensors; params a
+    DeformParams (or None: NULL); d_src_index an int32 device tensor of n entries or None; d_displacement a
+    float32 device tensor [n][2][H][W] or None.  Asynchronous on `stream` (a torch stream; None: the current)."""
+    import torch
+    for t in (d_src, d_dst):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.dim() == 4
+    n_src, Cc, H, W = d_src.shape
+    assert tuple(d_dst.shape[1:]) == (Cc, H, W) and d_dst.shape[0] >= n
+    if d_src_index is not None:
+        assert d_src_index.is_cuda and d_src_index.dtype == torch.int32 and d_src_index.is_contiguous()
+        assert d_src_index.numel() >= n
+    if d_displacement is not None:
+        assert d_displacement.is_cuda and d_displacement.dtype == torch.float32 and d_displacement.is_contiguous()
+        assert d_displacement.numel() >= n * 2 * H * W
+    st = (stream or torch.cuda.current_stream(d_src.device)).cuda_stream
+    rc = lib().cnn_deform_images(st, d_src.data_ptr(), int(n_src), d_dst.data_ptr(), int(n), int(Cc), int(H), int(W),
+                                 C.addressof(params) if params is not None else None, int(seed), int(first_index),
+                                 d_src_index.data_ptr() if d_src_index is not None else None,
+                                 d_displacement.data_ptr() if d_displacement is not None else None)
+    if rc:
+        raise CnnError(rc, "cnn_deform_images", _err())
 
 
 def arch_info(arch):

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcnn355.so")
-SOURCES = ["cnn355_kernels.hip", "cnn355_flow.hip", "cnn355_batch.hip", "cnn355_api.hip"]
+SOURCES = ["cnn355_kernels.hip", "cnn355_flow.hip", "cnn355_batch.hip", "cnn355_deform.hip", "cnn355_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-FP32 instructions are switched off on purpose: some of their forms have given wrong
 # results on this hardware, without any error

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cctype>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -33,6 +34,8 @@ hipError_t launch_batch_pool(hipStream_t stream, const BatchPool& q);
 hipError_t launch_batch_outputs(hipStream_t stream, const float* logits, float* probs, long long n_images,
                                 int n_classes, int out_units);
 hipError_t launch_batch_pack(hipStream_t stream, const BatchPack& q, long long wt_floats);
+hipError_t launch_deform(hipStream_t stream, const DeformJob& J);
+size_t deform_lds_bytes(const DeformJob& J);
 }  // namespace cnn355
 
 using namespace cnn355;
@@ -1485,6 +1488,48 @@ int cnn_forward_batch_scratch_bytes(cnn_t* net, size_t batch, size_t* bytes) {
   int rc = batch_plan(net, batch, B);
   if (rc) return rc;
   *bytes = B.floats(batch) * sizeof(float);
+  return CNN_OK;
+}
+
+int cnn_deform_images(void* hip_stream, const float* d_src, size_t n_src, float* d_dst, size_t n, int C, int H, int W,
+                      const cnn_deform_params* p, uint64_t seed, uint64_t first_index,
+                      const int32_t* d_src_index, float* d_displacement) {
+  if (n == 0) return CNN_OK;
+  if (n_src == 0 || n_src > 0x7fffffffull || (!d_src_index && n > n_src))
+    return fail(nullptr, CNN_E_ARG, "cnn_deform_images: more outputs than source images and no index list, or no source images");
+  if (!d_src || !d_dst || !p) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: NULL argument");
+  if (d_src == d_dst) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: source and destination must not overlap");
+  if (C < 1 || H < 1 || W < 1 || (long long)H * W > DEFORM_MAX_PIXELS || C > 1024)
+    return fail(nullptr, CNN_E_SHAPE, "cnn_deform_images: maps of 1 to 9216 pixels, 1 to 1024 maps per image");
+  if (n > (size_t)1 << 40) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: too many images");
+  const float ranges[6] = {p->max_translation, p->max_rotation, p->max_scaling, p->max_shear, p->sigma, p->fill};
+  for (float r : ranges)
+    if (!std::isfinite(r)) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: a parameter is not finite");
+  if (!std::isfinite(p->alpha)) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: a parameter is not finite");
+  if (p->max_translation < 0 || p->max_rotation < 0 || p->max_scaling < 0 || p->max_shear < 0 || p->sigma < 0)
+    return fail(nullptr, CNN_E_ARG, "cnn_deform_images: a range or sigma is negative");
+  if (p->max_scaling >= 1.0f) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: max_scaling must be below 1");
+  if (p->sigma > 16.0f) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: sigma above 16 pixels");
+  DeformJob J;
+  J.src = d_src; J.dst = d_dst; J.disp = d_displacement; J.src_index = d_src_index;
+  J.n = (long long)n; J.n_src = (long long)n_src; J.C = C; J.H = H; J.W = W;
+  J.max_tx = (float)((double)p->max_translation * W);
+  J.max_ty = (float)((double)p->max_translation * H);
+  J.max_rot = (float)((double)p->max_rotation * 3.14159265358979323846 / 180.0);
+  J.max_shear = p->max_shear; J.max_scale = p->max_scaling; J.alpha = p->alpha; J.fill = p->fill;
+  J.seed = seed; J.first_index = first_index;
+  J.R = -1;
+  for (float& t : J.taps) t = 0.f;
+  if (p->sigma > 0.f && p->alpha != 0.f) {
+    const double sg = p->sigma;
+    const int R = (int)std::ceil(3.0 * sg);
+    double g[2 * DEFORM_MAX_R + 1], sum = 0;
+    for (int i = -R; i <= R; ++i) sum += g[i + R] = std::exp(-(double)i * i / (2.0 * sg * sg));
+    for (int i = 0; i <= 2 * R; ++i) J.taps[i] = (float)(g[i] / sum);
+    J.R = R;
+  }
+  hipError_t e = launch_deform((hipStream_t)hip_stream, J);
+  if (e != hipSuccess) return fail(nullptr, CNN_E_HIP, std::string("cnn_deform_images: ") + hipGetErrorString(e));
   return CNN_OK;
 }
 

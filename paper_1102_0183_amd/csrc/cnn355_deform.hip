@@ -1,0 +1,143 @@
+// On-line deformation of training images (Sec. 4.1: affine maps -- translation, rotation, scaling,
+// horizontal shearing -- combined with elastic deformations after Simard et al. 2003; Sec. 4.2, 4.3:
+// random translations), one workgroup per image.  It depends on no weight, so it runs fully parallel
+// over a batch of presentations ahead of the on-line training chain, on the same stream.
+//
+// Every random number is a function of (seed, presentation number, draw number) alone: mix64, the output
+// function of SplitMix64 (Steele, Lea, Flood 2014), applied to key + GOLDEN * (draw + 1), where the key
+// of a presentation is mix64(seed + GOLDEN * (presentation + 1)).  A draw's two 32-bit halves give two
+// numbers of 24 bits each, so the same values exist exactly in float and in double.
+#include <hip/hip_runtime.h>
+
+// device pointers of the job descriptor are global-address-space pointers in this translation unit
+#define CNN_GLOBAL __attribute__((address_space(1)))
+#include "cnn355_dev.h"
+
+namespace cnn355 {
+
+namespace {
+
+constexpr int DT = 256;  // threads per workgroup
+constexpr unsigned long long GOLDEN = 0x9E3779B97F4A7C15ull;
+
+__device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// 32 random bits -> [-1, 1) in steps of 2^-23
+__device__ __forceinline__ float sym(unsigned int bits) { return (float)(bits >> 8) * (2.0f / 16777216.0f) - 1.0f; }
+
+// One pass of the separable Gaussian along a line of `len` elements `step` apart: element `at`
+// of the result; elements outside the line count as zero.
+__device__ __forceinline__ float blur_at(const float* line, int at, int len, int step, const float* taps, int R) {
+  const int lo = max(-R, -at), hi = min(R, len - 1 - at);
+  float s = 0.f;
+  for (int i = lo; i <= hi; ++i) s = fmaf(taps[i + R], line[(at + i) * step], s);
+  return s;
+}
+
+__global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
+  extern __shared__ float lds[];
+  const int H = J.H, W = J.W, HW = H * W, R = J.R;
+  float* rx = lds;            // random fields, then the smoothed ones
+  float* ry = lds + HW;
+  float* hx = lds + 2 * HW;   // after the pass along rows
+  float* hy = lds + 3 * HW;
+  float* taps = lds + 4 * HW; // [2R + 1]
+  const int tid = threadIdx.x;
+  const bool elastic = R >= 0;
+  if (elastic) {
+    for (int i = tid; i <= 2 * R; i += DT) taps[i] = J.taps[i];
+  }
+  const float cx = 0.5f * (float)(W - 1), cy = 0.5f * (float)(H - 1);
+  for (long long k = blockIdx.x; k < J.n; k += gridDim.x) {
+    const unsigned long long key = mix64(J.seed + GOLDEN * (J.first_index + (unsigned long long)k + 1ull));
+    // ---- the affine part: displacement = (A - I) (u, v) + (tx, ty), A = Rot . Shear . Scale
+    const unsigned long long d0 = mix64(key + GOLDEN * 1ull), d1 = mix64(key + GOLDEN * 2ull), d2 = mix64(key + GOLDEN * 3ull);
+    const float tx = sym((unsigned int)(d0 >> 32)) * J.max_tx, ty = sym((unsigned int)d0) * J.max_ty;
+    const float theta = sym((unsigned int)(d1 >> 32)) * J.max_rot, sh = sym((unsigned int)d1) * J.max_shear;
+    const float sx = 1.0f + sym((unsigned int)(d2 >> 32)) * J.max_scale, sy = 1.0f + sym((unsigned int)d2) * J.max_scale;
+    float sn, cs;
+    sincosf(theta, &sn, &cs);
+    const float a00 = cs * sx - 1.0f, a01 = (cs * sh - sn) * sy, a10 = sn * sx, a11 = (sn * sh + cs) * sy - 1.0f;
+    // ---- the elastic part: two random fields, smoothed along rows, then along columns
+    if (elastic) {
+      __syncthreads();  // the previous image's fields have been read
+      for (int p = tid; p < HW; p += DT) {
+        const unsigned long long d = mix64(key + GOLDEN * (unsigned long long)(p + 4));
+        rx[p] = sym((unsigned int)(d >> 32));
+        ry[p] = sym((unsigned int)d);
+      }
+      __syncthreads();
+      for (int p = tid; p < HW; p += DT) {
+        const int y = p / W, x = p - y * W;
+        hx[p] = blur_at(rx + y * W, x, W, 1, taps, R);
+        hy[p] = blur_at(ry + y * W, x, W, 1, taps, R);
+      }
+      __syncthreads();
+      for (int p = tid; p < HW; p += DT) {
+        const int y = p / W, x = p - y * W;
+        rx[p] = blur_at(hx + x, y, H, W, taps, R);
+        ry[p] = blur_at(hy + x, y, H, W, taps, R);
+      }
+      __syncthreads();
+    }
+    // ---- sample the source
+    long long s = J.src_index ? (long long)J.src_index[k] : k;
+    const bool known = s >= 0 && s < J.n_src;  // an index that names no source image gives an image of `fill`
+    if (!known) s = 0;
+    const CNN_GLOBAL float* src = J.src + s * J.C * HW;
+    CNN_GLOBAL float* dst = J.dst + k * J.C * HW;
+    for (int p = tid; p < HW; p += DT) {
+      const int y = p / W, x = p - y * W;
+      const float u = (float)x - cx, v = (float)y - cy;
+      float dx = fmaf(a00, u, fmaf(a01, v, tx)), dy = fmaf(a10, u, fmaf(a11, v, ty));
+      if (elastic) {
+        dx = fmaf(J.alpha, rx[p], dx);
+        dy = fmaf(J.alpha, ry[p], dy);
+      }
+      if (J.disp) {
+        J.disp[(k * 2) * HW + p] = dx;
+        J.disp[(k * 2 + 1) * HW + p] = dy;
+      }
+      // far outside in any direction reads the fill value only; the clamp keeps the integers small
+      const float fdx = floorf(fminf(fmaxf(dx, -(float)(W + 2)), (float)(W + 2)));
+      const float fdy = floorf(fminf(fmaxf(dy, -(float)(H + 2)), (float)(H + 2)));
+      const float fx = fminf(fmaxf(dx - fdx, 0.f), 1.f), fy = fminf(fmaxf(dy - fdy, 0.f), 1.f);
+      const int x0 = x + (int)fdx, y0 = y + (int)fdy;
+      const bool in_x0 = x0 >= 0 && x0 < W, in_x1 = x0 + 1 >= 0 && x0 + 1 < W;
+      const bool in_y0 = y0 >= 0 && y0 < H, in_y1 = y0 + 1 >= 0 && y0 + 1 < H;
+      const int xa = min(max(x0, 0), W - 1), xb = min(max(x0 + 1, 0), W - 1);
+      const int ya = min(max(y0, 0), H - 1), yb = min(max(y0 + 1, 0), H - 1);
+      const float w00 = (1.f - fy) * (1.f - fx), w01 = (1.f - fy) * fx, w10 = fy * (1.f - fx), w11 = fy * fx;
+      for (int c = 0; c < J.C; ++c) {
+        const CNN_GLOBAL float* m = src + (long long)c * HW;
+        const float v00 = in_y0 && in_x0 ? m[ya * W + xa] : J.fill;
+        const float v01 = in_y0 && in_x1 ? m[ya * W + xb] : J.fill;
+        const float v10 = in_y1 && in_x0 ? m[yb * W + xa] : J.fill;
+        const float v11 = in_y1 && in_x1 ? m[yb * W + xb] : J.fill;
+        dst[(long long)c * HW + p] = known ? fmaf(w00, v00, fmaf(w01, v01, fmaf(w10, v10, w11 * v11))) : J.fill;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+size_t deform_lds_bytes(const DeformJob& J) {
+  return J.R >= 0 ? ((size_t)4 * J.H * J.W + 2 * J.R + 1) * sizeof(float) : 0;
+}
+
+hipError_t launch_deform(hipStream_t stream, const DeformJob& J) {
+  if (J.n <= 0) return hipSuccess;
+  const size_t lds = deform_lds_bytes(J);
+  hipError_t e = hipFuncSetAttribute((const void*)k_deform, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  const unsigned int grid = (unsigned int)(J.n < 8192 ? J.n : 8192);
+  hipLaunchKernelGGL(k_deform, dim3(grid), dim3(DT), lds, stream, J);
+  return hipGetLastError();
+}
+
+}  // namespace cnn355

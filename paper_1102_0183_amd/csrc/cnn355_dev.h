@@ -232,4 +232,23 @@ struct BatchPack {
   int is_fc, full_table, Mi, Mo, K, n_in, MoPad;
 };
 
+// ---- on-line deformation of training images ---------------------------------------------------
+constexpr int DEFORM_MAX_R = 48;          // taps reach 48 pixels either way (sigma up to 16)
+constexpr int DEFORM_MAX_PIXELS = 9216;   // rows x columns of one map: four float planes of it fit in LDS
+
+struct DeformJob {
+  const CNN_GLOBAL float* src;      // [..][C][H][W]
+  CNN_GLOBAL float* dst;            // [n][C][H][W]
+  CNN_GLOBAL float* disp;           // [n][2][H][W] (x, then y displacement of every pixel's source), or null
+  const CNN_GLOBAL int* src_index;  // [n] source image of every output, or null: output k comes from image k
+  long long n, n_src;
+  int C, H, W;
+  int R;                            // taps on either side of the Gaussian's centre; -1: no elastic part
+  float max_tx, max_ty;             // pixels
+  float max_rot;                    // radians
+  float max_shear, max_scale, alpha, fill;
+  unsigned long long seed, first_index;
+  float taps[2 * DEFORM_MAX_R + 1]; // normalised to sum 1
+};
+
 }  // namespace cnn355

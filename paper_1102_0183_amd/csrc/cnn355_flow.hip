@@ -658,7 +658,6 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
   DECL_SPEC(Z, *rt.sh);
   const ConvSpec& C = Z.conv[l];
   float* lds = rt.lds;
-  const int tid = threadIdx.x;
   const JobStat S = fwd_job(Z, l);
   const JobDyn D = rt.sh->fwd[l];
   const int nm = D.n_maps;
