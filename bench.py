@@ -257,6 +257,37 @@ def main():
             extra[key + "_forward_batch_fp32_mfma_frac"] = round(tf / FP32_MFMA_PEAK_TFLOPS, 4)
             del scratch, d_probs
             net.close()
+        # on-line deformation of the training stream (Sec. 4.1): the whole stream in one call, then training with
+        # every launch's images deformed just ahead of it on the same stream
+        gp = binding.DeformParams(**synth.DEFORM_RECIPE)
+        d_src4 = d_imgs.view(n_stream, *wl.raw_shape)
+        d_def = torch.empty_like(d_src4)
+        binding.deform_images(d_src4, d_def, n_stream, gp, synth.DEFORM_SEED, 0)
+        torch.cuda.synchronize()
+        best = None
+        for r in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            binding.deform_images(d_src4, d_def, n_stream, gp, synth.DEFORM_SEED, (r + 1) * n_stream)
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        assert torch.isfinite(d_def).all()
+        extra["cfg2a_deform_images_per_s"] = round(n_stream / (best * 1e-3), 1)
+        extra["cfg2a_deform_hbm_frac"] = round(2 * 4 * int(np.prod(wl.raw_shape)) * n_stream / (best * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        net = make_net(wl, args.grid)
+        sz = net.image_size
+        buf = torch.empty((B,) + tuple(wl.raw_shape), dtype=torch.float32, device=dev)
+
+        def deformed_step(k):
+            o = (k % per_epoch) * B
+            binding.deform_images(d_src4[o:o + B], buf, B, gp, synth.DEFORM_SEED, k * B)
+            net.train_many(buf.view(-1), d_labs[o:o + B], wl.lr, n=B)
+        wall, kms = time_steps(torch, deformed_step, k_steps, 2)
+        extra["cfg2a_train_with_deformation_images_per_s"] = round(k_steps * B / wall, 1)
+        net.close()
+        del d_def, buf
         # the other benchmark networks, each in the mode that runs it fastest: on-line training of 400 seeded
         # images (one launch per stage: wide layers on the matrix cores; cfg5 fits the resident kernel)
         for key, mode_o in (("cfg3", binding.MODE_STAGES), ("cfg4a", binding.MODE_STAGES),

@@ -288,7 +288,7 @@ int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* 
  * (then n <= n_src); an entry outside [0, n_src) gives an image of `fill`.  d_displacement (device,
  * [n][2][H][W], or NULL): receives, per output pixel, its source position minus its own (x, then y).
  * hip_stream: a hipStream_t (NULL: the default stream).  Asynchronous; nothing is allocated; the caller owns
- * every buffer.  Limits: H W <= 9216, C <= 1024, sigma <= 16, max_scaling < 1, ranges >= 0 and finite.
+ * every buffer.  Limits: H x (W rounded up to odd) <= 9312 (so 96 x 96 fits), C <= 1024, sigma <= 16, max_scaling < 1, ranges >= 0 and finite.
  * Errors: CNN_E_ARG, CNN_E_SHAPE, CNN_E_HIP; the message is cnn_last_error(NULL)'s. */
 typedef struct cnn_deform_params {
   float max_translation; /* fraction of the image side                                   */

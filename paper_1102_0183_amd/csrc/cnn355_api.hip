@@ -1499,8 +1499,8 @@ int cnn_deform_images(void* hip_stream, const float* d_src, size_t n_src, float*
     return fail(nullptr, CNN_E_ARG, "cnn_deform_images: more outputs than source images and no index list, or no source images");
   if (!d_src || !d_dst || !p) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: NULL argument");
   if (d_src == d_dst) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: source and destination must not overlap");
-  if (C < 1 || H < 1 || W < 1 || (long long)H * W > DEFORM_MAX_PIXELS || C > 1024)
-    return fail(nullptr, CNN_E_SHAPE, "cnn_deform_images: maps of 1 to 9216 pixels, 1 to 1024 maps per image");
+  if (C < 1 || H < 1 || W < 1 || (long long)H * (W | 1) > DEFORM_MAX_PIXELS || C > 1024)
+    return fail(nullptr, CNN_E_SHAPE, "cnn_deform_images: rows x (columns rounded up to odd) at most 9312 (96 x 96), 1 to 1024 maps per image");
   if (n > (size_t)1 << 40) return fail(nullptr, CNN_E_ARG, "cnn_deform_images: too many images");
   const float ranges[6] = {p->max_translation, p->max_rotation, p->max_scaling, p->max_shear, p->sigma, p->fill};
   for (float r : ranges)

@@ -29,27 +29,53 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
 // 32 random bits -> [-1, 1) in steps of 2^-23
 __device__ __forceinline__ float sym(unsigned int bits) { return (float)(bits >> 8) * (2.0f / 16777216.0f) - 1.0f; }
 
-// One pass of the separable Gaussian along a line of `len` elements `step` apart: element `at`
-// of the result; elements outside the line count as zero.
-__device__ __forceinline__ float blur_at(const float* line, int at, int len, int step, const float* taps, int R) {
-  const int lo = max(-R, -at), hi = min(R, len - 1 - at);
-  float s = 0.f;
-  for (int i = lo; i <= hi; ++i) s = fmaf(taps[i + R], line[(at + i) * step], s);
-  return s;
+constexpr int SW = 4;    // outputs of one lane along the line being smoothed
+
+// One pass of the separable Gaussian over both fields: the lane's SW outputs out[k], k = at .. at + SW - 1,
+// of the line starting at `ax` / `ay` (elements `step` apart, `len` of them; outside counts as zero).  The loop
+// runs over the source elements that reach any of the outputs; the tap that links source j to output k is
+// tp[j - k]: as j advances the SW taps in use slide by one, so an iteration reads one tap and one element of
+// each field for 2 * SW multiply-adds.  tp points at the centre tap; R + SW zeros lie on either side of the taps.
+__device__ __forceinline__ void blur_strip(const float* ax, const float* ay, int at, int len, int step, const float* tp,
+                                           int R, float (&ox)[SW], float (&oy)[SW]) {
+  const int jlo = max(0, at - R), jhi = min(len - 1, at + SW - 1 + R);
+  float t[SW];
+#pragma unroll
+  for (int o = 0; o < SW; ++o) {
+    ox[o] = 0.f;
+    oy[o] = 0.f;
+    t[o] = tp[jlo - 1 - (at + o)];  // the taps of the element before the first
+  }
+  for (int j = jlo; j <= jhi; ++j) {
+#pragma unroll
+    for (int o = SW - 1; o > 0; --o) t[o] = t[o - 1];  // tp[j - (at + o)] = what output o - 1 used one element ago
+    t[0] = tp[j - at];
+    const float vx = ax[j * step], vy = ay[j * step];
+#pragma unroll
+    for (int o = 0; o < SW; ++o) {
+      ox[o] = fmaf(t[o], vx, ox[o]);
+      oy[o] = fmaf(t[o], vy, oy[o]);
+    }
+  }
 }
 
 __global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
   extern __shared__ float lds[];
   const int H = J.H, W = J.W, HW = H * W, R = J.R;
-  float* rx = lds;            // random fields, then the smoothed ones
-  float* ry = lds + HW;
-  float* hx = lds + 2 * HW;   // after the pass along rows
-  float* hy = lds + 3 * HW;
-  float* taps = lds + 4 * HW; // [2R + 1]
+  const int Wp = W | 1;       // odd row pitch: lanes on consecutive rows fall on different LDS banks
+  float* rx = lds;            // [H][Wp] random fields, then the smoothed ones
+  float* ry = lds + H * Wp;
+  float* hx = lds + 2 * H * Wp;   // after the pass along rows
+  float* hy = lds + 3 * H * Wp;
+  float* taps = lds + 4 * H * Wp; // [R + SW zeros][2R + 1 taps][R + SW zeros]
+  const float* tp = taps + 2 * R + SW;  // the centre tap
   const int tid = threadIdx.x;
   const bool elastic = R >= 0;
   if (elastic) {
-    for (int i = tid; i <= 2 * R; i += DT) taps[i] = J.taps[i];
+    for (int i = tid; i < 4 * R + 2 * SW + 1; i += DT) {
+      const int q = i - (R + SW);
+      taps[i] = q >= 0 && q <= 2 * R ? J.taps[q] : 0.f;
+    }
   }
   const float cx = 0.5f * (float)(W - 1), cy = 0.5f * (float)(H - 1);
   for (long long k = blockIdx.x; k < J.n; k += gridDim.x) {
@@ -65,22 +91,37 @@ __global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
     // ---- the elastic part: two random fields, smoothed along rows, then along columns
     if (elastic) {
       __syncthreads();  // the previous image's fields have been read
-      for (int p = tid; p < HW; p += DT) {
-        const unsigned long long d = mix64(key + GOLDEN * (unsigned long long)(p + 4));
-        rx[p] = sym((unsigned int)(d >> 32));
-        ry[p] = sym((unsigned int)d);
+      unsigned long long ctr = key + GOLDEN * (unsigned long long)(tid + 4);
+      for (int p = tid; p < HW; p += DT, ctr += GOLDEN * (unsigned long long)DT) {
+        const unsigned long long d = mix64(ctr);
+        const int y = p / W, x = p - y * W;
+        rx[y * Wp + x] = sym((unsigned int)(d >> 32));
+        ry[y * Wp + x] = sym((unsigned int)d);
       }
       __syncthreads();
-      for (int p = tid; p < HW; p += DT) {
-        const int y = p / W, x = p - y * W;
-        hx[p] = blur_at(rx + y * W, x, W, 1, taps, R);
-        hy[p] = blur_at(ry + y * W, x, W, 1, taps, R);
+      const int nsx = (W + SW - 1) / SW, nsy = (H + SW - 1) / SW;
+      for (int it = tid; it < H * nsx; it += DT) {  // along rows; consecutive lanes take consecutive rows
+        const int s = it / H, y = it - s * H, x0 = s * SW;
+        float ox[SW], oy[SW];
+        blur_strip(rx + y * Wp, ry + y * Wp, x0, W, 1, tp, R, ox, oy);
+#pragma unroll
+        for (int o = 0; o < SW; ++o)
+          if (x0 + o < W) {
+            hx[y * Wp + x0 + o] = ox[o];
+            hy[y * Wp + x0 + o] = oy[o];
+          }
       }
       __syncthreads();
-      for (int p = tid; p < HW; p += DT) {
-        const int y = p / W, x = p - y * W;
-        rx[p] = blur_at(hx + x, y, H, W, taps, R);
-        ry[p] = blur_at(hy + x, y, H, W, taps, R);
+      for (int it = tid; it < W * nsy; it += DT) {  // along columns; consecutive lanes take consecutive columns
+        const int s = it / W, x = it - s * W, y0 = s * SW;
+        float ox[SW], oy[SW];
+        blur_strip(hx + x, hy + x, y0, H, Wp, tp, R, ox, oy);
+#pragma unroll
+        for (int o = 0; o < SW; ++o)
+          if (y0 + o < H) {
+            rx[(y0 + o) * Wp + x] = ox[o];
+            ry[(y0 + o) * Wp + x] = oy[o];
+          }
       }
       __syncthreads();
     }
@@ -95,8 +136,8 @@ __global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
       const float u = (float)x - cx, v = (float)y - cy;
       float dx = fmaf(a00, u, fmaf(a01, v, tx)), dy = fmaf(a10, u, fmaf(a11, v, ty));
       if (elastic) {
-        dx = fmaf(J.alpha, rx[p], dx);
-        dy = fmaf(J.alpha, ry[p], dy);
+        dx = fmaf(J.alpha, rx[y * Wp + x], dx);
+        dy = fmaf(J.alpha, ry[y * Wp + x], dy);
       }
       if (J.disp) {
         J.disp[(k * 2) * HW + p] = dx;
@@ -127,7 +168,7 @@ __global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
 }  // namespace
 
 size_t deform_lds_bytes(const DeformJob& J) {
-  return J.R >= 0 ? ((size_t)4 * J.H * J.W + 2 * J.R + 1) * sizeof(float) : 0;
+  return J.R >= 0 ? ((size_t)4 * J.H * (J.W | 1) + 4 * J.R + 2 * SW + 1) * sizeof(float) : 0;
 }
 
 hipError_t launch_deform(hipStream_t stream, const DeformJob& J) {

@@ -234,7 +234,7 @@ struct BatchPack {
 
 // ---- on-line deformation of training images ---------------------------------------------------
 constexpr int DEFORM_MAX_R = 48;          // taps reach 48 pixels either way (sigma up to 16)
-constexpr int DEFORM_MAX_PIXELS = 9216;   // rows x columns of one map: four float planes of it fit in LDS
+constexpr int DEFORM_MAX_PIXELS = 9312;   // rows x (columns rounded up to odd) of one map: four float planes of it fit in LDS
 
 struct DeformJob {
   const CNN_GLOBAL float* src;      // [..][C][H][W]

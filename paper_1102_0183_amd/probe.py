@@ -4,6 +4,7 @@
     python3 paper_1102_0183_amd/probe.py --workload cfg4b --mode stages --images 200 --calls 1
     python3 paper_1102_0183_amd/probe.py --workload cfg2a --mode resident --images 1000 --calls 3 --copy-calibration
     python3 paper_1102_0183_amd/probe.py --workload cfg2a --forward --batch 4096 --images 16384 --calls 3
+    python3 paper_1102_0183_amd/probe.py --workload cfg2a --deform --images 60000 --calls 5
 
 --copy-calibration first runs a 256 MiB device-to-device copy three times, so that a counter
 collected in the same run (FETCH_SIZE, WRITE_SIZE) can be scaled by what it reads for a
@@ -27,6 +28,8 @@ def main():
     ap.add_argument("--forward", action="store_true", help="forward-only calls instead of training")
     ap.add_argument("--batch", type=int, default=0,
                     help="with --forward: cnn_forward_batch with this many images in flight")
+    ap.add_argument("--deform", action="store_true",
+                    help="instead of the network: cnn_deform_images over --images images of the workload, --calls times")
     ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
 
@@ -43,6 +46,15 @@ def main():
         torch.cuda.synchronize()
     wl = synth.WORKLOADS[args.workload]
     n = args.images
+    if args.deform:
+        d_src = torch.from_numpy(synth.images(wl, n)).to("cuda:0")
+        d_dst = torch.empty_like(d_src)
+        gp = binding.DeformParams(**synth.DEFORM_RECIPE)
+        for r in range(args.calls):
+            binding.deform_images(d_src, d_dst, n, gp, synth.DEFORM_SEED, r * n)
+        torch.cuda.synchronize()
+        print("probe done: %s, %d calls deforming %d images" % (args.workload, args.calls, n), flush=True)
+        return
     imgs, labs = synth.images(wl, n * args.calls), synth.labels(wl, n * args.calls)
     d_imgs = torch.from_numpy(imgs).to("cuda:0")
     d_labs = torch.from_numpy(labs).to("cuda:0")

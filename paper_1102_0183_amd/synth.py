@@ -55,6 +55,14 @@ WORKLOADS = {
 }
 
 
+# Ranges of the on-line deformation the measurements and full-size tests use (Sec. 4.1 names the ingredients and
+# gives no ranges): up to 5 % translation (Sec. 4.2), 15 degrees, 15 % scaling, 0.15 shear, an elastic field of
+# std about one pixel (sigma 6, alpha 36); -1 outside the image.  Seed of the draws: SEED0 + 60.
+DEFORM_RECIPE = dict(max_translation=0.05, max_rotation=15.0, max_scaling=0.15, max_shear=0.15, sigma=6.0, alpha=36.0,
+                     fill=-1.0)
+DEFORM_SEED = SEED0 + 60
+
+
 def images(wl: Workload, n: Optional[int] = None) -> np.ndarray:
     """First n images of the workload's stream, float32 [n, C, H, W].
 

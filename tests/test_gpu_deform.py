@@ -6,14 +6,14 @@ import numpy as np
 import pytest
 
 from oracle import deform_oracle as DO
-from paper_1102_0183_amd import binding
+from paper_1102_0183_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
 
-SEED = 11020183 + 60
+SEED = synth.DEFORM_SEED
 TOL = 1e-5
 
-ALL = dict(max_translation=0.05, max_rotation=15.0, max_scaling=0.15, max_shear=0.15, sigma=6.0, alpha=36.0, fill=-1.0)
+ALL = dict(synth.DEFORM_RECIPE)
 CASES = [
     # C, H, W, images, parameters
     (1, 29, 29, 40, ALL),                                                        # the benchmark stream's shape
