@@ -483,9 +483,11 @@ __device__ __forceinline__ float pixel_mac_k(int K, const float* in, const float
 // A tile of TH rows x SW consecutive output pixels (unit stride).  Per connection the K*K weights
 // are read once; every input row of SW+K-1 floats is read once and feeds the (up to K) kernel rows
 // and (up to TH) output rows it meets: (TH+K-1)(SW+K-1) + K*K LDS reads for TH*SW*K*K multiply-adds.
-template <int K, int SW, int TH>
+// CLIP: only the input rows iy in [iy_lo, iy_hi) are read; the others are known to hold zeros.
+template <int K, int SW, int TH, bool CLIP>
 __device__ __forceinline__ void strip_mac(const float* in, const float* w, const int* idx, int idx_off, int c0,
-                                          int cstep, int nc, int map_sz, int Wi, int base, float (&acc)[TH * SW]) {
+                                          int cstep, int nc, int map_sz, int Wi, int base, int iy_lo, int iy_hi,
+                                          float (&acc)[TH * SW]) {
   for (int c = c0; c < nc; c += cstep) {
     const float* ip = in + (idx[c] - idx_off) * map_sz + base;
     const float* wp = w + c * (K * K);
@@ -494,6 +496,7 @@ __device__ __forceinline__ void strip_mac(const float* in, const float* w, const
     for (int t = 0; t < K * K; ++t) wk[t] = wp[t];
 #pragma unroll
     for (int iy = 0; iy < TH + K - 1; ++iy) {
+      if (CLIP && (iy < iy_lo || iy >= iy_hi)) continue;
       float row[SW + K - 1];
 #pragma unroll
       for (int i = 0; i < SW + K - 1; ++i) row[i] = ip[iy * Wi + i];
@@ -528,6 +531,11 @@ struct JobStat {  // the part of a job the plan fixes
   int variant;          // (TH - 1) * 64 + SW * 8 + K for a job in tiles of TH rows x SW pixels, 0: one pixel per
                         // lane (any K, any stride)
   int table;            // LDS offset of the lane table [3][WG] (int), or -1
+  int band_lo, band_hi; // rows [band_lo, band_hi) of an input map that can hold non-zeros; outside lie the zero
+                        // borders of the pull's delta maps (FP: the whole map)
+  int ways_side_by_side; // lanes that share a unit are neighbours, so that a wavefront's lanes skip the same rows
+                        // (they then read different maps and filters at once: map_sz and K * K must be odd
+                        // to spread those reads over the LDS banks)
 };
 __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
   const ConvSpec& C = Z.conv[l];
@@ -537,6 +545,7 @@ __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
   S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn; S.plan_cnt = C.max_conn;
   S.variant = C.fwd_strip ? (C.fwd_rows - 1) * 64 + C.fwd_strip * 8 + C.K : 0;
   S.table = C.o_tab_fwd;
+  S.band_lo = 0; S.band_hi = C.Hi; S.ways_side_by_side = 0;
   return S;
 }
 __device__ __forceinline__ JobStat pull_job(const FlowSpec& Z, int l) {
@@ -544,11 +553,12 @@ __device__ __forceinline__ JobStat pull_job(const FlowSpec& Z, int l) {
   JobStat S;
   S.in = Z.o_scratch; S.w = C.o_wb; S.idx = C.o_bj; S.cnt = C.o_ncb;
   S.w_pitch = C.max_back; S.Ho = C.Hi; S.Wo = C.Wi; S.K = C.K; S.stride = 1;
-  S.Wi = C.Wi + C.K - 1; S.map_sz = (C.Hi + C.K - 1) * (C.Wi + C.K - 1);
+  S.Wi = C.Wi + C.K - 1; S.map_sz = (int)flow_border_map(C.Hi, C.Wi, C.K);
   S.max_cnt = min(C.max_back, C.pull_chunk);
   S.plan_cnt = min(C.max_back, C.Mo);
   S.variant = C.pull_strip ? (C.pull_rows - 1) * 64 + C.pull_strip * 8 + C.K : 0;
   S.table = C.o_tab_pull;
+  S.band_lo = C.K - 1; S.band_hi = C.K - 1 + (C.Ho - 1) * (C.S + 1) + 1; S.ways_side_by_side = C.K & 1;
   return S;
 }
 
@@ -575,9 +585,16 @@ __device__ __forceinline__ Lane lane_decode(const JobStat& S, const JobDyn& D, i
   Lane ln;
   const int u = pass * WG + (int)threadIdx.x;
   ln.on = u < D.U * D.R;
-  const FDiv dU(D.U);
-  ln.r = dU.div(u);
-  const int v = u - ln.r * D.U;
+  int v;
+  if (S.ways_side_by_side) {
+    const FDiv dR(D.R);
+    v = dR.div(u);
+    ln.r = u - v * D.R;
+  } else {
+    const FDiv dU(D.U);
+    ln.r = dU.div(u);
+    v = u - ln.r * D.U;
+  }
   ln.nrows = 1;
   if (SW) {
     const int NS = (S.Wo + SW - 1) / SW, NG = (S.Ho + TH - 1) / TH;
@@ -641,15 +658,19 @@ __device__ __forceinline__ void job_dispatch(int variant, Fn f) {
 }
 
 // acc[] += the lane's share of connections [e_lo, e_hi) of its map (maps numbered from idx_off)
-template <int K, int SW, int TH>
+template <int K, int SW, int TH, bool CLIP>
 __device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* lds, const Lane& ln, int e_lo, int e_hi,
                                         int idx_off, float (&acc)[TH * SW]) {
   const float* w = lds + S.w + (ln.am * S.w_pitch) * (S.K * S.K);
   const int* idx = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
   if constexpr (K == 0)
     acc[0] += pixel_mac_k(S.K, lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base);
-  else
-    strip_mac<K, SW, TH>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, acc);
+  else if constexpr (CLIP) {
+    const int y = ln.pix / S.Wo;  // first output row of the tile = first input row it reads
+    strip_mac<K, SW, TH, true>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base,
+                               S.band_lo - y, S.band_hi - y, acc);
+  } else
+    strip_mac<K, SW, TH, false>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, 0, 0, acc);
 }
 
 // ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
@@ -674,7 +695,7 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
 #pragma unroll
       for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
       if (ln.on) {
-        job_mac<K, SW, TH>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
+        job_mac<K, SW, TH, false>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
         if (D.R == 1) {  // unsplit: the finished sums go straight through the activation function
           const float b = bf[ln.am];
           float* dst = act + ln.am * Pn + ln.pix;
@@ -865,7 +886,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
             e_next = e_hi;
           }
           if (j0 == 0) DSTAMP(122);
-          job_mac<K, SW, TH>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
+          job_mac<K, SW, TH, true>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
         __syncthreads();
         if (j0 == 0) DSTAMP(123);

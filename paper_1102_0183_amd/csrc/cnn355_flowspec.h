@@ -84,6 +84,9 @@ constexpr int flow_split_ways(int U, int max_cnt) {
   const int iters = (max_cnt + r_max - 1) / r_max;
   return (max_cnt + iters - 1) / iters;
 }
+// floats of one zero-bordered delta map of the pull through a layer whose input maps are Hi x Wi: odd, so that
+// lanes that read the same place of different maps fall on different LDS banks
+constexpr long long flow_border_map(int Hi, int Wi, int K) { return ((long long)(Hi + K - 1) * (Wi + K - 1)) | 1; }
 // floats of partial sums a job of n_maps (or one map fewer: ranks differ by one) maps needs
 constexpr long long flow_part_need(int strip, int th, int n_maps, int rows, int width, int max_cnt) {
   long long need = 0;
@@ -183,7 +186,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
         C.pull_strip = tile & 15; C.pull_rows = tile ? tile >> 4 : 1;
       }
       max_dall = flow_maxl(max_dall, (long long)C.Mo * HW);
-      max_hwd = flow_maxl(max_hwd, (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1));
+      max_hwd = flow_maxl(max_hwd, flow_border_map(C.Hi, C.Wi, C.K));
       max_part = flow_maxl(max_part, flow_part_need(C.pull_strip, C.pull_rows, C.n_own_below, C.Hi, C.Wi,
                                                     flow_min(C.max_back, C.Mo)));
     }
@@ -236,7 +239,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     long long worst = 1;
     for (int l = 1; l < n_conv; ++l) {
       const ConvSpec& C = Z.conv[l];
-      const long long hwd = (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1);
+      const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
       const long long chunk = flow_maxl(1, flow_minl(C.Mo, (floats - pad) / hwd));
       worst = flow_maxl(worst, (C.Mo + chunk - 1) / chunk);
     }
@@ -256,7 +259,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
   long long scratch = need;
   for (int l = 1; l < n_conv; ++l) {
     const ConvSpec& C = Z.conv[l];
-    scratch = flow_maxl(scratch, (long long)C.Mo * (C.Hi + C.K - 1) * (C.Wi + C.K - 1) + pad);
+    scratch = flow_maxl(scratch, (long long)C.Mo * flow_border_map(C.Hi, C.Wi, C.K) + pad);
   }
   scratch = flow_minl(scratch, (long long)FLOW_LDS_FLOATS_MAX - off);
   Z.o_scratch = take(scratch);
@@ -264,7 +267,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
   Z.lds_floats = (int)off;
   for (int l = 1; l < n_conv; ++l) {
     ConvSpec& C = Z.conv[l];
-    const long long hwd = (long long)(C.Hi + C.K - 1) * (C.Wi + C.K - 1);
+    const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
     C.pull_chunk = (int)flow_maxl(1, flow_minl(C.Mo, (scratch - pad) / hwd));
   }
   return FLOW_OK;
