@@ -939,7 +939,7 @@ __device__ __forceinline__ void flow_matvec(const float* W, const float* b, cons
 // same order: lane (k, part) adds the ranks of its part one after the other as their words
 // arrive, the parts are then added in order.  y[k] = b[k] + sum.
 __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged* xp, int NR, int n1, const float* b,
-                                                     float* y, float* part, unsigned int tag) {
+                                                     float* y, float* part, unsigned int tag, bool through_act) {
   const int tid = threadIdx.x;
   const int parts = max(1, min(WG / max(n1, 1), NR));
   const int per = (NR + parts - 1) / parts;
@@ -961,7 +961,10 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
       part[pi * n1 + (k - k0)] = s;
     }
     __syncthreads();
-    if (tid < n1 - k0 && tid < WG) y[k0 + tid] = b[k0 + tid] + sum_strided(part, parts, n1, tid);
+    if (tid < n1 - k0 && tid < WG) {
+      const float v = b[k0 + tid] + sum_strided(part, parts, n1, tid);
+      y[k0 + tid] = through_act ? f_act(v) : v;
+    }
     __syncthreads();
     if (n1 <= WG) break;
   }
@@ -1251,12 +1254,8 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
         pend = false;
       }
       float* y = lds + L1.o_act;
-      if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, part, tag)) return;
+      if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, part, tag, !L1.is_output)) return;
       STAMP(31);
-      if (!L1.is_output) {
-        for (int k = tid; k < n1; k += WG) y[k] = f_act(y[k]);
-        __syncthreads();
-      }
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----
     for_up<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
@@ -1283,13 +1282,18 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
     {
       float* y = lds + Lo.o_act;
       float* d = lds + Lo.o_delta;
-      if (wave_softmax) {
+      // only the wavefronts whose lanes the output layer's BP below gives work need the deltas: the others
+      // would repeat the same instructions on the same four SIMDs and slow those down
+      const int soft_lanes = (max(n_fc >= 2 ? uni_of<ID>(Lo.n_in) : 1, N) + 63) & ~63;
+      if (wave_softmax && tid < soft_lanes) {
         const int k = tid & 63;
         const float yk = (k < N) ? y[k] : -INFINITY;
+        // exponential, reciprocal and logarithm of the hardware (relative error about 1e-7 each): this chain of
+        // dependent operations is walked by one wavefront while every other one waits
         const float mx = f_wave_max(yk);
-        const float e = (k < N) ? expf(yk - mx) : 0.f;
+        const float e = (k < N) ? __builtin_amdgcn_exp2f(1.44269504088896340736f * (yk - mx)) : 0.f;
         const float z = f_wave_sum(e);
-        float p = e / z;
+        float p = e * __builtin_amdgcn_rcpf(z);
         dreg = p - (k == label ? 1.f : 0.f);
         float err = 0.f;
         if (tanh_out) {  // scaled-tanh outputs, squared error against targets +1 / -1
@@ -1302,11 +1306,13 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
           if (rank == 0) {
             if (a.probs_out) a.probs_out[t * n_classes + k] = p;
             if (train && tanh_out && k == 0) status->loss = err;
-            if (train && !tanh_out && k == label) status->loss = -logf(p);
+            if (train && !tanh_out && k == label) status->loss = -0.69314718055994530942f * __builtin_amdgcn_logf(p);
           }
           if (taps || n_fc == 1) d[k] = dreg;
           if (taps && rank == 0) Po.act[k] = p;
         }
+      }
+      if (wave_softmax) {
         if (n_fc == 1) __syncthreads();  // the first FC layer's BP reads the deltas from LDS
       } else {
         if (tid < 64 && tanh_out) {
