@@ -480,11 +480,11 @@ __device__ __forceinline__ float pixel_mac_k(int K, const float* in, const float
   }
 }
 
-// A tile of TH rows x SW consecutive output pixels (unit stride).  Per connection the K*K weights
-// are read once; every input row of SW+K-1 floats is read once and feeds the (up to K) kernel rows
-// and (up to TH) output rows it meets: (TH+K-1)(SW+K-1) + K*K LDS reads for TH*SW*K*K multiply-adds.
+// A tile of TH rows x SW consecutive output pixels, input stride ST.  Per connection the K*K weights
+// are read once; every input row of (SW-1)ST+K floats is read once and feeds the (up to K) kernel rows
+// and (up to TH) output rows it meets: ((TH-1)ST+K)((SW-1)ST+K) + K*K LDS reads for TH*SW*K*K multiply-adds.
 // CLIP: only the input rows iy in [iy_lo, iy_hi) are read; the others are known to hold zeros.
-template <int K, int SW, int TH, bool CLIP>
+template <int K, int SW, int TH, bool CLIP, int ST>
 __device__ __forceinline__ void strip_mac(const float* in, const float* w, const int* idx, int idx_off, int c0,
                                           int cstep, int nc, int map_sz, int Wi, int base, int iy_lo, int iy_hi,
                                           float (&acc)[TH * SW]) {
@@ -495,19 +495,20 @@ __device__ __forceinline__ void strip_mac(const float* in, const float* w, const
 #pragma unroll
     for (int t = 0; t < K * K; ++t) wk[t] = wp[t];
 #pragma unroll
-    for (int iy = 0; iy < TH + K - 1; ++iy) {
+    for (int iy = 0; iy < (TH - 1) * ST + K; ++iy) {
       if (CLIP && (iy < iy_lo || iy >= iy_hi)) continue;
-      float row[SW + K - 1];
+      float row[(SW - 1) * ST + K];
 #pragma unroll
-      for (int i = 0; i < SW + K - 1; ++i) row[i] = ip[iy * Wi + i];
+      for (int i = 0; i < (SW - 1) * ST + K; ++i) row[i] = ip[iy * Wi + i];
 #pragma unroll
       for (int ty = 0; ty < TH; ++ty) {
-        const int ky = iy - ty;
+        const int ky = iy - ty * ST;
         if (ky >= 0 && ky < K) {
 #pragma unroll
           for (int s = 0; s < SW; ++s)
 #pragma unroll
-            for (int kx = 0; kx < K; ++kx) acc[ty * SW + s] = fmaf(wk[ky * K + kx], row[s + kx], acc[ty * SW + s]);
+            for (int kx = 0; kx < K; ++kx)
+              acc[ty * SW + s] = fmaf(wk[ky * K + kx], row[s * ST + kx], acc[ty * SW + s]);
         }
       }
     }
@@ -528,7 +529,7 @@ struct JobStat {  // the part of a job the plan fixes
                         // input map of every connection [n_maps][w_pitch], connections per map [n_maps]
   int w_pitch, Ho, Wo, K, stride, map_sz, Wi, max_cnt;
   int plan_cnt;         // the connection count the planner sized the partial sums for (>= max_cnt)
-  int variant;          // (TH - 1) * 64 + SW * 8 + K for a job in tiles of TH rows x SW pixels, 0: one pixel per
+  int variant;          // (stride - 1) * 128 + (TH - 1) * 64 + SW * 8 + K for a job in tiles of TH rows x SW pixels, 0: one pixel per
                         // lane (any K, any stride)
   int table;            // LDS offset of the lane table [3][WG] (int), or -1
   int band_lo, band_hi; // rows [band_lo, band_hi) of an input map that can hold non-zeros; outside lie the zero
@@ -543,7 +544,7 @@ __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
   S.in = C.o_in; S.w = C.o_wf; S.idx = C.o_cidx; S.cnt = C.o_ncf;
   S.w_pitch = C.max_conn; S.Ho = C.Ho; S.Wo = C.Wo; S.K = C.K; S.stride = C.S + 1;
   S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn; S.plan_cnt = C.max_conn;
-  S.variant = C.fwd_strip ? (C.fwd_rows - 1) * 64 + C.fwd_strip * 8 + C.K : 0;
+  S.variant = C.fwd_strip ? C.S * 128 + (C.fwd_rows - 1) * 64 + C.fwd_strip * 8 + C.K : 0;
   S.table = C.o_tab_fwd;
   S.band_lo = 0; S.band_hi = C.Hi; S.ways_side_by_side = 0;
   return S;
@@ -568,7 +569,7 @@ struct Lane {
 };
 
 __device__ __forceinline__ JobDyn job_dyn(const JobStat& S, int n_maps) {
-  const int SW = (S.variant >> 3) & 7, TH = (S.variant >> 6) + 1;
+  const int SW = (S.variant >> 3) & 7, TH = ((S.variant >> 6) & 1) + 1;
   JobDyn D;
   D.n_maps = n_maps;
   D.U = SW ? n_maps * ((S.Ho + TH - 1) / TH) * ((S.Wo + SW - 1) / SW) : n_maps * S.Ho * S.Wo;
@@ -581,7 +582,7 @@ __device__ __forceinline__ JobDyn job_dyn(const JobStat& S, int n_maps) {
 
 // the share of lane `tid` in pass `pass`
 __device__ __forceinline__ Lane lane_decode(const JobStat& S, const JobDyn& D, int pass) {
-  const int SW = (S.variant >> 3) & 7, TH = (S.variant >> 6) + 1;
+  const int SW = (S.variant >> 3) & 7, TH = ((S.variant >> 6) & 1) + 1;
   Lane ln;
   const int u = pass * WG + (int)threadIdx.x;
   ln.on = u < D.U * D.R;
@@ -605,7 +606,7 @@ __device__ __forceinline__ Lane lane_decode(const JobStat& S, const JobDyn& D, i
     ln.pix = y * S.Wo + x0;
     ln.ncols = min(SW, S.Wo - x0);
     ln.nrows = min(TH, S.Ho - y);
-    ln.base = y * S.Wi + x0;
+    ln.base = (y * S.Wi + x0) * S.stride;
   } else {
     const int Pn = S.Ho * S.Wo;
     const FDiv dP(Pn), dW(S.Wo);
@@ -642,23 +643,36 @@ __device__ __forceinline__ Lane lane_get(const JobStat& S, const JobDyn& D, cons
   return lane_decode(S, D, pass);
 }
 
-// call f(K, SW, TH) with the job's compile-time kernel size and tile (K = 0: any size, one pixel)
-template <class Fn>
+// call f(K, SW, TH, ST) with the job's compile-time kernel size, tile and input stride (K = 0: any size, one
+// pixel per lane, any stride).  STRIDE2: the caller has jobs with a skipping factor of 1 (FP only; tiles of one row)
+template <bool STRIDE2, class Fn>
 __device__ __forceinline__ void job_dispatch(int variant, Fn f) {
   switch (variant) {
-#define JOB_CASE(SW, K)                                         \
-  case SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<1>{}); break;        \
-  case 64 + SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<2>{}); break;
+#define JOB_CASE(SW, K)                                                  \
+  case SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<1>{}, IC<1>{}); break;        \
+  case 64 + SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<2>{}, IC<1>{}); break;
     JOB_CASE(4, 2) JOB_CASE(4, 3) JOB_CASE(4, 4) JOB_CASE(4, 5)
     JOB_CASE(5, 2) JOB_CASE(5, 3) JOB_CASE(5, 4) JOB_CASE(5, 5)
     JOB_CASE(7, 2) JOB_CASE(7, 3) JOB_CASE(7, 4) JOB_CASE(7, 5)
 #undef JOB_CASE
-    default: f(IC<0>{}, IC<1>{}, IC<1>{}); break;
+    default:
+      if constexpr (STRIDE2) {
+        switch (variant) {
+#define JOB_CASE(SW, K) \
+  case 128 + SW * 8 + K: f(IC<K>{}, IC<SW>{}, IC<1>{}, IC<2>{}); return;
+          JOB_CASE(4, 2) JOB_CASE(4, 3) JOB_CASE(4, 4) JOB_CASE(4, 5)
+          JOB_CASE(5, 2) JOB_CASE(5, 3) JOB_CASE(5, 4) JOB_CASE(5, 5)
+#undef JOB_CASE
+          default: break;
+        }
+      }
+      f(IC<0>{}, IC<1>{}, IC<1>{}, IC<1>{});
+      break;
   }
 }
 
 // acc[] += the lane's share of connections [e_lo, e_hi) of its map (maps numbered from idx_off)
-template <int K, int SW, int TH, bool CLIP>
+template <int K, int SW, int TH, bool CLIP, int ST>
 __device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* lds, const Lane& ln, int e_lo, int e_hi,
                                         int idx_off, float (&acc)[TH * SW]) {
   const float* w = lds + S.w + (ln.am * S.w_pitch) * (S.K * S.K);
@@ -667,10 +681,10 @@ __device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* ld
     acc[0] += pixel_mac_k(S.K, lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base);
   else if constexpr (CLIP) {
     const int y = ln.pix / S.Wo;  // first output row of the tile = first input row it reads
-    strip_mac<K, SW, TH, true>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base,
+    strip_mac<K, SW, TH, true, ST>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base,
                                S.band_lo - y, S.band_hi - y, acc);
   } else
-    strip_mac<K, SW, TH, false>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, 0, 0, acc);
+    strip_mac<K, SW, TH, false, ST>(lds + S.in, w, idx, idx_off, e_lo + ln.r, R, e_hi, S.map_sz, S.Wi, ln.base, 0, 0, acc);
 }
 
 // ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
@@ -687,15 +701,15 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
   const float* bf = lds + C.o_bf;
   const int* cnt = (const int*)(lds + S.cnt);
   const int Pn = S.Ho * S.Wo, tot = nm * Pn;
-  job_dispatch(S.variant, [&](auto k_, auto sw_, auto th_) {
-    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value;
+  job_dispatch<true>(S.variant, [&](auto k_, auto sw_, auto th_, auto st_) {
+    constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value, ST = decltype(st_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
       const Lane ln = lane_get(S, D, lds, pass);
       float acc[TH * SW];
 #pragma unroll
       for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
       if (ln.on) {
-        job_mac<K, SW, TH, false>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
+        job_mac<K, SW, TH, false, ST>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
         if (D.R == 1) {  // unsplit: the finished sums go straight through the activation function
           const float b = bf[ln.am];
           float* dst = act + ln.am * Pn + ln.pix;
@@ -853,7 +867,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
   const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
   DSTAMP(120);
-  job_dispatch(S.variant, [&](auto k_, auto sw_, auto th_) {
+  job_dispatch<false>(S.variant, [&](auto k_, auto sw_, auto th_, auto) {
     constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value;
     for (int pass = 0; pass < D.passes; ++pass) {
       const Lane ln = lane_get(S, D, lds, pass);
@@ -886,7 +900,7 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
             e_next = e_hi;
           }
           if (j0 == 0) DSTAMP(122);
-          job_mac<K, SW, TH, true>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
+          job_mac<K, SW, TH, true, 1>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
         __syncthreads();
         if (j0 == 0) DSTAMP(123);

@@ -103,15 +103,17 @@ constexpr long long flow_part_need(int strip, int th, int n_maps, int rows, int 
 // applies).  Two things bound that time: the multiply-adds of one lane (a wavefront issues one
 // vector instruction per about 5 cycles, however many wavefronts share its SIMD), and the LDS
 // reads of all wavefronts together (128 bytes per cycle and compute unit: 2 cycles per wavefront
-// read, taken as 3 with bank conflicts).  0 = one pixel per lane (any stride, any kernel size).
+// read, taken as 3 with bank conflicts).  0 = one pixel per lane (any stride, any kernel size); tiles exist
+// for strides 1 and 2 and kernels of 2 to 5.
 // Returns strip + 16 * rows.
 constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, int max_cnt) {
-  if (stride != 1 || K < 2 || K > 5) return 0;
+  if (stride < 1 || stride > 2 || K < 2 || K > 5) return 0;
   int best = 4 + 16;
   long long best_cost = -1;
   const int widths[3] = {4, 5, 7};
-  for (int th = 1; th <= 2; ++th)
-    for (int wi = 0; wi < 3; ++wi) {
+  // a skipping factor of 1: one row per tile, strips of 4 or 5 (the rows a lane keeps grow with the stride)
+  for (int th = 1; th <= (stride == 1 ? 2 : 1); ++th)
+    for (int wi = 0; wi < (stride == 1 ? 3 : 2); ++wi) {
       const int sw = widths[wi];
       const long long U = (long long)n_maps * ((rows + th - 1) / th) * ((width + sw - 1) / sw);
       long long iters = max_cnt;
@@ -121,7 +123,7 @@ constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, 
       }
       const long long passes = (U + WG - 1) / WG;
       const long long macs = (long long)th * sw * K * K;
-      const long long reads = (long long)(th + K - 1) * (sw + K - 1) + K * K;
+      const long long reads = (long long)((th - 1) * stride + K) * ((sw - 1) * stride + K) + K * K;
       const long long ways = (max_cnt + iters - 1) / iters;
       const long long waves = (flow_minl(U * ways, WG) + 63) / 64;
       const long long valu = iters * macs * 5, lds = waves * iters * reads * 3;
