@@ -1520,6 +1520,7 @@ hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_
   switch (static_id) {
     case 1: return launch_resident_id<1>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
     case 2: return launch_resident_id<2>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
+    case 3: return launch_resident_id<3>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
     default: return launch_resident_id<0>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
   }
 }
@@ -1528,6 +1529,7 @@ hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_
 int resident_static_id(const FlowSpec& z) {
   if (__builtin_memcmp(&z, &StaticSpec<1>::value, sizeof(FlowSpec)) == 0) return 1;
   if (__builtin_memcmp(&z, &StaticSpec<2>::value, sizeof(FlowSpec)) == 0) return 2;
+  if (__builtin_memcmp(&z, &StaticSpec<3>::value, sizeof(FlowSpec)) == 0) return 3;
   return 0;
 }
 

@@ -276,9 +276,11 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
 }
 
 // ---- networks the resident kernel is also compiled for, every size a literal --------------------
-// A network of convolutional layers with full connection tables, each followed by max-pooling of
-// Kp (1 = none), then fully connected layers; Eq. 1 of Sec. 2.2 gives the map sizes.
-struct StaticConv { int maps, K, S, Kp; };
+// A network of convolutional layers, each followed by max-pooling of Kp (1 = none), then fully
+// connected layers; Eq. 1 of Sec. 2.2 gives the map sizes.  fan_in = 0: full connection table; else every
+// output map reads fan_in input maps and the busiest input map is read by max_back output maps (the plan
+// depends on a table through these two numbers only).
+struct StaticConv { int maps, K, S, Kp, fan_in, max_back; };
 constexpr FlowSpec flow_static_spec(int C0, int H0, int W0, int n_conv, const StaticConv* conv, int n_fc, const int* fc,
                                     int team_ranks, int team_stride) {
   FlowSpec Z{};
@@ -293,6 +295,7 @@ constexpr FlowSpec flow_static_spec(int C0, int H0, int W0, int n_conv, const St
     C.Wo = (w - C.K) / (C.S + 1) + 1;
     C.Hp = C.Ho / C.Kp; C.Wp = C.Wo / C.Kp;
     C.max_conn = m; C.max_back = C.Mo; C.full_table = 1;
+    if (conv[l].fan_in > 0) { C.max_conn = conv[l].fan_in; C.max_back = conv[l].max_back; C.full_table = 0; }
     m = C.Mo; h = C.Hp; w = C.Wp;
   }
   int n_in = m * h * w;
@@ -309,20 +312,29 @@ constexpr FlowSpec flow_static_spec(int C0, int H0, int W0, int n_conv, const St
 
 // 1: 1x29x29-20C4-MP2-40C5-MP3-150N-10N (the benchmark network), automatic team
 // 2: 1x29x29-40C4-MP2-80C5-MP3-300N-10N, automatic team
-constexpr int FLOW_N_STATIC = 2;
+// 3: 4x44x44-40C5S1-MP2-80C3-MP2-100N-5N behind a fixed first layer, the second convolution reading 20 of the 40
+//    maps with the busiest map read 49 times (the benchmark's seeded table), automatic team
+constexpr int FLOW_N_STATIC = 3;
 template <int ID>
 struct StaticSpec;
 template <>
 struct StaticSpec<1> {
-  static constexpr StaticConv conv[2] = {{20, 4, 0, 2}, {40, 5, 0, 3}};
+  static constexpr StaticConv conv[2] = {{20, 4, 0, 2, 0, 0}, {40, 5, 0, 3, 0, 0}};
   static constexpr int fc[2] = {150, 10};
   static constexpr FlowSpec value = flow_static_spec(1, 29, 29, 2, conv, 2, fc, 0, 0);
 };
 template <>
 struct StaticSpec<2> {
-  static constexpr StaticConv conv[2] = {{40, 4, 0, 2}, {80, 5, 0, 3}};
+  static constexpr StaticConv conv[2] = {{40, 4, 0, 2, 0, 0}, {80, 5, 0, 3, 0, 0}};
   static constexpr int fc[2] = {300, 10};
   static constexpr FlowSpec value = flow_static_spec(1, 29, 29, 2, conv, 2, fc, 0, 0);
+};
+
+template <>
+struct StaticSpec<3> {
+  static constexpr StaticConv conv[2] = {{40, 5, 1, 2, 0, 0}, {80, 3, 0, 2, 20, 49}};
+  static constexpr int fc[2] = {100, 5};
+  static constexpr FlowSpec value = flow_static_spec(4, 44, 44, 2, conv, 2, fc, 0, 0);
 };
 
 }  // namespace cnn355

@@ -188,11 +188,11 @@ def test_resident_mode_repeats_bit_for_bit_wherever_the_team_sits(name):
     np.testing.assert_array_equal(results["many"], results["many-again"])
     np.testing.assert_array_equal(results["many"], results["step"])
     np.testing.assert_array_equal(results["one-xcd"], results["spread"])
-    # the two benchmark networks with their automatic teams run the kernels compiled for them
+    # three benchmark networks with their automatic teams run the kernels compiled for them
     # (every size a literal); any other network or team runs the kernel that reads its plan
     g, _ = build_pair(wl)
     use_mode(g, binding.MODE_RESIDENT)
-    assert g.resident_static_id() == {"cfg1": 1, "cfg2b": 2}.get(name, 0)
+    assert g.resident_static_id() == {"cfg1": 1, "cfg2b": 2, "cfg5": 3}.get(name, 0)
     g.set_team(32, 1)
     assert g.resident_static_id() == 0
     g.close()
