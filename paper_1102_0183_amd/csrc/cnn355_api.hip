@@ -663,9 +663,11 @@ int plan(cnn* net) {
     }
     Stage& s = add(ST_CONV_WGRAD, l, 0, barrier, 1);
     const int chunk_max = std::min(LDS_IN / (L.Hi * L.Wi), L.max_conn);
-    const int want_chunks = std::max(1, 192 / L.Mo);  // aim at about 192 work items: one round on 256 CUs
-    // together with the small stage that shares the barrier interval
-    int chunk = std::max(1, std::min(chunk_max, L.max_conn / std::max(1, want_chunks)));
+    // as many work items as fit one round on the compute units: the connection lists cut into
+    // floor(CUs / maps) chunks
+    const int n_cu_w = net->n_cu > 0 ? net->n_cu : 256;
+    const int want_chunks = std::max(1, n_cu_w / L.Mo);
+    int chunk = std::max(1, std::min(chunk_max, (L.max_conn + want_chunks - 1) / want_chunks));
     s.chunk = chunk;
     s.n_tiles = (L.max_conn + chunk - 1) / chunk;
     s.n_items = L.Mo * s.n_tiles;

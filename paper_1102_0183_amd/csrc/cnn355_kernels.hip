@@ -45,6 +45,23 @@ struct Ctx {
   float lr;
 };
 
+// Sum of n_terms partial sums for each of n_out outputs, parts[k * n_out + o]: up to 64 lanes share an output
+// (lane g adds the terms g, g + G, ... in that order, the G sums are then added across the lanes in a fixed
+// pattern) instead of one lane walking a chain of n_terms dependent LDS reads.  The totals pass through
+// res[n_out]; lane o < n_out returns output o.  Every lane of the workgroup must call it.
+__device__ __forceinline__ float sum_terms(const float* parts, int n_terms, int n_out, float* res) {
+  const int tid = threadIdx.x;
+  int gl2 = 0;
+  while (gl2 < 6 && (n_out << (gl2 + 1)) <= WG && (2 << gl2) <= n_terms) ++gl2;
+  const int G = 1 << gl2, o = tid >> gl2, g = tid & (G - 1);
+  float s = 0.f;
+  if (o < n_out)
+    for (int k = g; k < n_terms; k += G) s += parts[k * n_out + o];
+  for (int off = G >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (o < n_out && g == 0) res[o] = s;
+  __syncthreads();
+  return tid < n_out ? res[tid] : 0.f;
+}
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -206,7 +223,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
 
   int R = 1, r = 0, p0 = tid;
   if (TT == 1) {
-    R = WG / P;  // P <= WG here
+    R = max(1, min(WG / P, min(st.chunk, n_conn)));  // P <= WG here; no more ways than one chunk has connections
     r = tid / P;
     p0 = tid - r * P;
   }
@@ -253,10 +270,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   if (TT == 1 && R > 1) {
     if (r < R) lds_part[tid] = acc[0];  // tid == r * P + p0
     __syncthreads();
-    float s = 0.f;
-    if (tid < P)
-      for (int rr = 0; rr < R; ++rr) s += lds_part[rr * P + tid];
-    acc[0] = s;
+    acc[0] = sum_terms(lds_part, R, P, lds_out);
   }
   DBG(5);
 #pragma unroll
@@ -934,11 +948,7 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
   if (R > 1) {
     lds_part[tid] = acc;  // tid == r * PT + (p - tile * PT)
     __syncthreads();
-    float s = 0.f;
-    if (tid < PT)
-      for (int rr = 0; rr < R; ++rr) s += lds_part[rr * PT + tid];
-    acc = s;
-    __syncthreads();
+    acc = sum_terms(lds_part, R, PT, lds_part + WG);
   }
   if (r == 0 && active) {
     const size_t o = (size_t)i * Pin + p;
@@ -1039,9 +1049,8 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   } else {
     if (rr < R) lds_part[tid] = grad_of(wi0, rr, R);  // tid == rr * NW + wi0
     __syncthreads();
+    const float g = sum_terms(lds_part, R, NW, lds_part + WG);
     if (tid < NW) {
-      float g = 0.f;
-      for (int k = 0; k < R; ++k) g += lds_part[k * NW + tid];
       if (g_out) g_out[canon + tid] = g;
       else wbase[tid] = w_old[0] - lr * g;
     }
