@@ -25,7 +25,7 @@ int persistent_max_blocks_per_cu();
 void read_dbg(unsigned long long* out);
 hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, const float* d_images,
                                  long long image_stride, int n_images, int items_per_image, float* d_out);
-hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
+hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec& spec,
                            const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a);
 int resident_static_id(const FlowSpec& z);
 size_t batch_gemm_lds_bytes(const BatchGemm& g);
@@ -229,9 +229,8 @@ struct cnn {
   std::vector<HostTable> host_tables;  // per convolutional layer, rebuilt by plan()
 
   // resident mode
-  FlowSpec flow;                // the plan (plain integers)
+  FlowSpec flow;                // the plan (plain integers); the resident kernel takes it by value
   FlowPtrs flow_ptrs;           // where the layers and the exchange buffers lie on the device
-  FlowSpec* d_flow = nullptr;
   FlowPtrs* d_flow_ptrs = nullptr;
   int flow_static_id = 0;       // > 0: the plan equals that of a kernel compiled for a fixed network
   tagged_t* d_xbuf = nullptr;   // every exchange buffer, one after the other
@@ -294,7 +293,6 @@ size_t carve(cnn* net, void* base) {
       }
     net->d_mm_part = c.take<float>(mm);
   }
-  net->d_flow = c.take<FlowSpec>(1);
   net->d_flow_ptrs = c.take<FlowPtrs>(1);
   {  // resident mode: tagged exchange buffers, sized for any team (see plan_flow for the split)
     size_t words = 0, last_maps = 0, first_fc = 0;
@@ -831,7 +829,6 @@ int upload(cnn* net) {
     ++conv_i;
   }
   HIP_TRY(net, hipMemcpy(net->d_prog, &P, sizeof(P), hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
   HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   HIP_TRY(net, hipMemset(net->d_xbuf, 0, net->xbuf_words * sizeof(tagged_t)));
   net->epoch = 0;
@@ -894,7 +891,7 @@ int run(cnn* net, const RunArgs& a0) {
     if (!P.has_frontend) {
       a.epoch_base = (unsigned int)net->epoch;
       net->epoch += n;
-      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->d_flow, net->d_flow_ptrs,
+      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->flow, net->d_flow_ptrs,
                                    net->d_status, a));
       return CNN_OK;
     }
@@ -914,7 +911,7 @@ int run(cnn* net, const RunArgs& a0) {
       b.n_images = nb;
       b.epoch_base = (unsigned int)net->epoch;
       net->epoch += (unsigned long long)nb;
-      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->d_flow, net->d_flow_ptrs,
+      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->flow, net->d_flow_ptrs,
                                    net->d_status, b));
       if (t0 + nb >= n)  // parity tap: layer 0 of the last image
         HIP_TRY(net, hipMemcpyAsync(net->d_fe_out, net->d_fe_batch + (size_t)(nb - 1) * fe_sz, fe_sz * sizeof(float),
@@ -1283,8 +1280,7 @@ int cnn_set_mode(cnn_t* net, int mode) {
     if (rc) { net->mode = old_mode; return rc; }
     net->mode = mode;
     HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
-    HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
-    HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
+      HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   }
   return CNN_OK;
 }
@@ -1308,10 +1304,8 @@ int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride) {
   net->team_ranks = n_ranks;
   net->team_stride = xcd_stride;
   plan_flow(net);
-  if (net->d_flow) {
-    HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
+  if (net->d_flow_ptrs)
     HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
-  }
   if (net->mode == CNN_MODE_RESIDENT && !net->flow_ok) {
     net->mode = CNN_MODE_PERSISTENT;
     return fail(&net->err, CNN_E_STATE, net->flow_why);
@@ -1328,7 +1322,6 @@ int cnn_set_matrix_cores(cnn_t* net, int on) {
   int rc = plan(net);
   if (rc) return rc;
   HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
   HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   return CNN_OK;
 }
@@ -1342,7 +1335,6 @@ int cnn_set_output_units(cnn_t* net, int kind) {
   int rc = plan(net);
   if (rc) return rc;
   HIP_TRY(net, hipMemcpy(net->d_prog, &net->prog, sizeof(ProgramDev), hipMemcpyHostToDevice));
-  HIP_TRY(net, hipMemcpy(net->d_flow, &net->flow, sizeof(FlowSpec), hipMemcpyHostToDevice));
   HIP_TRY(net, hipMemcpy(net->d_flow_ptrs, &net->flow_ptrs, sizeof(FlowPtrs), hipMemcpyHostToDevice));
   return CNN_OK;
 }

@@ -168,7 +168,6 @@ struct JobDyn {  // the part of a correlation job that depends on the rank
   int n_maps, U, R, passes;
 };
 struct Shared {
-  FlowSpec spec;
   FlowPtrs ptrs;
   JobDyn fwd[FLOW_MAX_CONV];   // FP of the own maps of every convolutional layer
   JobDyn pull[FLOW_MAX_CONV];  // delta pull through layer l into the own maps of layer l-1 (l >= 1)
@@ -185,6 +184,7 @@ static_assert(sizeof(Shared) + sizeof(float) * FLOW_LDS_FLOATS_MAX <= 160 * 1024
 
 struct Rt {  // what every phase needs
   bool dbg;
+  const FlowSpec* spec;  // the plan (the kernel argument)
   Shared* sh;
   StatusDev* status;
   float* lds;
@@ -192,12 +192,13 @@ struct Rt {  // what every phase needs
   unsigned int spin_limit;
 };
 
-// The plan: literals in a kernel instantiated for a fixed network, the copy in LDS otherwise.  (A
+// The plan: literals in a kernel instantiated for a fixed network, the kernel's by-value argument otherwise
+// (read with scalar loads, uniform by construction).  (A
 // function-local constexpr copy, not a reference to the class-scope constant: a device-side
 // global may be initialised from outside the module, so the compiler would not fold its contents.)
-#define DECL_SPEC(Z, shared)                                                 \
+#define DECL_SPEC(Z, rt_)                                                    \
   constexpr FlowSpec Z##_lit = StaticSpec<(ID ? ID : 1)>::value;             \
-  const FlowSpec& Z = ID ? Z##_lit : (shared).spec
+  const FlowSpec& Z = ID ? Z##_lit : *(rt_).spec
 // a value every lane holds alike, made known to the compiler as such (nothing to do for a literal)
 template <int ID>
 __device__ __forceinline__ int uni_of(int v) {
@@ -328,7 +329,7 @@ __device__ __forceinline__ bool gather2(const Rt& rt, unsigned int* dst_a, const
 // ---- weights: global (canonical order) <-> LDS -------------------------------------------------
 template <int ID>
 __device__ __forceinline__ void flow_load(const Rt& rt) {
-  DECL_SPEC(Z, *rt.sh);
+  DECL_SPEC(Z, rt);
   const FlowPtrs& Q = rt.sh->ptrs;
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
@@ -405,7 +406,7 @@ __device__ __forceinline__ void flow_load(const Rt& rt) {
 
 template <int ID>
 __device__ __forceinline__ void flow_store(const Rt& rt) {
-  DECL_SPEC(Z, *rt.sh);
+  DECL_SPEC(Z, rt);
   const FlowPtrs& Q = rt.sh->ptrs;
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
@@ -690,7 +691,7 @@ __device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* ld
 // ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
 template <int ID>
 __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
-  DECL_SPEC(Z, *rt.sh);
+  DECL_SPEC(Z, rt);
   const ConvSpec& C = Z.conv[l];
   float* lds = rt.lds;
   const JobStat S = fwd_job(Z, l);
@@ -741,7 +742,7 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
 // order; the pooled value is what the next layer reads, so it is published at once.
 template <int ID>
 __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned int tag, bool taps) {
-  DECL_SPEC(Z, *rt.sh);
+  DECL_SPEC(Z, rt);
   const ConvSpec& C = Z.conv[l];
   const FlowConvPtrs& P = rt.sh->ptrs.conv[l];
   float* lds = rt.lds;
@@ -849,7 +850,7 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
 // delta_below[p] = pulled sum * f'(y_below[p]).
 template <int ID>
 __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall, const int* yxall) {
-  DECL_SPEC(Z, *rt.sh);
+  DECL_SPEC(Z, rt);
   const ConvSpec& C = Z.conv[l];
   const ConvSpec& Cb = Z.conv[l - 1];
   float* lds = rt.lds;
@@ -989,7 +990,7 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
 template <int ID>
 __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
   Shared& sh = *rt.sh;
-  DECL_SPEC(Z, sh);
+  DECL_SPEC(Z, rt);
   const int G = Z.G, rank = rt.rank;
   if (threadIdx.x == 0)
     for_up<ID, 0, FLOW_MAX_CONV>(Z.n_conv, [&](auto lc) {
@@ -1019,34 +1020,30 @@ __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
     if (stamp) status->stamps[i] = wall_clock64();                                            \
   } while (0)
 
-// ID = 0: any network, the plan read from *gspec.  ID > 0: the network of StaticSpec<ID>; the host
+// ID = 0: any network, the plan is the argument kspec.  ID > 0: the network of StaticSpec<ID>; the host
 // launches it only when the plan it made at run time equals that one word for word.
 template <int ID>
-__global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gspec, const FlowPtrs* __restrict__ gptrs,
+__global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const FlowPtrs* __restrict__ gptrs,
                                                  StatusDev* status, RunArgs a) {
   extern __shared__ float lds[];
   __shared__ Shared sh;
   const int tid = threadIdx.x;
   {
-    const int stride = ID ? StaticSpec<(ID ? ID : 1)>::value.stride : gspec->stride;
-    const int G0 = ID ? StaticSpec<(ID ? ID : 1)>::value.G : gspec->G;
+    const int stride = ID ? StaticSpec<(ID ? ID : 1)>::value.stride : kspec.stride;
+    const int G0 = ID ? StaticSpec<(ID ? ID : 1)>::value.G : kspec.G;
     if (blockIdx.x % stride != 0 || (int)(blockIdx.x / stride) >= G0) return;
-    if (ID == 0) {
-      const unsigned int* src = (const unsigned int*)gspec;
-      unsigned int* dst = (unsigned int*)&sh.spec;
-      for (int i = tid; i < (int)(sizeof(FlowSpec) / 4); i += WG) dst[i] = src[i];
-    }
     const unsigned int* src = (const unsigned int*)gptrs;
     unsigned int* dst = (unsigned int*)&sh.ptrs;
     for (int i = tid; i < (int)(sizeof(FlowPtrs) / 4); i += WG) dst[i] = src[i];
     if (tid == 0) sh.fail = 0;
     __syncthreads();
   }
-  DECL_SPEC(Z, sh);
+  Rt rt;
+  rt.spec = &kspec;
+  DECL_SPEC(Z, rt);
   const FlowPtrs& Q = sh.ptrs;
   const int G = uni_of<ID>(Z.G);
   const int rank = blockIdx.x / uni_of<ID>(Z.stride);
-  Rt rt;
   rt.sh = &sh; rt.status = status; rt.lds = lds; rt.rank = rank; rt.spin_limit = a.spin_limit;
   rt.dbg = false;
   flow_load<ID>(rt);
@@ -1504,24 +1501,25 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec* __restrict__ gs
 }
 
 template <int ID>
-static hipError_t launch_resident_id(int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
+static hipError_t launch_resident_id(int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec& spec,
                                      const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a) {
   hipError_t e = hipFuncSetAttribute((const void*)k_resident<ID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   RunArgs args = a;
-  void* params[] = {(void*)&d_spec, (void*)&d_ptrs, (void*)&d_status, (void*)&args};
+  FlowSpec plan = spec;
+  void* params[] = {(void*)&plan, (void*)&d_ptrs, (void*)&d_status, (void*)&args};
   return hipLaunchCooperativeKernel((const void*)k_resident<ID>, dim3(grid), dim3(WG), params, (unsigned int)lds_bytes, stream);
 }
 
 // static_id: 0 = the kernel for any network; k > 0 = the one compiled for StaticSpec<k> (the caller
-// has checked that the plan in *d_spec equals it)
-hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec* d_spec,
+// has checked that the plan equals it)
+hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec& spec,
                            const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a) {
   switch (static_id) {
-    case 1: return launch_resident_id<1>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
-    case 2: return launch_resident_id<2>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
-    case 3: return launch_resident_id<3>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
-    default: return launch_resident_id<0>(grid, lds_bytes, stream, d_spec, d_ptrs, d_status, a);
+    case 1: return launch_resident_id<1>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
+    case 2: return launch_resident_id<2>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
+    case 3: return launch_resident_id<3>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
+    default: return launch_resident_id<0>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
   }
 }
 
