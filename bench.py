@@ -306,8 +306,28 @@ def main():
             e1.record()
             e1.synchronize()
             extra[key + "_train_images_per_s"] = round(n_o / (e0.elapsed_time(e1) * 1e-3), 1)
+            # forward only: one image at a time in the same mode, and every layer a matrix product over the batch
+            net.forward_many(d_io, 50)
+            net.synchronize()
+            e0.record()
+            net.forward_many(d_io, n_o)
+            e1.record()
+            e1.synchronize()
+            extra[key + "_forward_only_images_per_s"] = round(n_o / (e0.elapsed_time(e1) * 1e-3), 1)
+            fb_o = {"cfg3": 512, "cfg4a": 512, "cfg4b": 256, "cfg5": 1024}[key]
+            n_b = 2 * fb_o
+            ib = torch.from_numpy(synth.images(wo, n_b)).to(dev)
+            scratch = torch.empty(net.forward_batch_scratch_bytes(fb_o), dtype=torch.uint8, device=dev)
+            pb = torch.empty(n_b * net.num_classes, dtype=torch.float32, device=dev)
+            net.forward_batch(ib, n_b, pb, scratch, fb_o)
+            net.synchronize()
+            e0.record()
+            net.forward_batch(ib, n_b, pb, scratch, fb_o)
+            e1.record()
+            e1.synchronize()
+            extra[key + "_forward_batch_images_per_s"] = round(n_b / (e0.elapsed_time(e1) * 1e-3), 1)
             net.close()
-            del d_io, d_lo
+            del d_io, d_lo, ib, scratch, pb
         # launch cost: the same images through one cnn_train_step call each
         net = make_net(wl, args.grid)
         sz = net.image_size
@@ -340,6 +360,12 @@ def main():
             "value": round(n / dt, 1), "unit": "images/s", "cores": cores, "kind": "oracle",
             "sample": "images %d..%d of the same stream, float32 instantiation of the oracle, "
                       "OpenMP over output maps, %.1f s" % (probe, probe + n, dt)}
+        # the same oracle on one thread (the paper's own baseline was one optimised CPU thread), 300 images
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        ref.train_many(imgs[:300], labs[:300], wl.lr)
+        out["cpu_baseline"]["single_thread_images_per_s"] = round(300 / (time.perf_counter() - t0), 1)
+        oracle.set_threads(0)
     print(json.dumps(out))
 
 
