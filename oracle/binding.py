@@ -118,10 +118,10 @@ class Oracle:
         return int(lib().oracle_image_size(self._h))
 
     def layer_info(self, layer):
-        info = np.zeros(6, dtype=np.int32)
+        info = np.zeros(8, dtype=np.int32)
         self._ck(lib().oracle_layer_info(self._h, int(layer), _p(info, C.c_int32)), "layer_info")
         return dict(kind=int(info[0]), maps=int(info[1]), h=int(info[2]), w=int(info[3]),
-                    K=int(info[4]), S=int(info[5]))
+                    K=int(info[4]), S=int(info[5]), Kx=int(info[6]), Sx=int(info[7]))
 
     def layer_size(self, layer):
         i = self.layer_info(layer)

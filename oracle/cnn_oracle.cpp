@@ -339,9 +339,21 @@ bool read_int(const char*& p, int& v) {
   return true;
 }
 
+// A size: <k> (the same in both directions) or <ky>x<kx> (rows, then columns): Sec. 2.2 and 2.3 give kernels,
+// skipping factors and pooling rectangles an x and a y value each.
+bool read_pair(const char*& p, int& vy, int& vx) {
+  if (!read_int(p, vy)) return false;
+  vx = vy;
+  if (*p == 'x') {
+    ++p;
+    if (!read_int(p, vx)) return false;
+  }
+  return true;
+}
+
 // Architecture string: <C>x<H>x<W> then one or more of
-//   -<M>C<K>[S<s>]  convolutional layer, M maps, KxK kernel, skipping factor s
-//   -MP<K>          max-pooling over KxK
+//   -<M>C<K>[S<s>]  convolutional layer, M maps, kernel K, skipping factor s (K, s: <k> or <ky>x<kx>)
+//   -MP<K>          max-pooling over rectangles of K
 //   -<N>N           fully connected layer with N neurons
 // the last token being the output layer (one unit per class, Sec. 2.4).
 int parse_arch(const char* s, Arch& out) {
@@ -363,38 +375,41 @@ int parse_arch(const char* s, Arch& out) {
     Layer l;
     if (p[0] == 'M' && p[1] == 'P') {
       p += 2;
-      int k;
-      if (!read_int(p, k)) return E_SYNTAX;
-      if (k < 1) return E_SHAPE;
+      int ky, kx;
+      if (!read_pair(p, ky, kx)) return E_SYNTAX;
+      if (ky < 1 || kx < 1) return E_SHAPE;
       if (prev.kind != K_CONV) return E_SYNTAX;  // a pooling layer follows a convolutional layer (Sec. 2)
       // Sec. 2.3: pooling down-samples by exactly K; a rectangle that does not
       // tile the map is rejected rather than guessed at.
-      if (prev.h % k || prev.w % k) return E_SHAPE;
+      if (prev.h % ky || prev.w % kx) return E_SHAPE;
       l.kind = K_POOL;
       l.maps = prev.maps;
-      l.ky = l.kx = k;
-      l.h = prev.h / k;
-      l.w = prev.w / k;
+      l.ky = ky;
+      l.kx = kx;
+      l.h = prev.h / ky;
+      l.w = prev.w / kx;
     } else {
       int n;
       if (!read_int(p, n)) return E_SYNTAX;
       if (n < 1) return E_SHAPE;
       if (*p == 'C') {
         ++p;
-        int k, sk = 0;
-        if (!read_int(p, k)) return E_SYNTAX;
+        int ky, kx, sy = 0, sx = 0;
+        if (!read_pair(p, ky, kx)) return E_SYNTAX;
         if (*p == 'S') {
           ++p;
-          if (!read_int(p, sk)) return E_SYNTAX;
+          if (!read_pair(p, sy, sx)) return E_SYNTAX;
         }
-        if (k < 1) return E_SHAPE;
+        if (ky < 1 || kx < 1) return E_SHAPE;
         if (seen_fc) return E_SYNTAX;
         l.kind = K_CONV;
         l.maps = n;
-        l.ky = l.kx = k;
-        l.sy = l.sx = sk;
-        l.h = conv_out_size(prev.h, k, sk);
-        l.w = conv_out_size(prev.w, k, sk);
+        l.ky = ky;
+        l.kx = kx;
+        l.sy = sy;
+        l.sx = sx;
+        l.h = conv_out_size(prev.h, ky, sy);
+        l.w = conv_out_size(prev.w, kx, sx);
         if (l.h < 1 || l.w < 1) return E_SHAPE;
         l.conn.assign(n, {});
         for (int j = 0; j < n; ++j)
@@ -749,7 +764,7 @@ int oracle_num_layers(oracle_t* h) {
   return n;
 }
 
-// info = {kind, maps, h, w, K, S}
+// info = {kind, maps, h, w, Ky, Sy, Kx, Sx}
 int oracle_layer_info(oracle_t* h, int layer, int32_t* info) {
   if (!h || !info) return E_ARG;
   int rc = E_OK;
@@ -758,6 +773,7 @@ int oracle_layer_info(oracle_t* h, int layer, int32_t* info) {
     else {
       const Layer& a = net.L()[layer];
       info[0] = a.kind; info[1] = a.maps; info[2] = a.h; info[3] = a.w; info[4] = a.ky; info[5] = a.sy;
+      info[6] = a.kx; info[7] = a.sx;
     }
   });
   return rc;

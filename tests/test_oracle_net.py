@@ -14,6 +14,10 @@ TINY = [
     ("3x8x8-4C3-MP3-4C2-6N-5N-4N", {1: 3}, False),               # maps shrink to 1 pixel, two hidden FC
     ("4x8x8-3C3S1-MP1-5N-2N", {}, True),                         # fixed front-end on a 2x12x12 raw image
     ("1x6x6-2C3-3N", {}, False),                                 # no pooling at all
+    # kernels, skipping factors and pooling rectangles with different x and y values (Sec. 2.2, 2.3)
+    ("2x14x11-3C4x2S1x0-MP2x5-4C1x2-5N-3N", {1: 2}, False),
+    ("1x10x12-2C3x5-MP4x2-4N", {}, False),
+    ("1x9x9-2C2S0x1-MP2x1-3C2x1S1x0-3N", {}, False),
 ]
 
 

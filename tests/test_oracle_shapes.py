@@ -108,6 +108,21 @@ def test_floor_when_stride_does_not_divide():
     assert oracle.conv_out_size(4, 5, 0) <= 0
 
 
+def test_sizes_with_different_x_and_y_values():
+    # Eq. 1 axis by axis (Sec. 2.2), pooling by Ky and Kx (Sec. 2.3): rows first, then columns
+    o = oracle.Oracle("2x14x11-3C4x2S1x0-MP2x5-4C1x2-5N-3N")
+    i = o.layer_info(1)
+    assert (i["h"], i["w"], i["K"], i["Kx"], i["S"], i["Sx"]) == ((14 - 4) // 2 + 1, (11 - 2) // 1 + 1, 4, 2, 1, 0)
+    i = o.layer_info(2)
+    assert (i["kind"], i["h"], i["w"], i["K"], i["Kx"]) == (KIND_POOL, 3, 2, 2, 5)
+    i = o.layer_info(3)
+    assert (i["h"], i["w"], i["K"], i["Kx"]) == (3, 1, 1, 2)
+    assert o.num_weights == (3 + 3 * 2 * 8) + (4 + 4 * 3 * 2) + (5 + 5 * 12) + (3 + 3 * 5)
+    # one number stands for both directions
+    a, b = oracle.Oracle("1x12x12-2C3x3S1x1-MP1x1-3N"), oracle.Oracle("1x12x12-2C3S1-MP1-3N")
+    assert [a.layer_info(l) for l in range(a.num_layers)] == [b.layer_info(l) for l in range(b.num_layers)]
+
+
 def test_kinds():
     o = oracle.Oracle("1x29x29-20C4-MP2-40C5-MP3-150N-10N")
     kinds = [o.layer_info(l)["kind"] for l in range(1, o.num_layers)]
@@ -122,6 +137,9 @@ def test_kinds():
     ("1x4x4-20C5-10N", E_SHAPE),            # kernel larger than the image (Sec. 2.2)
     ("0x4x4-10N", E_SHAPE), ("1x29x29-0C4-10N", E_SHAPE), ("1x29x29-20C4-MP0-10N", E_SHAPE),
     ("1x29x29--10N", E_SYNTAX), ("1x29x29-20C4S-10N", E_SYNTAX), ("1x29x29-20C4-10N-", E_SYNTAX),
+    ("1x29x29-20C4x-10N", E_SYNTAX), ("1x29x29-20C4x0-10N", E_SHAPE), ("1x29x29-20C4-MP2x-10N", E_SYNTAX),
+    ("1x29x29-20C4-MP2x3-10N", E_SHAPE),    # 26 columns are not a multiple of 3
+    ("1x29x29-20C4x30-10N", E_SHAPE),       # kernel wider than the image
 ])
 def test_rejected_architectures(arch, code):
     with pytest.raises(OracleError) as e:

@@ -14,13 +14,17 @@ def parse(arch):
     c, h, w = (int(v) for v in toks[0].split("x"))
     layers = []
     for t in toks[1:]:
-        m = re.fullmatch(r"(\d+)C(\d+)(?:S(\d+))?", t)
+        m = re.fullmatch(r"(\d+)C(\d+)(?:x(\d+))?(?:S(\d+)(?:x(\d+))?)?", t)
         if m:
-            layers.append(("conv", int(m.group(1)), int(m.group(2)), int(m.group(3) or 0)))
+            ky = int(m.group(2))
+            kx = int(m.group(3) or ky)
+            sy = int(m.group(4) or 0)
+            sx = int(m.group(5) or sy)
+            layers.append(("conv", int(m.group(1)), (ky, kx), (sy, sx)))
             continue
-        m = re.fullmatch(r"MP(\d+)", t)
+        m = re.fullmatch(r"MP(\d+)(?:x(\d+))?", t)
         if m:
-            layers.append(("pool", int(m.group(1))))
+            layers.append(("pool", (int(m.group(1)), int(m.group(2) or m.group(1)))))
             continue
         m = re.fullmatch(r"(\d+)N", t)
         layers.append(("fc", int(m.group(1))))
@@ -49,7 +53,7 @@ def loss_and_grads(arch, weights, image, label, tables=None, frontend=None, tanh
     maps = c
     for li, l in enumerate(layers):
         if l[0] == "conv":
-            _, mo, k, s = l
+            _, mo, (ky, kx), (sy, sx) = l
             table = np.asarray(tables.get(conv_idx, np.ones((mo, maps), dtype=np.uint8)))
             conv_idx += 1
             bias = wt[off:off + mo]
@@ -59,13 +63,13 @@ def loss_and_grads(arch, weights, image, label, tables=None, frontend=None, tanh
                 cols = []
                 for i in range(maps):
                     if table[j, i]:
-                        cols.append(wt[off:off + k * k].reshape(k, k))
-                        off += k * k
+                        cols.append(wt[off:off + ky * kx].reshape(ky, kx))
+                        off += ky * kx
                     else:
-                        cols.append(torch.zeros(k, k, dtype=torch.float64))
+                        cols.append(torch.zeros(ky, kx, dtype=torch.float64))
                 rows.append(torch.stack(cols))
             dense = torch.stack(rows)
-            x = A * torch.tanh(B * torch.nn.functional.conv2d(x, dense, bias, stride=s + 1))
+            x = A * torch.tanh(B * torch.nn.functional.conv2d(x, dense, bias, stride=(sy + 1, sx + 1)))
             maps = mo
         elif l[0] == "pool":
             x = torch.nn.functional.max_pool2d(x, l[1])
