@@ -79,6 +79,11 @@ enum {
  *                 where the fraction is not integral (the kernel stays inside the map).
  *   MP<K>         max-pooling over non-overlapping KxK rectangles (Sec. 2.3); must follow a
  *                 convolutional layer and K must divide the map size.
+ *   K and s may each be written <y>x<x>, rows then columns (Sec. 2.2 and 2.3 give kernel sizes,
+ *   skipping factors and pooling rectangles an x and a y value): "8C4x2S1x0", "MP2x5".  Eq. 1
+ *   then holds axis by axis.  Layers whose x and y values differ run on the vector kernels
+ *   of the stage and persistent modes; the resident mode and cnn_forward_batch refuse them
+ *   (CNN_E_STATE / CNN_E_SHAPE).
  *   <N>N          fully connected layer of N neurons (Sec. 2.4).  The last token must be
  *                 one: the output layer, one unit per class.  Hidden fully connected layers
  *                 use the scaled tanh y = 1.7159 tanh(0.6666 a) (Sec. 4); the output layer
@@ -95,6 +100,8 @@ enum {
  * {kind, maps, rows, cols, K, S}; at most max_layers layers are written; *n_layers gets
  * the full count.  No device is touched. */
 int cnn_arch_info(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers);
+/* The same with 8 int32 per layer: {kind, maps, rows, cols, Ky, Sy, Kx, Sx} (cnn_arch_info reports the y values). */
+int cnn_arch_info_xy(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers);
 
 /* Host-only: bytes of device workspace cnn_create needs for `arch` (an upper bound that
  * also covers any connection table and front-end set later).  Fails with CNN_E_SHAPE when a
@@ -135,6 +142,8 @@ int cnn_num_layers(const cnn_t* net);
 int cnn_num_classes(const cnn_t* net);
 /* {kind, maps, rows, cols, K, S} of one layer */
 int cnn_layer_info(const cnn_t* net, int layer, int32_t* info6);
+/* {kind, maps, rows, cols, Ky, Sy, Kx, Sx} of one layer */
+int cnn_layer_info_xy(const cnn_t* net, int layer, int32_t* info8);
 
 /*
  * Canonical weight order for get/set, n = cnn_num_weights: layer by layer in network

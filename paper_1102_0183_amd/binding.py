@@ -37,6 +37,7 @@ def lib():
         vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32
         sig = {
             "cnn_arch_info": (C.c_int, [C.c_char_p, vp, vp, i32]),
+            "cnn_arch_info_xy": (C.c_int, [C.c_char_p, vp, vp, i32]),
             "cnn_workspace_bytes": (C.c_int, [C.c_char_p, vp]),
             "cnn_plan_text": (C.c_int, [C.c_char_p, vp, sz]),
             "cnn_get_plan_text": (C.c_int, [vp, vp, sz]),
@@ -50,6 +51,7 @@ def lib():
             "cnn_num_layers": (C.c_int, [vp]),
             "cnn_num_classes": (C.c_int, [vp]),
             "cnn_layer_info": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_layer_info_xy": (C.c_int, [vp, C.c_int, vp]),
             "cnn_get_weights": (C.c_int, [vp, vp, sz]),
             "cnn_set_weights": (C.c_int, [vp, vp, sz]),
             "cnn_forward": (C.c_int, [vp, vp, vp]),
@@ -85,9 +87,9 @@ def lib():
     return _lib
 
 
-EXPORTS = ["cnn_arch_info", "cnn_workspace_bytes", "cnn_plan_text", "cnn_get_plan_text", "cnn_create", "cnn_destroy",
+EXPORTS = ["cnn_arch_info", "cnn_arch_info_xy", "cnn_workspace_bytes", "cnn_plan_text", "cnn_get_plan_text", "cnn_create", "cnn_destroy",
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
-           "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_get_weights", "cnn_set_weights",
+           "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_layer_info_xy", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many",
            "cnn_forward_batch_scratch_bytes", "cnn_forward_batch", "cnn_set_mode",
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
@@ -132,17 +134,17 @@ def deform_images(d_src, d_dst, n, params, seed, first_index, d_src_index=None, 
 
 
 def arch_info(arch):
-    """Host-only: list of dicts {kind, maps, h, w, K, S}, layer 0 = input."""
+    """Host-only: list of dicts {kind, maps, h, w, K, S, Kx, Sx} (K, S: the y values), layer 0 = input."""
     n = C.c_int32()
-    rc = lib().cnn_arch_info(arch.encode(), C.addressof(n), None, 0)
+    rc = lib().cnn_arch_info_xy(arch.encode(), C.addressof(n), None, 0)
     if rc:
-        raise CnnError(rc, "cnn_arch_info(%r)" % arch, _err())
-    info = np.zeros((n.value, 6), dtype=np.int32)
-    rc = lib().cnn_arch_info(arch.encode(), C.addressof(n), info.ctypes.data, n.value)
+        raise CnnError(rc, "cnn_arch_info_xy(%r)" % arch, _err())
+    info = np.zeros((n.value, 8), dtype=np.int32)
+    rc = lib().cnn_arch_info_xy(arch.encode(), C.addressof(n), info.ctypes.data, n.value)
     if rc:
-        raise CnnError(rc, "cnn_arch_info(%r)" % arch, _err())
-    return [dict(kind=int(r[0]), maps=int(r[1]), h=int(r[2]), w=int(r[3]), K=int(r[4]), S=int(r[5]))
-            for r in info]
+        raise CnnError(rc, "cnn_arch_info_xy(%r)" % arch, _err())
+    return [dict(kind=int(r[0]), maps=int(r[1]), h=int(r[2]), w=int(r[3]), K=int(r[4]), S=int(r[5]),
+                 Kx=int(r[6]), Sx=int(r[7])) for r in info]
 
 
 def workspace_bytes(arch):
@@ -229,10 +231,10 @@ class Cnn:
         return int(lib().cnn_num_classes(self._h))
 
     def layer_info(self, layer):
-        info = np.zeros(6, dtype=np.int32)
-        self._ck(lib().cnn_layer_info(self._h, int(layer), info.ctypes.data), "cnn_layer_info")
+        info = np.zeros(8, dtype=np.int32)
+        self._ck(lib().cnn_layer_info_xy(self._h, int(layer), info.ctypes.data), "cnn_layer_info_xy")
         return dict(kind=int(info[0]), maps=int(info[1]), h=int(info[2]), w=int(info[3]),
-                    K=int(info[4]), S=int(info[5]))
+                    K=int(info[4]), S=int(info[5]), Kx=int(info[6]), Sx=int(info[7]))
 
     def set_mode(self, mode):
         self._ck(lib().cnn_set_mode(self._h, int(mode)), "cnn_set_mode")

@@ -48,7 +48,8 @@ thread_local std::string g_err;  // message of the last failure that had no hand
 
 struct ArchLayer {
   int kind = CNN_LAYER_INPUT;
-  int maps = 0, h = 0, w = 0, K = 0, S = 0;
+  int maps = 0, h = 0, w = 0, K = 0, S = 0;  // K, S: the y (row) values of kernel / pooling rectangle and skipping factor
+  int Kx = 0, Sx = 0;                        // their x (column) values
 };
 
 int fail(std::string* where, int code, const std::string& msg) {
@@ -57,7 +58,7 @@ int fail(std::string* where, int code, const std::string& msg) {
   return code;
 }
 
-// ---- grammar: <C>x<H>x<W> { -<M>C<K>[S<s>] | -MP<K> | -<N>N }+ ------------------------------
+// ---- grammar: <C>x<H>x<W> { -<M>C<K>[S<s>] | -MP<K> | -<N>N }+ ; K, s: <k> or <ky>x<kx> -------------
 bool take_number(const std::string& s, size_t& pos, int& v) {
   if (pos >= s.size() || !std::isdigit((unsigned char)s[pos])) return false;
   long long x = 0;
@@ -67,6 +68,17 @@ bool take_number(const std::string& s, size_t& pos, int& v) {
     ++pos;
   }
   v = (int)x;
+  return true;
+}
+
+// <k> (both directions) or <ky>x<kx> (Sec. 2.2, 2.3: an x and a y value each)
+bool take_pair(const std::string& s, size_t& pos, int& vy, int& vx) {
+  if (!take_number(s, pos, vy)) return false;
+  vx = vy;
+  if (pos < s.size() && s[pos] == 'x') {
+    ++pos;
+    if (!take_number(s, pos, vx)) return false;
+  }
   return true;
 }
 
@@ -102,34 +114,34 @@ int parse_arch(const char* arch, std::vector<ArchLayer>& out, std::string* err) 
     size_t p = 0;
     if (t.size() >= 2 && t[0] == 'M' && t[1] == 'P') {
       p = 2;
-      if (!take_number(t, p, l.K) || p != t.size()) return fail(err, CNN_E_SYNTAX, "bad pooling token '" + t + "'");
+      if (!take_pair(t, p, l.K, l.Kx) || p != t.size()) return fail(err, CNN_E_SYNTAX, "bad pooling token '" + t + "'");
       if (prev.kind != CNN_LAYER_CONV)
         return fail(err, CNN_E_SYNTAX, "'" + t + "': max-pooling must follow a convolutional layer");
-      if (l.K < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty pooling rectangle");
-      if (prev.h % l.K || prev.w % l.K)
+      if (l.K < 1 || l.Kx < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty pooling rectangle");
+      if (prev.h % l.K || prev.w % l.Kx)
         return fail(err, CNN_E_SHAPE, "'" + t + "': rectangle does not tile a " + std::to_string(prev.h) + "x" +
                                           std::to_string(prev.w) + " map");
       l.kind = CNN_LAYER_POOL;
       l.maps = prev.maps;
       l.h = prev.h / l.K;
-      l.w = prev.w / l.K;
+      l.w = prev.w / l.Kx;
     } else {
       int n = 0;
       if (!take_number(t, p, n) || p >= t.size()) return fail(err, CNN_E_SYNTAX, "bad token '" + t + "'");
       const char c = t[p++];
       if (c == 'C') {
-        if (!take_number(t, p, l.K)) return fail(err, CNN_E_SYNTAX, "bad kernel size in '" + t + "'");
+        if (!take_pair(t, p, l.K, l.Kx)) return fail(err, CNN_E_SYNTAX, "bad kernel size in '" + t + "'");
         if (p < t.size()) {
-          if (t[p++] != 'S' || !take_number(t, p, l.S) || p != t.size())
+          if (t[p++] != 'S' || !take_pair(t, p, l.S, l.Sx) || p != t.size())
             return fail(err, CNN_E_SYNTAX, "bad skipping factor in '" + t + "'");
         }
         if (fc_seen) return fail(err, CNN_E_SYNTAX, "'" + t + "': convolution after a fully connected layer");
-        if (n < 1 || l.K < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty layer");
+        if (n < 1 || l.K < 1 || l.Kx < 1) return fail(err, CNN_E_SHAPE, "'" + t + "': empty layer");
         l.kind = CNN_LAYER_CONV;
         l.maps = n;
         // Eq. 1 of Sec. 2.2, rounded down: the kernel stays completely inside the map
         l.h = prev.h >= l.K ? (prev.h - l.K) / (l.S + 1) + 1 : 0;
-        l.w = prev.w >= l.K ? (prev.w - l.K) / (l.S + 1) + 1 : 0;
+        l.w = prev.w >= l.Kx ? (prev.w - l.Kx) / (l.Sx + 1) + 1 : 0;
         if (l.h < 1 || l.w < 1)
           return fail(err, CNN_E_SHAPE, "'" + t + "': kernel larger than its " + std::to_string(prev.h) + "x" +
                                             std::to_string(prev.w) + " input");
@@ -270,7 +282,7 @@ size_t carve(cnn* net, void* base) {
   // upper bound on weights: every table full
   size_t nw = 0;
   for (size_t l = 1; l < A.size(); ++l) {
-    if (A[l].kind == CNN_LAYER_CONV) nw += (size_t)A[l].maps * (1 + (size_t)A[l - 1].maps * A[l].K * A[l].K);
+    if (A[l].kind == CNN_LAYER_CONV) nw += (size_t)A[l].maps * (1 + (size_t)A[l - 1].maps * A[l].K * A[l].Kx);
     if (A[l].kind == CNN_LAYER_FC) nw += (size_t)A[l].maps * (1 + (size_t)A[l - 1].maps * A[l - 1].h * A[l - 1].w);
   }
   net->n_weights_max = nw;
@@ -315,7 +327,7 @@ size_t carve(cnn* net, void* base) {
   for (size_t l = 1; l < A.size(); ++l) {
     if (A[l].kind == CNN_LAYER_CONV) {
       // a pooling rectangle of one pixel is the identity: the pooled values are the activations
-      const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL && A[l + 1].K > 1;
+      const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL && (A[l + 1].K > 1 || A[l + 1].Kx > 1);
       const size_t full = (size_t)A[l].maps * A[l].h * A[l].w;
       const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : full;
       const size_t nc = (size_t)A[l].maps * A[l - 1].maps;
@@ -368,7 +380,7 @@ int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
   st.n_tiles = (Ho + rows - 1) / rows;
   st.n_items = L.Mo * st.n_tiles;
   const int map_sz = ((rows - 1) * (L.S + 1) + L.K) * L.Wi;
-  const int chunk = std::min({LDS_IN / map_sz, LDS_AUX / (L.K * L.K), L.max_conn});
+  const int chunk = std::min({LDS_IN / map_sz, LDS_AUX / (L.K * L.Kx), L.max_conn});
   if (chunk < 1) return fail(err, CNN_E_SHAPE, "convolution input rows do not fit the LDS staging area");
   st.chunk = chunk;
   st.tw_log2 = ceil_log2(std::min(map_sz, WG));
@@ -414,7 +426,7 @@ int check_plan(cnn* net) {
         if (st.pix_per_thread == 1 ? P_max > WG : P_max > MAX_TILE_PIX) return bad(s, "row band too large");
         if (st.pix_per_thread != 1 && st.pix_per_thread != 2) return bad(s, "bad pixels per thread");
         if (st.chunk < 1 || (long long)st.chunk * map_sz > LDS_IN) return bad(s, "input chunk exceeds the LDS input area");
-        if (st.chunk * L.K * L.K > LDS_AUX) return bad(s, "filter chunk exceeds the LDS filter area");
+        if (st.chunk * L.K * L.Kx > LDS_AUX) return bad(s, "filter chunk exceeds the LDS filter area");
         if (st.n_tiles * st.tile_rows < L.Ho || st.n_items != L.Mo * st.n_tiles) return bad(s, "row bands do not cover the map");
         if ((1 << st.tw_log2) > WG) return bad(s, "staging width");
         break;
@@ -422,7 +434,7 @@ int check_plan(cnn* net) {
       case ST_CONV_BWD: {
         const int pt = 1 << st.tw_log2;
         if (st.chunk < 1 || (long long)st.chunk * (L.Ho + 1) * (L.Wo + 1) > LDS_IN) return bad(s, "delta chunk exceeds its LDS area");
-        if (st.chunk * L.K * L.K > LDS_AUX) return bad(s, "filter chunk exceeds its LDS area");
+        if (st.chunk * L.K * L.Kx > LDS_AUX) return bad(s, "filter chunk exceeds its LDS area");
         if (pt < 1 || pt > WG || st.n_tiles * pt < L.Hi * L.Wi || st.n_items != L.Mi * st.n_tiles) return bad(s, "pixel tiles do not cover the map");
         if (st.layer < 1) return bad(s, "no layer below");
         break;
@@ -452,7 +464,7 @@ int check_plan(cnn* net) {
         const int KK = L.K * L.K, HiWi = L.Hi * L.Wi, Pn = L.Ho * L.Wo;
         const int NT = (Pn + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
         const int WP = st.chunk * KK + 1 + ((st.chunk * KK) & 1);
-        if (!L.full_table || !mfma_shape_ok(L.Mi, L.K, L.Mo, L.Ho, L.Wo)) return bad(s, "layer not fit for the matrix-core kernel");
+        if (L.rect || !L.full_table || !mfma_shape_ok(L.Mi, L.K, L.Mo, L.Ho, L.Wo)) return bad(s, "layer not fit for the matrix-core kernel");
         if (st.chunk < 1 || (long long)st.chunk * HiWi + 32LL * WP + (long long)st.chunk * KK > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
         if (st.n_tiles < 1 || st.n_tiles > L.Mi || st.n_items != ((L.Mo + 31) / 32) * st.n_tiles) return bad(s, "slices do not cover the input maps");
         if (st.rows_per_wg != st.n_tiles || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "too many partial-sum planes");
@@ -465,7 +477,7 @@ int check_plan(cnn* net) {
         const int NT = (Pn + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
         const int WP = st.chunk * KK + 1 + ((st.chunk * KK) & 1);
         if (net->mode != CNN_MODE_STAGES) return bad(s, "the matrix-core pull is planned for the stage-launch mode only");
-        if (!L.full_table || !mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) return bad(s, "layer not fit for the matrix-core pull");
+        if (L.rect || !L.full_table || !mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) return bad(s, "layer not fit for the matrix-core pull");
         if (st.chunk < 1 || (long long)st.chunk * HWd + 32LL * WP + (long long)st.chunk * KK > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
         if (st.n_tiles < 1 || st.n_tiles > L.Mo || st.n_items != ((L.Mi + 31) / 32) * st.n_tiles) return bad(s, "slices do not cover the output maps");
         if (st.rows_per_wg != st.n_tiles || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "too many partial-sum planes");
@@ -478,7 +490,7 @@ int check_plan(cnn* net) {
         const int KK = L.K * L.K, Pn = L.Ho * L.Wo, WP = Pn + 1 + (Pn & 1);
         const int NT = (std::min(st.chunk, L.Mi) * KK + 31) / 32, waves = WG / 64, KW = NT >= waves ? 1 : waves / NT;
         if (net->mode != CNN_MODE_STAGES) return bad(s, "the matrix-core gradient is planned for the stage-launch mode only");
-        if (!L.full_table || !mfma_wgrad_shape_ok(L.Mi, L.K, L.Mo, L.Hi, L.Wi, L.Ho, L.Wo)) return bad(s, "layer not fit for the matrix-core gradient");
+        if (L.rect || !L.full_table || !mfma_wgrad_shape_ok(L.Mi, L.K, L.Mo, L.Hi, L.Wi, L.Ho, L.Wo)) return bad(s, "layer not fit for the matrix-core gradient");
         if (st.chunk < 1 || (long long)st.chunk * L.Hi * L.Wi + 32LL * WP + Pn > LDS_FLOATS) return bad(s, "chunk exceeds LDS");
         if (NT > 4 * waves) return bad(s, "too many column tiles");
         if (KW * NT * 1024 > LDS_FLOATS) return bad(s, "k splits do not fit LDS");
@@ -528,15 +540,17 @@ int plan(cnn* net) {
       L.kind = L_CONV;
       L.Mi = A[l - 1].maps; L.Hi = A[l - 1].h; L.Wi = A[l - 1].w;
       L.Mo = A[l].maps; L.Ho = A[l].h; L.Wo = A[l].w;
-      L.K = A[l].K; L.S = A[l].S;
+      L.K = A[l].K; L.S = A[l].S; L.Kx = A[l].Kx; L.Sx = A[l].Sx;
       L.Kp = pooled ? A[l + 1].K : 1;
-      L.Hp = L.Ho / L.Kp; L.Wp = L.Wo / L.Kp;
+      L.Kpx = pooled ? A[l + 1].Kx : 1;
+      L.rect = (L.K != L.Kx || L.S != L.Sx || L.Kp != L.Kpx) ? 1 : 0;
+      L.Hp = L.Ho / L.Kp; L.Wp = L.Wo / L.Kpx;
       if (L.Ho >= 65536 || L.Wo >= 65536) return fail(&net->err, CNN_E_SHAPE, "map too large");
       if (L.Hp * L.Wp > MAX_POOLED_PIX)
         return fail(&net->err, CNN_E_SHAPE, "pooled map has more than " + std::to_string(MAX_POOLED_PIX) + " positions");
       if (L.Hi * L.Wi > LDS_IN || (L.Ho + 1) * (L.Wo + 1) > LDS_IN)
         return fail(&net->err, CNN_E_SHAPE, "a map has more than " + std::to_string(LDS_IN) + " pixels");
-      if (L.Kp > 15) return fail(&net->err, CNN_E_SHAPE, "pooling rectangle larger than 15x15");
+      if (L.Kp > 15 || L.Kpx > 15) return fail(&net->err, CNN_E_SHAPE, "pooling rectangle larger than 15x15");
       const cnn::ConvBuf& b = net->conv_buf[conv_i];
       L.act = b.act; L.out = b.out; L.delta = b.delta; L.arg = b.arg; L.argyx = b.argyx;
       L.csr_ptr = b.csr_ptr; L.csr_idx = b.csr_idx; L.csc_ptr = b.csc_ptr; L.csc_j = b.csc_j; L.csc_slot = b.csc_slot;
@@ -548,7 +562,7 @@ int plan(cnn* net) {
       const size_t n_conn = net->host_tables[conv_i].csr_idx.size();
       L.b_canon = (long long)woff;
       L.w_canon = (long long)(woff + L.Mo);
-      woff += L.Mo + n_conn * L.K * L.K;
+      woff += L.Mo + n_conn * L.K * L.Kx;
       ++conv_i;
     } else {
       L.kind = L_FC;
@@ -599,7 +613,7 @@ int plan(cnn* net) {
   if (fe) add(ST_FRONTEND, 0, (net->fe_n * A[0].h * A[0].w + WG - 1) / WG, 1, 0);
   for (int l = 0; l < nl; ++l) {  // forward, bottom up
     LayerDev& L = P.layers[l];
-    if (L.kind == L_CONV && net->use_mfma && L.full_table && mfma_shape_ok(L.Mi, L.K, L.Mo, L.Ho, L.Wo)) {
+    if (L.kind == L_CONV && net->use_mfma && !L.rect && L.full_table && mfma_shape_ok(L.Mi, L.K, L.Mo, L.Ho, L.Wo)) {
       // wide layer: implicit GEMM on the matrix cores, the contraction split over workgroups, then
       // a second stage that adds the partial sums and does what follows the sum
       const int n_cu = net->n_cu > 0 ? net->n_cu : 256;
@@ -637,7 +651,7 @@ int plan(cnn* net) {
   int pending_wgrad = -1;
   auto add_wgrad = [&](int l, int barrier) {
     LayerDev& L = P.layers[l];
-    if (net->use_mfma && net->mode == CNN_MODE_STAGES && L.full_table &&
+    if (net->use_mfma && net->mode == CNN_MODE_STAGES && !L.rect && L.full_table &&
         mfma_wgrad_shape_ok(L.Mi, L.K, L.Mo, L.Hi, L.Wi, L.Ho, L.Wo)) {
       // wide layer, one launch per stage: the gradients as a matrix product over the output pixels.
       // Input maps per work item: about one work item per compute unit, whole column tiles of 32
@@ -682,7 +696,7 @@ int plan(cnn* net) {
         // pull deltas into layer l-1 (reads the old weights of layer l) ...
         const bool with_pending = pending_wgrad >= 0;
         if (with_pending) { add_wgrad(pending_wgrad, 0); pending_wgrad = -1; }
-        if (net->use_mfma && net->mode == CNN_MODE_STAGES && L.full_table &&
+        if (net->use_mfma && net->mode == CNN_MODE_STAGES && !L.rect && L.full_table &&
             mfma_bwd_shape_ok(L.Mi, L.K, L.S, L.Mo, L.Hi, L.Wi)) {
           // wide layer, one launch per stage (the persistent kernel does not hold this stage kind:
           // its registers would slow every other stage): the pull as FP's mirror image on the matrix cores, the contraction over the
@@ -705,7 +719,7 @@ int plan(cnn* net) {
           }
         }
         Stage& s = add(ST_CONV_BWD, l, 0, 1, 1);
-        const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.K;
+        const int Pin = L.Hi * L.Wi, HW = L.Hp * L.Wp, KK = L.K * L.Kx;
         const int max_back = net->host_tables[conv_of_dev[l]].max_back;
         // pixel tile: a power of two between 16 and 1024, small enough to give about 256 work items
         int pt = WG;
@@ -759,6 +773,7 @@ void plan_flow(cnn* net) {
   Z.n_conv = n_conv; Z.n_fc = n_fc; Z.n_classes = P.n_classes; Z.out_units = net->out_units;
   for (int l = 0; l < n_conv; ++l) {
     const LayerDev& L = P.layers[l];
+    if (L.rect) return no("resident mode takes kernels, skipping factors and pooling rectangles with equal x and y values only");
     ConvSpec& C = Z.conv[l];
     C.Mi = L.Mi; C.Hi = L.Hi; C.Wi = L.Wi; C.Mo = L.Mo; C.Ho = L.Ho; C.Wo = L.Wo;
     C.K = L.K; C.S = L.S; C.Kp = L.Kp; C.Hp = L.Hp; C.Wp = L.Wp;
@@ -818,7 +833,7 @@ int upload(cnn* net) {
     HIP_TRY(net, hipMemcpy(b.csc_ptr, T.csc_ptr.data(), T.csc_ptr.size() * 4, hipMemcpyHostToDevice));
     HIP_TRY(net, hipMemcpy(b.csc_j, T.csc_j.data(), T.csc_j.size() * 4, hipMemcpyHostToDevice));
     HIP_TRY(net, hipMemcpy(b.csc_slot, T.csc_slot.data(), T.csc_slot.size() * 4, hipMemcpyHostToDevice));
-    if (L.Kp == 1) {  // no pooling: every neuron is its own winner
+    if (L.Kp == 1 && L.Kpx == 1) {  // no pooling: every neuron is its own winner
       std::vector<int> yx((size_t)L.Mo * L.Ho * L.Wo);
       for (int j = 0; j < L.Mo; ++j)
         for (int y = 0; y < L.Ho; ++y)
@@ -977,6 +992,8 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     BatchGemm& g = st.g;
     std::memset(&g, 0, sizeof(g));
     int Kp = 1, Ho = 1, Hp = 1, Wp = 1;
+    if (L.kind == L_CONV && L.rect)
+      return fail(&net->err, CNN_E_SHAPE, "the batched forward pass takes kernels, skipping factors and pooling rectangles with equal x and y values only");
     if (L.kind == L_CONV) {
       g.Mi = L.Mi; g.Hi = L.Hi; g.Wi = L.Wi; g.K = L.K; g.stride = L.S + 1; g.Mo = L.Mo; g.Wo = L.Wo;
       g.P = L.Ho * L.Wo; Ho = L.Ho; Kp = L.Kp; Hp = L.Hp; Wp = L.Wp;
@@ -1081,6 +1098,20 @@ int cnn_arch_info(const char* arch, int32_t* n_layers, int32_t* info, int32_t ma
     for (size_t l = 0; l < A.size() && (int32_t)l < max_layers; ++l) {
       int32_t* o = info + 6 * l;
       o[0] = A[l].kind; o[1] = A[l].maps; o[2] = A[l].h; o[3] = A[l].w; o[4] = A[l].K; o[5] = A[l].S;
+    }
+  return CNN_OK;
+}
+
+int cnn_arch_info_xy(const char* arch, int32_t* n_layers, int32_t* info, int32_t max_layers) {
+  std::vector<ArchLayer> A;
+  int rc = parse_arch(arch, A, nullptr);
+  if (rc) return rc;
+  if (n_layers) *n_layers = (int32_t)A.size();
+  if (info)
+    for (size_t l = 0; l < A.size() && (int32_t)l < max_layers; ++l) {
+      int32_t* o = info + 8 * l;
+      o[0] = A[l].kind; o[1] = A[l].maps; o[2] = A[l].h; o[3] = A[l].w; o[4] = A[l].K; o[5] = A[l].S;
+      o[6] = A[l].Kx; o[7] = A[l].Sx;
     }
   return CNN_OK;
 }
@@ -1210,6 +1241,13 @@ int cnn_layer_info(const cnn_t* net, int layer, int32_t* o) {
   if (!net || !o || layer < 0 || layer >= (int)net->arch.size()) return CNN_E_ARG;
   const ArchLayer& a = net->arch[layer];
   o[0] = a.kind; o[1] = a.maps; o[2] = a.h; o[3] = a.w; o[4] = a.K; o[5] = a.S;
+  return CNN_OK;
+}
+
+int cnn_layer_info_xy(const cnn_t* net, int layer, int32_t* o) {
+  if (!net || !o || layer < 0 || layer >= (int)net->arch.size()) return CNN_E_ARG;
+  const ArchLayer& a = net->arch[layer];
+  o[0] = a.kind; o[1] = a.maps; o[2] = a.h; o[3] = a.w; o[4] = a.K; o[5] = a.S; o[6] = a.Kx; o[7] = a.Sx;
   return CNN_OK;
 }
 

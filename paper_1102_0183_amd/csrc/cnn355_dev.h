@@ -35,9 +35,13 @@ enum LayerKind : int { L_CONV = 1, L_FC = 3 };
 // convolutional layer it follows (Kp = 1 when there is none).
 struct LayerDev {
   int kind;
-  // convolution geometry: Mi maps of Hi x Wi in, Mo maps of Ho x Wo out, K x K kernel,
-  // skipping factor S (stride S+1), pooled by Kp to Hp x Wp
+  // convolution geometry: Mi maps of Hi x Wi in, Mo maps of Ho x Wo out, K x Kx kernel,
+  // skipping factors S, Sx (strides S+1, Sx+1), pooled by Kp x Kpx to Hp x Wp
   int Mi, Hi, Wi, Mo, Ho, Wo, K, S, Kp, Hp, Wp;
+  // Sec. 2.2 and 2.3 give kernel, skipping factor and pooling rectangle an x and a y value each: K, S, Kp are
+  // the y (row) values, Kx, Sx, Kpx the x (column) values; rect = some pair differs (such a layer runs on the
+  // vector stage kernels only)
+  int Kx, Sx, Kpx, rect;
   int n_in, n_out;     // fully connected: W is [n_out][n_in]
   int is_output;       // output layer
   int out_units;       // output layer: 0 soft-max + cross-entropy, 1 scaled tanh + squared error (targets +-1)

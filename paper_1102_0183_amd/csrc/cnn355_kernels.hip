@@ -170,18 +170,18 @@ __device__ void frontend_item(const FrontendDev& fe, int item, const gfloat* ima
 // part of the forward stage that is compiled once per kernel size (KT = 0: any size)
 template <int KT, int TT>
 __device__ __forceinline__ void conv_fwd_mac(const float* lds_in, const float* lds_w, int c_first,
-                                             int n, int R, int map_sz, int Wi, int Krt,
+                                             int n, int R, int map_sz, int Wi, int Krt, int Kxrt,
                                              const int (&base)[TT], float (&acc)[TT]) {
-  const int K = KT ? KT : Krt;
-  const int KK = K * K;
+  const int K = KT ? KT : Krt, Kx = KT ? KT : Kxrt;  // KT: a square kernel of that size
+  const int KK = K * Kx;
   for (int c = c_first; c < n; c += R) {
     const float* ip = lds_in + c * map_sz;
     const float* wp = lds_w + c * KK;
 #pragma unroll
     for (int ky = 0; ky < K; ++ky) {
 #pragma unroll
-      for (int kx = 0; kx < K; ++kx) {
-        const float wv = wp[ky * K + kx];
+      for (int kx = 0; kx < Kx; ++kx) {
+        const float wv = wp[ky * Kx + kx];
         const int off = ky * Wi + kx;
 #pragma unroll
         for (int t = 0; t < TT; ++t) acc[t] = fmaf(wv, ip[base[t] + off], acc[t]);
@@ -194,10 +194,10 @@ template <int TT>
 __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
                               const gfloat* in, float* lds) {
   const int tid = threadIdx.x;
-  const int K = L.K;
-  const int KK = K * K;
+  const int K = L.K, Kx = L.Kx;
+  const int KK = K * Kx;
   const int Wi = L.Wi, Wo = L.Wo, Ho = L.Ho;
-  const int stride = L.S + 1;
+  const int stride = L.S + 1, stride_x = L.Sx + 1;
   const int j = item / st.n_tiles;
   const int tile = item - j * st.n_tiles;
   const int y0 = tile * st.tile_rows;
@@ -234,7 +234,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     const int p = p0 + t * WG;
     const bool ok = (r < R) && (p < P);
     const int y = p / Wo, x = p - y * Wo;
-    base[t] = ok ? (y * stride * Wi + x * stride) : 0;  // idle lanes read a valid address, result unused
+    base[t] = ok ? (y * stride * Wi + x * stride_x) : 0;  // idle lanes read a valid address, result unused
     acc[t] = 0.f;
   }
 
@@ -255,12 +255,12 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     DBG(3);
     {
       const int c_first = min(r, R - 1);  // lanes beyond the R splits repeat split R-1, unused
-      switch (K) {
-        case 2: conv_fwd_mac<2, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
-        case 3: conv_fwd_mac<3, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
-        case 4: conv_fwd_mac<4, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
-        case 5: conv_fwd_mac<5, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
-        default: conv_fwd_mac<0, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, base, acc); break;
+      switch (K == Kx ? K : 0) {  // compiled sizes are square; any other kernel takes the run-time loop
+        case 2: conv_fwd_mac<2, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
+        case 3: conv_fwd_mac<3, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
+        case 4: conv_fwd_mac<4, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
+        case 5: conv_fwd_mac<5, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
+        default: conv_fwd_mac<0, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
       }
     }
     __syncthreads();
@@ -284,24 +284,24 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   }
   __syncthreads();
   DBG(6);
-  const int Kp = L.Kp;
-  if (Kp > 1) {
+  const int Kp = L.Kp, Kpx = L.Kpx;
+  if (Kp > 1 || Kpx > 1) {
     const int Wp = L.Wp;
     const int nq = (rows / Kp) * Wp;
     for (int q = tid; q < nq; q += WG) {
       const int py = q / Wp, px = q - py * Wp;
-      const float* win = lds_out + py * Kp * Wo + px * Kp;
+      const float* win = lds_out + py * Kp * Wo + px * Kpx;
       float best = win[0];
       int wy = 0, wx = 0;
       for (int dy = 0; dy < Kp; ++dy)
-        for (int dx = 0; dx < Kp; ++dx) {
+        for (int dx = 0; dx < Kpx; ++dx) {
           const float v = win[dy * Wo + dx];
           if (v > best) { best = v; wy = dy; wx = dx; }
         }
       const size_t o = ((size_t)j * L.Hp + (y0 / Kp + py)) * Wp + px;
       L.out[o] = best;
-      L.arg[o] = (uint8_t)(wy * Kp + wx);
-      L.argyx[o] = ((y0 + py * Kp + wy) << 16) | (px * Kp + wx);
+      L.arg[o] = (uint8_t)(wy * Kpx + wx);
+      L.argyx[o] = ((y0 + py * Kp + wy) << 16) | (px * Kpx + wx);
     }
     __syncthreads();
   }
@@ -842,9 +842,9 @@ __device__ __forceinline__ float conv_bwd_mac(const float* lds_d, const float* l
 __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage& st, int item,
                               float* lds) {
   const int tid = threadIdx.x;
-  const int K = L.K;
-  const int KK = K * K;
-  const int stride = L.S + 1;
+  const int K = L.K, Kx = L.Kx;
+  const int KK = K * Kx;
+  const int stride = L.S + 1, stride_x = L.Sx + 1;
   const int Wi = L.Wi, Pin = L.Hi * L.Wi;
   const int Ho = L.Ho, Wo = L.Wo, HW = L.Hp * L.Wp;
   // the staged delta maps carry one extra row and one extra column of zeros: a kernel tap that
@@ -873,8 +873,8 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
   };
   auto col_off = [&](int kx) {
     const int rx = pc - kx;
-    const int x = rx / stride;
-    const bool ok = active && rx >= 0 && rx - x * stride == 0 && x < Wo;
+    const int x = rx / stride_x;
+    const bool ok = active && rx >= 0 && rx - x * stride_x == 0 && x < Wo;
     return ok ? x : Wo;
   };
   int yo[5], xo[5];
@@ -926,7 +926,7 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
           lds_d[cv[u] * HWd + (yxv[u] >> 16) * Wd + (yxv[u] & 0xffff)] = dv[u];
     }
     __syncthreads();
-    switch (K) {
+    switch (K == Kx ? K : 0) {  // compiled sizes are square; any other kernel takes the run-time loop
       case 1: acc = conv_bwd_mac<1>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
       case 2: acc = conv_bwd_mac<2>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
       case 3: acc = conv_bwd_mac<3>(lds_d, lds_w, r, n, R, HWd, yo, xo, acc); break;
@@ -938,7 +938,7 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
           const float* wp = lds_w + c * KK;
           for (int ky = 0; ky < K; ++ky) {
             const int ro = row_off(ky);
-            for (int kx = 0; kx < K; ++kx) acc = fmaf(dp[ro + col_off(kx)], wp[ky * K + kx], acc);
+            for (int kx = 0; kx < Kx; ++kx) acc = fmaf(dp[ro + col_off(kx)], wp[ky * Kx + kx], acc);
           }
         }
         break;
@@ -967,9 +967,9 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
 __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
                                 const gfloat* in, const Ctx& ctx, float* lds) {
   const int tid = threadIdx.x;
-  const int K = L.K;
-  const int KK = K * K;
-  const int stride = L.S + 1;
+  const int K = L.K, Kx = L.Kx;
+  const int KK = K * Kx;
+  const int stride = L.S + 1, stride_x = L.Sx + 1;
   const int Wi = L.Wi, Min = L.Hi * L.Wi, HW = L.Hp * L.Wp;
   const int j = item / st.n_tiles;
   const int kc = item - j * st.n_tiles;
@@ -1021,13 +1021,13 @@ __device__ void conv_wgrad_item(const LayerDev& L, const Stage& st, int item,
   // gradient of weight wi of the chunk, summed over the pooled positions q = q0, q0 + qs, ...
   auto grad_of = [&](int wi, int q0, int qs) {
     const int c = wi / KK, t = wi - c * KK;
-    const int ky = t / K, kx = t - ky * K;
+    const int ky = t / Kx, kx = t - ky * Kx;
     const float* ip = lds_in + c * Min + ky * Wi + kx;
     float s = 0.f;
 #pragma unroll 4
     for (int q = q0; q < HW; q += qs) {
       const int yx = lds_yx[q];
-      s = fmaf(lds_dp[q], ip[((yx >> 16) * Wi + (yx & 0xffff)) * stride], s);
+      s = fmaf(lds_dp[q], ip[(yx >> 16) * stride * Wi + (yx & 0xffff) * stride_x], s);
     }
     return s;
   };

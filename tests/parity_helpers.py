@@ -74,11 +74,11 @@ def compare_forward_state(g, o, tol=TOL_ACT, report=None):
             argo, argg = o.argmax(l), g.argmax(l)
             diff = np.argwhere(argo != argg)
             if len(diff):
-                K = info["K"]
+                K, Kx = info["K"], info["Kx"]
                 full = o.activation(l - 1)
                 scale = np.abs(full).max()
                 for j, y, x in diff:
-                    win = np.sort(full[j, y * K:(y + 1) * K, x * K:(x + 1) * K].ravel())
+                    win = np.sort(full[j, y * K:(y + 1) * K, x * Kx:(x + 1) * Kx].ravel())
                     assert win[-1] - win[-2] <= tol * scale, "arg-max differs away from a tie"
                 n_arg_diff += len(diff)
     if report is not None:
@@ -109,7 +109,7 @@ def layer_bounds(o):
         if info["kind"] == KIND_CONV:
             t = getattr(o, "tables", {}).get(conv_i)
             n_conn = int(np.count_nonzero(t)) if t is not None else info["maps"] * prev["maps"]
-            n = info["maps"] + n_conn * info["K"] * info["K"]
+            n = info["maps"] + n_conn * info["K"] * info["Kx"]
             conv_i += 1
         elif info["kind"] == KIND_FC:
             n = info["maps"] * (1 + prev["maps"] * prev["h"] * prev["w"])

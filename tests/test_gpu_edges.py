@@ -30,6 +30,12 @@ SHAPES = [
     ("1x70x70-4C3-MP4-3C4-MP2-6N", {}, 0, 1),                # several row bands per map, ragged last band
     ("3x34x47-7C4S1-8C3-MP2-9C2-MP3-20N-6N", {1: 4, 2: 5}, 0, 3),   # rectangular maps, three conv layers
     ("1x40x40-70C5-MP4-300C3-MP1-10N", {}, 0, 1),            # many maps on few pixels: chunked connection lists
+    # kernels, skipping factors and pooling rectangles whose x and y values differ (Sec. 2.2, 2.3)
+    ("2x14x11-3C4x2S1x0-MP2x5-4C1x2-5N-3N", {1: 2}, 0, 2),
+    ("1x10x12-2C3x5-MP4x2-4N", {}, 0, 1),
+    ("1x9x9-2C2S0x1-MP2x1-3C2x1S1x0-3N", {}, 0, 1),
+    ("3x40x33-9C5x3S1x2-MP2x1-8C2x4-MP1x2-7C3x1S0x1-12N-5N", {1: 4, 2: 3}, 0, 3),   # three such layers, sparse tables
+    ("1x30x70-6C7x2-MP8x3-5N", {}, 0, 1),                    # a kernel size without a compiled loop, a tall pooling rectangle
 ]
 
 
@@ -104,6 +110,23 @@ def test_create_errors():
     assert L.cnn_create(arch, None, need, None, C.addressof(h)) == binding.E_WORKSPACE
     assert L.cnn_create(arch, base, need, None, None) == binding.E_ARG
     assert b"workspace" in L.cnn_last_error(None) or L.cnn_last_error(None)
+
+
+def test_layers_with_different_x_and_y_values_run_on_the_vector_kernels_only():
+    import torch
+    g = binding.Cnn("1x10x12-2C3x5-MP4x2-4N")
+    assert g.mode_supported(binding.MODE_STAGES) and g.mode_supported(binding.MODE_PERSISTENT)
+    assert not g.mode_supported(binding.MODE_RESIDENT)
+    with pytest.raises(binding.CnnError) as e:
+        g.set_mode(binding.MODE_RESIDENT)
+    assert e.value.code == binding.E_STATE
+    with pytest.raises(binding.CnnError) as e:
+        g.forward_batch_scratch_bytes(16)
+    assert e.value.code == binding.E_SHAPE
+    info = g.layer_info(1)
+    assert (info["K"], info["Kx"], info["h"], info["w"]) == (3, 5, 8, 8)
+    g.close()
+    torch.cuda.synchronize()
 
 
 def test_argument_errors_and_bad_labels():

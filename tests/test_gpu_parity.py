@@ -64,7 +64,7 @@ def test_pooling_indices_are_exact_on_identical_inputs(name):
         if info["kind"] != KIND_POOL:
             continue
         pre = g.activation(l - 1)
-        out, arg = ops.maxpool_forward(pre.astype(np.float64), info["K"], info["K"])
+        out, arg = ops.maxpool_forward(pre.astype(np.float64), info["K"], info["Kx"])
         np.testing.assert_array_equal(g.argmax(l), arg)
         np.testing.assert_array_equal(g.activation(l).astype(np.float64), out)
     g.close()
