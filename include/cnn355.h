@@ -82,8 +82,8 @@ enum {
  *   K and s may each be written <y>x<x>, rows then columns (Sec. 2.2 and 2.3 give kernel sizes,
  *   skipping factors and pooling rectangles an x and a y value): "8C4x2S1x0", "MP2x5".  Eq. 1
  *   then holds axis by axis.  Layers whose x and y values differ run on the vector kernels
- *   of the stage and persistent modes; the resident mode and cnn_forward_batch refuse them
- *   (CNN_E_STATE / CNN_E_SHAPE).
+ *   of the stage and persistent modes and in cnn_forward_batch; the resident mode refuses
+ *   them (CNN_E_STATE).
  *   <N>N          fully connected layer of N neurons (Sec. 2.4).  The last token must be
  *                 one: the output layer, one unit per class.  Hidden fully connected layers
  *                 use the scaled tanh y = 1.7159 tanh(0.6666 a) (Sec. 4); the output layer

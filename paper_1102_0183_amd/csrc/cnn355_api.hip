@@ -991,15 +991,15 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     BatchStep st;
     BatchGemm& g = st.g;
     std::memset(&g, 0, sizeof(g));
-    int Kp = 1, Ho = 1, Hp = 1, Wp = 1;
-    if (L.kind == L_CONV && L.rect)
-      return fail(&net->err, CNN_E_SHAPE, "the batched forward pass takes kernels, skipping factors and pooling rectangles with equal x and y values only");
+    int Kp = 1, Kpx = 1, Ho = 1, Hp = 1, Wp = 1;
     if (L.kind == L_CONV) {
-      g.Mi = L.Mi; g.Hi = L.Hi; g.Wi = L.Wi; g.K = L.K; g.stride = L.S + 1; g.Mo = L.Mo; g.Wo = L.Wo;
-      g.P = L.Ho * L.Wo; Ho = L.Ho; Kp = L.Kp; Hp = L.Hp; Wp = L.Wp;
+      g.Mi = L.Mi; g.Hi = L.Hi; g.Wi = L.Wi; g.K = L.K; g.Kx = L.Kx; g.stride = L.S + 1; g.stride_x = L.Sx + 1;
+      g.Mo = L.Mo; g.Wo = L.Wo;
+      g.P = L.Ho * L.Wo; Ho = L.Ho; Kp = L.Kp; Kpx = L.Kpx; Hp = L.Hp; Wp = L.Wp;
     } else {  // a fully connected layer: n_in maps of one pixel, K = 1
-      g.Mi = L.n_in; g.Hi = 1; g.Wi = 1; g.K = 1; g.stride = 1; g.Mo = L.n_out; g.Wo = 1; g.P = 1;
+      g.Mi = L.n_in; g.Hi = 1; g.Wi = 1; g.K = 1; g.Kx = 1; g.stride = 1; g.stride_x = 1; g.Mo = L.n_out; g.Wo = 1; g.P = 1;
     }
+    const bool pooled = Kp * Kpx > 1;
     // map tiles per workgroup: the choice that pads the fewest maps, the larger on a tie
     int best_pad = 0;
     for (int mt : {4, 2, 1}) {
@@ -1007,7 +1007,7 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
       if (!best_pad || pad < best_pad) { best_pad = pad; g.MT = mt; }
     }
     g.MoPad = best_pad;
-    const int KK = g.K * g.K, HiWi = g.Hi * g.Wi;
+    const int KK = g.K * g.Kx, HiWi = g.Hi * g.Wi;
     // input maps per chunk: as many as the LDS budget takes; when that leaves several chunks,
     // prefer a chunk that also fits the prefetch registers (16 + 48 floats per thread), unless
     // such a chunk would be too short to hide anything behind.  One-pixel maps (fully connected
@@ -1025,14 +1025,15 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
       }
     };
     // Pooling inside the product: when the whole k range is one chunk, a column is a pooled pixel
-    // and the wavefront walks the Kp x Kp members of its window one after the other, keeping the
+    // and the wavefront walks the Kp x Kpx members of its window one after the other, keeping the
     // running maximum in registers; the full-resolution sums then never reach memory.
-    g.Kp = 1;
-    if (Kp > 1) {
+    g.Kp = 1; g.Kpx = 1;
+    bool pool_inside = false;
+    if (pooled) {
       fit(Hp * Wp, LDS_FLOATS);
-      if (ic == g.Mi) { g.Kp = Kp; g.P = Hp * Wp; g.Wo = Wp; }
+      if (ic == g.Mi) { g.Kp = Kp; g.Kpx = Kpx; g.P = Hp * Wp; g.Wo = Wp; pool_inside = true; }
     }
-    if (g.Kp == 1) {
+    if (!pool_inside) {
       fit(g.P, LDS_FLOATS);
       if (ic == 0) fit(g.P, LDS_FLOATS_BIG);
     }
@@ -1051,7 +1052,7 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     g.chunks_per_slice = (n_chunks + ks - 1) / ks;
     g.KS = (n_chunks + g.chunks_per_slice - 1) / g.chunks_per_slice;
     g.slice_stride = (long long)(batch * g.Mo * g.P);
-    g.fuse = ((Kp > 1 && g.Kp == 1) || g.KS > 1) ? 0 : (L.is_output ? 2 : 1);
+    g.fuse = ((pooled && !pool_inside) || g.KS > 1) ? 0 : (L.is_output ? 2 : 1);
     g.bias = L.bias;
     g.in_stride = (long long)g.Mi * HiWi;
     g.out_stride = (long long)g.Mo * g.P;
@@ -1061,7 +1062,7 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     BatchPack& k = st.pack;
     std::memset(&k, 0, sizeof(k));
     k.w = L.w; k.csr_ptr = L.csr_ptr; k.csr_idx = L.csr_idx;
-    k.is_fc = L.kind != L_CONV; k.full_table = L.full_table; k.Mi = g.Mi; k.Mo = g.Mo; k.K = g.K; k.n_in = L.n_in;
+    k.is_fc = L.kind != L_CONV; k.full_table = L.full_table; k.Mi = g.Mi; k.Mo = g.Mo; k.K = g.K; k.Kx = g.Kx; k.n_in = L.n_in;
     k.MoPad = g.MoPad;
     if (L.kind == L_CONV) {
       int ci = 0;
@@ -1072,9 +1073,9 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     }
     BatchPool& q = st.pool;
     std::memset(&q, 0, sizeof(q));
-    q.bias = L.bias; q.Mo = g.Mo; q.Ho = Ho; q.Wo = (L.kind == L_CONV) ? L.Wo : 1; q.Kp = Kp; q.Hp = Hp; q.Wp = Wp;
+    q.bias = L.bias; q.Mo = g.Mo; q.Ho = Ho; q.Wo = (L.kind == L_CONV) ? L.Wo : 1; q.Kp = Kp; q.Kpx = Kpx; q.Hp = Hp; q.Wp = Wp;
     q.n_slices = g.KS; q.slice_stride = g.slice_stride; q.act = L.is_output ? 0 : 1;
-    st.out_per_image = (Kp > 1) ? (size_t)g.Mo * Hp * Wp : (size_t)g.Mo * g.P;
+    st.out_per_image = pooled ? (size_t)g.Mo * Hp * Wp : (size_t)g.Mo * g.P;
     if (g.fuse == 0) B.sums_per_image = std::max(B.sums_per_image, up64((size_t)g.KS * g.Mo * g.P));
     // (g.P is Ho * Wo whenever fuse == 0 with pooling: pooling inside the product always has fuse != 0)
     B.act_per_image = std::max(B.act_per_image, up64(st.out_per_image));

@@ -48,7 +48,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   extern __shared__ float lds[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int lrow = lane & 31, lk = lane >> 5;
-  const int HiWi = g.Hi * g.Wi, KK = g.K * g.K;
+  const int HiWi = g.Hi * g.Wi, KK = g.K * g.Kx;
   const int slot_sz = g.IC * HiWi;
   const int KC = g.IC * KK;                        // k per full chunk
   constexpr int WROW = MT * 32;
@@ -71,7 +71,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     const int par = x >= KH, h = x - par * KH;
     const int k = min(2 * h + par, KC - 1);
     const int c = k / KK, t = k - c * KK;
-    const int ky = t / g.K, kx = t - ky * g.K;
+    const int ky = t / g.Kx, kx = t - ky * g.Kx;
     koff[x] = (c * HiWi + ky * g.Wi + kx) * 4;
   }
   const int n = n0 + wave * 32 + lrow;
@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     b = n / g.P;
     p = n - b * g.P;
     const int y = p / g.Wo, x = p - y * g.Wo;
-    pbase = (b - b_lo) * slot_sz + (y * g.Wi + x) * (g.Kp * g.stride);
+    pbase = (b - b_lo) * slot_sz + y * (g.Kp * g.stride) * g.Wi + x * (g.Kpx * g.stride_x);
   }
   v16f acc[MT], best[MT];
 #pragma unroll
@@ -192,9 +192,9 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     // Members of the pooling window, one after the other (one member, the pixel itself, without
     // pooling; with it the host has made the k range a single chunk, so a member's sums are
     // complete when its loop ends).
-    for (int d = 0; d < g.Kp * g.Kp; ++d) {
-      const int dy = d / g.Kp, dx = d - dy * g.Kp;
-      const int pb = pbase + (dy * g.Wi + dx) * g.stride;
+    for (int d = 0; d < g.Kp * g.Kpx; ++d) {
+      const int dy = d / g.Kpx, dx = d - dy * g.Kpx;
+      const int pb = pbase + dy * g.stride * g.Wi + dx * g.stride_x;
       // two k per instruction (lanes 0..31 the even one, lanes 32..63 the odd one); the operands
       // of four instructions per map tile are fetched together.  Whole groups of eight k first,
       // without any clamping; then the tail, where k beyond the chunk meets the zero row of Wt.
@@ -233,7 +233,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
 #pragma unroll
           for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
       }
-      if (g.Kp > 1) {
+      if (g.Kp * g.Kpx > 1) {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -255,7 +255,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     for (int v = 0; v < 16; ++v) {
       const int j = (mt0 + m) * 32 + (v >> 2) * 8 + lk * 4 + (v & 3);
       if (j < g.Mo) {
-        float s = (g.Kp > 1) ? best[m][v] : acc[m][v];
+        float s = (g.Kp * g.Kpx > 1) ? best[m][v] : acc[m][v];
         if (g.fuse) s += g.bias[j];
         if (g.fuse == 1) s = b_act(s);
         dst[o0 + (unsigned)j * (unsigned)g.P] = s;
@@ -275,10 +275,10 @@ __global__ void __launch_bounds__(256) k_batch_pool(BatchPool q) {
   const int w = (int)(x - bj * HpWp);
   const int j = (int)(bj % q.Mo);
   const int py = w / q.Wp, px = w - py * q.Wp;
-  cgf src = q.sums + bj * ((long long)q.Ho * q.Wo) + (py * q.Kp) * q.Wo + px * q.Kp;
+  cgf src = q.sums + bj * ((long long)q.Ho * q.Wo) + (py * q.Kp) * q.Wo + px * q.Kpx;
   float best = -INFINITY;
   for (int dy = 0; dy < q.Kp; ++dy)
-    for (int dx = 0; dx < q.Kp; ++dx) {
+    for (int dx = 0; dx < q.Kpx; ++dx) {
       float v = 0.f;
       for (int sl = 0; sl < q.n_slices; ++sl) v += src[(long long)sl * q.slice_stride + dy * q.Wo + dx];
       best = fmaxf(best, v);
@@ -316,7 +316,7 @@ __global__ void __launch_bounds__(256) k_batch_pack(BatchPack q) {
     q.wt[(long long)m * q.MoPad + j] = q.w[x];
     return;
   }
-  const int KK = q.K * q.K;
+  const int KK = q.K * q.Kx;
   const long long slot = x / KK;
   const int t = (int)(x - slot * KK);
   int j, i;
@@ -354,7 +354,7 @@ hipError_t launch_gemm_mt(hipStream_t stream, const BatchGemm& g, size_t lds_byt
 }  // namespace
 
 size_t batch_gemm_lds_bytes(const BatchGemm& g) {
-  const int KC = g.IC * g.K * g.K;
+  const int KC = g.IC * g.K * g.Kx;
   const size_t KH = ((((size_t)KC + 1) >> 1) + 3) & ~(size_t)3;
   return ((((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + 3) & ~(size_t)3) + (size_t)(KC + 1) * g.MT * 32 + 2 * KH) * sizeof(float);
 }

@@ -203,13 +203,14 @@ struct FlowPtrs {
 // One layer over a whole batch as a matrix product on the matrix cores (cnn355_batch.hip).
 struct BatchGemm {
   const CNN_GLOBAL float* in;    // [batch] images of [Mi][Hi][Wi], in_stride floats apart
-  const CNN_GLOBAL float* wt;    // [Mi*K*K][MoPad]: k = (input map, ky, kx) by output map, zero where unconnected
+  const CNN_GLOBAL float* wt;    // [Mi*K*Kx][MoPad]: k = (input map, ky, kx) by output map, zero where unconnected
   const CNN_GLOBAL float* bias;  // [Mo]
   CNN_GLOBAL float* out;         // [batch][Mo][P], out_stride floats per image (P: see below)
   long long in_stride, out_stride;
   long long N;                   // columns: batch * P
   int Mi, Hi, Wi, K, stride, Mo, MoPad, Wo, P;  // Wo, P: width and size of the column grid of one image
-  int Kp;                        // > 1: a column is a pooled pixel, its Kp x Kp window is maximised inside the product
+  int Kx, stride_x, Kpx;         // x (column) values of kernel, stride and pooling window; K, stride, Kp are the y values
+  int Kp;                        // Kp * Kpx > 1: a column is a pooled pixel, its Kp x Kpx window is maximised inside the product
   int IC;                        // input maps staged per chunk
   int n_img_max;                 // images the 128 columns of a workgroup can touch
   int MT;                        // map tiles (of 32) per workgroup: 1, 2 or 4
@@ -224,16 +225,16 @@ struct BatchPool {
   CNN_GLOBAL float* out;         // [batch][Mo][Hp][Wp]
   long long total;               // batch * Mo * Hp * Wp
   long long slice_stride;        // floats between the planes of partial sums
-  int Mo, Ho, Wo, Kp, Hp, Wp, n_slices;
+  int Mo, Ho, Wo, Kp, Kpx, Hp, Wp, n_slices;  // pooling window Kp rows x Kpx columns
   int act;                       // 1: scaled tanh, 0: none
 };
 struct BatchPack {
-  const CNN_GLOBAL float* w;     // conv: [n_conn][K*K] in table order; fc: [n_out][n_in]
+  const CNN_GLOBAL float* w;     // conv: [n_conn][K*Kx] in table order; fc: [n_out][n_in]
   CNN_GLOBAL float* wt;          // [Kdim][MoPad]
   const CNN_GLOBAL int* csr_ptr;
   const CNN_GLOBAL int* csr_idx;
   long long total;               // weights of the layer (biases apart)
-  int is_fc, full_table, Mi, Mo, K, n_in, MoPad;
+  int is_fc, full_table, Mi, Mo, K, Kx, n_in, MoPad;
 };
 
 // ---- on-line deformation of training images ---------------------------------------------------

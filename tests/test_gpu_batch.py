@@ -54,6 +54,36 @@ def test_batched_forward_matches_the_oracle(name, n, batch, n_check):
     g.close()
 
 
+@pytest.mark.parametrize("arch,fan", [
+    ("2x14x11-3C4x2S1x0-MP2x5-4C1x2-5N-3N", {1: 2}),
+    ("1x10x12-2C3x5-MP4x2-4N", {}),
+    ("3x40x33-9C5x3S1x2-MP2x1-8C2x4-MP1x2-7C3x1S0x1-12N-5N", {1: 4, 2: 3}),
+    ("1x30x70-40C7x2-MP8x3-70C2x3S0x1-MP2x1-5N", {}),      # wide enough for several map tiles and k chunks
+])
+def test_batched_forward_with_different_x_and_y_values(arch, fan):
+    """Kernels, skipping factors and pooling rectangles with an x and a y value each (Sec. 2.2, 2.3)."""
+    import oracle
+    import torch
+    print("case", arch, flush=True)
+    o0 = oracle.Oracle(arch)
+    convs = [l for l in range(1, o0.num_layers) if o0.layer_info(l)["kind"] == 1]
+    tables = {ci: synth.random_table(o0.layer_info(convs[ci])["maps"], o0.layer_info(convs[ci] - 1)["maps"], f, 77 + ci)
+              for ci, f in fan.items()}
+    g, o = build_pair(arch=arch, tables=tables, seed=5, wscale=0.3)
+    n, batch = 37, 16
+    rng = np.random.default_rng(9)
+    imgs = rng.uniform(-1, 1, (n, g.image_size)).astype(np.float32)
+    d_probs = torch.full((n * g.num_classes,), -1.0, dtype=torch.float32, device="cuda:0")
+    g.forward_batch(to_dev(imgs), n, d_probs, _scratch(g, batch), batch)
+    g.synchronize()
+    got = d_probs.cpu().numpy().reshape(n, -1)
+    want = np.stack([o.forward(imgs[i]) for i in range(n)])
+    e = np.abs(got - want).max() / np.abs(want).max()
+    print("  probabilities rel err %.2e" % e, flush=True)
+    assert e <= 1e-5
+    g.close()
+
+
 def test_batched_forward_sees_trained_weights_and_the_tanh_outputs():
     """The call reads the weights as they stand: after training in resident mode (weights live in
     LDS during a call and are written back at its end) it must see the trained values; with

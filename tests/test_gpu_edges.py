@@ -112,7 +112,7 @@ def test_create_errors():
     assert b"workspace" in L.cnn_last_error(None) or L.cnn_last_error(None)
 
 
-def test_layers_with_different_x_and_y_values_run_on_the_vector_kernels_only():
+def test_layers_with_different_x_and_y_values_are_refused_by_the_resident_mode():
     import torch
     g = binding.Cnn("1x10x12-2C3x5-MP4x2-4N")
     assert g.mode_supported(binding.MODE_STAGES) and g.mode_supported(binding.MODE_PERSISTENT)
@@ -120,9 +120,7 @@ def test_layers_with_different_x_and_y_values_run_on_the_vector_kernels_only():
     with pytest.raises(binding.CnnError) as e:
         g.set_mode(binding.MODE_RESIDENT)
     assert e.value.code == binding.E_STATE
-    with pytest.raises(binding.CnnError) as e:
-        g.forward_batch_scratch_bytes(16)
-    assert e.value.code == binding.E_SHAPE
+    assert g.forward_batch_scratch_bytes(16) > 0   # the batched forward pass takes them
     info = g.layer_info(1)
     assert (info["K"], info["Kx"], info["h"], info["w"]) == (3, 5, 8, 8)
     g.close()
