@@ -1546,9 +1546,9 @@ int cnn_deform_images(void* hip_stream, const float* d_src, size_t n_src, float*
   DeformJob J;
   J.src = d_src; J.dst = d_dst; J.disp = d_displacement; J.src_index = d_src_index;
   J.n = (long long)n; J.n_src = (long long)n_src; J.C = C; J.H = H; J.W = W;
-  J.max_tx = (float)((double)p->max_translation * W);
-  J.max_ty = (float)((double)p->max_translation * H);
-  J.max_rot = (float)((double)p->max_rotation * 3.14159265358979323846 / 180.0);
+  J.max_tx = (double)p->max_translation * W;
+  J.max_ty = (double)p->max_translation * H;
+  J.max_rot = (double)p->max_rotation * 3.14159265358979323846 / 180.0;
   J.max_shear = p->max_shear; J.max_scale = p->max_scaling; J.alpha = p->alpha; J.fill = p->fill;
   J.seed = seed; J.first_index = first_index;
   J.R = -1;

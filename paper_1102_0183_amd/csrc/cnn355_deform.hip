@@ -82,12 +82,13 @@ __global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
     const unsigned long long key = mix64(J.seed + GOLDEN * (J.first_index + (unsigned long long)k + 1ull));
     // ---- the affine part: displacement = (A - I) (u, v) + (tx, ty), A = Rot . Shear . Scale
     const unsigned long long d0 = mix64(key + GOLDEN * 1ull), d1 = mix64(key + GOLDEN * 2ull), d2 = mix64(key + GOLDEN * 3ull);
-    const float tx = sym((unsigned int)(d0 >> 32)) * J.max_tx, ty = sym((unsigned int)d0) * J.max_ty;
-    const float theta = sym((unsigned int)(d1 >> 32)) * J.max_rot, sh = sym((unsigned int)d1) * J.max_shear;
-    const float sx = 1.0f + sym((unsigned int)(d2 >> 32)) * J.max_scale, sy = 1.0f + sym((unsigned int)d2) * J.max_scale;
-    float sn, cs;
-    sincosf(theta, &sn, &cs);
-    const float a00 = cs * sx - 1.0f, a01 = (cs * sh - sn) * sy, a10 = sn * sx, a11 = (sn * sh + cs) * sy - 1.0f;
+    // (in double: the products reach tens of pixels on large maps, where a float keeps 1e-5 of a pixel at best)
+    const double tx = sym((unsigned int)(d0 >> 32)) * J.max_tx, ty = sym((unsigned int)d0) * J.max_ty;
+    const double theta = sym((unsigned int)(d1 >> 32)) * J.max_rot, sh = sym((unsigned int)d1) * J.max_shear;
+    const double sx = 1.0 + sym((unsigned int)(d2 >> 32)) * J.max_scale, sy = 1.0 + sym((unsigned int)d2) * J.max_scale;
+    double sn, cs;
+    sincos(theta, &sn, &cs);
+    const double a00 = cs * sx - 1.0, a01 = (cs * sh - sn) * sy, a10 = sn * sx, a11 = (sn * sh + cs) * sy - 1.0;
     // ---- the elastic part: two random fields, smoothed along rows, then along columns
     if (elastic) {
       __syncthreads();  // the previous image's fields have been read
@@ -133,20 +134,20 @@ __global__ void __launch_bounds__(DT) k_deform(const DeformJob J) {
     CNN_GLOBAL float* dst = J.dst + k * J.C * HW;
     for (int p = tid; p < HW; p += DT) {
       const int y = p / W, x = p - y * W;
-      const float u = (float)x - cx, v = (float)y - cy;
-      float dx = fmaf(a00, u, fmaf(a01, v, tx)), dy = fmaf(a10, u, fmaf(a11, v, ty));
+      const double u = (double)x - (double)cx, v = (double)y - (double)cy;
+      double dx = fma(a00, u, fma(a01, v, tx)), dy = fma(a10, u, fma(a11, v, ty));
       if (elastic) {
-        dx = fmaf(J.alpha, rx[y * Wp + x], dx);
-        dy = fmaf(J.alpha, ry[y * Wp + x], dy);
+        dx += (double)(J.alpha * rx[y * Wp + x]);
+        dy += (double)(J.alpha * ry[y * Wp + x]);
       }
       if (J.disp) {
-        J.disp[(k * 2) * HW + p] = dx;
-        J.disp[(k * 2 + 1) * HW + p] = dy;
+        J.disp[(k * 2) * HW + p] = (float)dx;
+        J.disp[(k * 2 + 1) * HW + p] = (float)dy;
       }
       // far outside in any direction reads the fill value only; the clamp keeps the integers small
-      const float fdx = floorf(fminf(fmaxf(dx, -(float)(W + 2)), (float)(W + 2)));
-      const float fdy = floorf(fminf(fmaxf(dy, -(float)(H + 2)), (float)(H + 2)));
-      const float fx = fminf(fmaxf(dx - fdx, 0.f), 1.f), fy = fminf(fmaxf(dy - fdy, 0.f), 1.f);
+      const double fdx = floor(fmin(fmax(dx, -(double)(W + 2)), (double)(W + 2)));
+      const double fdy = floor(fmin(fmax(dy, -(double)(H + 2)), (double)(H + 2)));
+      const float fx = fminf(fmaxf((float)(dx - fdx), 0.f), 1.f), fy = fminf(fmaxf((float)(dy - fdy), 0.f), 1.f);
       const int x0 = x + (int)fdx, y0 = y + (int)fdy;
       const bool in_x0 = x0 >= 0 && x0 < W, in_x1 = x0 + 1 >= 0 && x0 + 1 < W;
       const bool in_y0 = y0 >= 0 && y0 < H, in_y1 = y0 + 1 >= 0 && y0 + 1 < H;

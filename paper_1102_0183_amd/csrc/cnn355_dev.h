@@ -249,9 +249,11 @@ struct DeformJob {
   long long n, n_src;
   int C, H, W;
   int R;                            // taps on either side of the Gaussian's centre; -1: no elastic part
-  float max_tx, max_ty;             // pixels
-  float max_rot;                    // radians
-  float max_shear, max_scale, alpha, fill;
+  double max_tx, max_ty;            // pixels
+  double max_rot;                   // radians
+  double max_shear, max_scale;      // (the affine part of a source position is worked out in double: in float
+                                    // its rounding error grows with the displacement and with the map size)
+  float alpha, fill;
   unsigned long long seed, first_index;
   float taps[2 * DEFORM_MAX_R + 1]; // normalised to sum 1
 };

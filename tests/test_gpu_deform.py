@@ -1,7 +1,8 @@
 """On-line deformation of training images (cnn_deform_images) against the CPU oracle, through the C ABI.
 Needs a GPU (marked gpu).  Bar: the random draws are integers and must agree exactly, which shows in the
 displacements; displacements and images within 1e-5 of the oracle's largest value (fp32 against float64: a
-source position is off by about 1e-6 pixel, and neighbouring pixels differ by at most 2)."""
+source position is off by about 1e-6 pixel -- its affine part is worked out in double, the elastic part and the
+interpolation in fp32 -- and neighbouring pixels differ by at most 2)."""
 import numpy as np
 import pytest
 
@@ -106,6 +107,37 @@ def test_index_list_presentation_numbers_beyond_32_bits_and_a_long_call():
     for k in (0, 1, 8191, 8192, 8193, 16384, n - 1):
         w, wd = DO.deform_image(big[k], SEED, k, op)
         assert rel(got[k], w) <= TOL and np.abs(disp[k] - wd).max() <= TOL * max(np.abs(wd).max(), 1.0)
+
+
+def test_random_shapes_and_ranges_within_the_documented_limits():
+    """40 seeded draws of map shape (up to 96 x 96), number of maps, every range (rotations up to 90 degrees,
+    translations up to 30 % of the side, sigma up to 16) and seed: the bar must hold for all of them (the affine
+    part of a source position is worked out in double for that: displacements reach tens of pixels here)."""
+    rng = np.random.default_rng(SEED + 5)
+    worst = 0.0
+    for case in range(40):
+        while True:
+            H, W = int(rng.integers(1, 97)), int(rng.integers(1, 97))
+            if H * (W | 1) <= 9312:
+                break
+        C, n = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        sigma = float(rng.choice([0.0, 0.3, 1.0, 2.5, 6.0, 11.0, 16.0]))
+        if H * W > 3000:
+            sigma = min(sigma, 6.0)   # (keeps the oracle's two-dimensional convolution short)
+        kw = dict(max_translation=float(rng.uniform(0, 0.3)), max_rotation=float(rng.uniform(0, 90)),
+                  max_scaling=float(rng.uniform(0, 0.5)), max_shear=float(rng.uniform(0, 0.5)), sigma=sigma,
+                  alpha=float(rng.uniform(0, 40)), fill=float(rng.uniform(-2, 2)))
+        print("case", case, C, H, W, n, kw, flush=True)
+        src = rng.uniform(-1, 1, (n, C, H, W)).astype(np.float32)
+        seed, first = int(rng.integers(0, 2 ** 63)), int(rng.integers(0, 2 ** 40))
+        gp, op = params(**kw)
+        got, disp = run(src, n, gp, seed, first)
+        want, want_disp = DO.deform_images(src, seed, first, op)
+        e_i = rel(got, want)
+        e_d = float(np.abs(disp - want_disp).max() / max(np.abs(want_disp).max(), 1.0))
+        worst = max(worst, e_i, e_d)
+        assert e_i <= TOL and e_d <= TOL, (case, e_i, e_d)
+    print("  worst error %.2e" % worst, flush=True)
 
 
 def test_bad_arguments_are_refused():
