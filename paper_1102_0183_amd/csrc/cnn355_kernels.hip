@@ -1257,6 +1257,9 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
                                          const Ctx& ctx, StatusDev* status, float* lds) {
   const LayerDev& L = P.layers[st.layer];
   const gfloat* in = L.in_is_image ? ctx.image : L.in;
+  // the trainable layer below, if any (behind a fixed front-end the first layer reads a stored input
+  // but has no layer below it: nothing to pull deltas into)
+  const LayerDev* below = (L.in_is_image || st.layer == 0) ? nullptr : &P.layers[st.layer - 1];
   if constexpr (KIND == ST_FRONTEND) {
     frontend_item(P.fe, item, ctx.image);
   } else if constexpr (KIND == ST_CONV_FWD) {
@@ -1265,9 +1268,9 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
   } else if constexpr (KIND == ST_FC_FWD) {
     fc_fwd_item(L, st, item, in, lds);
   } else if constexpr (KIND == ST_HEAD) {
-    head_item(L, L.in_is_image ? nullptr : &P.layers[st.layer - 1], in, ctx, status, lds);
+    head_item(L, below, in, ctx, status, lds);
   } else if constexpr (KIND == ST_FC_BWD) {
-    fc_bwd_item(L, L.in_is_image ? nullptr : &P.layers[st.layer - 1], st, item, in, ctx, lds);
+    fc_bwd_item(L, below, st, item, in, ctx, lds);
   } else if constexpr (KIND == ST_CONV_BWD) {
     conv_bwd_item(L, P.layers[st.layer - 1], st, item, lds);
   } else if constexpr (KIND == ST_CONV_WGRAD) {

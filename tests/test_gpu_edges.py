@@ -23,6 +23,8 @@ SHAPES = [
     ("1x6x6-2C3-3N", {}, 0, 1),                              # no pooling at all
     ("1x5x5-4N", {}, 0, 1),                                  # no convolution at all: the output layer reads the image
     ("1x5x5-7N-4N", {}, 0, 1),
+    ("1x22x6-2N-19N-6N", {}, 2, 1),                          # fully connected layers straight behind a fixed front-end
+    ("3x6x6-4N", {}, 3, 2),                                  # ... and the output layer alone behind one
     ("2x10x10-5C1-MP2-3C1S1-6N-2N", {}, 0, 2),               # 1x1 kernels
     ("1x20x20-6C6-MP3-5C3S2-4N", {}, 0, 1),                  # kernel sizes without a compiled specialisation; skip 2
     ("2x23x23-5C7S1-4C2-MP2-3N", {1: 3}, 0, 2),
