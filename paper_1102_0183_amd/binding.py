@@ -375,6 +375,13 @@ class Cnn:
         f.argtypes = [C.c_void_p]
         return int(f(self._h))
 
+    def resident_pull_shares(self, conv_index):
+        """Development aid: ranks that share the delta pull into one input map of a conv layer of the resident plan."""
+        f = lib().cnn355_resident_pull_shares
+        f.restype = C.c_int
+        f.argtypes = [C.c_void_p, C.c_int]
+        return int(f(self._h, conv_index))
+
     def raw_stamps(self, n=128):
         """Development aid: device timestamps (100 MHz ticks) left by the last call."""
         buf = np.zeros(n, dtype=np.uint64)

@@ -313,6 +313,7 @@ size_t carve(cnn* net, void* base) {
         const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
         const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : (size_t)A[l].maps * A[l].h * A[l].w;
         words += 3 * 2 * small;  // pooled outputs, deltas, winner coordinates; two images in flight
+        words += 2 * 256 * (small / A[l].maps);  // pulled sums of the shares of a map's pull (fewer than 256 of them)
         last_maps = A[l].maps;
       } else if (A[l].kind == CNN_LAYER_FC && !first_fc) {
         first_fc = A[l].maps;
@@ -804,6 +805,8 @@ void plan_flow(cnn* net) {
     C.x_out = (l + 1 < n_conv) ? xtake(2 * small) : nullptr;
     C.x_delta = (l >= 1) ? xtake(2 * small) : nullptr;
     C.x_yx = (l >= 1) ? xtake(2 * small) : nullptr;
+    C.x_part = (l >= 1 && Z.conv[l].pull_shares > 1)
+                   ? xtake((size_t)2 * L.Mi * (Z.conv[l].pull_shares - 1) * L.Hi * L.Wi) : nullptr;
   }
   for (int f = 0; f < n_fc; ++f) {
     const LayerDev& L = P.layers[n_conv + f];
@@ -1336,6 +1339,11 @@ int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
 
 // development aid, not part of the public header: which compiled-in network the resident plan equals (0: none)
 int cnn355_resident_static_id(const cnn_t* net) { return net ? net->flow_static_id : -1; }
+// development aid: how many ranks share the delta pull into one input map of the resident plan's conv layer l
+int cnn355_resident_pull_shares(const cnn_t* net, int l) {
+  if (!net || !net->flow_ok || l < 0 || l >= net->flow.n_conv) return -1;
+  return net->flow.conv[l].pull_shares;
+}
 
 int cnn_set_team(cnn_t* net, int n_ranks, int xcd_stride) {
   if (!net || n_ranks < 0 || (xcd_stride != 0 && xcd_stride != 1 && xcd_stride != 8)) return CNN_E_ARG;

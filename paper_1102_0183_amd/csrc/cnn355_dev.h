@@ -165,6 +165,7 @@ constexpr int FLOW_MAX_FC = 4;
 // the arena a rank carves up, in floats (154 KB of the 160 KB of a gfx950 CU; the rest holds a copy
 // of the descriptors)
 constexpr int FLOW_LDS_FLOATS_MAX = 39424;
+constexpr long long FLOW_SHARE_MIN_MACS = 1ll << 18;  // multiply-adds of one map's delta pull from which ranks share it
 constexpr int FLOW_STRIP_MAX = 7;  // output pixels one lane accumulates in registers
 
 // What the resident kernel needs besides the plan (cnn355_flowspec.h): where things lie in global memory.
@@ -184,6 +185,7 @@ struct FlowConvPtrs {
   CNN_GLOBAL tagged_t* x_out;    // [2][Mo*Hp*Wp] pooled outputs, when a convolutional layer follows
   CNN_GLOBAL tagged_t* x_delta;  // [2][Mo*Hp*Wp] deltas at the winners (layers above the first)
   CNN_GLOBAL tagged_t* x_yx;     // [2][Mo*Hp*Wp] their coordinates
+  CNN_GLOBAL tagged_t* x_part;   // [2][Mi][shares - 1][Hi*Wi] pulled sums of the shares beyond the first, for the map's owner
   long long w_canon, b_canon;    // offsets in the canonical weight vector (gradient tap)
 };
 struct FlowFcPtrs {

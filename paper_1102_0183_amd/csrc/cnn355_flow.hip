@@ -136,6 +136,11 @@ __device__ __forceinline__ void reduce_partials(const float* part, int n, int to
 }
 
 __device__ __forceinline__ int n_mine(int M, int rank, int G) { return rank < M ? (M - rank + G - 1) / G : 0; }
+// Input maps of a layer with Mi of them whose delta pull a rank works on: its own maps i = rank, rank + G, ...
+// (all entries of each), or, when the pull is shared (H > 1 shares per map), the one map rank % Mi, share rank / Mi.
+__device__ __forceinline__ int n_pull_maps(int Mi, int rank, int G, int H) {
+  return H > 1 ? (rank < H * Mi ? 1 : 0) : n_mine(Mi, rank, G);
+}
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // x / d for 0 <= x < 2^20 and 1 <= d < 2^20 by a float multiplication with the hardware
@@ -357,25 +362,33 @@ __device__ __forceinline__ void flow_load(const Rt& rt) {
     if (l >= 1) {
       // pull copy: the filters that read the own maps of the layer below, each rotated by 180
       // degrees (tap t stored at K*K-1-t), entries in ascending order of the output map
-      const int nb = n_mine(C.Mi, rank, G);
+      const int H = C.pull_shares, BP = C.back_pitch;
+      const int nb = n_pull_maps(C.Mi, rank, G, H);
       float* wb = lds + C.o_wb;
       int* bj = (int*)(lds + C.o_bj);
       int* ncb = (int*)(lds + C.o_ncb);
       for (int a = 0; a < nb; ++a) {
-        const int i = rank + a * G;
+        const int i = H > 1 ? rank % C.Mi : rank + a * G;
         int eb = 0, ne = C.Mo;
         if (!C.full_table) { eb = P.csc_ptr[i]; ne = P.csc_ptr[i + 1] - eb; }
-        for (int x = tid; x < C.max_back * KK; x += WG) {
+        if (H > 1) {  // this rank's share of the map's entries
+          const int h = rank / C.Mi;
+          const int lo = (int)((long long)ne * h / H), hi = (int)((long long)ne * (h + 1) / H);
+          eb += lo;
+          ne = hi - lo;
+        }
+        const int e0 = C.full_table ? eb : 0;  // (full table: entry e is output map e, eb counts from 0)
+        for (int x = tid; x < BP * KK; x += WG) {
           const int e = x / KK, t = x - e * KK;
           float v = 0.f;
           if (e < ne) {
-            const int slot = C.full_table ? (e * C.Mi + i) : P.csc_slot[eb + e];
+            const int slot = C.full_table ? ((e0 + e) * C.Mi + i) : P.csc_slot[eb + e];
             v = P.w[(size_t)slot * KK + (KK - 1 - t)];
           }
-          wb[a * C.max_back * KK + x] = v;
+          wb[a * BP * KK + x] = v;
         }
-        for (int e = tid; e < C.max_back; e += WG)
-          bj[a * C.max_back + e] = (e < ne) ? (C.full_table ? e : P.csc_j[eb + e]) : 0;
+        for (int e = tid; e < BP; e += WG)
+          bj[a * BP + e] = (e < ne) ? (C.full_table ? e0 + e : P.csc_j[eb + e]) : 0;
         if (tid == 0) ncb[a] = ne;
       }
     }
@@ -554,10 +567,10 @@ __device__ __forceinline__ JobStat pull_job(const FlowSpec& Z, int l) {
   const ConvSpec& C = Z.conv[l];
   JobStat S;
   S.in = Z.o_scratch; S.w = C.o_wb; S.idx = C.o_bj; S.cnt = C.o_ncb;
-  S.w_pitch = C.max_back; S.Ho = C.Hi; S.Wo = C.Wi; S.K = C.K; S.stride = 1;
+  S.w_pitch = C.back_pitch; S.Ho = C.Hi; S.Wo = C.Wi; S.K = C.K; S.stride = 1;
   S.Wi = C.Wi + C.K - 1; S.map_sz = (int)flow_border_map(C.Hi, C.Wi, C.K);
-  S.max_cnt = min(C.max_back, C.pull_chunk);
-  S.plan_cnt = min(C.max_back, C.Mo);
+  S.max_cnt = min(C.back_pitch, C.pull_chunk);
+  S.plan_cnt = min(C.back_pitch, C.Mo);
   S.variant = C.pull_strip ? (C.pull_rows - 1) * 64 + C.pull_strip * 8 + C.K : 0;
   S.table = C.o_tab_pull;
   S.band_lo = C.K - 1; S.band_hi = C.K - 1 + (C.Ho - 1) * (C.S + 1) + 1; S.ways_side_by_side = C.K & 1;
@@ -849,7 +862,7 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
 // are kept zero between uses: after a chunk the winners' places are cleared again.
 // delta_below[p] = pulled sum * f'(y_below[p]).
 template <int ID>
-__device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall, const int* yxall) {
+__device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall, const int* yxall, unsigned int tag) {
   DECL_SPEC(Z, rt);
   const ConvSpec& C = Z.conv[l];
   const ConvSpec& Cb = Z.conv[l - 1];
@@ -863,8 +876,17 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
   const int Mo = C.Mo, HW = C.Hp * C.Wp, stride = C.S + 1, Km1 = C.K - 1;
   const int Wd = S.Wi, HWd = S.map_sz;
   const int chunk = C.pull_chunk;
-  const bool full = C.full_table != 0;
+  const int H = C.pull_shares;
+  const bool full = C.full_table != 0 && H == 1;  // (a share's entries are found through its list)
   const int* cnt = (const int*)(lds + S.cnt);
+  // output maps this rank's entries lie among: all of them, or, for a share, from its first entry to its last
+  int j_lo = 0, j_hi = Mo;
+  if (H > 1) {
+    const int* bj0 = (const int*)(lds + S.idx);
+    const int ne = cnt[0];
+    j_lo = ne > 0 ? bj0[0] : 0;
+    j_hi = ne > 0 ? bj0[ne - 1] + 1 : 0;
+  }
   const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
   DSTAMP(120);
@@ -876,15 +898,15 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
 #pragma unroll
       for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
       int e_next = 0;
-      for (int j0 = 0; j0 < Mo; j0 += chunk) {
-        const int n = min(chunk, Mo - j0);
+      for (int j0 = j_lo; j0 < j_hi; j0 += chunk) {
+        const int n = min(chunk, j_hi - j0);
         for (int x = tid; x < n * HW; x += WG) {
           const int c = dHW.div(x), q = x - c * HW;
           const int yx = yxall[(j0 + c) * HW + q];
           dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = dall[(j0 + c) * HW + q];
         }
         __syncthreads();
-        if (j0 == 0) DSTAMP(121);
+        if (j0 == j_lo) DSTAMP(121);
         if (ln.on) {
           // entries of the lane's input map whose output map lies in [j0, j0 + n): the list is
           // sorted, this chunk's start is the last chunk's end, its end is found by bisection
@@ -900,17 +922,17 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
             e_hi = lo;
             e_next = e_hi;
           }
-          if (j0 == 0) DSTAMP(122);
+          if (j0 == j_lo) DSTAMP(122);
           job_mac<K, SW, TH, true, 1>(S, D.R, lds, ln, e_lo, e_hi, j0, acc);
         }
         __syncthreads();
-        if (j0 == 0) DSTAMP(123);
+        if (j0 == j_lo) DSTAMP(123);
         for (int x = tid; x < n * HW; x += WG) {
           const int c = dHW.div(x), q = x - c * HW;
           const int yx = yxall[(j0 + c) * HW + q];
           dd[c * HWd + ((yx >> 16) * stride + Km1) * Wd + (yx & 0xffff) * stride + Km1] = 0.f;
         }
-        if (j0 + chunk < Mo) __syncthreads();
+        if (j0 + chunk < j_hi) __syncthreads();
       }
       if (ln.on) {
         float* dst = part + (ln.r * nb + ln.am) * (S.Ho * S.Wo) + ln.pix;
@@ -926,8 +948,36 @@ __device__ __forceinline__ void flow_pull(const Rt& rt, int l, const float* dall
   DSTAMP(124);
   const float* ybelow = lds + Cb.o_pool;
   float* dbelow = lds + Cb.o_delta;
-  reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s * f_dact(ybelow[p]); });
+  if (H == 1) {
+    reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s * f_dact(ybelow[p]); });
+    __syncthreads();
+    return true;
+  }
+  // A shared pull (one map, tot = Hi * Wi sums): the shares beyond the first send their sums to the map's owner,
+  // who adds them to its own in the order of the shares and multiplies by the activation derivative.
+  const int i = rt.rank % C.Mi, h = rt.rank / C.Mi;
+  const FlowConvPtrs& P = rt.sh->ptrs.conv[l];
+  gtagged* xp = P.x_part + ((size_t)(tag & 1u) * C.Mi + i) * (H - 1) * tot;
+  if (h > 0) {
+    reduce_partials(part, D.R, tot, [&](int p, float s) { put_f(xp + (size_t)(h - 1) * tot + p, s, tag); });
+    __syncthreads();
+    return true;
+  }
+  reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s; });
   __syncthreads();
+  bool ok = true;  // (a lane whose wait gave up goes on to the barrier like the others; the flag tells)
+  for (int p0 = 0; p0 < tot; p0 += WG) {
+    const int p = p0 + tid;
+    float s = p < tot ? dbelow[p] : 0.f;
+    for (int hh = 1; hh < H && ok; ++hh) {
+      tagged_t w[1];
+      ok = fetch_tagged<1>(rt, w, tag, [&](int) { return xp + (size_t)(hh - 1) * tot + min(p, tot - 1); });
+      s += __uint_as_float((unsigned int)w[0]);
+    }
+    if (ok && p < tot) dbelow[p] = s * f_dact(ybelow[p]);
+  }
+  __syncthreads();
+  return rt.sh->fail == 0;
 }
 
 // y[k] = b[k] + sum_m W[k][m] v[m], all in LDS; lane groups of a power of two per row.
@@ -996,7 +1046,7 @@ __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
     for_up<ID, 0, FLOW_MAX_CONV>(Z.n_conv, [&](auto lc) {
       const int l = lv(lc);
       sh.fwd[l] = job_dyn(fwd_job(Z, l), n_mine(Z.conv[l].Mo, rank, G));
-      if (l >= 1) sh.pull[l] = job_dyn(pull_job(Z, l), n_mine(Z.conv[l].Mi, rank, G));
+      if (l >= 1) sh.pull[l] = job_dyn(pull_job(Z, l), n_pull_maps(Z.conv[l].Mi, rank, G, Z.conv[l].pull_shares));
       return true;
     });
   __syncthreads();
@@ -1170,7 +1220,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       const int* yxall = (const int*)(lds + Z.o_yxall);
       const int* bj = (const int*)(lds + C.o_bj);
       const int* ncb = (const int*)(lds + C.o_ncb);
-      const int pitch = uni_of<ID>(C.max_back);
+      const int pitch = uni_of<ID>(C.back_pitch);
       const int per_map = pitch * KK;
       const FDiv dPM(per_map), dKK(KK), dK(K);
       flow_wgrad(lds + C.o_wb, nb * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, (gfloat*)nullptr,
@@ -1478,16 +1528,20 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
                        P.x_yx + (size_t)par * Mo * HW, Mo * HW, tag))
             return false;
           STAMP(42 + 4 * l);
-          flow_pull<ID>(rt, l, dall, yxall);
+          if (!flow_pull<ID>(rt, l, dall, yxall, tag)) return false;
           STAMP(43 + 4 * l);
+          // the pooled maps of the layer below that the pull copy's adjustment needs: the own ones, or, for a
+          // share of another rank's map, that map among this layer's inputs
+          const int Hs = uni_of<ID>(C.pull_shares), Mi = uni_of<ID>(C.Mi);
+          const float* own = (Hs > 1 && rank >= Mi) ? lds + C.o_in + (rank % Mi) * HiWi
+                                                    : lds + Z.conv[l >= 1 ? l - 1 : 0].o_pool;
           if (defer && l == 1) {
             // the pull copy is adjusted during the next image's wait; the next FP overwrites the
-            // own pooled maps it needs, so they are set aside
-            const float* own = lds + Z.conv[0].o_pool;
+            // pooled maps it needs, so they are set aside
             float* prev = lds + Z.o_prev;
             for (int x = tid; x < nb * HiWi; x += WG) prev[x] = own[x];
           } else if (!g_out) {
-            wgrad_pull(lc, lds + Z.conv[l >= 1 ? l - 1 : 0].o_pool);
+            wgrad_pull(lc, own);
           }
         }
       }

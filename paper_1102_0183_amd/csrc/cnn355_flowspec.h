@@ -15,6 +15,12 @@ struct ConvSpec {
   int full_table;
   int n_own;        // most output maps a rank owns: ceil(Mo / G)
   int n_own_below;  // most input maps a rank owns (maps of the layer below): ceil(Mi / G); 0 for the first layer
+  int pull_shares;  // > 1 (when the layer below has at most half as many maps as there are ranks and a map's pull
+                    //   is long enough, FLOW_SHARE_MIN_MACS): the delta pull
+                    //   into input map i is shared by the ranks i, i + Mi, ...: share h takes the entries
+                    //   [ne h / H, ne (h + 1) / H) of the map's list, holds and adjusts their filters, and hands
+                    //   its sums to rank i, the map's owner.  Then n_own_below = 1
+  int back_pitch;   // entries per own input map (or share of one) the pull copy has room for
   int wgrad_R_log2; // pooled positions are split 2^this ways when summing a weight gradient
   int pull_chunk;   // output maps rebuilt at full resolution per pass of the delta pull
   int fwd_strip;    // FP: a lane computes a tile of fwd_rows x fwd_strip output pixels (strip 0: one pixel per
@@ -28,8 +34,8 @@ struct ConvSpec {
   int o_bf;     // [n_own] biases
   int o_cidx;   // [n_own][max_conn] input map of every connection (int)
   int o_ncf;    // [n_own] connections of every own map (int)
-  int o_wb;     // [n_own_below][max_back][K*K] pull copy of the filters, rotated (layers above the first)
-  int o_bj;     // [n_own_below][max_back] output map of every entry (int)
+  int o_wb;     // [n_own_below][back_pitch][K*K] pull copy of the filters, rotated (layers above the first)
+  int o_bj;     // [n_own_below][back_pitch] output map of every entry (int)
   int o_ncb;    // [n_own_below] entries of every own input map (int)
   int o_pool;   // [n_own][Hp*Wp] pooled outputs of the own maps
   int o_yx;     // [n_own][Hp*Wp] winner coordinates (y << 16 | x) (int)
@@ -168,6 +174,12 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     C.n_own = (C.Mo + G - 1) / G;
     C.n_own_below = l >= 1 ? (C.Mi + G - 1) / G : 0;
     C.max_back = flow_max(1, C.max_back);
+    // (handing the sums over costs the owner a round trip through the L2, about what 2^17 multiply-adds of a
+    // map's pull take, so two shares pay from twice that: measured, sharing gains 1.5 us on 80 entries of 5x5
+    // into 13x13 maps and loses 0.8 us on 40 of them)
+    C.pull_shares = (l >= 1 && 2 * C.Mi <= G && (long long)C.max_back * KK * C.Hi * C.Wi >= FLOW_SHARE_MIN_MACS)
+                        ? G / C.Mi : 1;
+    C.back_pitch = (C.max_back + C.pull_shares - 1) / C.pull_shares;
     C.has_x_out = (l + 1 < n_conv) ? 1 : 0;
     C.o_in = take((long long)C.Mi * C.Hi * C.Wi);
     C.o_wf = take((long long)C.n_own * C.max_conn * KK);
@@ -180,17 +192,17 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     }
     C.o_wb = 0; C.o_bj = 0; C.o_ncb = 0; C.pull_strip = 0; C.pull_rows = 1; C.pull_chunk = 1;
     if (l >= 1) {
-      C.o_wb = take((long long)C.n_own_below * C.max_back * KK);
-      C.o_bj = take((long long)C.n_own_below * C.max_back);
+      C.o_wb = take((long long)C.n_own_below * C.back_pitch * KK);
+      C.o_bj = take((long long)C.n_own_below * C.back_pitch);
       C.o_ncb = take(C.n_own_below);
       {
-        const int tile = flow_tile_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.max_back);
+        const int tile = flow_tile_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.back_pitch);
         C.pull_strip = tile & 15; C.pull_rows = tile ? tile >> 4 : 1;
       }
       max_dall = flow_maxl(max_dall, (long long)C.Mo * HW);
       max_hwd = flow_maxl(max_hwd, flow_border_map(C.Hi, C.Wi, C.K));
       max_part = flow_maxl(max_part, flow_part_need(C.pull_strip, C.pull_rows, C.n_own_below, C.Hi, C.Wi,
-                                                    flow_min(C.max_back, C.Mo)));
+                                                    flow_min(C.back_pitch, C.Mo)));
     }
     C.o_pool = take((long long)C.n_own * HW);
     C.o_yx = take((long long)C.n_own * HW);
@@ -199,7 +211,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     max_part = flow_maxl(max_part, flow_part_need(C.fwd_strip, C.fwd_rows, C.n_own, C.Ho, C.Wo, C.max_conn));
     // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
     long long n_w = (long long)C.n_own * C.max_conn * KK;
-    if (l >= 1) n_w = flow_minl(n_w, (long long)C.n_own_below * C.max_back * KK);
+    if (l >= 1) n_w = flow_minl(n_w, (long long)C.n_own_below * C.back_pitch * KK);
     int rl2 = 0;
     while (rl2 < 6 && (n_w << (rl2 + 1)) <= WG && (2 << rl2) <= HW) ++rl2;
     C.wgrad_R_log2 = rl2;

@@ -38,7 +38,15 @@ SHAPES = [
     ("1x9x9-2C2S0x1-MP2x1-3C2x1S1x0-3N", {}, 0, 1),
     ("3x40x33-9C5x3S1x2-MP2x1-8C2x4-MP1x2-7C3x1S0x1-12N-5N", {1: 4, 2: 3}, 0, 3),   # three such layers, sparse tables
     ("1x30x70-6C7x2-MP8x3-5N", {}, 0, 1),                    # a kernel size without a compiled loop, a tall pooling rectangle
+    # few maps below many above: in resident mode several ranks share the delta pull into one map
+    ("1x28x28-6C5-MP2-100C5-MP2-8N", {}, 0, 1),              # 16 shares a map, full table
+    ("1x28x28-6C5-MP2-100C5-MP2-8N", {1: 5}, 0, 1),          # ... sparse table
+    ("1x28x28-40C5-MP2-80C5-MP2-8N", {1: 38}, 0, 1),         # 2 shares a map, sparse table
 ]
+SHARES = {"1x28x28-6C5-MP2-100C5-MP2-8N": 16, "1x28x28-40C5-MP2-80C5-MP2-8N": 2}
+# initial weight range where the default would saturate the units (950 inputs each): the derivative taken from
+# a saturated output loses the digits the comparison needs, in any fp32 summation order
+WSCALE = {"1x28x28-40C5-MP2-80C5-MP2-8N": 0.05}
 
 
 def _pair(arch, fan, fe_k, n_src, seed):
@@ -54,7 +62,7 @@ def _pair(arch, fan, fe_k, n_src, seed):
         filt = (rng.standard_normal((c, fe_k, fe_k)) * 0.2).astype(np.float32)
         src = rng.integers(0, n_src, size=c).astype(np.int32)
         frontend = (filt, src, n_src)
-    return build_pair(arch=arch, tables=tables, frontend=frontend, seed=seed, wscale=0.3)
+    return build_pair(arch=arch, tables=tables, frontend=frontend, seed=seed, wscale=WSCALE.get(arch, 0.3))
 
 
 @pytest.mark.parametrize("mode", MODES)
@@ -66,6 +74,8 @@ def test_shapes_one_step_and_ten_steps(arch, fan, fe_k, n_src, mode):
         g.close()
         pytest.skip("mode %d cannot run this network" % mode)
     g.set_mode(mode)
+    if mode == binding.MODE_RESIDENT and arch in SHARES:
+        assert g.resident_pull_shares(1) == SHARES[arch]
     rng = np.random.default_rng(17)
     n_cls = g.num_classes
     imgs = rng.uniform(-1, 1, (10, g.image_size)).astype(np.float32)
