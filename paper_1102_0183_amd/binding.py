@@ -164,6 +164,31 @@ def plan_text(arch):
     return buf.value.decode()
 
 
+def resident_plan(arch, fan_in=0, n_ranks=0, xcd_stride=0):
+    """Development aid, host-only: the resident-mode plan of an architecture, parsed: {"numbers": {name: value},
+    "conv": [{field: value}], "fc": [...], "regions": [(name, first_float, floats)]}, or {"unsupported": reason}.
+    fan_in > 0: output map j of every conv layer above the first reads input maps j .. j + fan_in - 1 (mod M_i)."""
+    f = lib().cnn355_resident_plan_text
+    f.restype = C.c_int
+    f.argtypes = [C.c_char_p, C.c_int, C.c_int, C.c_int, C.c_char_p, C.c_size_t]
+    buf = C.create_string_buffer(1 << 16)
+    rc = f(arch.encode(), fan_in, n_ranks, xcd_stride, buf, len(buf))
+    if rc:
+        raise CnnError(rc, "cnn355_resident_plan_text(%r)" % arch, _err())
+    plan = {"numbers": {}, "conv": [], "fc": [], "regions": []}
+    for line in buf.value.decode().splitlines():
+        w = line.split()
+        if w[0] == "unsupported":
+            return {"unsupported": " ".join(w[1:])}
+        if w[0] in ("conv", "fc"):
+            plan[w[0]].append({w[k]: int(w[k + 1]) for k in range(2, len(w), 2)})
+        elif w[0] == "region":
+            plan["regions"].append((w[1], int(w[2]), int(w[3])))
+        else:
+            plan["numbers"][w[0]] = int(w[1])
+    return plan
+
+
 class Cnn:
     """One network on the current HIP device.  The workspace is a torch uint8 tensor owned here."""
 

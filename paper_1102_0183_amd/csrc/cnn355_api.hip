@@ -1339,6 +1339,101 @@ int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
 
 // development aid, not part of the public header: which compiled-in network the resident plan equals (0: none)
 int cnn355_resident_static_id(const cnn_t* net) { return net ? net->flow_static_id : -1; }
+// development aid, host only (no device is touched): the resident plan of an architecture as text.  fan_in > 0
+// gives every convolutional layer above the first a table in which output map j reads the input maps
+// j, j + 1, ..., j + fan_in - 1 (mod M_i).  One line per number ("name value"), per layer ("conv l name value ...")
+// and per LDS region of a rank ("region name first_float floats"); a region's size is restated here from its
+// documented shape, not taken from the planner.
+int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd_stride, char* buf, size_t n) {
+  if (!buf || n == 0) return fail(nullptr, CNN_E_ARG, "buf is NULL");
+  cnn tmp;
+  int rc = parse_arch(arch, tmp.arch, nullptr);
+  if (rc) return rc;
+  carve(&tmp, nullptr);
+  for (size_t l = 1; l < tmp.arch.size(); ++l)
+    if (tmp.arch[l].kind == CNN_LAYER_CONV) {
+      const int Mo = tmp.arch[l].maps, Mi = tmp.arch[l - 1].maps;
+      const bool sparse = fan_in > 0 && fan_in < Mi && !tmp.tables.empty();
+      tmp.tables.emplace_back((size_t)Mo * Mi, (uint8_t)(sparse ? 0 : 1));
+      if (sparse)
+        for (int j = 0; j < Mo; ++j)
+          for (int k = 0; k < fan_in; ++k) tmp.tables.back()[(size_t)j * Mi + (j + k) % Mi] = 1;
+    }
+  tmp.team_ranks = n_ranks;
+  tmp.team_stride = xcd_stride;
+  rc = plan(&tmp);
+  if (rc) { g_err = tmp.err; return rc; }
+  std::string t;
+  auto num = [&](const char* name, long long v) { t += std::string(name) + " " + std::to_string(v) + "\n"; };
+  if (!tmp.flow_ok) {
+    t = "unsupported " + tmp.flow_why + "\n";
+  } else {
+    const FlowSpec& Z = tmp.flow;
+    num("G", Z.G); num("stride", Z.stride); num("n_conv", Z.n_conv); num("n_fc", Z.n_fc);
+    num("n_col_ranks", Z.n_col_ranks); num("lds_floats", Z.lds_floats); num("lds_floats_max", FLOW_LDS_FLOATS_MAX);
+    num("scratch_floats", Z.scratch_floats); num("defer", Z.defer); num("static_id", tmp.flow_static_id);
+    num("workgroup", WG); num("share_min_macs", FLOW_SHARE_MIN_MACS);
+    auto region = [&](const std::string& name, long long off, long long floats) {
+      t += "region " + name + " " + std::to_string(off) + " " + std::to_string(floats) + "\n";
+    };
+    long long act = 1, dall = 1;
+    for (int l = 0; l < Z.n_conv; ++l) {
+      const ConvSpec& C = Z.conv[l];
+      const long long KK = C.K * C.K, HW = C.Hp * C.Wp;
+      const std::string c = "conv" + std::to_string(l) + ".";
+      t += "conv " + std::to_string(l);
+      const std::pair<const char*, int> f[] = {
+          {"Mi", C.Mi}, {"Hi", C.Hi}, {"Wi", C.Wi}, {"Mo", C.Mo}, {"Ho", C.Ho}, {"Wo", C.Wo}, {"K", C.K}, {"S", C.S},
+          {"Kp", C.Kp}, {"Hp", C.Hp}, {"Wp", C.Wp}, {"max_conn", C.max_conn}, {"max_back", C.max_back},
+          {"full_table", C.full_table}, {"n_own", C.n_own}, {"n_own_below", C.n_own_below},
+          {"pull_shares", C.pull_shares}, {"back_pitch", C.back_pitch}, {"wgrad_R_log2", C.wgrad_R_log2},
+          {"pull_chunk", C.pull_chunk}, {"fwd_strip", C.fwd_strip}, {"fwd_rows", C.fwd_rows},
+          {"pull_strip", C.pull_strip}, {"pull_rows", C.pull_rows}};
+      for (const auto& kv : f) t += std::string(" ") + kv.first + " " + std::to_string(kv.second);
+      t += "\n";
+      region(c + "in", C.o_in, (long long)C.Mi * C.Hi * C.Wi);
+      region(c + "wf", C.o_wf, (long long)C.n_own * C.max_conn * KK);
+      region(c + "bf", C.o_bf, C.n_own);
+      region(c + "cidx", C.o_cidx, (long long)C.n_own * C.max_conn);
+      region(c + "ncf", C.o_ncf, C.n_own);
+      if (l >= 1) {
+        region(c + "wb", C.o_wb, (long long)C.n_own_below * C.back_pitch * KK);
+        region(c + "bj", C.o_bj, (long long)C.n_own_below * C.back_pitch);
+        region(c + "ncb", C.o_ncb, C.n_own_below);
+        dall = std::max(dall, (long long)C.Mo * HW);
+      }
+      region(c + "pool", C.o_pool, C.n_own * HW);
+      region(c + "yx", C.o_yx, C.n_own * HW);
+      region(c + "delta", C.o_delta, C.n_own * HW);
+      if (C.o_tab_fwd >= 0) region(c + "tab_fwd", C.o_tab_fwd, 3 * WG);
+      if (C.o_tab_pull >= 0) region(c + "tab_pull", C.o_tab_pull, 3 * WG);
+      act = std::max(act, (long long)C.n_own * C.Ho * C.Wo);
+    }
+    const ConvSpec& Cl = Z.conv[Z.n_conv - 1];
+    for (int f = 0; f < Z.n_fc; ++f) {
+      const FcSpec& Q = Z.fc[f];
+      const std::string c = "fc" + std::to_string(f) + ".";
+      t += "fc " + std::to_string(f) + " n_in " + std::to_string(Q.n_in) + " n_out " + std::to_string(Q.n_out) + "\n";
+      region(c + "w", Q.o_w, f == 0 ? (long long)Cl.n_own * Cl.Hp * Cl.Wp * Q.n_out : (long long)Q.n_out * Q.n_in);
+      region(c + "b", Q.o_b, Q.n_out);
+      region(c + "act", Q.o_act, Q.n_out);
+      region(c + "delta", Q.o_delta, Q.n_out);
+    }
+    region("act", Z.o_act, act);
+    // (the partial sums reach up to the next region: what they need is for the reader to work out)
+    region("part", Z.o_part, Z.o_dall - Z.o_part);
+    if (Z.n_conv > 1) {
+      region("dall", Z.o_dall, dall);
+      region("yxall", Z.o_yxall, dall);
+    }
+    if (Z.defer && Z.n_conv > 1) region("prev", Z.o_prev, (long long)Z.conv[1].n_own_below * Z.conv[1].Hi * Z.conv[1].Wi);
+    region("scratch", Z.o_scratch, Z.scratch_floats);
+  }
+  if (t.size() + 1 > n) return fail(nullptr, CNN_E_ARG, "buffer too small for the plan text");
+  std::memcpy(buf, t.c_str(), t.size() + 1);
+  return CNN_OK;
+}
+
 // development aid: how many ranks share the delta pull into one input map of the resident plan's conv layer l
 int cnn355_resident_pull_shares(const cnn_t* net, int l) {
   if (!net || !net->flow_ok || l < 0 || l >= net->flow.n_conv) return -1;

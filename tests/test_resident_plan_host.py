@@ -1,0 +1,193 @@
+"""Host logic of the resident mode (no GPU): the plan the library derives for an architecture -- team, per-rank
+LDS layout, tiles, shared delta pulls -- is checked against rules restated here from what the kernels need:
+regions disjoint and inside the LDS, room for the partial sums of every job however its connections are split
+over the lanes, room for the zero-bordered delta maps of a pull chunk, shares of a pulled map's entries that tile
+the list and fit the pull copy.  Runs on the benchmark networks, on the edge-case shapes and on seeded random ones."""
+import numpy as np
+import pytest
+
+from paper_1102_0183_amd import binding, synth
+
+CU = 256  # compute units the planner assumes when no device is there
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+def split_ways(U, cnt, wg):
+    """Ways U units share their (at most cnt) connections over wg lanes: as many as fit, then the fewest that
+    need no more passes per lane."""
+    if U >= wg or U < 1:
+        return 1
+    r_max = max(1, min(wg // U, cnt))
+    iters = ceil_div(cnt, r_max)
+    return ceil_div(cnt, iters)
+
+
+def job_units(strip, rows, nm, H, W):
+    return nm * ceil_div(H, rows) * ceil_div(W, strip) if strip else nm * H * W
+
+
+def check_plan(p, arch, n_ranks=0, stride=0):
+    num, regions = p["numbers"], p["regions"]
+    wg, G = num["workgroup"], num["G"]
+    # the team
+    max_maps = max(c["Mo"] for c in p["conv"])
+    want_stride = stride or (8 if (n_ranks or max_maps) <= CU // 8 else 1)
+    assert num["stride"] == want_stride
+    assert G == max(1, min(n_ranks or max_maps, max_maps, CU // want_stride)), arch
+    assert num["n_col_ranks"] == min(G, p["conv"][-1]["Mo"])
+    # regions: disjoint, aligned, inside the LDS
+    assert num["lds_floats"] <= num["lds_floats_max"]
+    spans = sorted((off, off + n, name) for name, off, n in regions)
+    for (a0, a1, an), (b0, b1, bn) in zip(spans, spans[1:]):
+        assert a1 <= b0, (arch, an, bn)
+    for off, end, name in spans:
+        assert off % 4 == 0 and off >= 0 and end <= num["lds_floats"], (arch, name)
+    size = {name: n for name, _, n in regions}
+    # layers
+    for l, c in enumerate(p["conv"]):
+        KK = c["K"] * c["K"]
+        assert c["n_own"] == ceil_div(c["Mo"], G)
+        assert c["n_own_below"] == (ceil_div(c["Mi"], G) if l else 0)
+        # FP: partial sums of the job, for a rank with the most maps and one with a map fewer
+        for nm in {c["n_own"], max(1, c["n_own"] - 1)}:
+            U = job_units(c["fwd_strip"], c["fwd_rows"], nm, c["Ho"], c["Wo"])
+            assert split_ways(U, c["max_conn"], wg) * nm * c["Ho"] * c["Wo"] <= size["part"], (arch, l, "fwd")
+        assert c["n_own"] * c["Ho"] * c["Wo"] <= size["act"]
+        if c["fwd_strip"]:
+            assert c["fwd_strip"] in (4, 5, 7) and c["fwd_rows"] in (1, 2) and 2 <= c["K"] <= 5 and c["S"] <= 1
+        if l == 0:
+            assert c["pull_shares"] == 1
+            continue
+        # shared pulls
+        macs = c["max_back"] * KK * c["Hi"] * c["Wi"]
+        shared = 2 * c["Mi"] <= G and macs >= num["share_min_macs"]
+        H = G // c["Mi"] if shared else 1
+        assert c["pull_shares"] == H, (arch, l)
+        assert c["back_pitch"] == ceil_div(c["max_back"], H)
+        if H > 1:
+            assert c["n_own_below"] == 1 and H * c["Mi"] <= G
+            for ne in range(c["max_back"] + 1):  # every list length: the shares tile it and fit the pull copy
+                cuts = [ne * h // H for h in range(H + 1)]
+                assert cuts[0] == 0 and cuts[-1] == ne
+                assert all(0 <= b - a <= c["back_pitch"] for a, b in zip(cuts, cuts[1:]))
+        # the pull: a chunk of zero-bordered delta maps in the scratch area, partial sums of the job
+        border = ((c["Hi"] + c["K"] - 1) * (c["Wi"] + c["K"] - 1)) | 1
+        pad = 16 + c["Wi"] + c["K"]
+        assert 1 <= c["pull_chunk"] <= c["Mo"]
+        assert c["pull_chunk"] * border + pad <= size["scratch"], (arch, l)
+        max_cnt, plan_cnt = min(c["back_pitch"], c["pull_chunk"]), min(c["back_pitch"], c["Mo"])
+        for nm in {c["n_own_below"], max(1, c["n_own_below"] - 1)}:
+            U = job_units(c["pull_strip"], c["pull_rows"], nm, c["Hi"], c["Wi"])
+            R = min(split_ways(U, max_cnt, wg), split_ways(U, plan_cnt, wg))
+            assert R * nm * c["Hi"] * c["Wi"] <= size["part"], (arch, l, "pull")
+        assert c["Mo"] * c["Hp"] * c["Wp"] <= size["dall"] == size["yxall"]
+        # sums over the pooled positions of a weight gradient: split 2^R ways while the weights of either copy fit
+        n_w = min(c["n_own"] * c["max_conn"] * KK, c["n_own_below"] * c["back_pitch"] * KK)
+        r = c["wgrad_R_log2"]
+        assert 0 <= r <= 6 and (r == 0 or ((n_w << r) <= wg and (1 << r) <= c["Hp"] * c["Wp"]))
+    # the first fully connected layer is held by columns: those of the own maps of the last conv layer
+    last = p["conv"][-1]
+    assert p["fc"][0]["n_in"] == last["Mo"] * last["Hp"] * last["Wp"]
+    assert size["fc0.w"] == last["n_own"] * last["Hp"] * last["Wp"] * p["fc"][0]["n_out"]
+    assert size["part"] >= wg
+
+
+@pytest.mark.parametrize("name,static_id", [("cfg1", 1), ("cfg2a", 1), ("cfg2b", 2)])
+def test_benchmark_networks_take_the_kernels_compiled_for_them(name, static_id):
+    arch = synth.WORKLOADS[name].arch
+    p = binding.resident_plan(arch)
+    check_plan(p, arch)
+    assert p["numbers"]["static_id"] == static_id
+    assert p["conv"][1]["pull_shares"] == (2 if name == "cfg2b" else 1)
+    for team in ((32, 1), (32, 8), (20, 8)):
+        q = binding.resident_plan(arch, 0, *team)
+        if "unsupported" in q:  # the large net on 20 ranks: four maps a rank, more weights than its LDS holds
+            assert name == "cfg2b" and team[0] == 20
+            continue
+        check_plan(q, arch, *team)
+        assert q["numbers"]["static_id"] == 0 and q["numbers"]["G"] == team[0]
+
+
+def test_cfg5_with_a_regular_half_table():
+    arch = synth.WORKLOADS["cfg5"].arch
+    p = binding.resident_plan(arch, fan_in=20)
+    check_plan(p, arch)
+    assert p["conv"][1]["full_table"] == 0 and p["conv"][1]["max_conn"] == 20 and p["conv"][1]["max_back"] == 40
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4a", "cfg4b"])
+def test_networks_whose_share_per_rank_exceeds_the_lds_are_refused(name):
+    p = binding.resident_plan(synth.WORKLOADS[name].arch)
+    assert "LDS" in p["unsupported"]
+
+
+def test_other_refusals():
+    assert "equal x and y" in binding.resident_plan("1x10x12-2C3x5-MP4x2-4N")["unsupported"]
+    assert "at least one convolutional" in binding.resident_plan("1x5x5-7N-4N")["unsupported"]
+    assert "at most" in binding.resident_plan("1x40x40-2C2-2C2-2C2-2C2-2C2-3N")["unsupported"]
+    with pytest.raises(binding.CnnError):
+        binding.resident_plan("1x5x5-3C9-2N")
+
+
+@pytest.mark.parametrize("arch,fan", [
+    ("1x9x9-3C4-MP2-4C2-5N-3N", 0), ("2x11x11-3C3S1-4C2-MP2-4N", 2), ("3x8x8-4C3-MP3-4C2-6N-5N-4N", 3),
+    ("1x6x6-2C3-3N", 0), ("2x10x10-5C1-MP2-3C1S1-6N-2N", 0), ("1x20x20-6C6-MP3-5C3S2-4N", 0),
+    ("1x8x600-3C3-MP2-4C2S1-5N", 0), ("1x70x70-4C3-MP4-3C4-MP2-6N", 0), ("3x34x47-7C4S1-8C3-MP2-9C2-MP3-20N-6N", 4),
+    ("1x40x40-70C5-MP4-300C3-MP1-10N", 0), ("1x28x28-6C5-MP2-100C5-MP2-8N", 0), ("1x28x28-6C5-MP2-100C5-MP2-8N", 5),
+    ("1x28x28-40C5-MP2-80C5-MP2-8N", 38), ("1x28x28-3C5-MP2-250C5-MP2-8N", 0),
+])
+def test_edge_shapes(arch, fan):
+    p = binding.resident_plan(arch, fan_in=fan)
+    if "unsupported" in p:
+        pytest.skip(p["unsupported"])
+    check_plan(p, arch)
+    for team in ((7, 1), (3, 8)):
+        q = binding.resident_plan(arch, fan, *team)
+        if "unsupported" not in q:
+            check_plan(q, arch, *team)
+
+
+def random_arch(rng):
+    """1 to 4 convolutional layers of up to 120 maps with square kernels, skips and pooling, then 1 to 3 FC layers."""
+    h = w = int(rng.integers(8, 49))
+    if rng.random() < 0.3:
+        w = int(rng.integers(8, 49))
+    s = "%dx%dx%d" % (int(rng.integers(1, 4)), h, w)
+    n_conv = 0
+    for _ in range(int(rng.integers(1, 5))):
+        k = int(rng.integers(1, min(7, h, w) + 1))
+        sk = int(rng.integers(0, 3)) if rng.random() < 0.3 else 0
+        ho, wo = (h - k) // (sk + 1) + 1, (w - k) // (sk + 1) + 1
+        m = int(rng.choice([2, 5, 12, 20, 40, 64, 100, 120]))
+        s += "-%dC%d%s" % (m, k, "S%d" % sk if sk else "")
+        n_conv += 1
+        h, w = ho, wo
+        both = [d for d in range(1, 5) if h % d == 0 and w % d == 0]
+        if rng.random() < 0.7:
+            d = int(rng.choice(both))
+            s += "-MP%d" % d
+            h, w = h // d, w // d
+        if min(h, w) < 2:
+            break
+    for _ in range(int(rng.integers(0, 3))):
+        s += "-%dN" % int(rng.integers(2, 200))
+    return s + "-%dN" % int(rng.integers(2, 12))
+
+
+def test_random_architectures():
+    rng = np.random.default_rng(5)
+    planned = shared = 0
+    for _ in range(400):
+        arch = random_arch(rng)
+        fan = int(rng.integers(1, 40)) if rng.random() < 0.4 else 0
+        team = (0, 0) if rng.random() < 0.6 else (int(rng.integers(1, 130)), int(rng.choice([0, 1, 8])))
+        p = binding.resident_plan(arch, fan, *team)
+        if "unsupported" in p:
+            continue
+        check_plan(p, arch, *team)
+        planned += 1
+        shared += any(c["pull_shares"] > 1 for c in p["conv"])
+    assert planned >= 100 and shared >= 10, (planned, shared)
