@@ -1,5 +1,5 @@
-"""The benchmark workload at its full size and in the launch configuration bench.py times: one
-on-line epoch over the whole 60000-image stream, resident mode, 1000 images per launch.  The
+"""The benchmark workload (both of its networks) at its full size and in the launch configuration bench.py
+times: one on-line epoch over the whole 60000-image stream, resident mode, 1000 images per launch.  The
 oracle cannot follow 60000 steps in lock-step within a test's time, so it checks sampled
 stretches (it continues from the GPU's weights at three points of the stream), and properties
 that hold at any size carry the rest.  Needs a GPU (marked gpu)."""
@@ -27,15 +27,17 @@ def _epoch(g, d_imgs, d_labs, lr, n, stops=()):
     return snap
 
 
-def test_one_epoch_in_the_benchmark_configuration():
-    wl = synth.WORKLOADS["cfg2a"]
+@pytest.mark.parametrize("name,static_id,shares", [("cfg2a", 1, 1), ("cfg2b", 2, 2)])
+def test_one_epoch_in_the_benchmark_configuration(name, static_id, shares):
+    wl = synth.WORKLOADS[name]
     n = wl.n_images
     assert n == 60000
     imgs, labs = synth.images(wl), synth.labels(wl)
     d_imgs, d_labs = to_dev(imgs), to_dev(labs)
     g, o = build_pair(wl)
     g.set_mode(binding.MODE_RESIDENT)
-    assert g.resident_static_id() == 1          # the kernel bench.py times
+    assert g.resident_static_id() == static_id  # the kernels bench.py times
+    assert g.resident_pull_shares(1) == shares  # (the larger net's delta pull is shared by two ranks a map)
     stops = (0, 19, 58)
     print("epoch of", n, "images,", LAUNCH, "per launch", flush=True)
     snap = _epoch(g, d_imgs, d_labs, wl.lr, n, stops)
