@@ -21,7 +21,7 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "cnn355_dev.h"),
+    deps = sources() + [os.path.join(CSRC, "cnn355_dev.h"), os.path.join(CSRC, "cnn355_flowspec.h"),
                         os.path.join(HERE, "..", "include", "cnn355.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
