@@ -18,6 +18,8 @@
 namespace cnn355 {
 hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const ProgramDev* d_prog, int s,
                         StatusDev* d_status, const RunArgs& a);
+hipError_t launch_stage_pair(int kind_a, int n_a, int kind_b, int n_b, hipStream_t stream, const ProgramDev* d_prog,
+                             int s, StatusDev* d_status, const RunArgs& a, bool* done);
 hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clear_label_flag);
 hipError_t launch_persistent(int grid, bool with_matrix_stages, hipStream_t stream, const ProgramDev* d_prog,
                              StatusDev* d_status, const RunArgs& a);
@@ -954,6 +956,14 @@ int run(cnn* net, const RunArgs& a0) {
     for (int s = 0; s < P.n_stages; ++s) {
       const Stage& st = P.stages[s];
       if (st.train_only && !a.train) continue;
+      if (!st.barrier_after && s + 1 < P.n_stages && P.stages[s + 1].train_only == st.train_only) {
+        // the next stage does not depend on this one: both in one launch, where a kernel for the pair exists
+        const Stage& nx = P.stages[s + 1];
+        bool done = false;
+        HIP_TRY(net, launch_stage_pair(st.kind, st.n_items, nx.kind, nx.n_items, net->stream, net->d_prog, s,
+                                       net->d_status, b, &done));
+        if (done) { ++s; continue; }
+      }
       HIP_TRY(net, launch_stage(st.kind, st.n_items, net->stream, net->d_prog, s, net->d_status, b));
     }
   }

@@ -1361,6 +1361,25 @@ STAGE_KERNEL(k_conv_bwd_mfma, ST_CONV_BWD_MFMA)
 STAGE_KERNEL(k_conv_bwd_epi, ST_CONV_BWD_EPI)
 STAGE_KERNEL(k_conv_wgrad_mfma, ST_CONV_WGRAD_MFMA)
 
+// Two consecutive stages that the plan declares independent (no barrier between them: a layer's weight
+// adjustment next to the stage that follows its pull) in one launch: the first stage's items, then the second's.
+// A launch costs some 4 us however little it does, so a step of 10 to 13 stages gains what a launch costs.
+template <int KA, int KB>
+__global__ void __launch_bounds__(WG) k_pair(const ProgramDev* __restrict__ P, int s, StatusDev* status, RunArgs a) {
+  __shared__ float lds[LDS_FLOATS];
+  const Ctx ctx = make_ctx(*P, a, 0, status);
+  const Stage& sa = P->stages[s];
+  const int n_a = sa.n_items;
+  if ((int)blockIdx.x < n_a) {
+    if (sa.train_only && !ctx.train) return;
+    run_item<KA>(*P, sa, blockIdx.x, ctx, status, lds);
+  } else {
+    const Stage& sb = P->stages[s + 1];
+    if (sb.train_only && !ctx.train) return;
+    run_item<KB>(*P, sb, (int)blockIdx.x - n_a, ctx, status, lds);
+  }
+}
+
 // Fixed image-processing layer for a whole batch at once (it depends on no weight, so it need not
 // sit inside the on-line chain): image t of `images` -> out[t], one workgroup per WG output pixels.
 // (plain pointer types in the signature: the host and the device pass must agree on its mangled name)
@@ -1542,6 +1561,27 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+// Stages s and s + 1 of kinds kind_a and kind_b in one launch; *done = false when no kernel is compiled for the pair
+// (the caller then launches them one after the other).
+hipError_t launch_stage_pair(int kind_a, int n_a, int kind_b, int n_b, hipStream_t stream, const ProgramDev* d_prog,
+                             int s, StatusDev* d_status, const RunArgs& a, bool* done) {
+  *done = false;
+  if (n_a <= 0 || n_b <= 0) return hipSuccess;
+  dim3 grid(n_a + n_b), block(WG);
+#define PAIR(KA, KB)                                                                              \
+  if (kind_a == KA && kind_b == KB) {                                                             \
+    hipLaunchKernelGGL((k_pair<KA, KB>), grid, block, 0, stream, d_prog, s, d_status, a);         \
+    *done = true;                                                                                 \
+    return hipGetLastError();                                                                     \
+  }
+  PAIR(ST_CONV_WGRAD, ST_CONV_BWD_EPI)
+  PAIR(ST_CONV_WGRAD_MFMA, ST_CONV_BWD_EPI)
+  PAIR(ST_CONV_WGRAD, ST_CONV_WGRAD)
+  PAIR(ST_CONV_WGRAD, ST_CONV_BWD)
+#undef PAIR
+  return hipSuccess;
 }
 
 hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, const float* d_images,
