@@ -969,10 +969,19 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
   for (int p0 = 0; p0 < tot; p0 += WG) {
     const int p = p0 + tid;
     float s = p < tot ? dbelow[p] : 0.f;
-    for (int hh = 1; hh < H && ok; ++hh) {
+    if (H == 2) {
       tagged_t w[1];
-      ok = fetch_tagged<1>(rt, w, tag, [&](int) { return xp + (size_t)(hh - 1) * tot + min(p, tot - 1); });
+      ok = fetch_tagged<1>(rt, w, tag, [&](int) { return xp + min(p, tot - 1); });
       s += __uint_as_float((unsigned int)w[0]);
+    } else {
+      // four shares' words in flight at a time (every batch is a round trip), added in the order of the shares
+      for (int h0 = 1; h0 < H && ok; h0 += 4) {
+        tagged_t w[4];
+        ok = fetch_tagged<4>(rt, w, tag, [&](int u) { return xp + (size_t)(min(h0 + u, H - 1) - 1) * tot + min(p, tot - 1); });
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (h0 + u < H) s += __uint_as_float((unsigned int)w[u]);
+      }
     }
     if (ok && p < tot) dbelow[p] = s * f_dact(ybelow[p]);
   }
