@@ -911,7 +911,10 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
           // entries of the lane's input map whose output map lies in [j0, j0 + n): the list is
           // sorted, this chunk's start is the last chunk's end, its end is found by bisection
           int e_lo = j0, e_hi = j0 + n;
-          if (!full) {
+          if (!full && n == j_hi - j_lo) {  // one chunk holds every map: the whole list, nothing to look for
+            e_lo = 0;
+            e_hi = cnt[ln.am];
+          } else if (!full) {
             const int* bj = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
             e_lo = e_next;
             int lo = e_lo, hi = cnt[ln.am];
