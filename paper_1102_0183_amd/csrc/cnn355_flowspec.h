@@ -109,7 +109,7 @@ constexpr long long flow_part_need(int strip, int th, int n_maps, int rows, int 
 // applies).  Two things bound that time: the multiply-adds of one lane (a wavefront issues one
 // vector instruction per about 5 cycles, however many wavefronts share its SIMD), and the LDS
 // reads of all wavefronts together (128 bytes per cycle and compute unit: 2 cycles per wavefront
-// read, taken as 3 with bank conflicts).  0 = one pixel per lane (any stride, any kernel size); tiles exist
+// read; with 3, to allow for bank conflicts, a sweep over all tiles showed the model passing over the fastest).  0 = one pixel per lane (any stride, any kernel size); tiles exist
 // for strides 1 and 2 and kernels of 2 to 5.
 // Returns strip + 16 * rows.
 constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, int max_cnt) {
@@ -132,7 +132,7 @@ constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, 
       const long long reads = (long long)((th - 1) * stride + K) * ((sw - 1) * stride + K) + K * K;
       const long long ways = (max_cnt + iters - 1) / iters;
       const long long waves = (flow_minl(U * ways, WG) + 63) / 64;
-      const long long valu = iters * macs * 5, lds = waves * iters * reads * 3;
+      const long long valu = iters * macs * 5, lds = waves * iters * reads * 2;
       long long cost = passes * ((valu > lds ? valu : lds) + 200);
       // partial sums beyond 32 KB crowd out the weights and maps a rank must hold: last resort only
       if (flow_part_need(sw, th, n_maps, rows, width, max_cnt) > 8 * WG) cost += 1000000;
