@@ -55,7 +55,7 @@ def test_one_epoch_in_the_benchmark_configuration(name, static_id, shares):
         wg, wo = g2.get_weights().astype(np.float64), o2.get_weights()
         e, e_upd = rel_err(wg, wo), rel_err(wg - snap[k], wo - snap[k])
         print("  weights rel err %.2e, update rel err %.2e, near-tie winners adopted %d" % (e, e_upd, adopted), flush=True)
-        assert e <= TOL_W100 and e_upd <= 1e-3
+        assert e <= TOL_W100 and e_upd <= TOL_W100
         # any size: the same 60 images in one launch land on the bits of the 60 single steps
         g3, _ = build_pair(wl, weights=snap[k])
         g3.set_mode(binding.MODE_RESIDENT)

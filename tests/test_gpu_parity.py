@@ -13,6 +13,8 @@ pytestmark = pytest.mark.gpu
 
 ALL = ["cfg1", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"]
 MODES = [binding.MODE_STAGES, binding.MODE_PERSISTENT, binding.MODE_RESIDENT]
+# lock-step runs: most near-tie pooling winners the oracle may take over from the GPU in 100 images
+MAX_ADOPTED = 8
 
 
 def use_mode(g, mode):
@@ -110,7 +112,8 @@ def test_weights_after_100_online_steps(name, mode):
     print("  weights rel err %.2e, accumulated update rel err %.2e, near-tie winners adopted: %d"
           % (e, e_upd, adopted), flush=True)
     assert e <= TOL_W100
-    assert e_upd <= 1e-3
+    assert e_upd <= TOL_W100
+    assert adopted <= MAX_ADOPTED
     for (a, b) in layer_bounds(o):
         assert rel_err(wg[a:b], wo[a:b]) <= TOL_W100, (a, b)
     # forward-only pass after training
@@ -128,6 +131,98 @@ def test_weights_after_100_online_steps(name, mode):
     np.testing.assert_array_equal(g2.get_weights(), wg)
     g.close()
     g2.close()
+
+
+_ORACLE_AFTER_100 = {}
+
+
+def oracle_weights_after_100(name):
+    """The oracle's weights after 100 on-line steps from the workload's seeded start, with nothing taken
+    from the GPU (computed once per workload and kept for the modes that follow)."""
+    if name not in _ORACLE_AFTER_100:
+        wl = synth.WORKLOADS[name]
+        g, o = build_pair(wl)
+        g.close()
+        o.train_many(synth.images(wl, 100), synth.labels(wl, 100), wl.lr)
+        _ORACLE_AFTER_100[name] = (o.get_weights(), layer_bounds(o))
+    return _ORACLE_AFTER_100[name]
+
+
+def first_parting(wl, mode, n):
+    """GPU and oracle stepped image by image from the same start, neither told anything about the other.
+    Returns (t, gap, e_before): the first image at which a pooling winner differs, the oracle's own
+    relative gap between its two best values there (the largest over the differing rectangles), and the
+    weights' relative error just before that image; or (None, None, e_end) when no winner ever differs."""
+    g, o = build_pair(wl)
+    g.set_mode(mode)
+    imgs, labs = synth.images(wl, n), synth.labels(wl, n)
+    d_imgs = to_dev(imgs)
+    sz = g.image_size
+    pools = [l for l in range(1, o.num_layers) if o.layer_info(l)["kind"] == KIND_POOL]
+    e_before = 0.0
+    for t in range(n):
+        g.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], int(labs[t]), wl.lr)
+        o.forward(imgs[t])
+        worst_gap = None
+        for l in pools:
+            argo, argg = o.argmax(l), g.argmax(l)
+            diff = np.argwhere(argo != argg)
+            if len(diff):
+                info = o.layer_info(l)
+                K, Kx = info["K"], info["Kx"]
+                full = o.activation(l - 1)
+                scale = np.abs(full).max()
+                for j, y, x in diff:
+                    win = np.sort(full[j, y * K:(y + 1) * K, x * Kx:(x + 1) * Kx].ravel())
+                    gap = (win[-1] - win[-2]) / scale
+                    worst_gap = gap if worst_gap is None else max(worst_gap, gap)
+        if worst_gap is not None:
+            g.close()
+            return t, worst_gap, e_before
+        o.backward_update(int(labs[t]), wl.lr)
+        e_before = rel_err(g.get_weights(), o.get_weights())
+    g.close()
+    return None, None, e_before
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name", ALL)
+def test_100_online_steps_with_nothing_fed_back(name, mode):
+    """The headline bar (Sec. 4: the GPU program against the CPU program started from the same net): 100
+    on-line steps on the GPU in one call, 100 in the oracle, neither seeing anything of the other; the
+    weights must agree to 1e-4 of the largest weight, overall and layer by layer.
+
+    One thing can legitimately break that: the two sides sum in different orders, and once in some million
+    pooling rectangles the two best values are closer than that rounding, so the winners differ.  Both
+    winners are valid, but the delta of that rectangle then goes to another neuron and the layer's filters
+    move by lr * delta * (difference of two inputs): 1e-3 of the weight range at once, for good.  When the
+    bar is missed the test therefore looks for that event, still without telling either side anything: both
+    are stepped image by image, the first image with a differing winner must exist, the oracle's own two
+    best values there must be closer than the activation tolerance, and up to that image the weights must
+    have met the bar.  Anything else fails.  (What happens after such an image is covered by the lock-step
+    test above, where the oracle follows the GPU through near-ties only.)"""
+    wl = synth.WORKLOADS[name]
+    print("case", name, "mode", mode, flush=True)
+    wo, bounds = oracle_weights_after_100(name)
+    g, _ = build_pair(wl)
+    use_mode(g, mode)
+    g.train_many(to_dev(synth.images(wl, 100)), to_dev(synth.labels(wl, 100)), wl.lr)
+    wg = g.get_weights()
+    g.close()
+    w0 = synth.weights(wl, len(wg))
+    e = rel_err(wg, wo)
+    e_upd = rel_err(wg.astype(np.float64) - w0, wo - w0)
+    worst_layer = max(rel_err(wg[a:b], wo[a:b]) for (a, b) in bounds)
+    print("  weights rel err %.2e (worst layer %.2e), accumulated update rel err %.2e" % (e, worst_layer, e_upd),
+          flush=True)
+    if e <= TOL_W100 and worst_layer <= TOL_W100:
+        return
+    t, gap, e_before = first_parting(wl, mode, 100)
+    assert t is not None, "weights differ by %.2e although no pooling winner ever differed" % e
+    print("  parted at image %d: winners differ where the oracle's two best values are %.2e of the layer's range "
+          "apart; weights rel err up to there %.2e" % (t, gap, e_before), flush=True)
+    assert gap <= TOL_ACT, "a pooling winner differs away from a tie"
+    assert e_before <= TOL_W100
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg5", "cfg4a"])
@@ -303,7 +398,7 @@ def test_tanh_output_units_one_step_and_100_steps(name, mode):
     e, e_upd = rel_err(wg, wo), rel_err(wg.astype(np.float64) - w0, wo - w0)
     print("  weights rel err %.2e, accumulated update rel err %.2e, near-tie winners adopted: %d"
           % (e, e_upd, adopted), flush=True)
-    assert e <= TOL_W100 and e_upd <= 1e-3
+    assert e <= TOL_W100 and e_upd <= TOL_W100 and adopted <= MAX_ADOPTED
     d_imgs, d_labs = to_dev(imgs), to_dev(labs)
     d_out = torch.empty(5 * g.num_classes, dtype=torch.float32, device="cuda:0")
     g.forward_many(d_imgs, 5, d_out)
