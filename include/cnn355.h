@@ -175,6 +175,19 @@ int cnn_forward_batch_scratch_bytes(cnn_t* net, size_t batch, size_t* bytes);
 int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
                       size_t scratch_bytes, size_t batch);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): cnn_forward_batch with its scratch memory taken from an array inside the
+ * library's device image (CNN_FORWARD_BATCH_STATIC_SCRATCH_BYTES bytes, which every GPU the library runs on
+ * holds until the process ends) instead of from the caller.  Same arguments otherwise, same kernels, same
+ * bits.  The call allocates and frees nothing on the device, it launches kernels on the handle's stream only.
+ * Call it with the device current on which the network was created (CNN_E_STATE otherwise).  A batch whose
+ * scratch need (cnn_forward_batch_scratch_bytes) exceeds the array is refused with CNN_E_WORKSPACE and a
+ * message that names both sizes.  Every call on a GPU, from any handle, uses that GPU's one array, which keeps
+ * the previous call's contents (every part that is read is written first in each call): calls that overlap in
+ * time on one GPU race and must be serialised by the caller.  Asynchronous. */
+#define CNN_FORWARD_BATCH_STATIC_SCRATCH_BYTES (64u << 20)
+int cnn_forward_batch_static(cnn_t* net, const float* d_images, size_t n, float* d_probs, size_t batch);
+
 /* Forward propagation of one image (Sec. 3.2).  d_image: cnn_image_size floats, maps then
  * rows then columns.  d_probs: cnn_num_classes floats (may be NULL).  Asynchronous. */
 int cnn_forward(cnn_t* net, const float* d_image, float* d_probs);

@@ -64,6 +64,7 @@ def lib():
             "cnn_set_team": (C.c_int, [vp, C.c_int, C.c_int]),
             "cnn_forward_batch_scratch_bytes": (C.c_int, [vp, sz, vp]),
             "cnn_forward_batch": (C.c_int, [vp, vp, sz, vp, vp, sz, sz]),
+            "cnn_forward_batch_static": (C.c_int, [vp, vp, sz, vp, sz]),
             "cnn_set_output_units": (C.c_int, [vp, C.c_int]),
             "cnn_get_output_units": (C.c_int, [vp]),
             "cnn_set_matrix_cores": (C.c_int, [vp, C.c_int]),
@@ -87,11 +88,13 @@ def lib():
     return _lib
 
 
+FORWARD_BATCH_STATIC_SCRATCH_BYTES = 64 << 20
+
 EXPORTS = ["cnn_arch_info", "cnn_arch_info_xy", "cnn_workspace_bytes", "cnn_plan_text", "cnn_get_plan_text", "cnn_create", "cnn_destroy",
            "cnn_set_connection_table", "cnn_set_fixed_frontend", "cnn_num_weights", "cnn_image_size",
            "cnn_num_layers", "cnn_num_classes", "cnn_layer_info", "cnn_layer_info_xy", "cnn_get_weights", "cnn_set_weights",
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many",
-           "cnn_forward_batch_scratch_bytes", "cnn_forward_batch", "cnn_set_mode",
+           "cnn_forward_batch_scratch_bytes", "cnn_forward_batch", "cnn_forward_batch_static", "cnn_set_mode",
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
            "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
@@ -357,6 +360,16 @@ class Cnn:
         p = self._dev_f32(d_probs, n * self.num_classes)
         self._ck(lib().cnn_forward_batch(self._h, d_images.data_ptr(), int(n), p, d_scratch.data_ptr(),
                                          d_scratch.numel(), int(batch)), "cnn_forward_batch")
+
+    def forward_batch_static(self, d_images, n, d_probs, batch):
+        """forward_batch with the scratch memory taken from the library's own device array (at most
+        FORWARD_BATCH_STATIC_SCRATCH_BYTES): nothing is allocated anywhere."""
+        torch = self._torch
+        assert d_images.is_cuda and d_images.dtype == torch.float32 and d_images.is_contiguous()
+        assert d_images.numel() >= n * self.image_size
+        p = self._dev_f32(d_probs, n * self.num_classes)
+        self._ck(lib().cnn_forward_batch_static(self._h, d_images.data_ptr(), int(n), p, int(batch)),
+                 "cnn_forward_batch_static")
 
     def synchronize(self):
         self._ck(lib().cnn_synchronize(self._h), "cnn_synchronize")

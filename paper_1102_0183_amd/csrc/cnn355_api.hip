@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -258,6 +259,7 @@ struct cnn {
   size_t image_size = 0;
   int n_classes = 0;
   hipStream_t stream = nullptr;
+  int device = 0;               // the device that was current at cnn_create
   int mode = CNN_MODE_STAGES;
   int n_cu = 0, grid_override = 0, coop_ok = 0, max_blocks_per_cu = 1;
   unsigned int spin_limit = 1u << 22;
@@ -1201,6 +1203,7 @@ int cnn_create(const char* arch, void* d_workspace, size_t bytes, void* hip_stre
   if (e == hipSuccess) e = hipDeviceGetAttribute(&net->n_cu, hipDeviceAttributeMultiprocessorCount, dev);
   if (e == hipSuccess) e = hipDeviceGetAttribute(&net->coop_ok, hipDeviceAttributeCooperativeLaunch, dev);
   if (e != hipSuccess) { rc = hip_fail(nullptr, e, "device query"); delete net; return rc; }
+  net->device = dev;
   net->max_blocks_per_cu = std::max(1, persistent_max_blocks_per_cu());
   rc = rebuild(net);
   if (rc) { g_err = net->err; delete net; return rc; }
@@ -1745,3 +1748,52 @@ int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_prob
 }
 
 }  // extern "C"
+
+// ---- the batched forward pass for callers that cannot allocate ------------------------------------
+// cnn_forward_batch takes its scratch memory from the caller.  This variant takes it from an array that
+// is part of the library's device image instead, so that the call allocates nothing anywhere.  In host
+// code the array's name only stands for the symbol: the address of the memory on the device that is
+// current comes from hipGetSymbolAddress, once per device (every device holds its own copy), and only
+// that address is ever used.
+namespace {
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)CNN_FORWARD_BATCH_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+void* g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// the array's address on the current device (asked for once per device), or NULL with *err set
+void* static_scratch_ptr(hipError_t* err, int* device) {
+  *err = hipGetDevice(device);
+  if (*err != hipSuccess) return nullptr;
+  if (*device < 0 || *device >= STATIC_SCRATCH_MAX_DEVICES) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[*device]) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || !p) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+    g_scratch_ptr[*device] = p;
+  }
+  return g_scratch_ptr[*device];
+}
+}  // namespace
+
+extern "C" int cnn_forward_batch_static(cnn_t* net, const float* d_images, size_t n, float* d_probs, size_t batch) {
+  if (!net) return fail(nullptr, CNN_E_ARG, "NULL handle");
+  if (n == 0) return CNN_OK;
+  if (!d_images || !d_probs || batch == 0) return fail(&net->err, CNN_E_ARG, "NULL argument or batch of 0");
+  size_t need = 0;
+  int rc = cnn_forward_batch_scratch_bytes(net, batch, &need);
+  if (rc) return rc;
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(&net->err, CNN_E_WORKSPACE, "cnn_forward_batch_static: a batch of " + std::to_string(batch) + " images needs " +
+                std::to_string(need) + " bytes of scratch, the library's own array holds " +
+                std::to_string(STATIC_SCRATCH_BYTES) + ": use a smaller batch, or cnn_forward_batch with memory of the caller's");
+  hipError_t e = hipSuccess;
+  int device = -1;
+  void* ptr = static_scratch_ptr(&e, &device);
+  if (!ptr) return hip_fail(net, e, "cnn_forward_batch_static: address of the scratch array");
+  if (device != net->device)
+    return fail(&net->err, CNN_E_STATE, "cnn_forward_batch_static: the current device is not the one the network was created on");
+  return cnn_forward_batch(net, d_images, n, d_probs, ptr, STATIC_SCRATCH_BYTES, batch);
+}
