@@ -233,11 +233,11 @@ struct cnn {
   int use_mfma = 1;
   int out_units = CNN_OUTPUT_SOFTMAX_XENT;
   struct ConvBuf {
-    float *act, *out, *delta;
+    float *act, *out, *delta, *dact;
     uint8_t* arg;
     int *argyx, *csr_ptr, *csr_idx, *csc_ptr, *csc_j, *csc_slot;
   };
-  struct FcBuf { float *act, *delta; };
+  struct FcBuf { float *act, *delta, *dact; };
   std::vector<ConvBuf> conv_buf;
   std::vector<FcBuf> fc_buf;
   struct HostTable { std::vector<int> csr_ptr, csr_idx, csc_ptr, csc_j, csc_slot; int max_conn = 0, max_back = 0; };
@@ -340,6 +340,7 @@ size_t carve(cnn* net, void* base) {
       b.act = c.take<float>(full);
       b.out = pooled ? c.take<float>(small) : b.act;
       b.delta = c.take<float>(small);
+      b.dact = c.take<float>(small);
       b.arg = c.take<uint8_t>(small);
       b.argyx = c.take<int>(small);
       b.csr_ptr = c.take<int>(A[l].maps + 1);
@@ -352,6 +353,7 @@ size_t carve(cnn* net, void* base) {
       cnn::FcBuf b;
       b.act = c.take<float>(A[l].maps);
       b.delta = c.take<float>(A[l].maps);
+      b.dact = c.take<float>(A[l].maps);
       net->fc_buf.push_back(b);
     }
   }
@@ -557,7 +559,7 @@ int plan(cnn* net) {
         return fail(&net->err, CNN_E_SHAPE, "a map has more than " + std::to_string(LDS_IN) + " pixels");
       if (L.Kp > 15 || L.Kpx > 15) return fail(&net->err, CNN_E_SHAPE, "pooling rectangle larger than 15x15");
       const cnn::ConvBuf& b = net->conv_buf[conv_i];
-      L.act = b.act; L.out = b.out; L.delta = b.delta; L.arg = b.arg; L.argyx = b.argyx;
+      L.act = b.act; L.out = b.out; L.delta = b.delta; L.dact = b.dact; L.arg = b.arg; L.argyx = b.argyx;
       L.csr_ptr = b.csr_ptr; L.csr_idx = b.csr_idx; L.csc_ptr = b.csc_ptr; L.csc_j = b.csc_j; L.csc_slot = b.csc_slot;
       L.mm_part = net->d_mm_part;
       conv_of_dev[nl] = conv_i;
@@ -578,7 +580,7 @@ int plan(cnn* net) {
       if (L.n_out > MAX_FC_OUT)
         return fail(&net->err, CNN_E_SHAPE, "fully connected layer wider than " + std::to_string(MAX_FC_OUT));
       const cnn::FcBuf& b = net->fc_buf[fc_i];
-      L.act = b.act; L.out = b.act; L.delta = b.delta;
+      L.act = b.act; L.out = b.act; L.delta = b.delta; L.dact = b.dact;
       L.b_canon = (long long)woff;
       L.w_canon = (long long)(woff + L.n_out);
       woff += (size_t)L.n_out * (1 + (size_t)L.n_in);
@@ -1418,6 +1420,7 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
       region(c + "pool", C.o_pool, C.n_own * HW);
       region(c + "yx", C.o_yx, C.n_own * HW);
       region(c + "delta", C.o_delta, C.n_own * HW);
+      region(c + "dact", C.o_dact, C.n_own * HW);
       if (C.o_tab_fwd >= 0) region(c + "tab_fwd", C.o_tab_fwd, 3 * WG);
       if (C.o_tab_pull >= 0) region(c + "tab_pull", C.o_tab_pull, 3 * WG);
       act = std::max(act, (long long)C.n_own * C.Ho * C.Wo);
@@ -1431,6 +1434,7 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
       region(c + "b", Q.o_b, Q.n_out);
       region(c + "act", Q.o_act, Q.n_out);
       region(c + "delta", Q.o_delta, Q.n_out);
+      region(c + "dact", Q.o_dact, Q.n_out);
     }
     region("act", Z.o_act, act);
     // (the partial sums reach up to the next region: what they need is for the reader to work out)

@@ -54,6 +54,8 @@ struct LayerDev {
   CNN_GLOBAL uint8_t* arg;        // conv: winner index dy*Kp+dx per pooled position
   CNN_GLOBAL int* argyx;          // conv: (y << 16) | x of the winner in conv-output coordinates
   CNN_GLOBAL float* delta;        // dE/d(pre-activation): conv at the winners [Mo][Hp][Wp]; fc [n_out]
+  CNN_GLOBAL float* dact;         // derivative of the activation function where a delta can arrive: conv at the
+                                  // winners [Mo][Hp][Wp]; hidden fc [n_out] (written by the forward pass)
   CNN_GLOBAL float* bias;
   CNN_GLOBAL float* w;            // conv: one K*K block per connection, CSR order; fc: [n_out][n_in]
   long long w_canon;   // offset of w in the canonical weight vector (for gradient taps)

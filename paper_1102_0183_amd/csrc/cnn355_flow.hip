@@ -51,8 +51,14 @@ __device__ __forceinline__ float f_act(float a) {
   const float z = __builtin_amdgcn_exp2f((2.0f * ACT_B * 1.44269504088896340736f) * a);
   return fmaf(-2.0f * ACT_A, __builtin_amdgcn_rcpf(z + 1.0f), ACT_A);
 }
-__device__ __forceinline__ float f_dact(float y) {
-  return (float)(1.7159 * 0.6666) - (float)(0.6666 / 1.7159) * y * y;
+// Its derivative A B (1 - tanh^2(B a)) = 4 A B z / (1 + z)^2 with z = e^{-2B|a|}, taken from the sum a the
+// unit received: no difference of nearly equal numbers anywhere, so a saturated unit keeps the relative
+// accuracy of its z (written in terms of the output, A B - (B/A) y^2, the two terms cancel to 1e-3 of
+// themselves there and fp32 keeps only 1e-4 of the result).
+__device__ __forceinline__ float f_dact_pre(float a) {
+  const float z = __builtin_amdgcn_exp2f(-(2.0f * ACT_B * 1.44269504088896340736f) * fabsf(a));
+  const float r = __builtin_amdgcn_rcpf(z + 1.0f);
+  return (4.0f * ACT_A * ACT_B) * z * r * r;
 }
 // Cross-lane moves inside a row of 16 lanes through the data-parallel primitives of the ALU (a few
 // cycles each), instead of the LDS crossbar a general shuffle goes through (an LDS latency each).
@@ -724,14 +730,14 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
       for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
       if (ln.on) {
         job_mac<K, SW, TH, false, ST>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
-        if (D.R == 1) {  // unsplit: the finished sums go straight through the activation function
+        if (D.R == 1) {  // unsplit: the finished sums (the activation function is applied where they are pooled)
           const float b = bf[ln.am];
           float* dst = act + ln.am * Pn + ln.pix;
 #pragma unroll
           for (int ty = 0; ty < TH; ++ty)
 #pragma unroll
             for (int i = 0; i < SW; ++i)
-              if (ty < ln.nrows && i < ln.ncols) dst[ty * S.Wo + i] = f_act(acc[ty * SW + i] + b);
+              if (ty < ln.nrows && i < ln.ncols) dst[ty * S.Wo + i] = acc[ty * SW + i] + b;
         } else {
           float* dst = part + (ln.r * nm + ln.am) * Pn + ln.pix;
 #pragma unroll
@@ -746,7 +752,7 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
   __syncthreads();
   if (D.R > 1) {
     const FDiv dP(Pn);
-    reduce_partials(part, D.R, tot, [&](int p, float s) { act[p] = f_act(s + bf[dP.div(p)]); });
+    reduce_partials(part, D.R, tot, [&](int p, float s) { act[p] = s + bf[dP.div(p)]; });
     __syncthreads();
   }
 }
@@ -761,8 +767,9 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
   float* lds = rt.lds;
   const int tid = threadIdx.x, G = Z.G, rank = rt.rank;
   const int Kp = C.Kp, Wo = C.Wo, Wp = C.Wp, HW = C.Hp * C.Wp, Pn = C.Ho * C.Wo;
-  const float* act = lds + Z.o_act;
+  const float* act = lds + Z.o_act;   // the sums the own maps' units received (bias included)
   float* pool = lds + C.o_pool;
+  float* dact = lds + C.o_dact;
   int* yx = (int*)(lds + C.o_yx);
   gtagged* xo = C.has_x_out ? P.x_out + (size_t)(tag & 1u) * C.Mo * HW : nullptr;
   const FDiv dHW(HW), dWp(Wp);
@@ -770,17 +777,22 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
     const int am = dHW.div(x), q = x - am * HW;
     const int py = dWp.div(q), px = q - py * Wp;
     const float* win = act + am * Pn + py * Kp * Wo + px * Kp;
-    float best = win[0];
+    // the maximum is taken over the outputs (what the parity taps show), and the winner's derivative
+    // from the sum it received
+    float best_a = win[0];
+    float best = f_act(best_a);
     int wy = 0, wx = 0;
 #pragma unroll 4
     for (int dy = 0; dy < Kp; ++dy)
 #pragma unroll 4
       for (int dx = 0; dx < Kp; ++dx) {
-        const float v = win[dy * Wo + dx];
-        if (v > best) { best = v; wy = dy; wx = dx; }
+        const float av = win[dy * Wo + dx];
+        const float v = f_act(av);
+        if (v > best) { best = v; best_a = av; wy = dy; wx = dx; }
       }
     const int code = ((py * Kp + wy) << 16) | (px * Kp + wx);
     pool[x] = best;
+    dact[x] = f_dact_pre(best_a);
     yx[x] = code;
     const size_t o = (size_t)(rank + am * G) * HW + q;
     if (xo) put_f(xo + o, best, tag);
@@ -794,7 +806,7 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
     const FDiv dP(Pn);
     for (int x = tid; x < nm * Pn; x += WG) {
       const int am = dP.div(x), p = x - am * Pn;
-      P.act[(size_t)(rank + am * G) * Pn + p] = act[x];
+      P.act[(size_t)(rank + am * G) * Pn + p] = f_act(act[x]);
     }
   }
   __syncthreads();
@@ -949,10 +961,10 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
   });
   __syncthreads();
   DSTAMP(124);
-  const float* ybelow = lds + Cb.o_pool;
+  const float* fbelow = lds + Cb.o_dact;   // f' of the own units of the layer below
   float* dbelow = lds + Cb.o_delta;
   if (H == 1) {
-    reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s * f_dact(ybelow[p]); });
+    reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s * fbelow[p]; });
     __syncthreads();
     return true;
   }
@@ -986,7 +998,7 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
           if (h0 + u < H) s += __uint_as_float((unsigned int)w[u]);
       }
     }
-    if (ok && p < tot) dbelow[p] = s * f_dact(ybelow[p]);
+    if (ok && p < tot) dbelow[p] = s * fbelow[p];
   }
   __syncthreads();
   return rt.sh->fail == 0;
@@ -1016,7 +1028,7 @@ __device__ __forceinline__ void flow_matvec(const float* W, const float* b, cons
 // same order: lane (k, part) adds the ranks of its part one after the other as their words
 // arrive, the parts are then added in order.  y[k] = b[k] + sum.
 __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged* xp, int NR, int n1, const float* b,
-                                                     float* y, float* part, unsigned int tag, bool through_act) {
+                                                     float* y, float* dy, float* part, unsigned int tag, bool through_act) {
   const int tid = threadIdx.x;
   const int parts = max(1, min(WG / max(n1, 1), NR));
   const int per = (NR + parts - 1) / parts;
@@ -1041,6 +1053,7 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
     if (tid < n1 - k0 && tid < WG) {
       const float v = b[k0 + tid] + sum_strided(part, parts, n1, tid);
       y[k0 + tid] = through_act ? f_act(v) : v;
+      if (through_act) dy[k0 + tid] = f_dact_pre(v);
     }
     __syncthreads();
     if (n1 <= WG) break;
@@ -1327,7 +1340,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         pend = false;
       }
       float* y = lds + L1.o_act;
-      if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, part, tag, !L1.is_output)) return;
+      if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, lds + L1.o_dact, part, tag, !L1.is_output)) return;
       STAMP(31);
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----
@@ -1337,7 +1350,12 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       float* y = lds + L.o_act;
       flow_matvec(lds + L.o_w, lds + L.o_b, lds + Z.fc[f >= 1 ? f - 1 : 0].o_act, y, uni_of<ID>(L.n_out), uni_of<ID>(L.n_in));
       if (!L.is_output) {
-        for (int k = tid; k < L.n_out; k += WG) y[k] = f_act(y[k]);
+        float* dy = lds + L.o_dact;
+        for (int k = tid; k < L.n_out; k += WG) {
+          const float v = y[k];
+          y[k] = f_act(v);
+          dy[k] = f_dact_pre(v);
+        }
         __syncthreads();
       }
       return true;
@@ -1365,14 +1383,19 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         // dependent operations is walked by one wavefront while every other one waits
         const float mx = f_wave_max(yk);
         const float e = (k < N) ? __builtin_amdgcn_exp2f(1.44269504088896340736f * (yk - mx)) : 0.f;
-        const float z = f_wave_sum(e);
-        float p = e * __builtin_amdgcn_rcpf(z);
-        dreg = p - (k == label ? 1.f : 0.f);
+        // the label's delta p - 1 = -(sum of the other classes' exponentials) / z: summed apart from the
+        // label's own term, so that a confident net (p -> 1) loses no digits of it
+        const float zo = f_wave_sum(k == label ? 0.f : e);
+        const float e_lab = lane_f(e, uni(label) & 63);
+        const float z = zo + ((label >= 0 && label < N) ? e_lab : 0.f);
+        const float rz = __builtin_amdgcn_rcpf(z);
+        float p = e * rz;
+        dreg = (k == label) ? -zo * rz : p;
         float err = 0.f;
         if (tanh_out) {  // scaled-tanh outputs, squared error against targets +1 / -1
           p = (k < N) ? f_act(yk) : 0.f;
           const float dev = (k < N) ? p - (k == label ? 1.f : -1.f) : 0.f;
-          dreg = dev * f_dact(p);
+          dreg = (k < N) ? dev * f_dact_pre(yk) : 0.f;
           err = 0.5f * f_wave_sum(dev * dev);
         }
         if (tid < N) {
@@ -1393,8 +1416,8 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
           for (int k = tid; k < N; k += 64) {
             const float p = f_act(y[k]);
             const float dev = p - (k == label ? 1.f : -1.f);
+            d[k] = dev * f_dact_pre(y[k]);
             y[k] = p;
-            d[k] = dev * f_dact(p);
             err = fmaf(dev, dev, err);
             if (rank == 0) {
               if (a.probs_out) a.probs_out[t * n_classes + k] = p;
@@ -1407,13 +1430,14 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
           float mx = -INFINITY;
           for (int k = tid; k < N; k += 64) mx = fmaxf(mx, y[k]);
           mx = f_wave_max(mx);
-          float z = 0.f;
-          for (int k = tid; k < N; k += 64) z += expf(y[k] - mx);
-          z = f_wave_sum(z);
+          float zo = 0.f;
+          for (int k = tid; k < N; k += 64) zo += (k == label) ? 0.f : expf(y[k] - mx);
+          zo = f_wave_sum(zo);
+          const float z = zo + ((label >= 0 && label < N) ? expf(y[max(label, 0)] - mx) : 0.f);
           for (int k = tid; k < N; k += 64) {
             const float p = expf(y[k] - mx) / z;
+            d[k] = (k == label) ? -zo / z : p;
             y[k] = p;
-            d[k] = p - (k == label ? 1.f : 0.f);
             if (rank == 0) {
               if (a.probs_out) a.probs_out[t * n_classes + k] = p;
               if (train && k == label) status->loss = -logf(p);
@@ -1442,6 +1466,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       float* b = lds + L.o_b;
       const float* d = lds + L.o_delta;
       const float* v = lds + Z.fc[f >= 1 ? f - 1 : 0].o_act;
+      const float* fprev = lds + Z.fc[f >= 1 ? f - 1 : 0].o_dact;
       float* dprev = lds + Z.fc[f >= 1 ? f - 1 : 0].o_delta;
       const int n_in = uni_of<ID>(L.n_in), n_out = uni_of<ID>(L.n_out);
       const bool from_reg = wave_softmax && f == n_fc - 1;
@@ -1466,7 +1491,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
             }
           }
         }
-        dprev[m] = g * f_dact(vm);
+        dprev[m] = g * fprev[m];
       }
       for (int k = tid; k < n_out; k += WG) {
         const float dk = from_reg ? dreg : d[k];   // tid < 64 here: lane k of wave 0
@@ -1481,7 +1506,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
     {  // ---- BP + AW, first fully connected layer: own columns ----
       const float* wc = lds + L1.o_w;
       const float* d = lds + L1.o_delta;
-      const float* vcol = lds + Cc.o_pool;
+      const float* fcol = lds + Cc.o_dact;
       float* dconv = lds + Cc.o_delta;
       const int* yxc = (const int*)(lds + Cc.o_yx);
       const int Moc = uni_of<ID>(Cc.Mo);
@@ -1492,7 +1517,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         for (int k = lane; k < n1; k += 64) s = fmaf(wc[c * n1 + k], d[k], s);
         s = f_wave_sum(s);
         if (lane == 0) {
-          const float dc = s * f_dact(vcol[c]);
+          const float dc = s * fcol[c];
           dconv[c] = dc;
           const int am = dHW.div(c), q = c - am * HWc;
           const size_t o = (size_t)(rank + am * G) * HWc + q;

@@ -40,6 +40,7 @@ struct ConvSpec {
   int o_pool;   // [n_own][Hp*Wp] pooled outputs of the own maps
   int o_yx;     // [n_own][Hp*Wp] winner coordinates (y << 16 | x) (int)
   int o_delta;  // [n_own][Hp*Wp] deltas at the winners
+  int o_dact;   // [n_own][Hp*Wp] derivative of the activation function at the winners
   int o_tab_fwd;   // [3][WG] every lane's share of the FP job (int), or -1
   int o_tab_pull;  // [3][WG] every lane's share of the pull job (int), or -1
 };
@@ -50,6 +51,7 @@ struct FcSpec {
   int o_b;      // [n_out]
   int o_act;    // [n_out]
   int o_delta;  // [n_out]
+  int o_dact;   // [n_out] derivative of the activation function (hidden layers)
 };
 
 struct FlowSpec {
@@ -207,6 +209,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     C.o_pool = take((long long)C.n_own * HW);
     C.o_yx = take((long long)C.n_own * HW);
     C.o_delta = take((long long)C.n_own * HW);
+    C.o_dact = take((long long)C.n_own * HW);
     max_act = flow_maxl(max_act, (long long)C.n_own * C.Ho * C.Wo);
     max_part = flow_maxl(max_part, flow_part_need(C.fwd_strip, C.fwd_rows, C.n_own, C.Ho, C.Wo, C.max_conn));
     // pooled positions split R ways when a rank has few weights to adjust (same R for both copies)
@@ -226,6 +229,7 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     Q.o_b = take(Q.n_out);
     Q.o_act = take(Q.n_out);
     Q.o_delta = take(Q.n_out);
+    Q.o_dact = take(Q.n_out);
   }
   Z.o_act = take(max_act);
   Z.o_part = take(max_part);

@@ -22,9 +22,14 @@ typedef CNN_GLOBAL float gfloat;  // a float in device (global) memory
 #define ACT_A 1.7159f
 #define ACT_B 0.6666f
 __device__ __forceinline__ float act_f(float a) { return ACT_A * tanhf(ACT_B * a); }
-// derivative written in terms of the output:  A*B*(1 - tanh^2) = A*B - (B/A) y^2
-__device__ __forceinline__ float dact_f(float y) {
-  return (float)(1.7159 * 0.6666) - (float)(0.6666 / 1.7159) * y * y;
+// Its derivative A B (1 - tanh^2(B a)) = 4 A B z / (1 + z)^2 with z = e^{-2B|a|}, from the sum a the unit
+// received (the forward pass stores it wherever a delta can arrive: at the pooling winners and at the hidden
+// fully connected units).  Written in terms of the output, A B - (B/A) y^2, the two terms cancel to 1e-3 of
+// themselves at a saturated unit and fp32 keeps only 1e-4 of the result; here nothing cancels.
+__device__ __forceinline__ float dact_pre_f(float a) {
+  const float z = expf(-2.0f * ACT_B * fabsf(a));
+  const float r = 1.0f / (1.0f + z);
+  return (4.0f * ACT_A * ACT_B) * z * r * r;
 }
 
 // Optional fine-grained timestamps inside work items (development aid; compiled out unless
@@ -211,6 +216,10 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   float* lds_w = lds + LDS_IN;
   float* lds_part = lds + LDS_IN + LDS_AUX + LDS_AUX2;
   float* lds_out = lds_part + WG;
+  float* lds_pre = lds_w;  // the sums the tile's units received: kept (once the filters are done with) for the
+                           // derivative at the pooling winners
+  const int Kp = L.Kp, Kpx = L.Kpx;
+  const bool pooled = Kp > 1 || Kpx > 1;
 
   DBG(0);
   const float b = L.bias[j];  // issued first, used last
@@ -277,15 +286,17 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   for (int t = 0; t < TT; ++t) {
     const int p = tid + t * WG;
     if (p < P && (TT > 1 || r == 0)) {
-      const float a = act_f(acc[t] + b);
+      const float sum = acc[t] + b;
+      const float a = act_f(sum);
       L.act[((size_t)j * Ho + y0) * Wo + p] = a;
       lds_out[p] = a;
+      lds_pre[p] = sum;
+      if (!pooled) L.dact[((size_t)j * Ho + y0) * Wo + p] = dact_pre_f(sum);
     }
   }
   __syncthreads();
   DBG(6);
-  const int Kp = L.Kp, Kpx = L.Kpx;
-  if (Kp > 1 || Kpx > 1) {
+  if (pooled) {
     const int Wp = L.Wp;
     const int nq = (rows / Kp) * Wp;
     for (int q = tid; q < nq; q += WG) {
@@ -300,6 +311,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
         }
       const size_t o = ((size_t)j * L.Hp + (y0 / Kp + py)) * Wp + px;
       L.out[o] = best;
+      L.dact[o] = dact_pre_f(lds_pre[(py * Kp + wy) * Wo + px * Kpx + wx]);
       L.arg[o] = (uint8_t)(wy * Kpx + wx);
       L.argyx[o] = ((y0 + py * Kp + wy) << 16) | (px * Kpx + wx);
     }
@@ -521,6 +533,8 @@ __device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* 
   const int n_planes = st.rows_per_wg;
   float* lds_out = lds;                 // [P]
   float* lds_part = lds + MAX_TILE_PIX; // [G][P] partial sums of the plane groups
+  float* lds_pre = lds_part + WG;       // [P] the sums the map's units received, for the derivative at the winners
+  const bool pooled = L.Kp > 1;
   const float b = L.bias[j];
   // G lane groups of P lanes each take every G-th block of 8 planes
   const int G = (P >= WG) ? 1 : min(WG / P, (n_planes + 7) / 8);
@@ -550,11 +564,13 @@ __device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* 
       const float a = act_f(s + b);
       L.act[(size_t)j * P + pp] = a;
       lds_out[pp] = a;
+      lds_pre[pp] = s + b;
+      if (!pooled) L.dact[(size_t)j * P + pp] = dact_pre_f(s + b);
     }
   }
   __syncthreads();
   const int Kp = L.Kp;
-  if (Kp > 1) {
+  if (pooled) {
     const int Wp = L.Wp;
     const int nq = L.Hp * Wp;
     for (int q = tid; q < nq; q += WG) {
@@ -569,6 +585,7 @@ __device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* 
         }
       const size_t o = (size_t)j * nq + q;
       L.out[o] = best;
+      L.dact[o] = dact_pre_f(lds_pre[(py * Kp + wy) * Wo + px * Kp + wx]);
       L.arg[o] = (uint8_t)(wy * Kp + wx);
       L.argyx[o] = ((py * Kp + wy) << 16) | (px * Kp + wx);
     }
@@ -604,7 +621,10 @@ __device__ void fc_fwd_item(const LayerDev& L, const Stage& st, int item,
     float t = 0.f;
     for (int k = 0; k < wpr; ++k) t += part[tid * wpr + k];
     const int rr = item * rpw + tid;
-    if (rr < L.n_out) L.act[rr] = act_f(t + bias);
+    if (rr < L.n_out) {
+      L.act[rr] = act_f(t + bias);
+      L.dact[rr] = dact_pre_f(t + bias);
+    }
   }
   __syncthreads();
 }
@@ -682,7 +702,7 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
       const float t = (k == ctx.label) ? 1.f : -1.f;
       L.act[k] = y;
       if (ctx.probs_out) ctx.probs_out[k] = y;
-      const float d = (y - t) * dact_f(y);
+      const float d = (y - t) * dact_pre_f(logit[k]);
       dl[k] = d;
       e = fmaf(y - t, y - t, e);
       if (ctx.train) L.delta[k] = d;
@@ -693,14 +713,18 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
     float mx = -INFINITY;
     for (int k = lane; k < N; k += 64) mx = fmaxf(mx, logit[k]);
     mx = wave_max(mx);
-    float z = 0.f;
-    for (int k = lane; k < N; k += 64) z += expf(logit[k] - mx);
-    z = wave_sum(z);
+    // the label's delta p - 1 = -(sum of the other classes' exponentials) / z: summed apart from the label's
+    // own term, so that a confident net (p -> 1) loses no digits of it
+    float zo = 0.f;
+    for (int k = lane; k < N; k += 64) zo += (k == ctx.label) ? 0.f : expf(logit[k] - mx);
+    zo = wave_sum(zo);
+    const bool has_label = ctx.label >= 0 && ctx.label < N;
+    const float z = zo + (has_label ? expf(logit[has_label ? ctx.label : 0] - mx) : 0.f);
     for (int k = lane; k < N; k += 64) {
       const float p = expf(logit[k] - mx) / z;
       L.act[k] = p;
       if (ctx.probs_out) ctx.probs_out[k] = p;
-      const float d = p - (k == ctx.label ? 1.f : 0.f);
+      const float d = (k == ctx.label) ? -zo / z : p;
       dl[k] = d;
       if (ctx.train) {
         L.delta[k] = d;
@@ -736,7 +760,7 @@ __device__ void head_item(const LayerDev& L, const LayerDev* Lp, const gfloat* v
         else *wp = w - lr * (d * vm);
       }
     }
-    if (Lp) Lp->delta[m] = g * dact_f(vm);
+    if (Lp) Lp->delta[m] = g * Lp->dact[m];
   }
   DBG(13);
   for (int k = tid; k < N; k += WG) {
@@ -801,7 +825,7 @@ __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& 
   if (ks == 0 && m < n_in && Lp) {
     float s = 0.f;
     for (int kk = 0; kk < KS; ++kk) s += part[kk * CM + cm];
-    Lp->delta[m] = s * dact_f(vm);
+    Lp->delta[m] = s * Lp->dact[m];
   }
   if (item == 0) {
     for (int k = tid; k < N; k += WG) {
@@ -952,7 +976,7 @@ __device__ void conv_bwd_item(const LayerDev& L, const LayerDev& Lp, const Stage
   }
   if (r == 0 && active) {
     const size_t o = (size_t)i * Pin + p;
-    Lp.delta[o] = acc * dact_f(Lp.out[o]);
+    Lp.delta[o] = acc * Lp.dact[o];
   }
 }
 
@@ -1244,7 +1268,7 @@ __device__ void conv_bwd_epi_item(const LayerDev& L, const LayerDev& Lp, const S
       for (int u = 0; u < 8; ++u) s += (s0 + u < n_planes) ? v[u] : 0.f;
     }
     const size_t o = (size_t)i * P + p;
-    Lp.delta[o] = s * dact_f(Lp.out[o]);
+    Lp.delta[o] = s * Lp.dact[o];
   }
 }
 

@@ -88,12 +88,28 @@ def compare_forward_state(g, o, tol=TOL_ACT, report=None):
 
 
 def compare_backward_state(g, o, tol=TOL_ACT):
+    """Deltas of every trainable layer.  Under a max-pooling layer a delta sits at the winner of its rectangle;
+    where the two sides' winners differ (compare_forward_state has made sure that happens at near-ties only)
+    both placements are valid, so there the delta is compared rectangle by rectangle (its value, wherever in
+    the rectangle it sits) and everywhere else element by element."""
     worst = 0.0
     for l in range(1, o.num_layers):
-        if o.layer_info(l)["kind"] in (KIND_CONV, KIND_FC):
-            e = rel_err(g.delta(l), o.delta(l))
-            worst = max(worst, e)
-            assert e <= tol, "delta of layer %d: rel err %.3g" % (l, e)
+        if o.layer_info(l)["kind"] not in (KIND_CONV, KIND_FC):
+            continue
+        dg, do = g.delta(l).astype(np.float64), o.delta(l)
+        pooled = l + 1 < o.num_layers and o.layer_info(l + 1)["kind"] == KIND_POOL
+        if pooled and np.any(g.argmax(l + 1) != o.argmax(l + 1)):
+            info = o.layer_info(l + 1)
+            K, Kx = info["K"], info["Kx"]
+            M, H, W = do.shape
+            per_window = lambda d: d.reshape(M, H // K, K, W // Kx, Kx).sum(axis=(2, 4))
+            same = np.repeat(np.repeat(g.argmax(l + 1) == o.argmax(l + 1), K, axis=1), Kx, axis=2)
+            scale = np.abs(do).max()
+            e = max(np.abs(per_window(dg) - per_window(do)).max(), np.abs((dg - do) * same).max()) / (scale if scale > 0 else 1.0)
+        else:
+            e = rel_err(dg, do)
+        worst = max(worst, e)
+        assert e <= tol, "delta of layer %d: rel err %.3g" % (l, e)
     return worst
 
 

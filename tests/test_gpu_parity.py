@@ -341,6 +341,39 @@ def test_matrix_core_forward_matches_the_vector_kernel(name):
     g.close()
 
 
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name,scale", [("cfg4a", 6.0), ("cfg2b", 6.0), ("cfg1", 20.0)])
+def test_saturated_units_keep_the_delta_bar(name, scale, mode):
+    """Weights several times the paper's initial range drive most units into saturation, which is where trained
+    nets live.  There the derivative of the activation function is a small number: taken from the sum the unit
+    received (Sec. 3.3 multiplies every pulled delta by it) it keeps fp32 accuracy, so activations, deltas and
+    gradients must still meet the 1e-5 bar, and one large step must land on the oracle's weights."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, "weights x", scale, "mode", mode, flush=True)
+    g, o = build_pair(wl)
+    w = (g.get_weights() * np.float32(scale)).astype(np.float32)
+    g.set_weights(w)
+    o.set_weights(w.astype(np.float64))
+    use_mode(g, mode)
+    img = synth.images(wl, 3)[2]
+    lab = int(synth.labels(wl, 3)[2])
+    grad_g = g.debug_gradients(to_dev(img), lab)
+    grad_o, loss_o = o.gradients(img, lab)
+    # the point of the case: a good share of the hidden units is saturated
+    sat = [np.mean(np.abs(o.activation(l)) > 1.6) for l in range(1, o.num_layers - 1)
+           if o.layer_info(l)["kind"] in (KIND_CONV, 3)]
+    print("  share of units beyond +-1.6 per layer:", " ".join("%.2f" % v for v in sat), flush=True)
+    assert max(sat) > 0.2
+    compare_forward_state(g, o)
+    e_d = compare_backward_state(g, o)
+    # (the error is a difference of output sums that are tens of units large here: fp32 keeps 1e-5 of it at best)
+    assert abs(g.loss() - loss_o) <= 1e-4 * max(1.0, abs(loss_o))
+    for (a, b) in layer_bounds(o):
+        assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
+    print("  deltas rel err %.2e" % e_d, flush=True)
+    g.close()
+
+
 def test_update_order_old_weights_feed_the_deltas():
     """A large learning rate makes a wrong order (weights adjusted before the deltas below
     them were pulled) visible after a single step."""
