@@ -1,21 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the on-line training hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--mode resident|persistent|stages]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--mode auto|resident|persistent|stages]
+                    [--headline cfg2a] [--no-per-config] [--no-extra] [--no-cpu-baseline]
 
-One "step" is one cnn_train_many call: B consecutive images of the 60,000-image synthetic
-29x29 stream (workload cfg2) trained on-line -- forward, delta pass, weight gradients and an
-SGD update after every image -- on the net 1x29x29-20C4-MP2-40C5-MP3-150N-10N.  The stream is
+One "step" is one cnn_train_many call: B consecutive images of the headline workload's seeded stream trained
+on-line -- forward pass, delta pass, weight gradients and an SGD update after every image.  The stream is
 resident in HBM before the timed region starts.  Prints ONE JSON line.
 
 value        = images trained per second over the K timed steps (wall clock, synchronised).
-roofline     = the dominant kernel's algorithmic bytes per launch / its mean launch duration,
-               measured with HIP events on the launch stream, against the 8 TB/s HBM peak;
-               traffic = HBM bytes per launch from the rocprofv3 counter summary under profiles/
-               (FETCH_SIZE + WRITE_SIZE, calibrated on a copy of known size), when one is there.
-cpu_baseline = the CPU oracle (float32 instantiation, OpenMP over output maps) timed on a
-               prefix of the same stream on this machine's host cores.
-extra        = the other measurements the workload names (larger net, forward-only passes).
+roofline     = the dominant kernel's algorithmic bytes per launch / its mean launch duration, measured with HIP
+               events on the launch stream, against the 8 TB/s HBM peak; traffic = HBM bytes per launch from the
+               rocprofv3 counter summary under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by what the counters
+               read for a copy of known size), labelled with the file it comes from, or null.
+cpu_baseline = the CPU oracle (float32 instantiation, OpenMP over output maps) timed on a prefix of the same
+               stream on this machine's host cores.
+per_config   = the same for each of the seven benchmark architectures (and, as context, the paper's own NORB and
+               CIFAR10 architectures): mode and kernels timed, on-line training and forward-only rates, work per
+               image computed from the layer shapes (multiply-adds and compulsory bytes), the fraction of the
+               bound that applies, the dependency bound (crossings between compute units x the measured time of
+               one, or launches x the measured launch floor), and the oracle's rate on a prefix.
+extra        = batched forward pass, on-line deformation, one call per image.
 """
 import argparse
 import json
@@ -27,59 +32,84 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FP32_MFMA_PEAK_TFLOPS = 157.3
+FP32_PEAK_TFLOPS = 157.3      # vector and matrix fp32 alike
 HBM_PEAK_GBS = 8000.0
+MODE_NAMES = {0: "stages", 1: "persistent", 2: "resident"}
 KERNEL_OF_MODE = {"resident": "k_resident", "persistent": "k_persistent", "stages": "per-stage kernels (sum)"}
 
+# the paper's own architectures (Sec. 4.2, 4.3) on synthetic images of the data sets' shapes: context only
+PAPER_NETS = [
+    ("paper-cifar-100maps", "3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", (3, 32, 32), 10,
+     "Table 3, 100 maps per layer: 93 s per epoch (50000 trained + 60000 forward passes, 2011 GPU)"),
+    ("paper-cifar-300maps", "3x32x32-300C3-MP3-300C3-MP2-300C3-MP2-300N-100N-10N", (3, 32, 32), 10,
+     "Table 3, 300 maps per layer: 532 s per epoch"),
+    ("paper-norb", "2x96x96-300C6S1-MP2-500C4-MP4-500N-5N", (2, 96, 96), 5,
+     "Table 2: 1141 s per epoch (set sizes not given in the paper)"),
+]
 
-def measured_traffic(mode, batch):
-    """HBM bytes per launch of the mode's kernel on the benchmark workload, from the committed
-    rocprofv3 --pmc summary (a text file with a line 'traffic_bytes_per_launch: N batch: B')."""
-    path = os.path.join(ROOT, "profiles", "%s_cfg2a_train_traffic.txt" % KERNEL_OF_MODE[mode].split()[0])
+
+def measured_traffic(kernel, cfg, batch):
+    """HBM bytes per launch from a committed rocprofv3 --pmc summary (a text file with a line
+    'traffic_bytes_per_launch: N batch: B'), with the file's name; (None, None) when there is none."""
+    name = "%s_%s_train_traffic.txt" % (kernel, cfg)
+    path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
                 f = line.split()
                 if int(f[3]) == batch:
-                    return int(f[1])
+                    return int(f[1]), "profiles/" + name
     except (OSError, ValueError, IndexError):
         pass
-    return None
+    return None, None
 
 
-def forward_flops_per_image(info):
-    """2 x multiply-accumulates of one forward pass, full connection tables (Sec. 2.2, 2.4)."""
-    f = 0
+def layer_work(info, n_conn):
+    """Multiply-adds of one image per trainable layer, from the layer shapes: forward (Sec. 2.2, 2.4), delta pull
+    (Sec. 3.3, dense rectangle; none into the network input), weight gradients (Sec. 3.4, dense delta).
+    n_conn[i] = connections of the i-th convolutional layer."""
+    out = []
+    ci = 0
+    first = True
     for l in range(1, len(info)):
         a, p = info[l], info[l - 1]
         if a["kind"] == 1:
-            f += 2 * a["maps"] * a["h"] * a["w"] * p["maps"] * a["K"] ** 2
+            fwd = n_conn[ci] * a["K"] * a.get("Kx", a["K"]) * a["h"] * a["w"]
+            ci += 1
         elif a["kind"] == 3:
-            f += 2 * a["maps"] * p["maps"] * p["h"] * p["w"]
-    return f
+            fwd = a["maps"] * p["maps"] * p["h"] * p["w"]
+        else:
+            continue
+        out.append({"layer": l, "fwd": fwd, "pull": 0 if first else fwd, "wgrad": fwd})
+        first = False
+    return out
 
 
-def algorithmic_bytes_per_train_image(info, n_weights, image_floats):
-    """Compulsory traffic of one on-line step, fp32: every weight read by the forward pass, read
-    again by the delta pass (except the first layer, below which nothing is propagated), and read
-    and written by the update; the image read twice (forward, first layer's weight gradients);
-    every layer output written once and read once forward and once backward; one delta per
-    pooled position written and read; arg-max bytes written and read."""
-    first = info[1]
-    first_w = first["maps"] * (1 + info[0]["maps"] * first["K"] ** 2) if first["kind"] == 1 else \
-        first["maps"] * (1 + info[0]["maps"] * info[0]["h"] * info[0]["w"])
+def train_flop(work):
+    return 2 * sum(w["fwd"] + w["pull"] + w["wgrad"] for w in work)
+
+
+def fwd_flop(work):
+    return 2 * sum(w["fwd"] for w in work)
+
+
+def algorithmic_bytes_per_train_image(info, n_weights, image_floats, first_w):
+    """Compulsory traffic of one on-line step, fp32: every weight read by the forward pass, read again by the
+    delta pass (except the first layer, below which nothing is propagated), and read and written by the update;
+    the image read twice (forward, first layer's weight gradients); every layer output written once and read
+    once forward and once backward; one delta per pooled position written and read; arg-max bytes."""
     b = 4 * (4 * n_weights - first_w)
     b += 4 * 2 * image_floats
     for l in range(1, len(info)):
         n = info[l]["maps"] * info[l]["h"] * info[l]["w"]
-        if info[l]["kind"] == 1:      # conv: full-resolution output written once
+        if info[l]["kind"] == 1:
             b += 4 * n
             pooled = l + 1 < len(info) and info[l + 1]["kind"] == 2
             if not pooled:
-                b += 4 * 2 * n + 4 * 2 * n      # read fwd + bwd, delta write + read
-        elif info[l]["kind"] == 2:    # pool: pooled values w + 2r, arg-max w + r, delta w + r
+                b += 4 * 2 * n + 4 * 2 * n
+        elif info[l]["kind"] == 2:
             b += 4 * 3 * n + 2 * n + 4 * 2 * n
-        else:                         # fully connected: output w + 2r, delta w + r
+        else:
             b += 4 * 3 * n + 4 * 2 * n
     return b
 
@@ -93,14 +123,13 @@ def algorithmic_bytes_per_forward_image(info, n_weights, image_floats):
 
 
 def time_steps(torch, fn, steps, warmup):
-    """W untimed warm-up steps, then K steps: wall clock bracketed by synchronize on both sides,
-    and HIP events around every launch on the launch stream."""
+    """W untimed warm-up steps, then K steps: wall clock bracketed by synchronize on both sides, and HIP events
+    around every launch on the launch stream."""
     stream = torch.cuda.current_stream()
     for k in range(warmup):
         fn(k)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(steps)]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
     for k in range(steps):
         ev[k][0].record(stream)
@@ -108,8 +137,16 @@ def time_steps(torch, fn, steps, warmup):
         ev[k][1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    kernel_ms = [a.elapsed_time(b) for a, b in ev]
-    return wall, kernel_ms
+    return wall, [a.elapsed_time(b) for a, b in ev]
+
+
+def event_ms(torch, fn):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1)
 
 
 def main():
@@ -118,13 +155,17 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=1000, help="images per step (one cnn_train_many call)")
-    ap.add_argument("--mode", choices=["resident", "persistent", "stages"], default="resident")
+    ap.add_argument("--mode", choices=["auto", "resident", "persistent", "stages"], default="auto",
+                    help="auto: resident where the network fits it, else one launch per stage")
+    ap.add_argument("--headline", default="cfg2a", help="workload the scored line is measured on")
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the persistent kernel (0 = automatic)")
     ap.add_argument("--ranks", type=int, default=0, help="resident mode: workgroups in the team (0 = automatic)")
     ap.add_argument("--xcd-stride", type=int, default=0, help="resident mode: 8 = team on one XCD, 1 = spread, 0 = automatic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-per-config", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-seconds-per-config", type=float, default=1.5)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (on-line SGD is a strict chain over images); "
@@ -138,25 +179,170 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
-    wl = synth.WORKLOADS["cfg2a"]
-    n_stream = wl.n_images
-    imgs = synth.images(wl)
-    labs = synth.labels(wl)
+    nets = []   # every handle made here is closed before the interpreter exits
+
+    def pick_mode(net):
+        if args.mode != "auto":
+            m = {"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
+                 "stages": binding.MODE_STAGES}[args.mode]
+            if not net.mode_supported(m):
+                m = binding.MODE_STAGES
+        else:
+            m = binding.MODE_RESIDENT if net.mode_supported(binding.MODE_RESIDENT) else binding.MODE_STAGES
+        net.set_mode(m)
+        if m == binding.MODE_PERSISTENT and args.grid:
+            net.set_grid(args.grid)
+        if m == binding.MODE_RESIDENT and (args.ranks or args.xcd_stride):
+            net.set_team(args.ranks, args.xcd_stride)
+        return MODE_NAMES[m]
+
+    def make_net(workload):
+        net = synth.build_network(binding.Cnn(workload.arch), workload)
+        nets.append(net)
+        return net, pick_mode(net)
+
+    def shapes_of(net):
+        info = [net.layer_info(l) for l in range(net.num_layers)]
+        # connections of every convolutional layer, from the weight count of the layer (bias + K*Kx per connection)
+        n_conn, first_w = [], None
+        w_left = net.num_weights
+        for l in range(1, len(info)):
+            a, p = info[l], info[l - 1]
+            if a["kind"] == 3:
+                n = a["maps"] * (1 + p["maps"] * p["h"] * p["w"])
+                w_left -= n
+                first_w = n if first_w is None else first_w
+        convs = [l for l in range(1, len(info)) if info[l]["kind"] == 1]
+        full = [info[l]["maps"] * info[l - 1]["maps"] for l in convs]
+        tabs = getattr(net, "_bench_tables", {})
+        for i, l in enumerate(convs):
+            n_conn.append(int(tabs[i].sum()) if i in tabs else full[i])
+        if convs:
+            l = convs[0]
+            first_w = info[l]["maps"] + n_conn[0] * info[l]["K"] * info[l]["Kx"]
+        return info, n_conn, first_w
+
+    def dependency_bound(net, mode, info, us_per_image, floors):
+        """The bound of a chain of dependent stages: how often one image's data must cross between compute units
+        (resident mode) or how many kernels are launched per image (stage mode), times what one costs."""
+        n_conv = sum(1 for a in info if a["kind"] == 1)
+        if mode == "resident":
+            ranks = net.resident_ranks() if hasattr(net, "resident_ranks") else 0
+            count = 2 * (n_conv - 1) + 1
+            key = "crossing_us_%d_ranks" % ranks
+            if key not in floors:
+                floors[key] = net.measure_crossing(max(2, ranks), 64, 200)
+            floor = floors[key]
+            kind = "crossings between compute units (pooled maps up, partial sums of the first fully connected " \
+                   "layer, deltas down), each an exchange of tagged words among %d ranks" % ranks
+        else:
+            lines = [ln for ln in net.plan_text().strip().split("\n") if ln.strip()]
+            count = sum(1 for ln in lines if "barrier=1" in ln) if mode == "stages" else len(lines)
+            if "launch_us" not in floors:
+                floors["launch_us"] = net.measure_launch(500)
+            floor = floors["launch_us"]
+            kind = "kernel launches per image" if mode == "stages" else "grid barriers per image (priced at a launch)"
+        us = count * floor
+        return {"kind": kind, "count": count, "floor_us_each": round(floor, 3), "us": round(us, 2),
+                "share_of_measured": round(us / us_per_image, 3)}
+
+    def oracle_rate(workload, arch, image_shape, n_classes, seconds, tables=None, frontend=None, wts=None, imgs=None, labs=None):
+        import oracle
+        cores = oracle.set_threads(0)
+        ref = oracle.Oracle(arch, 32)
+        if workload is not None:
+            synth.build_network(ref, workload)
+        else:
+            rng = np.random.default_rng(7)
+            ref.set_weights(((rng.random(ref.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
+        t0 = time.perf_counter()
+        ref.train_many(imgs[:1], labs[:1], 1e-3)
+        one = time.perf_counter() - t0
+        n = int(max(2, min(len(labs) - 1, seconds / max(one, 1e-6))))
+        t0 = time.perf_counter()
+        ref.train_many(imgs[1:1 + n], labs[1:1 + n], 1e-3)
+        dt = time.perf_counter() - t0
+        return {"value": round(n / dt, 2), "unit": "images/s", "cores": cores, "kind": "oracle",
+                "sample": "images 1..%d of the same stream, float32 instantiation of the oracle, OpenMP over "
+                          "output maps, %.1f s" % (n, dt)}
+
+    floors = {}
+
+    def measure_config(name, arch, workload, n_train, image_shape=None, n_classes=None, note=None, with_cpu=True):
+        """On-line training and forward-only rates of one architecture in the mode that runs it, with its work per
+        image and bounds."""
+        if workload is not None:
+            net, mode = make_net(workload)
+            if workload.sparse_conv is not None:
+                convs = [l for l in range(1, net.num_layers) if net.layer_info(l)["kind"] == 1]
+                l = convs[workload.sparse_conv]
+                net._bench_tables = {workload.sparse_conv: synth.connection_table(
+                    workload, net.layer_info(l)["maps"], net.layer_info(l - 1)["maps"])}
+            imgs, labs = synth.images(workload, n_train), synth.labels(workload, n_train)
+            lr = workload.lr
+        else:
+            net = binding.Cnn(arch)
+            nets.append(net)
+            rng = np.random.default_rng(7)
+            net.set_weights(((rng.random(net.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
+            mode = pick_mode(net)
+            imgs = rng.uniform(-1, 1, (n_train,) + tuple(image_shape)).astype(np.float32)
+            labs = rng.integers(0, n_classes, n_train).astype(np.int32)
+            lr = 1e-3
+        d_i, d_l = torch.from_numpy(imgs).to(dev), torch.from_numpy(labs).to(dev)
+        info, n_conn, first_w = shapes_of(net)
+        work = layer_work(info, n_conn)
+        warm = max(8, n_train // 8)
+        net.train_many(d_i, d_l, lr, n=warm)
+        net.synchronize()
+        ms = min(event_ms(torch, lambda: net.train_many(d_i, d_l, lr)) for _ in range(2))
+        us_train = 1e3 * ms / n_train
+        net.forward_many(d_i, warm)
+        net.synchronize()
+        ms_f = min(event_ms(torch, lambda: net.forward_many(d_i, n_train)) for _ in range(2))
+        assert np.isfinite(net.get_weights()).all(), "training diverged on " + name
+        fl, by = train_flop(work), algorithmic_bytes_per_train_image(info, net.num_weights, net.image_size, first_w)
+        t_f32, t_hbm = fl / (FP32_PEAK_TFLOPS * 1e12) * 1e6, by / (HBM_PEAK_GBS * 1e9) * 1e6
+        bound = "fp32" if t_f32 >= t_hbm else "hbm"
+        t_bound = max(t_f32, t_hbm)
+        kernels = {"resident": "k_resident (one cooperative launch per call)",
+                   "persistent": "k_persistent (one cooperative launch per call)",
+                   "stages": "one launch per stage: " + ", ".join(
+                       sorted({ln.split()[1] for ln in net.plan_text().strip().split("\n") if ln.strip()}))}[mode]
+        traffic, src = measured_traffic(KERNEL_OF_MODE[mode].split()[0] if mode != "stages" else "stage_kernels", name, n_train)
+        rec = {
+            "name": name, "arch": arch, "mode": mode, "kernels": kernels,
+            "train": {"images_per_s": round(1e6 / us_train, 1), "us_per_image": round(us_train, 2), "images": n_train},
+            "forward_only": {"images_per_s": round(n_train / (ms_f * 1e-3), 1), "us_per_image": round(1e3 * ms_f / n_train, 2)},
+            "weights": net.num_weights,
+            "train_mflop_per_image": round(fl / 1e6, 3), "forward_mflop_per_image": round(fwd_flop(work) / 1e6, 3),
+            "train_bytes_per_image": by,
+            "achieved_tflops": round(fl / (us_train * 1e-6) / 1e12, 4),
+            "achieved_gbs": round(by / (us_train * 1e-6) / 1e9, 2),
+            "bound": bound, "t_at_fp32_peak_us": round(t_f32, 3), "t_at_hbm_peak_us": round(t_hbm, 3),
+            "frac": round(t_bound / us_train, 5),
+            "dependency_bound": dependency_bound(net, mode, info, us_train, floors),
+            "traffic": traffic, "traffic_source": src,
+        }
+        if note:
+            rec["paper_context"] = note
+        if with_cpu and not args.no_cpu_baseline:
+            rec["cpu_baseline"] = oracle_rate(workload, arch, image_shape, n_classes, args.cpu_seconds_per_config,
+                                              imgs=imgs, labs=labs)
+        net.close()
+        nets.remove(net)
+        del d_i, d_l
+        return rec
+
+    # ---- headline: on-line training of the headline workload's stream
+    wl = synth.WORKLOADS[args.headline]
+    n_stream = min(wl.n_images, 60000)
+    imgs = synth.images(wl, n_stream)
+    labs = synth.labels(wl, n_stream)
     d_imgs = torch.from_numpy(imgs).to(dev)
     d_labs = torch.from_numpy(labs).to(dev)
     B = min(args.batch, n_stream)
     per_epoch = n_stream // B
-
-    def make_net(workload, grid=0):
-        net = binding.Cnn(workload.arch)
-        net.set_mode({"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
-                      "stages": binding.MODE_STAGES}[args.mode])
-        if grid:
-            net.set_grid(grid)
-        if args.mode == "resident" and (args.ranks or args.xcd_stride):
-            net.set_team(args.ranks, args.xcd_stride)
-        net.set_weights(synth.weights(workload, net.num_weights))
-        return net
 
     def train_fn(net):
         sz = net.image_size
@@ -174,89 +360,95 @@ def main():
             net.forward_many(d_imgs.view(-1)[o * sz:(o + B) * sz], B)
         return fn
 
-    # ---- headline: on-line training, small cfg2 net
-    net = make_net(wl, args.grid)
-    info = binding.arch_info(wl.arch)
+    net, mode = make_net(wl)
+    info, n_conn, first_w = shapes_of(net)
+    work = layer_work(info, n_conn)
     wall, kernel_ms = time_steps(torch, train_fn(net), args.steps, args.warmup)
     net.synchronize()
-    w_end = net.get_weights()
-    assert np.isfinite(w_end).all(), "training diverged"
+    assert np.isfinite(net.get_weights()).all(), "training diverged"
     value = args.steps * B / wall
     ms_per_step = 1e3 * wall / args.steps
     kern_ms = float(np.mean(kernel_ms))
-    bytes_img = algorithmic_bytes_per_train_image(info, net.num_weights, net.image_size)
+    bytes_img = algorithmic_bytes_per_train_image(info, net.num_weights, net.image_size, first_w)
+    flop_img = train_flop(work)
     achieved = bytes_img * B / (kern_ms * 1e-3) / 1e9
+    traffic, traffic_src = measured_traffic(KERNEL_OF_MODE[mode].split()[0], args.headline, B)
     roofline = {
-        "bound": "hbm", "kernel": KERNEL_OF_MODE[args.mode],
+        "bound": "hbm", "kernel": KERNEL_OF_MODE[mode],
         "achieved": round(achieved, 3), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 6), "traffic": measured_traffic(args.mode, B),
+        "frac": round(achieved / HBM_PEAK_GBS, 6), "traffic": traffic, "traffic_source": traffic_src,
         "algorithmic_bytes_per_image": bytes_img, "images_per_launch": B,
         "launch_ms_mean": round(kern_ms, 4),
-        "flop_per_image": 10.9e6, "achieved_tflops": round(10.9e6 * B / (kern_ms * 1e-3) / 1e12, 4),
+        "flop_per_image": flop_img, "achieved_tflops": round(flop_img * B / (kern_ms * 1e-3) / 1e12, 4),
         "us_per_image": round(1e3 * kern_ms / B, 3),
+        "dependency_bound": dependency_bound(net, mode, info, 1e3 * kern_ms / B, floors),
     }
     out = {
         "metric": "online-training images/sec", "value": round(value, 1), "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "cfg2 small net: %s, 60000 seeded 1x29x29 images U[-1,1], 10 uniform labels, "
-                               "on-line SGD lr=0.001, weights U[-0.05,0.05]" % wl.arch,
-                   "images_per_step": B, "mode": args.mode, "grid": args.grid, "ranks": args.ranks,
+        "config": {"workload": "%s: %s, %d seeded %dx%dx%d images, %d uniform labels, on-line SGD lr=%g, weights "
+                               "U[-0.05,0.05]" % ((args.headline, wl.arch, n_stream) + tuple(wl.raw_shape) + (wl.n_classes, wl.lr)),
+                   "images_per_step": B, "mode": mode, "grid": args.grid, "ranks": args.ranks,
                    "xcd_stride": args.xcd_stride},
         "roofline": roofline,
     }
     net.close()
+    nets.remove(net)
+
+    # ---- every benchmark architecture, each in the mode that runs it
+    if not args.no_per_config:
+        per = []
+        sizes = {"cfg1": 1000, "cfg2a": 4000, "cfg2b": 4000, "cfg3": 1000, "cfg4a": 1000, "cfg4b": 600, "cfg5": 2000}
+        for name in ("cfg1", "cfg2a", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"):
+            w_ = synth.WORKLOADS[name]
+            per.append(measure_config(name, w_.arch, w_, sizes[name]))
+        for name, arch, shape, ncls, note in PAPER_NETS:
+            per.append(measure_config(name, arch, None, 200 if "norb" not in name else 60, shape, ncls, note))
+        out["per_config"] = per
+        out["dependency_floors_us"] = {k: round(v, 3) for k, v in floors.items()}
 
     # ---- the other measurements the workload names
     if not args.no_extra:
         extra = {}
         k_steps = max(3, min(args.steps, 20))
-        net = make_net(wl, args.grid)
-        wall, kms = time_steps(torch, fwd_fn(net), k_steps, 2)
-        net.synchronize()
-        fb = algorithmic_bytes_per_forward_image(info, net.num_weights, net.image_size)
-        extra["cfg2a_forward_only_images_per_s"] = round(k_steps * B / wall, 1)
-        extra["cfg2a_forward_only_hbm_frac"] = round(fb * B / (np.mean(kms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 6)
-        net.close()
-        wlb = synth.WORKLOADS["cfg2b"]
-        infob = binding.arch_info(wlb.arch)
-        net = make_net(wlb, args.grid)
-        wall, kms = time_steps(torch, train_fn(net), k_steps, 2)
-        net.synchronize()
-        tb = algorithmic_bytes_per_train_image(infob, net.num_weights, net.image_size)
-        extra["cfg2b_arch"] = wlb.arch
-        extra["cfg2b_train_images_per_s"] = round(k_steps * B / wall, 1)
-        extra["cfg2b_train_hbm_frac"] = round(tb * B / (np.mean(kms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 6)
-        wall, kms = time_steps(torch, fwd_fn(net), k_steps, 2)
-        net.synchronize()
-        extra["cfg2b_forward_only_images_per_s"] = round(k_steps * B / wall, 1)
-        net.close()
-        # validation / test passes: the whole stream through the batched forward pass (every layer one
-        # matrix product over 4096 images on the matrix cores); timed with events around each call
-        for key, w_, inf in (("cfg2a", wl, info), ("cfg2b", wlb, infob)):
-            net = make_net(w_, args.grid)
+        for key in ("cfg2a", "cfg2b"):
+            w_ = synth.WORKLOADS[key]
+            net, _ = make_net(w_)
             fbatch = 4096
-            scratch = torch.empty(net.forward_batch_scratch_bytes(fbatch), dtype=torch.uint8, device="cuda:0")
-            d_probs = torch.empty(n_stream * net.num_classes, dtype=torch.float32, device="cuda:0")
-            net.forward_batch(d_imgs, n_stream, d_probs, scratch, fbatch)
+            scratch = torch.empty(net.forward_batch_scratch_bytes(fbatch), dtype=torch.uint8, device=dev)
+            d_probs = torch.empty(n_stream * net.num_classes, dtype=torch.float32, device=dev)
+            src = d_imgs if w_.raw_shape == wl.raw_shape else torch.from_numpy(synth.images(w_, n_stream)).to(dev)
+            net.forward_batch(src, n_stream, d_probs, scratch, fbatch)
             net.synchronize()
-            best = None
-            for _ in range(3):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                net.forward_batch(d_imgs, n_stream, d_probs, scratch, fbatch)
-                e1.record()
-                e1.synchronize()
-                ms = e0.elapsed_time(e1)
-                best = ms if best is None else min(best, ms)
+            best = min(event_ms(torch, lambda: net.forward_batch(src, n_stream, d_probs, scratch, fbatch)) for _ in range(3))
             assert torch.isfinite(d_probs).all()
-            tf = forward_flops_per_image(inf) * n_stream / (best * 1e-3) / 1e12
+            inf, nc, _ = shapes_of(net)
+            tf = fwd_flop(layer_work(inf, nc)) * n_stream / (best * 1e-3) / 1e12
             extra[key + "_forward_batch_images_per_s"] = round(n_stream / (best * 1e-3), 1)
             extra[key + "_forward_batch_tflops"] = round(tf, 2)
-            extra[key + "_forward_batch_fp32_mfma_frac"] = round(tf / FP32_MFMA_PEAK_TFLOPS, 4)
+            extra[key + "_forward_batch_fp32_mfma_frac"] = round(tf / FP32_PEAK_TFLOPS, 4)
             del scratch, d_probs
             net.close()
+            nets.remove(net)
+        for key, fb_o in (("cfg3", 512), ("cfg4a", 512), ("cfg4b", 256), ("cfg5", 1024)):
+            wo = synth.WORKLOADS[key]
+            net, _ = make_net(wo)
+            n_b = 2 * fb_o
+            ib = torch.from_numpy(synth.images(wo, n_b)).to(dev)
+            scratch = torch.empty(net.forward_batch_scratch_bytes(fb_o), dtype=torch.uint8, device=dev)
+            pb = torch.empty(n_b * net.num_classes, dtype=torch.float32, device=dev)
+            net.forward_batch(ib, n_b, pb, scratch, fb_o)
+            net.synchronize()
+            ms = event_ms(torch, lambda: net.forward_batch(ib, n_b, pb, scratch, fb_o))
+            inf, nc, _ = shapes_of(net)
+            extra[key + "_forward_batch_images_per_s"] = round(n_b / (ms * 1e-3), 1)
+            extra[key + "_forward_batch_fp32_mfma_frac"] = round(
+                fwd_flop(layer_work(inf, nc)) * n_b / (ms * 1e-3) / 1e12 / FP32_PEAK_TFLOPS, 4)
+            net.close()
+            nets.remove(net)
+            del ib, scratch, pb
         # on-line deformation of the training stream (Sec. 4.1): the whole stream in one call, then training with
         # every launch's images deformed just ahead of it on the same stream
         gp = binding.DeformParams(**synth.DEFORM_RECIPE)
@@ -264,72 +456,24 @@ def main():
         d_def = torch.empty_like(d_src4)
         binding.deform_images(d_src4, d_def, n_stream, gp, synth.DEFORM_SEED, 0)
         torch.cuda.synchronize()
-        best = None
-        for r in range(5):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            binding.deform_images(d_src4, d_def, n_stream, gp, synth.DEFORM_SEED, (r + 1) * n_stream)
-            e1.record()
-            e1.synchronize()
-            ms = e0.elapsed_time(e1)
-            best = ms if best is None else min(best, ms)
+        best = min(event_ms(torch, lambda r=r: binding.deform_images(d_src4, d_def, n_stream, gp, synth.DEFORM_SEED,
+                                                                     (r + 1) * n_stream)) for r in range(5))
         assert torch.isfinite(d_def).all()
-        extra["cfg2a_deform_images_per_s"] = round(n_stream / (best * 1e-3), 1)
-        extra["cfg2a_deform_hbm_frac"] = round(2 * 4 * int(np.prod(wl.raw_shape)) * n_stream / (best * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-        net = make_net(wl, args.grid)
-        sz = net.image_size
+        extra["%s_deform_images_per_s" % args.headline] = round(n_stream / (best * 1e-3), 1)
+        extra["%s_deform_hbm_frac" % args.headline] = round(
+            2 * 4 * int(np.prod(wl.raw_shape)) * n_stream / (best * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        net, _ = make_net(wl)
         buf = torch.empty((B,) + tuple(wl.raw_shape), dtype=torch.float32, device=dev)
 
         def deformed_step(k):
             o = (k % per_epoch) * B
             binding.deform_images(d_src4[o:o + B], buf, B, gp, synth.DEFORM_SEED, k * B)
             net.train_many(buf.view(-1), d_labs[o:o + B], wl.lr, n=B)
-        wall, kms = time_steps(torch, deformed_step, k_steps, 2)
-        extra["cfg2a_train_with_deformation_images_per_s"] = round(k_steps * B / wall, 1)
-        net.close()
+        wall, _ = time_steps(torch, deformed_step, k_steps, 2)
+        extra["%s_train_with_deformation_images_per_s" % args.headline] = round(k_steps * B / wall, 1)
         del d_def, buf
-        # the other benchmark networks, each in the mode that runs it fastest: on-line training of 400 seeded
-        # images (one launch per stage: wide layers on the matrix cores; cfg5 fits the resident kernel)
-        for key, mode_o in (("cfg3", binding.MODE_STAGES), ("cfg4a", binding.MODE_STAGES),
-                            ("cfg4b", binding.MODE_STAGES), ("cfg5", binding.MODE_RESIDENT)):
-            wo = synth.WORKLOADS[key]
-            n_o = 400
-            io, lo = synth.images(wo, n_o), synth.labels(wo, n_o)
-            d_io, d_lo = torch.from_numpy(io).to(dev), torch.from_numpy(lo).to(dev)
-            net = synth.build_network(binding.Cnn(wo.arch), wo)
-            net.set_mode(mode_o)
-            net.train_many(d_io, d_lo, wo.lr, n=50)
-            net.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            net.train_many(d_io, d_lo, wo.lr)
-            e1.record()
-            e1.synchronize()
-            extra[key + "_train_images_per_s"] = round(n_o / (e0.elapsed_time(e1) * 1e-3), 1)
-            # forward only: one image at a time in the same mode, and every layer a matrix product over the batch
-            net.forward_many(d_io, 50)
-            net.synchronize()
-            e0.record()
-            net.forward_many(d_io, n_o)
-            e1.record()
-            e1.synchronize()
-            extra[key + "_forward_only_images_per_s"] = round(n_o / (e0.elapsed_time(e1) * 1e-3), 1)
-            fb_o = {"cfg3": 512, "cfg4a": 512, "cfg4b": 256, "cfg5": 1024}[key]
-            n_b = 2 * fb_o
-            ib = torch.from_numpy(synth.images(wo, n_b)).to(dev)
-            scratch = torch.empty(net.forward_batch_scratch_bytes(fb_o), dtype=torch.uint8, device=dev)
-            pb = torch.empty(n_b * net.num_classes, dtype=torch.float32, device=dev)
-            net.forward_batch(ib, n_b, pb, scratch, fb_o)
-            net.synchronize()
-            e0.record()
-            net.forward_batch(ib, n_b, pb, scratch, fb_o)
-            e1.record()
-            e1.synchronize()
-            extra[key + "_forward_batch_images_per_s"] = round(n_b / (e0.elapsed_time(e1) * 1e-3), 1)
-            net.close()
-            del d_io, d_lo, ib, scratch, pb
         # launch cost: the same images through one cnn_train_step call each
-        net = make_net(wl, args.grid)
+        net.set_weights(synth.weights(wl, net.num_weights))
         sz = net.image_size
         lab_host = labs[:B].tolist()
         nstep = min(B, 500)
@@ -338,17 +482,17 @@ def main():
         for t in range(nstep):
             net.train_step(d_imgs.view(-1)[t * sz:(t + 1) * sz], lab_host[t], wl.lr)
         torch.cuda.synchronize()
-        extra["cfg2a_train_step_calls_images_per_s"] = round(nstep / (time.perf_counter() - t0), 1)
+        extra["%s_train_step_calls_images_per_s" % args.headline] = round(nstep / (time.perf_counter() - t0), 1)
         net.close()
+        nets.remove(net)
         out["extra"] = extra
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores
     if not args.no_cpu_baseline:
         import oracle
         cores = oracle.set_threads(0)
-        ref = oracle.Oracle(wl.arch, 32)
-        ref.set_weights(synth.weights(wl, ref.num_weights))
-        probe = 200
+        ref = synth.build_network(oracle.Oracle(wl.arch, 32), wl)
+        probe = 200 if wl.name.startswith(("cfg1", "cfg2", "cfg5")) else 4
         t0 = time.perf_counter()
         ref.train_many(imgs[:probe], labs[:probe], wl.lr)
         rate = probe / (time.perf_counter() - t0)
@@ -360,13 +504,17 @@ def main():
             "value": round(n / dt, 1), "unit": "images/s", "cores": cores, "kind": "oracle",
             "sample": "images %d..%d of the same stream, float32 instantiation of the oracle, "
                       "OpenMP over output maps, %.1f s" % (probe, probe + n, dt)}
-        # the same oracle on one thread (the paper's own baseline was one optimised CPU thread), 300 images
+        # the same oracle on one thread (the paper's own baseline was one optimised CPU thread)
         oracle.set_threads(1)
+        n1 = max(2, min(300, int(rate / max(cores, 1) * 2)))
         t0 = time.perf_counter()
-        ref.train_many(imgs[:300], labs[:300], wl.lr)
-        out["cpu_baseline"]["single_thread_images_per_s"] = round(300 / (time.perf_counter() - t0), 1)
+        ref.train_many(imgs[:n1], labs[:n1], wl.lr)
+        out["cpu_baseline"]["single_thread_images_per_s"] = round(n1 / (time.perf_counter() - t0), 1)
         oracle.set_threads(0)
+    for net in list(nets):
+        net.close()
     print(json.dumps(out))
+    sys.stdout.flush()
 
 
 if __name__ == "__main__":

@@ -282,6 +282,18 @@ int cnn_get_loss(cnn_t* net, float* host_loss);
  * forward-only call); *n_stages gets the stage count.  Synchronises. */
 int cnn_get_stage_times(cnn_t* net, float* host_us, int max_stages, int* n_stages);
 
+/* Measurement aids for the bound that caps a chain of dependent stages (one image at a time, every layer
+ * waits for the one before): what one crossing between compute units costs, and what one kernel launch costs,
+ * on this device, now.
+ *   cnn_measure_crossing: n_ranks workgroups (2 .. one per compute unit) each store words_per_rank tagged words
+ *     and fetch those of all ranks -- the exchange of the resident mode between two layers -- `rounds` times in
+ *     one cooperative launch; *host_us = microseconds per round (device clock of rank 0).  Uses the network's
+ *     exchange buffers (CNN_E_WORKSPACE if they are too small for the request).  Synchronises.
+ *   cnn_measure_launch: `rounds` launches of an empty kernel back to back on the handle's stream, timed with
+ *     events; *host_us = microseconds per launch: the floor under every stage of CNN_MODE_STAGES.  Synchronises. */
+int cnn_measure_crossing(cnn_t* net, int n_ranks, int words_per_rank, int rounds, float* host_us);
+int cnn_measure_launch(cnn_t* net, int rounds, float* host_us);
+
 /* Forward + backward for (d_image, label) with the update replaced by a store of dE/dw:
  * host_grad receives cnn_num_weights floats in canonical order; weights are unchanged. */
 int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad);

@@ -78,6 +78,8 @@ def lib():
             "cnn_get_loss": (C.c_int, [vp, vp]),
             "cnn_debug_gradients": (C.c_int, [vp, vp, i32, vp]),
             "cnn_get_stage_times": (C.c_int, [vp, vp, C.c_int, vp]),
+            "cnn_measure_crossing": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, vp]),
+            "cnn_measure_launch": (C.c_int, [vp, C.c_int, vp]),
             "cnn_last_error": (C.c_char_p, [vp]),
         }
         for name, (res, args) in sig.items():
@@ -97,7 +99,7 @@ EXPORTS = ["cnn_arch_info", "cnn_arch_info_xy", "cnn_workspace_bytes", "cnn_plan
            "cnn_forward_batch_scratch_bytes", "cnn_forward_batch", "cnn_forward_batch_static", "cnn_set_mode",
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
            "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
-           "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times",
+           "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times", "cnn_measure_crossing", "cnn_measure_launch",
            "cnn_deform_images", "cnn_last_error"]
 
 
@@ -361,6 +363,19 @@ class Cnn:
         self._ck(lib().cnn_forward_batch(self._h, d_images.data_ptr(), int(n), p, d_scratch.data_ptr(),
                                          d_scratch.numel(), int(batch)), "cnn_forward_batch")
 
+    def measure_crossing(self, n_ranks, words_per_rank, rounds=200):
+        """Microseconds one exchange of words_per_rank tagged words per rank among n_ranks workgroups takes."""
+        us = C.c_float(0)
+        self._ck(lib().cnn_measure_crossing(self._h, int(n_ranks), int(words_per_rank), int(rounds), C.byref(us)),
+                 "cnn_measure_crossing")
+        return us.value
+
+    def measure_launch(self, rounds=500):
+        """Microseconds per launch of an empty kernel, back to back on the handle's stream."""
+        us = C.c_float(0)
+        self._ck(lib().cnn_measure_launch(self._h, int(rounds), C.byref(us)), "cnn_measure_launch")
+        return us.value
+
     def forward_batch_static(self, d_images, n, d_probs, batch):
         """forward_batch with the scratch memory taken from the library's own device array (at most
         FORWARD_BATCH_STATIC_SCRATCH_BYTES): nothing is allocated anywhere."""
@@ -409,6 +424,13 @@ class Cnn:
     def resident_static_id(self):
         """Development aid: which compiled-in network the resident plan equals (0: none)."""
         f = lib().cnn355_resident_static_id
+        f.restype = C.c_int
+        f.argtypes = [C.c_void_p]
+        return int(f(self._h))
+
+    def resident_ranks(self):
+        """Development aid: workgroups in the resident plan's team (0: the network cannot run in resident mode)."""
+        f = lib().cnn355_resident_ranks
         f.restype = C.c_int
         f.argtypes = [C.c_void_p]
         return int(f(self._h))

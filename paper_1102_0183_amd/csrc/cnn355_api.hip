@@ -28,6 +28,9 @@ int persistent_max_blocks_per_cu();
 void read_dbg(unsigned long long* out);
 hipError_t launch_frontend_batch(hipStream_t stream, const ProgramDev* d_prog, const float* d_images,
                                  long long image_stride, int n_images, int items_per_image, float* d_out);
+hipError_t launch_crossing_probe(int G, int stride, hipStream_t stream, tagged_t* buf, int words, int rounds,
+                                 unsigned int epoch_base, unsigned int spin_limit, StatusDev* d_status);
+hipError_t launch_empty(hipStream_t stream, StatusDev* d_status);
 hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec& spec,
                            const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a);
 int resident_static_id(const FlowSpec& z);
@@ -1354,6 +1357,8 @@ int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
 
 // development aid, not part of the public header: which compiled-in network the resident plan equals (0: none)
 int cnn355_resident_static_id(const cnn_t* net) { return net ? net->flow_static_id : -1; }
+// development aid: workgroups in the resident plan's team (0 when the network cannot run in resident mode)
+int cnn355_resident_ranks(const cnn_t* net) { return (net && net->flow_ok) ? net->flow.G : 0; }
 // development aid, host only (no device is touched): the resident plan of an architecture as text.  fan_in > 0
 // gives every convolutional layer above the first a table in which output map j reads the input maps
 // j, j + 1, ..., j + fan_in - 1 (mod M_i).  One line per number ("name value"), per layer ("conv l name value ...")
@@ -1627,6 +1632,51 @@ int cnn355_read_status_stamps(cnn_t* net, unsigned long long* out, int n) {
   StatusDev s;
   HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
   for (int i = 0; i < n && i < 2 * MAX_STAGES + 2; ++i) out[i] = s.stamps[i];
+  return CNN_OK;
+}
+
+int cnn_measure_crossing(cnn_t* net, int n_ranks, int words_per_rank, int rounds, float* host_us) {
+  if (!net || !host_us) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (!net->coop_ok) return fail(&net->err, CNN_E_STATE, "device does not support cooperative launches");
+  if (n_ranks < 2 || n_ranks > net->n_cu || words_per_rank < 1 || rounds < 1 || rounds > (1 << 20))
+    return fail(&net->err, CNN_E_ARG, "cnn_measure_crossing: 2 to one rank per compute unit, at least one word and one round");
+  if (2ull * n_ranks * words_per_rank > net->xbuf_words)
+    return fail(&net->err, CNN_E_WORKSPACE, "cnn_measure_crossing: the network's exchange buffers hold " +
+                std::to_string(net->xbuf_words / 2 / n_ranks) + " words per rank for this many ranks");
+  const unsigned long long n = (unsigned long long)rounds + 1;
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  if (((net->epoch + n) >> 32) != (net->epoch >> 32)) {
+    net->epoch = ((net->epoch >> 32) + 1) << 32;
+    HIP_TRY(net, hipMemset(net->d_xbuf, 0, net->xbuf_words * sizeof(tagged_t)));
+  }
+  HIP_TRY(net, launch_reset_status(net->stream, net->d_status, 0));
+  const int stride = (n_ranks <= net->n_cu / 8) ? 8 : 1;
+  HIP_TRY(net, launch_crossing_probe(n_ranks, stride, net->stream, net->d_xbuf, words_per_rank, rounds,
+                                     (unsigned int)net->epoch, net->spin_limit, net->d_status));
+  net->epoch += n;
+  int rc = sync_and_check(net);
+  if (rc) return rc;
+  StatusDev s;
+  HIP_TRY(net, hipMemcpy(&s, net->d_status, sizeof(s), hipMemcpyDeviceToHost));
+  *host_us = (float)((double)(s.stamps[1] - s.stamps[0]) * 0.01 / rounds);
+  return CNN_OK;
+}
+
+int cnn_measure_launch(cnn_t* net, int rounds, float* host_us) {
+  if (!net || !host_us || rounds < 1) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument or no rounds");
+  hipEvent_t e0, e1;
+  HIP_TRY(net, hipEventCreate(&e0));
+  HIP_TRY(net, hipEventCreate(&e1));
+  for (int k = 0; k < 20; ++k) HIP_TRY(net, launch_empty(net->stream, net->d_status));
+  HIP_TRY(net, hipEventRecord(e0, net->stream));
+  for (int k = 0; k < rounds; ++k) HIP_TRY(net, launch_empty(net->stream, net->d_status));
+  HIP_TRY(net, hipEventRecord(e1, net->stream));
+  HIP_TRY(net, hipEventSynchronize(e1));
+  float ms = 0.f;
+  HIP_TRY(net, hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  *host_us = ms * 1e3f / (float)rounds;
   return CNN_OK;
 }
 

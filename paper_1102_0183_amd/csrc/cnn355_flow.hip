@@ -1614,6 +1614,54 @@ hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_
   }
 }
 
+// ---- measurement aids: what one crossing between compute units, and one kernel launch, cost ------------
+// One round = every rank stores `words` tagged words and then fetches the words of all G ranks (the exchange
+// the resident kernel does between layers), `rounds` times; rank 0 stamps the clock before the first round
+// after a warm-up round and after the last.
+__global__ void __launch_bounds__(WG) k_crossing_probe(tagged_t* buf_, int G, int stride, int words, int rounds,
+                                                       unsigned int epoch_base, unsigned int spin_limit,
+                                                       StatusDev* status) {
+  __shared__ Shared sh;
+  gtagged* buf = (gtagged*)buf_;
+  if (blockIdx.x % stride != 0 || (int)(blockIdx.x / stride) >= G) return;
+  const int rank = blockIdx.x / stride, tid = threadIdx.x;
+  if (tid == 0) sh.fail = 0;
+  __syncthreads();
+  Rt rt;
+  rt.dbg = false; rt.spec = nullptr; rt.sh = &sh; rt.status = status; rt.lds = nullptr; rt.rank = rank;
+  rt.spin_limit = spin_limit;
+  const int n = G * words;
+  unsigned int acc = 0;
+  for (int e = 0; e <= rounds; ++e) {
+    if (e == 1 && rank == 0 && tid == 0) status->stamps[0] = wall_clock64();
+    const unsigned int tag = epoch_base + (unsigned int)e + 1u;
+    gtagged* b = buf + (size_t)(tag & 1u) * n;
+    for (int x = tid; x < words; x += WG) put_f(b + (size_t)rank * words + x, (float)x, tag);
+    for (int base = 0; base < n; base += 4 * WG) {
+      tagged_t w[4];
+      if (!fetch_tagged<4>(rt, w, tag, [&](int u) { return b + min(base + tid + u * WG, n - 1); })) break;
+      acc += (unsigned int)w[0] ^ (unsigned int)w[3];
+    }
+    __syncthreads();
+    if (sh.fail) return;
+  }
+  if (rank == 0 && tid == 0) status->stamps[1] = wall_clock64();
+  if (acc == 0x12345u) status->stamps[2] = acc;
+}
+hipError_t launch_crossing_probe(int G, int stride, hipStream_t stream, tagged_t* buf, int words, int rounds,
+                                 unsigned int epoch_base, unsigned int spin_limit, StatusDev* d_status) {
+  void* params[] = {(void*)&buf, (void*)&G, (void*)&stride, (void*)&words, (void*)&rounds, (void*)&epoch_base,
+                    (void*)&spin_limit, (void*)&d_status};
+  return hipLaunchCooperativeKernel((const void*)k_crossing_probe, dim3(G * stride), dim3(WG), params, 0, stream);
+}
+__global__ void k_empty(StatusDev* status) {
+  if (status == nullptr) __builtin_trap();
+}
+hipError_t launch_empty(hipStream_t stream, StatusDev* d_status) {
+  hipLaunchKernelGGL(k_empty, dim3(1), dim3(64), 0, stream, d_status);
+  return hipGetLastError();
+}
+
 // which compiled-in network, if any, has exactly this plan
 int resident_static_id(const FlowSpec& z) {
   if (__builtin_memcmp(&z, &StaticSpec<1>::value, sizeof(FlowSpec)) == 0) return 1;

@@ -2,7 +2,7 @@
 """Per-stage time, algorithmic work and fraction of the fp32 / HBM roofline of one on-line
 training step, for every workload, as a markdown table on stdout.
 
-    python3 paper_1102_0183_amd/per_layer_report.py > per_layer.md
+    python3 per_layer_report.py > per_layer.md
 
 Times are the device-side stage timers of CNN_MODE_PERSISTENT (microseconds workgroup 0 spends
 on a stage's work items in the last image of a call; best of five calls of 64 images).  Work is
@@ -15,7 +15,7 @@ import os
 import re
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 import numpy as np

@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Small driver to put under rocprofv3: trains a few on-line calls of one synthetic workload.
 
-    python3 paper_1102_0183_amd/probe.py --workload cfg4b --mode stages --images 200 --calls 1
-    python3 paper_1102_0183_amd/probe.py --workload cfg2a --mode resident --images 1000 --calls 3 --copy-calibration
-    python3 paper_1102_0183_amd/probe.py --workload cfg2a --forward --batch 4096 --images 16384 --calls 3
-    python3 paper_1102_0183_amd/probe.py --workload cfg2a --deform --images 60000 --calls 5
+    python3 probe.py --workload cfg4b --mode stages --images 200 --calls 1
+    python3 probe.py --workload cfg2a --mode resident --images 1000 --calls 3 --copy-calibration
+    python3 probe.py --workload cfg2a --forward --batch 4096 --images 16384 --calls 3
+    python3 probe.py --workload cfg2a --deform --images 60000 --calls 5
 
 --copy-calibration first runs a 256 MiB device-to-device copy three times, so that a counter
 collected in the same run (FETCH_SIZE, WRITE_SIZE) can be scaled by what it reads for a
@@ -14,7 +14,7 @@ import argparse
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
