@@ -16,7 +16,11 @@ HEADERS = [os.path.join(CSRC, "cnn355_dev.h"), os.path.join(CSRC, "cnn355_flowsp
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-FP32 instructions are switched off on purpose: some of their forms have given wrong
 # results on this hardware, without any error
+# (the resident kernel takes its plan as a by-value kernel argument; the optimiser turns the copy of it that the
+# language semantics ask for back into scalar loads of the argument only if it can look at every use, and gives
+# up beyond 300 of them: the plan has more, and would otherwise be copied to scratch memory and read from there)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+         "-mllvm", "-instcombine-max-copied-from-constant-users=100000",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-pass-failed"]
 
 

@@ -321,6 +321,7 @@ size_t carve(cnn* net, void* base) {
         const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : (size_t)A[l].maps * A[l].h * A[l].w;
         words += 3 * 2 * small;  // pooled outputs, deltas, winner coordinates; two images in flight
         words += 2 * 256 * (small / A[l].maps);  // pulled sums of the shares of a map's pull (fewer than 256 of them)
+        words += 2 * (size_t)A[l].maps * A[l - 1].maps * A[l].K * A[l].Kx;  // adjusted filters on their way to the forward copies
         last_maps = A[l].maps;
       } else if (A[l].kind == CNN_LAYER_FC && !first_fc) {
         first_fc = A[l].maps;
@@ -816,6 +817,7 @@ void plan_flow(cnn* net) {
     C.x_yx = (l >= 1) ? xtake(2 * small) : nullptr;
     C.x_part = (l >= 1 && Z.conv[l].pull_shares > 1)
                    ? xtake((size_t)2 * L.Mi * (Z.conv[l].pull_shares - 1) * L.Hi * L.Wi) : nullptr;
+    C.x_w = (l >= 1 && Z.stream) ? xtake((size_t)2 * net->host_tables[l].csr_idx.size() * L.K * L.K) : nullptr;
   }
   for (int f = 0; f < n_fc; ++f) {
     const LayerDev& L = P.layers[n_conv + f];
@@ -1392,6 +1394,7 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
     num("G", Z.G); num("stride", Z.stride); num("n_conv", Z.n_conv); num("n_fc", Z.n_fc);
     num("n_col_ranks", Z.n_col_ranks); num("lds_floats", Z.lds_floats); num("lds_floats_max", FLOW_LDS_FLOATS_MAX);
     num("scratch_floats", Z.scratch_floats); num("defer", Z.defer); num("static_id", tmp.flow_static_id);
+    num("stream", Z.stream);
     num("workgroup", WG); num("share_min_macs", FLOW_SHARE_MIN_MACS);
     auto region = [&](const std::string& name, long long off, long long floats) {
       t += "region " + name + " " + std::to_string(off) + " " + std::to_string(floats) + "\n";
@@ -1408,10 +1411,10 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
           {"full_table", C.full_table}, {"n_own", C.n_own}, {"n_own_below", C.n_own_below},
           {"pull_shares", C.pull_shares}, {"back_pitch", C.back_pitch}, {"wgrad_R_log2", C.wgrad_R_log2},
           {"pull_chunk", C.pull_chunk}, {"fwd_strip", C.fwd_strip}, {"fwd_rows", C.fwd_rows},
-          {"pull_strip", C.pull_strip}, {"pull_rows", C.pull_rows}};
+          {"pull_strip", C.pull_strip}, {"pull_rows", C.pull_rows}, {"in_chunk", C.in_chunk}};
       for (const auto& kv : f) t += std::string(" ") + kv.first + " " + std::to_string(kv.second);
       t += "\n";
-      region(c + "in", C.o_in, (long long)C.Mi * C.Hi * C.Wi);
+      if (!(Z.stream && l >= 1)) region(c + "in", C.o_in, (long long)C.Mi * C.Hi * C.Wi);
       region(c + "wf", C.o_wf, (long long)C.n_own * C.max_conn * KK);
       region(c + "bf", C.o_bf, C.n_own);
       region(c + "cidx", C.o_cidx, (long long)C.n_own * C.max_conn);
@@ -1443,7 +1446,7 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
     }
     region("act", Z.o_act, act);
     // (the partial sums reach up to the next region: what they need is for the reader to work out)
-    region("part", Z.o_part, Z.o_dall - Z.o_part);
+    if (!Z.stream) region("part", Z.o_part, Z.o_dall - Z.o_part);
     if (Z.n_conv > 1) {
       region("dall", Z.o_dall, dall);
       region("yxall", Z.o_yxall, dall);

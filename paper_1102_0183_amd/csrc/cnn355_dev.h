@@ -188,6 +188,8 @@ struct FlowConvPtrs {
   CNN_GLOBAL tagged_t* x_delta;  // [2][Mo*Hp*Wp] deltas at the winners (layers above the first)
   CNN_GLOBAL tagged_t* x_yx;     // [2][Mo*Hp*Wp] their coordinates
   CNN_GLOBAL tagged_t* x_part;   // [2][Mi][shares - 1][Hi*Wi] pulled sums of the shares beyond the first, for the map's owner
+  CNN_GLOBAL tagged_t* x_w;      // [2][connections * K*K] streamed plans: the filters as their pull-copy holders have just
+                                 //   adjusted them, in table order, for the holders of the forward copies
   long long w_canon, b_canon;    // offsets in the canonical weight vector (gradient tap)
 };
 struct FlowFcPtrs {

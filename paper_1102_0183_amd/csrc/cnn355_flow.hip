@@ -337,6 +337,46 @@ __device__ __forceinline__ bool gather2(const Rt& rt, unsigned int* dst_a, const
   return rt.sh->fail == 0;
 }
 
+// ---- bulk exchange (streamed plans) -----------------------------------------------------------------
+// The pooled maps a wide layer hands to the next are too many words to poll one by one, twice over.  In a
+// streamed plan they travel as plain floats, written through to device scope, plus one flag word per map that
+// its owner sets to the image's tag once the stores have completed; a reader polls the flags of the maps it is
+// about to fetch and then loads their floats 128 bits at a time, past the caches.  Layout inside the layer's
+// exchange area of 2 N tagged words (N = Mo Hp Wp): floats [2][N], then flags [2][Mo].
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+typedef CNN_GLOBAL unsigned int guint;
+__device__ __forceinline__ gfloat* bulk_data(gtagged* x, int N, unsigned int par) { return (gfloat*)x + (size_t)par * N; }
+__device__ __forceinline__ guint* bulk_flags(gtagged* x, int N, int Mo, unsigned int par) {
+  return (guint*)((gfloat*)x + 2 * (size_t)N) + (size_t)par * Mo;
+}
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// n floats at `data` (whose n_flags maps' flags must carry `tag`) -> dst (16-byte aligned LDS, may be written up to
+// 3 floats past n).  Ends with a workgroup barrier; false: a wait gave up.
+__device__ __forceinline__ bool gather_bulk(const Rt& rt, float* dst, const gfloat* data, int n, const guint* flags,
+                                            int n_flags, unsigned int tag) {
+  const int tid = threadIdx.x;
+  for (int m = tid; m < n_flags; m += WG) {
+    unsigned int spins = 0;
+    while (__hip_atomic_load(flags + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tag)
+      if (!poll_again(rt, spins)) break;
+  }
+  __syncthreads();
+  if (rt.sh->fail) return false;
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)data, 0, n * 4, 0x00020000);
+  constexpr int U = 4;
+  for (int base = tid * 4; base < n; base += U * WG * 4) {
+    u4v v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)   // (a load past n floats returns zeros: the buffer descriptor bounds it)
+      v[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, (base + u * WG * 4) * 4, 0, 16 /* device scope */);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (base + u * WG * 4 < n) *(u4v*)(dst + base + u * WG * 4) = v[u];
+  }
+  __syncthreads();
+  return true;
+}
+
 // ---- weights: global (canonical order) <-> LDS -------------------------------------------------
 template <int ID>
 __device__ __forceinline__ void flow_load(const Rt& rt) {
@@ -563,7 +603,7 @@ __device__ __forceinline__ JobStat fwd_job(const FlowSpec& Z, int l) {
   JobStat S;
   S.in = C.o_in; S.w = C.o_wf; S.idx = C.o_cidx; S.cnt = C.o_ncf;
   S.w_pitch = C.max_conn; S.Ho = C.Ho; S.Wo = C.Wo; S.K = C.K; S.stride = C.S + 1;
-  S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = C.max_conn; S.plan_cnt = C.max_conn;
+  S.map_sz = C.Hi * C.Wi; S.Wi = C.Wi; S.max_cnt = min(C.max_conn, C.in_chunk); S.plan_cnt = C.max_conn;
   S.variant = C.fwd_strip ? C.S * 128 + (C.fwd_rows - 1) * 64 + C.fwd_strip * 8 + C.K : 0;
   S.table = C.o_tab_fwd;
   S.band_lo = 0; S.band_hi = C.Hi; S.ways_side_by_side = 0;
@@ -708,8 +748,10 @@ __device__ __forceinline__ void job_mac(const JobStat& S, int R, const float* ld
 }
 
 // ---- FP of the own maps of one layer (Sec. 2.2, Sec. 3.2) ------------------------------------------
+// src: the exchange area of the layer below when the plan streams this layer's inputs (they are then fetched
+// chunk by chunk of in_chunk maps into the arena); else null: the inputs are in LDS already.  False: a wait gave up.
 template <int ID>
-__device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
+__device__ __forceinline__ bool flow_conv_fwd(const Rt& rt, int l, gtagged* src, unsigned int tag) {
   DECL_SPEC(Z, rt);
   const ConvSpec& C = Z.conv[l];
   float* lds = rt.lds;
@@ -721,15 +763,48 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
   const float* bf = lds + C.o_bf;
   const int* cnt = (const int*)(lds + S.cnt);
   const int Pn = S.Ho * S.Wo, tot = nm * Pn;
+  const bool stream = Z.stream != 0 && src != nullptr;
+  bool ok = true;
   job_dispatch<true>(S.variant, [&](auto k_, auto sw_, auto th_, auto st_) {
     constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value, ST = decltype(st_)::value;
-    for (int pass = 0; pass < D.passes; ++pass) {
+    for (int pass = 0; pass < D.passes && ok; ++pass) {
       const Lane ln = lane_get(S, D, lds, pass);
       float acc[TH * SW];
 #pragma unroll
       for (int i = 0; i < TH * SW; ++i) acc[i] = 0.f;
-      if (ln.on) {
+      if (stream) {
+        const int Mi = C.Mi, chunk = C.in_chunk, full = C.full_table;
+        int e_next = 0;
+        if (l == 1) DSTAMP(100);
+        for (int i0 = 0; i0 < Mi; i0 += chunk) {
+          const int n = min(chunk, Mi - i0);
+          if (i0 > 0 || pass > 0) __syncthreads();  // the chunk before has been read by everybody
+          if (!gather_bulk(rt, lds + S.in, bulk_data(src, Mi * S.map_sz, tag & 1u) + (size_t)i0 * S.map_sz, n * S.map_sz,
+                           bulk_flags(src, Mi * S.map_sz, Mi, tag & 1u) + i0, n, tag)) { ok = false; break; }
+          if (l == 1 && i0 / chunk < 4) DSTAMP(101 + 2 * (i0 / chunk));
+          if (ln.on) {
+            // connections of the lane's map whose input map lies in [i0, i0 + n): the list is sorted
+            int e_lo = i0, e_hi = i0 + n;
+            if (!full) {
+              const int* ci = (const int*)(lds + S.idx) + ln.am * S.w_pitch;
+              e_lo = e_next;
+              int lo = e_lo, hi = cnt[ln.am];
+              while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (ci[mid] < i0 + n) lo = mid + 1; else hi = mid;
+              }
+              e_hi = lo;
+              e_next = e_hi;
+            }
+            job_mac<K, SW, TH, false, ST>(S, D.R, lds, ln, e_lo, e_hi, i0, acc);
+          }
+          if (l == 1 && i0 / chunk < 4) DSTAMP(102 + 2 * (i0 / chunk));
+        }
+      } else if (ln.on) {
         job_mac<K, SW, TH, false, ST>(S, D.R, lds, ln, 0, cnt[ln.am], 0, acc);
+      }
+      if (Z.stream != 0 && D.R > 1) __syncthreads();  // the partial sums go where the last chunk of maps lies
+      if (ln.on && ok) {
         if (D.R == 1) {  // unsplit: the finished sums (the activation function is applied where they are pooled)
           const float b = bf[ln.am];
           float* dst = act + ln.am * Pn + ln.pix;
@@ -750,11 +825,15 @@ __device__ __forceinline__ void flow_conv_fwd(const Rt& rt, int l) {
     }
   });
   __syncthreads();
+  if (l == 1) DSTAMP(110);
+  if (!ok || rt.sh->fail) return false;
   if (D.R > 1) {
     const FDiv dP(Pn);
     reduce_partials(part, D.R, tot, [&](int p, float s) { act[p] = s + bf[dP.div(p)]; });
     __syncthreads();
   }
+  if (l == 1) DSTAMP(111);
+  return true;
 }
 
 // Max-pooling of the own maps (Sec. 2.3): value and position of the first maximum in row-major
@@ -771,31 +850,37 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
   float* pool = lds + C.o_pool;
   float* dact = lds + C.o_dact;
   int* yx = (int*)(lds + C.o_yx);
-  gtagged* xo = C.has_x_out ? P.x_out + (size_t)(tag & 1u) * C.Mo * HW : nullptr;
+  const bool bulk = Z.stream != 0 && C.has_x_out;   // (the next layer streams its inputs)
+  gtagged* xo = (C.has_x_out && !bulk) ? P.x_out + (size_t)(tag & 1u) * C.Mo * HW : nullptr;
+  gfloat* xb = bulk ? bulk_data(P.x_out, C.Mo * HW, tag & 1u) : nullptr;
   const FDiv dHW(HW), dWp(Wp);
+  // the outputs of the own maps, every lane its share (the partial sums' area is free by now and at least as
+  // large): the maximum below is taken over them -- they are what the parity taps show -- and the winner's
+  // derivative from the sum it received
+  float* yout = lds + Z.o_part;
+  for (int x = tid; x < nm * Pn; x += WG) yout[x] = f_act(act[x]);
+  __syncthreads();
   for (int x = tid; x < nm * HW; x += WG) {
     const int am = dHW.div(x), q = x - am * HW;
     const int py = dWp.div(q), px = q - py * Wp;
-    const float* win = act + am * Pn + py * Kp * Wo + px * Kp;
-    // the maximum is taken over the outputs (what the parity taps show), and the winner's derivative
-    // from the sum it received
-    float best_a = win[0];
-    float best = f_act(best_a);
+    const int w0 = am * Pn + py * Kp * Wo + px * Kp;
+    const float* win = yout + w0;
+    float best = win[0];
     int wy = 0, wx = 0;
 #pragma unroll 4
     for (int dy = 0; dy < Kp; ++dy)
 #pragma unroll 4
       for (int dx = 0; dx < Kp; ++dx) {
-        const float av = win[dy * Wo + dx];
-        const float v = f_act(av);
-        if (v > best) { best = v; best_a = av; wy = dy; wx = dx; }
+        const float v = win[dy * Wo + dx];
+        if (v > best) { best = v; wy = dy; wx = dx; }
       }
     const int code = ((py * Kp + wy) << 16) | (px * Kp + wx);
     pool[x] = best;
-    dact[x] = f_dact_pre(best_a);
+    dact[x] = f_dact_pre(act[w0 + wy * Wo + wx]);
     yx[x] = code;
     const size_t o = (size_t)(rank + am * G) * HW + q;
     if (xo) put_f(xo + o, best, tag);
+    if (xb) __hip_atomic_store(xb + o, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (taps) {
       if (Kp > 1) P.out[o] = best;
       P.arg[o] = (uint8_t)(wy * Kp + wx);
@@ -806,10 +891,15 @@ __device__ __forceinline__ void flow_pool(const Rt& rt, int l, int nm, unsigned 
     const FDiv dP(Pn);
     for (int x = tid; x < nm * Pn; x += WG) {
       const int am = dP.div(x), p = x - am * Pn;
-      P.act[(size_t)(rank + am * G) * Pn + p] = f_act(act[x]);
+      P.act[(size_t)(rank + am * G) * Pn + p] = yout[x];
     }
   }
+  if (bulk) stores_done();
   __syncthreads();
+  if (bulk) {  // every lane's stores have completed: the maps' flags go up
+    guint* fl = bulk_flags(P.x_out, C.Mo * HW, C.Mo, tag & 1u);
+    for (int am = tid; am < nm; am += WG) __hip_atomic_store(fl + rank + am * G, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 // ---- AW of a set of filters held in LDS (Sec. 3.4) ------------------------------------------------
@@ -864,6 +954,67 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
   }
 }
 
+// AW of the pull copy in a streamed plan (Sec. 3.4), where it is the only place a filter above the first layer
+// is adjusted: a lane takes a whole K x K filter -- entry e of an own input map, i.e. the connection to output
+// map bj[e] -- and a share of that map's pooling winners, so that a winner's delta and coordinates are read once
+// for K*K multiply-adds (flow_wgrad reads them once per multiply-add); the shares are then added across the
+// 2^gl2 neighbouring lanes that split the winners.  The adjusted filter goes to its place in the rotated copy
+// and, tap order turned back, on its way to the rank that holds the forward copy (x_w, table order).
+template <int K>
+__device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, const int* ncb, int nb, int pitch,
+                                                   const float* dall, const int* yxall, int HW, const float* own_in,
+                                                   int HiWi, int Wi, int stride, float lr, int Mi, int rank, int G,
+                                                   bool full, const CNN_GLOBAL int* csc_ptr, const CNN_GLOBAL int* csc_slot,
+                                                   gtagged* xw, unsigned int tag, const Rt& rt) {
+  constexpr int KK = K * K;
+  const int tid = threadIdx.x;
+  int gl2 = 0;  // winners of a map are split over 2^gl2 lanes
+  while (gl2 < 3 && ((nb * pitch) << (gl2 + 1)) <= WG && (2 << gl2) <= HW) ++gl2;
+  const int Gq = 1 << gl2;
+  const int total = (nb * pitch) << gl2;
+  for (int u0 = 0; u0 < total; u0 += WG) {
+    const int u = u0 + tid;
+    const int ei = u >> gl2, g = u & (Gq - 1);
+    const int ab = ei / pitch, e = ei - ab * pitch;
+    const bool on = u < total && e < ncb[min(ab, nb - 1)];
+    float acc[KK];
+#pragma unroll
+    for (int t = 0; t < KK; ++t) acc[t] = 0.f;
+    int j = 0;
+    if (on) {
+      j = bj[ab * pitch + e];
+      const float* d = dall + j * HW;
+      const int* yx = yxall + j * HW;
+      const float* in = own_in + ab * HiWi;
+      for (int q = g; q < HW; q += Gq) {
+        const int c = yx[q];
+        const float dv = d[q];
+        const float* p = in + ((c >> 16) * Wi + (c & 0xffff)) * stride;
+#pragma unroll
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+          for (int kx = 0; kx < K; ++kx) acc[ky * K + kx] = fmaf(dv, p[ky * Wi + kx], acc[ky * K + kx]);
+      }
+    }
+    DSTAMP(112);
+#pragma unroll
+    for (int t = 0; t < KK; ++t) acc[t] = group_sum(acc[t], gl2);
+    DSTAMP(113);
+    if (on && g == 0) {
+      const int i = rank + ab * G;
+      const int slot = full ? j * Mi + i : csc_slot[csc_ptr[i] + e];
+      float* w = wb + (ab * pitch + e) * KK;
+#pragma unroll
+      for (int t = 0; t < KK; ++t) {   // natural tap t lies at KK-1-t of the rotated copy
+        const float v = fmaf(-lr, acc[t], w[KK - 1 - t]);
+        w[KK - 1 - t] = v;
+        put_f(xw + (size_t)slot * KK + t, v, tag);
+      }
+    }
+    DSTAMP(114);
+  }
+}
+
 // ---- BP through a convolutional layer, pull form (Sec. 3.3), for the own input maps ------------------
 // Neuron (r, c) of input map i collects, over every output map j that reads map i, the deltas of
 // the output neurons whose receptive field covers it (the four inequalities of Sec. 3.3), each
@@ -901,6 +1052,10 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
   }
   const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
+  if (Z.stream) {  // the arena has held chunks of input maps since the last pull: the delta maps start from zeros
+    for (int x = tid; x < Z.scratch_floats; x += WG) dd[x] = 0.f;
+    __syncthreads();
+  }
   DSTAMP(120);
   job_dispatch<false>(S.variant, [&](auto k_, auto sw_, auto th_, auto) {
     constexpr int K = decltype(k_)::value, SW = decltype(sw_)::value, TH = decltype(th_)::value;
@@ -949,6 +1104,7 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
         }
         if (j0 + chunk < j_hi) __syncthreads();
       }
+      if (Z.stream != 0) __syncthreads();  // the partial sums go where the delta maps lay
       if (ln.on) {
         float* dst = part + (ln.r * nb + ln.am) * (S.Ho * S.Wo) + ln.pix;
 #pragma unroll
@@ -1100,7 +1256,7 @@ __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
 template <int ID>
 __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const FlowPtrs* __restrict__ gptrs,
                                                  StatusDev* status, RunArgs a) {
-  extern __shared__ float lds[];
+  extern __shared__ __attribute__((aligned(16))) float lds[];
   __shared__ Shared sh;
   const int tid = threadIdx.x;
   {
@@ -1137,6 +1293,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
   const float lr = a.lr;
 
   bool pend = false;  // the previous image left adjustments to do
+  bool ship_pend = false;  // streamed plan: the previous image's adjusted filters are on their way to the forward copies
   constexpr int IMG_U = 4;
   const int img_n = uni_of<ID>(Z.conv[0].Mi) * uni_of<ID>(Z.conv[0].Hi) * uni_of<ID>(Z.conv[0].Wi);
   const bool img_ahead = img_n <= IMG_U * WG;
@@ -1162,7 +1319,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
 
     // ---- AW pieces that may run either in place or during the next image's waits ----
     // first fully connected layer: own columns, and the (replicated) biases
-    auto fc1_update = [&]() {
+    auto fc1_update = [&]() __attribute__((always_inline)) {
       const FlowFcPtrs& P1 = Q.fc[0];
       float* wc = lds + L1.o_w;
       float* b = lds + L1.o_b;
@@ -1186,7 +1343,9 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       }
     };
     // forward copy of the own maps' filters of conv layer l, and their biases
-    auto wgrad_fwd = [&](auto lc) {
+    // (tagw: the tag of the image the gradient belongs to -- this image's, or the one before when the adjustment was
+    // put off; a plan that streams the layer's inputs fetches them again under that tag, chunk by chunk)
+    auto wgrad_fwd = [&](auto lc, unsigned int tagw, bool with_weights) __attribute__((always_inline)) {
       const int l = lv(lc);
       const ConvSpec& C = Z.conv[l];
       const FlowConvPtrs& P = Q.conv[l];
@@ -1204,6 +1363,48 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       const FDiv dPM(per_map), dKK(KK), dK(K);
       const bool full = C.full_table != 0;
       const int Mi = uni_of<ID>(C.Mi);
+      if (!with_weights) {
+        // (the filters arrive adjusted from the holders of the pull copies: only the biases are this rank's to do)
+      } else if (Z.stream != 0 && l >= 1) {
+        gtagged* src = Q.conv[l >= 1 ? l - 1 : 0].x_out;
+        const int chunk = C.in_chunk;
+        for (int i0 = 0; i0 < Mi; i0 += chunk) {
+          const int n = min(chunk, Mi - i0);
+          __syncthreads();  // whoever read the arena before is done
+          if (!gather_bulk(rt, lds + C.o_in, bulk_data(src, Mi * HiWi, tagw & 1u) + (size_t)i0 * HiWi, n * HiWi,
+                           bulk_flags(src, Mi * HiWi, Mi, tagw & 1u) + i0, n, tagw)) return;
+          for (int am = 0; am < nm; ++am) {
+            // connections of own map am whose input map lies in [i0, i0 + n) (the list is sorted)
+            int c_lo = i0, c_hi = min(i0 + n, ncf[am]);
+            if (!full) {
+              const int* ci = cidx + am * pitch;
+              int lo = 0, hi = ncf[am];
+              while (lo < hi) { const int mid = (lo + hi) >> 1; if (ci[mid] < i0) lo = mid + 1; else hi = mid; }
+              c_lo = lo;
+              hi = ncf[am];
+              while (lo < hi) { const int mid = (lo + hi) >> 1; if (ci[mid] < i0 + n) lo = mid + 1; else hi = mid; }
+              c_hi = lo;
+            }
+            if (c_hi <= c_lo) continue;
+            flow_wgrad(lds + C.o_wf + (am * pitch + c_lo) * KK, (c_hi - c_lo) * KK, HW, stride, Wi,
+                       uni_of<ID>(C.wgrad_R_log2), lr, g_out, [&](int wi) {
+              const int cc = dKK.div(wi), tt = wi - cc * KK, c = c_lo + cc;
+              const int ky = dK.div(tt), kx = tt - ky * K;
+              WgradInfo I;
+              I.ok = true;
+              I.d = dl + am * HW;
+              I.yx = yx + am * HW;
+              I.in = in + (cidx[am * pitch + c] - i0) * HiWi + ky * Wi + kx;
+              I.canon = 0;
+              if (g_out) {
+                const int j = rank + am * G;
+                I.canon = P.w_canon + (long long)((full ? j * Mi : P.csr_ptr[j]) + c) * KK + tt;
+              }
+              return I;
+            });
+          }
+        }
+      } else
       flow_wgrad(lds + C.o_wf, nm * per_map, HW, stride, Wi, uni_of<ID>(C.wgrad_R_log2), lr, g_out, [&](int wi) {
         const int am = dPM.div(wi), rem = wi - am * per_map;
         const int c = dKK.div(rem), tt = rem - c * KK;
@@ -1234,7 +1435,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
     };
     // pull copy of the filters of conv layer l that read the own maps of the layer below (stored
     // rotated); own_in = those maps' pooled outputs, [n_own_below][Hi*Wi]
-    auto wgrad_pull = [&](auto lc, const float* own_in) {
+    auto wgrad_pull = [&](auto lc, const float* own_in) __attribute__((always_inline)) {
       const int l = lv(lc);
       const ConvSpec& C = Z.conv[l];
       const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1,
@@ -1268,6 +1469,47 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
     // conv layers' forward copies (above the first layer) and of the first FC layer run while the
     // next image's inputs of that layer are on their way, the pull copy of the second conv layer
     // while the first FC layer's partial sums are.  Same arithmetic on the same values, only later.
+    // Streamed plans adjust every filter above the first layer once, in the pull copy (whose holder has the deltas
+    // of all output maps at hand and the input map in its own LDS), and send the new values to the rank that holds
+    // the forward copy: entry (j, i) goes to its place in row j of the table, tap order turned back.
+    auto ship_rows = [&](auto lc, unsigned int tagw) __attribute__((always_inline)) {
+      const int l = lv(lc);
+      const ConvSpec& C = Z.conv[l];
+      const FlowConvPtrs& P = Q.conv[l];
+      const int KK = C.K * C.K, pitch = C.back_pitch, Mi = C.Mi;
+      const int nb = sh.pull[l].n_maps;
+      const float* wb = lds + C.o_wb;
+      const int* bj = (const int*)(lds + C.o_bj);
+      const int* ncb = (const int*)(lds + C.o_ncb);
+      const bool full = C.full_table != 0;
+      const FDiv dKK(KK);
+      for (int ab = 0; ab < nb; ++ab) {
+        const int i = rank + ab * G, ne = ncb[ab];
+        const int eb = full ? 0 : P.csc_ptr[i];
+        gtagged* dst = P.x_w + (size_t)(tagw & 1u) * (full ? (size_t)C.Mo * Mi : (size_t)P.csr_ptr[C.Mo]) * KK;
+        for (int x = tid; x < ne * KK; x += WG) {
+          const int e = dKK.div(x), t = x - e * KK;
+          const int slot = full ? bj[ab * pitch + e] * Mi + i : P.csc_slot[eb + e];
+          put_f(dst + (size_t)slot * KK + (KK - 1 - t), wb[(ab * pitch + e) * KK + t], tagw);
+        }
+      }
+    };
+    auto take_rows = [&](auto lc, unsigned int tagw) __attribute__((always_inline)) -> bool {
+      const int l = lv(lc);
+      const ConvSpec& C = Z.conv[l];
+      const FlowConvPtrs& P = Q.conv[l];
+      const int KK = C.K * C.K, Mi = C.Mi;
+      const int nm = sh.fwd[l].n_maps;
+      const int* ncf = (const int*)(lds + C.o_ncf);
+      const bool full = C.full_table != 0;
+      const gtagged* src0 = P.x_w + (size_t)(tagw & 1u) * (full ? (size_t)C.Mo * Mi : (size_t)P.csr_ptr[C.Mo]) * KK;
+      for (int am = 0; am < nm; ++am) {
+        const int j = rank + am * G;
+        const size_t cb = full ? (size_t)j * Mi : (size_t)P.csr_ptr[j];
+        if (!gather(rt, (unsigned int*)(lds + C.o_wf + am * C.max_conn * KK), src0 + cb * KK, ncf[am] * KK, tagw)) return false;
+      }
+      return true;
+    };
     const bool defer = Z.defer != 0 && !taps && !g_out && train;
     STAMP(0);
     {  // the image: a small one was fetched into registers while the previous image was being worked on
@@ -1292,19 +1534,24 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
     if (!for_up<ID, 0, FLOW_MAX_CONV>(n_conv, [&](auto lc) {
           const int l = lv(lc);
           const ConvSpec& C = Z.conv[l];
+          gtagged* src = nullptr;
           if (l >= 1) {
             if (pend) {
               if (l == n_conv - 1) fc1_update();
-              wgrad_fwd(lc);
+              if (Z.stream == 0) wgrad_fwd(lc, tag - 1u, true);
             }
+            if (Z.stream != 0 && ship_pend && !take_rows(lc, tag - 1u)) return false;
             const int nw = C.Mi * C.Hi * C.Wi;
-            if (!gather(rt, (unsigned int*)(lds + C.o_in), Q.conv[l >= 1 ? l - 1 : 0].x_out + (size_t)par * nw, nw, tag))
-              return false;
+            src = Q.conv[l >= 1 ? l - 1 : 0].x_out;
+            if (Z.stream == 0) {
+              if (!gather(rt, (unsigned int*)(lds + C.o_in), src + (size_t)par * nw, nw, tag)) return false;
+              src = nullptr;
+            }
           }
           STAMP(2 + 2 * l);
           const int nm = sh.fwd[l].n_maps;
           if (nm > 0) {
-            flow_conv_fwd<ID>(rt, l);
+            if (!flow_conv_fwd<ID>(rt, l, src, tag)) return false;
             flow_pool<ID>(rt, l, nm, tag, taps);
           }
           STAMP(3 + 2 * l);
@@ -1336,9 +1583,10 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       }
       STAMP(30);
       if (pend) {
-        wgrad_pull(IC<1>{}, lds + Z.o_prev);
+        if (Z.stream == 0) wgrad_pull(IC<1>{}, lds + Z.o_prev);
         pend = false;
       }
+      ship_pend = false;
       float* y = lds + L1.o_act;
       if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, lds + L1.o_dact, part, tag, !L1.is_output)) return;
       STAMP(31);
@@ -1554,7 +1802,10 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         }
       }
       STAMP(40 + 4 * l);
-      if (!(defer && l >= 1)) wgrad_fwd(lc);
+      // streamed plan: the filters above the first layer are adjusted once, by the holders of the pull copies, who
+      // send them on (ship_rows below); the gradient tap still works them out here, from the inputs fetched again
+      if (Z.stream != 0 && l >= 1) wgrad_fwd(lc, tag, g_out != nullptr);
+      else if (!(defer && l >= 1)) wgrad_fwd(lc, tag, true);
       STAMP(41 + 4 * l);
       if (l >= 1) {
         const int nb = sh.pull[l].n_maps;
@@ -1572,7 +1823,33 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
           const int Hs = uni_of<ID>(C.pull_shares), Mi = uni_of<ID>(C.Mi);
           const float* own = (Hs > 1 && rank >= Mi) ? lds + C.o_in + (rank % Mi) * HiWi
                                                     : lds + Z.conv[l >= 1 ? l - 1 : 0].o_pool;
-          if (defer && l == 1) {
+          if (Z.stream != 0) {
+            if (!g_out) {
+              if (l == 1) DSTAMP(125);
+              const int K = C.K;
+              if (K >= 2 && K <= 5) {
+                const bool full = C.full_table != 0;
+                gtagged* xw = P.x_w + (size_t)par * (full ? (size_t)Mo * Mi : (size_t)P.csr_ptr[Mo]) * (K * K);
+                auto go = [&](auto k_) __attribute__((always_inline)) {
+                  flow_wgrad_entries<decltype(k_)::value>(lds + C.o_wb, (const int*)(lds + C.o_bj), (const int*)(lds + C.o_ncb),
+                      nb, C.back_pitch, lds + Z.o_dall, (const int*)(lds + Z.o_yxall), HW, own, HiWi, C.Wi, C.S + 1, lr, Mi,
+                      rank, G, full, P.csc_ptr, P.csc_slot, xw, tag, rt);
+                };
+                switch (K) {
+                  case 2: go(IC<2>{}); break;
+                  case 3: go(IC<3>{}); break;
+                  case 4: go(IC<4>{}); break;
+                  default: go(IC<5>{}); break;
+                }
+                if (l == 1) DSTAMP(126);
+                __syncthreads();
+              } else {
+                wgrad_pull(lc, own);
+                ship_rows(lc, tag);
+              }
+              if (l == 1) DSTAMP(127);
+            }
+          } else if (defer && l == 1) {
             // the pull copy is adjusted during the next image's wait; the next FP overwrites the
             // pooled maps it needs, so they are set aside
             float* prev = lds + Z.o_prev;
@@ -1587,6 +1864,13 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       return;
     STAMP(60);
     pend = defer;
+    // streamed plan: the forward copies take their adjusted filters at the next image's FP -- or now, after the
+    // last image of the call (the copies go back to global memory below)
+    ship_pend = Z.stream != 0 && !g_out;
+    if (ship_pend && taps) {
+      if (!for_up<ID, 1, FLOW_MAX_CONV>(n_conv, [&](auto lc) { return take_rows(lc, tag); })) return;
+      ship_pend = false;
+    }
   }
   if (!g_out && a.train) flow_store<ID>(rt);
 }

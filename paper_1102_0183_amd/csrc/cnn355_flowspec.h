@@ -28,6 +28,7 @@ struct ConvSpec {
   int pull_strip;   // same for the delta pull through this layer
   int pull_rows;
   int has_x_out;    // the pooled outputs are exchanged (a convolutional layer follows)
+  int in_chunk;     // input maps held in LDS at a time: Mi, or fewer when the plan streams this layer's inputs
   // LDS offsets, in floats
   int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
   int o_wf;     // [n_own][max_conn][K*K] forward copy of the filters
@@ -70,6 +71,9 @@ struct FlowSpec {
   int out_units;    // 0 soft-max + cross-entropy, 1 scaled tanh + squared error
   int defer;        // 1: weight adjustments nobody is waiting for are put off into the next image's waits
   int o_prev;       // [conv[1].n_own_below * Hi * Wi] the own pooled maps of the first layer, previous image
+  int stream;       // 1: the inputs of every convolutional layer above the first do not stay in LDS: FP and the
+                    //    adjustment of the forward copy walk them chunk by chunk (in_chunk maps at a time, fetched
+                    //    from the exchange buffers into the arena the delta pull uses for its zero-bordered maps)
   ConvSpec conv[FLOW_MAX_CONV];
   FcSpec fc[FLOW_MAX_FC];
 };
@@ -146,8 +150,9 @@ constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, 
 // Choose the team and lay out every rank's LDS.  On entry Z holds the shape (n_conv, n_fc,
 // n_classes, out_units, and per layer Mi..Wp, max_conn, max_back, full_table / n_in, n_out, is_output); on
 // success the rest of Z is filled in.  team_ranks / team_stride: 0 = automatic.
-constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) {
+constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_cu, int stream) {
   const int n_conv = Z.n_conv, n_fc = Z.n_fc;
+  Z.stream = stream;
   if (n_conv < 1) return FLOW_NO_CONV;
   if (n_conv > FLOW_MAX_CONV || n_fc > FLOW_MAX_FC || n_fc < 1) return FLOW_TOO_MANY_LAYERS;
   int max_maps = 1;
@@ -179,11 +184,15 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     // (handing the sums over costs the owner a round trip through the L2, about what 2^17 multiply-adds of a
     // map's pull take, so two shares pay from twice that: measured, sharing gains 1.5 us on 80 entries of 5x5
     // into 13x13 maps and loses 0.8 us on 40 of them)
-    C.pull_shares = (l >= 1 && 2 * C.Mi <= G && (long long)C.max_back * KK * C.Hi * C.Wi >= FLOW_SHARE_MIN_MACS)
+    // (a plan that streams its inputs does not share pulls: a share adjusts its filters from an input map of the
+    // layer, which then is not at hand)
+    C.pull_shares = (l >= 1 && !stream && 2 * C.Mi <= G &&
+                     (long long)C.max_back * KK * C.Hi * C.Wi >= FLOW_SHARE_MIN_MACS)
                         ? G / C.Mi : 1;
     C.back_pitch = (C.max_back + C.pull_shares - 1) / C.pull_shares;
     C.has_x_out = (l + 1 < n_conv) ? 1 : 0;
-    C.o_in = take((long long)C.Mi * C.Hi * C.Wi);
+    C.in_chunk = C.Mi;
+    C.o_in = (stream && l >= 1) ? 0 : take((long long)C.Mi * C.Hi * C.Wi);   // (streamed: the arena, set below)
     C.o_wf = take((long long)C.n_own * C.max_conn * KK);
     C.o_bf = take(C.n_own);
     C.o_cidx = take((long long)C.n_own * C.max_conn);
@@ -231,8 +240,9 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     Q.o_delta = take(Q.n_out);
     Q.o_dact = take(Q.n_out);
   }
+  max_part = flow_maxl(max_part, max_act);   // (the pooling step lays the own maps' outputs out there)
   Z.o_act = take(max_act);
-  Z.o_part = take(max_part);
+  Z.o_part = take(stream ? 0 : max_part);   // (streamed plan: the partial sums go into the arena, see below)
   Z.o_dall = take(n_conv > 1 ? max_dall : 0);
   Z.o_yxall = take(n_conv > 1 ? max_dall : 0);
   Z.defer = 0;
@@ -240,7 +250,12 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
   // tiles read a few floats past the end of the last row of a map, and a row past its last row
   long long pad = 16;
   for (int l = 1; l < n_conv; ++l) pad = flow_maxl(pad, 16 + Z.conv[l].Wi + Z.conv[l].K);
-  const long long need = n_conv > 1 ? max_hwd + pad : pad;
+  long long need = n_conv > 1 ? max_hwd + pad : pad;
+  if (stream) {
+    for (int l = 1; l < n_conv; ++l) need = flow_maxl(need, (long long)Z.conv[l].Hi * Z.conv[l].Wi + pad);
+    // a job's partial sums are stored when its last chunk of maps has been read: they share the arena
+    need = flow_maxl(need, max_part);
+  }
   if (off + need > FLOW_LDS_FLOATS_MAX) return FLOW_NO_LDS;
   if (n_conv > 1) {
     const long long prev = (long long)Z.conv[1].n_own_below * Z.conv[1].Hi * Z.conv[1].Wi;
@@ -260,6 +275,10 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
       const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
       const long long chunk = flow_maxl(1, flow_minl(C.Mo, (floats - pad) / hwd));
       worst = flow_maxl(worst, (C.Mo + chunk - 1) / chunk);
+      if (stream) {  // the chunks of input maps FP walks through the same arena
+        const long long ic = flow_maxl(1, flow_minl(C.Mi, (floats - pad) / ((long long)C.Hi * C.Wi)));
+        worst = flow_maxl(worst, (C.Mi + ic - 1) / ic);
+      }
     }
     return worst;
   };
@@ -279,6 +298,8 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     const ConvSpec& C = Z.conv[l];
     scratch = flow_maxl(scratch, (long long)C.Mo * flow_border_map(C.Hi, C.Wi, C.K) + pad);
   }
+  if (stream)
+    for (int l = 1; l < n_conv; ++l) scratch = flow_maxl(scratch, (long long)Z.conv[l].Mi * Z.conv[l].Hi * Z.conv[l].Wi + pad);
   scratch = flow_minl(scratch, (long long)FLOW_LDS_FLOATS_MAX - off);
   Z.o_scratch = take(scratch);
   Z.scratch_floats = (int)scratch;
@@ -287,8 +308,27 @@ constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) 
     ConvSpec& C = Z.conv[l];
     const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
     C.pull_chunk = (int)flow_maxl(1, flow_minl(C.Mo, (scratch - pad) / hwd));
+    if (stream) {
+      // the pull stores its partial sums in the arena after its one walk over the delta maps: a job with
+      // more units than lanes would walk them again and meet its own sums there
+      const long long U = C.pull_strip
+          ? (long long)C.n_own_below * ((C.Hi + C.pull_rows - 1) / C.pull_rows) * ((C.Wi + C.pull_strip - 1) / C.pull_strip)
+          : (long long)C.n_own_below * C.Hi * C.Wi;
+      if (U > WG) return FLOW_NO_LDS;
+      Z.o_part = Z.o_scratch;
+      C.o_in = Z.o_scratch;
+      C.in_chunk = (int)flow_maxl(1, flow_minl(C.Mi, (scratch - pad) / ((long long)C.Hi * C.Wi)));
+    }
   }
   return FLOW_OK;
+}
+
+// The plan that keeps every layer's inputs in LDS where that fits (the fewest fetches), else the one that
+// streams them.
+constexpr int flow_plan(FlowSpec& Z, int team_ranks, int team_stride, int n_cu) {
+  const int rc = flow_plan_as(Z, team_ranks, team_stride, n_cu, 0);
+  if (rc != FLOW_NO_LDS || Z.n_conv < 2) return rc;
+  return flow_plan_as(Z, team_ranks, team_stride, n_cu, 1);
 }
 
 // ---- networks the resident kernel is also compiled for, every size a literal --------------------

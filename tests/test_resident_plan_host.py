@@ -46,6 +46,12 @@ def check_plan(p, arch, n_ranks=0, stride=0):
     for off, end, name in spans:
         assert off % 4 == 0 and off >= 0 and end <= num["lds_floats"], (arch, name)
     size = {name: n for name, _, n in regions}
+    stream = num["stream"]
+    if stream:
+        # the streamed plan: inputs of the layers above the first, the pull's delta maps and every job's partial
+        # sums take turns in one arena
+        assert "part" not in size and not any(("conv%d.in" % l) in size for l in range(1, len(p["conv"])))
+        size["part"] = size["scratch"]
     # layers
     for l, c in enumerate(p["conv"]):
         KK = c["K"] * c["K"]
@@ -54,7 +60,8 @@ def check_plan(p, arch, n_ranks=0, stride=0):
         # FP: partial sums of the job, for a rank with the most maps and one with a map fewer
         for nm in {c["n_own"], max(1, c["n_own"] - 1)}:
             U = job_units(c["fwd_strip"], c["fwd_rows"], nm, c["Ho"], c["Wo"])
-            assert split_ways(U, c["max_conn"], wg) * nm * c["Ho"] * c["Wo"] <= size["part"], (arch, l, "fwd")
+            R = min(split_ways(U, min(c["max_conn"], c["in_chunk"]), wg), split_ways(U, c["max_conn"], wg))
+            assert R * nm * c["Ho"] * c["Wo"] <= size["part"], (arch, l, "fwd")
         assert c["n_own"] * c["Ho"] * c["Wo"] <= size["act"]
         if c["fwd_strip"]:
             assert c["fwd_strip"] in (4, 5, 7) and c["fwd_rows"] in (1, 2) and 2 <= c["K"] <= 5 and c["S"] <= 1
@@ -63,7 +70,7 @@ def check_plan(p, arch, n_ranks=0, stride=0):
             continue
         # shared pulls
         macs = c["max_back"] * KK * c["Hi"] * c["Wi"]
-        shared = 2 * c["Mi"] <= G and macs >= num["share_min_macs"]
+        shared = 2 * c["Mi"] <= G and macs >= num["share_min_macs"] and not stream
         H = G // c["Mi"] if shared else 1
         assert c["pull_shares"] == H, (arch, l)
         assert c["back_pitch"] == ceil_div(c["max_back"], H)
@@ -84,6 +91,12 @@ def check_plan(p, arch, n_ranks=0, stride=0):
             R = min(split_ways(U, max_cnt, wg), split_ways(U, plan_cnt, wg))
             assert R * nm * c["Hi"] * c["Wi"] <= size["part"], (arch, l, "pull")
         assert c["Mo"] * c["Hp"] * c["Wp"] <= size["dall"] == size["yxall"]
+        if stream:
+            # a chunk of input maps fits the arena, the chunks tile the maps, and the pull walks its maps once
+            assert 1 <= c["in_chunk"] <= c["Mi"] and c["in_chunk"] * c["Hi"] * c["Wi"] + pad <= size["scratch"], (arch, l)
+            assert job_units(c["pull_strip"], c["pull_rows"], c["n_own_below"], c["Hi"], c["Wi"]) <= wg
+        else:
+            assert c["in_chunk"] == c["Mi"] and size["conv%d.in" % l] == c["Mi"] * c["Hi"] * c["Wi"]
         # sums over the pooled positions of a weight gradient: split 2^R ways while the weights of either copy fit
         n_w = min(c["n_own"] * c["max_conn"] * KK, c["n_own_below"] * c["back_pitch"] * KK)
         r = c["wgrad_R_log2"]
@@ -104,10 +117,9 @@ def test_benchmark_networks_take_the_kernels_compiled_for_them(name, static_id):
     assert p["conv"][1]["pull_shares"] == (2 if name == "cfg2b" else 1)
     for team in ((32, 1), (32, 8), (20, 8)):
         q = binding.resident_plan(arch, 0, *team)
-        if "unsupported" in q:  # the large net on 20 ranks: four maps a rank, more weights than its LDS holds
-            assert name == "cfg2b" and team[0] == 20
-            continue
         check_plan(q, arch, *team)
+        # (the large net on 20 ranks: four maps a rank, more than its LDS holds next to all inputs: streamed)
+        assert q["numbers"]["stream"] == (1 if (name == "cfg2b" and team[0] == 20) else 0)
         assert q["numbers"]["static_id"] == 0 and q["numbers"]["G"] == team[0]
 
 
@@ -118,9 +130,21 @@ def test_cfg5_with_a_regular_half_table():
     assert p["conv"][1]["full_table"] == 0 and p["conv"][1]["max_conn"] == 20 and p["conv"][1]["max_back"] == 40
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4a", "cfg4b"])
-def test_networks_whose_share_per_rank_exceeds_the_lds_are_refused(name):
-    p = binding.resident_plan(synth.WORKLOADS[name].arch)
+@pytest.mark.parametrize("name", ["cfg3", "cfg4a"])
+def test_wide_networks_stream_their_inputs(name):
+    """A rank's share of these nets does not fit next to all input maps of every layer: the plan keeps the
+    weights resident and walks the inputs in chunks."""
+    arch = synth.WORKLOADS[name].arch
+    p = binding.resident_plan(arch)
+    check_plan(p, arch)
+    assert p["numbers"]["stream"] == 1 and p["numbers"]["static_id"] == 0
+    assert all(c["pull_shares"] == 1 for c in p["conv"])
+    assert any(c["in_chunk"] < c["Mi"] for c in p["conv"][1:])
+
+
+def test_the_widest_network_is_refused():
+    """Two maps of 300C4 and their pull copies alone are 19200 weights a rank, next to those of the other layers."""
+    p = binding.resident_plan(synth.WORKLOADS["cfg4b"].arch)
     assert "LDS" in p["unsupported"]
 
 
