@@ -435,6 +435,13 @@ class Cnn:
         f.argtypes = [C.c_void_p]
         return int(f(self._h))
 
+    def resident_streams(self):
+        """Development aid: whether the resident plan streams the inputs of the layers above the first."""
+        f = lib().cnn355_resident_streams
+        f.restype = C.c_int
+        f.argtypes = [C.c_void_p]
+        return bool(f(self._h))
+
     def resident_pull_shares(self, conv_index):
         """Development aid: ranks that share the delta pull into one input map of a conv layer of the resident plan."""
         f = lib().cnn355_resident_pull_shares

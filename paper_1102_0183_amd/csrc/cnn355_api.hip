@@ -1359,6 +1359,8 @@ int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
 
 // development aid, not part of the public header: which compiled-in network the resident plan equals (0: none)
 int cnn355_resident_static_id(const cnn_t* net) { return net ? net->flow_static_id : -1; }
+// development aid: 1 when the resident plan streams the inputs of the layers above the first (0: they stay in LDS)
+int cnn355_resident_streams(const cnn_t* net) { return (net && net->flow_ok) ? net->flow.stream : 0; }
 // development aid: workgroups in the resident plan's team (0 when the network cannot run in resident mode)
 int cnn355_resident_ranks(const cnn_t* net) { return (net && net->flow_ok) ? net->flow.G : 0; }
 // development aid, host only (no device is touched): the resident plan of an architecture as text.  fan_in > 0

@@ -1894,6 +1894,8 @@ hipError_t launch_resident(int static_id, int grid, size_t lds_bytes, hipStream_
     case 1: return launch_resident_id<1>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
     case 2: return launch_resident_id<2>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
     case 3: return launch_resident_id<3>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
+    case 4: return launch_resident_id<4>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
+    case 5: return launch_resident_id<5>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
     default: return launch_resident_id<0>(grid, lds_bytes, stream, spec, d_ptrs, d_status, a);
   }
 }
@@ -1951,6 +1953,8 @@ int resident_static_id(const FlowSpec& z) {
   if (__builtin_memcmp(&z, &StaticSpec<1>::value, sizeof(FlowSpec)) == 0) return 1;
   if (__builtin_memcmp(&z, &StaticSpec<2>::value, sizeof(FlowSpec)) == 0) return 2;
   if (__builtin_memcmp(&z, &StaticSpec<3>::value, sizeof(FlowSpec)) == 0) return 3;
+  if (__builtin_memcmp(&z, &StaticSpec<4>::value, sizeof(FlowSpec)) == 0) return 4;
+  if (__builtin_memcmp(&z, &StaticSpec<5>::value, sizeof(FlowSpec)) == 0) return 5;
   return 0;
 }
 

@@ -370,7 +370,9 @@ constexpr FlowSpec flow_static_spec(int C0, int H0, int W0, int n_conv, const St
 // 2: 1x29x29-40C4-MP2-80C5-MP3-300N-10N, automatic team
 // 3: 4x44x44-40C5S1-MP2-80C3-MP2-100N-5N behind a fixed first layer, the second convolution reading 20 of the 40
 //    maps with the busiest map read 49 times (the benchmark's seeded table), automatic team
-constexpr int FLOW_N_STATIC = 3;
+// 4: 2x48x48-50C5-MP2-128C3-MP4-100N-5N, automatic team (a streamed plan)
+// 5: 3x32x32-100C5-MP2-100C5-MP2-100C4-MP2-300N-10N, automatic team (a streamed plan)
+constexpr int FLOW_N_STATIC = 5;
 template <int ID>
 struct StaticSpec;
 template <>
@@ -391,6 +393,19 @@ struct StaticSpec<3> {
   static constexpr StaticConv conv[2] = {{40, 5, 1, 2, 0, 0}, {80, 3, 0, 2, 20, 49}};
   static constexpr int fc[2] = {100, 5};
   static constexpr FlowSpec value = flow_static_spec(4, 44, 44, 2, conv, 2, fc, 0, 0);
+};
+
+template <>
+struct StaticSpec<4> {
+  static constexpr StaticConv conv[2] = {{50, 5, 0, 2, 0, 0}, {128, 3, 0, 4, 0, 0}};
+  static constexpr int fc[2] = {100, 5};
+  static constexpr FlowSpec value = flow_static_spec(2, 48, 48, 2, conv, 2, fc, 0, 0);
+};
+template <>
+struct StaticSpec<5> {
+  static constexpr StaticConv conv[3] = {{100, 5, 0, 2, 0, 0}, {100, 5, 0, 2, 0, 0}, {100, 4, 0, 2, 0, 0}};
+  static constexpr int fc[2] = {300, 10};
+  static constexpr FlowSpec value = flow_static_spec(3, 32, 32, 3, conv, 2, fc, 0, 0);
 };
 
 }  // namespace cnn355

@@ -45,7 +45,7 @@ SHAPES = [
 ]
 SHARES = {"1x28x28-6C5-MP2-100C5-MP2-8N": 16, "1x28x28-40C5-MP2-80C5-MP2-8N": 2}
 
-def _pair(arch, fan, fe_k, n_src, seed):
+def _pair(arch, fan, fe_k, n_src, seed, wscale=0.3):
     import oracle
     o0 = oracle.Oracle(arch)
     convs = [l for l in range(1, o0.num_layers) if o0.layer_info(l)["kind"] == 1]
@@ -58,7 +58,7 @@ def _pair(arch, fan, fe_k, n_src, seed):
         filt = (rng.standard_normal((c, fe_k, fe_k)) * 0.2).astype(np.float32)
         src = rng.integers(0, n_src, size=c).astype(np.int32)
         frontend = (filt, src, n_src)
-    return build_pair(arch=arch, tables=tables, frontend=frontend, seed=seed, wscale=0.3)
+    return build_pair(arch=arch, tables=tables, frontend=frontend, seed=seed, wscale=wscale)
 
 
 @pytest.mark.parametrize("mode", MODES)
@@ -93,6 +93,52 @@ def test_shapes_one_step_and_ten_steps(arch, fan, fe_k, n_src, mode):
     # the batched call lands on the same bits as the image-by-image calls
     g.set_weights(w0)
     g.train_many(to_dev(imgs), to_dev(labs), 0.01)
+    np.testing.assert_array_equal(g.get_weights(), w_step)
+    g.close()
+
+
+# Networks whose per-rank share does not fit next to all inputs of every layer: the resident plan streams the
+# inputs (chunks of maps through one arena), adjusts every filter above the first layer once and sends it on.
+STREAMED = [
+    ("3x32x32-100C5-MP2-100C5-MP2-8N", {}, (0, 0)),
+    ("3x32x32-100C5-MP2-100C5-MP2-8N", {1: 60}, (50, 1)),      # sparse table, two maps a rank
+    ("2x40x40-60C5S1-120C3-MP2-6N", {1: 31}, (50, 1)),         # skipping factor below, ranks with 3 and with 2 maps, sparse
+    ("1x40x40-64C5-MP2-64C1-MP2-64C3-9N", {}, (50, 1)),        # three layers, a 1x1 kernel (no compiled filter loop)
+    ("1x44x44-90C3-MP2-90C6-MP2-7N", {1: 50}, (0, 0)),         # 6x6 kernel, sparse
+]
+
+
+@pytest.mark.parametrize("arch,fan,team", STREAMED)
+def test_streamed_resident_plans(arch, fan, team):
+    print("case", arch, fan, team, flush=True)
+    # (weights in the paper's range: with hundreds of inputs per unit a wider range saturates whole maps, whose
+    # pooling winners are then ties by the hundred -- saturated nets have their own test)
+    g, o = _pair(arch, fan, 0, 1, 11, wscale=0.05)
+    g.set_mode(binding.MODE_RESIDENT)
+    if team != (0, 0):
+        g.set_team(*team)
+    assert g.resident_streams()
+    rng = np.random.default_rng(23)
+    imgs = rng.uniform(-1, 1, (10, g.image_size)).astype(np.float32)
+    labs = rng.integers(0, g.num_classes, size=10).astype(np.int32)
+    grad_g = g.debug_gradients(to_dev(imgs[0]), int(labs[0]))
+    grad_o, loss_o = o.gradients(imgs[0], int(labs[0]))
+    compare_forward_state(g, o)
+    compare_backward_state(g, o)
+    for (a, b) in layer_bounds(o):
+        assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
+    w0 = g.get_weights()
+    adopted = lockstep_train(g, o, imgs, labs, 0.01)
+    w_step = g.get_weights()
+    print("  near-tie winners adopted:", adopted, flush=True)
+    assert rel_err(w_step, o.get_weights()) <= TOL_W100
+    # the batched call lands on the same bits as the image-by-image calls, and so do two calls of five
+    g.set_weights(w0)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.01)
+    np.testing.assert_array_equal(g.get_weights(), w_step)
+    g.set_weights(w0)
+    g.train_many(to_dev(imgs[:5]), to_dev(labs[:5]), 0.01)
+    g.train_many(to_dev(imgs[5:]), to_dev(labs[5:]), 0.01)
     np.testing.assert_array_equal(g.get_weights(), w_step)
     g.close()
 

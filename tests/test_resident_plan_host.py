@@ -130,14 +130,16 @@ def test_cfg5_with_a_regular_half_table():
     assert p["conv"][1]["full_table"] == 0 and p["conv"][1]["max_conn"] == 20 and p["conv"][1]["max_back"] == 40
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4a"])
-def test_wide_networks_stream_their_inputs(name):
+@pytest.mark.parametrize("name,static_id", [("cfg3", 4), ("cfg4a", 5)])
+def test_wide_networks_stream_their_inputs(name, static_id):
     """A rank's share of these nets does not fit next to all input maps of every layer: the plan keeps the
     weights resident and walks the inputs in chunks."""
     arch = synth.WORKLOADS[name].arch
     p = binding.resident_plan(arch)
     check_plan(p, arch)
-    assert p["numbers"]["stream"] == 1 and p["numbers"]["static_id"] == 0
+    assert p["numbers"]["stream"] == 1 and p["numbers"]["static_id"] == static_id
+    q = binding.resident_plan(arch, 0, 90, 1)      # another team: the kernel that reads its plan
+    assert "unsupported" in q or q["numbers"]["static_id"] == 0
     assert all(c["pull_shares"] == 1 for c in p["conv"])
     assert any(c["in_chunk"] < c["Mi"] for c in p["conv"][1:])
 
