@@ -74,6 +74,33 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-fno-sanitize-recover=all", "-g"]
+
+
+def build_host_sanitizer_driver(driver_cpp: str, force: bool = False) -> str:
+    """An executable of `driver_cpp` plus the library's sources with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the HOST pass (the device pass is compiled as usual and never runs here):
+    for checking parser, planners and workspace sizing without a GPU.  Objects live in _build/san/."""
+    out_dir = os.path.join(OBJ, "san")
+    os.makedirs(out_dir, exist_ok=True)
+    exe = os.path.join(out_dir, "plan_san")
+    srcs = sources() + [driver_cpp]
+    objs = [os.path.join(out_dir, os.path.basename(x).rsplit(".", 1)[0] + ".o") for x in srcs]
+    jobs = []
+    for src, obj in zip(srcs, objs):
+        if force or _older(obj, [src] + HEADERS):
+            cmd = [HIPCC] + [f for f in FLAGS if f != "-O3"] + ["-O1", "-x", "hip"] + SAN_FLAGS + ["-c", "-o", obj, src]
+            jobs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for src, p in jobs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError("hipcc (host sanitizers) failed on %s:\n%s" % (src, out))
+    if jobs or not os.path.exists(exe):
+        subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", "-fsanitize=address", "-fsanitize=undefined",
+                        "-o", exe] + objs, check=True)
+    return exe
+
+
 if __name__ == "__main__":
     import sys
     print(build(force="--all" in sys.argv, verbose=True))

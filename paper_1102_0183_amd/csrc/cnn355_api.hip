@@ -590,8 +590,9 @@ int plan(cnn* net) {
       woff += (size_t)L.n_out * (1 + (size_t)L.n_in);
       ++fc_i;
     }
-    L.bias = net->d_weights + L.b_canon;
-    L.w = net->d_weights + L.w_canon;
+    // (a handle that only plans, without a workspace, has no weights to point into)
+    L.bias = net->d_weights ? net->d_weights + L.b_canon : nullptr;
+    L.w = net->d_weights ? net->d_weights + L.w_canon : nullptr;
     below = L.out;
     has_below = true;
     net->dev_of_arch[l] = nl;
