@@ -963,7 +963,7 @@ __device__ __forceinline__ void flow_wgrad(float* w, int n_w, int HW, int stride
 template <int K>
 __device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, const int* ncb, int nb, int pitch,
                                                    const float* dall, const int* yxall, int HW, const float* own_in,
-                                                   int HiWi, int Wi, int stride, float lr, int Mi, int rank, int G,
+                                                   int HiWi, int Wi, int stride, float lr, int Mi, int Mo, int rank, int G,
                                                    bool full, const CNN_GLOBAL int* csc_ptr, const CNN_GLOBAL int* csc_slot,
                                                    gtagged* xw, unsigned int tag, const Rt& rt) {
   constexpr int KK = K * K;
@@ -1000,16 +1000,25 @@ __device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, con
 #pragma unroll
     for (int t = 0; t < KK; ++t) acc[t] = group_sum(acc[t], gl2);
     DSTAMP(113);
-    if (on && g == 0) {
+    if (on) {  // every lane of the group holds all K*K sums: lane g stores the taps g, g + Gq, ...
       const int i = rank + ab * G;
-      const int slot = full ? j * Mi + i : csc_slot[csc_ptr[i] + e];
+      // where the filter goes: with a full table the filters of input map i lie side by side as plain floats,
+      // [i][j][tap] (one run of whole cache lines per map, and a flag per map once they have landed; the reader
+      // picks its row out of the Mi runs); with a sparse table as tagged words at their place in table order
+      const size_t at = full ? ((size_t)i * Mo + j) * KK : (size_t)csc_slot[csc_ptr[i] + e] * KK;
       float* w = wb + (ab * pitch + e) * KK;
+      float wv[KK];   // (all of the filter read at once: one LDS latency instead of one per tap)
 #pragma unroll
-      for (int t = 0; t < KK; ++t) {   // natural tap t lies at KK-1-t of the rotated copy
-        const float v = fmaf(-lr, acc[t], w[KK - 1 - t]);
-        w[KK - 1 - t] = v;
-        put_f(xw + (size_t)slot * KK + t, v, tag);
-      }
+      for (int t = 0; t < KK; ++t) wv[t] = w[KK - 1 - t];   // natural tap t lies at KK-1-t of the rotated copy
+#pragma unroll
+      for (int t = 0; t < KK; ++t) wv[t] = fmaf(-lr, acc[t], wv[t]);
+#pragma unroll
+      for (int t = 0; t < KK; ++t)
+        if ((t & (Gq - 1)) == g) {
+          w[KK - 1 - t] = wv[t];
+          if (full) __hip_atomic_store((gfloat*)xw + at + t, wv[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          else put_f(xw + at + t, wv[t], tag);
+        }
     }
     DSTAMP(114);
   }
@@ -1483,15 +1492,24 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       const int* ncb = (const int*)(lds + C.o_ncb);
       const bool full = C.full_table != 0;
       const FDiv dKK(KK);
+      const size_t n_w = (full ? (size_t)C.Mo * Mi : (size_t)P.csr_ptr[C.Mo]) * KK;
       for (int ab = 0; ab < nb; ++ab) {
         const int i = rank + ab * G, ne = ncb[ab];
         const int eb = full ? 0 : P.csc_ptr[i];
-        gtagged* dst = P.x_w + (size_t)(tagw & 1u) * (full ? (size_t)C.Mo * Mi : (size_t)P.csr_ptr[C.Mo]) * KK;
+        gtagged* dst = P.x_w + (size_t)(tagw & 1u) * n_w;
+        gfloat* dstf = bulk_data(P.x_w, (int)n_w, tagw & 1u);
         for (int x = tid; x < ne * KK; x += WG) {
           const int e = dKK.div(x), t = x - e * KK;
-          const int slot = full ? bj[ab * pitch + e] * Mi + i : P.csc_slot[eb + e];
-          put_f(dst + (size_t)slot * KK + (KK - 1 - t), wb[(ab * pitch + e) * KK + t], tagw);
+          const float v = wb[(ab * pitch + e) * KK + t];
+          if (full) __hip_atomic_store(dstf + ((size_t)i * C.Mo + bj[ab * pitch + e]) * KK + (KK - 1 - t), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          else put_f(dst + (size_t)P.csc_slot[eb + e] * KK + (KK - 1 - t), v, tagw);
         }
+      }
+      if (full) {
+        stores_done();
+        __syncthreads();
+        guint* fl = bulk_flags(P.x_w, (int)n_w, Mi, tagw & 1u);
+        for (int ab = tid; ab < nb; ab += WG) __hip_atomic_store(fl + rank + ab * G, tagw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     };
     auto take_rows = [&](auto lc, unsigned int tagw) __attribute__((always_inline)) -> bool {
@@ -1505,10 +1523,42 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       const gtagged* src0 = P.x_w + (size_t)(tagw & 1u) * (full ? (size_t)C.Mo * Mi : (size_t)P.csr_ptr[C.Mo]) * KK;
       for (int am = 0; am < nm; ++am) {
         const int j = rank + am * G;
-        const size_t cb = full ? (size_t)j * Mi : (size_t)P.csr_ptr[j];
-        if (!gather(rt, (unsigned int*)(lds + C.o_wf + am * C.max_conn * KK), src0 + cb * KK, ncf[am] * KK, tagw)) return false;
+        unsigned int* dst = (unsigned int*)(lds + C.o_wf + am * C.max_conn * KK);
+        if (!full) {
+          if (!gather(rt, dst, src0 + (size_t)P.csr_ptr[j] * KK, ncf[am] * KK, tagw)) return false;
+          continue;
+        }
+        // full table: row j is spread over the runs of the Mi input maps, K*K floats in each; wait for every
+        // map's flag (once, for all own maps), then pick the row out
+        const int n = Mi * KK;
+        const size_t n_w = (size_t)C.Mo * Mi * KK;
+        if (am == 0) {
+          const guint* fl = bulk_flags(P.x_w, (int)n_w, Mi, tagw & 1u);
+          for (int m = tid; m < Mi; m += WG) {
+            unsigned int spins = 0;
+            while (__hip_atomic_load(fl + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tagw)
+              if (!poll_again(rt, spins)) break;
+          }
+          __syncthreads();
+          if (sh.fail) return false;
+        }
+        const gfloat* data = bulk_data(P.x_w, (int)n_w, tagw & 1u);
+        const FDiv dKK(KK);
+        for (int base = 0; base < n; base += 4 * WG) {
+          float v[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int x = min(base + tid + u * WG, n - 1);
+            const int c = dKK.div(x);
+            v[u] = __hip_atomic_load(data + ((size_t)c * C.Mo + j) * KK + (x - c * KK), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (base + tid + u * WG < n) ((float*)dst)[base + tid + u * WG] = v[u];
+        }
       }
-      return true;
+      __syncthreads();
+      return sh.fail == 0;
     };
     const bool defer = Z.defer != 0 && !taps && !g_out && train;
     STAMP(0);
@@ -1829,10 +1879,11 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
               const int K = C.K;
               if (K >= 2 && K <= 5) {
                 const bool full = C.full_table != 0;
-                gtagged* xw = P.x_w + (size_t)par * (full ? (size_t)Mo * Mi : (size_t)P.csr_ptr[Mo]) * (K * K);
+                const size_t n_w = (full ? (size_t)Mo * Mi : (size_t)P.csr_ptr[Mo]) * (K * K);
+                gtagged* xw = full ? (gtagged*)bulk_data(P.x_w, (int)n_w, par) : P.x_w + (size_t)par * n_w;
                 auto go = [&](auto k_) __attribute__((always_inline)) {
                   flow_wgrad_entries<decltype(k_)::value>(lds + C.o_wb, (const int*)(lds + C.o_bj), (const int*)(lds + C.o_ncb),
-                      nb, C.back_pitch, lds + Z.o_dall, (const int*)(lds + Z.o_yxall), HW, own, HiWi, C.Wi, C.S + 1, lr, Mi,
+                      nb, C.back_pitch, lds + Z.o_dall, (const int*)(lds + Z.o_yxall), HW, own, HiWi, C.Wi, C.S + 1, lr, Mi, Mo,
                       rank, G, full, P.csc_ptr, P.csc_slot, xw, tag, rt);
                 };
                 switch (K) {
@@ -1842,7 +1893,12 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
                   default: go(IC<5>{}); break;
                 }
                 if (l == 1) DSTAMP(126);
+                if (full) stores_done();
                 __syncthreads();
+                if (full) {  // the runs of the own input maps have landed: their flags go up
+                  guint* fl = bulk_flags(P.x_w, (int)n_w, Mi, par);
+                  for (int ab = tid; ab < nb; ab += WG) __hip_atomic_store(fl + rank + ab * G, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
               } else {
                 wgrad_pull(lc, own);
                 ship_rows(lc, tag);
