@@ -321,7 +321,7 @@ size_t carve(cnn* net, void* base) {
         const size_t small = pooled ? (size_t)A[l + 1].maps * A[l + 1].h * A[l + 1].w : (size_t)A[l].maps * A[l].h * A[l].w;
         words += 3 * 2 * small;  // pooled outputs, deltas, winner coordinates; two images in flight
         words += 2 * 256 * (small / A[l].maps);  // pulled sums of the shares of a map's pull (fewer than 256 of them)
-        words += 2 * (size_t)A[l].maps * A[l - 1].maps * A[l].K * A[l].Kx;  // adjusted filters on their way to the forward copies
+        words += 2 * (size_t)A[l].maps * A[l - 1].maps * (A[l].K * A[l].Kx + 4);  // adjusted filters on their way to the forward copies
         last_maps = A[l].maps;
       } else if (A[l].kind == CNN_LAYER_FC && !first_fc) {
         first_fc = A[l].maps;
@@ -818,7 +818,7 @@ void plan_flow(cnn* net) {
     C.x_yx = (l >= 1) ? xtake(2 * small) : nullptr;
     C.x_part = (l >= 1 && Z.conv[l].pull_shares > 1)
                    ? xtake((size_t)2 * L.Mi * (Z.conv[l].pull_shares - 1) * L.Hi * L.Wi) : nullptr;
-    C.x_w = (l >= 1 && Z.stream) ? xtake((size_t)2 * net->host_tables[l].csr_idx.size() * L.K * L.K) : nullptr;
+    C.x_w = (l >= 1 && Z.stream) ? xtake((size_t)2 * net->host_tables[l].csr_idx.size() * (L.K * L.K + 4)) : nullptr;
   }
   for (int f = 0; f < n_fc; ++f) {
     const LayerDev& L = P.layers[n_conv + f];

@@ -344,6 +344,7 @@ __device__ __forceinline__ bool gather2(const Rt& rt, unsigned int* dst_a, const
 // about to fetch and then loads their floats 128 bits at a time, past the caches.  Layout inside the layer's
 // exchange area of 2 N tagged words (N = Mo Hp Wp): floats [2][N], then flags [2][Mo].
 typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 typedef CNN_GLOBAL unsigned int guint;
 __device__ __forceinline__ gfloat* bulk_data(gtagged* x, int N, unsigned int par) { return (gfloat*)x + (size_t)par * N; }
 __device__ __forceinline__ guint* bulk_flags(gtagged* x, int N, int Mo, unsigned int par) {
@@ -1002,10 +1003,9 @@ __device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, con
     DSTAMP(113);
     if (on) {  // every lane of the group holds all K*K sums: lane g stores the taps g, g + Gq, ...
       const int i = rank + ab * G;
-      // where the filter goes: with a full table the filters of input map i lie side by side as plain floats,
-      // [i][j][tap] (one run of whole cache lines per map, and a flag per map once they have landed; the reader
-      // picks its row out of the Mi runs); with a sparse table as tagged words at their place in table order
-      const size_t at = full ? ((size_t)i * Mo + j) * KK : (size_t)csc_slot[csc_ptr[i] + e] * KK;
+      // where the filter goes: with a sparse table, as tagged words to its place in table order; the filters of a
+      // full table are sent afterwards, all of an input map in one run (ship_rows)
+      const size_t at = full ? 0 : (size_t)csc_slot[csc_ptr[i] + e] * KK;
       float* w = wb + (ab * pitch + e) * KK;
       float wv[KK];   // (all of the filter read at once: one LDS latency instead of one per tap)
 #pragma unroll
@@ -1016,8 +1016,7 @@ __device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, con
       for (int t = 0; t < KK; ++t)
         if ((t & (Gq - 1)) == g) {
           w[KK - 1 - t] = wv[t];
-          if (full) __hip_atomic_store((gfloat*)xw + at + t, wv[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          else put_f(xw + at + t, wv[t], tag);
+          if (!full) put_f(xw + at + t, wv[t], tag);
         }
     }
     DSTAMP(114);
@@ -1488,29 +1487,45 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       const int KK = C.K * C.K, pitch = C.back_pitch, Mi = C.Mi;
       const int nb = sh.pull[l].n_maps;
       const float* wb = lds + C.o_wb;
-      const int* bj = (const int*)(lds + C.o_bj);
       const int* ncb = (const int*)(lds + C.o_ncb);
       const bool full = C.full_table != 0;
-      const FDiv dKK(KK);
-      const size_t n_w = (full ? (size_t)C.Mo * Mi : (size_t)P.csr_ptr[C.Mo]) * KK;
+      if (!full) {  // sparse table: tagged words to their places in table order
+        const FDiv dKK(KK);
+        gtagged* dst = P.x_w + (size_t)(tagw & 1u) * ((size_t)P.csr_ptr[C.Mo] * KK);
+        for (int ab = 0; ab < nb; ++ab) {
+          const int i = rank + ab * G, ne = ncb[ab], eb = P.csc_ptr[i];
+          for (int x = tid; x < ne * KK; x += WG) {
+            const int e = dKK.div(x), t = x - e * KK;
+            put_f(dst + (size_t)P.csc_slot[eb + e] * KK + (KK - 1 - t), wb[(ab * pitch + e) * KK + t], tagw);
+          }
+        }
+        return;
+      }
+      // full table: the filters of input map i as plain floats [i][j][K*K rounded up to a multiple of 4], stored 128
+      // bits a lane so that a wavefront writes whole cache lines (a written-through store of one word is a memory
+      // transaction of its own: sent word by word these were most of the bytes the kernel wrote); then the map's flag
+      const int KKp = (KK + 3) & ~3, U4 = KKp >> 2, Mo = C.Mo;
+      const int n_w = Mi * Mo * KKp;
+      gfloat* data = bulk_data(P.x_w, n_w, tagw & 1u);
+      const FDiv dU4(U4);
       for (int ab = 0; ab < nb; ++ab) {
-        const int i = rank + ab * G, ne = ncb[ab];
-        const int eb = full ? 0 : P.csc_ptr[i];
-        gtagged* dst = P.x_w + (size_t)(tagw & 1u) * n_w;
-        gfloat* dstf = bulk_data(P.x_w, (int)n_w, tagw & 1u);
-        for (int x = tid; x < ne * KK; x += WG) {
-          const int e = dKK.div(x), t = x - e * KK;
-          const float v = wb[(ab * pitch + e) * KK + t];
-          if (full) __hip_atomic_store(dstf + ((size_t)i * C.Mo + bj[ab * pitch + e]) * KK + (KK - 1 - t), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          else put_f(dst + (size_t)P.csc_slot[eb + e] * KK + (KK - 1 - t), v, tagw);
+        const int i = rank + ab * G;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)(data + (size_t)i * Mo * KKp), 0, Mo * KKp * 4, 0x00020000);
+        for (int x = tid; x < Mo * U4; x += WG) {
+          const int e = dU4.div(x), u = x - e * U4;   // (entry e of a full table is output map e)
+          f4v v;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int t = 4 * u + c;   // natural tap t lies at KK-1-t of the rotated copy
+            v[c] = t < KK ? wb[(ab * pitch + e) * KK + (KK - 1 - t)] : 0.f;
+          }
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4v, v), rs, (e * KKp + 4 * u) * 4, 0, 16 /* device scope */);
         }
       }
-      if (full) {
-        stores_done();
-        __syncthreads();
-        guint* fl = bulk_flags(P.x_w, (int)n_w, Mi, tagw & 1u);
-        for (int ab = tid; ab < nb; ab += WG) __hip_atomic_store(fl + rank + ab * G, tagw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+      stores_done();
+      __syncthreads();
+      guint* fl = bulk_flags(P.x_w, n_w, Mi, tagw & 1u);
+      for (int ab = tid; ab < nb; ab += WG) __hip_atomic_store(fl + rank + ab * G, tagw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     auto take_rows = [&](auto lc, unsigned int tagw) __attribute__((always_inline)) -> bool {
       const int l = lv(lc);
@@ -1528,12 +1543,12 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
           if (!gather(rt, dst, src0 + (size_t)P.csr_ptr[j] * KK, ncf[am] * KK, tagw)) return false;
           continue;
         }
-        // full table: row j is spread over the runs of the Mi input maps, K*K floats in each; wait for every
-        // map's flag (once, for all own maps), then pick the row out
-        const int n = Mi * KK;
-        const size_t n_w = (size_t)C.Mo * Mi * KK;
+        // full table: row j is spread over the runs of the Mi input maps, one padded filter in each; wait for every
+        // map's flag (once, for all own maps), then pick the row out, 128 bits a lane
+        const int KKp = (KK + 3) & ~3, U4 = KKp >> 2;
+        const int n_w = Mi * C.Mo * KKp;
         if (am == 0) {
-          const guint* fl = bulk_flags(P.x_w, (int)n_w, Mi, tagw & 1u);
+          const guint* fl = bulk_flags(P.x_w, n_w, Mi, tagw & 1u);
           for (int m = tid; m < Mi; m += WG) {
             unsigned int spins = 0;
             while (__hip_atomic_load(fl + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tagw)
@@ -1542,19 +1557,16 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
           __syncthreads();
           if (sh.fail) return false;
         }
-        const gfloat* data = bulk_data(P.x_w, (int)n_w, tagw & 1u);
-        const FDiv dKK(KK);
-        for (int base = 0; base < n; base += 4 * WG) {
-          float v[4];
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)bulk_data(P.x_w, n_w, tagw & 1u), 0, n_w * 4, 0x00020000);
+        const FDiv dU4(U4);
+        float* wrow = (float*)dst;
+        for (int x = tid; x < Mi * U4; x += WG) {
+          const int c = dU4.div(x), u = x - c * U4;
+          const u4v raw = __builtin_amdgcn_raw_buffer_load_b128(rs, ((c * C.Mo + j) * KKp + 4 * u) * 4, 0, 16 /* device scope */);
+          const f4v v = __builtin_bit_cast(f4v, raw);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int x = min(base + tid + u * WG, n - 1);
-            const int c = dKK.div(x);
-            v[u] = __hip_atomic_load(data + ((size_t)c * C.Mo + j) * KK + (x - c * KK), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            if (base + tid + u * WG < n) ((float*)dst)[base + tid + u * WG] = v[u];
+          for (int cc = 0; cc < 4; ++cc)
+            if (4 * u + cc < KK) wrow[c * KK + 4 * u + cc] = v[cc];
         }
       }
       __syncthreads();
@@ -1879,8 +1891,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
               const int K = C.K;
               if (K >= 2 && K <= 5) {
                 const bool full = C.full_table != 0;
-                const size_t n_w = (full ? (size_t)Mo * Mi : (size_t)P.csr_ptr[Mo]) * (K * K);
-                gtagged* xw = full ? (gtagged*)bulk_data(P.x_w, (int)n_w, par) : P.x_w + (size_t)par * n_w;
+                gtagged* xw = full ? nullptr : P.x_w + (size_t)par * ((size_t)P.csr_ptr[Mo] * (K * K));
                 auto go = [&](auto k_) __attribute__((always_inline)) {
                   flow_wgrad_entries<decltype(k_)::value>(lds + C.o_wb, (const int*)(lds + C.o_bj), (const int*)(lds + C.o_ncb),
                       nb, C.back_pitch, lds + Z.o_dall, (const int*)(lds + Z.o_yxall), HW, own, HiWi, C.Wi, C.S + 1, lr, Mi, Mo,
@@ -1893,12 +1904,8 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
                   default: go(IC<5>{}); break;
                 }
                 if (l == 1) DSTAMP(126);
-                if (full) stores_done();
                 __syncthreads();
-                if (full) {  // the runs of the own input maps have landed: their flags go up
-                  guint* fl = bulk_flags(P.x_w, (int)n_w, Mi, par);
-                  for (int ab = tid; ab < nb; ab += WG) __hip_atomic_store(fl + rank + ab * G, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+                if (full) ship_rows(lc, tag);
               } else {
                 wgrad_pull(lc, own);
                 ship_rows(lc, tag);

@@ -1,11 +1,16 @@
 #!/usr/bin/env python3
 """Per-stage time, algorithmic work and fraction of the fp32 / HBM roofline of one on-line
-training step, for every workload, as a markdown table on stdout.
+training step, for every workload, as markdown tables on stdout.
 
     python3 per_layer_report.py > per_layer.md
 
-Times are the device-side stage timers of CNN_MODE_PERSISTENT (microseconds workgroup 0 spends
-on a stage's work items in the last image of a call; best of five calls of 64 images).  Work is
+A network that runs in resident mode (what bench.py times it in) gets the time line of rank 0 through one image
+-- device clock stamps around every phase of the resident kernel, best of five calls of 64 images -- with the
+multiply-adds of the phases that have any, and what share of the fp32 peak of ONE compute unit's share of the team
+that is.  Every network also gets the stage table of CNN_MODE_PERSISTENT (same stage functions as the one-launch-
+per-stage mode, which is what bench.py times the networks in that resident mode cannot take; there the kernel
+trace under profiles/ has the per-launch figures): microseconds workgroup 0 spends
+on a stage's work items in the last image of a call; best of five calls of 64 images.  Work is
 algorithmic: the multiply-adds and compulsory bytes of the stage as the method defines it (the
 delta pull is scored against the dense rectangle it multiplies, the weight gradients against
 the pooling winners only).  Bound = fp32 peak (157.3 TFLOP/s) when FLOP/B exceeds the machine
@@ -25,6 +30,60 @@ from paper_1102_0183_amd import binding, synth
 PEAK_F32 = 157.3e12
 PEAK_HBM = 8e12
 out = []
+
+
+def resident_phases(name, wl, g, d_imgs, d_labs, layers):
+    """Time line of rank 0 through the last image but one of a call in resident mode."""
+    g.set_mode(binding.MODE_RESIDENT)
+    n_conv = sum(1 for d in layers if d["kind"] == 1)
+    best = None
+    for rep in range(5):
+        g.train_many(d_imgs, d_labs, wl.lr); g.synchronize()
+        st = g.raw_stamps(128).astype(np.int64)
+        if best is None or st[60] - st[0] < best[60] - best[0]:
+            best = st
+    st = best
+    convs = [d for d in layers if d["kind"] == 1]
+    fcs = [d for d in layers if d["kind"] == 3]
+    fwd = lambda d: (d["nconn"] * d["K"] ** 2 * d["h"] * d["w"]) if d["kind"] == 1 else d["maps"] * d["prev"]["maps"] * d["prev"]["h"] * d["prev"]["w"]
+    lab = lambda d: ("%dC%d" % (d["maps"], d["K"])) if d["kind"] == 1 else "%dN" % d["maps"]
+    rows = [(1, "image into LDS", 0)]
+    for l, d in enumerate(convs):
+        rows.append((2 + 2 * l, "FP %s: inputs at hand (adjustments put off from the last image run here)" % lab(d), 0))
+        rows.append((3 + 2 * l, "FP %s: multiply-adds, activation, pooling, outputs on their way" % lab(d), 2 * fwd(d)))
+    rows += [(30, "FP %s: partial sums over the own columns, on their way" % lab(fcs[0]), 2 * fwd(fcs[0])),
+             (31, "FP %s: partial sums of all ranks added" % lab(fcs[0]), 0),
+             (32, "FP remaining fully connected layers", 2 * sum(fwd(d) for d in fcs[1:])),
+             (33, "output units, error, output delta", 0),
+             (34, "BP + AW remaining fully connected layers", 4 * sum(fwd(d) for d in fcs[1:])),
+             (35, "BP + AW %s (own columns), deltas of the last conv layer on their way" % lab(fcs[0]), 4 * fwd(fcs[0]))]
+    for l in range(n_conv - 1, -1, -1):
+        d = convs[l]
+        rows.append((40 + 4 * l, "%s: deltas on their way%s" % (lab(d), " (before that: AW of the pull copy of the layer above)" if l + 1 < n_conv else ""), 0))
+        rows.append((41 + 4 * l, "AW %s, forward copy / biases" % lab(d), 2 * fwd(d) // max(1, d["Kp"] ** 2) if l == 0 else 0))
+        if l >= 1:
+            rows.append((42 + 4 * l, "BP through %s: deltas of all maps at hand" % lab(d), 0))
+            rows.append((43 + 4 * l, "BP through %s: pull into the own maps below" % lab(d), 2 * fwd(d)))
+    rows.append((60, "end of image (AW of the last pull copy before it)", 0))
+    t0 = int(st[0])
+    ranks = g.resident_ranks()
+    out.append("### %s  `%s`  resident mode, %d ranks%s: %.1f us per image as rank 0 sees it" %
+               (name, wl.arch, ranks, ", inputs streamed" if g.resident_streams() else "", (int(st[60]) - t0) * 0.01))
+    out.append("")
+    out.append("| phase of rank 0 | at us | took us | MFLOP (whole team) | % of fp32 peak of the team's compute units |")
+    out.append("|---|---|---|---|---|")
+    prev = t0
+    for i, what, fl in sorted(rows, key=lambda r: int(st[r[0]])):
+        t = int(st[i])
+        if t < t0 or t == 0:
+            continue
+        took = (t - prev) * 0.01
+        frac = (fl / (took * 1e-6) / (PEAK_F32 * ranks / 256.0)) if (fl and took > 0) else None
+        out.append("| %s | %.2f | %.2f | %s | %s |" % (what, (t - t0) * 0.01, took, ("%.3f" % (fl / 1e6)) if fl else "", ("%.2f" % (100 * frac)) if frac else ""))
+        prev = t
+    out.append("")
+
+
 for name in ("cfg1", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"):
     wl = synth.WORKLOADS[name]
     n = 64
@@ -61,6 +120,9 @@ for name in ("cfg1", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"):
             full = d["maps"] * d["prev"]["maps"]
             d["nconn"] = int(table.sum()) if (table is not None and conv_i == wl.sparse_conv) else full
             conv_i += 1
+    if g.mode_supported(binding.MODE_RESIDENT):
+        resident_phases(name, wl, g, d_imgs, d_labs, layers)
+        g.set_mode(binding.MODE_PERSISTENT)
     lines = [ln for ln in g.plan_text().strip().split("\n")]
     kinds = [(ln.split()[1], int(re.search(r"layer=(\d+)", ln).group(1))) for ln in lines]
     if len(kinds) != len(st):

@@ -81,6 +81,7 @@ def main():
         per_call.append(time.perf_counter() - t0)
     print("probe done: %s, %s mode, %d calls of %d images; best call %.2f us per image (host clock)" %
           (args.workload, args.mode, args.calls, n, min(per_call) / n * 1e6), flush=True)
+    net.close()
 
 
 if __name__ == "__main__":
