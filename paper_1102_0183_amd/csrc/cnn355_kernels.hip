@@ -1317,8 +1317,10 @@ __device__ __forceinline__ void run_item(const ProgramDev& P, const Stage& st, i
 // them).  The matrix-core pull is not compiled into the persistent kernel at all: with it the
 // register allocation of every stage suffers (measured: all stages 1.5 x slower); the host plans
 // it for the stage-launch mode only.
+// (Forced inline: as a called function it would get the program and stage descriptors in vector registers and
+// every stage would fetch its operands' addresses with per-lane loads -- measured, all stages 2 x slower.)
 template <bool MM>
-__device__ void run_stage_items(const ProgramDev& P, const Stage& st, int first, int step,
+__device__ __forceinline__ void run_stage_items(const ProgramDev& P, const Stage& st, int first, int step,
                                 const Ctx& ctx, StatusDev* status, float* lds) {
   if constexpr (MM) {
     switch (st.kind) {
