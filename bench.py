@@ -49,19 +49,26 @@ PAPER_NETS = [
 
 
 def measured_traffic(kernel, cfg, batch):
-    """HBM bytes per launch from a committed rocprofv3 --pmc summary (a text file with a line
-    'traffic_bytes_per_launch: N batch: B'), with the file's name; (None, None) when there is none."""
-    name = "%s_%s_train_traffic.txt" % (kernel, cfg)
-    path = os.path.join(ROOT, "profiles", name)
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                f = line.split()
-                if int(f[3]) == batch:
-                    return int(f[1]), "profiles/" + name
-    except (OSError, ValueError, IndexError):
-        pass
-    return None, None
+    """HBM bytes from a committed rocprofv3 --pmc summary (a text file with lines
+    'traffic_bytes_per_launch: N batch: B', one per measured number B of images per call).
+    Returns (bytes per launch at this batch or None, bytes per image, the B that figure was measured at,
+    file name); all None when there is no file."""
+    per_launch, per_image, at, src = None, None, None, None
+    for name in ("%s_%s_train_traffic.txt" % (kernel, cfg), "%s_%s_train.txt" % (kernel, cfg)):
+        try:
+            for line in open(os.path.join(ROOT, "profiles", name)):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    f = line.split()
+                    n, b = int(f[1]), int(f[3])
+                    if b == batch:
+                        per_launch = n
+                    if at is None or b == batch:
+                        per_image, at, src = round(n / b), b, "profiles/" + name
+        except (OSError, ValueError, IndexError):
+            pass
+        if src:
+            break
+    return per_launch, per_image, at, src
 
 
 def layer_work(info, n_conn):
@@ -309,7 +316,8 @@ def main():
                    "persistent": "k_persistent (one cooperative launch per call)",
                    "stages": "one launch per stage: " + ", ".join(
                        sorted({ln.split()[1] for ln in net.plan_text().strip().split("\n") if ln.strip()}))}[mode]
-        traffic, src = measured_traffic(KERNEL_OF_MODE[mode].split()[0] if mode != "stages" else "stage_kernels", name, n_train)
+        traffic, traffic_image, traffic_at, src = measured_traffic(
+            KERNEL_OF_MODE[mode].split()[0] if mode != "stages" else "stage_kernels", name, n_train)
         rec = {
             "name": name, "arch": arch, "mode": mode, "kernels": kernels,
             "train": {"images_per_s": round(1e6 / us_train, 1), "us_per_image": round(us_train, 2), "images": n_train},
@@ -322,7 +330,8 @@ def main():
             "bound": bound, "t_at_fp32_peak_us": round(t_f32, 3), "t_at_hbm_peak_us": round(t_hbm, 3),
             "frac": round(t_bound / us_train, 5),
             "dependency_bound": dependency_bound(net, mode, info, us_train, floors),
-            "traffic": traffic, "traffic_source": src,
+            "traffic": traffic, "traffic_bytes_per_image": traffic_image, "traffic_measured_at_images_per_call": traffic_at,
+            "traffic_source": src,
         }
         if note:
             rec["paper_context"] = note
@@ -372,7 +381,9 @@ def main():
     bytes_img = algorithmic_bytes_per_train_image(info, net.num_weights, net.image_size, first_w)
     flop_img = train_flop(work)
     achieved = bytes_img * B / (kern_ms * 1e-3) / 1e9
-    traffic, traffic_src = measured_traffic(KERNEL_OF_MODE[mode].split()[0], args.headline, B)
+    traffic, _, _, traffic_src = measured_traffic(KERNEL_OF_MODE[mode].split()[0], args.headline, B)
+    if traffic is None:
+        traffic_src = None
     roofline = {
         "bound": "hbm", "kernel": KERNEL_OF_MODE[mode],
         "achieved": round(achieved, 3), "peak": HBM_PEAK_GBS, "unit": "GB/s",
