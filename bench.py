@@ -496,6 +496,28 @@ def main():
         extra["%s_train_step_calls_images_per_s" % args.headline] = round(nstep / (time.perf_counter() - t0), 1)
         net.close()
         nets.remove(net)
+        # a network the library holds no kernel for: the resident kernel that reads its plan against the one
+        # compiled for that network alone and loaded as a code object (paper_1102_0183_amd/specialize.py)
+        from paper_1102_0183_amd import specialize
+        arch_o = specialize.EXAMPLES["narrow"][0]
+        net = binding.Cnn(arch_o)
+        nets.append(net)
+        rng = np.random.default_rng(7)
+        net.set_weights(((rng.random(net.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
+        net.set_mode(binding.MODE_RESIDENT)
+        n_o = 2000
+        d_io = torch.from_numpy(rng.uniform(-1, 1, (n_o, net.image_size)).astype(np.float32)).to(dev)
+        d_lo = torch.from_numpy(rng.integers(0, net.num_classes, n_o).astype(np.int32)).to(dev)
+        net.train_many(d_io, d_lo, 1e-3)
+        ms_plan = min(event_ms(torch, lambda: net.train_many(d_io, d_lo, 1e-3)) for _ in range(3))
+        specialize.specialize(net)
+        net.train_many(d_io, d_lo, 1e-3)
+        ms_code = min(event_ms(torch, lambda: net.train_many(d_io, d_lo, 1e-3)) for _ in range(3))
+        extra["other_net_arch"] = arch_o
+        extra["other_net_kernel_reading_its_plan_us_per_image"] = round(1e3 * ms_plan / n_o, 2)
+        extra["other_net_kernel_compiled_for_it_us_per_image"] = round(1e3 * ms_code / n_o, 2)
+        net.close()
+        nets.remove(net)
         out["extra"] = extra
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores

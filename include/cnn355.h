@@ -294,6 +294,29 @@ int cnn_get_stage_times(cnn_t* net, float* host_us, int max_stages, int* n_stage
 int cnn_measure_crossing(cnn_t* net, int n_ranks, int words_per_rank, int rounds, float* host_us);
 int cnn_measure_launch(cnn_t* net, int rounds, float* host_us);
 
+/* ---- a resident kernel compiled for the handle's own network ---------------------------------
+ * The resident mode (spec: the whole on-line step of Sec. 3.2 - 3.4 without per-stage launches) runs a
+ * benchmark network in a kernel compiled for it, every size, offset and trip count a literal, and any other
+ * network in a kernel that reads its plan at run time, at about 1.5 x the time per image.  These calls give
+ * any network the first kind of kernel:
+ *   cnn_resident_spec_source: writes into host_buf (n bytes, NUL-terminated, truncated if too small) the text of
+ *     a C++ header that describes this handle's network as it stands now (layer shapes, connection-table
+ *     statistics, output variant, team) to the library's own kernel source, and returns the length of the whole
+ *     text (call with n = 0 to size the buffer).  CNN_E_STATE when resident mode cannot run the network.
+ *     Compiling csrc/cnn355_flow.hip for gfx950, device code only, with -DCNN355_SPECIAL_HEADER="<path of that
+ *     header>" gives a code object (paper_1102_0183_amd/specialize.py does both steps and keeps the result).
+ *   cnn_load_resident_code: loads such a code object (host_path: a file) into the handle.  The plan compiled into
+ *     it must equal the handle's own plan word for word, else CNN_E_STATE and nothing changes; a file that is no
+ *     such code object gives CNN_E_ARG.  From then on resident-mode calls run that kernel; whenever the plan changes
+ *     (another table, output variant or team) the handle falls back to the compiled-in kernels by itself and
+ *     returns to the loaded one when the plan is that one again.  Results are bit for bit those of the compiled-in
+ *     kernels (same source, same order of operations).  Synchronises.  The code object stays loaded until
+ *     cnn_destroy or the next cnn_load_resident_code.
+ *   cnn_resident_code_active: 1 while resident-mode calls would run the loaded kernel, else 0. */
+int cnn_resident_spec_source(const cnn_t* net, char* host_buf, size_t n);
+int cnn_load_resident_code(cnn_t* net, const char* host_path);
+int cnn_resident_code_active(const cnn_t* net);
+
 /* Forward + backward for (d_image, label) with the update replaced by a store of dE/dw:
  * host_grad receives cnn_num_weights floats in canonical order; weights are unchanged. */
 int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad);

@@ -80,6 +80,9 @@ def lib():
             "cnn_get_stage_times": (C.c_int, [vp, vp, C.c_int, vp]),
             "cnn_measure_crossing": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, vp]),
             "cnn_measure_launch": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_resident_spec_source": (C.c_int, [vp, vp, C.c_size_t]),
+            "cnn_load_resident_code": (C.c_int, [vp, C.c_char_p]),
+            "cnn_resident_code_active": (C.c_int, [vp]),
             "cnn_last_error": (C.c_char_p, [vp]),
         }
         for name, (res, args) in sig.items():
@@ -100,6 +103,7 @@ EXPORTS = ["cnn_arch_info", "cnn_arch_info_xy", "cnn_workspace_bytes", "cnn_plan
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
            "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times", "cnn_measure_crossing", "cnn_measure_launch",
+           "cnn_resident_spec_source", "cnn_load_resident_code", "cnn_resident_code_active",
            "cnn_deform_images", "cnn_last_error"]
 
 
@@ -192,6 +196,19 @@ def resident_plan(arch, fan_in=0, n_ranks=0, xcd_stride=0):
         else:
             plan["numbers"][w[0]] = int(w[1])
     return plan
+
+
+def resident_spec_source_for(arch, fan_in=0, n_ranks=0, xcd_stride=0):
+    """Development aid, host-only: what Cnn.resident_spec_source() returns for a handle of this architecture with the
+    tables of resident_plan() and the default output units, on a device of 256 compute units."""
+    f = lib().cnn355_resident_spec_source_for
+    f.restype = C.c_int
+    f.argtypes = [C.c_char_p, C.c_int, C.c_int, C.c_int, C.c_char_p, C.c_size_t]
+    buf = C.create_string_buffer(1 << 16)
+    rc = f(arch.encode(), fan_in, n_ranks, xcd_stride, buf, len(buf))
+    if rc < 0:
+        raise CnnError(rc, "cnn355_resident_spec_source_for(%r)" % arch, _err())
+    return buf.value.decode()
 
 
 class Cnn:
@@ -375,6 +392,23 @@ class Cnn:
         us = C.c_float(0)
         self._ck(lib().cnn_measure_launch(self._h, int(rounds), C.byref(us)), "cnn_measure_launch")
         return us.value
+
+    def resident_spec_source(self):
+        """The header text that describes this handle's network to the resident kernel's source (see specialize.py)."""
+        n = lib().cnn_resident_spec_source(self._h, None, 0)
+        if n < 0:
+            raise CnnError(n, "cnn_resident_spec_source", _err(None))
+        buf = C.create_string_buffer(n + 1)
+        lib().cnn_resident_spec_source(self._h, buf, n + 1)
+        return buf.value.decode()
+
+    def load_resident_code(self, path):
+        """Run resident-mode calls in the kernel of the code object at `path`, compiled for this handle's plan."""
+        self._ck(lib().cnn_load_resident_code(self._h, os.fsencode(path)), "cnn_load_resident_code")
+
+    @property
+    def resident_code_active(self):
+        return bool(lib().cnn_resident_code_active(self._h))
 
     def forward_batch_static(self, d_images, n, d_probs, batch):
         """forward_batch with the scratch memory taken from the library's own device array (at most

@@ -251,6 +251,11 @@ struct cnn {
   FlowPtrs flow_ptrs;           // where the layers and the exchange buffers lie on the device
   FlowPtrs* d_flow_ptrs = nullptr;
   int flow_static_id = 0;       // > 0: the plan equals that of a kernel compiled for a fixed network
+  // a resident kernel compiled for this handle's own network and loaded from a code object
+  hipModule_t special_module = nullptr;
+  hipFunction_t special_func = nullptr;
+  FlowSpec special_plan;        // the plan that code object was compiled for
+  bool special_active = false;  // the current plan equals it: calls go to special_func
   tagged_t* d_xbuf = nullptr;   // every exchange buffer, one after the other
   size_t xbuf_words = 0;
   bool flow_ok = false;
@@ -774,6 +779,7 @@ void plan_flow(cnn* net) {
   std::memset(&Q, 0, sizeof(Q));
   net->flow_ok = false;
   net->flow_static_id = 0;
+  net->special_active = false;
   auto no = [&](const std::string& why) { net->flow_why = why; };
   int n_conv = 0;
   while (n_conv < P.n_layers && P.layers[n_conv].kind == L_CONV) ++n_conv;
@@ -829,6 +835,7 @@ void plan_flow(cnn* net) {
   if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
   if (xb && !Q.xp) return no("internal: an exchange buffer was not laid out");
   net->flow_static_id = resident_static_id(Z);
+  net->special_active = net->special_func != nullptr && std::memcmp(&Z, &net->special_plan, sizeof(FlowSpec)) == 0;
   net->flow_ok = true;
   net->flow_why.clear();
 }
@@ -901,6 +908,19 @@ int persistent_grid(const cnn* net, int train) {
   return std::max(1, std::min(most, net->n_cu));
 }
 
+// The resident kernel of this handle: the one loaded for its own network when the plan is still the one that was
+// compiled for, else a compiled-in one (for a benchmark network, or the one that reads its plan).
+static hipError_t launch_resident_of(cnn* net, int grid, size_t lds_bytes, const RunArgs& a) {
+  if (!net->special_active)
+    return launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->flow, net->d_flow_ptrs, net->d_status, a);
+  RunArgs args = a;
+  FlowSpec plan = net->flow;
+  const FlowPtrs* d_ptrs = net->d_flow_ptrs;
+  StatusDev* d_status = net->d_status;
+  void* params[] = {(void*)&plan, (void*)&d_ptrs, (void*)&d_status, (void*)&args};
+  return hipModuleLaunchCooperativeKernel(net->special_func, (unsigned)grid, 1, 1, WG, 1, 1, (unsigned)lds_bytes, net->stream, params);
+}
+
 int run(cnn* net, const RunArgs& a0) {
   RunArgs a = a0;
   a.spin_limit = net->spin_limit;
@@ -921,8 +941,7 @@ int run(cnn* net, const RunArgs& a0) {
     if (!P.has_frontend) {
       a.epoch_base = (unsigned int)net->epoch;
       net->epoch += n;
-      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->flow, net->d_flow_ptrs,
-                                   net->d_status, a));
+      HIP_TRY(net, launch_resident_of(net, grid, lds_bytes, a));
       return CNN_OK;
     }
     // fixed front-end: computed for FE_BATCH images at a time by all compute units, outside the
@@ -941,8 +960,7 @@ int run(cnn* net, const RunArgs& a0) {
       b.n_images = nb;
       b.epoch_base = (unsigned int)net->epoch;
       net->epoch += (unsigned long long)nb;
-      HIP_TRY(net, launch_resident(net->flow_static_id, grid, lds_bytes, net->stream, net->flow, net->d_flow_ptrs,
-                                   net->d_status, b));
+      HIP_TRY(net, launch_resident_of(net, grid, lds_bytes, b));
       if (t0 + nb >= n)  // parity tap: layer 0 of the last image
         HIP_TRY(net, hipMemcpyAsync(net->d_fe_out, net->d_fe_batch + (size_t)(nb - 1) * fe_sz, fe_sz * sizeof(float),
                                     hipMemcpyDeviceToDevice, net->stream));
@@ -1222,6 +1240,7 @@ int cnn_create(const char* arch, void* d_workspace, size_t bytes, void* hip_stre
 void cnn_destroy(cnn_t* net) {
   if (!net) return;
   (void)hipStreamSynchronize(net->stream);
+  if (net->special_module) (void)hipModuleUnload(net->special_module);
   delete net;
 }
 
@@ -1358,6 +1377,83 @@ int cnn_mode_supported(cnn_t* net, int mode) {
 
 int cnn_get_mode(const cnn_t* net) { return net ? net->mode : CNN_E_ARG; }
 
+// ---- a resident kernel compiled for the handle's own network -----------------------------------------
+// The text of a header that gives cnn355_flowspec.h the network of this handle as StaticSpec<FLOW_SPECIAL_ID>:
+// the same inputs plan_flow() hands the planner, so the compiler arrives at the same plan.
+int cnn_resident_spec_source(const cnn_t* net, char* buf, size_t n) {
+  if (!net) return fail(nullptr, CNN_E_ARG, "net is NULL");
+  if (!net->flow_ok) return fail(nullptr, CNN_E_STATE, "resident mode cannot run this network: " + net->flow_why);
+  const FlowSpec& Z = net->flow;
+  std::string t = "// written by cnn_resident_spec_source\n";
+  t += "constexpr FlowSpec flow_special_spec() {\n  FlowSpec Z{};\n";
+  auto set = [&](const std::string& name, int v) { t += "  Z." + name + " = " + std::to_string(v) + ";\n"; };
+  set("n_conv", Z.n_conv); set("n_fc", Z.n_fc); set("n_classes", Z.n_classes); set("out_units", Z.out_units);
+  for (int l = 0; l < Z.n_conv; ++l) {
+    const ConvSpec& C = Z.conv[l];
+    const std::string c = "conv[" + std::to_string(l) + "].";
+    set(c + "Mi", C.Mi); set(c + "Hi", C.Hi); set(c + "Wi", C.Wi); set(c + "Mo", C.Mo); set(c + "Ho", C.Ho); set(c + "Wo", C.Wo);
+    set(c + "K", C.K); set(c + "S", C.S); set(c + "Kp", C.Kp); set(c + "Hp", C.Hp); set(c + "Wp", C.Wp);
+    set(c + "max_conn", C.max_conn); set(c + "max_back", C.max_back); set(c + "full_table", C.full_table);
+  }
+  for (int f = 0; f < Z.n_fc; ++f) {
+    const std::string c = "fc[" + std::to_string(f) + "].";
+    set(c + "n_in", Z.fc[f].n_in); set(c + "n_out", Z.fc[f].n_out); set(c + "is_output", Z.fc[f].is_output);
+  }
+  t += "  flow_plan(Z, " + std::to_string(net->team_ranks) + ", " + std::to_string(net->team_stride) + ", " +
+       std::to_string(net->n_cu > 0 ? net->n_cu : 256) + ");\n  return Z;\n}\n";
+  t += "template <>\nstruct StaticSpec<FLOW_SPECIAL_ID> {\n  static constexpr FlowSpec value = flow_special_spec();\n};\n";
+  if (buf && n > 0) {
+    const size_t k = std::min(n - 1, t.size());
+    std::memcpy(buf, t.data(), k);
+    buf[k] = 0;
+  }
+  return (int)t.size();
+}
+
+int cnn_load_resident_code(cnn_t* net, const char* path) {
+  if (!net || !path) return fail(net ? &net->err : nullptr, CNN_E_ARG, "NULL argument");
+  if (!net->d_status) return fail(&net->err, CNN_E_STATE, "cnn_load_resident_code: the handle has no workspace");
+  if (!net->flow_ok) return fail(&net->err, CNN_E_STATE, "resident mode cannot run this network: " + net->flow_why);
+  int device = -1;
+  HIP_TRY(net, hipGetDevice(&device));
+  if (device != net->device)
+    return fail(&net->err, CNN_E_STATE, "cnn_load_resident_code: the current device is not the one the network was created on");
+  HIP_TRY(net, hipStreamSynchronize(net->stream));
+  hipModule_t mod = nullptr;
+  if (hipModuleLoad(&mod, path) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(&net->err, CNN_E_ARG, std::string("cannot load a gfx950 code object from ") + path);
+  }
+  auto drop = [&](int code, const std::string& why) { (void)hipModuleUnload(mod); return fail(&net->err, code, why); };
+  hipDeviceptr_t d_plan = nullptr;
+  size_t bytes = 0;
+  if (hipModuleGetGlobal(&d_plan, &bytes, mod, "cnn355_special_plan") != hipSuccess || bytes != sizeof(FlowSpec)) {
+    (void)hipGetLastError();
+    return drop(CNN_E_ARG, "the code object holds no plan of this library's layout (built from other sources?)");
+  }
+  FlowSpec plan;
+  if (hipMemcpy(&plan, d_plan, sizeof(FlowSpec), hipMemcpyDeviceToHost) != hipSuccess) {
+    (void)hipGetLastError();
+    return drop(CNN_E_HIP, "cannot read the plan out of the code object");
+  }
+  if (std::memcmp(&plan, &net->flow, sizeof(FlowSpec)) != 0)
+    return drop(CNN_E_STATE, "the code object was compiled for another network, table, output variant or team than this "
+                             "handle has now");
+  hipFunction_t f = nullptr;
+  if (hipModuleGetFunction(&f, mod, "_ZN6cnn35510k_residentILi99EEEvNS_8FlowSpecEPKNS_8FlowPtrsEPNS_9StatusDevENS_7RunArgsE") != hipSuccess) {
+    (void)hipGetLastError();
+    return drop(CNN_E_ARG, "the code object holds no resident kernel");
+  }
+  if (net->special_module) (void)hipModuleUnload(net->special_module);
+  net->special_module = mod;
+  net->special_func = f;
+  net->special_plan = plan;
+  net->special_active = true;
+  return CNN_OK;
+}
+
+int cnn_resident_code_active(const cnn_t* net) { return (net && net->flow_ok && net->special_active) ? 1 : 0; }
+
 // development aid, not part of the public header: which compiled-in network the resident plan equals (0: none)
 int cnn355_resident_static_id(const cnn_t* net) { return net ? net->flow_static_id : -1; }
 // development aid: 1 when the resident plan streams the inputs of the layers above the first (0: they stay in LDS)
@@ -1369,9 +1465,7 @@ int cnn355_resident_ranks(const cnn_t* net) { return (net && net->flow_ok) ? net
 // j, j + 1, ..., j + fan_in - 1 (mod M_i).  One line per number ("name value"), per layer ("conv l name value ...")
 // and per LDS region of a rank ("region name first_float floats"); a region's size is restated here from its
 // documented shape, not taken from the planner.
-int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd_stride, char* buf, size_t n) {
-  if (!buf || n == 0) return fail(nullptr, CNN_E_ARG, "buf is NULL");
-  cnn tmp;
+static int plan_only(cnn& tmp, const char* arch, int fan_in, int n_ranks, int xcd_stride) {
   int rc = parse_arch(arch, tmp.arch, nullptr);
   if (rc) return rc;
   carve(&tmp, nullptr);
@@ -1387,7 +1481,24 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
   tmp.team_ranks = n_ranks;
   tmp.team_stride = xcd_stride;
   rc = plan(&tmp);
-  if (rc) { g_err = tmp.err; return rc; }
+  if (rc) g_err = tmp.err;
+  return rc;
+}
+
+// development aid, host only: cnn_resident_spec_source for an architecture without a handle (tables as in
+// cnn355_resident_plan_text), so that code objects can be compiled where there is no GPU
+int cnn355_resident_spec_source_for(const char* arch, int fan_in, int n_ranks, int xcd_stride, char* buf, size_t n) {
+  cnn tmp;
+  const int rc = plan_only(tmp, arch, fan_in, n_ranks, xcd_stride);
+  if (rc) return rc;
+  return cnn_resident_spec_source(&tmp, buf, n);
+}
+
+int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd_stride, char* buf, size_t n) {
+  if (!buf || n == 0) return fail(nullptr, CNN_E_ARG, "buf is NULL");
+  cnn tmp;
+  int rc = plan_only(tmp, arch, fan_in, n_ranks, xcd_stride);
+  if (rc) return rc;
   std::string t;
   auto num = [&](const char* name, long long v) { t += std::string(name) + " " + std::to_string(v) + "\n"; };
   if (!tmp.flow_ok) {

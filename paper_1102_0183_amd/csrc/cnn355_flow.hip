@@ -1938,6 +1938,13 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
   if (!g_out && a.train) flow_store<ID>(rt);
 }
 
+#ifdef CNN355_SPECIAL_HEADER
+// ---- this file compiled for one network alone: its kernel and its plan, nothing else -------------------
+template __global__ void k_resident<FLOW_SPECIAL_ID>(const FlowSpec, const FlowPtrs* __restrict__, StatusDev*, RunArgs);
+extern "C" __device__ __attribute__((used)) const FlowSpec cnn355_special_plan = StaticSpec<FLOW_SPECIAL_ID>::value;
+}  // namespace cnn355
+#else
+
 template <int ID>
 static hipError_t launch_resident_id(int grid, size_t lds_bytes, hipStream_t stream, const FlowSpec& spec,
                                      const FlowPtrs* d_ptrs, StatusDev* d_status, const RunArgs& a) {
@@ -2022,3 +2029,4 @@ int resident_static_id(const FlowSpec& z) {
 }
 
 }  // namespace cnn355
+#endif  // CNN355_SPECIAL_HEADER

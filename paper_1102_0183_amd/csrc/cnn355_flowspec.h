@@ -408,4 +408,13 @@ struct StaticSpec<5> {
   static constexpr FlowSpec value = flow_static_spec(3, 32, 32, 3, conv, 2, fc, 0, 0);
 };
 
+// One more, defined outside this file: the network of a handle, written out by cnn_resident_spec_source() as a
+// header that specialises StaticSpec<FLOW_SPECIAL_ID>.  cnn355_flow.hip compiled with -DCNN355_SPECIAL_HEADER="<that
+// header>" gives a code object that holds k_resident<FLOW_SPECIAL_ID> and its plan (cnn355_special_plan) and nothing
+// else; cnn_load_resident_code() loads it into a handle whose run-time plan equals that plan word for word.
+constexpr int FLOW_SPECIAL_ID = 99;
+#ifdef CNN355_SPECIAL_HEADER
+#include CNN355_SPECIAL_HEADER
+#endif
+
 }  // namespace cnn355

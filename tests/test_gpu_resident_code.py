@@ -1,0 +1,151 @@
+"""Resident kernels compiled for one network and loaded into its handle (cnn_resident_spec_source,
+cnn_load_resident_code; paper_1102_0183_amd/specialize.py): same bits as the compiled-in kernels, parity with the
+oracle, the speed of the kernels the library holds for the benchmark networks, and the error paths.  The code
+objects are the ones tests/test_resident_code_host.py leaves under paper_1102_0183_amd/_spec/ (compiled now if
+they are not there: hipcc needs no GPU, some 10 - 40 s each)."""
+import numpy as np
+import pytest
+
+from paper_1102_0183_amd import binding, specialize
+from tests.parity_helpers import (TOL_ACT, TOL_W100, build_pair, compare_backward_state, compare_forward_state,
+                                  lockstep_train, rel_err, to_dev)
+from tests.resident_code_cases import CASES, table_for
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(name, seed=5):
+    arch, fan = CASES[name]
+    tables = None
+    if fan:
+        import oracle
+        o0 = oracle.Oracle(arch)
+        convs = [l for l in range(1, o0.num_layers) if o0.layer_info(l)["kind"] == 1]
+        tables = {ci: table_for(o0.layer_info(convs[ci])["maps"], o0.layer_info(convs[ci] - 1)["maps"], fan)
+                  for ci in range(1, len(convs))}
+    g, o = build_pair(arch=arch, tables=tables, seed=seed)
+    g.set_mode(binding.MODE_RESIDENT)
+    return g, o
+
+
+def _data(g, n, seed=31):
+    rng = np.random.default_rng(seed)
+    imgs = rng.uniform(-1, 1, (n, g.image_size)).astype(np.float32)
+    labs = rng.integers(0, g.num_classes, size=n).astype(np.int32)
+    return imgs, labs
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_loaded_kernel_gives_the_bits_of_the_compiled_in_one_and_meets_the_oracle(name):
+    print("case", name, CASES[name], flush=True)
+    g, o = _pair(name)
+    imgs, labs = _data(g, 100)
+    w0 = g.get_weights()
+    # the compiled-in kernels first (the one that reads its plan; for the benchmark net the one compiled for it)
+    assert not g.resident_code_active
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    w_builtin = g.get_weights()
+    # the same handle with the kernel compiled for its network
+    g.set_weights(w0)
+    specialize.specialize(g)
+    assert g.resident_code_active
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    w_loaded = g.get_weights()
+    assert np.array_equal(w_builtin, w_loaded), "loaded and compiled-in kernels differ: %.2e" % rel_err(w_loaded, w_builtin)
+    # one step against the oracle, layer by layer, then 100 on-line steps in lock-step
+    g.set_weights(w0)
+    d = to_dev(imgs)
+    g.train_step(d.view(-1)[:g.image_size], int(labs[0]), 0.001)
+    o.forward(imgs[0])
+    compare_forward_state(g, o)
+    o.backward_update(int(labs[0]), 0.001)
+    compare_backward_state(g, o)
+    adopted = lockstep_train(g, o, imgs[1:], labs[1:], 0.001)
+    e = rel_err(g.get_weights(), o.get_weights())
+    print("  weights after 100 steps rel err %.2e, %d winners adopted" % (e, adopted), flush=True)
+    assert e <= TOL_W100 and adopted <= 8
+    g.close()
+
+
+def _us_per_image(g, imgs, labs, reps=3):
+    import torch
+    d_i, d_l = to_dev(imgs), to_dev(labs)
+    g.train_many(d_i, d_l, 0.001)
+    g.synchronize()
+    best = None
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        g.train_many(d_i, d_l, 0.001)
+        b.record()
+        g.synchronize()
+        torch.cuda.synchronize()
+        t = a.elapsed_time(b) * 1e3 / len(labs)
+        best = t if best is None else min(best, t)
+    return best
+
+
+def test_loaded_kernel_is_as_fast_as_the_one_the_library_holds_for_the_benchmark_net():
+    """The benchmark net through its compiled-in kernel and through a code object compiled for it from the same
+    source: within 15 % of each other.  A net the library holds no kernel for: the loaded kernel takes at most 0.8
+    of the time of the kernel that reads its plan, and at most 1.3 x what the benchmark net takes per image (it has
+    1.2 x the maps)."""
+    g, _ = _pair("benchmark")
+    imgs, labs = _data(g, 2000)
+    assert binding.lib().cnn355_resident_static_id(g._h) == 1
+    t_lit = _us_per_image(g, imgs, labs)
+    specialize.specialize(g)
+    assert g.resident_code_active
+    t_loaded = _us_per_image(g, imgs, labs)
+    g.close()
+    g, _ = _pair("narrow")
+    imgs, labs = _data(g, 2000)
+    t_plan = _us_per_image(g, imgs, labs)
+    specialize.specialize(g)
+    t_narrow = _us_per_image(g, imgs, labs)
+    g.close()
+    print("benchmark net: compiled-in %.2f us/image, loaded %.2f; 24/48-map net: reading its plan %.2f, loaded %.2f"
+          % (t_lit, t_loaded, t_plan, t_narrow), flush=True)
+    assert t_loaded <= 1.15 * t_lit
+    assert t_narrow <= 0.8 * t_plan
+    assert t_narrow <= 1.3 * t_lit
+
+
+def test_a_code_object_for_another_plan_is_refused_and_a_changed_plan_falls_back(tmp_path):
+    g, _ = _pair("narrow")
+    path = specialize.specialize(g)
+    assert g.resident_code_active
+    imgs, labs = _data(g, 40)
+    w0 = g.get_weights()
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    w_ref = g.get_weights()
+    # another team: another plan, so the handle goes back to the kernel that reads its plan, with the same result
+    g.set_team(24, 1)
+    assert not g.resident_code_active
+    g.set_weights(w0)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    assert rel_err(g.get_weights(), w_ref) <= 1e-5
+    # loading the code object now is refused: it was compiled for the automatic team
+    with pytest.raises(binding.CnnError) as e:
+        g.load_resident_code(path)
+    assert e.value.code == binding.E_STATE and "another network" in str(e.value)
+    # back to the automatic team: the loaded kernel is used again
+    g.set_team(0, 0)
+    assert g.resident_code_active
+    g.set_weights(w0)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    assert np.array_equal(g.get_weights(), w_ref)
+    g.close()
+    # another network's code object, and a file that is none
+    h, _ = _pair("benchmark")
+    with pytest.raises(binding.CnnError) as e:
+        h.load_resident_code(path)
+    assert e.value.code == binding.E_STATE
+    junk = tmp_path / "junk.hsaco"
+    junk.write_bytes(b"not a code object" * 100)
+    with pytest.raises(binding.CnnError) as e:
+        h.load_resident_code(str(junk))
+    assert e.value.code == binding.E_ARG
+    assert not h.resident_code_active
+    h.train_many(to_dev(_data(h, 8)[0]), to_dev(_data(h, 8)[1]), 0.001)   # still works
+    h.close()
