@@ -1525,7 +1525,7 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
           {"full_table", C.full_table}, {"n_own", C.n_own}, {"n_own_below", C.n_own_below},
           {"pull_shares", C.pull_shares}, {"back_pitch", C.back_pitch}, {"wgrad_R_log2", C.wgrad_R_log2},
           {"pull_chunk", C.pull_chunk}, {"fwd_strip", C.fwd_strip}, {"fwd_rows", C.fwd_rows},
-          {"pull_strip", C.pull_strip}, {"pull_rows", C.pull_rows}, {"in_chunk", C.in_chunk}};
+          {"pull_strip", C.pull_strip}, {"pull_rows", C.pull_rows}, {"in_chunk", C.in_chunk}, {"pull_slots", C.pull_slots}};
       for (const auto& kv : f) t += std::string(" ") + kv.first + " " + std::to_string(kv.second);
       t += "\n";
       if (!(Z.stream && l >= 1)) region(c + "in", C.o_in, (long long)C.Mi * C.Hi * C.Wi);

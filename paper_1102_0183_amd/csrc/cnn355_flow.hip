@@ -1023,6 +1023,84 @@ __device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, con
   }
 }
 
+// ---- BP through a pooled convolutional layer: only the pooling winners carry a delta ------------------
+// Under max-pooling of Kp x Kp one output neuron in Kp^2 has a non-zero delta (Sec. 2.3: the others did not
+// reach the layer above), so the sums of Sec. 3.3 have K^2 HW non-zero terms per connection instead of K^2
+// times the map.  They are formed term by term: a lane takes a winner p of one connection (an entry of an own
+// input map's list), its delta and coordinates, and adds delta * w[ky][kx] at the K^2 input neurons of that
+// winner's receptive field.  The lanes that share a connection hold different winners, i.e. different receptive
+// fields' corners, so at one tap they add at different places; the taps follow one another in program order and
+// LDS serves a wavefront's instructions in order, so every place receives its terms in a fixed order and the
+// result does not depend on timing.  It pays where a pooling rectangle holds 9 or more neurons: a term costs two
+// LDS accesses here, against a third of one and Kp^2 times the terms in the correlation over whole maps.  Connections worked on at the same time (a slot: UW lanes of a wavefront)
+// add into copies of their own of the rank's input maps; the copies are added up afterwards (reduce_partials),
+// in the order of the slots.  Every copy: [n_maps][Hi * Wi].
+template <int ID>
+__device__ __forceinline__ void pull_winners(const Rt& rt, int l, const float* dall, const int* yxall, float* copies,
+                                             int slots, int nb) {
+  DECL_SPEC(Z, rt);
+  const ConvSpec& C = Z.conv[l];
+  float* lds = rt.lds;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = uni_of<ID>(C.K), KK = K * K, HW = uni_of<ID>(C.Hp) * uni_of<ID>(C.Wp), stride = uni_of<ID>(C.S) + 1;
+  const int Wi = uni_of<ID>(C.Wi), HiWi = uni_of<ID>(C.Hi) * Wi, pitch = uni_of<ID>(C.back_pitch);
+  const int parts = (HW + 63) >> 6, UW = (HW + parts - 1) / parts, UPW = 64 / UW;
+  const int tot = nb * HiWi;
+  for (int x = tid; x < slots * tot; x += WG) copies[x] = 0.f;
+  __syncthreads();
+  const FDiv dUW(UW), dP(parts), dPitch(pitch);
+  const int su = dUW.div(lane), pl = lane - su * UW;
+  const int slot = wave * UPW + su;
+  const int* cnt = (const int*)(lds + C.o_ncb);
+  const int* bj = (const int*)(lds + C.o_bj);
+  const float* wb = lds + C.o_wb;
+  const int n_units = nb * pitch * parts;
+  if (su < UPW && slot < slots) {
+    float* mine = copies + slot * tot;
+    for (int u = slot; u < n_units; u += slots) {
+      const int ue = dP.div(u), part = u - ue * parts;
+      const int am = dPitch.div(ue), e = ue - am * pitch;
+      const int p = part * UW + pl;
+      if (e < cnt[am] && p < HW) {
+        const int j = bj[am * pitch + e];
+        const float d = dall[j * HW + p];
+        const int yx = yxall[j * HW + p];
+        float* o = mine + am * HiWi + ((yx >> 16) * stride) * Wi + (yx & 0xffff) * stride;
+        const float* w = wb + (am * pitch + e) * KK + (KK - 1);   // (the copy is rotated: tap t lies at K*K-1-t)
+        // (read, add, write, with the compiler kept from moving the next tap's read above this tap's write:
+        // another lane of the unit may have written that place.  LDS atomic float adds would say the same in one
+        // instruction and take 30 x as long on this hardware: measured.)
+        auto taps = [&](auto k_) __attribute__((always_inline)) {
+          constexpr int KC = decltype(k_)::value;
+          const int Kn = KC ? KC : K;
+          float wr[KC ? KC * KC : 1];
+          if (KC) {
+#pragma unroll
+            for (int t = 0; t < KC * KC; ++t) wr[t] = w[-t];
+          }
+#pragma unroll
+          for (int ky = 0; ky < Kn; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < Kn; ++kx) {
+              float* a = o + ky * Wi + kx;
+              const float v = *a;
+              *a = fmaf(d, KC ? wr[ky * KC + kx] : w[-(ky * Kn + kx)], v);
+              asm volatile("" ::: "memory");
+            }
+        };
+        switch (K) {
+          case 2: taps(IC<2>{}); break;
+          case 3: taps(IC<3>{}); break;
+          case 4: taps(IC<4>{}); break;
+          case 5: taps(IC<5>{}); break;
+          default: taps(IC<0>{}); break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
 // ---- BP through a convolutional layer, pull form (Sec. 3.3), for the own input maps ------------------
 // Neuron (r, c) of input map i collects, over every output map j that reads map i, the deltas of
 // the output neurons whose receptive field covers it (the four inequalities of Sec. 3.3), each
@@ -1060,7 +1138,13 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
   }
   const int tot = nb * S.Ho * S.Wo;
   const FDiv dHW(HW);
-  if (Z.stream) {  // the arena has held chunks of input maps since the last pull: the delta maps start from zeros
+  const int slots = uni_of<ID>(C.pull_slots);
+  const float* sums = slots > 0 ? dd : part;    // planes of partial sums [n_sums][tot]
+  const int n_sums = slots > 0 ? slots : D.R;
+  if (slots > 0) {
+    pull_winners<ID>(rt, l, dall, yxall, dd, slots, nb);
+  } else {
+  if (flow_arena_shared(Z)) {  // the arena has held other things since the last pull: the delta maps start from zeros
     for (int x = tid; x < Z.scratch_floats; x += WG) dd[x] = 0.f;
     __syncthreads();
   }
@@ -1124,11 +1208,12 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
     }
   });
   __syncthreads();
+  }
   DSTAMP(124);
   const float* fbelow = lds + Cb.o_dact;   // f' of the own units of the layer below
   float* dbelow = lds + Cb.o_delta;
   if (H == 1) {
-    reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s * fbelow[p]; });
+    reduce_partials(sums, n_sums, tot, [&](int p, float s) { dbelow[p] = s * fbelow[p]; });
     __syncthreads();
     return true;
   }
@@ -1138,11 +1223,11 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
   const FlowConvPtrs& P = rt.sh->ptrs.conv[l];
   gtagged* xp = P.x_part + ((size_t)(tag & 1u) * C.Mi + i) * (H - 1) * tot;
   if (h > 0) {
-    reduce_partials(part, D.R, tot, [&](int p, float s) { put_f(xp + (size_t)(h - 1) * tot + p, s, tag); });
+    reduce_partials(sums, n_sums, tot, [&](int p, float s) { put_f(xp + (size_t)(h - 1) * tot + p, s, tag); });
     __syncthreads();
     return true;
   }
-  reduce_partials(part, D.R, tot, [&](int p, float s) { dbelow[p] = s; });
+  reduce_partials(sums, n_sums, tot, [&](int p, float s) { dbelow[p] = s; });
   __syncthreads();
   bool ok = true;  // (a lane whose wait gave up goes on to the barrier like the others; the flag tells)
   for (int p0 = 0; p0 < tot; p0 += WG) {

@@ -29,6 +29,10 @@ struct ConvSpec {
   int pull_rows;
   int has_x_out;    // the pooled outputs are exchanged (a convolutional layer follows)
   int in_chunk;     // input maps held in LDS at a time: Mi, or fewer when the plan streams this layer's inputs
+  int pull_slots;   // > 0 (pooled layers above the first): the delta pull through this layer visits the pooling
+                    //   winners only, pull_slots connections at a time, each adding into a copy of its own of the
+                    //   rank's input maps ([pull_slots][n_own_below][Hi*Wi] in the arena); 0: the pull is a
+                    //   correlation over whole maps
   // LDS offsets, in floats
   int o_in;     // [Mi][Hi*Wi] inputs of the layer (the image, or every pooled map of the layer below)
   int o_wf;     // [n_own][max_conn][K*K] forward copy of the filters
@@ -78,6 +82,15 @@ struct FlowSpec {
   FcSpec fc[FLOW_MAX_FC];
 };
 
+// The pull that correlates over whole maps keeps its arena of zero-bordered delta maps zero between uses -- unless
+// something else writes there in between: the input chunks of a streamed plan, or the copies of a pull that
+// visits winners only (another layer of the same network).  Then it clears the arena before every use.
+constexpr bool flow_arena_shared(const FlowSpec& Z) {
+  bool shared = Z.stream != 0;
+  for (int l = 1; l < Z.n_conv; ++l) shared = shared || Z.conv[l].pull_slots > 0;
+  return shared;
+}
+
 // reasons a network cannot run in resident mode
 enum FlowWhy : int {
   FLOW_OK = 0, FLOW_NO_CONV, FLOW_TOO_MANY_LAYERS, FLOW_BAD_STRIDE, FLOW_TOO_LARGE, FLOW_NO_LDS
@@ -99,6 +112,15 @@ constexpr int flow_split_ways(int U, int max_cnt) {
 // floats of one zero-bordered delta map of the pull through a layer whose input maps are Hi x Wi: odd, so that
 // lanes that read the same place of different maps fall on different LDS banks
 constexpr long long flow_border_map(int Hi, int Wi, int K) { return ((long long)(Hi + K - 1) * (Wi + K - 1)) | 1; }
+// The pull that visits winners only (pull_slots): a connection's HW winners are taken by UW lanes at a time
+// (all of them when HW <= 64, else HW split into the fewest equal parts of at most 64), and a workgroup works on
+// (WG / 64) * (64 / UW) such units at once when it has room for as many copies of its input maps.
+// It pays from pooling rectangles of 3 x 3 on (measured: a term costs two LDS accesses of a wavefront there,
+// against a third of one for each of Kp^2 times as many terms in the correlation over whole maps).
+constexpr int FLOW_WINNERS_MIN_KP = 3;
+constexpr int flow_winner_parts(int HW) { return (HW + 63) / 64; }
+constexpr int flow_winner_lanes(int HW) { return (HW + flow_winner_parts(HW) - 1) / flow_winner_parts(HW); }
+constexpr int flow_winner_slots_max(int HW) { return (WG / 64) * (64 / flow_winner_lanes(HW)); }
 // floats of partial sums a job of n_maps (or one map fewer: ranks differ by one) maps needs
 constexpr long long flow_part_need(int strip, int th, int n_maps, int rows, int width, int max_cnt) {
   long long need = 0;
@@ -186,7 +208,10 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
     // into 13x13 maps and loses 0.8 us on 40 of them)
     // (a plan that streams its inputs does not share pulls: a share adjusts its filters from an input map of the
     // layer, which then is not at hand)
-    C.pull_shares = (l >= 1 && !stream && 2 * C.Mi <= G &&
+    // (a pull that visits the pooling winners only is too short to be worth the hand-over: not shared)
+    const bool winners_only = l >= 1 && C.Kp >= FLOW_WINNERS_MIN_KP;
+    C.pull_slots = 0;
+    C.pull_shares = (l >= 1 && !stream && !winners_only && 2 * C.Mi <= G &&
                      (long long)C.max_back * KK * C.Hi * C.Wi >= FLOW_SHARE_MIN_MACS)
                         ? G / C.Mi : 1;
     C.back_pitch = (C.max_back + C.pull_shares - 1) / C.pull_shares;
@@ -211,9 +236,13 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
         C.pull_strip = tile & 15; C.pull_rows = tile ? tile >> 4 : 1;
       }
       max_dall = flow_maxl(max_dall, (long long)C.Mo * HW);
-      max_hwd = flow_maxl(max_hwd, flow_border_map(C.Hi, C.Wi, C.K));
-      max_part = flow_maxl(max_part, flow_part_need(C.pull_strip, C.pull_rows, C.n_own_below, C.Hi, C.Wi,
-                                                    flow_min(C.back_pitch, C.Mo)));
+      if (winners_only) {   // at least one copy of the own input maps
+        max_hwd = flow_maxl(max_hwd, (long long)C.n_own_below * C.Hi * C.Wi);
+      } else {
+        max_hwd = flow_maxl(max_hwd, flow_border_map(C.Hi, C.Wi, C.K));
+        max_part = flow_maxl(max_part, flow_part_need(C.pull_strip, C.pull_rows, C.n_own_below, C.Hi, C.Wi,
+                                                      flow_min(C.back_pitch, C.Mo)));
+      }
     }
     C.o_pool = take((long long)C.n_own * HW);
     C.o_yx = take((long long)C.n_own * HW);
@@ -268,19 +297,26 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
   // image), the first layers' jobs first -- but only where a table does not cost the pull a pass:
   // the zero-bordered delta maps below get what is left, and every pass over a chunk of them costs
   // more than decoding a job again.
-  auto pull_passes = [&](long long floats) {
-    long long worst = 1;
+  auto pull_passes = [&](long long floats) {   // (summed over the layers: a table must not cost any of them a pass)
+    long long total = 0;
     for (int l = 1; l < n_conv; ++l) {
       const ConvSpec& C = Z.conv[l];
-      const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
-      const long long chunk = flow_maxl(1, flow_minl(C.Mo, (floats - pad) / hwd));
-      worst = flow_maxl(worst, (C.Mo + chunk - 1) / chunk);
+      if (C.Kp >= FLOW_WINNERS_MIN_KP) {   // winners only: rounds of as many connections as there are copies
+        const long long copy = (long long)C.n_own_below * C.Hi * C.Wi;
+        const long long units = (long long)C.n_own_below * C.back_pitch * flow_winner_parts(C.Hp * C.Wp);
+        const long long sl = flow_maxl(1, flow_minl(flow_minl(flow_winner_slots_max(C.Hp * C.Wp), units), floats / copy));
+        total += (units + sl - 1) / sl;
+      } else {
+        const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
+        const long long chunk = flow_maxl(1, flow_minl(C.Mo, (floats - pad) / hwd));
+        total += (C.Mo + chunk - 1) / chunk;
+      }
       if (stream) {  // the chunks of input maps FP walks through the same arena
         const long long ic = flow_maxl(1, flow_minl(C.Mi, (floats - pad) / ((long long)C.Hi * C.Wi)));
-        worst = flow_maxl(worst, (C.Mi + ic - 1) / ic);
+        total += (C.Mi + ic - 1) / ic;
       }
     }
-    return worst;
+    return total;
   };
   for (int l = 0; l < n_conv; ++l) {
     const long long free_now = (long long)FLOW_LDS_FLOATS_MAX - off;
@@ -288,7 +324,7 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
         pull_passes(free_now - 3 * WG) == pull_passes(free_now))
       Z.conv[l].o_tab_fwd = take(3 * WG);
     const long long free_then = (long long)FLOW_LDS_FLOATS_MAX - off;
-    if (l >= 1 && Z.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX &&
+    if (l >= 1 && Z.conv[l].Kp < FLOW_WINNERS_MIN_KP && Z.conv[l].n_own_below < 1024 && off + need + 3 * WG <= FLOW_LDS_FLOATS_MAX &&
         pull_passes(free_then - 3 * WG) == pull_passes(free_then))
       Z.conv[l].o_tab_pull = take(3 * WG);
   }
@@ -296,7 +332,12 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
   long long scratch = need;
   for (int l = 1; l < n_conv; ++l) {
     const ConvSpec& C = Z.conv[l];
-    scratch = flow_maxl(scratch, (long long)C.Mo * flow_border_map(C.Hi, C.Wi, C.K) + pad);
+    if (C.Kp >= FLOW_WINNERS_MIN_KP) {
+      const long long units = (long long)C.n_own_below * C.back_pitch * flow_winner_parts(C.Hp * C.Wp);
+      scratch = flow_maxl(scratch, flow_minl(flow_winner_slots_max(C.Hp * C.Wp), units) * C.n_own_below * C.Hi * C.Wi);
+    } else {
+      scratch = flow_maxl(scratch, (long long)C.Mo * flow_border_map(C.Hi, C.Wi, C.K) + pad);
+    }
   }
   if (stream)
     for (int l = 1; l < n_conv; ++l) scratch = flow_maxl(scratch, (long long)Z.conv[l].Mi * Z.conv[l].Hi * Z.conv[l].Wi + pad);
@@ -308,13 +349,18 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
     ConvSpec& C = Z.conv[l];
     const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);
     C.pull_chunk = (int)flow_maxl(1, flow_minl(C.Mo, (scratch - pad) / hwd));
+    if (C.Kp >= FLOW_WINNERS_MIN_KP) {
+      const long long units = (long long)C.n_own_below * C.back_pitch * flow_winner_parts(C.Hp * C.Wp);
+      C.pull_slots = (int)flow_minl(flow_minl(flow_winner_slots_max(C.Hp * C.Wp), units),
+                                    scratch / ((long long)C.n_own_below * C.Hi * C.Wi));
+    }
     if (stream) {
       // the pull stores its partial sums in the arena after its one walk over the delta maps: a job with
       // more units than lanes would walk them again and meet its own sums there
       const long long U = C.pull_strip
           ? (long long)C.n_own_below * ((C.Hi + C.pull_rows - 1) / C.pull_rows) * ((C.Wi + C.pull_strip - 1) / C.pull_strip)
           : (long long)C.n_own_below * C.Hi * C.Wi;
-      if (U > WG) return FLOW_NO_LDS;
+      if (C.pull_slots == 0 && U > WG) return FLOW_NO_LDS;
       Z.o_part = Z.o_scratch;
       C.o_in = Z.o_scratch;
       C.in_chunk = (int)flow_maxl(1, flow_minl(C.Mi, (scratch - pad) / ((long long)C.Hi * C.Wi)));

@@ -42,8 +42,13 @@ SHAPES = [
     ("1x28x28-6C5-MP2-100C5-MP2-8N", {}, 0, 1),              # 16 shares a map, full table
     ("1x28x28-6C5-MP2-100C5-MP2-8N", {1: 5}, 0, 1),          # ... sparse table
     ("1x28x28-40C5-MP2-80C5-MP2-8N", {1: 38}, 0, 1),         # 2 shares a map, sparse table
+    # pooling rectangles of 3 x 3 and more: in resident mode the delta pull visits the pooling winners only
+    ("1x47x47-6C4-MP2-100C5-MP3-8N", {}, 0, 1),              # many maps above few: not shared all the same, 36 winners a map
+    ("1x65x65-8C4-MP2-20C5-MP3-6N", {}, 0, 1),               # 81 winners a map: two parts of 41 lanes
+    ("1x65x65-8C4-MP2-20C5-MP3-6N", {1: 3}, 0, 1),           # ... sparse table
+    ("2x60x60-3C5-MP4-7C4S1-MP3-4C1-MP1-5N", {1: 2}, 0, 2),  # skipping factor 1 under the winners, 1x1 kernels above
 ]
-SHARES = {"1x28x28-6C5-MP2-100C5-MP2-8N": 16, "1x28x28-40C5-MP2-80C5-MP2-8N": 2}
+SHARES = {"1x28x28-6C5-MP2-100C5-MP2-8N": 16, "1x28x28-40C5-MP2-80C5-MP2-8N": 2, "1x47x47-6C4-MP2-100C5-MP3-8N": 1}
 
 def _pair(arch, fan, fe_k, n_src, seed, wscale=0.3):
     import oracle

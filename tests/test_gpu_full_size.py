@@ -27,7 +27,7 @@ def _epoch(g, d_imgs, d_labs, lr, n, stops=()):
     return snap
 
 
-@pytest.mark.parametrize("name,static_id,shares", [("cfg2a", 1, 1), ("cfg2b", 2, 2)])
+@pytest.mark.parametrize("name,static_id,shares", [("cfg2a", 1, 1), ("cfg2b", 2, 1)])
 def test_one_epoch_in_the_benchmark_configuration(name, static_id, shares):
     wl = synth.WORKLOADS[name]
     n = wl.n_images
@@ -37,7 +37,7 @@ def test_one_epoch_in_the_benchmark_configuration(name, static_id, shares):
     g, o = build_pair(wl)
     g.set_mode(binding.MODE_RESIDENT)
     assert g.resident_static_id() == static_id  # the kernels bench.py times
-    assert g.resident_pull_shares(1) == shares  # (the larger net's delta pull is shared by two ranks a map)
+    assert g.resident_pull_shares(1) == shares  # (pulls that visit the pooling winners only are not shared)
     stops = (0, 19, 58)
     print("epoch of", n, "images,", LAUNCH, "per launch", flush=True)
     snap = _epoch(g, d_imgs, d_labs, wl.lr, n, stops)
