@@ -1031,8 +1031,8 @@ __device__ __forceinline__ void flow_wgrad_entries(float* wb, const int* bj, con
 // winner's receptive field.  The lanes that share a connection hold different winners, i.e. different receptive
 // fields' corners, so at one tap they add at different places; the taps follow one another in program order and
 // LDS serves a wavefront's instructions in order, so every place receives its terms in a fixed order and the
-// result does not depend on timing.  It pays where a pooling rectangle holds 9 or more neurons: a term costs two
-// LDS accesses here, against a third of one and Kp^2 times the terms in the correlation over whole maps.  Connections worked on at the same time (a slot: UW lanes of a wavefront)
+// result does not depend on timing.  A term costs two LDS accesses here, against a third of one and Kp^2 times the
+// terms in the correlation over whole maps; measured, it pays from 2 x 2 pooling on.  Connections worked on at the same time (a slot: UW lanes of a wavefront)
 // add into copies of their own of the rank's input maps; the copies are added up afterwards (reduce_partials),
 // in the order of the slots.  Every copy: [n_maps][Hi * Wi].
 template <int ID>

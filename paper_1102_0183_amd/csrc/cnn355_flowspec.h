@@ -115,9 +115,9 @@ constexpr long long flow_border_map(int Hi, int Wi, int K) { return ((long long)
 // The pull that visits winners only (pull_slots): a connection's HW winners are taken by UW lanes at a time
 // (all of them when HW <= 64, else HW split into the fewest equal parts of at most 64), and a workgroup works on
 // (WG / 64) * (64 / UW) such units at once when it has room for as many copies of its input maps.
-// It pays from pooling rectangles of 3 x 3 on (measured: a term costs two LDS accesses of a wavefront there,
-// against a third of one for each of Kp^2 times as many terms in the correlation over whole maps).
-constexpr int FLOW_WINNERS_MIN_KP = 3;
+// Any pooling at all makes it pay (measured: 2 x 2 rectangles, a quarter of the terms: cfg4a 55.8 -> 54.0 us per
+// image, cfg5 16.5 -> 16.2; 3 x 3 and 4 x 4: the benchmark net 16.3 -> 15.6, cfg3 43.3 -> 38.1).
+constexpr int FLOW_WINNERS_MIN_KP = 2;
 constexpr int flow_winner_parts(int HW) { return (HW + 63) / 64; }
 constexpr int flow_winner_lanes(int HW) { return (HW + flow_winner_parts(HW) - 1) / flow_winner_parts(HW); }
 constexpr int flow_winner_slots_max(int HW) { return (WG / 64) * (64 / flow_winner_lanes(HW)); }

@@ -68,9 +68,9 @@ def check_plan(p, arch, n_ranks=0, stride=0):
         if l == 0:
             assert c["pull_shares"] == 1
             continue
-        # a pooled layer's pull visits the pooling winners only (from rectangles of 3 x 3 on)
+        # a pooled layer's pull visits the pooling winners only
         HW = c["Hp"] * c["Wp"]
-        winners = c["Kp"] >= 3
+        winners = c["Kp"] >= 2
         # shared pulls
         macs = c["max_back"] * KK * c["Hi"] * c["Wi"]
         shared = 2 * c["Mi"] <= G and macs >= num["share_min_macs"] and not stream and not winners
@@ -181,6 +181,8 @@ def test_other_refusals():
     ("1x8x600-3C3-MP2-4C2S1-5N", 0), ("1x70x70-4C3-MP4-3C4-MP2-6N", 0), ("3x34x47-7C4S1-8C3-MP2-9C2-MP3-20N-6N", 4),
     ("1x40x40-70C5-MP4-300C3-MP1-10N", 0), ("1x28x28-6C5-MP2-100C5-MP2-8N", 0), ("1x28x28-6C5-MP2-100C5-MP2-8N", 5),
     ("1x28x28-40C5-MP2-80C5-MP2-8N", 38), ("1x28x28-3C5-MP2-250C5-MP2-8N", 0),
+    ("1x28x28-6C5-MP2-100C5-MP1-8N", 0), ("1x28x28-6C5-MP2-100C5-MP1-8N", 5), ("1x28x28-40C5-MP2-80C5-MP1-8N", 38),
+    ("1x47x47-6C4-MP2-100C5-MP3-8N", 0), ("1x65x65-8C4-MP2-20C5-MP3-6N", 3), ("2x60x60-3C5-MP4-7C4S1-MP3-4C1-MP1-5N", 2),
 ])
 def test_edge_shapes(arch, fan):
     p = binding.resident_plan(arch, fan_in=fan)
