@@ -317,6 +317,17 @@ int cnn_resident_spec_source(const cnn_t* net, char* host_buf, size_t n);
 int cnn_load_resident_code(cnn_t* net, const char* host_path);
 int cnn_resident_code_active(const cnn_t* net);
 
+/* Parity tap of the batched forward pass (Sec. 3.2 for many images): runs cnn_forward_batch's kernels on n images
+ * as one batch (d_scratch as for cnn_forward_batch with batch = n) up to and including trainable layer
+ * `trainable_layer` (0 = the first convolutional or fully connected layer of the architecture string, counting
+ * those two kinds only) and copies that layer's outputs to host_out: [image][map][Hp][Wp] pooled activations of
+ * a convolutional layer (its own activations when no pooling follows), [image][unit] activations of a hidden fully
+ * connected layer, [image][class] the sums of the output layer before the output units.  *host_floats_per_image
+ * receives the floats per image (host_out must hold n times that: at most the largest layer output).
+ * Synchronises.  CNN_E_ARG for a layer index beyond the last. */
+int cnn_debug_forward_batch_layer(cnn_t* net, const float* d_images, size_t n, int trainable_layer, float* host_out,
+                                  size_t* host_floats_per_image, void* d_scratch, size_t scratch_bytes);
+
 /* Forward + backward for (d_image, label) with the update replaced by a store of dE/dw:
  * host_grad receives cnn_num_weights floats in canonical order; weights are unchanged. */
 int cnn_debug_gradients(cnn_t* net, const float* d_image, int32_t label, float* host_grad);

@@ -80,6 +80,7 @@ def lib():
             "cnn_get_stage_times": (C.c_int, [vp, vp, C.c_int, vp]),
             "cnn_measure_crossing": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, vp]),
             "cnn_measure_launch": (C.c_int, [vp, C.c_int, vp]),
+            "cnn_debug_forward_batch_layer": (C.c_int, [vp, vp, C.c_size_t, C.c_int, vp, vp, vp, C.c_size_t]),
             "cnn_resident_spec_source": (C.c_int, [vp, vp, C.c_size_t]),
             "cnn_load_resident_code": (C.c_int, [vp, C.c_char_p]),
             "cnn_resident_code_active": (C.c_int, [vp]),
@@ -103,7 +104,7 @@ EXPORTS = ["cnn_arch_info", "cnn_arch_info_xy", "cnn_workspace_bytes", "cnn_plan
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
            "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times", "cnn_measure_crossing", "cnn_measure_launch",
-           "cnn_resident_spec_source", "cnn_load_resident_code", "cnn_resident_code_active",
+           "cnn_resident_spec_source", "cnn_load_resident_code", "cnn_resident_code_active", "cnn_debug_forward_batch_layer",
            "cnn_deform_images", "cnn_last_error"]
 
 
@@ -379,6 +380,19 @@ class Cnn:
         p = self._dev_f32(d_probs, n * self.num_classes)
         self._ck(lib().cnn_forward_batch(self._h, d_images.data_ptr(), int(n), p, d_scratch.data_ptr(),
                                          d_scratch.numel(), int(batch)), "cnn_forward_batch")
+
+    def debug_forward_batch_layer(self, d_images, n, trainable_layer, d_scratch):
+        """Outputs of one trainable layer of the batched forward pass for n images run as one batch: (n, floats)."""
+        torch = self._torch
+        assert d_images.is_cuda and d_images.dtype == torch.float32 and d_images.is_contiguous()
+        assert d_images.numel() >= n * self.image_size
+        biggest = max(i["maps"] * i["h"] * i["w"] for i in (self.layer_info(l) for l in range(self.num_layers)))
+        out = np.empty((n, biggest), dtype=np.float32)
+        per = C.c_size_t(0)
+        self._ck(lib().cnn_debug_forward_batch_layer(self._h, d_images.data_ptr(), int(n), int(trainable_layer),
+                                                     out.ctypes.data, C.byref(per), d_scratch.data_ptr(), d_scratch.numel()),
+                 "cnn_debug_forward_batch_layer")
+        return out.reshape(-1)[:n * per.value].reshape(n, per.value).copy()
 
     def measure_crossing(self, n_ranks, words_per_rank, rounds=200):
         """Microseconds one exchange of words_per_rank tagged words per rank among n_ranks workgroups takes."""

@@ -1853,11 +1853,13 @@ int cnn_deform_images(void* hip_stream, const float* d_src, size_t n_src, float*
   return CNN_OK;
 }
 
-int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
-                      size_t scratch_bytes, size_t batch) {
+// tap_step >= 0 (parity tap): the pass stops behind that trainable layer and its outputs for the n <= batch
+// images, [image][out_per_image], are copied to host_tap; d_probs is not written then.
+static int forward_batch_impl(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
+                              size_t scratch_bytes, size_t batch, int tap_step, float* host_tap, size_t* tap_per_image) {
   if (!net) return fail(nullptr, CNN_E_ARG, "NULL handle");
   if (n == 0) return CNN_OK;
-  if (!d_images || !d_probs || !d_scratch || batch == 0) return fail(&net->err, CNN_E_ARG, "NULL argument or batch of 0");
+  if (!d_images || (!d_probs && tap_step < 0) || !d_scratch || batch == 0) return fail(&net->err, CNN_E_ARG, "NULL argument or batch of 0");
   if (((uintptr_t)d_scratch & 255u) != 0) return fail(&net->err, CNN_E_ARG, "scratch must be 256-byte aligned");
   BatchPlan B;
   int rc = batch_plan(net, batch, B);
@@ -1873,6 +1875,8 @@ int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_prob
     return fail(&net->err, CNN_E_ARG, "batch too large: the images of one batch must stay below 2^31 floats");
   if (scratch_bytes < B.floats(batch) * sizeof(float))
     return fail(&net->err, CNN_E_WORKSPACE, "scratch smaller than cnn_forward_batch_scratch_bytes says");
+  if (tap_step >= 0 && (tap_step >= (int)B.steps.size() || n > batch || !host_tap))
+    return fail(&net->err, CNN_E_ARG, "no such trainable layer, more images than one batch, or no buffer");
   const ProgramDev& P = net->prog;
   float* base = (float*)d_scratch;
   float* d_sums = base + B.wt_total;
@@ -1912,10 +1916,27 @@ int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_prob
       in = out;
       in_stride = (long long)st.out_per_image;
       cur ^= 1;
+      if ((int)s == tap_step) {
+        HIP_TRY(net, hipStreamSynchronize(net->stream));
+        HIP_TRY(net, hipMemcpy(host_tap, out, nb * st.out_per_image * sizeof(float), hipMemcpyDeviceToHost));
+        if (tap_per_image) *tap_per_image = st.out_per_image;
+        return CNN_OK;
+      }
     }
     HIP_TRY(net, launch_batch_outputs(net->stream, in, d_probs + t0 * P.n_classes, (long long)nb, P.n_classes, net->out_units));
   }
   return CNN_OK;
+}
+
+int cnn_forward_batch(cnn_t* net, const float* d_images, size_t n, float* d_probs, void* d_scratch,
+                      size_t scratch_bytes, size_t batch) {
+  return forward_batch_impl(net, d_images, n, d_probs, d_scratch, scratch_bytes, batch, -1, nullptr, nullptr);
+}
+
+int cnn_debug_forward_batch_layer(cnn_t* net, const float* d_images, size_t n, int trainable_layer, float* host_out,
+                                  size_t* host_floats_per_image, void* d_scratch, size_t scratch_bytes) {
+  return forward_batch_impl(net, d_images, n, nullptr, d_scratch, scratch_bytes, n, trainable_layer, host_out,
+                            host_floats_per_image);
 }
 
 }  // extern "C"

@@ -125,3 +125,40 @@ def test_batched_forward_argument_errors():
     g.forward_batch(d_imgs, 0, d_probs[:0], _scratch(g, 4), 4)  # no images: nothing to do
     g.synchronize()
     g.close()
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 37), ("cfg2b", 20), ("cfg3", 9), ("cfg4a", 9), ("cfg4b", 5), ("cfg5", 21)])
+def test_every_layer_of_the_batched_pass_matches_the_oracle(name, n):
+    """The parity tap of the batched pass: the outputs of every trainable layer (pooled maps of a convolutional
+    layer, units of a fully connected one, the output layer's sums) for every image of a batch against the
+    oracle's, layer by layer, so that an error in one layer cannot hide behind a soft-max that is sure anyway."""
+    wl = synth.WORKLOADS[name]
+    print("case", name, "images", n, flush=True)
+    g, o = build_pair(wl)
+    imgs = synth.images(wl, n)
+    d_imgs = to_dev(imgs)
+    scratch = _scratch(g, n)
+    layers = [l for l in range(1, o.num_layers) if o.layer_info(l)["kind"] in (1, 3)]
+    want = {k: [] for k in range(len(layers))}
+    for i in range(n):
+        o.forward(imgs[i])
+        for k, l in enumerate(layers):
+            pooled = l + 1 < o.num_layers and o.layer_info(l + 1)["kind"] == 2
+            a = o.activation(l + 1 if pooled else l)
+            want[k].append(np.asarray(a, dtype=np.float64).ravel())
+    for k in range(len(layers)):
+        got = g.debug_forward_batch_layer(d_imgs, n, k, scratch).astype(np.float64)
+        w = np.stack(want[k])
+        assert got.shape == w.shape, (k, got.shape, w.shape)
+        if k == len(layers) - 1:
+            # the tap shows the output layer's sums, the oracle its soft-max: sums minus their log-sum-exp are the
+            # logarithms of the probabilities
+            m = got.max(axis=1, keepdims=True)
+            got = got - (m + np.log(np.exp(got - m).sum(axis=1, keepdims=True)))
+            w = np.log(w)
+        e = np.abs(got - w).max() / np.abs(w).max()
+        print("  trainable layer %d: %d values an image, rel err %.2e" % (k, w.shape[1], e), flush=True)
+        assert e <= 1e-5, k
+    with pytest.raises(binding.CnnError):
+        g.debug_forward_batch_layer(d_imgs, n, len(layers), scratch)
+    g.close()
