@@ -378,6 +378,31 @@ __device__ __forceinline__ bool gather_bulk(const Rt& rt, float* dst, const gflo
   return true;
 }
 
+// The same in three steps, so that a chunk can be on its way while the one before it is worked on: wait for the
+// flags (ends with a workgroup barrier), issue the loads into registers (at most BULK_PF x 128 bits a lane: chunks
+// of up to BULK_PF * 4 * WG floats), store the registers to LDS.
+constexpr int BULK_PF = 4;
+__device__ __forceinline__ bool bulk_wait(const Rt& rt, const guint* flags, int n_flags, unsigned int tag) {
+  for (int m = threadIdx.x; m < n_flags; m += WG) {
+    unsigned int spins = 0;
+    while (__hip_atomic_load(flags + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tag)
+      if (!poll_again(rt, spins)) break;
+  }
+  __syncthreads();
+  return rt.sh->fail == 0;
+}
+__device__ __forceinline__ void bulk_issue(u4v (&v)[BULK_PF], const gfloat* data, int n) {
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)data, 0, n * 4, 0x00020000);
+#pragma unroll
+  for (int u = 0; u < BULK_PF; ++u)   // (a load past n floats returns zeros: the buffer descriptor bounds it)
+    v[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, (threadIdx.x * 4 + u * WG * 4) * 4, 0, 16 /* device scope */);
+}
+__device__ __forceinline__ void bulk_commit(const u4v (&v)[BULK_PF], float* dst, int n) {
+#pragma unroll
+  for (int u = 0; u < BULK_PF; ++u)
+    if ((int)threadIdx.x * 4 + u * WG * 4 < n) *(u4v*)(dst + threadIdx.x * 4 + u * WG * 4) = v[u];
+}
+
 // ---- weights: global (canonical order) <-> LDS -------------------------------------------------
 template <int ID>
 __device__ __forceinline__ void flow_load(const Rt& rt) {
@@ -777,11 +802,27 @@ __device__ __forceinline__ bool flow_conv_fwd(const Rt& rt, int l, gtagged* src,
         const int Mi = C.Mi, chunk = C.in_chunk, full = C.full_table;
         int e_next = 0;
         if (l == 1) DSTAMP(100);
+        // chunks that fit the prefetch registers travel while the chunk before them is multiplied
+        const bool ahead = chunk * S.map_sz <= BULK_PF * 4 * WG && Mi > chunk;
+        const gfloat* data = bulk_data(src, Mi * S.map_sz, tag & 1u);
+        u4v pf[BULK_PF];
+        if (ahead) {
+          if (pass > 0) __syncthreads();
+          if (!bulk_wait(rt, bulk_flags(src, Mi * S.map_sz, Mi, tag & 1u), Mi, tag)) { ok = false; break; }
+          bulk_issue(pf, data, min(chunk, Mi) * S.map_sz);
+        }
         for (int i0 = 0; i0 < Mi; i0 += chunk) {
           const int n = min(chunk, Mi - i0);
+          if (ahead) {
+            if (i0 > 0) __syncthreads();  // the chunk before has been read by everybody
+            bulk_commit(pf, lds + S.in, n * S.map_sz);
+            __syncthreads();
+            if (i0 + chunk < Mi) bulk_issue(pf, data + (size_t)(i0 + chunk) * S.map_sz, min(chunk, Mi - i0 - chunk) * S.map_sz);
+          } else {
           if (i0 > 0 || pass > 0) __syncthreads();  // the chunk before has been read by everybody
-          if (!gather_bulk(rt, lds + S.in, bulk_data(src, Mi * S.map_sz, tag & 1u) + (size_t)i0 * S.map_sz, n * S.map_sz,
+          if (!gather_bulk(rt, lds + S.in, data + (size_t)i0 * S.map_sz, n * S.map_sz,
                            bulk_flags(src, Mi * S.map_sz, Mi, tag & 1u) + i0, n, tag)) { ok = false; break; }
+          }
           if (l == 1 && i0 / chunk < 4) DSTAMP(101 + 2 * (i0 / chunk));
           if (ln.on) {
             // connections of the lane's map whose input map lies in [i0, i0 + n): the list is sorted
@@ -1144,7 +1185,7 @@ __device__ __forceinline__ bool flow_pull(const Rt& rt, int l, const float* dall
   if (slots > 0) {
     pull_winners<ID>(rt, l, dall, yxall, dd, slots, nb);
   } else {
-  if (flow_arena_shared(Z)) {  // the arena has held other things since the last pull: the delta maps start from zeros
+  if (Z.arena_shared) {  // the arena has held other things since the last pull: the delta maps start from zeros
     for (int x = tid; x < Z.scratch_floats; x += WG) dd[x] = 0.f;
     __syncthreads();
   }

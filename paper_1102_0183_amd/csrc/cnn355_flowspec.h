@@ -78,18 +78,12 @@ struct FlowSpec {
   int stream;       // 1: the inputs of every convolutional layer above the first do not stay in LDS: FP and the
                     //    adjustment of the forward copy walk them chunk by chunk (in_chunk maps at a time, fetched
                     //    from the exchange buffers into the arena the delta pull uses for its zero-bordered maps)
+  int arena_shared; // 1: the pull that correlates over whole maps cannot count on its arena of zero-bordered delta
+                    //    maps being zero from the last use (input chunks of a streamed plan, or the copies of
+                    //    another layer's winners-only pull, lie there in between) and clears it before every use
   ConvSpec conv[FLOW_MAX_CONV];
   FcSpec fc[FLOW_MAX_FC];
 };
-
-// The pull that correlates over whole maps keeps its arena of zero-bordered delta maps zero between uses -- unless
-// something else writes there in between: the input chunks of a streamed plan, or the copies of a pull that
-// visits winners only (another layer of the same network).  Then it clears the arena before every use.
-constexpr bool flow_arena_shared(const FlowSpec& Z) {
-  bool shared = Z.stream != 0;
-  for (int l = 1; l < Z.n_conv; ++l) shared = shared || Z.conv[l].pull_slots > 0;
-  return shared;
-}
 
 // reasons a network cannot run in resident mode
 enum FlowWhy : int {
@@ -345,6 +339,9 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
   Z.o_scratch = take(scratch);
   Z.scratch_floats = (int)scratch;
   Z.lds_floats = (int)off;
+  Z.arena_shared = stream ? 1 : 0;
+  for (int l = 1; l < n_conv; ++l)
+    if (Z.conv[l].Kp >= FLOW_WINNERS_MIN_KP) Z.arena_shared = 1;
   for (int l = 1; l < n_conv; ++l) {
     ConvSpec& C = Z.conv[l];
     const long long hwd = flow_border_map(C.Hi, C.Wi, C.K);

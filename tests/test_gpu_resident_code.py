@@ -108,6 +108,9 @@ def test_loaded_kernel_is_as_fast_as_the_one_the_library_holds_for_the_benchmark
           % (t_lit, t_loaded, t_plan, t_narrow), flush=True)
     assert t_loaded <= 1.15 * t_lit
     assert t_narrow <= 0.8 * t_plan
+    # (and the kernel that reads its plan keeps it in scalar registers: copied to scratch memory by the compiler,
+    # which has happened, it takes 2.5 x and more)
+    assert t_plan <= 2.1 * t_narrow
     assert t_narrow <= 1.3 * t_lit
 
 
