@@ -243,6 +243,18 @@ int cnn_get_output_units(const cnn_t* net);
  * Results agree to rounding.  Weights and tables are kept.  Synchronises. */
 int cnn_set_matrix_cores(cnn_t* net, int on);
 
+/* CNN_MODE_STAGES launches every stage of every image by itself (10 - 14 launches per image for the wide nets of
+ * Sec. 4.2 and 4.3, about 2.5 us each whatever the kernel does).  With images_per_graph > 0 cnn_train_many and
+ * cnn_forward_many replay instead a graph that holds the launches of that many consecutive images: as many whole
+ * graphs as the call has images for when it has at least twice that many, the rest stage by stage as before.
+ * Same kernels, same order, same results bit for bit.  Off (0) by default: an empty kernel costs 1.5 us as a node
+ * of a graph against 2.5 us launched, but with the stage kernels of the benchmark nets a replay takes as long as
+ * the launches (measured on 1024 images: the widest net 132.6 against 132.0 us per image, the benchmark net 43.3
+ * against 44.5).  At most 1024 images per graph.  The graph is built at the first call that uses it and again after
+ * anything that changes the stage list (mode, tables, output variant, matrix cores).  CNN_E_ARG for a value
+ * outside the range. */
+int cnn_set_launch_graph(cnn_t* net, int images_per_graph);
+
 /* Persistent mode: number of workgroups of the cooperative launch (0 = automatic: the
  * largest stage's work items, capped at the number of compute units).  Values above what
  * can be co-resident are clamped. */

@@ -68,6 +68,7 @@ def lib():
             "cnn_set_output_units": (C.c_int, [vp, C.c_int]),
             "cnn_get_output_units": (C.c_int, [vp]),
             "cnn_set_matrix_cores": (C.c_int, [vp, C.c_int]),
+            "cnn_set_launch_graph": (C.c_int, [vp, C.c_int]),
             "cnn_set_grid": (C.c_int, [vp, C.c_int]),
             "cnn_set_spin_limit": (C.c_int, [vp, C.c_uint]),
             "cnn_set_barrier": (C.c_int, [vp, C.c_int]),
@@ -102,7 +103,7 @@ EXPORTS = ["cnn_arch_info", "cnn_arch_info_xy", "cnn_workspace_bytes", "cnn_plan
            "cnn_forward", "cnn_train_step", "cnn_train_many", "cnn_forward_many",
            "cnn_forward_batch_scratch_bytes", "cnn_forward_batch", "cnn_forward_batch_static", "cnn_set_mode",
            "cnn_get_mode", "cnn_mode_supported", "cnn_set_team", "cnn_set_output_units", "cnn_get_output_units",
-           "cnn_set_matrix_cores", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
+           "cnn_set_matrix_cores", "cnn_set_launch_graph", "cnn_set_grid", "cnn_set_spin_limit", "cnn_set_barrier", "cnn_synchronize", "cnn_get_activation",
            "cnn_get_delta", "cnn_get_argmax", "cnn_get_loss", "cnn_debug_gradients", "cnn_get_stage_times", "cnn_measure_crossing", "cnn_measure_launch",
            "cnn_resident_spec_source", "cnn_load_resident_code", "cnn_resident_code_active", "cnn_debug_forward_batch_layer",
            "cnn_deform_images", "cnn_last_error"]
@@ -302,6 +303,10 @@ class Cnn:
 
     def set_team(self, n_ranks=0, xcd_stride=0):
         self._ck(lib().cnn_set_team(self._h, int(n_ranks), int(xcd_stride)), "cnn_set_team")
+
+    def set_launch_graph(self, images_per_graph):
+        """Stage mode: replay graphs of the launches of this many images (0: launch every stage by itself)."""
+        self._ck(lib().cnn_set_launch_graph(self._h, int(images_per_graph)), "cnn_set_launch_graph")
 
     def set_output_units(self, kind):
         """OUTPUT_SOFTMAX_XENT (default) or OUTPUT_TANH_SQERR."""

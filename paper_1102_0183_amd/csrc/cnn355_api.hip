@@ -22,6 +22,10 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
 hipError_t launch_stage_pair(int kind_a, int n_a, int kind_b, int n_b, hipStream_t stream, const ProgramDev* d_prog,
                              int s, StatusDev* d_status, const RunArgs& a, bool* done);
 hipError_t launch_reset_status(hipStream_t stream, StatusDev* d_status, int clear_label_flag);
+hipError_t launch_call_set(hipStream_t stream, CallArgs* d_call, const CallArgs& v);
+const void* call_advance_kernel();
+const void* stage_kernel(int kind);
+const void* stage_pair_kernel(int kind_a, int kind_b);
 hipError_t launch_persistent(int grid, bool with_matrix_stages, hipStream_t stream, const ProgramDev* d_prog,
                              StatusDev* d_status, const RunArgs& a);
 int persistent_max_blocks_per_cu();
@@ -226,6 +230,12 @@ struct cnn {
   ProgramDev prog;  // host copy with device pointers
   ProgramDev* d_prog = nullptr;
   StatusDev* d_status = nullptr;
+  // stage mode: the launches of graph_images images as one graph, replayed (one for training, one forward only)
+  CallArgs* d_call = nullptr;
+  int graph_images = 0;         // 0: every stage of every image is launched by itself (the default: measured, a
+                                //   replayed kernel node costs what a launch costs once the kernels do real work)
+  hipGraphExec_t graph_exec[2] = {nullptr, nullptr};
+  int graph_built_for[2] = {0, 0};
   float* d_weights = nullptr;
   float* d_grad = nullptr;
   float* d_fe_filters = nullptr;
@@ -300,6 +310,7 @@ size_t carve(cnn* net, void* base) {
   net->n_weights_max = nw;
   net->d_prog = c.take<ProgramDev>(1);
   net->d_status = c.take<StatusDev>(1);
+  net->d_call = c.take<CallArgs>(1);
   net->d_weights = c.take<float>(nw);
   net->d_grad = c.take<float>(nw);
   net->d_fe_filters = c.take<float>((size_t)A[0].maps * MAX_FRONTEND_K * MAX_FRONTEND_K);
@@ -529,10 +540,12 @@ int check_plan(cnn* net) {
 }
 
 void plan_flow(cnn* net);
+void drop_stage_graphs(cnn* net);
 
 // Build layer descriptors, tables and the stage list on the host (no device call).  Works on
 // a handle whose workspace pointers are NULL (measuring / checking only).
 int plan(cnn* net) {
+  drop_stage_graphs(net);   // (their nodes carry the stage list that is about to change)
   const auto& A = net->arch;
   ProgramDev& P = net->prog;
   std::memset(&P, 0, sizeof(P));
@@ -908,6 +921,77 @@ int persistent_grid(const cnn* net, int train) {
   return std::max(1, std::min(most, net->n_cu));
 }
 
+void drop_stage_graphs(cnn* net) {
+  if (net->graph_exec[0] || net->graph_exec[1]) (void)hipStreamSynchronize(net->stream);  // (replays may be in flight)
+  for (int w = 0; w < 2; ++w) {
+    if (net->graph_exec[w]) (void)hipGraphExecDestroy(net->graph_exec[w]);
+    net->graph_exec[w] = nullptr;
+    net->graph_built_for[w] = 0;
+  }
+}
+
+// The stage launches of `images` consecutive images as a chain of kernel nodes behind one node that moves the
+// call's image counter on; every stage node carries its image's place in the graph, the rest comes from *d_call.
+int build_stage_graph(cnn* net, int which, int images, const RunArgs& a0) {
+  const ProgramDev& P = net->prog;
+  if (net->graph_exec[which]) { (void)hipGraphExecDestroy(net->graph_exec[which]); net->graph_exec[which] = nullptr; }
+  hipGraph_t graph = nullptr;
+  HIP_TRY(net, hipGraphCreate(&graph, 0));
+  auto give_up = [&](hipError_t e, const char* what) { (void)hipGraphDestroy(graph); return hip_fail(net, e, what); };
+  hipGraphNode_t prev = nullptr;
+  auto add = [&](const void* fn, unsigned grid, unsigned block, void** params) -> hipError_t {
+    hipKernelNodeParams kp;
+    std::memset(&kp, 0, sizeof(kp));
+    kp.func = const_cast<void*>(fn);
+    kp.gridDim = dim3(grid); kp.blockDim = dim3(block); kp.sharedMemBytes = 0; kp.kernelParams = params; kp.extra = nullptr;
+    hipGraphNode_t node = nullptr;
+    hipError_t e = hipGraphAddKernelNode(&node, graph, prev ? &prev : nullptr, prev ? 1 : 0, &kp);
+    prev = node;
+    return e;
+  };
+  {
+    CallArgs* d_call = net->d_call;
+    int step = images;
+    void* params[] = {(void*)&d_call, (void*)&step};
+    hipError_t e = add(call_advance_kernel(), 1, 64, params);
+    if (e != hipSuccess) return give_up(e, "graph node (image counter)");
+  }
+  const ProgramDev* d_prog = net->d_prog;
+  StatusDev* d_status = net->d_status;
+  for (int i = 0; i < images; ++i) {
+    RunArgs b = a0;
+    b.call = net->d_call; b.t_local = i;
+    b.images = nullptr; b.labels = nullptr; b.probs_out = nullptr; b.grad_out = nullptr; b.n_images = 1;
+    for (int s = 0; s < P.n_stages; ++s) {
+      const Stage& st = P.stages[s];
+      if (st.train_only && !which) continue;
+      if (st.n_items <= 0) continue;
+      int stage = s;
+      void* params[] = {(void*)&d_prog, (void*)&stage, (void*)&d_status, (void*)&b};
+      if (!st.barrier_after && s + 1 < P.n_stages && P.stages[s + 1].train_only == st.train_only && P.stages[s + 1].n_items > 0) {
+        const Stage& nx = P.stages[s + 1];
+        if (const void* fn = stage_pair_kernel(st.kind, nx.kind)) {
+          hipError_t e = add(fn, (unsigned)(st.n_items + nx.n_items), WG, params);
+          if (e != hipSuccess) return give_up(e, "graph node (pair of stages)");
+          ++s;
+          continue;
+        }
+      }
+      const void* fn = stage_kernel(st.kind);
+      if (!fn) return give_up(hipErrorInvalidValue, "graph node (unknown stage)");
+      hipError_t e = add(fn, (unsigned)st.n_items, WG, params);
+      if (e != hipSuccess) return give_up(e, "graph node (stage)");
+    }
+  }
+  hipGraphExec_t exec = nullptr;
+  hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) return hip_fail(net, e, "hipGraphInstantiate");
+  net->graph_exec[which] = exec;
+  net->graph_built_for[which] = images;
+  return CNN_OK;
+}
+
 // The resident kernel of this handle: the one loaded for its own network when the plan is still the one that was
 // compiled for, else a compiled-in one (for a benchmark network, or the one that reads its plan).
 static hipError_t launch_resident_of(cnn* net, int grid, size_t lds_bytes, const RunArgs& a) {
@@ -975,7 +1059,24 @@ int run(cnn* net, const RunArgs& a0) {
     return CNN_OK;
   }
   const long long n = a.n_images;
-  for (long long t = 0; t < n; ++t) {
+  long long t_first = 0;
+  const int GB = net->graph_images;
+  if (GB > 0 && a.labels && !a.grad_out && n >= 2 * GB) {
+    // whole graphs of GB images first; what is left over is launched stage by stage below
+    const int which = a.train ? 1 : 0;
+    if (!net->graph_exec[which] || net->graph_built_for[which] != GB) {
+      int rc = build_stage_graph(net, which, GB, a);
+      if (rc) return rc;
+    }
+    CallArgs c;
+    c.images = a.images; c.labels = a.labels; c.probs_out = a.probs_out; c.image_stride = a.image_stride;
+    c.t0 = -(long long)GB; c.lr = a.lr; c.train = a.train;
+    HIP_TRY(net, launch_call_set(net->stream, net->d_call, c));
+    const long long n_graphs = n / GB;
+    for (long long g = 0; g < n_graphs; ++g) HIP_TRY(net, hipGraphLaunch(net->graph_exec[which], net->stream));
+    t_first = n_graphs * GB;
+  }
+  for (long long t = t_first; t < n; ++t) {
     RunArgs b = a;
     b.images = a.images + t * a.image_stride;
     b.labels = a.labels ? a.labels + t : nullptr;
@@ -1241,6 +1342,7 @@ void cnn_destroy(cnn_t* net) {
   if (!net) return;
   (void)hipStreamSynchronize(net->stream);
   if (net->special_module) (void)hipModuleUnload(net->special_module);
+  drop_stage_graphs(net);
   delete net;
 }
 
@@ -1621,6 +1723,13 @@ int cnn_set_output_units(cnn_t* net, int kind) {
 }
 
 int cnn_get_output_units(const cnn_t* net) { return net ? net->out_units : CNN_E_ARG; }
+
+int cnn_set_launch_graph(cnn_t* net, int images_per_graph) {
+  if (!net || images_per_graph < 0 || images_per_graph > 1024) return fail(net ? &net->err : nullptr, CNN_E_ARG, "images_per_graph must lie in [0, 1024]");
+  if (images_per_graph != net->graph_images) drop_stage_graphs(net);
+  net->graph_images = images_per_graph;
+  return CNN_OK;
+}
 
 int cnn_set_grid(cnn_t* net, int n_workgroups) {
   if (!net || n_workgroups < 0) return CNN_E_ARG;

@@ -136,7 +136,22 @@ struct StatusDev {
 };
 
 // Per-call arguments.
+// What a replayed graph of stage launches cannot carry in its nodes: the arguments of the call it is launched for.
+// They lie in device memory; a node knows its image's place inside the graph (RunArgs::t_local), the first node of
+// the graph moves t0 on by the images of one graph.
+struct CallArgs {
+  const CNN_GLOBAL float* images;
+  const CNN_GLOBAL int* labels;
+  CNN_GLOBAL float* probs_out;
+  long long image_stride;
+  long long t0;          // image of the call the graph being replayed starts at
+  float lr;
+  int train;
+};
+
 struct RunArgs {
+  const CNN_GLOBAL CallArgs* call;  // set in the nodes of a graph: images, labels, outputs, rate and image number
+  int t_local;                      //   come from there (image call->t0 + t_local), not from the fields below
   const CNN_GLOBAL float* images;   // first image
   const CNN_GLOBAL int* labels;     // device labels, or NULL to use label_imm
   CNN_GLOBAL float* probs_out;      // optional [n_images][n_classes]

@@ -1350,12 +1350,23 @@ __device__ __forceinline__ void run_stage_items(const ProgramDev& P, const Stage
 __device__ __forceinline__ Ctx make_ctx(const ProgramDev& P, const RunArgs& a, long long t,
                                         StatusDev* status) {
   Ctx c;
+  if (a.call) {   // a node of a replayed graph: the call's arguments lie in device memory
+    const CNN_GLOBAL CallArgs& q = *a.call;
+    const long long tq = q.t0 + a.t_local;
+    c.image = q.images + tq * q.image_stride;
+    c.probs_out = q.probs_out ? q.probs_out + tq * P.n_classes : nullptr;
+    c.grad_out = nullptr;
+    c.label = q.labels[tq];
+    c.lr = q.lr;
+    c.train = q.train;
+  } else {
   c.image = a.images + t * a.image_stride;
   c.probs_out = a.probs_out ? a.probs_out + t * P.n_classes : nullptr;
   c.grad_out = a.grad_out;
   c.label = a.labels ? a.labels[t] : a.label_imm;
   c.lr = a.lr;
   c.train = a.train;
+  }
   if (a.train && (c.label < 0 || c.label >= P.n_classes)) {
     // a label outside the classes: the image is skipped and the host is told
     c.train = 0;
@@ -1587,6 +1598,50 @@ hipError_t launch_stage(int kind, int n_items, hipStream_t stream, const Program
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+// ---- the stage launches of several images as one graph ----------------------------------------------------
+// A launch costs about 2.5 us however little the kernel does, a kernel node of a graph about 1.5: the nets that
+// run one launch per stage (10 - 14 per image) replay a graph of the launches of a few images instead.  The
+// kernels of a node are the ones above; what changes from one replay to the next -- the images, labels, outputs
+// and rate of the call, and how far into it the graph starts -- lies in device memory (CallArgs).
+__global__ void k_call_set(CallArgs* d, CallArgs v) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *(CNN_GLOBAL CallArgs*)d = v;
+}
+__global__ void k_call_advance(CallArgs* d, int images) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) ((CNN_GLOBAL CallArgs*)d)->t0 += images;
+}
+hipError_t launch_call_set(hipStream_t stream, CallArgs* d_call, const CallArgs& v) {
+  hipLaunchKernelGGL(k_call_set, dim3(1), dim3(64), 0, stream, d_call, v);
+  return hipGetLastError();
+}
+const void* call_advance_kernel() { return (const void*)k_call_advance; }
+// the kernel of a stage kind, and of two kinds in one launch (null: none compiled)
+const void* stage_kernel(int kind) {
+  switch (kind) {
+    case ST_FRONTEND: return (const void*)k_frontend;
+    case ST_CONV_FWD: return (const void*)k_conv_fwd;
+    case ST_FC_FWD: return (const void*)k_fc_fwd;
+    case ST_HEAD: return (const void*)k_head;
+    case ST_FC_BWD: return (const void*)k_fc_bwd;
+    case ST_CONV_BWD: return (const void*)k_conv_bwd;
+    case ST_CONV_WGRAD: return (const void*)k_conv_wgrad;
+    case ST_CONV_FWD_MFMA: return (const void*)k_conv_fwd_mfma;
+    case ST_CONV_EPI: return (const void*)k_conv_epi;
+    case ST_CONV_BWD_MFMA: return (const void*)k_conv_bwd_mfma;
+    case ST_CONV_BWD_EPI: return (const void*)k_conv_bwd_epi;
+    case ST_CONV_WGRAD_MFMA: return (const void*)k_conv_wgrad_mfma;
+    default: return nullptr;
+  }
+}
+const void* stage_pair_kernel(int kind_a, int kind_b) {
+#define PAIR(KA, KB) if (kind_a == KA && kind_b == KB) return (const void*)k_pair<KA, KB>;
+  PAIR(ST_CONV_WGRAD, ST_CONV_BWD_EPI)
+  PAIR(ST_CONV_WGRAD_MFMA, ST_CONV_BWD_EPI)
+  PAIR(ST_CONV_WGRAD, ST_CONV_WGRAD)
+  PAIR(ST_CONV_WGRAD, ST_CONV_BWD)
+#undef PAIR
+  return nullptr;
 }
 
 // Stages s and s + 1 of kinds kind_a and kind_b in one launch; *done = false when no kernel is compiled for the pair
