@@ -333,6 +333,13 @@ def main():
             "traffic": traffic, "traffic_bytes_per_image": traffic_image, "traffic_measured_at_images_per_call": traffic_at,
             "traffic_source": src,
         }
+        if mode == "resident" and workload is not None:
+            import per_layer_report
+            _, lay = per_layer_report.trainable_layers(net, workload)
+            rows, us0 = per_layer_report.resident_phase_rows(net, workload, d_i.view(-1)[:64 * net.image_size].contiguous(),
+                                                             d_l[:64].contiguous(), lay, lr)
+            rec["per_layer"] = {"unit": "phases of one image, rank 0 of %d" % net.resident_ranks(),
+                                "us_per_image_rank0": round(us0, 2), "phases": rows}
         if note:
             rec["paper_context"] = note
         if with_cpu and not args.no_cpu_baseline:
@@ -405,6 +412,16 @@ def main():
                    "xcd_stride": args.xcd_stride},
         "roofline": roofline,
     }
+    if mode == "resident":
+        # the per-layer share of the roofline in the mode just timed (BASELINE's metric asks for it): the phases of
+        # one image as rank 0 of the team sees them (device clock stamps of the resident kernel), each with the
+        # team's arithmetic and its share of the fp32 peak of the compute units the team occupies
+        import per_layer_report
+        _, layers = per_layer_report.trainable_layers(net, wl)
+        rows, us_rank0 = per_layer_report.resident_phase_rows(net, wl, d_imgs.view(-1)[:64 * net.image_size].contiguous(),
+                                                              d_labs[:64].contiguous(), layers, wl.lr)
+        roofline["per_layer"] = {"unit": "phases of one image, rank 0 of %d" % net.resident_ranks(),
+                                 "us_per_image_rank0": round(us_rank0, 2), "phases": rows}
     net.close()
     nets.remove(net)
 
