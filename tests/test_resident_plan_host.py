@@ -181,7 +181,7 @@ def test_other_refusals():
     ("1x8x600-3C3-MP2-4C2S1-5N", 0), ("1x70x70-4C3-MP4-3C4-MP2-6N", 0), ("3x34x47-7C4S1-8C3-MP2-9C2-MP3-20N-6N", 4),
     ("1x40x40-70C5-MP4-300C3-MP1-10N", 0), ("1x28x28-6C5-MP2-100C5-MP2-8N", 0), ("1x28x28-6C5-MP2-100C5-MP2-8N", 5),
     ("1x28x28-40C5-MP2-80C5-MP2-8N", 38), ("1x28x28-3C5-MP2-250C5-MP2-8N", 0),
-    ("1x28x28-6C5-MP2-100C5-MP1-8N", 0), ("1x28x28-6C5-MP2-100C5-MP1-8N", 5), ("1x28x28-40C5-MP2-80C5-MP1-8N", 38),
+    ("1x28x28-6C5-MP2-100C9-MP1-8N", 0), ("1x28x28-6C5-MP2-100C9-MP1-8N", 5), ("1x28x28-40C5-MP2-80C9-MP1-8N", 12),
     ("1x47x47-6C4-MP2-100C5-MP3-8N", 0), ("1x65x65-8C4-MP2-20C5-MP3-6N", 3), ("2x60x60-3C5-MP4-7C4S1-MP3-4C1-MP1-5N", 2),
 ])
 def test_edge_shapes(arch, fan):
