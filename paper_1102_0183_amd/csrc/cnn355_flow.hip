@@ -1725,8 +1725,10 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
           gtagged* src = nullptr;
           if (l >= 1) {
             if (pend) {
+              if (l == 1) DSTAMP(90);
               if (l == n_conv - 1) fc1_update();
               if (Z.stream == 0) wgrad_fwd(lc, tag - 1u, true);
+              if (l == 1) DSTAMP(91);
             }
             if (Z.stream != 0 && ship_pend && !take_rows(lc, tag - 1u)) return false;
             const int nw = C.Mi * C.Hi * C.Wi;
@@ -1771,7 +1773,9 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       }
       STAMP(30);
       if (pend) {
+        DSTAMP(92);
         if (Z.stream == 0) wgrad_pull(IC<1>{}, lds + Z.o_prev);
+        DSTAMP(93);
         pend = false;
       }
       ship_pend = false;
