@@ -1142,11 +1142,18 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
       g.Mi = L.n_in; g.Hi = 1; g.Wi = 1; g.K = 1; g.Kx = 1; g.stride = 1; g.stride_x = 1; g.Mo = L.n_out; g.Wo = 1; g.P = 1;
     }
     const bool pooled = Kp * Kpx > 1;
-    // map tiles per workgroup: the choice that pads the fewest maps, the larger on a tie
+    // map tiles per workgroup: the choice that pads the fewest maps, the larger on a tie; tiles of 16 maps only
+    // where they pad fewer than tiles of 32 do (40 maps: 48 rows instead of 64), at least two of them a workgroup
+    // (an operand fetched from the staged images should feed several instructions)
     int best_pad = 0;
+    g.TR = 32;
     for (int mt : {4, 2, 1}) {
       const int pad = (g.Mo + 32 * mt - 1) / (32 * mt) * (32 * mt);
       if (!best_pad || pad < best_pad) { best_pad = pad; g.MT = mt; }
+    }
+    for (int mt : {6, 5, 4, 3, 2}) {
+      const int pad = (g.Mo + 16 * mt - 1) / (16 * mt) * (16 * mt);
+      if (pad < best_pad) { best_pad = pad; g.MT = mt; g.TR = 16; }
     }
     g.MoPad = best_pad;
     const int KK = g.K * g.Kx, HiWi = g.Hi * g.Wi;
@@ -1159,8 +1166,8 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
       g.n_img_max = (int)std::min<size_t>(std::max<size_t>(batch, 1), (size_t)((128 - 1 + cols_per_image - 1) / cols_per_image + 1));
       ic = 0; ic_pre = 0;
       for (int c = 1; c <= g.Mi; ++c) {
-        const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * 32;
-        if (in_f + 3 + w_f + (size_t)c * KK + 9 > budget) break;
+        const size_t in_f = (size_t)g.n_img_max * c * HiWi, w_f = (size_t)(c * KK + 1) * g.MT * g.TR;
+        if (in_f + 3 + w_f + (size_t)c * KK + (g.TR == 32 ? 9 : 20) > budget) break;
         if (HiWi == 1 && c < g.Mi && (c & (c - 1)) != 0) continue;
         ic = c;
         if (in_f <= 16 * 256 && w_f <= 48 * 256) ic_pre = c;
@@ -1188,7 +1195,7 @@ int batch_plan(cnn* net, size_t batch, BatchPlan& B) {
     // few columns and a long k range (fully connected layers, deep layers on small maps): the k
     // range is cut into slices, one workgroup each, until some 512 workgroups are in flight
     const int n_chunks = (g.Mi + ic - 1) / ic;
-    const size_t wgs = ((batch * g.P + 127) / 128) * (size_t)(g.MoPad / (32 * g.MT));
+    const size_t wgs = ((batch * g.P + 127) / 128) * (size_t)(g.MoPad / (g.TR * g.MT));
     int ks = 1;
     if (wgs < 512 && n_chunks > 1) ks = (int)std::min<size_t>((size_t)n_chunks, (512 + wgs - 1) / wgs);
     g.chunks_per_slice = (n_chunks + ks - 1) / ks;

@@ -36,58 +36,73 @@ __device__ __forceinline__ float b_act(float a) {
 constexpr int PRE_IN = 16;     // floats per thread a prefetched chunk may hold: staged images ...
 constexpr int PRE_W = 48;      // ... and rows of Wt
 
-// Workgroup (x, y): columns [128 x, 128 x + 128) and map tiles [MT y, MT y + MT) of 32 maps each.
+// Workgroup (x, y): columns [128 x, 128 x + 128) and map tiles [MT y, MT y + MT) of TR maps each.  TR = 32:
+// v_mfma_f32_32x32x2_f32, a wavefront's 32 columns are one tile wide, a lane takes the even or the odd k.  TR = 16:
+// v_mfma_f32_16x16x4_f32, the 32 columns are two tiles of 16, a lane takes one k in four; it is chosen where 16-row
+// tiles pad fewer maps (40 maps: 48 rows instead of 64).
 // Every wavefront owns 32 columns and all MT map tiles, so one operand fetched from the staged
 // images feeds MT matrix instructions.  The k range is walked in chunks of IC input maps: the
 // chunk's maps of every image the columns touch, and the chunk's rows of Wt, are staged in LDS.
 // With g.prefetch the next chunk is fetched into registers while the matrix cores work on the
 // present one (global latency hidden behind arithmetic); the host sets it only when a chunk
 // fits the register budget (PRE_IN, PRE_W floats per thread).
-template <int MT>
+template <int MT, int TR>
 __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   extern __shared__ float lds[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int lrow = lane & 31, lk = lane >> 5;
+  constexpr int KS = TR == 32 ? 2 : 4;             // k values one instruction takes, one per group of 64 / KS lanes
+  constexpr int CT = 32 / TR;                      // column tiles of a wavefront
+  constexpr int AV = TR == 32 ? 16 : 4;            // accumulator floats per lane and tile
+  const int lrow = lane & (TR - 1), lk = lane / TR;
   const int HiWi = g.Hi * g.Wi, KK = g.K * g.Kx;
   const int slot_sz = g.IC * HiWi;
   const int KC = g.IC * KK;                        // k per full chunk
-  constexpr int WROW = MT * 32;
+  constexpr int WROW = MT * TR;
   float* lds_in = lds;                              // [n_img_max][IC][Hi*Wi]
   float* lds_w = lds + ((g.n_img_max * slot_sz + 3) & ~3);  // [KC + 1][MT * 32]; the row behind the last is zero
-  // byte offset of k inside a staged image, even k and odd k apart so that a lane (which takes the
-  // k of its own parity) finds the four it needs next to each other: [2][KH], KH a multiple of 4
-  const int KH = (((KC + 1) >> 1) + 3) & ~3;
+  // byte offset of k inside a staged image, the k of every residue mod KS apart so that a lane (which takes the
+  // k of its own residue) finds the four it needs next to each other: [KS][KH], KH a multiple of 4
+  const int KH = (((KC + KS - 1) / KS) + 3) & ~3;
   int* koff = (int*)(lds_w + (KC + 1) * WROW);
 
   // (columns are counted in 32 bits: the host keeps batch * P below 2^31)
   const int N = (int)g.N;
   const int n0 = blockIdx.x * BCOLS;
-  const int mt0 = blockIdx.y * MT;
+  const int mt0 = blockIdx.y * MT;                 // first tile (of TR maps) of the workgroup
   const int b_lo = n0 / g.P;
   const int n_last = min(n0 + BCOLS, N) - 1;
   const int n_img = n_last / g.P - b_lo + 1;
 
-  for (int x = tid; x < 2 * KH; x += BT) {
-    const int par = x >= KH, h = x - par * KH;
-    const int k = min(2 * h + par, KC - 1);
+  for (int x = tid; x < KS * KH; x += BT) {
+    const int par = x / KH, h = x - par * KH;
+    const int k = min(KS * h + par, KC - 1);
     const int c = k / KK, t = k - c * KK;
     const int ky = t / g.Kx, kx = t - ky * g.Kx;
     koff[x] = (c * HiWi + ky * g.Wi + kx) * 4;
   }
-  const int n = n0 + wave * 32 + lrow;
-  const bool col_ok = n < N;
-  int b = 0, p = 0, pbase = 0;
-  if (col_ok) {
-    b = n / g.P;
-    p = n - b * g.P;
-    const int y = p / g.Wo, x = p - y * g.Wo;
-    pbase = (b - b_lo) * slot_sz + y * (g.Kp * g.stride) * g.Wi + x * (g.Kpx * g.stride_x);
+  // the lane's column in each of the wavefront's column tiles
+  bool col_ok[CT];
+  int cb[CT], cp[CT], pbase[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    const int n = n0 + wave * 32 + ct * TR + lrow;
+    col_ok[ct] = n < N;
+    cb[ct] = 0; cp[ct] = 0; pbase[ct] = 0;
+    if (col_ok[ct]) {
+      cb[ct] = n / g.P;
+      cp[ct] = n - cb[ct] * g.P;
+      const int y = cp[ct] / g.Wo, x = cp[ct] - y * g.Wo;
+      pbase[ct] = (cb[ct] - b_lo) * slot_sz + y * (g.Kp * g.stride) * g.Wi + x * (g.Kpx * g.stride_x);
+    }
   }
-  v16f acc[MT], best[MT];
+  typedef float accv __attribute__((ext_vector_type(AV)));
+  accv acc[MT][CT], best[MT][CT];
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { acc[m][v] = 0.f; best[m][v] = -INFINITY; }
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int v = 0; v < AV; ++v) { acc[m][ct][v] = 0.f; best[m][ct][v] = -INFINITY; }
 
   // Element e of a chunk's staged images is float x of image slot s, e = s * cnt + x, where
   // cnt = n_ic * Hi * Wi is the run of contiguous floats the chunk takes from one image; a thread
@@ -117,7 +132,7 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
   auto w_val = [&](int ic0, int kc, int e4) -> v4f {
     const int kr = e4 / (WROW / 4), c = (e4 - kr * (WROW / 4)) * 4;
     if (kr >= kc) return v4f{0.f, 0.f, 0.f, 0.f};
-    return *(const CNN_GLOBAL v4f*)(g.wt + ((long long)ic0 * KK * g.MoPad + mt0 * 32) + (unsigned)(kr * g.MoPad + c));
+    return *(const CNN_GLOBAL v4f*)(g.wt + ((long long)ic0 * KK * g.MoPad + mt0 * TR) + (unsigned)(kr * g.MoPad + c));
   };
   // straight to LDS, eight loads in flight per thread (first chunk, and every chunk without prefetch)
   auto stage_now = [&](int ic0) {
@@ -194,73 +209,88 @@ __global__ void __launch_bounds__(BT) k_batch_gemm(BatchGemm g) {
     // complete when its loop ends).
     for (int d = 0; d < g.Kp * g.Kpx; ++d) {
       const int dy = d / g.Kpx, dx = d - dy * g.Kpx;
-      const int pb = pbase + dy * g.stride * g.Wi + dx * g.stride_x;
-      // two k per instruction (lanes 0..31 the even one, lanes 32..63 the odd one); the operands
-      // of four instructions per map tile are fetched together.  Whole groups of eight k first,
-      // without any clamping; then the tail, where k beyond the chunk meets the zero row of Wt.
-      const char* in_b = (const char*)lds_in + pb * 4;
-      const int kc8 = kc & ~7;
-      for (int kk = 0; kk < kc8; kk += 8) {
-        const int4 ko = *(const int4*)(koff + lk * KH + (kk >> 1));
+      const int pd = dy * g.stride * g.Wi + dx * g.stride_x;
+      // KS k per instruction (lanes 0 .. 64/KS - 1 the first, and so on); the operands of four instructions per
+      // tile are fetched together.  Whole groups of 4 KS k first, without any clamping; then the tail, where k
+      // beyond the chunk meets the zero row of Wt.
+      const char* in_b[CT];
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) in_b[ct] = (const char*)lds_in + (pbase[ct] + pd) * 4;
+#define CNN355_MAC(a, bv)                                                                                            \
+  _Pragma("unroll") for (int u = 0; u < 4; ++u)                                                                      \
+  _Pragma("unroll") for (int m = 0; m < MT; ++m)                                                                     \
+  _Pragma("unroll") for (int ct = 0; ct < CT; ++ct) {                                                                \
+    if constexpr (TR == 32) acc[m][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u][ct], acc[m][ct], 0, 0, 0); \
+    else acc[m][ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][m], bv[u][ct], acc[m][ct], 0, 0, 0);                  \
+  }
+      constexpr int KG = 4 * KS;
+      const int kcg = kc - kc % KG;
+      for (int kk = 0; kk < kcg; kk += KG) {
+        const int4 ko = *(const int4*)(koff + lk * KH + kk / KS);
         const float* wr = lds_w + (kk + lk) * WROW + lrow;
-        float a[4][MT], bv[4];
+        float a[4][MT], bv[4][CT];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
-          for (int m = 0; m < MT; ++m) a[u][m] = wr[2 * u * WROW + m * 32];
-        bv[0] = *(const float*)(in_b + ko.x);
-        bv[1] = *(const float*)(in_b + ko.y);
-        bv[2] = *(const float*)(in_b + ko.z);
-        bv[3] = *(const float*)(in_b + ko.w);
+          for (int m = 0; m < MT; ++m) a[u][m] = wr[KS * u * WROW + m * TR];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
+        for (int ct = 0; ct < CT; ++ct) {
+          bv[0][ct] = *(const float*)(in_b[ct] + ko.x);
+          bv[1][ct] = *(const float*)(in_b[ct] + ko.y);
+          bv[2][ct] = *(const float*)(in_b[ct] + ko.z);
+          bv[3][ct] = *(const float*)(in_b[ct] + ko.w);
+        }
+        CNN355_MAC(a, bv)
       }
-      if (kc8 < kc) {
-        float a[4][MT], bv[4];
+      if (kcg < kc) {
+        float a[4][MT], bv[4][CT];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int k = kc8 + 2 * u + lk;
+          const int k = kcg + KS * u + lk;
           const int kr = min(k, kc);               // row kc is the zero row
-          const int ko = koff[lk * KH + min(k >> 1, KH - 1)];
+          const int ko = koff[lk * KH + min(k / KS, KH - 1)];
 #pragma unroll
-          for (int m = 0; m < MT; ++m) a[u][m] = lds_w[kr * WROW + m * 32 + lrow];
-          bv[u] = *(const float*)(in_b + ko);
+          for (int m = 0; m < MT; ++m) a[u][m] = lds_w[kr * WROW + m * TR + lrow];
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) bv[u][ct] = *(const float*)(in_b[ct] + ko);
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int m = 0; m < MT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][m], bv[u], acc[m], 0, 0, 0);
+        CNN355_MAC(a, bv)
       }
+#undef CNN355_MAC
       if (g.Kp * g.Kpx > 1) {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            best[m][v] = fmaxf(best[m][v], acc[m][v]);
-            acc[m][v] = 0.f;
-          }
+          for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int v = 0; v < AV; ++v) {
+              best[m][ct][v] = fmaxf(best[m][ct][v], acc[m][ct][v]);
+              acc[m][ct][v] = 0.f;
+            }
       }
     }
     __syncthreads();
   }
-  if (!col_ok) return;
-  // element v of a lane: row (v / 4) * 8 + (lane / 32) * 4 + v % 4 of the tile, column lane % 32
+  // element v of a lane, 32-row tiles: row (v / 4) * 8 + (lane / 32) * 4 + v % 4 of the tile, column lane % 32;
+  // 16-row tiles: row (lane / 16) * 4 + v, column lane % 16
   gf dst = g.out + (long long)blockIdx.z * g.slice_stride;
-  const unsigned o0 = (unsigned)b * (unsigned)g.out_stride + (unsigned)p;
 #pragma unroll
-  for (int m = 0; m < MT; ++m)
+  for (int ct = 0; ct < CT; ++ct) {
+    if (!col_ok[ct]) continue;
+    const unsigned o0 = (unsigned)cb[ct] * (unsigned)g.out_stride + (unsigned)cp[ct];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int j = (mt0 + m) * 32 + (v >> 2) * 8 + lk * 4 + (v & 3);
-      if (j < g.Mo) {
-        float s = (g.Kp * g.Kpx > 1) ? best[m][v] : acc[m][v];
-        if (g.fuse) s += g.bias[j];
-        if (g.fuse == 1) s = b_act(s);
-        dst[o0 + (unsigned)j * (unsigned)g.P] = s;
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+      for (int v = 0; v < AV; ++v) {
+        const int j = (mt0 + m) * TR + (TR == 32 ? (v >> 2) * 8 + lk * 4 + (v & 3) : lk * 4 + v);
+        if (j < g.Mo) {
+          float sv = (g.Kp * g.Kpx > 1) ? best[m][ct][v] : acc[m][ct][v];
+          if (g.fuse) sv += g.bias[j];
+          if (g.fuse == 1) sv = b_act(sv);
+          dst[o0 + (unsigned)j * (unsigned)g.P] = sv;
+        }
       }
-    }
+  }
 }
 
 // bias + scaled tanh + max-pooling (Sec. 2.2, 2.3) of the raw sums of a whole batch; the sums may
@@ -341,13 +371,13 @@ __global__ void __launch_bounds__(256) k_batch_zero(gf p, long long n) {
   if (x < n) p[x] = 0.f;
 }
 
-template <int MT>
+template <int MT, int TR>
 hipError_t launch_gemm_mt(hipStream_t stream, const BatchGemm& g, size_t lds_bytes) {
-  hipError_t e = hipFuncSetAttribute((const void*)k_batch_gemm<MT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  hipError_t e = hipFuncSetAttribute((const void*)k_batch_gemm<MT, TR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   const unsigned gx = (unsigned)((g.N + BCOLS - 1) / BCOLS);
-  const unsigned gy = (unsigned)((g.MoPad / 32 + MT - 1) / MT);
-  hipLaunchKernelGGL(k_batch_gemm<MT>, dim3(gx, gy, (unsigned)g.KS), dim3(BT), lds_bytes, stream, g);
+  const unsigned gy = (unsigned)((g.MoPad / TR + MT - 1) / MT);
+  hipLaunchKernelGGL((k_batch_gemm<MT, TR>), dim3(gx, gy, (unsigned)g.KS), dim3(BT), lds_bytes, stream, g);
   return hipGetLastError();
 }
 
@@ -355,17 +385,29 @@ hipError_t launch_gemm_mt(hipStream_t stream, const BatchGemm& g, size_t lds_byt
 
 size_t batch_gemm_lds_bytes(const BatchGemm& g) {
   const int KC = g.IC * g.K * g.Kx;
-  const size_t KH = ((((size_t)KC + 1) >> 1) + 3) & ~(size_t)3;
-  return ((((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + 3) & ~(size_t)3) + (size_t)(KC + 1) * g.MT * 32 + 2 * KH) * sizeof(float);
+  const size_t KS = g.TR == 32 ? 2 : 4;
+  const size_t KH = ((((size_t)KC + KS - 1) / KS) + 3) & ~(size_t)3;
+  return ((((size_t)g.n_img_max * g.IC * g.Hi * g.Wi + 3) & ~(size_t)3) + (size_t)(KC + 1) * g.MT * g.TR + KS * KH) * sizeof(float);
 }
 
 hipError_t launch_batch_gemm(hipStream_t stream, const BatchGemm& g) {
   if (g.N <= 0) return hipSuccess;
   const size_t lds_bytes = batch_gemm_lds_bytes(g);
+  if (g.TR == 32) {
+    switch (g.MT) {
+      case 1: return launch_gemm_mt<1, 32>(stream, g, lds_bytes);
+      case 2: return launch_gemm_mt<2, 32>(stream, g, lds_bytes);
+      case 4: return launch_gemm_mt<4, 32>(stream, g, lds_bytes);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  if (g.TR != 16) return hipErrorInvalidValue;
   switch (g.MT) {
-    case 1: return launch_gemm_mt<1>(stream, g, lds_bytes);
-    case 2: return launch_gemm_mt<2>(stream, g, lds_bytes);
-    case 4: return launch_gemm_mt<4>(stream, g, lds_bytes);
+    case 2: return launch_gemm_mt<2, 16>(stream, g, lds_bytes);
+    case 3: return launch_gemm_mt<3, 16>(stream, g, lds_bytes);
+    case 4: return launch_gemm_mt<4, 16>(stream, g, lds_bytes);
+    case 5: return launch_gemm_mt<5, 16>(stream, g, lds_bytes);
+    case 6: return launch_gemm_mt<6, 16>(stream, g, lds_bytes);
     default: return hipErrorInvalidValue;
   }
 }

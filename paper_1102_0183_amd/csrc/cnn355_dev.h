@@ -234,7 +234,8 @@ struct BatchGemm {
   int Kp;                        // Kp * Kpx > 1: a column is a pooled pixel, its Kp x Kpx window is maximised inside the product
   int IC;                        // input maps staged per chunk
   int n_img_max;                 // images the 128 columns of a workgroup can touch
-  int MT;                        // map tiles (of 32) per workgroup: 1, 2 or 4
+  int MT;                        // map tiles per workgroup: 1, 2 or 4 of 32 maps, or 2 .. 6 of 16
+  int TR;                        // maps per tile: 32 (v_mfma_f32_32x32x2_f32) or 16 (v_mfma_f32_16x16x4_f32)
   int KS, chunks_per_slice;      // the k range is cut into KS slices of so many chunks, one per blockIdx.z,
   long long slice_stride;        //   each writing its own plane of `out`, slice_stride floats apart
   int prefetch;                  // the next chunk is fetched into registers during the arithmetic
