@@ -236,6 +236,8 @@ def main():
         if mode == "resident":
             ranks = net.resident_ranks() if hasattr(net, "resident_ranks") else 0
             count = 2 * (n_conv - 1) + 1
+            if any(q.get("by_cols") for q in binding.resident_plan(net.arch).get("fc", [])):
+                count += 2      # a hidden layer held by columns: its partial sums up, the deltas of its inputs down
             key = "crossing_us_%d_ranks" % ranks
             if key not in floors:
                 floors[key] = net.measure_crossing(max(2, ranks), 64, 200)

@@ -330,7 +330,7 @@ size_t carve(cnn* net, void* base) {
   }
   net->d_flow_ptrs = c.take<FlowPtrs>(1);
   {  // resident mode: tagged exchange buffers, sized for any team (see plan_flow for the split)
-    size_t words = 0, last_maps = 0, first_fc = 0;
+    size_t words = 0, last_maps = 0, first_fc = 0, n_fc_seen = 0;
     for (size_t l = 1; l < A.size(); ++l) {
       if (A[l].kind == CNN_LAYER_CONV) {
         const bool pooled = l + 1 < A.size() && A[l + 1].kind == CNN_LAYER_POOL;
@@ -339,8 +339,10 @@ size_t carve(cnn* net, void* base) {
         words += 2 * 256 * (small / A[l].maps);  // pulled sums of the shares of a map's pull (fewer than 256 of them)
         words += 2 * (size_t)A[l].maps * A[l - 1].maps * (A[l].K * A[l].Kx + 4);  // adjusted filters on their way to the forward copies
         last_maps = A[l].maps;
-      } else if (A[l].kind == CNN_LAYER_FC && !first_fc) {
-        first_fc = A[l].maps;
+      } else if (A[l].kind == CNN_LAYER_FC) {
+        if (!first_fc) first_fc = A[l].maps;
+        // a second fully connected layer held by columns: partial sums of up to 256 ranks, deltas of its inputs
+        if (++n_fc_seen == 2) words += 2 * (size_t)256 * A[l].maps + 2 * (size_t)A[l - 1].maps * A[l - 1].h * A[l - 1].w;
       }
     }
     words += 2 * std::min<size_t>(last_maps, 256) * first_fc;
@@ -843,6 +845,11 @@ void plan_flow(cnn* net) {
     const LayerDev& L = P.layers[n_conv + f];
     FlowFcPtrs& C = Q.fc[f];
     C.w = L.w; C.bias = L.bias; C.act = L.act; C.delta = L.delta; C.w_canon = L.w_canon; C.b_canon = L.b_canon;
+    C.x_part = nullptr; C.x_dprev = nullptr;
+    if (Z.fc[f].by_cols) {
+      C.x_part = xtake((size_t)2 * std::min(Z.G, Z.fc[f].n_in) * Z.fc[f].n_out);
+      C.x_dprev = xtake((size_t)2 * Z.fc[f].n_in);
+    }
   }
   Q.xp = xtake((size_t)2 * Z.n_col_ranks * Z.fc[0].n_out);
   if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
@@ -1660,8 +1667,10 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
     for (int f = 0; f < Z.n_fc; ++f) {
       const FcSpec& Q = Z.fc[f];
       const std::string c = "fc" + std::to_string(f) + ".";
-      t += "fc " + std::to_string(f) + " n_in " + std::to_string(Q.n_in) + " n_out " + std::to_string(Q.n_out) + "\n";
-      region(c + "w", Q.o_w, f == 0 ? (long long)Cl.n_own * Cl.Hp * Cl.Wp * Q.n_out : (long long)Q.n_out * Q.n_in);
+      t += "fc " + std::to_string(f) + " n_in " + std::to_string(Q.n_in) + " n_out " + std::to_string(Q.n_out) +
+           " by_cols " + std::to_string(Q.by_cols) + " n_own " + std::to_string(Q.n_own) + "\n";
+      region(c + "w", Q.o_w, f == 0 ? (long long)Cl.n_own * Cl.Hp * Cl.Wp * Q.n_out
+                             : Q.by_cols ? (long long)Q.n_own * Q.n_out : (long long)Q.n_out * Q.n_in);
       region(c + "b", Q.o_b, Q.n_out);
       region(c + "act", Q.o_act, Q.n_out);
       region(c + "delta", Q.o_delta, Q.n_out);

@@ -213,6 +213,10 @@ struct FlowFcPtrs {
   CNN_GLOBAL float* act;
   CNN_GLOBAL float* delta;
   long long w_canon, b_canon;
+  // a layer held by columns (FcSpec::by_cols): the ranks' partial sums [2][ranks][n_out] going forward, the deltas
+  // of the layer's inputs [2][n_in] going back (tagged words)
+  CNN_GLOBAL tagged_t* x_part;
+  CNN_GLOBAL tagged_t* x_dprev;
 };
 struct FlowPtrs {
   FlowConvPtrs conv[FLOW_MAX_CONV];

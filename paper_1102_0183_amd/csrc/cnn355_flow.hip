@@ -482,7 +482,15 @@ __device__ __forceinline__ void flow_load(const Rt& rt) {
   for_up<ID, 1, FLOW_MAX_FC>(Z.n_fc, [&](auto fc_) {
     const int f = lv(fc_);
     const FcSpec& L = Z.fc[f];
-    for (int x = tid; x < L.n_out * L.n_in; x += WG) lds[L.o_w + x] = Q.fc[f].w[x];
+    if (L.by_cols) {  // the columns rank, rank + G, ... of the weight matrix, column after column
+      const int nq = n_mine(L.n_in, rank, G) * L.n_out;
+      for (int x = tid; x < nq; x += WG) {
+        const int c = x / L.n_out, k = x - c * L.n_out;
+        lds[L.o_w + x] = Q.fc[f].w[(size_t)k * L.n_in + rank + c * G];
+      }
+    } else {
+      for (int x = tid; x < L.n_out * L.n_in; x += WG) lds[L.o_w + x] = Q.fc[f].w[x];
+    }
     for (int k = tid; k < L.n_out; k += WG) lds[L.o_b + k] = Q.fc[f].bias[k];
     return true;
   });
@@ -525,14 +533,22 @@ __device__ __forceinline__ void flow_store(const Rt& rt) {
     if (rank == 0)
       for (int k = tid; k < n1; k += WG) Q.fc[0].bias[k] = lds[L.o_b + k];
   }
-  if (rank == 0)
-    for_up<ID, 1, FLOW_MAX_FC>(Z.n_fc, [&](auto fc_) {
-      const int f = lv(fc_);
-      const FcSpec& L = Z.fc[f];
+  for_up<ID, 1, FLOW_MAX_FC>(Z.n_fc, [&](auto fc_) {
+    const int f = lv(fc_);
+    const FcSpec& L = Z.fc[f];
+    if (L.by_cols) {
+      const int nq = n_mine(L.n_in, rank, G) * L.n_out;
+      for (int x = tid; x < nq; x += WG) {
+        const int c = x / L.n_out, k = x - c * L.n_out;
+        Q.fc[f].w[(size_t)k * L.n_in + rank + c * G] = lds[L.o_w + x];
+      }
+    } else if (rank == 0) {
       for (int x = tid; x < L.n_out * L.n_in; x += WG) Q.fc[f].w[x] = lds[L.o_w + x];
+    }
+    if (rank == 0)
       for (int k = tid; k < L.n_out; k += WG) Q.fc[f].bias[k] = lds[L.o_b + k];
-      return true;
-    });
+    return true;
+  });
 }
 
 // ---- the two multiply-accumulate loops -------------------------------------------------------------
@@ -1784,10 +1800,28 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       STAMP(31);
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----
-    for_up<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
+    if (!for_up<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
       const int f = lv(fc_);
       const FcSpec& L = Z.fc[f];
       float* y = lds + L.o_act;
+      if (L.by_cols) {
+        // a layer too large to hold whole: partial sums over the own columns, added up by every rank
+        const int n_out = uni_of<ID>(L.n_out), n_in = uni_of<ID>(L.n_in);
+        const int NQ = min(G, n_in), nq = n_mine(n_in, rank, G);
+        const float* wq = lds + L.o_w;
+        const float* v = lds + Z.fc[f >= 1 ? f - 1 : 0].o_act;
+        const FlowFcPtrs& PL = Q.fc[f];
+        if (rank < NQ) {
+          gtagged* xq = PL.x_part + ((size_t)par * NQ + rank) * n_out;
+          for (int k = tid; k < n_out; k += WG) {
+            float s = 0.f;
+            for (int c = 0; c < nq; ++c) s = fmaf(wq[c * n_out + k], v[rank + c * G], s);
+            put_f(xq + k, s, tag);
+          }
+        }
+        return flow_reduce_partials(rt, PL.x_part + (size_t)par * NQ * n_out, NQ, n_out, lds + L.o_b, y, lds + L.o_dact,
+                                    part, tag, true);
+      }
       flow_matvec(lds + L.o_w, lds + L.o_b, lds + Z.fc[f >= 1 ? f - 1 : 0].o_act, y, uni_of<ID>(L.n_out), uni_of<ID>(L.n_in));
       if (!L.is_output) {
         float* dy = lds + L.o_dact;
@@ -1799,7 +1833,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         __syncthreads();
       }
       return true;
-    });
+    })) return;
     STAMP(32);
     // soft-max, cross-entropy error, output delta  delta_k = p_k - [k == label].  With at most 64
     // classes every wavefront works them out for itself (lane k holds class k), so nobody waits
@@ -1898,7 +1932,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
     if (!train) continue;
 
     // ---- BP + AW, fully connected layers behind the first (every rank, same arithmetic) ----
-    for_down<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
+    if (!for_down<ID, 1, FLOW_MAX_FC>(n_fc, [&](auto fc_) {
       const int f = lv(fc_);
       const FcSpec& L = Z.fc[f];
       const FlowFcPtrs& PL = Q.fc[f];
@@ -1910,6 +1944,32 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       float* dprev = lds + Z.fc[f >= 1 ? f - 1 : 0].o_delta;
       const int n_in = uni_of<ID>(L.n_in), n_out = uni_of<ID>(L.n_out);
       const bool from_reg = wave_softmax && f == n_fc - 1;
+      if (L.by_cols) {
+        // own columns: a wavefront per column works out the delta of the unit below, adjusts the column and
+        // sends the delta to everybody
+        const int nq = n_mine(n_in, rank, G);
+        const int wave = tid >> 6, lane = tid & 63;
+        for (int c = wave; c < nq; c += WG / 64) {
+          const int m = rank + c * G;
+          const float vm = v[m];
+          float g = 0.f;
+          for (int k = lane; k < n_out; k += 64) {
+            const float wv = W[c * n_out + k], dk = d[k];
+            g = fmaf(wv, dk, g);
+            if (g_out) g_out[PL.w_canon + (long long)k * n_in + m] = dk * vm;
+            else W[c * n_out + k] = fmaf(-lr, dk * vm, wv);
+          }
+          g = f_wave_sum(g);
+          if (lane == 0) put_f(PL.x_dprev + (size_t)par * n_in + m, g * fprev[m], tag);
+        }
+        for (int k = tid; k < n_out; k += WG) {
+          const float dk = d[k];
+          if (g_out) { if (rank == 0) g_out[PL.b_canon + k] = dk; }
+          else b[k] = fmaf(-lr, dk, b[k]);
+          if (taps && rank == 0) PL.delta[k] = dk;
+        }
+        return gather(rt, (unsigned int*)dprev, PL.x_dprev + (size_t)par * n_in, n_in, tag);
+      }
       for (int m = tid; m < n_in; m += WG) {
         const float vm = v[m];
         float g = 0.f;
@@ -1941,7 +2001,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       }
       __syncthreads();
       return true;
-    });
+    })) return;
     STAMP(34);
     {  // ---- BP + AW, first fully connected layer: own columns ----
       const float* wc = lds + L1.o_w;

@@ -52,7 +52,12 @@ struct ConvSpec {
 
 struct FcSpec {
   int n_in, n_out, is_output;
-  int o_w;      // first layer: [columns of the own maps][n_out]; others: [n_out][n_in], every rank
+  int by_cols;  // second layer only: 1 when its weights are too many to keep a copy in every rank.  Then it is
+                // held by columns like the first: rank r has columns r, r + G, ... (at most n_own of them),
+                // the ranks exchange partial sums going forward and the deltas of their own inputs going back
+  int n_own;    // by_cols: most columns a rank holds, ceil(n_in / G)
+  int o_w;      // first layer: [columns of the own maps][n_out]; a layer held by columns: [n_own][n_out];
+                // others: [n_out][n_in], every rank
   int o_b;      // [n_out]
   int o_act;    // [n_out]
   int o_delta;  // [n_out]
@@ -109,6 +114,9 @@ constexpr long long flow_border_map(int Hi, int Wi, int K) { return ((long long)
 // The pull that visits winners only (pull_slots): a connection's HW winners are taken by UW lanes at a time
 // (all of them when HW <= 64, else HW split into the fewest equal parts of at most 64), and a workgroup works on
 // (WG / 64) * (64 / UW) such units at once when it has room for as many copies of its input maps.
+// A fully connected layer behind the first is kept whole by every rank up to this many weights; a larger second
+// layer (300N-100N of Sec. 4.3: 30 000) is held by columns instead, at the price of two more crossings per image.
+constexpr int FLOW_FC_REPLICATE_MAX = 8192;
 // Any pooling at all makes it pay (measured: 2 x 2 rectangles, a quarter of the terms: cfg4a 55.8 -> 54.0 us per
 // image, cfg5 16.5 -> 16.2; 3 x 3 and 4 x 4: the benchmark net 16.3 -> 15.6, cfg3 43.3 -> 38.1).
 constexpr int FLOW_WINNERS_MIN_KP = 2;
@@ -257,7 +265,10 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
   Z.n_col_ranks = flow_min(G, Cl.Mo);
   for (int f = 0; f < n_fc; ++f) {
     FcSpec& Q = Z.fc[f];
-    Q.o_w = take(f == 0 ? (long long)Cl.n_own * Cl.Hp * Cl.Wp * Q.n_out : (long long)Q.n_out * Q.n_in);
+    Q.by_cols = (f == 1 && !Q.is_output && (long long)Q.n_out * Q.n_in > FLOW_FC_REPLICATE_MAX) ? 1 : 0;
+    Q.n_own = Q.by_cols ? (Q.n_in + G - 1) / G : 0;
+    Q.o_w = take(f == 0 ? (long long)Cl.n_own * Cl.Hp * Cl.Wp * Q.n_out
+                        : Q.by_cols ? (long long)Q.n_own * Q.n_out : (long long)Q.n_out * Q.n_in);
     Q.o_b = take(Q.n_out);
     Q.o_act = take(Q.n_out);
     Q.o_delta = take(Q.n_out);

@@ -152,6 +152,54 @@ def test_streamed_resident_plans(arch, fan, team):
     g.close()
 
 
+# Networks with a large hidden layer behind the first fully connected one (Sec. 3's CIFAR nets end in 300N-100N-10N):
+# the resident plan holds that layer by columns, like the first one.
+BY_COLUMNS = [
+    ("1x20x20-6C5-MP2-12C4-MP1-120N-90N-7N", (0, 0), 0.1, False),            # ten columns a rank
+    ("1x20x20-6C5-MP2-12C4-MP1-120N-90N-7N", (5, 1), 0.1, False),            # 24 columns a rank, ranks with 3 and 2 maps
+    ("1x12x12-100C3-MP2-90N-100N-5N", (0, 0), 0.05, False),                  # more ranks than columns
+    ("1x16x16-7C3-MP2-100N-83N-11N-4N", (0, 0), 0.1, False),                 # two more layers behind it; ragged columns
+    ("3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", (0, 0), 0.05, False),
+    ("3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", (50, 1), 0.05, False),
+    ("3x32x32-200C3-MP3-200C3-MP2-200C3-MP2-300N-100N-10N", (0, 0), 0.05, True),   # with streamed inputs
+]
+
+
+@pytest.mark.parametrize("arch,team,wscale,streams", BY_COLUMNS)
+def test_resident_plans_with_a_hidden_layer_held_by_columns(arch, team, wscale, streams):
+    print("case", arch, team, flush=True)
+    g, o = _pair(arch, {}, 0, 1, 13, wscale=wscale)
+    g.set_mode(binding.MODE_RESIDENT)
+    if team != (0, 0):
+        g.set_team(*team)
+    plan = binding.resident_plan(arch, 0, *team)
+    assert plan["fc"][1]["by_cols"] == 1 and bool(g.resident_streams()) == streams
+    rng = np.random.default_rng(29)
+    imgs = rng.uniform(-1, 1, (10, g.image_size)).astype(np.float32)
+    labs = rng.integers(0, g.num_classes, size=10).astype(np.int32)
+    grad_g = g.debug_gradients(to_dev(imgs[0]), int(labs[0]))
+    grad_o, loss_o = o.gradients(imgs[0], int(labs[0]))
+    compare_forward_state(g, o)
+    compare_backward_state(g, o)
+    assert abs(g.loss() - loss_o) <= 1e-5 * max(1.0, abs(loss_o))
+    for (a, b) in layer_bounds(o):
+        assert rel_err(grad_g[a:b], grad_o[a:b]) <= TOL_ACT, (a, b)
+    w0 = g.get_weights()
+    adopted = lockstep_train(g, o, imgs, labs, 0.01)
+    w_step = g.get_weights()
+    print("  near-tie winners adopted:", adopted, flush=True)
+    assert rel_err(w_step, o.get_weights()) <= TOL_W100
+    # the batched call lands on the same bits as the image-by-image calls, and on those of the launch-per-stage mode
+    g.set_weights(w0)
+    g.train_many(to_dev(imgs), to_dev(labs), 0.01)
+    np.testing.assert_array_equal(g.get_weights(), w_step)
+    g.set_weights(w0)
+    g.train_many(to_dev(imgs[:5]), to_dev(labs[:5]), 0.01)
+    g.train_many(to_dev(imgs[5:]), to_dev(labs[5:]), 0.01)
+    np.testing.assert_array_equal(g.get_weights(), w_step)
+    g.close()
+
+
 def test_create_errors():
     import torch
     for arch, code in [("1x29x29-20C4-MP4-10N", binding.E_SHAPE), ("1x29x29-20C4", binding.E_SYNTAX),

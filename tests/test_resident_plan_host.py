@@ -122,6 +122,15 @@ def check_plan(p, arch, n_ranks=0, stride=0):
     assert p["fc"][0]["n_in"] == last["Mo"] * last["Hp"] * last["Wp"]
     assert size["fc0.w"] == last["n_own"] * last["Hp"] * last["Wp"] * p["fc"][0]["n_out"]
     assert size["part"] >= wg
+    # the layers behind it are held whole by every rank, except a hidden second layer of more than 8192 weights:
+    # that one by columns rank, rank + G, ... of its matrix
+    for f, q in enumerate(p["fc"][1:], 1):
+        large = f == 1 and f < len(p["fc"]) - 1 and q["n_in"] * q["n_out"] > 8192
+        assert q["by_cols"] == (1 if large else 0), (arch, f)
+        if large:
+            assert q["n_own"] == ceil_div(q["n_in"], G) and size["fc%d.w" % f] == q["n_own"] * q["n_out"]
+        else:
+            assert size["fc%d.w" % f] == q["n_in"] * q["n_out"]
 
 
 @pytest.mark.parametrize("name,static_id", [("cfg1", 1), ("cfg2a", 1), ("cfg2b", 2)])
@@ -237,3 +246,14 @@ def test_random_architectures():
         shared += any(c["pull_shares"] > 1 for c in p["conv"])
         winners += any(c["pull_slots"] > 0 for c in p["conv"])
     assert planned >= 100 and shared >= 5 and winners >= 20, (planned, shared, winners)
+
+
+@pytest.mark.parametrize("arch,G", [("3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", 100),
+                                    ("3x32x32-200C3-MP3-200C3-MP2-200C3-MP2-300N-100N-10N", 200),
+                                    ("1x20x20-6C5-MP2-12C4-MP1-120N-90N-7N", 12)])
+def test_a_large_hidden_layer_behind_the_first_is_held_by_columns(arch, G):
+    """Section 3's CIFAR nets end in 300N-100N-10N: the 30000 weights between the hidden layers do not fit every
+    rank's LDS next to its maps, a rank's columns of them do."""
+    p = binding.resident_plan(arch)
+    check_plan(p, arch)
+    assert p["numbers"]["G"] == G and p["fc"][1]["by_cols"] == 1 and p["fc"][2]["by_cols"] == 0
