@@ -41,6 +41,8 @@ KERNEL_OF_MODE = {"resident": "k_resident", "persistent": "k_persistent", "stage
 PAPER_NETS = [
     ("paper-cifar-100maps", "3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", (3, 32, 32), 10,
      "Table 3, 100 maps per layer: 93 s per epoch (50000 trained + 60000 forward passes, 2011 GPU)"),
+    ("paper-cifar-200maps", "3x32x32-200C3-MP3-200C3-MP2-200C3-MP2-300N-100N-10N", (3, 32, 32), 10,
+     "Table 3, 200 maps per layer: 248 s per epoch"),
     ("paper-cifar-300maps", "3x32x32-300C3-MP3-300C3-MP2-300C3-MP2-300N-100N-10N", (3, 32, 32), 10,
      "Table 3, 300 maps per layer: 532 s per epoch"),
     ("paper-norb", "2x96x96-300C6S1-MP2-500C4-MP4-500N-5N", (2, 96, 96), 5,
@@ -304,6 +306,17 @@ def main():
         warm = max(8, n_train // 8)
         net.train_many(d_i, d_l, lr, n=warm)
         net.synchronize()
+        us_plan_kernel = None
+        if mode == "resident" and net.resident_static_id() == 0:
+            # no kernel compiled into the library for this network: the one the build step compiled for it and left
+            # as a code object (paper_1102_0183_amd/specialize.py), when there is one; else the kernel that reads its plan
+            from paper_1102_0183_amd import specialize
+            path = specialize.built_code_object(net)
+            if path:
+                us_plan_kernel = 1e3 * event_ms(torch, lambda: net.train_many(d_i, d_l, lr)) / n_train
+                net.load_resident_code(path)
+                net.train_many(d_i, d_l, lr, n=warm)
+                net.synchronize()
         ms = min(event_ms(torch, lambda: net.train_many(d_i, d_l, lr)) for _ in range(2))
         us_train = 1e3 * ms / n_train
         net.forward_many(d_i, warm)
@@ -314,7 +327,8 @@ def main():
         t_f32, t_hbm = fl / (FP32_PEAK_TFLOPS * 1e12) * 1e6, by / (HBM_PEAK_GBS * 1e9) * 1e6
         bound = "fp32" if t_f32 >= t_hbm else "hbm"
         t_bound = max(t_f32, t_hbm)
-        kernels = {"resident": "k_resident (one cooperative launch per call)",
+        kernels = {"resident": "k_resident (one cooperative launch per call)" +
+                               (", compiled for this network and loaded as a code object" if us_plan_kernel else ""),
                    "persistent": "k_persistent (one cooperative launch per call)",
                    "stages": "one launch per stage: " + ", ".join(
                        sorted({ln.split()[1] for ln in net.plan_text().strip().split("\n") if ln.strip()}))}[mode]
@@ -342,6 +356,8 @@ def main():
                                                              d_l[:64].contiguous(), lay, lr)
             rec["per_layer"] = {"unit": "phases of one image, rank 0 of %d" % net.resident_ranks(),
                                 "us_per_image_rank0": round(us0, 2), "phases": rows}
+        if us_plan_kernel:
+            rec["train_with_the_kernel_reading_its_plan_us_per_image"] = round(us_plan_kernel, 2)
         if note:
             rec["paper_context"] = note
         if with_cpu and not args.no_cpu_baseline:

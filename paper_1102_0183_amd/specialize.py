@@ -65,7 +65,27 @@ EXAMPLES = {
     "benchmark": ("1x29x29-20C4-MP2-40C5-MP3-150N-10N", 0),    # the library also holds a compiled-in kernel for it
     "sparse": ("1x29x29-20C4-MP2-40C5-MP3-150N-10N", 8),
     "streamed": ("3x32x32-80C5-MP2-110C5-MP2-80N-10N", 0),     # does not fit with every layer's inputs in LDS
+    # Sec. 4.3's CIFAR10 architectures with 100 and 200 maps a layer (their second hidden layer is held by columns)
+    "cifar100": ("3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", 0),
+    "cifar200": ("3x32x32-200C3-MP3-200C3-MP2-200C3-MP2-300N-100N-10N", 0),
 }
+
+
+def prune():
+    """Delete the code objects of sources that have changed since (their names no longer match what they hold)."""
+    if not os.path.isdir(SPEC_DIR):
+        return
+    for name in sorted(os.listdir(SPEC_DIR)):
+        if name.startswith("spec_") and name.endswith(".h"):
+            tag = name[5:-2]
+            with open(os.path.join(SPEC_DIR, name)) as f:
+                stale = _digest(f.read()) != tag
+            if stale:
+                for ext in (".h", ".hsaco"):
+                    try:
+                        os.remove(os.path.join(SPEC_DIR, "spec_" + tag + ext))
+                    except FileNotFoundError:
+                        pass
 
 
 def build_examples(force=True):
@@ -73,10 +93,17 @@ def build_examples(force=True):
     from concurrent.futures import ThreadPoolExecutor
 
     from . import binding
+    prune()
     texts = {k: binding.resident_spec_source_for(a, f) for k, (a, f) in EXAMPLES.items()}
     with ThreadPoolExecutor(max_workers=4) as ex:
         paths = list(ex.map(lambda k: code_object_for(texts[k], force=force), sorted(texts)))
     return dict(zip(sorted(texts), paths))
+
+
+def built_code_object(net):
+    """Path of the code object for the network of `net` if an earlier call or the build step compiled it, else None."""
+    out = os.path.join(SPEC_DIR, "spec_%s.hsaco" % _digest(net.resident_spec_source()))
+    return out if os.path.exists(out) else None
 
 
 def specialize(net, force=False, verbose=False):

@@ -20,7 +20,7 @@ def test_the_description_of_a_network_compiles(name):
     assert os.path.getsize(path) > 10000
     # the same description gives the same file; another network another one
     assert specialize.code_object_for(text) == path
-    other = binding.resident_spec_source_for(arch.replace("150N", "151N").replace("80N", "81N"), fan)
+    other = binding.resident_spec_source_for(arch.replace("150N", "151N").replace("80N", "81N").replace("300N", "301N"), fan)
     assert specialize._digest(other) != specialize._digest(text)
 
 
