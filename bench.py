@@ -38,15 +38,19 @@ MODE_NAMES = {0: "stages", 1: "persistent", 2: "resident"}
 KERNEL_OF_MODE = {"resident": "k_resident", "persistent": "k_persistent", "stages": "per-stage kernels (sum)"}
 
 # the paper's own architectures (Sec. 4.2, 4.3) on synthetic images of the data sets' shapes: context only
+# (name, architecture, image shape, classes, what the paper says, fan-in of the tables above the first layer: 0 = full)
 PAPER_NETS = [
     ("paper-cifar-100maps", "3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", (3, 32, 32), 10,
-     "Table 3, 100 maps per layer: 93 s per epoch (50000 trained + 60000 forward passes, 2011 GPU)"),
+     "Table 3, 100 maps per layer: 93 s per epoch (50000 trained + 60000 forward passes, 2011 GPU)", 0),
     ("paper-cifar-200maps", "3x32x32-200C3-MP3-200C3-MP2-200C3-MP2-300N-100N-10N", (3, 32, 32), 10,
-     "Table 3, 200 maps per layer: 248 s per epoch"),
+     "Table 3, 200 maps per layer: 248 s per epoch", 0),
     ("paper-cifar-300maps", "3x32x32-300C3-MP3-300C3-MP2-300C3-MP2-300N-100N-10N", (3, 32, 32), 10,
-     "Table 3, 300 maps per layer: 532 s per epoch"),
+     "Table 3, 300 maps per layer: 532 s per epoch", 0),
     ("paper-norb", "2x96x96-300C6S1-MP2-500C4-MP4-500N-5N", (2, 96, 96), 5,
-     "Table 2: 1141 s per epoch (set sizes not given in the paper)"),
+     "Table 2: 1141 s per epoch (set sizes not given in the paper)", 0),
+    ("paper-mnist-deep", "1x29x29-20C4-MP2-40C2-60C3-80C3-MP2-100C2-120C3-150N-10N", (1, 29, 29), 10,
+     "Table 1, 20M-40M-60M-80M-100M-120M-150N with random partial connectivity: no time given; kernel sizes and the "
+     "share of connections kept (here half, in a regular pattern) are not given either", -2),
 ]
 
 
@@ -264,6 +268,8 @@ def main():
         if workload is not None:
             synth.build_network(ref, workload)
         else:
+            for ci, tab in (tables or {}).items():
+                ref.set_connection_table(ci, tab)
             rng = np.random.default_rng(7)
             ref.set_weights(((rng.random(ref.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
         t0 = time.perf_counter()
@@ -279,7 +285,7 @@ def main():
 
     floors = {}
 
-    def measure_config(name, arch, workload, n_train, image_shape=None, n_classes=None, note=None, with_cpu=True):
+    def measure_config(name, arch, workload, n_train, image_shape=None, n_classes=None, note=None, with_cpu=True, fan=0):
         """On-line training and forward-only rates of one architecture in the mode that runs it, with its work per
         image and bounds."""
         if workload is not None:
@@ -294,6 +300,12 @@ def main():
         else:
             net = binding.Cnn(arch)
             nets.append(net)
+            tables = {}
+            if fan:
+                convs = [l for l in range(1, net.num_layers) if net.layer_info(l)["kind"] == 1]
+                for ci in range(1, len(convs)):
+                    tables[ci] = synth.regular_table(net.layer_info(convs[ci])["maps"], net.layer_info(convs[ci] - 1)["maps"], fan)
+                    net.set_connection_table(ci, tables[ci])
             rng = np.random.default_rng(7)
             net.set_weights(((rng.random(net.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
             mode = pick_mode(net)
@@ -362,7 +374,7 @@ def main():
             rec["paper_context"] = note
         if with_cpu and not args.no_cpu_baseline:
             rec["cpu_baseline"] = oracle_rate(workload, arch, image_shape, n_classes, args.cpu_seconds_per_config,
-                                              imgs=imgs, labs=labs)
+                                              tables=None if workload is not None else tables, imgs=imgs, labs=labs)
         net.close()
         nets.remove(net)
         del d_i, d_l
@@ -450,8 +462,8 @@ def main():
         for name in ("cfg1", "cfg2a", "cfg2b", "cfg3", "cfg4a", "cfg4b", "cfg5"):
             w_ = synth.WORKLOADS[name]
             per.append(measure_config(name, w_.arch, w_, sizes[name]))
-        for name, arch, shape, ncls, note in PAPER_NETS:
-            per.append(measure_config(name, arch, None, 200 if "norb" not in name else 60, shape, ncls, note))
+        for name, arch, shape, ncls, note, fan in PAPER_NETS:
+            per.append(measure_config(name, arch, None, 200 if "norb" not in name else 60, shape, ncls, note, fan=fan))
         out["per_config"] = per
         out["dependency_floors_us"] = {k: round(v, 3) for k, v in floors.items()}
 

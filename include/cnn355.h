@@ -51,7 +51,7 @@ enum {
   CNN_MODE_RESIDENT = 2   /* one cooperative launch per call; every workgroup owns whole
                              maps and keeps their weights in LDS for the whole call; what
                              workgroups exchange per image travels as tagged words, with no
-                             grid barrier.  Needs one to four convolutional and one to four
+                             grid barrier.  Needs one to six convolutional and one to four
                              fully connected layers and a network whose per-workgroup share
                              fits the LDS (cnn_mode_supported tells).  Weights in the
                              workspace are read at the start of a call and written back at

@@ -178,7 +178,8 @@ def plan_text(arch):
 def resident_plan(arch, fan_in=0, n_ranks=0, xcd_stride=0):
     """Development aid, host-only: the resident-mode plan of an architecture, parsed: {"numbers": {name: value},
     "conv": [{field: value}], "fc": [...], "regions": [(name, first_float, floats)]}, or {"unsupported": reason}.
-    fan_in > 0: output map j of every conv layer above the first reads input maps j .. j + fan_in - 1 (mod M_i)."""
+    fan_in > 0: output map j of every conv layer above the first reads input maps j .. j + fan_in - 1 (mod M_i);
+    fan_in = -d: M_i / d of them in every layer."""
     f = lib().cnn355_resident_plan_text
     f.restype = C.c_int
     f.argtypes = [C.c_char_p, C.c_int, C.c_int, C.c_int, C.c_char_p, C.c_size_t]

@@ -1578,7 +1578,7 @@ int cnn355_resident_streams(const cnn_t* net) { return (net && net->flow_ok) ? n
 int cnn355_resident_ranks(const cnn_t* net) { return (net && net->flow_ok) ? net->flow.G : 0; }
 // development aid, host only (no device is touched): the resident plan of an architecture as text.  fan_in > 0
 // gives every convolutional layer above the first a table in which output map j reads the input maps
-// j, j + 1, ..., j + fan_in - 1 (mod M_i).  One line per number ("name value"), per layer ("conv l name value ...")
+// j, j + 1, ..., j + fan_in - 1 (mod M_i); fan_in = -d stands for M_i / d of them in every layer.  One line per number ("name value"), per layer ("conv l name value ...")
 // and per LDS region of a rank ("region name first_float floats"); a region's size is restated here from its
 // documented shape, not taken from the planner.
 static int plan_only(cnn& tmp, const char* arch, int fan_in, int n_ranks, int xcd_stride) {
@@ -1588,11 +1588,12 @@ static int plan_only(cnn& tmp, const char* arch, int fan_in, int n_ranks, int xc
   for (size_t l = 1; l < tmp.arch.size(); ++l)
     if (tmp.arch[l].kind == CNN_LAYER_CONV) {
       const int Mo = tmp.arch[l].maps, Mi = tmp.arch[l - 1].maps;
-      const bool sparse = fan_in > 0 && fan_in < Mi && !tmp.tables.empty();
+      const int fan = fan_in < 0 ? std::max(1, Mi / -fan_in) : fan_in;
+      const bool sparse = fan > 0 && fan < Mi && !tmp.tables.empty();
       tmp.tables.emplace_back((size_t)Mo * Mi, (uint8_t)(sparse ? 0 : 1));
       if (sparse)
         for (int j = 0; j < Mo; ++j)
-          for (int k = 0; k < fan_in; ++k) tmp.tables.back()[(size_t)j * Mi + (j + k) % Mi] = 1;
+          for (int k = 0; k < fan; ++k) tmp.tables.back()[(size_t)j * Mi + (j + k) % Mi] = 1;
     }
   tmp.team_ranks = n_ranks;
   tmp.team_stride = xcd_stride;

@@ -177,7 +177,7 @@ struct RunArgs {
 // tag names the image, so a reader needs no barrier: it polls the word until the tag matches.
 typedef unsigned long long tagged_t;
 
-constexpr int FLOW_MAX_CONV = 4;
+constexpr int FLOW_MAX_CONV = 6;
 constexpr int FLOW_MAX_FC = 4;
 // the arena a rank carves up, in floats (154 KB of the 160 KB of a gfx950 CU; the rest holds a copy
 // of the descriptors)

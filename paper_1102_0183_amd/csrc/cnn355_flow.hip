@@ -1420,7 +1420,9 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
     __syncthreads();
   }
   Rt rt;
-  rt.spec = &kspec;
+  // the plan where the launch put it: the kernel's argument block, whose first bytes it is.  (The address of
+  // the parameter itself would be that of a copy in each lane's scratch memory.)
+  rt.spec = (const FlowSpec*)__builtin_amdgcn_kernarg_segment_ptr();
   DECL_SPEC(Z, rt);
   const FlowPtrs& Q = sh.ptrs;
   const int G = uni_of<ID>(Z.G);
@@ -2115,7 +2117,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       return true;
     }))
       return;
-    STAMP(60);
+    STAMP(70);
     pend = defer;
     // streamed plan: the forward copies take their adjusted filters at the next image's FP -- or now, after the
     // last image of the call (the copies go back to global memory below)

@@ -59,7 +59,7 @@ def code_object_for(text, force=False, verbose=False):
 
 # Networks the build step compiles code objects for, so that they are there where no compiler should run (the
 # GPU tests load them): (architecture, fan_in), fan_in > 0 meaning that output map j of every convolutional layer
-# above the first reads the input maps j .. j + fan_in - 1 (mod M_i), 0 fully connected tables.
+# above the first reads the input maps j .. j + fan_in - 1 (mod M_i), 0 fully connected tables, -d: M_i / d of them.
 EXAMPLES = {
     "narrow": ("1x29x29-24C4-MP2-48C5-MP3-150N-10N", 0),       # the benchmark net's shape with other map counts
     "benchmark": ("1x29x29-20C4-MP2-40C5-MP3-150N-10N", 0),    # the library also holds a compiled-in kernel for it
@@ -68,6 +68,9 @@ EXAMPLES = {
     # Sec. 4.3's CIFAR10 architectures with 100 and 200 maps a layer (their second hidden layer is held by columns)
     "cifar100": ("3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", 0),
     "cifar200": ("3x32x32-200C3-MP3-200C3-MP2-200C3-MP2-300N-100N-10N", 0),
+    # Sec. 4.1's deepest net (Table 1: 20 to 120 maps in six convolutional layers, 150 hidden neurons), kernel sizes
+    # that end at 1 x 1 maps (the paper does not give them), half of the connections above the first layer
+    "mnist-deep": ("1x29x29-20C4-MP2-40C2-60C3-80C3-MP2-100C2-120C3-150N-10N", -2),
 }
 
 

@@ -113,6 +113,19 @@ def random_table(m_out: int, m_in: int, fan_in: int, seed: int) -> np.ndarray:
     return t
 
 
+def regular_table(m_out: int, m_in: int, fan_in: int) -> np.ndarray:
+    """Connection table [m_out, m_in] in which output map j reads the input maps j, j + 1, ..., j + fan_in - 1
+    (mod m_in); fan_in = -d stands for m_in / d of them.  Every output map reads as many maps and every input map
+    feeds (nearly) as many, so the table's sizes, which the resident plan depends on, follow from the three numbers."""
+    if fan_in < 0:
+        fan_in = max(1, m_in // -fan_in)
+    t = np.zeros((m_out, m_in), dtype=np.uint8)
+    for j in range(m_out):
+        for k in range(min(fan_in, m_in)):
+            t[j, (j + k) % m_in] = 1
+    return t
+
+
 def connection_table(wl: Workload, m_out: int, m_in: int) -> Optional[np.ndarray]:
     if wl.sparse_conv is None:
         return None

@@ -50,6 +50,7 @@ SHAPES = [
     ("1x65x65-8C4-MP2-20C5-MP3-6N", {}, 0, 1),               # 81 winners a map: two parts of 41 lanes
     ("1x65x65-8C4-MP2-20C5-MP3-6N", {1: 3}, 0, 1),           # ... sparse table
     ("2x60x60-3C5-MP4-7C4S1-MP3-4C1-MP1-5N", {1: 2}, 0, 2),  # skipping factor 1 under the winners, 1x1 kernels above
+    ("1x18x18-3C2-4C2-MP2-5C3-4C2-MP1-3C2S1-4C1-6N-3N", {2: 2, 4: 3}, 0, 1),   # six convolutional layers
 ]
 SHARES = {"1x28x28-6C5-MP2-100C9-MP1-8N": 16, "1x28x28-40C5-MP2-80C9-MP1-8N": 2, "1x28x28-6C5-MP2-100C5-MP2-8N": 1,
           "1x47x47-6C4-MP2-100C5-MP3-8N": 1}

@@ -62,7 +62,7 @@ def test_papers_architectures_one_step_and_batched_forward(name, arch, n_steps):
 
 def test_deep_randomly_connected_net():
     """The deepest net of Sec. 4.1 (Table 1), six convolutional layers with random connection tables:
-    one step in the stage and persistent modes, ten lock-step steps, and the batched forward pass
+    one step in every mode, ten lock-step steps in resident mode, and the batched forward pass
     (absent connections are zero columns of its weight matrices)."""
     import torch
     import oracle
@@ -77,7 +77,8 @@ def test_deep_randomly_connected_net():
     n = 10
     imgs = rng.uniform(-1, 1, (n, g.image_size)).astype(np.float32)
     labs = rng.integers(0, g.num_classes, n).astype(np.int32)
-    for mode in (binding.MODE_STAGES, binding.MODE_PERSISTENT):
+    assert g.mode_supported(binding.MODE_RESIDENT)      # (six convolutional layers: the most that mode takes)
+    for mode in (binding.MODE_STAGES, binding.MODE_PERSISTENT, binding.MODE_RESIDENT):
         g.set_mode(mode)
         grad_g = g.debug_gradients(to_dev(imgs[0]), int(labs[0]))
         grad_o, loss_o = o.gradients(imgs[0], int(labs[0]))
@@ -91,8 +92,13 @@ def test_deep_randomly_connected_net():
     g.synchronize()
     want = o.forward_many(imgs, n)
     assert np.abs(d_out.cpu().numpy().reshape(n, -1) - want).max() / np.abs(want).max() <= 1e-5
+    # ten on-line steps in lock-step with the oracle, in the mode that runs this net fastest (one launch per call)
     w0 = g.get_weights().astype(np.float64)
     lockstep_train(g, o, imgs, labs, 0.001)
     wg, wo = g.get_weights().astype(np.float64), o.get_weights()
     assert rel_err(wg, wo) <= 1e-5 and rel_err(wg - w0, wo - w0) <= 1e-4
+    # ... and the same ten as one call: the same bits
+    g.set_weights(w0.astype(np.float32))
+    g.train_many(to_dev(imgs), to_dev(labs), 0.001)
+    np.testing.assert_array_equal(g.get_weights().astype(np.float64), wg)
     g.close()

@@ -179,7 +179,8 @@ def test_the_widest_network_is_refused():
 def test_other_refusals():
     assert "equal x and y" in binding.resident_plan("1x10x12-2C3x5-MP4x2-4N")["unsupported"]
     assert "at least one convolutional" in binding.resident_plan("1x5x5-7N-4N")["unsupported"]
-    assert "at most" in binding.resident_plan("1x40x40-2C2-2C2-2C2-2C2-2C2-3N")["unsupported"]
+    assert "at most" in binding.resident_plan("1x40x40-2C2-2C2-2C2-2C2-2C2-2C2-2C2-3N")["unsupported"]
+    check_plan(binding.resident_plan("1x16x16-2C2-2C2-2C2-2C2-2C2-2C2-3N"), "1x16x16-2C2-2C2-2C2-2C2-2C2-2C2-3N")   # six layers
     with pytest.raises(binding.CnnError):
         binding.resident_plan("1x5x5-3C9-2N")
 
@@ -192,6 +193,8 @@ def test_other_refusals():
     ("1x28x28-40C5-MP2-80C5-MP2-8N", 38), ("1x28x28-3C5-MP2-250C5-MP2-8N", 0),
     ("1x28x28-6C5-MP2-100C9-MP1-8N", 0), ("1x28x28-6C5-MP2-100C9-MP1-8N", 5), ("1x28x28-40C5-MP2-80C9-MP1-8N", 12),
     ("1x47x47-6C4-MP2-100C5-MP3-8N", 0), ("1x65x65-8C4-MP2-20C5-MP3-6N", 3), ("2x60x60-3C5-MP4-7C4S1-MP3-4C1-MP1-5N", 2),
+    # Sec. 4.1's deepest net (Table 1): six convolutional layers, half of the connections above the first
+    ("1x29x29-20C4-MP2-40C2-60C3-80C3-MP2-100C2-120C3-150N-10N", 0),
 ])
 def test_edge_shapes(arch, fan):
     p = binding.resident_plan(arch, fan_in=fan)
