@@ -345,7 +345,7 @@ size_t carve(cnn* net, void* base) {
         if (++n_fc_seen == 2) words += 2 * (size_t)256 * A[l].maps + 2 * (size_t)A[l - 1].maps * A[l - 1].h * A[l - 1].w;
       }
     }
-    words += 2 * std::min<size_t>(last_maps, 256) * first_fc;
+    words += 2 * std::min<size_t>(last_maps, 256) * first_fc + 2 * first_fc;
     net->xbuf_words = words;
     net->d_xbuf = c.take<tagged_t>(words);
   }
@@ -852,6 +852,7 @@ void plan_flow(cnn* net) {
     }
   }
   Q.xp = xtake((size_t)2 * Z.n_col_ranks * Z.fc[0].n_out);
+  Q.xsum = xtake((size_t)2 * Z.fc[0].n_out);
   if (xoff > net->xbuf_words) return no("internal: exchange buffers exceed their workspace area");
   if (xb && !Q.xp) return no("internal: an exchange buffer was not laid out");
   net->flow_static_id = resident_static_id(Z);
@@ -1623,7 +1624,7 @@ int cnn355_resident_plan_text(const char* arch, int fan_in, int n_ranks, int xcd
   } else {
     const FlowSpec& Z = tmp.flow;
     num("G", Z.G); num("stride", Z.stride); num("n_conv", Z.n_conv); num("n_fc", Z.n_fc);
-    num("n_col_ranks", Z.n_col_ranks); num("lds_floats", Z.lds_floats); num("lds_floats_max", FLOW_LDS_FLOATS_MAX);
+    num("n_col_ranks", Z.n_col_ranks); num("fc1_owned", Z.fc1_owned); num("lds_floats", Z.lds_floats); num("lds_floats_max", FLOW_LDS_FLOATS_MAX);
     num("scratch_floats", Z.scratch_floats); num("defer", Z.defer); num("static_id", tmp.flow_static_id);
     num("stream", Z.stream);
     num("workgroup", WG); num("share_min_macs", FLOW_SHARE_MIN_MACS);

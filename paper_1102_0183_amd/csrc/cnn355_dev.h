@@ -222,6 +222,7 @@ struct FlowPtrs {
   FlowConvPtrs conv[FLOW_MAX_CONV];
   FlowFcPtrs fc[FLOW_MAX_FC];
   CNN_GLOBAL tagged_t* xp;  // [2][n_col_ranks][n_out of the first FC layer] partial sums
+  CNN_GLOBAL tagged_t* xsum;  // [2][n_out of the first FC layer] their sums plus bias, from the ranks that own them
 };
 
 // ---- batched forward pass ----------------------------------------------------------------

@@ -1367,6 +1367,42 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
   return rt.sh->fail == 0;
 }
 
+// The same sums when the partial sums are many: output k is added up by rank k mod G alone (a wavefront per
+// output, lane l taking the ranks l, l + 64, ...), which sends sum + bias round; every rank gathers the n1 values.
+// One more crossing, but n1 words to read per rank instead of NR x n1.
+__device__ __forceinline__ bool flow_reduce_owned(const Rt& rt, const gtagged* xp, gtagged* xs, int NR, int n1, int G,
+                                                  const float* b, float* y, float* dy, unsigned int tag,
+                                                  bool through_act) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nk = n_mine(n1, rt.rank, G);
+  for (int a = wave; a < nk; a += WG / 64) {
+    const int k = rt.rank + a * G;
+    float s = 0.f;
+    constexpr int U = 2;
+    for (int r0 = 0; r0 < NR; r0 += 64 * U) {
+      tagged_t w[U];
+      if (r0 + lane < NR) {
+        if (!fetch_tagged<U>(rt, w, tag, [&](int u) { return xp + (size_t)min(r0 + lane + 64 * u, NR - 1) * n1 + k; })) break;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (r0 + lane + 64 * u < NR) s += __uint_as_float((unsigned int)w[u]);
+      }
+    }
+    s = f_wave_sum(s);
+    if (lane == 0) put_f(xs + k, s + b[k], tag);
+  }
+  if (!gather(rt, (unsigned int*)y, xs, n1, tag)) return false;
+  if (through_act) {
+    for (int k = tid; k < n1; k += WG) {
+      const float v = y[k];
+      y[k] = f_act(v);
+      dy[k] = f_dact_pre(v);
+    }
+    __syncthreads();
+  }
+  return rt.sh->fail == 0;
+}
+
 // Work out the rank's share of the correlation jobs and fill their lane tables (once per call).
 template <int ID>
 __device__ __forceinline__ void flow_prepare_jobs(const Rt& rt) {
@@ -1798,7 +1834,10 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
       }
       ship_pend = false;
       float* y = lds + L1.o_act;
-      if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, lds + L1.o_dact, part, tag, !L1.is_output)) return;
+      if (Z.fc1_owned) {
+        if (!flow_reduce_owned(rt, Q.xp + (size_t)par * NR * n1, Q.xsum + (size_t)par * n1, NR, n1, G, lds + L1.o_b, y,
+                               lds + L1.o_dact, tag, !L1.is_output)) return;
+      } else if (!flow_reduce_partials(rt, Q.xp + (size_t)par * NR * n1, NR, n1, lds + L1.o_b, y, lds + L1.o_dact, part, tag, !L1.is_output)) return;
       STAMP(31);
     }
     // ---- FP, remaining fully connected layers: every rank computes all of them ----

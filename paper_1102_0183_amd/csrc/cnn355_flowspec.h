@@ -69,6 +69,7 @@ struct FlowSpec {
   int stride;       // rank r is workgroup r * stride of the launch (8: all ranks on one XCD)
   int n_conv, n_fc;
   int n_col_ranks;  // ranks that own maps of the last convolutional layer (and so columns of the first FC layer)
+  int fc1_owned;    // 1: each sum of the first FC layer is added up by one rank (k mod G) and sent round; 0: by every rank
   int n_classes;
   int lds_floats;
   int o_act;        // [max n_own*Ho*Wo] full-resolution outputs of the own maps of the layer being computed
@@ -117,6 +118,9 @@ constexpr long long flow_border_map(int Hi, int Wi, int K) { return ((long long)
 // A fully connected layer behind the first is kept whole by every rank up to this many weights; a larger second
 // layer (300N-100N of Sec. 4.3: 30 000) is held by columns instead, at the price of two more crossings per image.
 constexpr int FLOW_FC_REPLICATE_MAX = 8192;
+// Partial sums of the first fully connected layer (ranks with columns x outputs) up to which every rank reads all
+// of them; beyond, reading them is what the step waits for, and one rank per output adds them up and sends the sum on.
+constexpr int FLOW_FC1_DIRECT_MAX = 16384;
 // Any pooling at all makes it pay (measured: 2 x 2 rectangles, a quarter of the terms: cfg4a 55.8 -> 54.0 us per
 // image, cfg5 16.5 -> 16.2; 3 x 3 and 4 x 4: the benchmark net 16.3 -> 15.6, cfg3 43.3 -> 38.1).
 constexpr int FLOW_WINNERS_MIN_KP = 2;
@@ -263,6 +267,7 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
   }
   const ConvSpec& Cl = Z.conv[n_conv - 1];
   Z.n_col_ranks = flow_min(G, Cl.Mo);
+  Z.fc1_owned = ((long long)Z.n_col_ranks * Z.fc[0].n_out > FLOW_FC1_DIRECT_MAX) ? 1 : 0;
   for (int f = 0; f < n_fc; ++f) {
     FcSpec& Q = Z.fc[f];
     Q.by_cols = (f == 1 && !Q.is_output && (long long)Q.n_out * Q.n_in > FLOW_FC_REPLICATE_MAX) ? 1 : 0;

@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="cfg2a")
+    ap.add_argument("--arch", default=None,
+                    help="instead of a workload: any architecture, full tables, seeded weights in [-0.05, 0.05], "
+                         "images uniform in [-1, 1], rate 0.001")
     ap.add_argument("--mode", choices=["resident", "persistent", "stages"], default="resident")
     ap.add_argument("--images", type=int, default=1000, help="images per cnn_train_many call")
     ap.add_argument("--calls", type=int, default=3)
@@ -46,6 +49,18 @@ def main():
         torch.cuda.synchronize()
     wl = synth.WORKLOADS[args.workload]
     n = args.images
+    if args.arch and not args.deform:
+        import numpy as np
+        net = binding.Cnn(args.arch)
+        rng = np.random.default_rng(7)
+        net.set_weights(((rng.random(net.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
+        imgs = rng.uniform(-1, 1, (n * args.calls, net.image_size)).astype(np.float32)
+        labs = rng.integers(0, net.num_classes, n * args.calls).astype(np.int32)
+        lr, what = 1e-3, args.arch
+    elif not args.deform:
+        imgs, labs = synth.images(wl, n * args.calls), synth.labels(wl, n * args.calls)
+        net = synth.build_network(binding.Cnn(wl.arch), wl)
+        lr, what = wl.lr, args.workload
     if args.deform:
         d_src = torch.from_numpy(synth.images(wl, n)).to("cuda:0")
         d_dst = torch.empty_like(d_src)
@@ -55,10 +70,8 @@ def main():
         torch.cuda.synchronize()
         print("probe done: %s, %d calls deforming %d images" % (args.workload, args.calls, n), flush=True)
         return
-    imgs, labs = synth.images(wl, n * args.calls), synth.labels(wl, n * args.calls)
     d_imgs = torch.from_numpy(imgs).to("cuda:0")
     d_labs = torch.from_numpy(labs).to("cuda:0")
-    net = synth.build_network(binding.Cnn(wl.arch), wl)
     net.set_mode({"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
                   "stages": binding.MODE_STAGES}[args.mode])
     sz = net.image_size
@@ -76,11 +89,11 @@ def main():
         elif args.forward:
             net.forward_many(im, n)
         else:
-            net.train_many(im, d_labs[r * n:(r + 1) * n], wl.lr, n=n)
+            net.train_many(im, d_labs[r * n:(r + 1) * n], lr, n=n)
         net.synchronize()
         per_call.append(time.perf_counter() - t0)
     print("probe done: %s, %s mode, %d calls of %d images; best call %.2f us per image (host clock)" %
-          (args.workload, args.mode, args.calls, n, min(per_call) / n * 1e6), flush=True)
+          (what, args.mode, args.calls, n, min(per_call) / n * 1e6), flush=True)
     net.close()
 
 

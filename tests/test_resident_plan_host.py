@@ -38,6 +38,9 @@ def check_plan(p, arch, n_ranks=0, stride=0):
     assert num["stride"] == want_stride
     assert G == max(1, min(n_ranks or max_maps, max_maps, CU // want_stride)), arch
     assert num["n_col_ranks"] == min(G, p["conv"][-1]["Mo"])
+    # the partial sums of the first fully connected layer: read by every rank while they are few, else each sum is
+    # added up by one rank and sent round
+    assert num["fc1_owned"] == (1 if num["n_col_ranks"] * p["fc"][0]["n_out"] > 16384 else 0)
     # regions: disjoint, aligned, inside the LDS
     assert num["lds_floats"] <= num["lds_floats_max"]
     spans = sorted((off, off + n, name) for name, off, n in regions)
