@@ -269,6 +269,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
         case 3: conv_fwd_mac<3, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
         case 4: conv_fwd_mac<4, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
         case 5: conv_fwd_mac<5, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
+        case 6: conv_fwd_mac<6, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
         default: conv_fwd_mac<0, TT>(lds_in, lds_w, c_first, n, R, map_sz, Wi, K, Kx, base, acc); break;
       }
     }
@@ -810,14 +811,23 @@ __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& 
         else L.w[(size_t)k * n_in + m] = wv[u] - lr * (d * vm);
       }
     }
-#pragma unroll 4
-    for (int k = ks + FB * KS; k < N; k += KS) {
-      gfloat* wp = L.w + (size_t)k * n_in + m;
-      const float w = *wp;
-      const float d = dl[k];
-      g = fmaf(w, d, g);
-      if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
-      else *wp = w - lr * (d * vm);
+    // the rows beyond, FB2 at a time: all their loads first, then the arithmetic and the stores (a store to one
+    // row of W and a load from another cannot be told apart by the compiler, which would run them one by one)
+    constexpr int FB2 = 8;
+    for (int k0 = ks + FB * KS; k0 < N; k0 += FB2 * KS) {
+      float wn[FB2];
+#pragma unroll
+      for (int u = 0; u < FB2; ++u) wn[u] = L.w[(size_t)min(k0 + u * KS, N - 1) * n_in + m];
+#pragma unroll
+      for (int u = 0; u < FB2; ++u) {
+        const int k = k0 + u * KS;
+        if (k < N) {
+          const float d = dl[k];
+          g = fmaf(wn[u], d, g);
+          if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+          else L.w[(size_t)k * n_in + m] = wn[u] - lr * (d * vm);
+        }
+      }
     }
   }
   part[tid] = g;
