@@ -721,7 +721,9 @@ int plan(cnn* net) {
     LayerDev& L = P.layers[l];
     if (L.kind == L_FC) {
       Stage& s = add(ST_FC_BWD, l, 0, 1, 1);
-      s.cm_log2 = (L.n_in / 16 > 2048) ? 6 : 4;
+      // columns per work item: whole 256-byte (or 128-byte) pieces of a row of W where that still gives most
+      // compute units an item, else 64-byte pieces
+      s.cm_log2 = (L.n_in / 64 >= 160) ? 6 : (L.n_in / 32 >= 160) ? 5 : 4;
       s.n_items = (L.n_in + (1 << s.cm_log2) - 1) >> s.cm_log2;
     } else {
       if (!L.in_is_image && l > 0) {

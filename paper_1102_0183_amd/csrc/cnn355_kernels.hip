@@ -96,13 +96,20 @@ __device__ __forceinline__ void stage_maps_u(float* dst, const gfloat* base, int
     int off[U];  // element offset of each map from `base` (32 bits: keeps the register count low)
 #pragma unroll
     for (int u = 0; u < U; ++u) off[u] = off_of(min(c0 + u * tcn, n - 1));
-    for (int o = to; o < map_sz; o += tw) {
-      float v[U];
+    // (a map larger than the lanes that walk it: V steps of the walk at a time, so that U x V loads are in
+    // flight before the first wait instead of U)
+    constexpr int V = U >= 8 ? 1 : (U == 4 ? 2 : 4);
+    for (int o = to; o < map_sz; o += tw * V) {
+      float v[V][U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) v[u] = base[off[u] + o];
+      for (int s = 0; s < V; ++s)
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (c0 + u * tcn < n) dst[(c0 + u * tcn) * map_sz + o] = v[u];
+        for (int u = 0; u < U; ++u) v[s][u] = base[off[u] + min(o + s * tw, map_sz - 1)];
+#pragma unroll
+      for (int s = 0; s < V; ++s)
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (c0 + u * tcn < n && o + s * tw < map_sz) dst[(c0 + u * tcn) * map_sz + o + s * tw] = v[s][u];
     }
   }
 }
