@@ -96,8 +96,19 @@ __device__ __forceinline__ void stage_maps_u(float* dst, const gfloat* base, int
     int off[U];  // element offset of each map from `base` (32 bits: keeps the register count low)
 #pragma unroll
     for (int u = 0; u < U; ++u) off[u] = off_of(min(c0 + u * tcn, n - 1));
-    // (a map larger than the lanes that walk it: V steps of the walk at a time, so that U x V loads are in
-    // flight before the first wait instead of U)
+    if (map_sz <= tw) {  // one step
+      if (to < map_sz) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = base[off[u] + to];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (c0 + u * tcn < n) dst[(c0 + u * tcn) * map_sz + to] = v[u];
+      }
+      continue;
+    }
+    // a map larger than the lanes that walk it: V steps of the walk at a time, so that U x V loads are in
+    // flight before the first wait instead of U
     constexpr int V = U >= 8 ? 1 : (U == 4 ? 2 : 4);
     for (int o = to; o < map_sz; o += tw * V) {
       float v[V][U];
@@ -821,10 +832,20 @@ __device__ void fc_bwd_item(const LayerDev& L, const LayerDev* Lp, const Stage& 
     // the rows beyond, FB2 at a time: all their loads first, then the arithmetic and the stores (a store to one
     // row of W and a load from another cannot be told apart by the compiler, which would run them one by one)
     constexpr int FB2 = 8;
+    if (N <= (FB + 2) * KS) {  // (a row or two: nothing to batch)
+      for (int k = ks + FB * KS; k < N; k += KS) {
+        gfloat* wp = L.w + (size_t)k * n_in + m;
+        const float w = *wp;
+        const float d = dl[k];
+        g = fmaf(w, d, g);
+        if (g_out) g_out[L.w_canon + (size_t)k * n_in + m] = d * vm;
+        else *wp = w - lr * (d * vm);
+      }
+    } else
     for (int k0 = ks + FB * KS; k0 < N; k0 += FB2 * KS) {
       float wn[FB2];
 #pragma unroll
-      for (int u = 0; u < FB2; ++u) wn[u] = L.w[(size_t)min(k0 + u * KS, N - 1) * n_in + m];
+      for (int u = 0; u < FB2; ++u) wn[u] = (k0 + u * KS < N) ? L.w[(size_t)(k0 + u * KS) * n_in + m] : 0.f;
 #pragma unroll
       for (int u = 0; u < FB2; ++u) {
         const int k = k0 + u * KS;
