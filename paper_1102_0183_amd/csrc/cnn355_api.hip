@@ -527,12 +527,15 @@ int check_plan(cnn* net) {
         break;
       }
       case ST_CONV_BWD_EPI:
-        if (st.n_items != L.Mi || st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
+        if (st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
+        if (st.chunk < 1 || st.n_items != (L.Mi + st.chunk - 1) / st.chunk) return bad(s, "work items do not cover the input maps");
         if (st.layer < 1) return bad(s, "no layer below");
         break;
       case ST_CONV_EPI:
-        if (st.n_items != L.Mo || st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
+        if (st.rows_per_wg < 1 || st.rows_per_wg > MFMA_MAX_SLICES) return bad(s, "partial-sum planes");
+        if (st.chunk < 1 || st.n_items != (L.Mo + st.chunk - 1) / st.chunk) return bad(s, "work items do not cover the maps");
         if (L.Ho * L.Wo > MAX_TILE_PIX) return bad(s, "map too large");
+        if (st.chunk > 1 && st.chunk * L.Ho * L.Wo > WG) return bad(s, "maps of a work item exceed its lanes");
         break;
       default:
         return bad(s, "unknown stage kind");
@@ -661,8 +664,15 @@ int plan(cnn* net) {
       if (IC < 1) return fail(&net->err, CNN_E_SHAPE, "an input map does not fit the LDS staging area of the matrix-core kernel");
       Stage& s = add(ST_CONV_FWD_MFMA, l, RT * KS, 1, 0);
       s.n_tiles = KS; s.chunk = IC; s.rows_per_wg = KS;
-      Stage& e = add(ST_CONV_EPI, l, L.Mo, 1, 0);
+      // maps per work item of the second stage, side by side in its lanes: as many as leave every map its
+      // lane groups (one per 8 planes, at most 4), and at least what brings the items down to one round of
+      // the compute units where the lanes allow
+      const int g_want = std::min((KS + 7) / 8, 4);
+      const int mp_keep = std::max(1, WG / (P * g_want)), mp_need = (L.Mo + n_cu - 1) / n_cu;
+      const int mp = P >= WG ? 1 : std::max(1, std::min({std::max(mp_keep, std::min(mp_need, WG / P)), L.Mo, 64}));
+      Stage& e = add(ST_CONV_EPI, l, (L.Mo + mp - 1) / mp, 1, 0);
       e.rows_per_wg = KS;
+      e.chunk = mp;
     } else if (L.kind == L_CONV) {
       Stage& s = add(ST_CONV_FWD, l, 0, 1, 0);
       int rc = plan_conv_fwd(L, s, &net->err);
@@ -747,8 +757,13 @@ int plan(cnn* net) {
             Stage& s = add(ST_CONV_BWD_MFMA, l, RT * KS, 1, 1);
             s.n_tiles = KS; s.chunk = IC; s.rows_per_wg = KS;
             add_wgrad(l, 0);
-            Stage& e = add(ST_CONV_BWD_EPI, l, L.Mi, 1, 1);
+            // input maps per work item of the second stage: up to two passes of the lanes over their pixels, but at
+            // least 16 items (the weight adjustment that shares the interval leaves few compute units idle)
+            const int Pin2 = L.Hi * L.Wi;
+            const int mpb = std::max(1, std::min({2 * WG / Pin2, (L.Mi + 15) / 16, L.Mi}));
+            Stage& e = add(ST_CONV_BWD_EPI, l, (L.Mi + mpb - 1) / mpb, 1, 1);
             e.rows_per_wg = KS;
+            e.chunk = mpb;
             continue;
           }
         }

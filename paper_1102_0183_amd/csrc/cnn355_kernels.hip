@@ -546,21 +546,27 @@ __device__ void conv_mfma_item(const LayerDev& L, const Stage& st, int item, con
 // partial sums (lane groups share the planes, eight loads in flight per lane, fixed order), bias,
 // scaled tanh, store; then the pooled maximum with the index of the first maximum in row-major
 // order, exactly as the one-stage forward kernel does.
-__device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* lds) {
+__device__ void conv_epi_item(const LayerDev& L, const Stage& st, int item, float* lds) {
   const int tid = threadIdx.x;
   const int Wo = L.Wo, Ho = L.Ho, P = Ho * Wo, Mo = L.Mo;
   const int n_planes = st.rows_per_wg;
-  float* lds_out = lds;                 // [P]
-  float* lds_part = lds + MAX_TILE_PIX; // [G][P] partial sums of the plane groups
-  float* lds_pre = lds_part + WG;       // [P] the sums the map's units received, for the derivative at the winners
+  // st.chunk maps per work item, side by side in the lanes (one map when it has more pixels than half the lanes)
+  const int mp = st.chunk;
+  const int lpm = WG / mp;                // lanes of one map
+  float* lds_out = lds;                   // [mp][P]
+  float* lds_part = lds + MAX_TILE_PIX;   // [mp][G][P] partial sums of the plane groups
+  float* lds_pre = lds_part + WG;         // [mp][P] the sums the maps' units received, for the derivative at the winners
   const bool pooled = L.Kp > 1;
-  const float b = L.bias[j];
+  const int slot = (P >= WG) ? 0 : tid / lpm, lt = (P >= WG) ? tid : tid - slot * lpm;
+  const int j = item * mp + slot;
+  const bool mine = slot < mp && j < Mo;
+  const float b = mine ? L.bias[j] : 0.f;
   // G lane groups of P lanes each take every G-th block of 8 planes
-  const int G = (P >= WG) ? 1 : min(WG / P, (n_planes + 7) / 8);
-  const int grp = (P >= WG) ? 0 : tid / P;
+  const int G = (P >= WG) ? 1 : min(lpm / P, (n_planes + 7) / 8);
+  const int grp = (P >= WG) ? 0 : lt / P;
   for (int p0 = 0; p0 < P; p0 += WG) {
-    const int p = (P >= WG) ? p0 + tid : tid - grp * P;
-    const bool on = grp < G && p < P;
+    const int p = (P >= WG) ? p0 + tid : lt - grp * P;
+    const bool on = mine && grp < G && p < P;
     float s = 0.f;
     if (on)
       for (int s0 = grp * 8; s0 < n_planes; s0 += G * 8) {
@@ -571,19 +577,19 @@ __device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* 
         for (int u = 0; u < 8; ++u) s += (s0 + u < n_planes) ? v[u] : 0.f;
       }
     if (G > 1) {
-      if (on) lds_part[grp * P + p] = s;
+      if (on) lds_part[slot * lpm + grp * P + p] = s;
       __syncthreads();
-      if (tid < P) {
+      if (mine && lt < P) {
         s = 0.f;
-        for (int q = 0; q < G; ++q) s += lds_part[q * P + tid];
+        for (int q = 0; q < G; ++q) s += lds_part[slot * lpm + q * P + lt];
       }
     }
-    if ((G > 1) ? (tid < P) : on) {
-      const int pp = (G > 1) ? tid : p;
+    if ((G > 1) ? (mine && lt < P) : on) {
+      const int pp = (G > 1) ? lt : p;
       const float a = act_f(s + b);
       L.act[(size_t)j * P + pp] = a;
-      lds_out[pp] = a;
-      lds_pre[pp] = s + b;
+      lds_out[slot * P + pp] = a;
+      lds_pre[slot * P + pp] = s + b;
       if (!pooled) L.dact[(size_t)j * P + pp] = dact_pre_f(s + b);
     }
   }
@@ -592,9 +598,12 @@ __device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* 
   if (pooled) {
     const int Wp = L.Wp;
     const int nq = L.Hp * Wp;
-    for (int q = tid; q < nq; q += WG) {
+    for (int x = tid; x < mp * nq; x += WG) {
+      const int sl = x / nq, q = x - sl * nq;
+      const int jj = item * mp + sl;
+      if (jj >= Mo) break;
       const int py = q / Wp, px = q - py * Wp;
-      const float* win = lds_out + py * Kp * Wo + px * Kp;
+      const float* win = lds_out + sl * P + py * Kp * Wo + px * Kp;
       float best = win[0];
       int wy = 0, wx = 0;
       for (int dy = 0; dy < Kp; ++dy)
@@ -602,9 +611,9 @@ __device__ void conv_epi_item(const LayerDev& L, const Stage& st, int j, float* 
           const float v = win[dy * Wo + dx];
           if (v > best) { best = v; wy = dy; wx = dx; }
         }
-      const size_t o = (size_t)j * nq + q;
+      const size_t o = (size_t)jj * nq + q;
       L.out[o] = best;
-      L.dact[o] = dact_pre_f(lds_pre[(py * Kp + wy) * Wo + px * Kp + wx]);
+      L.dact[o] = dact_pre_f(lds_pre[sl * P + (py * Kp + wy) * Wo + px * Kp + wx]);
       L.arg[o] = (uint8_t)(wy * Kp + wx);
       L.argyx[o] = ((py * Kp + wy) << 16) | (px * Kp + wx);
     }
@@ -1292,20 +1301,23 @@ __device__ void conv_wgrad_mfma_item(const LayerDev& L, const Stage& st, int ite
 // Second half of the matrix-core delta pull: the planes of partial sums of input map i added in a
 // fixed order, times the derivative of the activation function at the output of the layer below
 // (Sec. 3.3): delta of that layer at its pooled positions.  One work item per input map.
-__device__ void conv_bwd_epi_item(const LayerDev& L, const LayerDev& Lp, const Stage& st, int i) {
+__device__ void conv_bwd_epi_item(const LayerDev& L, const LayerDev& Lp, const Stage& st, int item) {
   const int tid = threadIdx.x;
   const int P = L.Hi * L.Wi, Mi = L.Mi;
   const int n_planes = st.rows_per_wg;
-  for (int p = tid; p < P; p += WG) {
+  // st.chunk input maps per work item: their pixels are laid side by side over the lanes
+  const int i0 = item * st.chunk;
+  const int n = min(st.chunk, Mi - i0) * P;
+  for (int x = tid; x < n; x += WG) {
+    const size_t o = (size_t)i0 * P + x;   // (map i0 + x / P, pixel x % P: consecutive maps are consecutive in memory)
     float s = 0.f;
     for (int s0 = 0; s0 < n_planes; s0 += 8) {
       float v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = L.mm_part[((size_t)min(s0 + u, n_planes - 1) * Mi + i) * P + p];
+      for (int u = 0; u < 8; ++u) v[u] = L.mm_part[(size_t)min(s0 + u, n_planes - 1) * Mi * P + o];
 #pragma unroll
       for (int u = 0; u < 8; ++u) s += (s0 + u < n_planes) ? v[u] : 0.f;
     }
-    const size_t o = (size_t)i * P + p;
     Lp.delta[o] = s * Lp.dact[o];
   }
 }
