@@ -383,7 +383,7 @@ size_t carve(cnn* net, void* base) {
 }
 
 // Choose the band of conv rows one workgroup computes in the forward stage.
-int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
+int plan_conv_fwd(const LayerDev& L, Stage& st, int n_cu, std::string* err) {
   const int Kp = L.Kp, Wo = L.Wo, Ho = L.Ho;
   const int target = 256;
   int rows = 0;
@@ -413,6 +413,14 @@ int plan_conv_fwd(const LayerDev& L, Stage& st, std::string* err) {
   if (chunk < 1) return fail(err, CNN_E_SHAPE, "convolution input rows do not fit the LDS staging area");
   st.chunk = chunk;
   st.tw_log2 = ceil_log2(std::min(map_sz, WG));
+  // A few items more than compute units would leave most units idle through a second round: then two (or
+  // three) output maps per item, which share the staged input maps (full table, all of them in one chunk).
+  st.rows_per_wg = 1;
+  if (L.full_table && L.Mi <= chunk && st.n_items > n_cu && st.n_items <= 3 * n_cu && st.n_items % n_cu < n_cu / 2 && st.n_items % n_cu != 0) {
+    const int mp = (st.n_items + n_cu - 1) / n_cu;
+    st.rows_per_wg = mp;
+    st.n_items = ((L.Mo + mp - 1) / mp) * st.n_tiles;
+  }
   return CNN_OK;
 }
 
@@ -456,7 +464,9 @@ int check_plan(cnn* net) {
         if (st.pix_per_thread != 1 && st.pix_per_thread != 2) return bad(s, "bad pixels per thread");
         if (st.chunk < 1 || (long long)st.chunk * map_sz > LDS_IN) return bad(s, "input chunk exceeds the LDS input area");
         if (st.chunk * L.K * L.Kx > LDS_AUX) return bad(s, "filter chunk exceeds the LDS filter area");
-        if (st.n_tiles * st.tile_rows < L.Ho || st.n_items != L.Mo * st.n_tiles) return bad(s, "row bands do not cover the map");
+        if (st.rows_per_wg < 1 || st.n_tiles * st.tile_rows < L.Ho || st.n_items != ((L.Mo + st.rows_per_wg - 1) / st.rows_per_wg) * st.n_tiles)
+          return bad(s, "row bands do not cover the maps");
+        if (st.rows_per_wg > 1 && (!L.full_table || L.Mi > st.chunk)) return bad(s, "output maps of one work item must share one chunk of input maps");
         if ((1 << st.tw_log2) > WG) return bad(s, "staging width");
         break;
       }
@@ -675,7 +685,7 @@ int plan(cnn* net) {
       e.chunk = mp;
     } else if (L.kind == L_CONV) {
       Stage& s = add(ST_CONV_FWD, l, 0, 1, 0);
-      int rc = plan_conv_fwd(L, s, &net->err);
+      int rc = plan_conv_fwd(L, s, net->n_cu > 0 ? net->n_cu : 256, &net->err);
       if (rc) return rc;
     } else if (!L.is_output) {
       Stage& s = add(ST_FC_FWD, l, 0, 1, 0);

@@ -221,8 +221,11 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   const int KK = K * Kx;
   const int Wi = L.Wi, Wo = L.Wo, Ho = L.Ho;
   const int stride = L.S + 1, stride_x = L.Sx + 1;
-  const int j = item / st.n_tiles;
-  const int tile = item - j * st.n_tiles;
+  // st.rows_per_wg (> 1) output maps per work item, one after the other: they read the same input maps (full
+  // table, one chunk), which are staged once
+  const int mp = max(st.rows_per_wg, 1);
+  const int jg = item / st.n_tiles;
+  const int tile = item - jg * st.n_tiles;
   const int y0 = tile * st.tile_rows;
   const int rows = min(st.tile_rows, Ho - y0);
   const int P = rows * Wo;
@@ -240,6 +243,9 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
   const bool pooled = Kp > 1 || Kpx > 1;
 
   DBG(0);
+  for (int jj = 0; jj < mp; ++jj) {
+  const int j = jg * mp + jj;
+  if (j >= L.Mo) break;
   const float b = L.bias[j];  // issued first, used last
   int c_begin = j * L.Mi, n_conn = L.Mi;
   if (!L.full_table) {
@@ -270,7 +276,9 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
     const gfloat* wsrc = L.w + (size_t)(c_begin + c0) * KK;
     float wv[4];
     prefetch_flat(wv, wsrc, n * KK);  // filters in flight together with the input maps
-    if (L.full_table)  // uniform: input map of slot c is c itself
+    if (jj > 0) {
+      // (the maps the first output map of this item staged are the ones this one reads)
+    } else if (L.full_table)  // uniform: input map of slot c is c itself
       stage_maps(lds_in, in0, n, map_sz, st.tw_log2, [&](int c) { return (c0 + c) * in_map; });
     else
       stage_maps(lds_in, in0, n, map_sz, st.tw_log2,
@@ -335,6 +343,7 @@ __device__ void conv_fwd_item(const LayerDev& L, const Stage& st, int item,
       L.argyx[o] = ((y0 + py * Kp + wy) << 16) | (px * Kpx + wx);
     }
     __syncthreads();
+  }
   }
   DBG(7);
 }
