@@ -210,15 +210,16 @@ def test_edge_shapes(arch, fan):
             check_plan(q, arch, *team)
 
 
-def random_arch(rng):
-    """1 to 4 convolutional layers of up to 120 maps with square kernels, skips and pooling, then 1 to 3 FC layers."""
+def random_arch(rng, deep=False):
+    """1 to 4 convolutional layers of up to 120 maps with square kernels, skips and pooling, then 1 to 3 FC layers.
+    deep: up to 6 layers with kernels of at most 3 and less pooling, up to 3 hidden FC layers of up to 300 units."""
     h = w = int(rng.integers(8, 49))
     if rng.random() < 0.3:
         w = int(rng.integers(8, 49))
     s = "%dx%dx%d" % (int(rng.integers(1, 4)), h, w)
     n_conv = 0
-    for _ in range(int(rng.integers(1, 5))):
-        k = int(rng.integers(1, min(7, h, w) + 1))
+    for _ in range(int(rng.integers(3, 7)) if deep else int(rng.integers(1, 5))):
+        k = int(rng.integers(1, min(3 if deep else 7, h, w) + 1))
         sk = int(rng.integers(0, 3)) if rng.random() < 0.3 else 0
         ho, wo = (h - k) // (sk + 1) + 1, (w - k) // (sk + 1) + 1
         m = int(rng.choice([2, 5, 12, 20, 40, 64, 100, 120]))
@@ -226,14 +227,14 @@ def random_arch(rng):
         n_conv += 1
         h, w = ho, wo
         both = [d for d in range(1, 5) if h % d == 0 and w % d == 0]
-        if rng.random() < 0.7:
+        if rng.random() < (0.35 if deep else 0.7):
             d = int(rng.choice(both))
             s += "-MP%d" % d
             h, w = h // d, w // d
         if min(h, w) < 2:
             break
-    for _ in range(int(rng.integers(0, 3))):
-        s += "-%dN" % int(rng.integers(2, 200))
+    for _ in range(int(rng.integers(1, 4)) if deep else int(rng.integers(0, 3))):
+        s += "-%dN" % int(rng.integers(2, 300 if deep else 200))
     return s + "-%dN" % int(rng.integers(2, 12))
 
 
@@ -252,6 +253,24 @@ def test_random_architectures():
         shared += any(c["pull_shares"] > 1 for c in p["conv"])
         winners += any(c["pull_slots"] > 0 for c in p["conv"])
     assert planned >= 100 and shared >= 5 and winners >= 20, (planned, shared, winners)
+
+
+def test_random_deep_architectures():
+    rng = np.random.default_rng(6)
+    planned = cols = owned = deep = 0
+    for _ in range(300):
+        arch = random_arch(rng, deep=True)
+        fan = int(rng.integers(1, 40)) if rng.random() < 0.4 else 0
+        team = (0, 0) if rng.random() < 0.6 else (int(rng.integers(1, 130)), int(rng.choice([0, 1, 8])))
+        p = binding.resident_plan(arch, fan, *team)
+        if "unsupported" in p:
+            continue
+        check_plan(p, arch, *team)
+        planned += 1
+        cols += any(q["by_cols"] for q in p["fc"])
+        owned += p["numbers"]["fc1_owned"]
+        deep += p["numbers"]["n_conv"] >= 5
+    assert planned >= 80 and cols >= 10 and owned >= 5 and deep >= 20, (planned, cols, owned, deep)
 
 
 @pytest.mark.parametrize("arch,G", [("3x32x32-100C3-MP3-100C3-MP2-100C3-MP2-300N-100N-10N", 100),
