@@ -25,6 +25,11 @@ def main():
     ap.add_argument("--arch", default=None,
                     help="instead of a workload: any architecture, full tables, seeded weights in [-0.05, 0.05], "
                          "images uniform in [-1, 1], rate 0.001")
+    ap.add_argument("--fan", type=int, default=0,
+                    help="with --arch: output map j of every convolutional layer above the first reads the input maps "
+                         "j .. j + fan - 1 (mod M_i); -d: M_i / d of them; 0: full tables")
+    ap.add_argument("--code-object", action="store_true",
+                    help="resident mode: load the kernel the build step compiled for this network, if there is one")
     ap.add_argument("--mode", choices=["resident", "persistent", "stages"], default="resident")
     ap.add_argument("--images", type=int, default=1000, help="images per cnn_train_many call")
     ap.add_argument("--calls", type=int, default=3)
@@ -52,6 +57,11 @@ def main():
     if args.arch and not args.deform:
         import numpy as np
         net = binding.Cnn(args.arch)
+        if args.fan:
+            convs = [l for l in range(1, net.num_layers) if net.layer_info(l)["kind"] == 1]
+            for ci in range(1, len(convs)):
+                net.set_connection_table(ci, synth.regular_table(net.layer_info(convs[ci])["maps"],
+                                                                 net.layer_info(convs[ci] - 1)["maps"], args.fan))
         rng = np.random.default_rng(7)
         net.set_weights(((rng.random(net.num_weights, dtype=np.float32) - np.float32(0.5)) * np.float32(0.1)))
         imgs = rng.uniform(-1, 1, (n * args.calls, net.image_size)).astype(np.float32)
@@ -74,6 +84,12 @@ def main():
     d_labs = torch.from_numpy(labs).to("cuda:0")
     net.set_mode({"resident": binding.MODE_RESIDENT, "persistent": binding.MODE_PERSISTENT,
                   "stages": binding.MODE_STAGES}[args.mode])
+    if args.code_object and args.mode == "resident":
+        from paper_1102_0183_amd import specialize
+        path = specialize.built_code_object(net)
+        if path:
+            net.load_resident_code(path)
+        print("probe: kernel compiled for this network %s" % ("loaded" if path else "not built"), flush=True)
     sz = net.image_size
     if args.batch:
         scratch = torch.empty(net.forward_batch_scratch_bytes(args.batch), dtype=torch.uint8, device="cuda:0")
