@@ -46,12 +46,24 @@ typedef CNN_GLOBAL tagged_t gtagged;
 #define ACT_B 0.6666f
 // Scaled hyperbolic tangent of Sec. 4, constants as printed, as 1 - 2 / (e^{2Ba} + 1) on the hardware
 // exponential and reciprocal: absolute error about 3e-7 (the library tanhf costs thirty times as
-// many cycles on the critical path of every layer); saturates correctly at both ends.  (The odd series of
-// tanh below |Ba| = 0.3 would keep the digits of small activations -- relative error 1.4e-7 instead of an
-// absolute 3e-7 -- and was measured to cost 1.3 % of the time per image of the benchmark net: left out.)
+// many cycles on the critical path of every layer); saturates correctly at both ends.  This one is for the
+// units of the convolutional layers (the series below, applied to them too, was measured to cost 1.3 % of the
+// time per image of the benchmark net).
 __device__ __forceinline__ float f_act(float a) {
   const float z = __builtin_amdgcn_exp2f((2.0f * ACT_B * 1.44269504088896340736f) * a);
   return fmaf(-2.0f * ACT_A, __builtin_amdgcn_rcpf(z + 1.0f), ACT_A);
+}
+// The same for the units of the fully connected layers (one per lane, once per image: what it costs does not
+// show): below |Ba| = 0.3 the odd series of tanh up to x^9 (next term 1382/155925 x^11: 5e-8 of the result at
+// 0.3), so that a small output keeps its digits.
+__device__ __forceinline__ float f_act_fc(float a) {
+  const float big = f_act(a);
+  const float x = ACT_B * a, x2 = x * x;
+  float p = fmaf(x2, 62.0f / 2835.0f, -17.0f / 315.0f);
+  p = fmaf(x2, p, 2.0f / 15.0f);
+  p = fmaf(x2, p, -1.0f / 3.0f);
+  const float small = ACT_A * fmaf(x, x2 * p, x);
+  return fabsf(x) < 0.3f ? small : big;
 }
 // Its derivative A B (1 - tanh^2(B a)) = 4 A B z / (1 + z)^2 with z = e^{-2B|a|}, taken from the sum a the
 // unit received: no difference of nearly equal numbers anywhere, so a saturated unit keeps the relative
@@ -1360,7 +1372,7 @@ __device__ __forceinline__ bool flow_reduce_partials(const Rt& rt, const gtagged
     __syncthreads();
     if (tid < n1 - k0 && tid < WG) {
       const float v = b[k0 + tid] + sum_strided(part, parts, n1, tid);
-      y[k0 + tid] = through_act ? f_act(v) : v;
+      y[k0 + tid] = through_act ? f_act_fc(v) : v;
       if (through_act) dy[k0 + tid] = f_dact_pre(v);
     }
     __syncthreads();
@@ -1397,7 +1409,7 @@ __device__ __forceinline__ bool flow_reduce_owned(const Rt& rt, const gtagged* x
   if (through_act) {
     for (int k = tid; k < n1; k += WG) {
       const float v = y[k];
-      y[k] = f_act(v);
+      y[k] = f_act_fc(v);
       dy[k] = f_dact_pre(v);
     }
     __syncthreads();
@@ -1870,7 +1882,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         float* dy = lds + L.o_dact;
         for (int k = tid; k < L.n_out; k += WG) {
           const float v = y[k];
-          y[k] = f_act(v);
+          y[k] = f_act_fc(v);
           dy[k] = f_dact_pre(v);
         }
         __syncthreads();
@@ -1910,7 +1922,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         dreg = (k == label) ? -zo * rz : p;
         float err = 0.f;
         if (tanh_out) {  // scaled-tanh outputs, squared error against targets +1 / -1
-          p = (k < N) ? f_act(yk) : 0.f;
+          p = (k < N) ? f_act_fc(yk) : 0.f;
           const float dev = (k < N) ? p - (k == label ? 1.f : -1.f) : 0.f;
           dreg = (k < N) ? dev * f_dact_pre(yk) : 0.f;
           err = 0.5f * f_wave_sum(dev * dev);
@@ -1931,7 +1943,7 @@ __global__ void __launch_bounds__(WG) k_resident(const FlowSpec kspec, const Flo
         if (tid < 64 && tanh_out) {
           float err = 0.f;
           for (int k = tid; k < N; k += 64) {
-            const float p = f_act(y[k]);
+            const float p = f_act_fc(y[k]);
             const float dev = p - (k == label ? 1.f : -1.f);
             d[k] = dev * f_dact_pre(y[k]);
             y[k] = p;
