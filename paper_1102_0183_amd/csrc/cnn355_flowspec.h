@@ -146,8 +146,37 @@ constexpr long long flow_part_need(int strip, int th, int n_maps, int rows, int 
 // read; with 3, to allow for bank conflicts, a sweep over all tiles showed the model passing over the fastest).  0 = one pixel per lane (any stride, any kernel size); tiles exist
 // for strides 1 and 2 and kernels of 2 to 5.
 // Returns strip + 16 * rows.
-constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, int max_cnt) {
-  if (stride < 1 || stride > 2 || K < 2 || K > 5) return 0;
+// The most lanes of a wavefront whose reads of one tap fall into one LDS bank (32 banks of one float): the lanes
+// of a wavefront read the same tap of their tiles at once, so this many reads go through one bank one after the
+// other (2 at best: 64 lanes, 32 banks).  Lane u takes tile t = u mod U and way u / U of the connections (side:
+// way u mod ways, tile u / ways), tiles numbered (map, band of th rows, strip of sw pixels) as the kernel deals
+// them out; a way further on reads a map further on.  pitch: floats from one input row to the next, map: from one
+// map to the next.
+constexpr int flow_bank_load(int n_maps, int rows, int width, int th, int sw, int stride, int pitch, long long map,
+                             long long ways, int side) {
+  const int NS = (width + sw - 1) / sw, NG = (rows + th - 1) / th;
+  const long long U = (long long)n_maps * NG * NS;
+  int cnt[32] = {};
+  int worst = 0;
+  for (int u = 0; u < 64; ++u) {
+    const long long t = side ? u / ways : u % U, r = side ? u % ways : u / U;
+    if (t >= U || r >= ways) continue;
+    const int row = (int)(t / NS), sx = (int)(t - (long long)row * NS);
+    const int am = row / NG, y = (row - am * NG) * th;
+    const long long a = (long long)(y * pitch + sx * sw) * stride + (am + r) * map;
+    const int b = (int)(a & 31);
+    if (++cnt[b] > worst) worst = cnt[b];
+  }
+  return worst;
+}
+
+// FLOW_BANK_LOAD_MAX: how many reads of one tap may queue at one bank before the tile is chosen with the queues in
+// the bill.  Up to there the bill without them picks better (measured on the benchmark net: its queues of 3 to 4
+// cost less than the lanes a taller tile leaves idle); beyond, e.g. with input rows of 14, 22, 32 or 48 floats under
+// strips of 4, a read takes 5 to 16 turns and the strips of 5 or 7 that spread over the banks win.
+constexpr int FLOW_BANK_LOAD_MAX = 4;
+constexpr int flow_tile_pick(int K, int stride, int n_maps, int rows, int width, int max_cnt, int pitch, long long map,
+                             int side, bool with_banks, int* load_of_best) {
   int best = 4 + 16;
   long long best_cost = -1;
   const int widths[3] = {4, 5, 7};
@@ -166,13 +195,22 @@ constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, 
       const long long reads = (long long)((th - 1) * stride + K) * ((sw - 1) * stride + K) + K * K;
       const long long ways = (max_cnt + iters - 1) / iters;
       const long long waves = (flow_minl(U * ways, WG) + 63) / 64;
-      const long long valu = iters * macs * 5, lds = waves * iters * reads * 2;
+      const int load = flow_bank_load(n_maps, rows, width, th, sw, stride, pitch, map, ways, side);
+      const long long valu = iters * macs * 5, lds = waves * iters * reads * ((with_banks && load > 2) ? load : 2);
       long long cost = passes * ((valu > lds ? valu : lds) + 200);
       // partial sums beyond 32 KB crowd out the weights and maps a rank must hold: last resort only
       if (flow_part_need(sw, th, n_maps, rows, width, max_cnt) > 8 * WG) cost += 1000000;
-      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sw + 16 * th; }
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sw + 16 * th; *load_of_best = load; }
     }
   return best;
+}
+constexpr int flow_tile_for(int K, int stride, int n_maps, int rows, int width, int max_cnt, int pitch, long long map,
+                            int side) {
+  if (stride < 1 || stride > 2 || K < 2 || K > 5) return 0;
+  int load = 0;
+  const int plain = flow_tile_pick(K, stride, n_maps, rows, width, max_cnt, pitch, map, side, false, &load);
+  if (load <= FLOW_BANK_LOAD_MAX) return plain;
+  return flow_tile_pick(K, stride, n_maps, rows, width, max_cnt, pitch, map, side, true, &load);
 }
 
 // Choose the team and lay out every rank's LDS.  On entry Z holds the shape (n_conv, n_fc,
@@ -229,7 +267,7 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
     C.o_cidx = take((long long)C.n_own * C.max_conn);
     C.o_ncf = take(C.n_own);
     {
-      const int tile = flow_tile_for(C.K, C.S + 1, C.n_own, C.Ho, C.Wo, C.max_conn);
+      const int tile = flow_tile_for(C.K, C.S + 1, C.n_own, C.Ho, C.Wo, C.max_conn, C.Wi, (long long)C.Hi * C.Wi, 0);
       C.fwd_strip = tile & 15; C.fwd_rows = tile ? tile >> 4 : 1;
     }
     C.o_wb = 0; C.o_bj = 0; C.o_ncb = 0; C.pull_strip = 0; C.pull_rows = 1; C.pull_chunk = 1;
@@ -238,7 +276,8 @@ constexpr int flow_plan_as(FlowSpec& Z, int team_ranks, int team_stride, int n_c
       C.o_bj = take((long long)C.n_own_below * C.back_pitch);
       C.o_ncb = take(C.n_own_below);
       {
-        const int tile = flow_tile_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.back_pitch);
+        const int tile = flow_tile_for(C.K, 1, C.n_own_below, C.Hi, C.Wi, C.back_pitch, C.Wi + C.K - 1,
+                                       flow_border_map(C.Hi, C.Wi, C.K), C.K & 1);
         C.pull_strip = tile & 15; C.pull_rows = tile ? tile >> 4 : 1;
       }
       max_dall = flow_maxl(max_dall, (long long)C.Mo * HW);
